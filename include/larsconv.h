@@ -1,0 +1,116 @@
+/*
+ * larsconv -- one worker's share of large-batch LARS training on one MI355X (gfx950):
+ * convolution forward, backward-data, backward-weight, and the layer-wise LARS update.
+ *
+ * The operations are those of the synchronous data-parallel iteration described in
+ * "Data-Parallelism SGD" (every worker computes its local gradient independently) with the
+ * optimizer named in "Scaling up Batch Size" (LARS, momentum, weight decay, poly schedule of
+ * power 2 -- hyper-parameters in the caption of the AlexNet accuracy table).  The gradient
+ * sum across workers that sits between the two is not part of this library.
+ *
+ * Conventions for every entry point
+ *  - Tensor pointers are DEVICE pointers owned by the caller unless a parameter says HOST.
+ *    The library never allocates, frees or keeps them.  Outputs are overwritten, inputs are
+ *    not modified (lars_step updates w and v in place).
+ *  - Work is enqueued on `hip_stream` (a hipStream_t passed as void*, NULL = the default
+ *    stream) and the call returns without waiting for it.  Calls on one stream are ordered.
+ *  - `workspace` is caller-owned device scratch of at least the size the matching *_workspace_bytes
+ *    query returns (256-byte aligned); its contents are undefined between calls.
+ *  - Arguments are validated before anything is launched; errors come back as lc_status, never
+ *    as exceptions or aborts, and a failing call launches nothing.
+ *  - Kernels exist for gfx950 only.
+ */
+#ifndef LARSCONV_H
+#define LARSCONV_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    LC_OK = 0,
+    LC_ERR_NULL = 1,        /* a required pointer is NULL                                  */
+    LC_ERR_SHAPE = 2,       /* non-positive size, empty output, negative pad, bad count     */
+    LC_ERR_UNSUPPORTED = 3, /* unknown enum value or a combination that is not built        */
+    LC_ERR_WORKSPACE = 4,   /* workspace NULL, misaligned or smaller than the query         */
+    LC_ERR_LAUNCH = 5,      /* the HIP runtime reported an error while enqueueing           */
+    LC_ERR_ALIGN = 6        /* a tensor pointer is not aligned to its element size          */
+} lc_status;
+
+typedef enum { LC_F32 = 0, LC_BF16 = 1 } lc_dtype;   /* operand type; sums are always fp32 */
+typedef enum { LC_NCHW = 0, LC_NHWC = 1 } lc_layout; /* filter is KCRS for NCHW, KRSC for NHWC */
+typedef enum { LC_PASS_FWD = 0, LC_PASS_BWD_DATA = 1, LC_PASS_BWD_WEIGHT = 2 } lc_pass;
+
+/* One convolution layer: input X[n,c,h,w], filter W[k,c,r,s], output Y[n,k,p,q] with
+ * p = floor((h + 2*pad_h - r)/stride_h) + 1 (q likewise).  Cross-correlation (no filter flip),
+ * zero padding, dilation 1, one group, no bias -- the convolution of the Caffe-style layers the
+ * paper's networks are made of ("Experimental Settings").  NHWC is the layout the matrix cores
+ * are fed from; NCHW tensors are accepted and transposed through the workspace. */
+typedef struct {
+    int n, c, h, w;
+    int k, r, s;
+    int stride_h, stride_w, pad_h, pad_w;
+    lc_dtype dtype;   /* type of x, w, y, dy, dx.  dw is always fp32. */
+    lc_layout layout;
+} lc_conv_desc;
+
+/* Output height p and width q.  HOST pointers.  LC_ERR_SHAPE if the window does not fit. */
+lc_status conv2d_out_shape(const lc_conv_desc* desc, int* p, int* q);
+
+/* Scratch bytes conv2d_{fwd,bwd_data,bwd_weight} needs for `desc` (0 is possible).  Returns 0 for an
+ * invalid descriptor; the call itself then reports the error. */
+size_t conv2d_workspace_bytes(const lc_conv_desc* desc, lc_pass pass);
+
+/* Forward pass: the per-image work the paper counts in flops ("Benefits of Large-Batch Training",
+ * "Model Selection").   y[n,k,p,q] = sum_{c,r,s} x[n,c,p*stride_h-pad_h+r, q*stride_w-pad_w+s] * w[k,c,r,s],
+ * reads outside the image being zero.  x: n*c*h*w, w: k*c*r*s, y: n*k*p*q elements of desc->dtype. */
+lc_status conv2d_fwd(const lc_conv_desc* desc, const void* x, const void* w, void* y,
+                     void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* Gradient with respect to the input (back-propagation through the layer; part of the local
+ * gradient computation of "Data-Parallelism SGD").  dx[n,c,h,w] = sum over all (k,p,q,r,s) whose
+ * forward read touched (h,w) of dy[n,k,p,q] * w[k,c,r,s].  dx is written in full, zeros included. */
+lc_status conv2d_bwd_data(const lc_conv_desc* desc, const void* dy, const void* w, void* dx,
+                          void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* Gradient with respect to the filter: the worker's local gradient that the data-parallel scheme sums
+ * over workers.  dw[k,c,r,s] = sum_{n,p,q} dy[n,k,p,q] * x[n,c,p*stride_h-pad_h+r, q*stride_w-pad_w+s].
+ * dw is fp32 for every operand dtype and is overwritten.  The reduction is split over the batch and
+ * summed in a fixed order: results are bit-identical from run to run. */
+lc_status conv2d_bwd_weight(const lc_conv_desc* desc, const void* x, const void* dy, float* dw,
+                            void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* Scratch bytes lars_step needs for this list of tensor sizes (HOST array).  0 on invalid input. */
+size_t lars_workspace_bytes(int n_tensors, const int64_t* numel);
+
+/* One LARS step over a list of parameter tensors, each its own "layer" ("Scaling up Batch Size":
+ * LARS with warmup; momentum and weight decay as in the AlexNet accuracy table).  For tensor l:
+ *     trust_l = eta * ||w_l|| / (||g_l|| + weight_decay * ||w_l||)     (Euclidean norms; 1 if undefined)
+ *     v_l <- momentum * v_l + lr * trust_l * (g_l + weight_decay * w_l)
+ *     w_l <- w_l - v_l
+ * w, g, v: HOST arrays of n_tensors DEVICE pointers to fp32 data (4-byte aligned; 16-byte alignment
+ * takes the vector path); numel: HOST array of element counts (0 allowed).  w and v are updated in
+ * place, g is read only; the three must not overlap.  trust_out: DEVICE, n_tensors floats, or NULL.
+ * w_lowp_out: HOST array of DEVICE pointers receiving the new weights rounded to bf16 (nearest even),
+ * or NULL; single entries may be NULL.  n_tensors = 0 is a no-op.  Norms are reduced in a fixed
+ * order: results are bit-identical from run to run and independent of the other tensors in the list. */
+lc_status lars_step(int n_tensors, float* const* w, const float* const* g, float* const* v,
+                    const int64_t* numel, float eta, float momentum, float weight_decay, float lr,
+                    float* trust_out, void* const* w_lowp_out,
+                    void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* Poly learning-rate policy (HOST arithmetic): base_lr * (1 - iter/max_iter)^power, 0 past max_iter.
+ * The paper trains with power 2; max_iter = epochs * images / batch ("Scaling Efficiency of Large
+ * Batches").  The result is the `lr` argument of lars_step. */
+float lars_poly_lr(float base_lr, int64_t iter, int64_t max_iter, float power);
+
+/* Static, human-readable name of a status code. */
+const char* lc_status_string(lc_status status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LARSCONV_H */

@@ -1,0 +1,317 @@
+// C-ABI entry points of the convolution passes: validation, workspace planning and dispatch to
+// the implicit-GEMM kernels.  Everything that can fail is checked before the first launch, so the
+// error paths behave the same on a machine without a GPU.
+#include <hip/hip_runtime.h>
+#include <limits.h>
+#include <stdint.h>
+
+#include "internal.h"
+
+namespace {
+
+struct Regions {
+    size_t off = 0;
+    size_t take(size_t bytes) {
+        const size_t at = off;
+        off += (bytes + 255) & ~(size_t)255;
+        return at;
+    }
+};
+
+struct Plan {
+    int P = 0, Q = 0, esize = 4;
+    bool nchw = false;
+    int cpad = 0;                    // channel count the kernels see for x / w (c rounded up to 4)
+    size_t a_nhwc = 0, b_nhwc = 0, out_nhwc = 0;   // NCHW staging: first operand, second operand, result
+    size_t xpad = 0, wpad = 0;       // channel-padded copies
+    size_t wt = 0;                   // re-ordered filter for backward-data
+    size_t part = 0;                 // split partials of backward-weight
+    int splits = 1, m_per_split = 0;
+    bool wgrad_direct = true;
+    size_t total = 0;
+};
+
+lc_status check_desc(const lc_conv_desc* d, int* P, int* Q) {
+    if (!d) return LC_ERR_NULL;
+    if (d->n <= 0 || d->c <= 0 || d->h <= 0 || d->w <= 0 || d->k <= 0 || d->r <= 0 || d->s <= 0 ||
+        d->stride_h <= 0 || d->stride_w <= 0 || d->pad_h < 0 || d->pad_w < 0)
+        return LC_ERR_SHAPE;
+    if ((long long)d->h + 2LL * d->pad_h < d->r || (long long)d->w + 2LL * d->pad_w < d->s) return LC_ERR_SHAPE;
+    if (d->dtype != LC_F32 && d->dtype != LC_BF16) return LC_ERR_UNSUPPORTED;
+    if (d->layout != LC_NCHW && d->layout != LC_NHWC) return LC_ERR_UNSUPPORTED;
+    *P = (d->h + 2 * d->pad_h - d->r) / d->stride_h + 1;
+    *Q = (d->w + 2 * d->pad_w - d->s) / d->stride_w + 1;
+    // index ranges the kernels hold in 32-bit integers
+    const long long lim = INT_MAX;
+    const long long cp = (d->c + 3) & ~3, kp = (d->k + 3) & ~3;
+    if ((long long)d->n * *P * *Q > lim || (long long)d->n * d->h * d->w > lim) return LC_ERR_UNSUPPORTED;
+    if ((long long)d->r * d->s * cp > lim || (long long)d->r * d->s * kp > lim) return LC_ERR_UNSUPPORTED;
+    if ((long long)d->h * d->w * cp > lim || (long long)*P * *Q * kp > lim) return LC_ERR_UNSUPPORTED;
+    if ((long long)d->k * d->r * d->s * cp > lim) return LC_ERR_UNSUPPORTED;
+    return LC_OK;
+}
+
+lc_status make_plan(const lc_conv_desc* d, lc_pass pass, Plan* pl) {
+    const lc_status st = check_desc(d, &pl->P, &pl->Q);
+    if (st != LC_OK) return st;
+    if (pass != LC_PASS_FWD && pass != LC_PASS_BWD_DATA && pass != LC_PASS_BWD_WEIGHT) return LC_ERR_UNSUPPORTED;
+    if (d->dtype != LC_F32) return LC_ERR_UNSUPPORTED;   // bf16 kernels are not built yet
+    pl->esize = 4;
+    pl->nchw = d->layout == LC_NCHW;
+    const size_t es = (size_t)pl->esize;
+    const size_t nx = (size_t)d->n * d->h * d->w * d->c, ny = (size_t)d->n * pl->P * pl->Q * d->k;
+    const size_t nw = (size_t)d->k * d->r * d->s * d->c;
+    pl->cpad = (d->c + 3) & ~3;
+    const bool pad = pl->cpad != d->c;
+    Regions rg;
+    if (pass == LC_PASS_FWD) {
+        if (pl->nchw) {
+            pl->a_nhwc = rg.take(nx * es);
+            pl->b_nhwc = rg.take(nw * es);
+            pl->out_nhwc = rg.take(ny * es);
+        }
+        if (pad) {
+            pl->xpad = rg.take((size_t)d->n * d->h * d->w * pl->cpad * es);
+            pl->wpad = rg.take((size_t)d->k * d->r * d->s * pl->cpad * es);
+        }
+    } else if (pass == LC_PASS_BWD_DATA) {
+        if (pl->nchw) {
+            pl->a_nhwc = rg.take(ny * es);
+            pl->b_nhwc = rg.take(nw * es);
+            pl->out_nhwc = rg.take(nx * es);
+        }
+        pl->wt = rg.take(nw * es);
+    } else {
+        if (pl->nchw) {
+            pl->a_nhwc = rg.take(nx * es);
+            pl->b_nhwc = rg.take(ny * es);
+            pl->out_nhwc = rg.take(nw * sizeof(float));
+        }
+        if (pad) pl->xpad = rg.take((size_t)d->n * d->h * d->w * pl->cpad * es);
+        const int M = d->n * pl->P * pl->Q, J = d->r * d->s * pl->cpad;
+        pl->splits = lc_wgrad_splits(M, d->k, J);
+        pl->m_per_split = (M + pl->splits - 1) / pl->splits;
+        pl->wgrad_direct = pl->splits == 1 && !pad;
+        if (!pl->wgrad_direct) pl->part = rg.take((size_t)pl->splits * d->k * J * sizeof(float));
+    }
+    pl->total = rg.off;
+    return LC_OK;
+}
+
+lc_status check_buffers(const lc_conv_desc* d, const Plan& pl, const void* a, const void* b, const void* c,
+                        const void* ws, size_t ws_bytes) {
+    if (!a || !b || !c) return LC_ERR_NULL;
+    const uintptr_t mask = (uintptr_t)(pl.esize - 1);
+    if (((uintptr_t)a | (uintptr_t)b) & mask) return LC_ERR_ALIGN;
+    (void)d;
+    if (pl.total) {
+        if (!ws || ((uintptr_t)ws & 255) || ws_bytes < pl.total) return LC_ERR_WORKSPACE;
+    }
+    return LC_OK;
+}
+
+inline char* at(void* ws, size_t off) { return static_cast<char*>(ws) + off; }
+
+}  // namespace
+
+extern "C" lc_status conv2d_out_shape(const lc_conv_desc* desc, int* p, int* q) {
+    if (!desc || !p || !q) return LC_ERR_NULL;
+    int P, Q;
+    const lc_status st = check_desc(desc, &P, &Q);
+    if (st != LC_OK) return st;
+    *p = P;
+    *q = Q;
+    return LC_OK;
+}
+
+extern "C" size_t conv2d_workspace_bytes(const lc_conv_desc* desc, lc_pass pass) {
+    Plan pl;
+    if (make_plan(desc, pass, &pl) != LC_OK) return 0;
+    return pl.total;
+}
+
+extern "C" lc_status conv2d_fwd(const lc_conv_desc* d, const void* x, const void* w, void* y,
+                                void* workspace, size_t workspace_bytes, void* hip_stream) {
+    Plan pl;
+    lc_status st = make_plan(d, LC_PASS_FWD, &pl);
+    if (st != LC_OK) return st;
+    st = check_buffers(d, pl, x, w, y, workspace, workspace_bytes);
+    if (st != LC_OK) return st;
+    if (((uintptr_t)y) & (uintptr_t)(pl.esize - 1)) return LC_ERR_ALIGN;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+
+    const void* xs = x;
+    const void* wsrc = w;
+    void* ydst = y;
+    if (pl.nchw) {
+        lc_nchw_to_nhwc(x, at(workspace, pl.a_nhwc), d->n, d->c, d->h * d->w, pl.esize, stream);
+        lc_nchw_to_nhwc(w, at(workspace, pl.b_nhwc), d->k, d->c, d->r * d->s, pl.esize, stream);
+        xs = at(workspace, pl.a_nhwc);
+        wsrc = at(workspace, pl.b_nhwc);
+        ydst = at(workspace, pl.out_nhwc);
+    }
+    if (pl.cpad != d->c) {
+        lc_pad_channels(xs, at(workspace, pl.xpad), (size_t)d->n * d->h * d->w, d->c, pl.cpad, pl.esize, stream);
+        lc_pad_channels(wsrc, at(workspace, pl.wpad), (size_t)d->k * d->r * d->s, d->c, pl.cpad, pl.esize, stream);
+        xs = at(workspace, pl.xpad);
+        wsrc = at(workspace, pl.wpad);
+    }
+    GemmConv g = {};
+    g.a = xs;
+    g.b = wsrc;
+    g.d = ydst;
+    g.M = d->n * pl.P * pl.Q;
+    g.N = d->k;
+    g.Kg = d->r * d->s * pl.cpad;
+    g.Hi = d->h;
+    g.Wi = d->w;
+    g.Ci = pl.cpad;
+    g.Po = pl.P;
+    g.Qo = pl.Q;
+    g.R = d->r;
+    g.S = d->s;
+    g.sh = d->stride_h;
+    g.sw = d->stride_w;
+    g.ph = d->pad_h;
+    g.pw = d->pad_w;
+    g.dh = g.dw = 1;
+    g.ldd = d->k;
+    st = lc_launch_conv_gemm_f32(g, stream);
+    if (st != LC_OK) return st;
+    if (pl.nchw) lc_nhwc_to_nchw(ydst, y, d->n, d->k, pl.P * pl.Q, pl.esize, stream);
+    return hipGetLastError() == hipSuccess ? LC_OK : LC_ERR_LAUNCH;
+}
+
+extern "C" lc_status conv2d_bwd_data(const lc_conv_desc* d, const void* dy, const void* w, void* dx,
+                                     void* workspace, size_t workspace_bytes, void* hip_stream) {
+    Plan pl;
+    lc_status st = make_plan(d, LC_PASS_BWD_DATA, &pl);
+    if (st != LC_OK) return st;
+    st = check_buffers(d, pl, dy, w, dx, workspace, workspace_bytes);
+    if (st != LC_OK) return st;
+    if (((uintptr_t)dx) & (uintptr_t)(pl.esize - 1)) return LC_ERR_ALIGN;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+
+    const void* dys = dy;
+    const void* wsrc = w;
+    void* dxdst = dx;
+    if (pl.nchw) {
+        lc_nchw_to_nhwc(dy, at(workspace, pl.a_nhwc), d->n, d->k, pl.P * pl.Q, pl.esize, stream);
+        lc_nchw_to_nhwc(w, at(workspace, pl.b_nhwc), d->k, d->c, d->r * d->s, pl.esize, stream);
+        dys = at(workspace, pl.a_nhwc);
+        wsrc = at(workspace, pl.b_nhwc);
+        dxdst = at(workspace, pl.out_nhwc);
+    }
+    // filter of the backward convolution: [c][R-1-r][S-1-s][k]
+    void* wt = at(workspace, pl.wt);
+    lc_filter_for_bwd_data(wsrc, wt, d->k, d->c, d->r, d->s, pl.esize, stream);
+
+    GemmConv g = {};
+    g.a = dys;
+    g.b = wt;
+    g.d = dxdst;
+    g.N = d->c;
+    g.Kg = d->r * d->s * d->k;
+    g.Hi = pl.P;
+    g.Wi = pl.Q;
+    g.Ci = d->k;
+    g.R = d->r;
+    g.S = d->s;
+    g.ldd = d->c;
+    g.dh = g.dw = 1;
+    if (d->r == 1 && d->s == 1 && d->pad_h == 0 && d->pad_w == 0) {
+        // 1x1 window: one GEMM row per dy pixel; with a stride the result lands on the stride grid
+        // of dx and the rest of each stride cell is zero.
+        g.M = d->n * pl.P * pl.Q;
+        g.Po = pl.P;
+        g.Qo = pl.Q;
+        g.sh = g.sw = 1;
+        g.ph = g.pw = 0;
+        if (d->stride_h > 1 || d->stride_w > 1) {
+            g.scatter = 1;
+            g.Ho = d->h;
+            g.Wo = d->w;
+            g.esh = d->stride_h;
+            g.esw = d->stride_w;
+        }
+    } else {
+        // one GEMM row per dx pixel, reading dy as if zeros were inserted between its pixels
+        g.M = d->n * d->h * d->w;
+        g.Po = d->h;
+        g.Qo = d->w;
+        g.sh = g.sw = 1;
+        g.ph = d->r - 1 - d->pad_h;
+        g.pw = d->s - 1 - d->pad_w;
+        g.dh = d->stride_h;
+        g.dw = d->stride_w;
+    }
+    st = lc_launch_conv_gemm_f32(g, stream);
+    if (st != LC_OK) return st;
+    if (pl.nchw) lc_nhwc_to_nchw(dxdst, dx, d->n, d->c, d->h * d->w, pl.esize, stream);
+    return hipGetLastError() == hipSuccess ? LC_OK : LC_ERR_LAUNCH;
+}
+
+extern "C" lc_status conv2d_bwd_weight(const lc_conv_desc* d, const void* x, const void* dy, float* dw,
+                                       void* workspace, size_t workspace_bytes, void* hip_stream) {
+    Plan pl;
+    lc_status st = make_plan(d, LC_PASS_BWD_WEIGHT, &pl);
+    if (st != LC_OK) return st;
+    st = check_buffers(d, pl, x, dy, dw, workspace, workspace_bytes);
+    if (st != LC_OK) return st;
+    if (((uintptr_t)dw) & 3) return LC_ERR_ALIGN;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+
+    const void* xs = x;
+    const void* dys = dy;
+    float* dwdst = dw;
+    if (pl.nchw) {
+        lc_nchw_to_nhwc(x, at(workspace, pl.a_nhwc), d->n, d->c, d->h * d->w, pl.esize, stream);
+        lc_nchw_to_nhwc(dy, at(workspace, pl.b_nhwc), d->n, d->k, pl.P * pl.Q, pl.esize, stream);
+        xs = at(workspace, pl.a_nhwc);
+        dys = at(workspace, pl.b_nhwc);
+        dwdst = reinterpret_cast<float*>(at(workspace, pl.out_nhwc));
+    }
+    if (pl.cpad != d->c) {
+        lc_pad_channels(xs, at(workspace, pl.xpad), (size_t)d->n * d->h * d->w, d->c, pl.cpad, pl.esize, stream);
+        xs = at(workspace, pl.xpad);
+    }
+    GemmWgrad g = {};
+    g.dy = dys;
+    g.x = xs;
+    g.M = d->n * pl.P * pl.Q;
+    g.K = d->k;
+    g.J = d->r * d->s * pl.cpad;
+    g.H = d->h;
+    g.W = d->w;
+    g.C = pl.cpad;
+    g.P = pl.P;
+    g.Q = pl.Q;
+    g.R = d->r;
+    g.S = d->s;
+    g.sh = d->stride_h;
+    g.sw = d->stride_w;
+    g.ph = d->pad_h;
+    g.pw = d->pad_w;
+    g.splits = pl.splits;
+    g.m_per_split = pl.m_per_split;
+    g.d = pl.wgrad_direct ? dwdst : reinterpret_cast<float*>(at(workspace, pl.part));
+    st = lc_launch_wgrad_f32(g, stream);
+    if (st != LC_OK) return st;
+    if (!pl.wgrad_direct)
+        lc_reduce_splits(g.d, dwdst, pl.splits, (size_t)d->k * g.J, pl.cpad, d->c, stream);
+    if (pl.nchw) lc_nhwc_to_nchw(dwdst, dw, d->k, d->c, d->r * d->s, 4, stream);
+    return hipGetLastError() == hipSuccess ? LC_OK : LC_ERR_LAUNCH;
+}
+
+extern "C" const char* lc_status_string(lc_status status) {
+    switch (status) {
+        case LC_OK: return "ok";
+        case LC_ERR_NULL: return "null pointer";
+        case LC_ERR_SHAPE: return "invalid shape";
+        case LC_ERR_UNSUPPORTED: return "unsupported configuration";
+        case LC_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
+        case LC_ERR_LAUNCH: return "HIP launch error";
+        case LC_ERR_ALIGN: return "misaligned tensor pointer";
+    }
+    return "unknown status";
+}

@@ -1,0 +1,60 @@
+// Declarations shared by the translation units of liblarsconv (not part of the C ABI).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "../../include/larsconv.h"
+
+// ---- small device-side utilities (layout.hip) ----
+void lc_fill_f32(float* dst, float value, size_t count, hipStream_t stream);
+void lc_fill_u32x4(void* dst, size_t bytes16, hipStream_t stream);   // zero `bytes16` * 16 bytes
+
+// NCHW <-> NHWC for activations ([n][c][hw] <-> [n][hw][c]); esize 4 (fp32) or 2 (bf16).
+void lc_nchw_to_nhwc(const void* src, void* dst, int n, int c, int hw, int esize, hipStream_t stream);
+void lc_nhwc_to_nchw(const void* src, void* dst, int n, int c, int hw, int esize, hipStream_t stream);
+
+// Filter re-ordering.  All take and give fp32 or bf16 by esize.
+//  KRSC -> [c][R-1-r][S-1-s][k]  (the filter of the backward-data convolution)
+void lc_filter_for_bwd_data(const void* w_krsc, void* out, int k, int c, int r, int s, int esize, hipStream_t stream);
+//  pad the channel dimension (innermost) of an [rows][c] array with zeros to [rows][cpad]
+void lc_pad_channels(const void* src, void* dst, size_t rows, int c, int cpad, int esize, hipStream_t stream);
+
+// dw[k][j] (j < cols, c index j % cpad < c kept) = sum over splits of part[z][k][cols] in index order.
+void lc_reduce_splits(const float* part, float* dw, int splits, size_t rows_times_cols, int cpad, int c, hipStream_t stream);
+
+// ---- implicit-GEMM convolution kernels (conv_igemm.hip) ----
+// One problem D[m][n] = sum_kg A(m, kg) * B[n][kg] where A is gathered from an NHWC tensor:
+// row m = (img, po, qo), column kg = (r, s, ci).
+struct GemmConv {
+    const void* a;      // gathered tensor [imgs][Hi][Wi][Ci]
+    const void* b;      // [N][Kg], Kg = R*S*Ci contiguous
+    void* d;            // output rows of ldd elements
+    int M, N, Kg;
+    int Hi, Wi, Ci;
+    int Po, Qo;         // m -> (img, po, qo)
+    int R, S;
+    int sh, sw;         // position stride:  h = po*sh - ph + r
+    int ph, pw;
+    int dh, dw;         // > 1: "dilated" read, valid only where h % dh == 0, then h /= dh
+    int ldd;
+    // scatter epilogue (0 = off): row (img,po,qo) owns the cell [po*esh, po*esh+esh) x [qo*esw, ...) of
+    // an [imgs][Ho][Wo][ldd] tensor; the value goes to the cell's corner, zeros to the rest of it.
+    int scatter, Ho, Wo, esh, esw;
+};
+lc_status lc_launch_conv_gemm_f32(const GemmConv& p, hipStream_t stream);
+
+// Filter gradient: D[k][j] = sum_m dY[m][k] * Xg(m, j), m = (img, p, q), j = (r, s, c); the reduction
+// over m is cut into `splits` ranges, split z writing to d + z * K * J.
+struct GemmWgrad {
+    const void* dy;     // [M][K]
+    const void* x;      // [imgs][H][W][C]
+    float* d;           // [splits][K][J]
+    int M, K, J;
+    int H, W, C, P, Q, R, S;
+    int sh, sw, ph, pw;
+    int splits, m_per_split;
+};
+lc_status lc_launch_wgrad_f32(const GemmWgrad& p, hipStream_t stream);
+int lc_wgrad_splits(int M, int K, int J);   // fixed function of the shape (determinism)

@@ -1,0 +1,313 @@
+// Layer-wise LARS update for gfx950: segmented per-tensor norm reduction, then one streaming
+// update pass.  Both kernels are bound by HBM bandwidth: 8 B/param for the norms (read w, g) and
+// 20 B/param for the update (read w, g, v; write w, v), 22 with the bf16 weight copy.
+//
+// The parameter list is cut into fixed-size chunks of one tensor each, so that 161 tensors of
+// 64 .. 2.4 M elements (ResNet-50) load the chip evenly and no launch is made per tensor.
+//   1. lars_table_kernel   copies the per-tensor descriptors (passed as kernel arguments, so the
+//                          call needs no host staging buffer and no copy engine) into the
+//                          workspace, fills the chunk -> tensor map and clears the arrival counters.
+//   2. lars_norm_kernel    one block per chunk: sum w^2 and sum g^2 (fp32 per thread over 16
+//                          elements, then fp64 across lanes with wavefront shuffles and across waves
+//                          through LDS) -> one fp64 partial per chunk.  The block that arrives last
+//                          for a tensor adds that tensor's partials in index order and writes the
+//                          trust ratio: the result does not depend on which block was last.
+//   3. lars_update_kernel  one block per chunk, chunks taken in reverse so that the tail of the
+//                          norm pass, still resident in L2 / Infinity Cache, is re-read first.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "internal.h"
+
+namespace {
+
+constexpr int kThreads = 256;
+constexpr int kVecPerThread = 4;                            // float4 loads per thread per array
+constexpr int kChunk = kThreads * kVecPerThread * 4;        // 4096 elements
+constexpr int kTablePerLaunch = 64;                         // descriptors per table launch (3 KB of kernel arguments)
+
+struct LarsTensor {
+    float* w;
+    const float* g;
+    float* v;
+    uint16_t* w_lowp;      // bf16 copy of the new weights or null
+    long long numel;
+    int chunk_start;       // first chunk of this tensor
+    int n_chunks;
+};
+static_assert(sizeof(LarsTensor) == 48, "descriptor layout");
+
+struct LarsTableArgs {
+    LarsTensor t[kTablePerLaunch];
+    int first;             // index of t[0] in the full list
+    int count;
+};
+
+struct LarsWorkspace {      // device pointers carved out of the caller's workspace
+    LarsTensor* table;
+    int* chunk_tensor;
+    double* partial;        // [n_chunks][2]
+    unsigned int* arrived;  // [n_tensors]
+    float* step_scale;      // [n_tensors]  lr * trust
+};
+
+__global__ void __launch_bounds__(kThreads) lars_table_kernel(const LarsTableArgs args, LarsWorkspace ws) {
+    const int i = blockIdx.x;
+    if (i >= args.count) return;
+    const LarsTensor t = args.t[i];
+    const int l = args.first + i;
+    if (threadIdx.x == 0) {
+        ws.table[l] = t;
+        ws.arrived[l] = 0u;
+    }
+    for (int c = threadIdx.x; c < t.n_chunks; c += kThreads) ws.chunk_tensor[t.chunk_start + c] = l;
+}
+
+__device__ __forceinline__ double wave_sum(double x) {
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) x += __shfl_xor(x, off, 64);
+    return x;
+}
+
+// Sum over the block in a fixed tree; every thread returns the total.
+__device__ __forceinline__ double2 block_sum2(double a, double b, double* lds /* 2*4 doubles */) {
+    a = wave_sum(a);
+    b = wave_sum(b);
+    const int wave = threadIdx.x >> 6;
+    __syncthreads();
+    if ((threadIdx.x & 63) == 0) {
+        lds[wave] = a;
+        lds[4 + wave] = b;
+    }
+    __syncthreads();
+    return make_double2((lds[0] + lds[1]) + (lds[2] + lds[3]), (lds[4] + lds[5]) + (lds[6] + lds[7]));
+}
+
+__global__ void __launch_bounds__(kThreads)
+lars_norm_kernel(LarsWorkspace ws, float eta, float weight_decay, float lr, float* __restrict__ trust_out) {
+    __shared__ double red[8];
+    __shared__ int is_last;
+    const int chunk = blockIdx.x;
+    const int l = ws.chunk_tensor[chunk];
+    const LarsTensor t = ws.table[l];
+    const long long off = (long long)(chunk - t.chunk_start) * kChunk;
+    const long long rem = t.numel - off;
+    const int len = rem < kChunk ? (int)rem : kChunk;
+    const float* __restrict__ w = t.w + off;
+    const float* __restrict__ g = t.g + off;
+
+    float sw = 0.f, sg = 0.f;
+    const bool vec = ((((uintptr_t)w) | ((uintptr_t)g)) & 15) == 0;
+    if (vec && len == kChunk) {
+        float4 a[kVecPerThread], b[kVecPerThread];
+#pragma unroll
+        for (int i = 0; i < kVecPerThread; ++i) {
+            a[i] = reinterpret_cast<const float4*>(w)[threadIdx.x + i * kThreads];
+            b[i] = reinterpret_cast<const float4*>(g)[threadIdx.x + i * kThreads];
+        }
+#pragma unroll
+        for (int i = 0; i < kVecPerThread; ++i) {
+            sw += a[i].x * a[i].x + a[i].y * a[i].y + a[i].z * a[i].z + a[i].w * a[i].w;
+            sg += b[i].x * b[i].x + b[i].y * b[i].y + b[i].z * b[i].z + b[i].w * b[i].w;
+        }
+    } else {
+        for (int i = threadIdx.x; i < len; i += kThreads) {
+            const float x = w[i], y = g[i];
+            sw += x * x;
+            sg += y * y;
+        }
+    }
+    const double2 s = block_sum2((double)sw, (double)sg, red);
+
+    // publish the partial, then count arrivals; the last block of the tensor finishes it
+    if (threadIdx.x == 0) {
+        __hip_atomic_store(&ws.partial[2 * chunk], s.x, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __hip_atomic_store(&ws.partial[2 * chunk + 1], s.y, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        const unsigned int before =
+            __hip_atomic_fetch_add(&ws.arrived[l], 1u, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
+        is_last = (before + 1u == (unsigned int)t.n_chunks);
+    }
+    __syncthreads();
+    if (!is_last) return;
+
+    double pw = 0.0, pg = 0.0;
+    for (int c = threadIdx.x; c < t.n_chunks; c += kThreads) {
+        pw += __hip_atomic_load(&ws.partial[2 * (t.chunk_start + c)], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        pg += __hip_atomic_load(&ws.partial[2 * (t.chunk_start + c) + 1], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    const double2 tot = block_sum2(pw, pg, red);
+    if (threadIdx.x == 0) {
+        const double nw = sqrt(tot.x), ng = sqrt(tot.y);
+        const double den = ng + (double)weight_decay * nw;
+        const double trust = (nw > 0.0 && den > 0.0) ? (double)eta * nw / den : 1.0;
+        ws.step_scale[l] = (float)((double)lr * trust);
+        if (trust_out) trust_out[l] = (float)trust;
+    }
+}
+
+__device__ __forceinline__ uint16_t bf16_rne(float x) {
+    const uint32_t u = __float_as_uint(x);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40u);   // NaN stays NaN
+    return (uint16_t)((u + 0x7fffu + ((u >> 16) & 1u)) >> 16);
+}
+
+__global__ void __launch_bounds__(kThreads)
+lars_update_kernel(LarsWorkspace ws, int n_chunks, float momentum, float weight_decay) {
+    const int chunk = n_chunks - 1 - (int)blockIdx.x;
+    const int l = ws.chunk_tensor[chunk];
+    const LarsTensor t = ws.table[l];
+    const float scale = ws.step_scale[l];
+    const long long off = (long long)(chunk - t.chunk_start) * kChunk;
+    const long long rem = t.numel - off;
+    const int len = rem < kChunk ? (int)rem : kChunk;
+    float* __restrict__ w = t.w + off;
+    const float* __restrict__ g = t.g + off;
+    float* __restrict__ v = t.v + off;
+    uint16_t* __restrict__ lp = t.w_lowp ? t.w_lowp + off : nullptr;
+
+    const bool vec = ((((uintptr_t)w) | ((uintptr_t)g) | ((uintptr_t)v)) & 15) == 0 && (((uintptr_t)lp) & 7) == 0;
+    if (vec && len == kChunk) {
+        float4 a[kVecPerThread], b[kVecPerThread], m[kVecPerThread];
+#pragma unroll
+        for (int i = 0; i < kVecPerThread; ++i) {
+            a[i] = reinterpret_cast<const float4*>(w)[threadIdx.x + i * kThreads];
+            b[i] = reinterpret_cast<const float4*>(g)[threadIdx.x + i * kThreads];
+            m[i] = reinterpret_cast<const float4*>(v)[threadIdx.x + i * kThreads];
+        }
+#pragma unroll
+        for (int i = 0; i < kVecPerThread; ++i) {
+            float4 nv, nw;
+            nv.x = fmaf(momentum, m[i].x, scale * fmaf(weight_decay, a[i].x, b[i].x));
+            nv.y = fmaf(momentum, m[i].y, scale * fmaf(weight_decay, a[i].y, b[i].y));
+            nv.z = fmaf(momentum, m[i].z, scale * fmaf(weight_decay, a[i].z, b[i].z));
+            nv.w = fmaf(momentum, m[i].w, scale * fmaf(weight_decay, a[i].w, b[i].w));
+            nw.x = a[i].x - nv.x;
+            nw.y = a[i].y - nv.y;
+            nw.z = a[i].z - nv.z;
+            nw.w = a[i].w - nv.w;
+            reinterpret_cast<float4*>(v)[threadIdx.x + i * kThreads] = nv;
+            reinterpret_cast<float4*>(w)[threadIdx.x + i * kThreads] = nw;
+            if (lp) {
+                ushort4 h;
+                h.x = bf16_rne(nw.x);
+                h.y = bf16_rne(nw.y);
+                h.z = bf16_rne(nw.z);
+                h.w = bf16_rne(nw.w);
+                reinterpret_cast<ushort4*>(lp)[threadIdx.x + i * kThreads] = h;
+            }
+        }
+    } else {
+        for (int i = threadIdx.x; i < len; i += kThreads) {
+            const float x = w[i];
+            const float nv = fmaf(momentum, v[i], scale * fmaf(weight_decay, x, g[i]));
+            const float nw = x - nv;
+            v[i] = nv;
+            w[i] = nw;
+            if (lp) lp[i] = bf16_rne(nw);
+        }
+    }
+}
+
+// Workspace carving shared by the size query and the call.
+struct LarsLayout {
+    size_t table, chunk_tensor, partial, arrived, step_scale, total;
+    long long n_chunks;
+};
+
+bool lars_layout(int n_tensors, const int64_t* numel, LarsLayout* out) {
+    long long chunks = 0;
+    for (int l = 0; l < n_tensors; ++l) {
+        if (numel[l] < 0) return false;
+        chunks += (numel[l] + kChunk - 1) / kChunk;
+    }
+    if (chunks > 0x7fffffffLL) return false;
+    size_t off = 0;
+    auto take = [&](size_t bytes) {
+        const size_t at = off;
+        off += (bytes + 255) & ~(size_t)255;
+        return at;
+    };
+    out->table = take(sizeof(LarsTensor) * (size_t)n_tensors);
+    out->chunk_tensor = take(sizeof(int) * (size_t)chunks);
+    out->partial = take(sizeof(double) * 2 * (size_t)chunks);
+    out->arrived = take(sizeof(unsigned int) * (size_t)n_tensors);
+    out->step_scale = take(sizeof(float) * (size_t)n_tensors);
+    out->total = off;
+    out->n_chunks = chunks;
+    return true;
+}
+
+}  // namespace
+
+extern "C" size_t lars_workspace_bytes(int n_tensors, const int64_t* numel) {
+    LarsLayout lay;
+    if (n_tensors <= 0 || !numel || !lars_layout(n_tensors, numel, &lay)) return 0;
+    return lay.total;
+}
+
+extern "C" lc_status lars_step(int n_tensors, float* const* w, const float* const* g, float* const* v,
+                               const int64_t* numel, float eta, float momentum, float weight_decay, float lr,
+                               float* trust_out, void* const* w_lowp_out,
+                               void* workspace, size_t workspace_bytes, void* hip_stream) {
+    if (n_tensors < 0) return LC_ERR_SHAPE;
+    if (n_tensors == 0) return LC_OK;
+    if (!w || !g || !v || !numel) return LC_ERR_NULL;
+    LarsLayout lay;
+    if (!lars_layout(n_tensors, numel, &lay)) return LC_ERR_SHAPE;
+    for (int l = 0; l < n_tensors; ++l) {
+        if (numel[l] == 0) continue;
+        if (!w[l] || !g[l] || !v[l]) return LC_ERR_NULL;
+        if ((((uintptr_t)w[l]) | ((uintptr_t)g[l]) | ((uintptr_t)v[l])) & 3) return LC_ERR_ALIGN;
+        if (w_lowp_out && (((uintptr_t)w_lowp_out[l]) & 1)) return LC_ERR_ALIGN;
+    }
+    if (!workspace || (((uintptr_t)workspace) & 255) || workspace_bytes < lay.total) return LC_ERR_WORKSPACE;
+
+    char* base = static_cast<char*>(workspace);
+    LarsWorkspace ws;
+    ws.table = reinterpret_cast<LarsTensor*>(base + lay.table);
+    ws.chunk_tensor = reinterpret_cast<int*>(base + lay.chunk_tensor);
+    ws.partial = reinterpret_cast<double*>(base + lay.partial);
+    ws.arrived = reinterpret_cast<unsigned int*>(base + lay.arrived);
+    ws.step_scale = reinterpret_cast<float*>(base + lay.step_scale);
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+
+    LarsTableArgs args;
+    int chunk_cursor = 0;
+    for (int first = 0; first < n_tensors; first += kTablePerLaunch) {
+        const int count = (n_tensors - first) < kTablePerLaunch ? (n_tensors - first) : kTablePerLaunch;
+        for (int i = 0; i < count; ++i) {
+            const int l = first + i;
+            LarsTensor& t = args.t[i];
+            t.w = w[l];
+            t.g = g[l];
+            t.v = v[l];
+            t.w_lowp = w_lowp_out ? static_cast<uint16_t*>(w_lowp_out[l]) : nullptr;
+            t.numel = numel[l];
+            t.chunk_start = chunk_cursor;
+            t.n_chunks = (int)((numel[l] + kChunk - 1) / kChunk);
+            chunk_cursor += t.n_chunks;
+        }
+        args.first = first;
+        args.count = count;
+        hipLaunchKernelGGL(lars_table_kernel, dim3(count), dim3(kThreads), 0, stream, args, ws);
+    }
+    if (hipGetLastError() != hipSuccess) return LC_ERR_LAUNCH;
+    if (trust_out) {
+        // empty tensors have no chunk and therefore no block: their ratio is 1 by definition
+        bool any_empty = false;
+        for (int l = 0; l < n_tensors; ++l) any_empty |= (numel[l] == 0);
+        if (any_empty) lc_fill_f32(trust_out, 1.0f, (size_t)n_tensors, stream);
+    }
+    if (lay.n_chunks == 0) return hipGetLastError() == hipSuccess ? LC_OK : LC_ERR_LAUNCH;
+    const int n_chunks = (int)lay.n_chunks;
+    hipLaunchKernelGGL(lars_norm_kernel, dim3(n_chunks), dim3(kThreads), 0, stream, ws, eta, weight_decay, lr, trust_out);
+    hipLaunchKernelGGL(lars_update_kernel, dim3(n_chunks), dim3(kThreads), 0, stream, ws, n_chunks, momentum, weight_decay);
+    return hipGetLastError() == hipSuccess ? LC_OK : LC_ERR_LAUNCH;
+}
+
+extern "C" float lars_poly_lr(float base_lr, int64_t iter, int64_t max_iter, float power) {
+    if (max_iter <= 0) return base_lr;
+    double frac = 1.0 - (double)iter / (double)max_iter;
+    if (frac < 0.0) frac = 0.0;
+    return (float)((double)base_lr * pow(frac, (double)power));
+}

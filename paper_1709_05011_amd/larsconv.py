@@ -1,0 +1,194 @@
+"""Thin ctypes binding of liblarsconv.so: same names as the C ABI, argument marshalling only.
+
+Every function takes objects exposing ``data_ptr()`` (torch tensors on the GPU) or plain integer
+addresses, passes them through and raises :class:`LarsConvError` on a non-zero status.  Nothing is
+computed here, and there is no fallback: if the HIP library has not been built, loading fails.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from dataclasses import dataclass
+from typing import Optional, Sequence
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "liblarsconv.so")
+
+LC_OK, LC_ERR_NULL, LC_ERR_SHAPE, LC_ERR_UNSUPPORTED, LC_ERR_WORKSPACE, LC_ERR_LAUNCH, LC_ERR_ALIGN = range(7)
+LC_F32, LC_BF16 = 0, 1
+LC_NCHW, LC_NHWC = 0, 1
+LC_PASS_FWD, LC_PASS_BWD_DATA, LC_PASS_BWD_WEIGHT = 0, 1, 2
+
+EXPORTS = ["conv2d_out_shape", "conv2d_workspace_bytes", "conv2d_fwd", "conv2d_bwd_data", "conv2d_bwd_weight",
+           "lars_workspace_bytes", "lars_step", "lars_poly_lr", "lc_status_string"]
+
+
+class LarsConvError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {status_string(status)} (lc_status {status})")
+
+
+class lc_conv_desc(ctypes.Structure):
+    _fields_ = [(f, ctypes.c_int) for f in
+                ("n", "c", "h", "w", "k", "r", "s", "stride_h", "stride_w", "pad_h", "pad_w", "dtype", "layout")]
+
+
+@dataclass(frozen=True)
+class ConvDesc:
+    n: int
+    c: int
+    h: int
+    w: int
+    k: int
+    r: int
+    s: int
+    stride_h: int = 1
+    stride_w: int = 1
+    pad_h: int = 0
+    pad_w: int = 0
+    dtype: int = LC_F32
+    layout: int = LC_NHWC
+
+    def c_struct(self) -> lc_conv_desc:
+        return lc_conv_desc(self.n, self.c, self.h, self.w, self.k, self.r, self.s, self.stride_h, self.stride_w,
+                            self.pad_h, self.pad_w, self.dtype, self.layout)
+
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    """The loaded library; raises if it has not been built (run ``__graft_entry__.build()``)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} is missing: build it with __graft_entry__.build() "
+                               "(python -m paper_1709_05011_amd.build); there is no CPU fallback")
+        L = ctypes.CDLL(LIB_PATH)
+        vp, sz, i32 = ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int
+        dp = ctypes.POINTER(lc_conv_desc)
+        L.conv2d_out_shape.restype = i32
+        L.conv2d_out_shape.argtypes = [dp, ctypes.POINTER(i32), ctypes.POINTER(i32)]
+        L.conv2d_workspace_bytes.restype = sz
+        L.conv2d_workspace_bytes.argtypes = [dp, i32]
+        for name in ("conv2d_fwd", "conv2d_bwd_data", "conv2d_bwd_weight"):
+            fn = getattr(L, name)
+            fn.restype = i32
+            fn.argtypes = [dp, vp, vp, vp, vp, sz, vp]
+        L.lars_workspace_bytes.restype = sz
+        L.lars_workspace_bytes.argtypes = [i32, vp]
+        L.lars_step.restype = i32
+        L.lars_step.argtypes = [i32, vp, vp, vp, vp, ctypes.c_float, ctypes.c_float, ctypes.c_float, ctypes.c_float,
+                                vp, vp, vp, sz, vp]
+        L.lars_poly_lr.restype = ctypes.c_float
+        L.lars_poly_lr.argtypes = [ctypes.c_float, ctypes.c_int64, ctypes.c_int64, ctypes.c_float]
+        L.lc_status_string.restype = ctypes.c_char_p
+        L.lc_status_string.argtypes = [i32]
+        _lib = L
+    return _lib
+
+
+def _ptr(obj) -> Optional[int]:
+    if obj is None:
+        return None
+    if hasattr(obj, "data_ptr"):
+        return obj.data_ptr() or None
+    return int(obj) or None
+
+
+def _nbytes(ws) -> int:
+    if ws is None:
+        return 0
+    return ws.numel() * ws.element_size()
+
+
+def _stream(stream) -> Optional[int]:
+    if stream is None:
+        import torch
+        return torch.cuda.current_stream().cuda_stream or None
+    if hasattr(stream, "cuda_stream"):
+        return stream.cuda_stream or None
+    return int(stream) or None
+
+
+def _desc(desc) -> lc_conv_desc:
+    return desc.c_struct() if isinstance(desc, ConvDesc) else desc
+
+
+def _check(status: int, where: str) -> None:
+    if status != LC_OK:
+        raise LarsConvError(status, where)
+
+
+def status_string(status: int) -> str:
+    return lib().lc_status_string(status).decode()
+
+
+lc_status_string = status_string
+
+
+def conv2d_out_shape(desc):
+    p, q = ctypes.c_int(), ctypes.c_int()
+    _check(lib().conv2d_out_shape(ctypes.byref(_desc(desc)), ctypes.byref(p), ctypes.byref(q)), "conv2d_out_shape")
+    return p.value, q.value
+
+
+def conv2d_workspace_bytes(desc, pass_: int) -> int:
+    return int(lib().conv2d_workspace_bytes(ctypes.byref(_desc(desc)), pass_))
+
+
+def conv2d_fwd(desc, x, w, y, workspace=None, stream=None, workspace_bytes: Optional[int] = None) -> None:
+    nb = _nbytes(workspace) if workspace_bytes is None else workspace_bytes
+    _check(lib().conv2d_fwd(ctypes.byref(_desc(desc)), _ptr(x), _ptr(w), _ptr(y), _ptr(workspace), nb, _stream(stream)),
+           "conv2d_fwd")
+
+
+def conv2d_bwd_data(desc, dy, w, dx, workspace=None, stream=None, workspace_bytes: Optional[int] = None) -> None:
+    nb = _nbytes(workspace) if workspace_bytes is None else workspace_bytes
+    _check(lib().conv2d_bwd_data(ctypes.byref(_desc(desc)), _ptr(dy), _ptr(w), _ptr(dx), _ptr(workspace), nb,
+                                 _stream(stream)), "conv2d_bwd_data")
+
+
+def conv2d_bwd_weight(desc, x, dy, dw, workspace=None, stream=None, workspace_bytes: Optional[int] = None) -> None:
+    nb = _nbytes(workspace) if workspace_bytes is None else workspace_bytes
+    _check(lib().conv2d_bwd_weight(ctypes.byref(_desc(desc)), _ptr(x), _ptr(dy), _ptr(dw), _ptr(workspace), nb,
+                                   _stream(stream)), "conv2d_bwd_weight")
+
+
+def _i64_array(vals: Sequence[int]):
+    return (ctypes.c_int64 * max(len(vals), 1))(*vals)
+
+
+def _ptr_array(objs: Sequence):
+    return (ctypes.c_void_p * max(len(objs), 1))(*[_ptr(o) for o in objs])
+
+
+def lars_workspace_bytes(numel: Sequence[int]) -> int:
+    return int(lib().lars_workspace_bytes(len(numel), _i64_array(list(numel))))
+
+
+class LarsArgs:
+    """Host-side pointer and size arrays of one parameter list, marshalled once and reusable."""
+
+    def __init__(self, w: Sequence, g: Sequence, v: Sequence, numel: Optional[Sequence[int]] = None,
+                 w_lowp: Optional[Sequence] = None):
+        if numel is None:
+            numel = [t.numel() for t in w]
+        self.n = len(w)
+        self.numel = list(numel)
+        self.w, self.g, self.v = _ptr_array(w), _ptr_array(g), _ptr_array(v)
+        self.numel_arr = _i64_array(self.numel)
+        self.w_lowp = _ptr_array(w_lowp) if w_lowp is not None else None
+        self._keep = (list(w), list(g), list(v), list(w_lowp) if w_lowp is not None else None)
+
+
+def lars_step(args: LarsArgs, eta: float, momentum: float, weight_decay: float, lr: float, trust_out=None,
+              workspace=None, stream=None, workspace_bytes: Optional[int] = None) -> None:
+    nb = _nbytes(workspace) if workspace_bytes is None else workspace_bytes
+    _check(lib().lars_step(args.n, args.w, args.g, args.v, args.numel_arr, eta, momentum, weight_decay, lr,
+                           _ptr(trust_out), args.w_lowp, _ptr(workspace), nb, _stream(stream)), "lars_step")
+
+
+def lars_poly_lr(base_lr: float, it: int, max_iter: int, power: float = 2.0) -> float:
+    return float(lib().lars_poly_lr(base_lr, it, max_iter, power))

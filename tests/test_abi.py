@@ -1,0 +1,119 @@
+"""The C-ABI library on a machine without a GPU: it loads, exports every function the header
+declares, and rejects bad arguments before launching anything."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_1709_05011_amd import larsconv as lc
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+FAKE = 0x10000000  # never dereferenced: every call below fails validation first
+
+
+def _declared_functions():
+    text = open(os.path.join(ROOT, "include", "larsconv.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return re.findall(r"\b([a-z_0-9]+)\s*\([^;{]*\)\s*;", text)
+
+
+def test_header_functions_are_exported():
+    names = _declared_functions()
+    assert set(names) == set(lc.EXPORTS)
+    L = lc.lib()
+    for n in names:
+        assert hasattr(L, n), n
+
+
+def test_status_strings():
+    assert lc.status_string(lc.LC_OK) == "ok"
+    assert len({lc.status_string(i) for i in range(7)}) == 7
+    assert lc.status_string(99) == "unknown status"
+
+
+def test_out_shape_and_descriptor_validation():
+    assert lc.conv2d_out_shape(lc.ConvDesc(1, 3, 224, 224, 64, 7, 7, 2, 2, 3, 3)) == (112, 112)
+    assert lc.conv2d_out_shape(lc.ConvDesc(1, 3, 227, 227, 96, 11, 11, 4, 4, 0, 0)) == (55, 55)
+    assert lc.conv2d_out_shape(lc.ConvDesc(1, 256, 56, 56, 512, 1, 1, 2, 2, 0, 0)) == (28, 28)
+    for bad in [lc.ConvDesc(0, 3, 8, 8, 4, 3, 3), lc.ConvDesc(1, 3, 8, 8, 4, 3, 3, 0, 1),
+                lc.ConvDesc(1, 3, 8, 8, 4, 3, 3, 1, 1, -1, 0), lc.ConvDesc(1, 3, 2, 2, 4, 3, 3)]:
+        with pytest.raises(lc.LarsConvError) as e:
+            lc.conv2d_out_shape(bad)
+        assert e.value.status == lc.LC_ERR_SHAPE
+    with pytest.raises(lc.LarsConvError) as e:
+        lc.conv2d_out_shape(lc.ConvDesc(1, 3, 8, 8, 4, 3, 3, dtype=7))
+    assert e.value.status == lc.LC_ERR_UNSUPPORTED
+    with pytest.raises(lc.LarsConvError) as e:
+        lc.conv2d_out_shape(lc.ConvDesc(1, 3, 8, 8, 4, 3, 3, layout=2))
+    assert e.value.status == lc.LC_ERR_UNSUPPORTED
+    assert lc.lib().conv2d_out_shape(None, None, None) == lc.LC_ERR_NULL
+
+
+def test_workspace_queries():
+    nhwc = lc.ConvDesc(8, 64, 14, 14, 64, 3, 3, 1, 1, 1, 1)
+    assert lc.conv2d_workspace_bytes(nhwc, lc.LC_PASS_FWD) == 0
+    assert lc.conv2d_workspace_bytes(nhwc, lc.LC_PASS_BWD_DATA) >= 64 * 64 * 9 * 4
+    assert lc.conv2d_workspace_bytes(nhwc, lc.LC_PASS_BWD_WEIGHT) % 256 == 0
+    nchw = lc.ConvDesc(8, 64, 14, 14, 64, 3, 3, 1, 1, 1, 1, layout=lc.LC_NCHW)
+    assert lc.conv2d_workspace_bytes(nchw, lc.LC_PASS_FWD) >= 2 * 8 * 64 * 14 * 14 * 4
+    assert lc.conv2d_workspace_bytes(lc.ConvDesc(0, 1, 1, 1, 1, 1, 1), lc.LC_PASS_FWD) == 0
+    assert lc.lars_workspace_bytes([64, 0, 5000]) > 0
+    assert lc.lars_workspace_bytes([]) == 0
+    assert lc.lars_workspace_bytes([-1]) == 0
+
+
+@pytest.mark.parametrize("fn", [lc.conv2d_fwd, lc.conv2d_bwd_data, lc.conv2d_bwd_weight])
+def test_conv_calls_reject_bad_arguments_before_launch(fn):
+    d = lc.ConvDesc(2, 8, 9, 9, 8, 3, 3, 1, 1, 1, 1, layout=lc.LC_NCHW)   # needs a workspace in every pass
+
+    def status(*args, **kw):
+        with pytest.raises(lc.LarsConvError) as e:
+            fn(*args, stream=0, **kw)
+        return e.value.status
+
+    assert status(d, None, FAKE, FAKE) == lc.LC_ERR_NULL
+    assert status(d, FAKE, FAKE, None) == lc.LC_ERR_NULL
+    assert status(d, FAKE + 2, FAKE, FAKE, FAKE, workspace_bytes=1 << 30) == lc.LC_ERR_ALIGN
+    assert status(d, FAKE, FAKE, FAKE, None, workspace_bytes=0) == lc.LC_ERR_WORKSPACE
+    assert status(d, FAKE, FAKE, FAKE, FAKE, workspace_bytes=16) == lc.LC_ERR_WORKSPACE
+    assert status(d, FAKE, FAKE, FAKE, FAKE + 64, workspace_bytes=1 << 30) == lc.LC_ERR_WORKSPACE
+    assert status(lc.ConvDesc(2, 8, 9, 9, 8, 3, 3, 1, 1, 1, 1, dtype=5), FAKE, FAKE, FAKE) == lc.LC_ERR_UNSUPPORTED
+    assert status(lc.ConvDesc(2, 8, 2, 2, 8, 3, 3), FAKE, FAKE, FAKE) == lc.LC_ERR_SHAPE
+    assert status(lc.ConvDesc(1 << 20, 8, 64, 64, 8, 3, 3), FAKE, FAKE, FAKE) == lc.LC_ERR_UNSUPPORTED  # > 2^31 rows
+
+
+def test_lars_step_rejects_bad_arguments_before_launch():
+    L = lc.lib()
+    arr = (ctypes.c_void_p * 2)(FAKE, FAKE)
+    odd = (ctypes.c_void_p * 2)(FAKE, FAKE + 2)
+    null = (ctypes.c_void_p * 2)(FAKE, None)
+    numel = (ctypes.c_int64 * 2)(100, 5000)
+    neg = (ctypes.c_int64 * 2)(100, -5)
+
+    def call(w, g, v, n, ws, ws_bytes, count=2):
+        return L.lars_step(count, w, g, v, n, 0.001, 0.9, 5e-4, 1.0, None, None, ws, ws_bytes, None)
+
+    assert call(arr, arr, arr, numel, FAKE, 1 << 20, count=-1) == lc.LC_ERR_SHAPE
+    assert call(arr, arr, arr, numel, None, 0, count=0) == lc.LC_OK            # empty list: no-op
+    assert call(None, arr, arr, numel, FAKE, 1 << 20) == lc.LC_ERR_NULL
+    assert call(arr, null, arr, numel, FAKE, 1 << 20) == lc.LC_ERR_NULL
+    assert call(arr, arr, arr, neg, FAKE, 1 << 20) == lc.LC_ERR_SHAPE
+    assert call(arr, arr, odd, numel, FAKE, 1 << 20) == lc.LC_ERR_ALIGN
+    assert call(arr, arr, arr, numel, None, 0) == lc.LC_ERR_WORKSPACE
+    assert call(arr, arr, arr, numel, FAKE, 8) == lc.LC_ERR_WORKSPACE
+    assert call(arr, arr, arr, numel, FAKE + 8, 1 << 20) == lc.LC_ERR_WORKSPACE
+
+
+def test_poly_lr_host_arithmetic():
+    assert lc.lars_poly_lr(1.0, 0, 3516) == 1.0
+    assert lc.lars_poly_lr(1.0, 3516, 3516) == 0.0
+    assert abs(lc.lars_poly_lr(1.0, 1000, 3516) - (1 - 1000 / 3516) ** 2) < 1e-7
+    assert abs(lc.lars_poly_lr(0.2, 879, 3516) - 0.1125) < 1e-8
+
+
+def test_binding_has_no_fallback(monkeypatch):
+    monkeypatch.setattr(lc, "_lib", None)
+    monkeypatch.setattr(lc, "LIB_PATH", "/nonexistent/liblarsconv.so")
+    with pytest.raises(RuntimeError, match="no CPU fallback"):
+        lc.lib()

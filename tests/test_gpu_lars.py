@@ -1,0 +1,129 @@
+"""GPU parity: lars_step through the C ABI against the CPU oracle on the same seeded tensors.
+Tolerances: trust ratio |gpu - oracle| <= 1e-5 * oracle; new w and v max-error / max-value <= 1e-4
+(observed differences are a few fp32 ulps: the GPU updates in fp32, the oracle in double)."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_1709_05011_amd import larsconv as lc
+from paper_1709_05011_amd import synth
+
+import gpu_util as gu
+
+pytestmark = pytest.mark.gpu
+ETA, MOM = 0.001, 0.9
+
+
+def _tensors(sizes, seed, gstd=0.01, vstd=0.001):
+    w = [synth.normal((n,), seed + 3 * i) for i, n in enumerate(sizes)]
+    g = [synth.normal((n,), seed + 3 * i + 1, std=gstd) for i, n in enumerate(sizes)]
+    v = [synth.normal((n,), seed + 3 * i + 2, std=vstd) for i, n in enumerate(sizes)]
+    return w, g, v
+
+
+def _run_gpu(w, g, v, eta, mom, wd, lr, lowp=False, offset=0):
+    """Each tensor lives in its own device buffer, shifted by `offset` floats to break 16-byte alignment."""
+    def put(a):
+        buf = torch.empty(a.size + offset, dtype=torch.float32, device=gu.DEV)
+        view = buf[offset:]
+        view.copy_(torch.from_numpy(a))
+        return view
+    wd_, gd_, vd_ = [put(a) for a in w], [put(a) for a in g], [put(a) for a in v]
+    lp = [torch.zeros(a.size, dtype=torch.int16, device=gu.DEV) for a in w] if lowp else None
+    args = lc.LarsArgs(wd_, gd_, vd_, [a.size for a in w], lp)
+    trust = torch.full((len(w),), float("nan"), dtype=torch.float32, device=gu.DEV)
+    ws = gu.workspace(lc.lars_workspace_bytes(args.numel))
+    lc.lars_step(args, eta, mom, wd, lr, trust, ws)
+    torch.cuda.synchronize()
+    out_w = [t.cpu().numpy() for t in wd_]
+    out_v = [t.cpu().numpy() for t in vd_]
+    out_lp = [t.cpu().numpy().view(np.uint16) for t in lp] if lowp else None
+    return trust.cpu().numpy(), out_w, out_v, out_lp
+
+
+def _check(sizes, seed, wd, lr, **kw):
+    w, g, v = _tensors(sizes, seed)
+    f = np.float32
+    trust, gw, gv, glp = _run_gpu(w, g, v, ETA, MOM, wd, lr, **kw)
+    ow, ov = [a.copy() for a in w], [a.copy() for a in v]
+    # the C ABI takes float hyper-parameters: the oracle gets the same float values
+    otrust, _ = oracle.lars_step(ow, g, ov, float(f(ETA)), float(f(MOM)), float(f(wd)), float(f(lr)))
+    for l, n in enumerate(sizes):
+        assert abs(trust[l] - otrust[l]) <= 1e-5 * otrust[l], (l, n, trust[l], otrust[l])
+        if n:
+            assert gu.scaled_err(gw[l], ow[l]) <= 1e-4
+            assert gu.scaled_err(gv[l], ov[l]) <= 1e-4
+            # element-wise it is far tighter than the stated bar
+            np.testing.assert_allclose(gw[l], ow[l], rtol=2e-6, atol=1e-8)
+    return trust, gw, gv, glp
+
+
+def test_ragged_sizes_around_the_chunk_size():
+    _check([1, 63, 64, 4095, 4096, 4097, 10000, 3 * 4096 + 5, 0, 2, 8192], 100, 5e-4, 1.0)
+
+
+def test_hand_values():
+    w = [np.array([3, 4], np.float32), np.array([.5, .5, .5, .5], np.float32), np.array([3, 4], np.float32)]
+    g = [np.array([0.6, 0.8], np.float32), np.array([.25, -.25, .25, -.25], np.float32), np.zeros(2, np.float32)]
+    v = [np.zeros(2, np.float32), np.zeros(4, np.float32), np.zeros(2, np.float32)]
+    trust, gw, gv, _ = _run_gpu(w, g, v, ETA, MOM, 5e-4, 1.0)
+    np.testing.assert_allclose(trust, [0.004987531172069826, 0.0019980019980019984, 2.0], rtol=1e-6)
+    np.testing.assert_allclose(gv[0], [0.003, 0.004], rtol=1e-6)
+    np.testing.assert_allclose(gw[0], [2.997, 3.996], rtol=1e-6)
+    np.testing.assert_allclose(gw[2], [2.997, 3.996], rtol=1e-6)      # zero gradient: decay only
+
+
+def test_zero_norm_fallbacks_and_empty_list():
+    w = [np.zeros(3, np.float32), np.array([1, 2], np.float32), np.zeros(0, np.float32)]
+    g = [np.array([1, -2, 0.5], np.float32), np.zeros(2, np.float32), np.zeros(0, np.float32)]
+    v = [np.zeros(3, np.float32), np.array([0.5, 0.5], np.float32), np.zeros(0, np.float32)]
+    trust, gw, gv, _ = _run_gpu(w, g, v, ETA, 0.5, 0.0, 0.25)
+    assert trust.tolist() == [1.0, 1.0, 1.0]
+    np.testing.assert_array_equal(gw[0], np.array([-0.25, 0.5, -0.125], np.float32))
+    np.testing.assert_array_equal(gv[1], np.array([0.25, 0.25], np.float32))
+    np.testing.assert_array_equal(gw[1], np.array([0.75, 1.75], np.float32))
+    lc.lars_step(lc.LarsArgs([], [], [], []), ETA, MOM, 0.0, 1.0)      # n_tensors = 0: no-op
+
+
+def test_unaligned_tensors_take_the_scalar_path():
+    _check([5000, 4096, 9000], 200, 5e-4, 0.5, offset=1)
+
+
+def test_bf16_weight_copy_is_the_rounded_new_weight():
+    sizes = [4096 * 2, 777, 4097]
+    trust, gw, gv, glp = _check(sizes, 300, 5e-5, 0.7, lowp=True)
+    for l in range(len(sizes)):
+        want = oracle.round_to_bf16(gw[l]).view(np.uint32) >> 16
+        assert np.array_equal(glp[l].astype(np.uint32), want)
+
+
+@pytest.mark.parametrize("net", ["resnet50", "alexnet_bn"])
+def test_full_parameter_lists(net):
+    if net == "resnet50":
+        sizes, wd = synth.resnet50_param_numels(), 5e-5
+        lr = lc.lars_poly_lr(1.0, 1000, synth.poly_total_iters())
+    else:
+        sizes, wd, lr = synth.alexnet_bn_param_numels(), 5e-4, 1.0
+    print(f"{net}: {len(sizes)} tensors, {sum(sizes)} parameters, lr {lr}", flush=True)
+    _check(sizes, 400, wd, lr)
+
+
+def test_bit_reproducible_and_independent_of_list_order():
+    sizes = [64, 1, 4097, 300, 2048, 50000]
+    w, g, v = _tensors(sizes, 500)
+    t1, w1, v1, _ = _run_gpu(w, g, v, ETA, MOM, 5e-4, 0.7)
+    t2, w2, v2, _ = _run_gpu(w, g, v, ETA, MOM, 5e-4, 0.7)
+    assert np.array_equal(t1, t2) and all(np.array_equal(a, b) for a, b in zip(w1, w2))
+    perm = [5, 3, 0, 4, 2, 1]
+    t3, w3, v3, _ = _run_gpu([w[i] for i in perm], [g[i] for i in perm], [v[i] for i in perm], ETA, MOM, 5e-4, 0.7)
+    for j, i in enumerate(perm):
+        assert t1[i] == t3[j] and np.array_equal(w1[i], w3[j]) and np.array_equal(v1[i], v3[j])
+
+
+def test_step_length_invariant_on_gpu():
+    # beta = 0, m = 0: ||delta w|| / ||w|| = lr * eta for any gradient
+    w, g, v = _tensors([100000], 600, gstd=3.0)
+    _, gw, _, _ = _run_gpu(w, g, [np.zeros_like(w[0])], ETA, 0.0, 0.0, 0.5)
+    ratio = np.linalg.norm(gw[0].astype(np.float64) - w[0]) / np.linalg.norm(w[0].astype(np.float64))
+    assert abs(ratio - 0.5 * ETA) < 1e-4 * 0.5 * ETA
