@@ -1,0 +1,351 @@
+#!/usr/bin/env python3
+"""Benchmark of the conv + LARS training hot path on one MI355X.
+
+Default run (the driver's contract): one "step" = forward of all 53 ResNet-50 convolutions and the
+classifier, backward-data and backward-weight of every layer (no backward-data for the first
+layer: there is no gradient with respect to the image), then one lars_step over the 161 parameter
+tensors, fp32, batch 256, NHWC, synthetic N(0,1) inputs resident in HBM.  Prints ONE JSON line:
+images/s, plus "roofline" for the dominant kernel and "cpu_baseline" (the CPU oracle timed on the
+host cores on a bounded sample).
+
+    python bench.py [--steps K] [--warmup W]          # the headline line
+    python bench.py --sweep [--batch 128]             # every distinct ResNet-50 conv shape x 3 passes
+    python bench.py --lars resnet50|alexnet_bn        # lars_step alone, GB/s against HBM peak
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_MFMA_F32 = 157.3      # TFLOP/s, MI355X dense fp32 matrix
+PEAK_HBM = 8000.0          # GB/s
+LARS_BYTES_PER_PARAM = 28  # norm pass reads w, g (8 B); update reads w, g, v and writes w, v (20 B)
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+class Layer:
+    """Device buffers and descriptor of one convolution of the workload."""
+
+    def __init__(self, cs, gen, torch, lc, first: bool):
+        dev = "cuda:0"
+        self.cs = cs
+        self.first = first
+        self.desc = lc.ConvDesc(cs.n, cs.c, cs.h, cs.w, cs.k, cs.r, cs.s, cs.stride, cs.stride, cs.pad, cs.pad,
+                                lc.LC_F32, lc.LC_NHWC)
+        std = (2.0 / (cs.c * cs.r * cs.s)) ** 0.5
+        self.x = torch.randn((cs.n, cs.h, cs.w, cs.c), generator=gen, device=dev)
+        self.w = torch.randn((cs.k, cs.r, cs.s, cs.c), generator=gen, device=dev) * std
+        self.dy = torch.randn((cs.n, cs.p, cs.q, cs.k), generator=gen, device=dev)
+        self.y = torch.empty((cs.n, cs.p, cs.q, cs.k), device=dev)
+        self.dx = None if first else torch.empty((cs.n, cs.h, cs.w, cs.c), device=dev)
+        self.dw = torch.empty((cs.k, cs.r, cs.s, cs.c), device=dev)
+        self.ws_bytes = max(lc.conv2d_workspace_bytes(self.desc, p) for p in range(3))
+
+
+def make_workspace(nbytes, torch):
+    return torch.empty(max(nbytes, 256), dtype=torch.uint8, device="cuda:0")
+
+
+class Timer:
+    """HIP events on the stream the kernels are launched on (torch's current stream)."""
+
+    def __init__(self, torch):
+        self.torch = torch
+        self.spans = []          # (key, start, stop)
+
+    def span(self, key):
+        t = self.torch
+        a, b = t.cuda.Event(enable_timing=True), t.cuda.Event(enable_timing=True)
+        self.spans.append((key, a, b))
+        return a, b
+
+    def totals(self):
+        out = {}
+        for key, a, b in self.spans:
+            ms, n = out.get(key, (0.0, 0))
+            out[key] = (ms + a.elapsed_time(b), n + 1)
+        return out
+
+
+def timed(timer, key, fn):
+    if timer is None:
+        fn()
+        return
+    a, b = timer.span(key)
+    a.record()
+    fn()
+    b.record()
+
+
+def run_resnet50_step(args):
+    import torch
+    from paper_1709_05011_amd import larsconv as lc
+    from paper_1709_05011_amd import synth
+
+    lc.lib()
+    batch = args.batch or 256
+    gen = torch.Generator(device="cuda:0")
+    gen.manual_seed(0x5EED0300)
+    shapes = synth.resnet50_convs(batch) + [synth.resnet50_fc(batch)]
+    layers = [Layer(cs, gen, torch, lc, i == 0) for i, cs in enumerate(shapes)]
+    ws = make_workspace(max(l.ws_bytes for l in layers), torch)
+
+    # the 161 parameter tensors: filter, batch-norm scale, batch-norm shift per conv; classifier weight, bias
+    pw, pg, pv = [], [], []
+    for l in layers[:-1]:
+        k = l.cs.k
+        pw += [l.w, torch.ones(k, device="cuda:0"), torch.zeros(k, device="cuda:0")]
+        pg += [l.dw, torch.randn(k, generator=gen, device="cuda:0") * 1e-2,
+               torch.randn(k, generator=gen, device="cuda:0") * 1e-2]
+    pw += [layers[-1].w, torch.zeros(1000, device="cuda:0")]
+    pg += [layers[-1].dw, torch.randn(1000, generator=gen, device="cuda:0") * 1e-2]
+    pv = [torch.zeros_like(t) for t in pw]
+    largs = lc.LarsArgs(pw, pg, pv)
+    assert largs.n == 161 and sum(largs.numel) == 25_557_032
+    lws = make_workspace(lc.lars_workspace_bytes(largs.numel), torch)
+    trust = torch.empty(largs.n, device="cuda:0")
+    T = synth.poly_total_iters()
+    lr = lc.lars_poly_lr(1.0, 1000, T)
+
+    def gemm_kernel_of(l, pass_):
+        """Which conv kernel instance a call ends in (mirrors the library's dispatch; labels only)."""
+        cs = l.cs
+        if pass_ == "bwd_weight":
+            return "wgrad"
+        n_gemm = cs.k if pass_ == "fwd" else cs.c
+        return "conv_gemm_128x128" if n_gemm > 64 else "conv_gemm_128x64"
+
+    def step(timer=None):
+        for l in layers:
+            timed(timer, ("fwd", gemm_kernel_of(l, "fwd"), l.cs.flops),
+                  lambda l=l: lc.conv2d_fwd(l.desc, l.x, l.w, l.y, ws))
+        for l in reversed(layers):
+            if not l.first:
+                timed(timer, ("bwd_data", gemm_kernel_of(l, "bwd_data"), l.cs.flops),
+                      lambda l=l: lc.conv2d_bwd_data(l.desc, l.dy, l.w, l.dx, ws))
+            timed(timer, ("bwd_weight", "wgrad", l.cs.flops),
+                  lambda l=l: lc.conv2d_bwd_weight(l.desc, l.x, l.dy, l.dw, ws))
+        timed(timer, ("lars", "lars", 0), lambda: lc.lars_step(largs, 0.001, 0.9, 5e-5, lr, trust, lws))
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    timer = Timer(torch)
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step(timer)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ms_per_step = wall * 1e3 / args.steps
+
+    # aggregate the per-call spans
+    per_pass, per_kernel = {}, {}
+    for (pass_, kern, flops), a, b in timer.spans:
+        ms = a.elapsed_time(b)
+        p = per_pass.setdefault(pass_, [0.0, 0, 0])
+        p[0] += ms; p[1] += 1; p[2] += flops
+        q = per_kernel.setdefault(kern, [0.0, 0, 0])
+        q[0] += ms; q[1] += 1; q[2] += flops
+    conv_ms = sum(per_pass[p][0] for p in ("fwd", "bwd_data", "bwd_weight"))
+    conv_flops = sum(per_pass[p][2] for p in ("fwd", "bwd_data", "bwd_weight"))
+    lars_ms = per_pass["lars"][0] / per_pass["lars"][1]
+    lars_gbps = LARS_BYTES_PER_PARAM * sum(largs.numel) / (lars_ms * 1e-3) / 1e9
+    dom = max((k for k in per_kernel if k != "lars"), key=lambda k: per_kernel[k][0])
+    dms, dn, dfl = per_kernel[dom]
+    achieved = dfl / (dms * 1e-3) / 1e12
+    result = {
+        "metric": "ResNet-50 fwd+bwd+LARS images/sec/GPU",
+        "value": round(batch / (ms_per_step * 1e-3), 2),
+        "unit": "images/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 3),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": f"resnet50_train_step_fp32_batch{batch}_nhwc (53 convs + fc: fwd, bwd_data, bwd_weight; "
+                               "lars_step over 161 tensors / 25.6M params)",
+                   "batch": batch, "layout": "NHWC", "lars": {"eta": 0.001, "momentum": 0.9, "weight_decay": 5e-5, "lr": lr}},
+        "roofline": {"bound": "mfma", "kernel": dom, "achieved": round(achieved, 2), "peak": PEAK_MFMA_F32,
+                     "unit": "TFLOP/s", "frac": round(achieved / PEAK_MFMA_F32, 4), "traffic": None,
+                     "launches_per_step": dn // args.steps, "avg_launch_ms": round(dms / dn, 4),
+                     "flops_per_launch": dfl / dn},
+        "conv_tflops": {p: round(per_pass[p][2] / (per_pass[p][0] * 1e-3) / 1e12, 2) for p in ("fwd", "bwd_data", "bwd_weight")},
+        "conv_tflops_all": round(conv_flops / (conv_ms * 1e-3) / 1e12, 2),
+        "conv_frac_of_mfma_peak": round(conv_flops / (conv_ms * 1e-3) / 1e12 / PEAK_MFMA_F32, 4),
+        "lars": {"ms": round(lars_ms, 4), "GBps": round(lars_gbps, 1), "frac_of_hbm_peak": round(lars_gbps / PEAK_HBM, 4),
+                 "bytes_per_param": LARS_BYTES_PER_PARAM},
+        "kernel_ms_per_step": {k: round(v[0] / args.steps, 3) for k, v in per_kernel.items()},
+    }
+    if not args.no_cpu:
+        result["cpu_baseline"] = cpu_baseline(args.cpu_batch)
+    return result
+
+
+def cpu_baseline(batch: int):
+    """The oracle as it stands, timed on the host cores on a bounded sample: the same network (all
+    54 layers x 3 passes + the 161-tensor LARS step) at a small batch."""
+    import numpy as np
+    import oracle
+    from paper_1709_05011_amd import synth
+
+    shapes = synth.resnet50_convs(batch) + [synth.resnet50_fc(batch)]
+    cache = {}
+
+    def data(cs):
+        key = cs.key()
+        if key not in cache:
+            cache[key] = (synth.normal((cs.n, cs.h, cs.w, cs.c), 1), synth.normal((cs.k, cs.r, cs.s, cs.c), 2),
+                          synth.normal((cs.n, cs.p, cs.q, cs.k), 3))
+        return cache[key]
+
+    for cs in shapes:
+        data(cs)
+    sizes = synth.resnet50_param_numels()
+    w = [synth.normal((n,), 10) for n in sizes]
+    g = [synth.normal((n,), 11, std=0.01) for n in sizes]
+    v = [np.zeros(n, np.float32) for n in sizes]
+    t0 = time.perf_counter()
+    for i, cs in enumerate(shapes):
+        x, wt, dy = data(cs)
+        oracle.conv2d_fwd(x, wt, cs.stride, cs.pad, oracle.NHWC)
+        if i:
+            oracle.conv2d_bwd_data(dy, wt, (cs.h, cs.w), cs.stride, cs.pad, oracle.NHWC)
+        oracle.conv2d_bwd_weight(x, dy, (cs.r, cs.s), cs.stride, cs.pad, oracle.NHWC)
+    t1 = time.perf_counter()
+    oracle.lars_step(w, g, v, 0.001, 0.9, 5e-5, 0.5)
+    t2 = time.perf_counter()
+    return {"value": round(batch / (t2 - t0), 3), "unit": "images/s", "cores": oracle.threads(), "kind": "oracle",
+            "sample": f"whole ResNet-50 step (54 layers x fwd/bwd_data/bwd_weight + 161-tensor LARS) at batch {batch}: "
+                      f"conv {t1 - t0:.1f} s, LARS {t2 - t1:.2f} s",
+            "lars_GBps": round(LARS_BYTES_PER_PARAM * sum(sizes) / (t2 - t1) / 1e9, 2)}
+
+
+def time_call(torch, fn, iters, warmup=2):
+    for _ in range(warmup):
+        fn()
+    evs = []
+    for _ in range(iters):
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        fn()
+        b.record()
+        evs.append((a, b))
+    torch.cuda.synchronize()
+    ms = sorted(a.elapsed_time(b) for a, b in evs)
+    return ms[len(ms) // 2], ms[0]
+
+
+def run_sweep(args):
+    """Every distinct ResNet-50 convolution shape, each pass timed separately."""
+    import torch
+    from paper_1709_05011_amd import larsconv as lc
+    from paper_1709_05011_amd import synth
+
+    batch = args.batch or 128
+    gen = torch.Generator(device="cuda:0")
+    gen.manual_seed(0x5EED0200)
+    rows = []
+    tot = {"fwd": [0.0, 0.0], "bwd_data": [0.0, 0.0], "bwd_weight": [0.0, 0.0]}
+    for idx, (cs, count) in enumerate(synth.resnet50_distinct_shapes(batch), start=1):
+        if args.only and idx not in args.only:
+            continue
+        l = Layer(cs, gen, torch, lc, False)
+        ws = make_workspace(l.ws_bytes, torch)
+        calls = {
+            "fwd": lambda: lc.conv2d_fwd(l.desc, l.x, l.w, l.y, ws),
+            "bwd_data": lambda: lc.conv2d_bwd_data(l.desc, l.dy, l.w, l.dx, ws),
+            "bwd_weight": lambda: lc.conv2d_bwd_weight(l.desc, l.x, l.dy, l.dw, ws),
+        }
+        row = {"shape": idx, "name": cs.name, "c": cs.c, "k": cs.k, "rs": cs.r, "stride": cs.stride, "hw": cs.h,
+               "count": count, "gflop": round(cs.flops / 1e9, 2)}
+        for p, fn in calls.items():
+            med, mn = time_call(torch, fn, args.iters)
+            row[p + "_ms"] = round(med, 4)
+            row[p + "_tflops"] = round(cs.flops / (med * 1e-3) / 1e12, 2)
+            tot[p][0] += med * count
+            tot[p][1] += cs.flops * count
+        rows.append(row)
+        log(json.dumps(row))
+        del l, ws
+        torch.cuda.empty_cache()
+    summary = {p: round(v[1] / (v[0] * 1e-3) / 1e12, 2) for p, v in tot.items() if v[0] > 0}
+    all_ms = sum(v[0] for v in tot.values())
+    all_fl = sum(v[1] for v in tot.values())
+    return {"sweep": "resnet50_distinct_conv_shapes", "batch": batch, "dtype": "f32", "layout": "NHWC",
+            "weighted_tflops": summary, "weighted_tflops_all": round(all_fl / (all_ms * 1e-3) / 1e12, 2),
+            "frac_of_mfma_peak": round(all_fl / (all_ms * 1e-3) / 1e12 / PEAK_MFMA_F32, 4), "rows": rows}
+
+
+def run_lars(args):
+    import torch
+    from paper_1709_05011_amd import larsconv as lc
+    from paper_1709_05011_amd import synth
+
+    sizes = synth.resnet50_param_numels() if args.lars == "resnet50" else synth.alexnet_bn_param_numels()
+    gen = torch.Generator(device="cuda:0")
+    gen.manual_seed(0x5EED0400)
+    n_sets = args.rotate          # rotate over several parameter sets so that no call finds its data in cache
+    sets = []
+    for _ in range(n_sets):
+        w = [torch.randn(n, generator=gen, device="cuda:0") for n in sizes]
+        g = [torch.randn(n, generator=gen, device="cuda:0") * 1e-2 for n in sizes]
+        v = [torch.zeros(n, device="cuda:0") for n in sizes]
+        sets.append(lc.LarsArgs(w, g, v))
+    lws = make_workspace(lc.lars_workspace_bytes(sizes), torch)
+    trust = torch.empty(len(sizes), device="cuda:0")
+    state = {"i": 0}
+
+    def call():
+        a = sets[state["i"] % n_sets]
+        state["i"] += 1
+        lc.lars_step(a, 0.001, 0.9, 5e-5, 0.5, trust, lws)
+
+    med, mn = time_call(torch, call, args.iters, warmup=max(2, n_sets))
+    nbytes = LARS_BYTES_PER_PARAM * sum(sizes)
+    return {"lars": args.lars, "tensors": len(sizes), "params": sum(sizes), "rotating_sets": n_sets,
+            "ms_median": round(med, 4), "ms_min": round(mn, 4), "GBps_median": round(nbytes / (med * 1e-3) / 1e9, 1),
+            "frac_of_hbm_peak": round(nbytes / (med * 1e-3) / 1e9 / PEAK_HBM, 4), "bytes_per_param": LARS_BYTES_PER_PARAM}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--batch", type=int, default=0)
+    ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
+    ap.add_argument("--cpu-batch", type=int, default=4)
+    ap.add_argument("--sweep", action="store_true")
+    ap.add_argument("--only", type=int, nargs="*", help="sweep: shape numbers to run")
+    ap.add_argument("--iters", type=int, default=10)
+    ap.add_argument("--lars", choices=["resnet50", "alexnet_bn"])
+    ap.add_argument("--rotate", type=int, default=1)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py measures one GPU: the hot path built here has no multi-GPU part "
+                 "(the gradient all-reduce between backward and lars_step is out of scope); run with --gpus 1")
+    if args.sweep:
+        res = run_sweep(args)
+    elif args.lars:
+        res = run_lars(args)
+    else:
+        res = run_resnet50_step(args)
+    print(json.dumps(res), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -110,6 +110,10 @@ float lars_poly_lr(float base_lr, int64_t iter, int64_t max_iter, float power);
 /* Static, human-readable name of a status code. */
 const char* lc_status_string(lc_status status);
 
+/* Text of the HIP runtime error behind the most recent LC_ERR_LAUNCH returned on the calling thread
+ * ("" if there was none).  The pointer stays valid until the thread's next failing call. */
+const char* lc_last_error_detail(void);
+
 #ifdef __cplusplus
 }
 #endif

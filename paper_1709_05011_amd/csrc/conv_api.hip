@@ -3,6 +3,7 @@
 // error paths behave the same on a machine without a GPU.
 #include <hip/hip_runtime.h>
 #include <limits.h>
+#include <stdio.h>
 #include <stdint.h>
 
 #include "internal.h"
@@ -112,7 +113,20 @@ lc_status check_buffers(const lc_conv_desc* d, const Plan& pl, const void* a, co
 
 inline char* at(void* ws, size_t off) { return static_cast<char*>(ws) + off; }
 
+thread_local char g_detail[256] = "";
+
 }  // namespace
+
+void lc_begin_call() { (void)hipGetLastError(); }
+
+lc_status lc_end_call() {
+    const hipError_t e = hipGetLastError();
+    if (e == hipSuccess) return LC_OK;
+    snprintf(g_detail, sizeof(g_detail), "%s: %s", hipGetErrorName(e), hipGetErrorString(e));
+    return LC_ERR_LAUNCH;
+}
+
+extern "C" const char* lc_last_error_detail(void) { return g_detail; }
 
 extern "C" lc_status conv2d_out_shape(const lc_conv_desc* desc, int* p, int* q) {
     if (!desc || !p || !q) return LC_ERR_NULL;
@@ -139,6 +153,7 @@ extern "C" lc_status conv2d_fwd(const lc_conv_desc* d, const void* x, const void
     if (st != LC_OK) return st;
     if (((uintptr_t)y) & (uintptr_t)(pl.esize - 1)) return LC_ERR_ALIGN;
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    lc_begin_call();
 
     const void* xs = x;
     const void* wsrc = w;
@@ -179,7 +194,7 @@ extern "C" lc_status conv2d_fwd(const lc_conv_desc* d, const void* x, const void
     st = lc_launch_conv_gemm_f32(g, stream);
     if (st != LC_OK) return st;
     if (pl.nchw) lc_nhwc_to_nchw(ydst, y, d->n, d->k, pl.P * pl.Q, pl.esize, stream);
-    return hipGetLastError() == hipSuccess ? LC_OK : LC_ERR_LAUNCH;
+    return lc_end_call();
 }
 
 extern "C" lc_status conv2d_bwd_data(const lc_conv_desc* d, const void* dy, const void* w, void* dx,
@@ -191,6 +206,7 @@ extern "C" lc_status conv2d_bwd_data(const lc_conv_desc* d, const void* dy, cons
     if (st != LC_OK) return st;
     if (((uintptr_t)dx) & (uintptr_t)(pl.esize - 1)) return LC_ERR_ALIGN;
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    lc_begin_call();
 
     const void* dys = dy;
     const void* wsrc = w;
@@ -248,7 +264,7 @@ extern "C" lc_status conv2d_bwd_data(const lc_conv_desc* d, const void* dy, cons
     st = lc_launch_conv_gemm_f32(g, stream);
     if (st != LC_OK) return st;
     if (pl.nchw) lc_nhwc_to_nchw(dxdst, dx, d->n, d->c, d->h * d->w, pl.esize, stream);
-    return hipGetLastError() == hipSuccess ? LC_OK : LC_ERR_LAUNCH;
+    return lc_end_call();
 }
 
 extern "C" lc_status conv2d_bwd_weight(const lc_conv_desc* d, const void* x, const void* dy, float* dw,
@@ -260,6 +276,7 @@ extern "C" lc_status conv2d_bwd_weight(const lc_conv_desc* d, const void* x, con
     if (st != LC_OK) return st;
     if (((uintptr_t)dw) & 3) return LC_ERR_ALIGN;
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    lc_begin_call();
 
     const void* xs = x;
     const void* dys = dy;
@@ -300,7 +317,7 @@ extern "C" lc_status conv2d_bwd_weight(const lc_conv_desc* d, const void* x, con
     if (!pl.wgrad_direct)
         lc_reduce_splits(g.d, dwdst, pl.splits, (size_t)d->k * g.J, pl.cpad, d->c, stream);
     if (pl.nchw) lc_nhwc_to_nchw(dwdst, dw, d->k, d->c, d->r * d->s, 4, stream);
-    return hipGetLastError() == hipSuccess ? LC_OK : LC_ERR_LAUNCH;
+    return lc_end_call();
 }
 
 extern "C" const char* lc_status_string(lc_status status) {

@@ -392,7 +392,7 @@ lc_status launch_conv(const GemmConv& p, hipStream_t stream) {
     const long long tiles = (long long)((p.M + BM - 1) / BM) * ((p.N + BN - 1) / BN);
     if (tiles <= 0 || tiles > 0x7fffffffLL) return LC_ERR_UNSUPPORTED;
     hipLaunchKernelGGL((conv_gemm_f32_kernel<BM, BN, BK, 2, 2, VEC>), dim3((unsigned)tiles), dim3(256), 0, stream, p);
-    return hipGetLastError() == hipSuccess ? LC_OK : LC_ERR_LAUNCH;
+    return lc_end_call();
 }
 
 template <int BM, int BN, int BK, int VEC>
@@ -401,7 +401,7 @@ lc_status launch_wgrad(const GemmWgrad& p, hipStream_t stream) {
     if (tiles <= 0 || tiles > 0x7fffffffLL || p.splits > 65535) return LC_ERR_UNSUPPORTED;
     hipLaunchKernelGGL((wgrad_f32_kernel<BM, BN, BK, 2, 2, VEC>), dim3((unsigned)tiles, (unsigned)p.splits), dim3(256), 0,
                        stream, p);
-    return hipGetLastError() == hipSuccess ? LC_OK : LC_ERR_LAUNCH;
+    return lc_end_call();
 }
 
 }  // namespace

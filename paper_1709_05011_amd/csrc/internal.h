@@ -7,6 +7,11 @@
 
 #include "../../include/larsconv.h"
 
+// Launch bookkeeping (conv_api.hip).  lc_begin_call() drops any stale error another user of the HIP
+// runtime left on this thread, so that lc_end_call() reports only what this library's launches caused.
+void lc_begin_call();
+lc_status lc_end_call();     // LC_OK, or LC_ERR_LAUNCH with the detail text recorded
+
 // ---- small device-side utilities (layout.hip) ----
 void lc_fill_f32(float* dst, float value, size_t count, hipStream_t stream);
 void lc_fill_u32x4(void* dst, size_t bytes16, hipStream_t stream);   // zero `bytes16` * 16 bytes

@@ -270,6 +270,7 @@ extern "C" lc_status lars_step(int n_tensors, float* const* w, const float* cons
     ws.arrived = reinterpret_cast<unsigned int*>(base + lay.arrived);
     ws.step_scale = reinterpret_cast<float*>(base + lay.step_scale);
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    lc_begin_call();
 
     LarsTableArgs args;
     int chunk_cursor = 0;
@@ -291,18 +292,18 @@ extern "C" lc_status lars_step(int n_tensors, float* const* w, const float* cons
         args.count = count;
         hipLaunchKernelGGL(lars_table_kernel, dim3(count), dim3(kThreads), 0, stream, args, ws);
     }
-    if (hipGetLastError() != hipSuccess) return LC_ERR_LAUNCH;
+    if (lc_end_call() != LC_OK) return LC_ERR_LAUNCH;
     if (trust_out) {
         // empty tensors have no chunk and therefore no block: their ratio is 1 by definition
         bool any_empty = false;
         for (int l = 0; l < n_tensors; ++l) any_empty |= (numel[l] == 0);
         if (any_empty) lc_fill_f32(trust_out, 1.0f, (size_t)n_tensors, stream);
     }
-    if (lay.n_chunks == 0) return hipGetLastError() == hipSuccess ? LC_OK : LC_ERR_LAUNCH;
+    if (lay.n_chunks == 0) return lc_end_call();
     const int n_chunks = (int)lay.n_chunks;
     hipLaunchKernelGGL(lars_norm_kernel, dim3(n_chunks), dim3(kThreads), 0, stream, ws, eta, weight_decay, lr, trust_out);
     hipLaunchKernelGGL(lars_update_kernel, dim3(n_chunks), dim3(kThreads), 0, stream, ws, n_chunks, momentum, weight_decay);
-    return hipGetLastError() == hipSuccess ? LC_OK : LC_ERR_LAUNCH;
+    return lc_end_call();
 }
 
 extern "C" float lars_poly_lr(float base_lr, int64_t iter, int64_t max_iter, float power) {

@@ -20,13 +20,14 @@ LC_NCHW, LC_NHWC = 0, 1
 LC_PASS_FWD, LC_PASS_BWD_DATA, LC_PASS_BWD_WEIGHT = 0, 1, 2
 
 EXPORTS = ["conv2d_out_shape", "conv2d_workspace_bytes", "conv2d_fwd", "conv2d_bwd_data", "conv2d_bwd_weight",
-           "lars_workspace_bytes", "lars_step", "lars_poly_lr", "lc_status_string"]
+           "lars_workspace_bytes", "lars_step", "lars_poly_lr", "lc_status_string", "lc_last_error_detail"]
 
 
 class LarsConvError(RuntimeError):
     def __init__(self, status: int, where: str):
         self.status = status
-        super().__init__(f"{where}: {status_string(status)} (lc_status {status})")
+        detail = lib().lc_last_error_detail().decode() if status == LC_ERR_LAUNCH else ""
+        super().__init__(f"{where}: {status_string(status)} (lc_status {status})" + (f": {detail}" if detail else ""))
 
 
 class lc_conv_desc(ctypes.Structure):
@@ -65,6 +66,10 @@ def lib() -> ctypes.CDLL:
         if not os.path.exists(LIB_PATH):
             raise RuntimeError(f"{LIB_PATH} is missing: build it with __graft_entry__.build() "
                                "(python -m paper_1709_05011_amd.build); there is no CPU fallback")
+        # torch ships its own HIP runtime (same soname as the system one).  It must be the one in the
+        # process before this library is loaded, or device pointers and streams handed over by torch
+        # would belong to another runtime instance than the one the kernels are launched with.
+        import torch  # noqa: F401
         L = ctypes.CDLL(LIB_PATH)
         vp, sz, i32 = ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int
         dp = ctypes.POINTER(lc_conv_desc)
@@ -85,6 +90,8 @@ def lib() -> ctypes.CDLL:
         L.lars_poly_lr.argtypes = [ctypes.c_float, ctypes.c_int64, ctypes.c_int64, ctypes.c_float]
         L.lc_status_string.restype = ctypes.c_char_p
         L.lc_status_string.argtypes = [i32]
+        L.lc_last_error_detail.restype = ctypes.c_char_p
+        L.lc_last_error_detail.argtypes = []
         _lib = L
     return _lib
 
@@ -126,6 +133,10 @@ def status_string(status: int) -> str:
 
 
 lc_status_string = status_string
+
+
+def lc_last_error_detail() -> str:
+    return lib().lc_last_error_detail().decode()
 
 
 def conv2d_out_shape(desc):
