@@ -4,16 +4,16 @@
 //
 // The parameter list is cut into fixed-size chunks of one tensor each, so that 161 tensors of
 // 64 .. 2.4 M elements (ResNet-50) load the chip evenly and no launch is made per tensor.
-//   1. lars_table_kernel   copies the per-tensor descriptors (passed as kernel arguments, so the
-//                          call needs no host staging buffer and no copy engine) into the
-//                          workspace, fills the chunk -> tensor map and clears the arrival counters.
-//   2. lars_norm_kernel    one block per chunk: sum w^2 and sum g^2 (fp32 per thread over 16
-//                          elements, then fp64 across lanes with wavefront shuffles and across waves
-//                          through LDS) -> one fp64 partial per chunk.  The block that arrives last
-//                          for a tensor adds that tensor's partials in index order and writes the
-//                          trust ratio: the result does not depend on which block was last.
-//   3. lars_update_kernel  one block per chunk, chunks taken in reverse so that the tail of the
-//                          norm pass, still resident in L2 / Infinity Cache, is re-read first.
+//   1. lars_norm_kernel      one block per chunk: sum w^2 and sum g^2 (fp32 per thread over 16
+//                            elements, then fp64 across lanes with wavefront shuffles and across waves
+//                            through LDS) -> one fp64 partial per chunk.  The per-tensor descriptors
+//                            travel as kernel arguments (64 per launch: no host staging buffer, no
+//                            copy engine, nothing to keep alive after the call returns); the blocks
+//                            copy them into the workspace and fill the chunk -> tensor map on the way.
+//   2. lars_finalize_kernel  one block per tensor adds its partials in index order and writes
+//                            lr * trust ratio: bit-identical from run to run.
+//   3. lars_update_kernel    one block per chunk, chunks taken in reverse so that the tail of the
+//                            norm pass, still resident in L2 / Infinity Cache, is re-read first.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -37,31 +37,20 @@ struct LarsTensor {
 };
 static_assert(sizeof(LarsTensor) == 48, "descriptor layout");
 
-struct LarsTableArgs {
+struct LarsGroupArgs {
     LarsTensor t[kTablePerLaunch];
     int first;             // index of t[0] in the full list
     int count;
+    int chunk_begin;       // first chunk of the group
+    int chunk_count;
 };
 
 struct LarsWorkspace {      // device pointers carved out of the caller's workspace
     LarsTensor* table;
     int* chunk_tensor;
     double* partial;        // [n_chunks][2]
-    unsigned int* arrived;  // [n_tensors]
     float* step_scale;      // [n_tensors]  lr * trust
 };
-
-__global__ void __launch_bounds__(kThreads) lars_table_kernel(const LarsTableArgs args, LarsWorkspace ws) {
-    const int i = blockIdx.x;
-    if (i >= args.count) return;
-    const LarsTensor t = args.t[i];
-    const int l = args.first + i;
-    if (threadIdx.x == 0) {
-        ws.table[l] = t;
-        ws.arrived[l] = 0u;
-    }
-    for (int c = threadIdx.x; c < t.n_chunks; c += kThreads) ws.chunk_tensor[t.chunk_start + c] = l;
-}
 
 __device__ __forceinline__ double wave_sum(double x) {
 #pragma unroll
@@ -83,13 +72,21 @@ __device__ __forceinline__ double2 block_sum2(double a, double b, double* lds /*
     return make_double2((lds[0] + lds[1]) + (lds[2] + lds[3]), (lds[4] + lds[5]) + (lds[6] + lds[7]));
 }
 
-__global__ void __launch_bounds__(kThreads)
-lars_norm_kernel(LarsWorkspace ws, float eta, float weight_decay, float lr, float* __restrict__ trust_out) {
+__global__ void __launch_bounds__(kThreads) lars_norm_kernel(const LarsGroupArgs args, LarsWorkspace ws) {
     __shared__ double red[8];
-    __shared__ int is_last;
-    const int chunk = blockIdx.x;
-    const int l = ws.chunk_tensor[chunk];
-    const LarsTensor t = ws.table[l];
+    if (blockIdx.x == 0 && threadIdx.x < args.count) ws.table[args.first + threadIdx.x] = args.t[threadIdx.x];
+    if ((int)blockIdx.x >= args.chunk_count) return;      // a group of empty tensors still gets its table written
+    const int chunk = args.chunk_begin + blockIdx.x;
+    // last tensor of the group whose first chunk is <= chunk (tensors without elements own no chunk)
+    int lo = 0, hi = args.count - 1;
+    while (lo < hi) {
+        const int mid = (lo + hi + 1) >> 1;
+        if (args.t[mid].chunk_start <= chunk) lo = mid; else hi = mid - 1;
+    }
+    while (args.t[lo].n_chunks == 0) --lo;                // skip back over empty tensors sharing the start
+    const LarsTensor t = args.t[lo];
+    if (threadIdx.x == 0) ws.chunk_tensor[chunk] = args.first + lo;
+
     const long long off = (long long)(chunk - t.chunk_start) * kChunk;
     const long long rem = t.numel - off;
     const int len = rem < kChunk ? (int)rem : kChunk;
@@ -118,22 +115,21 @@ lars_norm_kernel(LarsWorkspace ws, float eta, float weight_decay, float lr, floa
         }
     }
     const double2 s = block_sum2((double)sw, (double)sg, red);
-
-    // publish the partial, then count arrivals; the last block of the tensor finishes it
     if (threadIdx.x == 0) {
-        __hip_atomic_store(&ws.partial[2 * chunk], s.x, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        __hip_atomic_store(&ws.partial[2 * chunk + 1], s.y, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        const unsigned int before =
-            __hip_atomic_fetch_add(&ws.arrived[l], 1u, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
-        is_last = (before + 1u == (unsigned int)t.n_chunks);
+        ws.partial[2 * chunk] = s.x;
+        ws.partial[2 * chunk + 1] = s.y;
     }
-    __syncthreads();
-    if (!is_last) return;
+}
 
+__global__ void __launch_bounds__(kThreads)
+lars_finalize_kernel(LarsWorkspace ws, float eta, float weight_decay, float lr, float* __restrict__ trust_out) {
+    __shared__ double red[8];
+    const int l = blockIdx.x;
+    const int chunk_start = ws.table[l].chunk_start, n_chunks = ws.table[l].n_chunks;
     double pw = 0.0, pg = 0.0;
-    for (int c = threadIdx.x; c < t.n_chunks; c += kThreads) {
-        pw += __hip_atomic_load(&ws.partial[2 * (t.chunk_start + c)], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        pg += __hip_atomic_load(&ws.partial[2 * (t.chunk_start + c) + 1], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    for (int c = threadIdx.x; c < n_chunks; c += kThreads) {
+        pw += ws.partial[2 * (chunk_start + c)];
+        pg += ws.partial[2 * (chunk_start + c) + 1];
     }
     const double2 tot = block_sum2(pw, pg, red);
     if (threadIdx.x == 0) {
@@ -210,7 +206,7 @@ lars_update_kernel(LarsWorkspace ws, int n_chunks, float momentum, float weight_
 
 // Workspace carving shared by the size query and the call.
 struct LarsLayout {
-    size_t table, chunk_tensor, partial, arrived, step_scale, total;
+    size_t table, chunk_tensor, partial, step_scale, total;
     long long n_chunks;
 };
 
@@ -230,7 +226,6 @@ bool lars_layout(int n_tensors, const int64_t* numel, LarsLayout* out) {
     out->table = take(sizeof(LarsTensor) * (size_t)n_tensors);
     out->chunk_tensor = take(sizeof(int) * (size_t)chunks);
     out->partial = take(sizeof(double) * 2 * (size_t)chunks);
-    out->arrived = take(sizeof(unsigned int) * (size_t)n_tensors);
     out->step_scale = take(sizeof(float) * (size_t)n_tensors);
     out->total = off;
     out->n_chunks = chunks;
@@ -267,15 +262,15 @@ extern "C" lc_status lars_step(int n_tensors, float* const* w, const float* cons
     ws.table = reinterpret_cast<LarsTensor*>(base + lay.table);
     ws.chunk_tensor = reinterpret_cast<int*>(base + lay.chunk_tensor);
     ws.partial = reinterpret_cast<double*>(base + lay.partial);
-    ws.arrived = reinterpret_cast<unsigned int*>(base + lay.arrived);
     ws.step_scale = reinterpret_cast<float*>(base + lay.step_scale);
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     lc_begin_call();
 
-    LarsTableArgs args;
+    LarsGroupArgs args;
     int chunk_cursor = 0;
     for (int first = 0; first < n_tensors; first += kTablePerLaunch) {
         const int count = (n_tensors - first) < kTablePerLaunch ? (n_tensors - first) : kTablePerLaunch;
+        args.chunk_begin = chunk_cursor;
         for (int i = 0; i < count; ++i) {
             const int l = first + i;
             LarsTensor& t = args.t[i];
@@ -290,19 +285,14 @@ extern "C" lc_status lars_step(int n_tensors, float* const* w, const float* cons
         }
         args.first = first;
         args.count = count;
-        hipLaunchKernelGGL(lars_table_kernel, dim3(count), dim3(kThreads), 0, stream, args, ws);
+        args.chunk_count = chunk_cursor - args.chunk_begin;
+        const int grid = args.chunk_count > 0 ? args.chunk_count : 1;
+        hipLaunchKernelGGL(lars_norm_kernel, dim3(grid), dim3(kThreads), 0, stream, args, ws);
     }
-    if (lc_end_call() != LC_OK) return LC_ERR_LAUNCH;
-    if (trust_out) {
-        // empty tensors have no chunk and therefore no block: their ratio is 1 by definition
-        bool any_empty = false;
-        for (int l = 0; l < n_tensors; ++l) any_empty |= (numel[l] == 0);
-        if (any_empty) lc_fill_f32(trust_out, 1.0f, (size_t)n_tensors, stream);
-    }
-    if (lay.n_chunks == 0) return lc_end_call();
-    const int n_chunks = (int)lay.n_chunks;
-    hipLaunchKernelGGL(lars_norm_kernel, dim3(n_chunks), dim3(kThreads), 0, stream, ws, eta, weight_decay, lr, trust_out);
-    hipLaunchKernelGGL(lars_update_kernel, dim3(n_chunks), dim3(kThreads), 0, stream, ws, n_chunks, momentum, weight_decay);
+    hipLaunchKernelGGL(lars_finalize_kernel, dim3(n_tensors), dim3(kThreads), 0, stream, ws, eta, weight_decay, lr, trust_out);
+    if (lay.n_chunks > 0)
+        hipLaunchKernelGGL(lars_update_kernel, dim3((unsigned)lay.n_chunks), dim3(kThreads), 0, stream, ws, (int)lay.n_chunks,
+                           momentum, weight_decay);
     return lc_end_call();
 }
 

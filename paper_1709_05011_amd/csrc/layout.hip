@@ -80,17 +80,45 @@ __global__ void pad_channels_kernel(const T* __restrict__ src, T* __restrict__ d
     }
 }
 
-__global__ void reduce_splits_kernel(const float* __restrict__ part, float* __restrict__ dw, int splits, size_t count,
-                                     int cpad, int c) {
-    for (size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x; i < count; i += (size_t)gridDim.x * blockDim.x) {
-        float acc = 0.f;
-        for (int z = 0; z < splits; ++z) acc += part[(size_t)z * count + i];   // index order: fixed result
-        if (cpad == c) {
-            dw[i] = acc;
-        } else {
-            const int ch = (int)(i % cpad);
-            if (ch < c) dw[(i / cpad) * c + ch] = acc;
+// dw[i] = sum_z part[z][i].  SL lanes of the block share one output: lane j adds the j-th run of
+// consecutive splits (four interleaved partial sums, combined in a fixed tree), then the SL lane sums are
+// added in lane order.  The order depends on (splits, SL) only, never on timing: bit-identical reruns.
+template <int SL>
+__global__ void __launch_bounds__(256) reduce_splits_kernel(const float* __restrict__ part, float* __restrict__ dw, int splits,
+                                                            size_t count, int cpad, int c) {
+    constexpr int OUT = 256 / SL;
+    __shared__ float sm[SL][OUT];
+    const int o = threadIdx.x % OUT, lane = threadIdx.x / OUT;
+    const size_t i = (size_t)blockIdx.x * OUT + o;
+    float acc = 0.f;
+    if (i < count) {
+        const int per = (splits + SL - 1) / SL;
+        const int z0 = lane * per, z1 = min(splits, z0 + per);
+        float a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f;
+        int z = z0;
+        for (; z + 4 <= z1; z += 4) {
+            a0 += part[(size_t)z * count + i];
+            a1 += part[(size_t)(z + 1) * count + i];
+            a2 += part[(size_t)(z + 2) * count + i];
+            a3 += part[(size_t)(z + 3) * count + i];
         }
+        for (; z < z1; ++z) a0 += part[(size_t)z * count + i];
+        acc = (a0 + a1) + (a2 + a3);
+    }
+    if (SL > 1) {
+        sm[lane][o] = acc;
+        __syncthreads();
+        if (lane != 0) return;
+        acc = sm[0][o];
+#pragma unroll
+        for (int j = 1; j < SL; ++j) acc += sm[j][o];
+    }
+    if (i >= count) return;
+    if (cpad == c) {
+        dw[i] = acc;
+    } else {
+        const int ch = (int)(i % cpad);
+        if (ch < c) dw[(i / cpad) * c + ch] = acc;
     }
 }
 
@@ -139,5 +167,14 @@ void lc_pad_channels(const void* src, void* dst, size_t rows, int c, int cpad, i
 
 void lc_reduce_splits(const float* part, float* dw, int splits, size_t count, int cpad, int c, hipStream_t stream) {
     if (!count) return;
-    hipLaunchKernelGGL(reduce_splits_kernel, dim3(grid_for(count, 256)), dim3(256), 0, stream, part, dw, splits, count, cpad, c);
+    // few outputs: spread each output's splits over more lanes so that the chip still fills
+    if (count >= (size_t)1 << 18)
+        hipLaunchKernelGGL(reduce_splits_kernel<1>, dim3((unsigned)((count + 255) / 256)), dim3(256), 0, stream, part, dw, splits,
+                           count, cpad, c);
+    else if (count >= (size_t)1 << 15)
+        hipLaunchKernelGGL(reduce_splits_kernel<4>, dim3((unsigned)((count + 63) / 64)), dim3(256), 0, stream, part, dw, splits,
+                           count, cpad, c);
+    else
+        hipLaunchKernelGGL(reduce_splits_kernel<16>, dim3((unsigned)((count + 15) / 16)), dim3(256), 0, stream, part, dw, splits,
+                           count, cpad, c);
 }
