@@ -27,6 +27,7 @@ struct Plan {
     size_t xpad = 0, wpad = 0;       // channel-padded copies
     size_t wt = 0;                   // re-ordered filter for backward-data
     size_t part = 0;                 // split partials of backward-weight
+    size_t sk = 0, sk_bytes = 0;     // partial tiles of the stream-K blocks (forward, backward-data)
     int splits = 1, m_per_split = 0;
     bool wgrad_direct = true;
     size_t total = 0;
@@ -52,6 +53,68 @@ lc_status check_desc(const lc_conv_desc* d, int* P, int* Q) {
     return LC_OK;
 }
 
+// The implicit-GEMM view of the forward pass (pointers left empty).
+GemmConv gemm_fwd(const lc_conv_desc* d, int P, int Q, int cpad) {
+    GemmConv g = {};
+    g.M = d->n * P * Q;
+    g.N = d->k;
+    g.Kg = d->r * d->s * cpad;
+    g.Hi = d->h;
+    g.Wi = d->w;
+    g.Ci = cpad;
+    g.Po = P;
+    g.Qo = Q;
+    g.R = d->r;
+    g.S = d->s;
+    g.sh = d->stride_h;
+    g.sw = d->stride_w;
+    g.ph = d->pad_h;
+    g.pw = d->pad_w;
+    g.dh = g.dw = 1;
+    g.ldd = d->k;
+    return g;
+}
+
+// ... and of the backward-data pass: dy is the gathered tensor, the re-ordered filter [c][R-1-r][S-1-s][k] is B.
+GemmConv gemm_bwd_data(const lc_conv_desc* d, int P, int Q) {
+    GemmConv g = {};
+    g.N = d->c;
+    g.Kg = d->r * d->s * d->k;
+    g.Hi = P;
+    g.Wi = Q;
+    g.Ci = d->k;
+    g.R = d->r;
+    g.S = d->s;
+    g.ldd = d->c;
+    g.dh = g.dw = 1;
+    g.sh = g.sw = 1;
+    if (d->r == 1 && d->s == 1 && d->pad_h == 0 && d->pad_w == 0) {
+        // 1x1 window: one GEMM row per dy pixel; with a stride the result lands on the stride grid
+        // of dx and the rest of each stride cell is zero.
+        g.M = d->n * P * Q;
+        g.Po = P;
+        g.Qo = Q;
+        g.ph = g.pw = 0;
+        if (d->stride_h > 1 || d->stride_w > 1) {
+            g.scatter = 1;
+            g.Ho = d->h;
+            g.Wo = d->w;
+            g.esh = d->stride_h;
+            g.esw = d->stride_w;
+        }
+    } else {
+        // one GEMM row per dx pixel, reading dy as if zeros were inserted between its pixels
+        g.M = d->n * d->h * d->w;
+        g.Po = d->h;
+        g.Qo = d->w;
+        g.ph = d->r - 1 - d->pad_h;
+        g.pw = d->s - 1 - d->pad_w;
+        g.dh = d->stride_h;
+        g.dw = d->stride_w;
+    }
+    return g;
+}
+
 lc_status make_plan(const lc_conv_desc* d, lc_pass pass, Plan* pl) {
     const lc_status st = check_desc(d, &pl->P, &pl->Q);
     if (st != LC_OK) return st;
@@ -75,6 +138,8 @@ lc_status make_plan(const lc_conv_desc* d, lc_pass pass, Plan* pl) {
             pl->xpad = rg.take((size_t)d->n * d->h * d->w * pl->cpad * es);
             pl->wpad = rg.take((size_t)d->k * d->r * d->s * pl->cpad * es);
         }
+        pl->sk_bytes = lc_conv_gemm_workspace(gemm_fwd(d, pl->P, pl->Q, pl->cpad));
+        if (pl->sk_bytes) pl->sk = rg.take(pl->sk_bytes);
     } else if (pass == LC_PASS_BWD_DATA) {
         if (pl->nchw) {
             pl->a_nhwc = rg.take(ny * es);
@@ -82,6 +147,8 @@ lc_status make_plan(const lc_conv_desc* d, lc_pass pass, Plan* pl) {
             pl->out_nhwc = rg.take(nx * es);
         }
         pl->wt = rg.take(nw * es);
+        pl->sk_bytes = lc_conv_gemm_workspace(gemm_bwd_data(d, pl->P, pl->Q));
+        if (pl->sk_bytes) pl->sk = rg.take(pl->sk_bytes);
     } else {
         if (pl->nchw) {
             pl->a_nhwc = rg.take(nx * es);
@@ -171,26 +238,11 @@ extern "C" lc_status conv2d_fwd(const lc_conv_desc* d, const void* x, const void
         xs = at(workspace, pl.xpad);
         wsrc = at(workspace, pl.wpad);
     }
-    GemmConv g = {};
+    GemmConv g = gemm_fwd(d, pl.P, pl.Q, pl.cpad);
     g.a = xs;
     g.b = wsrc;
     g.d = ydst;
-    g.M = d->n * pl.P * pl.Q;
-    g.N = d->k;
-    g.Kg = d->r * d->s * pl.cpad;
-    g.Hi = d->h;
-    g.Wi = d->w;
-    g.Ci = pl.cpad;
-    g.Po = pl.P;
-    g.Qo = pl.Q;
-    g.R = d->r;
-    g.S = d->s;
-    g.sh = d->stride_h;
-    g.sw = d->stride_w;
-    g.ph = d->pad_h;
-    g.pw = d->pad_w;
-    g.dh = g.dw = 1;
-    g.ldd = d->k;
+    g.partial = pl.sk_bytes ? reinterpret_cast<float*>(at(workspace, pl.sk)) : nullptr;
     st = lc_launch_conv_gemm_f32(g, stream);
     if (st != LC_OK) return st;
     if (pl.nchw) lc_nhwc_to_nchw(ydst, y, d->n, d->k, pl.P * pl.Q, pl.esize, stream);
@@ -222,45 +274,11 @@ extern "C" lc_status conv2d_bwd_data(const lc_conv_desc* d, const void* dy, cons
     void* wt = at(workspace, pl.wt);
     lc_filter_for_bwd_data(wsrc, wt, d->k, d->c, d->r, d->s, pl.esize, stream);
 
-    GemmConv g = {};
+    GemmConv g = gemm_bwd_data(d, pl.P, pl.Q);
     g.a = dys;
     g.b = wt;
     g.d = dxdst;
-    g.N = d->c;
-    g.Kg = d->r * d->s * d->k;
-    g.Hi = pl.P;
-    g.Wi = pl.Q;
-    g.Ci = d->k;
-    g.R = d->r;
-    g.S = d->s;
-    g.ldd = d->c;
-    g.dh = g.dw = 1;
-    if (d->r == 1 && d->s == 1 && d->pad_h == 0 && d->pad_w == 0) {
-        // 1x1 window: one GEMM row per dy pixel; with a stride the result lands on the stride grid
-        // of dx and the rest of each stride cell is zero.
-        g.M = d->n * pl.P * pl.Q;
-        g.Po = pl.P;
-        g.Qo = pl.Q;
-        g.sh = g.sw = 1;
-        g.ph = g.pw = 0;
-        if (d->stride_h > 1 || d->stride_w > 1) {
-            g.scatter = 1;
-            g.Ho = d->h;
-            g.Wo = d->w;
-            g.esh = d->stride_h;
-            g.esw = d->stride_w;
-        }
-    } else {
-        // one GEMM row per dx pixel, reading dy as if zeros were inserted between its pixels
-        g.M = d->n * d->h * d->w;
-        g.Po = d->h;
-        g.Qo = d->w;
-        g.sh = g.sw = 1;
-        g.ph = d->r - 1 - d->pad_h;
-        g.pw = d->s - 1 - d->pad_w;
-        g.dh = d->stride_h;
-        g.dw = d->stride_w;
-    }
+    g.partial = pl.sk_bytes ? reinterpret_cast<float*>(at(workspace, pl.sk)) : nullptr;
     st = lc_launch_conv_gemm_f32(g, stream);
     if (st != LC_OK) return st;
     if (pl.nchw) lc_nhwc_to_nchw(dxdst, dx, d->n, d->c, d->h * d->w, pl.esize, stream);

@@ -49,12 +49,14 @@ __device__ __forceinline__ int xcd_tile(int bid, int total) {
 // Write one wave's accumulators (TM x TN tiles of 32x32) to D: plain rows, or the scatter form used by
 // the strided 1x1 backward-data pass.
 template <int TM, int TN>
-__device__ __forceinline__ void store_tile(const GemmConv& p, const f32x16 (&acc)[TM][TN], int row0, int col0, int lane) {
+__device__ __forceinline__ void store_tile(const GemmConv& p, const f32x16 (&acc)[TM][TN], int row0, int col0, int lane,
+                                           int vsel = -1 /* >= 0: only accumulator register vsel of each tile */) {
     float* __restrict__ D = static_cast<float*>(p.d);
 #pragma unroll
     for (int i = 0; i < TM; ++i)
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
+            if (vsel >= 0 && v != vsel) continue;
             const int row = row0 + i * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
             if (row >= p.M) continue;
             if (!p.scatter) {
@@ -239,31 +241,28 @@ __global__ void __launch_bounds__(WGM* WGN * 64) conv_gemm_f32_kernel(const Gemm
 }
 
 // ------------------------------------------------------------------------------------------------
-// forward / backward-data kernel, pipelined: global -> LDS without passing through registers
-// (global_load_lds_dwordx4), STAGES tiles in flight, fragments of the next k-step read while the
-// current one is multiplied.  Requires channel counts that are multiples of 4 and no dilated read.
+// Main forward / backward-data kernel (channel counts that are multiples of 4, no dilated read).
 //
-// LDS tile: [row][16 floats] unpadded (a wave-wide direct load fills 16 rows x 64 B contiguously); the
-// four 16-byte chunks of a row are permuted by chunk ^ swz(row) so that the b128 fragment reads of 8 or
-// 16 consecutive rows hit distinct banks.  The permutation is applied on the global side: the lane that
-// owns LDS slot s of a row fetches chunk s ^ swz(row).  Positions outside the image, rows past M or N
-// and columns past Kg fetch from a 16-byte block of zeros instead, so every lane always loads.
+// LDS tile: [row][16 floats] unpadded; the four 16-byte chunks of a row are permuted by chunk ^ swz(row)
+// so that the b128 fragment reads of 8 or 16 consecutive rows hit distinct banks.  The permutation is
+// applied on the global side: the lane that owns LDS slot s of a row fetches chunk s ^ swz(row).
+// Positions outside the image, rows past M or N and columns past Kg fetch from a 16-byte block of zeros
+// instead, so every lane always loads and the loop has no branch.
+//
+// Pipeline per 16-wide k-step ("tile"): the tile two steps ahead travels global -> registers, the tile one
+// step ahead registers -> LDS (two LDS buffers), fragments are double-buffered in registers so that the LDS
+// reads of the next half-step and the global loads are issued in the shadow of the MFMAs.
+//
+// Work distribution ("stream-K"): the first dp_tiles output tiles are computed one per block.  The k-steps
+// of the remaining tiles are laid end to end and cut into sk_blocks equal ranges, one per block, so that the
+// last, partially filled round of blocks costs its share of the work instead of a whole round.  A block
+// whose range covers only part of a tile's k-steps writes its accumulators to the workspace; a second small
+// kernel adds the parts of each such tile in k order (fixed order: bit-identical reruns) and stores it.
 // ------------------------------------------------------------------------------------------------
 __device__ __attribute__((aligned(16))) const float g_zero_chunk[4] = {0.f, 0.f, 0.f, 0.f};
 
 __device__ __forceinline__ int swz(int row) { return ((row >> 1) ^ (row >> 2)) & 3; }
 
-// The direct loads and the waits on them are written as inline assembly: the compiler then keeps no
-// score of them and does not add a wait for *all* loads in flight in front of every LDS read (it cannot
-// tell the stages apart); the kernel counts them itself.  Each is a compiler barrier for memory accesses.
-// m0 holds the wave-uniform LDS byte address of the 1 KB run the 64 lanes fill (16 B per lane, lane order).
-__device__ __forceinline__ void lds_dma16(const void* gptr, unsigned lds_byte_addr) {
-    asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(gptr), "s"(lds_byte_addr) : "memory");
-}
-template <int N>
-__device__ __forceinline__ void wait_vmcnt() {
-    asm volatile("s_waitcnt vmcnt(%0)" : : "n"(N) : "memory");
-}
 // ok ? a : b on pointers by bit masking: never a branch, whatever the cost of computing a
 __device__ __forceinline__ const float* pick(bool ok, const float* a, const float* b) {
     const uintptr_t m = (uintptr_t)0 - (uintptr_t)ok;
@@ -275,363 +274,256 @@ __device__ __forceinline__ float4 load_global16(const float* ptr) {
     const gf4 v = *(const __attribute__((address_space(1))) gf4*)(uintptr_t)ptr;
     return make_float4(v.x, v.y, v.z, v.w);
 }
-__device__ __forceinline__ void block_barrier() { asm volatile("s_barrier" : : : "memory"); }
+// This wave's LDS writes and reads are complete, then the workgroup barrier.  Global loads stay in flight
+// (__syncthreads() would wait for them too).
+__device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" : : : "memory"); }
 
-typedef __attribute__((address_space(3))) void* lds_ptr_t;
-
-// Three LDS stages hold tiles kt-1 (being vacated), kt (being multiplied) and kt+1 (landing).  Per tile:
-//   read the k = 8..15 fragments of tile kt; first 4 MFMAs of its k = 0..7 half
-//   wait for this thread's loads of tile kt+1, barrier          (everybody's loads have landed)
-//   issue the loads of tile kt+2 into the stage of tile kt-1, one load per group of 4 MFMAs, so that the
-//   address arithmetic runs in the shadow of the matrix pipe
-//   read the k = 0..7 fragments of tile kt+1; the 16 MFMAs of the k = 8..15 half of tile kt
-// A stage is overwritten only one full iteration after its last fragment read was consumed by an MFMA,
-// so no wait on LDS reads is needed in front of the barrier.
-// SMALLC: the gathered tensor has fewer than 16 channels, one 16-wide k-step then spans several filter taps.
-template <int BM, int BN, bool SMALLC, bool DIST2>
-__global__ void __launch_bounds__(256) conv_gemm_f32_pipe_kernel(const GemmConv p) {
-    constexpr int BK = 16, STAGES = 3;
-    constexpr int LA = BM / 64, LB = BN / 64;     // 16-row blocks per wave and tile
-    constexpr int LPT = LA + LB;                  // direct loads per thread and tile
-    constexpr int WTM = BM / 2, WTN = BN / 2, TM = WTM / 32, TN = WTN / 32;
-    constexpr int STAGE = (BM + BN) * BK;         // floats per stage: A rows then B rows
-    static_assert(BM % 64 == 0 && BN % 64 == 0, "tile shape");
-
-    __shared__ __attribute__((aligned(1024))) float lds[STAGES * STAGE];
-    const unsigned lds_addr = (unsigned)(uintptr_t)(lds_ptr_t)lds;
-
-    const int tid = threadIdx.x, lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);     // wave-uniform, lives in an SGPR
-    const int wm = wave >> 1, wn = wave & 1;
-    const int nbn = (p.N + BN - 1) / BN;
-    const int tile = xcd_tile(blockIdx.x, gridDim.x);
-    const int m0 = (tile / nbn) * BM, n0 = (tile % nbn) * BN;
-
-    const float* __restrict__ A = static_cast<const float*>(p.a);
-    const float* __restrict__ B = static_cast<const float*>(p.b);
-
-    // this lane's place in a 16-row block: row lane/4, LDS slot lane%4, global chunk slot ^ swz(row)
-    const int lrow = lane >> 2;
-    const int kq = (lane & 3) ^ swz(lrow);
-
-    long long a_base[LA];
-    int a_h[LA], a_w[LA];
-#pragma unroll
-    for (int i = 0; i < LA; ++i) {
-        const int m = m0 + (i * 4 + wave) * 16 + lrow;
-        if (m < p.M) {
-            const int qo = m % p.Qo, t = m / p.Qo;
-            const int po = t % p.Po, img = t / p.Po;
-            a_h[i] = po * p.sh - p.ph;
-            a_w[i] = qo * p.sw - p.pw;
-            a_base[i] = (long long)img * p.Hi * p.Wi * p.Ci;
-        } else {
-            a_h[i] = -(1 << 28);
-            a_w[i] = 0;
-            a_base[i] = 0;
-        }
-    }
-    long long b_off[LB];
-#pragma unroll
-    for (int i = 0; i < LB; ++i) {
-        const int n = n0 + (i * 4 + wave) * 16 + lrow;
-        b_off[i] = n < p.N ? (long long)n * p.Kg : -1;
-    }
-
-    int kg = kq * 4;
-    // copies of the descriptor fields used inside the main loop (the inline-assembly memory clobbers would
-    // otherwise make the compiler re-read them from the kernel arguments every iteration)
-    const int Hi_ = p.Hi, Wi_ = p.Wi, Ci_ = p.Ci, R_ = p.R, S_ = p.S;
-    int c = kg % p.Ci, r, s;
-    {
-        const int rs = kg / p.Ci;
-        s = rs % p.S;
-        r = rs / p.S;
-    }
-
-    // direct load number l (A blocks first, then B blocks) of the tile at (r, s, c) into stage st
-    auto issue_one = [&](int st, int l) {
-        const unsigned base = lds_addr + (unsigned)(st * STAGE + wave * 256) * 4u;
-        const bool kok = r < R_;
-        if (l < LA) {
-            const int h = a_h[l] + r, w = a_w[l] + s;
-            const bool ok = kok & ((unsigned)h < (unsigned)Hi_) & ((unsigned)w < (unsigned)Wi_);   // no short-circuit branches
-            lds_dma16(pick(ok, A + a_base[l] + ((long long)h * Wi_ + w) * Ci_ + c, g_zero_chunk), base + l * 4096u);
-        } else {
-            const int i = l - LA;
-            lds_dma16(pick(kok & (b_off[i] >= 0), B + b_off[i] + kg, g_zero_chunk), base + (unsigned)(BM * BK) * 4u + i * 4096u);
-        }
-    };
-    // step (r, s, c) to the next tile
-    auto advance = [&]() {
-        kg += BK;
-        c += BK;
-        if (SMALLC) {
-            while (c >= Ci_) {
-                c -= Ci_;
-                if (++s == S_) {
-                    s = 0;
-                    ++r;
-                }
-            }
-        } else {                                  // at most one wrap: written without branches
-            const bool wrap = c >= Ci_;
-            c = wrap ? c - Ci_ : c;
-            s += wrap ? 1 : 0;
-            const bool wrap2 = s == S_;
-            s = wrap2 ? 0 : s;
-            r += wrap2 ? 1 : 0;
-        }
-    };
-    auto issue_tile = [&](int st) {
-#pragma unroll
-        for (int l = 0; l < LPT; ++l) issue_one(st, l);
-        advance();
-    };
-
-    f32x16 acc[TM][TN];
-#pragma unroll
-    for (int i = 0; i < TM; ++i)
-#pragma unroll
-        for (int j = 0; j < TN; ++j)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
-
-    // fragment addressing: lane reads row (lane & 31) of a 32-row MFMA tile, chunk 2*k8 + (lane >> 5)
-    const int frow = lane & 31, fhalf = lane >> 5;
-    const int fsw = swz(frow);
-    const int a_frag = (wm * WTM + frow) * BK, b_frag = BM * BK + (wn * WTN + frow) * BK;
-    float4 fa[2][TM], fb[2][TN];
-    auto read_frags = [&](int st, int k8, int slot) {
-        const float* base = lds + st * STAGE;
-        const int ch = ((2 * k8 + fhalf) ^ fsw) * 4;
-#pragma unroll
-        for (int i = 0; i < TM; ++i) fa[slot][i] = *reinterpret_cast<const float4*>(base + a_frag + i * 32 * BK + ch);
-#pragma unroll
-        for (int j = 0; j < TN; ++j) fb[slot][j] = *reinterpret_cast<const float4*>(base + b_frag + j * 32 * BK + ch);
-    };
-    auto mfma_e = [&](int slot, int e) {
-#pragma unroll
-        for (int i = 0; i < TM; ++i)
-#pragma unroll
-            for (int j = 0; j < TN; ++j)
-                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(elem(fa[slot][i], e), elem(fb[slot][j], e), acc[i][j], 0, 0, 0);
-    };
-
-    const int nkt = (p.Kg + BK - 1) / BK;
-    issue_tile(0);
-    issue_tile(1);
-    wait_vmcnt<LPT>();                            // tile 0 has landed (this thread's part)
-    block_barrier();
-    if (DIST2) issue_tile(2);
-    read_frags(0, 0, 0);
-    int st = 0;                                   // stage of tile kt
-    // The last tile is peeled off so that the loop body has no branch between the fragment reads and the
-    // MFMAs that follow them (a join there makes the compiler wait for the reads just issued).
-    for (int kt = 0; kt + 1 < nkt; ++kt) {
-        const int nx = st == 2 ? 0 : st + 1;      // stage of tile kt+1
-        const int fr = nx == 2 ? 0 : nx + 1;      // stage of tile kt-1 = stage of tile kt+2
-        read_frags(st, 1, 1);
-        mfma_e(0, 0);
-        __builtin_amdgcn_sched_barrier(0);
-        if (DIST2) {
-            wait_vmcnt<LPT>();                    // tile kt+1 landed; tile kt+2 may still be in flight
-            asm volatile("s_waitcnt lgkmcnt(0)" : : : "memory");   // the k = 8..15 reads of tile kt are in registers
-        } else {
-            wait_vmcnt<0>();
-        }
-        block_barrier();
-#pragma unroll
-        for (int e = 1; e < 4; ++e) {             // loads spread over the three remaining MFMA groups
-#pragma unroll
-            for (int l = 0; l < LPT; ++l)
-                if (l * 3 / LPT == e - 1) issue_one(DIST2 ? st : fr, l);
-            if (e == 3) advance();
-            mfma_e(0, e);
-            __builtin_amdgcn_sched_barrier(0);
-        }
-        read_frags(nx, 0, 0);
-#pragma unroll
-        for (int e = 0; e < 4; ++e) mfma_e(1, e);
-        st = nx;
-    }
-    read_frags(st, 1, 1);
-#pragma unroll
-    for (int e = 0; e < 4; ++e) mfma_e(0, e);
-#pragma unroll
-    for (int e = 0; e < 4; ++e) mfma_e(1, e);
-    // the loads of the tile past the end (zeros) may still be in flight into LDS: let them land before exit
-    wait_vmcnt<0>();
-
-    store_tile<TM, TN>(p, acc, m0 + wm * WTM, n0 + wn * WTN, lane);
+// Accumulators of one wave <-> a partial-tile slot in the workspace, in register order: every store
+// instruction writes 64 consecutive floats.
+template <int TM, int TN>
+__device__ __forceinline__ size_t partial_index(int wave, int i, int j, int v, int lane) {
+    return ((((size_t)wave * TM + i) * TN + j) * 16 + v) * 64 + lane;
 }
 
-// ------------------------------------------------------------------------------------------------
-// forward / backward-data kernel, register-staged variant of the pipelined kernel: same LDS layout and
-// MFMA schedule, but a tile travels global -> registers (one iteration in flight) -> LDS (two buffers).
-// ------------------------------------------------------------------------------------------------
 template <int BM, int BN, bool SMALLC>
-__global__ void __launch_bounds__(256) conv_gemm_f32_stage_kernel(const GemmConv p) {
+__global__ void __launch_bounds__(256) conv_gemm_f32_sk_kernel(const GemmConv p) {
     constexpr int BK = 16;
-    constexpr int LA = BM / 64, LB = BN / 64, LPT = LA + LB;
+    constexpr int LA = BM / 64, LB = BN / 64, LPT = LA + LB;   // 16-row blocks (= 16-byte loads) per thread and tile
     constexpr int WTM = BM / 2, WTN = BN / 2, TM = WTM / 32, TN = WTN / 32;
-    constexpr int STAGE = (BM + BN) * BK;
+    constexpr int STAGE = (BM + BN) * BK;                       // floats per LDS buffer: A rows then B rows
     static_assert(BM % 64 == 0 && BN % 64 == 0, "tile shape");
 
     __shared__ __attribute__((aligned(1024))) float lds[2 * STAGE];
 
     const int tid = threadIdx.x, lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform, lives in an SGPR
     const int wm = wave >> 1, wn = wave & 1;
     const int nbn = (p.N + BN - 1) / BN;
-    const int tile = xcd_tile(blockIdx.x, gridDim.x);
-    const int m0 = (tile / nbn) * BM, n0 = (tile % nbn) * BN;
+    const int nkt = (p.Kg + BK - 1) / BK;
+
+    // this block's range of (tile, k-step) pairs, as positions in the end-to-end sequence of k-steps
+    int it, it_end, sk_id = -1;
+    if ((int)blockIdx.x < p.dp_tiles) {
+        it = xcd_tile(blockIdx.x, p.dp_tiles) * nkt;
+        it_end = it + nkt;
+    } else {
+        sk_id = blockIdx.x - p.dp_tiles;
+        const long long base = (long long)p.dp_tiles * nkt;
+        it = (int)(base + (long long)sk_id * p.sk_iters / p.sk_blocks);
+        it_end = (int)(base + (long long)(sk_id + 1) * p.sk_iters / p.sk_blocks);
+    }
+    const int it_begin = it;
 
     const float* __restrict__ A = static_cast<const float*>(p.a);
     const float* __restrict__ B = static_cast<const float*>(p.b);
+    // this lane's place in a 16-row block: row lane/4, LDS slot lane%4, global chunk slot ^ swz(row)
     const int lrow = lane >> 2;
     const int kq = (lane & 3) ^ swz(lrow);
-
-    long long a_base[LA];
-    int a_h[LA], a_w[LA];
-#pragma unroll
-    for (int i = 0; i < LA; ++i) {
-        const int m = m0 + (i * 4 + wave) * 16 + lrow;
-        if (m < p.M) {
-            const int qo = m % p.Qo, t = m / p.Qo;
-            const int po = t % p.Po, img = t / p.Po;
-            a_h[i] = po * p.sh - p.ph;
-            a_w[i] = qo * p.sw - p.pw;
-            a_base[i] = (long long)img * p.Hi * p.Wi * p.Ci;
-        } else {
-            a_h[i] = -(1 << 28);
-            a_w[i] = 0;
-            a_base[i] = 0;
-        }
-    }
-    long long b_off[LB];
-#pragma unroll
-    for (int i = 0; i < LB; ++i) {
-        const int n = n0 + (i * 4 + wave) * 16 + lrow;
-        b_off[i] = n < p.N ? (long long)n * p.Kg : -1;
-    }
-    int kg = kq * 4;
+    // copies of the descriptor fields used in the main loop (the inline-assembly memory clobbers would
+    // otherwise make the compiler re-read them from the kernel arguments every iteration)
     const int Hi_ = p.Hi, Wi_ = p.Wi, Ci_ = p.Ci, R_ = p.R, S_ = p.S;
-    int c = kg % p.Ci, r, s;
-    {
-        const int rs = kg / p.Ci;
-        s = rs % p.S;
-        r = rs / p.S;
-    }
+    // fragment addressing: lane reads row (lane & 31) of a 32-row MFMA tile, chunk 2*k8 + (lane >> 5)
+    const int frow = lane & 31, fhalf = lane >> 5;
+    const int fsw = swz(frow);
+    const int a_frag = (wm * WTM + frow) * BK, b_frag = BM * BK + (wn * WTN + frow) * BK;
 
-    float4 g[LPT];                                // the tile in flight
-    auto gload_one = [&](int l) {
-        const bool kok = r < R_;
-        float4 v;
-        if (l < LA) {
-            const int h = a_h[l] + r, w = a_w[l] + s;
-            const bool ok = kok & ((unsigned)h < (unsigned)Hi_) & ((unsigned)w < (unsigned)Wi_);   // no short-circuit branches
-            v = load_global16(pick(ok, A + a_base[l] + ((long long)h * Wi_ + w) * Ci_ + c, g_zero_chunk));
-        } else {
-            v = load_global16(pick(kok & (b_off[l - LA] >= 0), B + b_off[l - LA] + kg, g_zero_chunk));
-        }
-        g[l] = v;
-    };
-    auto advance = [&]() {
-        kg += BK;
-        c += BK;
-        if (SMALLC) {
-            while (c >= Ci_) {
-                c -= Ci_;
-                if (++s == S_) {
-                    s = 0;
-                    ++r;
-                }
-            }
-        } else {
-            const bool wrap = c >= Ci_;
-            c = wrap ? c - Ci_ : c;
-            s += wrap ? 1 : 0;
-            const bool wrap2 = s == S_;
-            s = wrap2 ? 0 : s;
-            r += wrap2 ? 1 : 0;
-        }
-    };
-    // registers -> LDS: lane (row lane/4, slot lane%4) of 16-row block (l*4 + wave); 16 B per lane, lane order
-    auto sstore = [&](int buf) {
-        float* base = lds + buf * STAGE + wave * 256 + lane * 4;
+    while (it < it_end) {
+        const int tile = it / nkt;
+        const int k0 = it - tile * nkt;
+        const int k1 = min(nkt, k0 + (it_end - it));
+        const int m0 = (tile / nbn) * BM, n0 = (tile % nbn) * BN;
+
+        long long a_base[LA];
+        int a_h[LA], a_w[LA];
 #pragma unroll
-        for (int l = 0; l < LPT; ++l)
-            *reinterpret_cast<float4*>(base + (l < LA ? l * 1024 : BM * BK + (l - LA) * 1024)) = g[l];
-    };
+        for (int i = 0; i < LA; ++i) {
+            const int m = m0 + (i * 4 + wave) * 16 + lrow;
+            if (m < p.M) {
+                const int qo = m % p.Qo, t = m / p.Qo;
+                const int po = t % p.Po, img = t / p.Po;
+                a_h[i] = po * p.sh - p.ph;
+                a_w[i] = qo * p.sw - p.pw;
+                a_base[i] = (long long)img * p.Hi * p.Wi * p.Ci;
+            } else {
+                a_h[i] = -(1 << 28);              // every tap fails the bounds test
+                a_w[i] = 0;
+                a_base[i] = 0;
+            }
+        }
+        long long b_off[LB];
+#pragma unroll
+        for (int i = 0; i < LB; ++i) {
+            const int n = n0 + (i * 4 + wave) * 16 + lrow;
+            b_off[i] = n < p.N ? (long long)n * p.Kg : -1;
+        }
+        // position of this lane's 16-byte chunk inside the filter window at k-step k0
+        int kg = k0 * BK + kq * 4;
+        int c = kg % p.Ci, r, s;
+        {
+            const int rs = kg / p.Ci;
+            s = rs % p.S;
+            r = rs / p.S;
+        }
+
+        float4 g[LPT];                            // the tile in flight between global memory and LDS
+        auto gload_one = [&](int l) {
+            const bool kok = r < R_;              // same as kg < Kg
+            if (l < LA) {
+                const int h = a_h[l] + r, w = a_w[l] + s;
+                const bool ok = kok & ((unsigned)h < (unsigned)Hi_) & ((unsigned)w < (unsigned)Wi_);
+                g[l] = load_global16(pick(ok, A + a_base[l] + ((long long)h * Wi_ + w) * Ci_ + c, g_zero_chunk));
+            } else {
+                g[l] = load_global16(pick(kok & (b_off[l - LA] >= 0), B + b_off[l - LA] + kg, g_zero_chunk));
+            }
+        };
+        auto advance = [&]() {
+            kg += BK;
+            c += BK;
+            if (SMALLC) {                         // fewer than 16 channels: a k-step spans several taps
+                while (c >= Ci_) {
+                    c -= Ci_;
+                    if (++s == S_) {
+                        s = 0;
+                        ++r;
+                    }
+                }
+            } else {                              // at most one wrap: written without branches
+                const bool wrap = c >= Ci_;
+                c = wrap ? c - Ci_ : c;
+                s += wrap ? 1 : 0;
+                const bool wrap2 = s == S_;
+                s = wrap2 ? 0 : s;
+                r += wrap2 ? 1 : 0;
+            }
+        };
+        auto gload_tile = [&]() {
+#pragma unroll
+            for (int l = 0; l < LPT; ++l) gload_one(l);
+            advance();
+        };
+        // registers -> LDS: lane (row lane/4, slot lane%4) of 16-row block (l*4 + wave): 16 B per lane in lane order
+        auto sstore = [&](int buf) {
+            float* base = lds + buf * STAGE + wave * 256 + lane * 4;
+#pragma unroll
+            for (int l = 0; l < LPT; ++l)
+                *reinterpret_cast<float4*>(base + (l < LA ? l * 1024 : BM * BK + (l - LA) * 1024)) = g[l];
+        };
+
+        f32x16 acc[TM][TN];
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+        float4 fa[2][TM], fb[2][TN];
+        auto read_frags = [&](int buf, int k8, int slot) {
+            const float* base = lds + buf * STAGE;
+            const int ch = ((2 * k8 + fhalf) ^ fsw) * 4;
+#pragma unroll
+            for (int i = 0; i < TM; ++i) fa[slot][i] = *reinterpret_cast<const float4*>(base + a_frag + i * 32 * BK + ch);
+#pragma unroll
+            for (int j = 0; j < TN; ++j) fb[slot][j] = *reinterpret_cast<const float4*>(base + b_frag + j * 32 * BK + ch);
+        };
+        auto mfma_e = [&](int slot, int e) {
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(elem(fa[slot][i], e), elem(fb[slot][j], e), acc[i][j], 0, 0, 0);
+        };
+
+        gload_tile();                             // k-step k0
+        sstore(0);
+        gload_tile();                             // k-step k0+1 (zeros past the end of the filter window)
+        lds_barrier();
+        read_frags(0, 0, 0);
+        int cur = 0;
+        // The last k-step is peeled off so that the loop body is one basic block (a join between the fragment
+        // reads and the MFMAs that follow would make the compiler wait for the reads just issued).
+        for (int kt = k0; kt + 1 < k1; ++kt) {
+            read_frags(cur, 1, 1);                // k = 8..15 of this step
+            mfma_e(0, 0);
+            mfma_e(0, 1);
+            __builtin_amdgcn_sched_barrier(0);
+            sstore(cur ^ 1);                      // next step: its buffer was last read one iteration ago
+            mfma_e(0, 2);
+            __builtin_amdgcn_sched_barrier(0);
+            gload_tile();                         // the step after next, into the registers just stored
+            mfma_e(0, 3);
+            __builtin_amdgcn_sched_barrier(0);
+            lds_barrier();
+            read_frags(cur ^ 1, 0, 0);            // k = 0..7 of the next step
+#pragma unroll
+            for (int e = 0; e < 4; ++e) mfma_e(1, e);
+            cur ^= 1;
+        }
+        read_frags(cur, 1, 1);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) mfma_e(0, e);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) mfma_e(1, e);
+
+        if (k0 == 0 && k1 == nkt) {
+            store_tile<TM, TN>(p, acc, m0 + wm * WTM, n0 + wn * WTN, lane);
+        } else {
+            // part of a tile: first segment of this block's range -> slot 2*sk_id, last -> slot 2*sk_id + 1
+            float* part = p.partial + ((size_t)2 * sk_id + (it == it_begin ? 0 : 1)) * (BM * BN);
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) part[partial_index<TM, TN>(wave, i, j, v, lane)] = acc[i][j][v];
+        }
+        it += k1 - k0;
+        lds_barrier();                            // everybody is done with the LDS buffers before the next segment
+    }
+}
+
+// Adds the parts of every tile that stream-K blocks split between them, in k order, and stores the tile.
+// Block (t, v) handles accumulator register v of every 32x32 MFMA tile of stream-K tile t, with the thread
+// geometry of the main kernel: 16 blocks per tile keep the whole chip busy on what is a small reduction.
+template <int BM, int BN>
+__global__ void __launch_bounds__(256) conv_gemm_f32_fixup_kernel(const GemmConv p) {
+    constexpr int BK = 16, TM = BM / 64, TN = BN / 64;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int wm = wave >> 1, wn = wave & 1;
+    const int v = blockIdx.y;
+    const int nbn = (p.N + BN - 1) / BN;
+    const int nkt = (p.Kg + BK - 1) / BK;
+    const long long tb = (long long)blockIdx.x * nkt, te = tb + nkt;      // this tile's k-steps in stream-K positions
+    auto begin_of = [&](long long j) { return j * p.sk_iters / p.sk_blocks; };
+    long long j = tb * p.sk_blocks / p.sk_iters;
+    while (j > 0 && begin_of(j) > tb) --j;
+    while (begin_of(j + 1) <= tb) ++j;
+    if (begin_of(j) <= tb && begin_of(j + 1) >= te) return;              // one block did the whole tile and stored it
 
     f32x16 acc[TM][TN];
 #pragma unroll
     for (int i = 0; i < TM; ++i)
 #pragma unroll
-        for (int j = 0; j < TN; ++j)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
-
-    const int frow = lane & 31, fhalf = lane >> 5;
-    const int fsw = swz(frow);
-    const int a_frag = (wm * WTM + frow) * BK, b_frag = BM * BK + (wn * WTN + frow) * BK;
-    float4 fa[2][TM], fb[2][TN];
-    auto read_frags = [&](int buf, int k8, int slot) {
-        const float* base = lds + buf * STAGE;
-        const int ch = ((2 * k8 + fhalf) ^ fsw) * 4;
-#pragma unroll
-        for (int i = 0; i < TM; ++i) fa[slot][i] = *reinterpret_cast<const float4*>(base + a_frag + i * 32 * BK + ch);
-#pragma unroll
-        for (int j = 0; j < TN; ++j) fb[slot][j] = *reinterpret_cast<const float4*>(base + b_frag + j * 32 * BK + ch);
-    };
-    auto mfma_e = [&](int slot, int e) {
+        for (int jj = 0; jj < TN; ++jj) acc[i][jj][0] = 0.f;
+    for (; j < p.sk_blocks && begin_of(j) < te; ++j) {
+        const bool first_of_block = begin_of(j) >= tb;                   // the segment starts where the block's range starts
+        const float* part = p.partial + ((size_t)2 * j + (first_of_block ? 0 : 1)) * (BM * BN);
 #pragma unroll
         for (int i = 0; i < TM; ++i)
 #pragma unroll
-            for (int j = 0; j < TN; ++j)
-                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(elem(fa[slot][i], e), elem(fb[slot][j], e), acc[i][j], 0, 0, 0);
-    };
-    // LDS writes and reads of this wave are complete, then the barrier; global loads stay in flight
-    auto lds_barrier = [&]() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" : : : "memory"); };
-
-    const int nkt = (p.Kg + BK - 1) / BK;
-#pragma unroll
-    for (int l = 0; l < LPT; ++l) gload_one(l);   // tile 0
-    advance();
-    sstore(0);
-#pragma unroll
-    for (int l = 0; l < LPT; ++l) gload_one(l);   // tile 1 (zeros if there is none)
-    advance();
-    lds_barrier();
-    read_frags(0, 0, 0);
-    int cur = 0;
-    for (int kt = 0; kt + 1 < nkt; ++kt) {
-        read_frags(cur, 1, 1);                    // k = 8..15 of tile kt
-        mfma_e(0, 0);
-        mfma_e(0, 1);
-        __builtin_amdgcn_sched_barrier(0);
-        sstore(cur ^ 1);                          // tile kt+1: its buffer was last read one iteration ago
-        mfma_e(0, 2);
-        __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-        for (int l = 0; l < LPT; ++l) gload_one(l);   // tile kt+2 into the registers just stored
-        advance();
-        mfma_e(0, 3);
-        __builtin_amdgcn_sched_barrier(0);
-        lds_barrier();
-        read_frags(cur ^ 1, 0, 0);                // k = 0..7 of tile kt+1
-#pragma unroll
-        for (int e = 0; e < 4; ++e) mfma_e(1, e);
-        cur ^= 1;
+            for (int jj = 0; jj < TN; ++jj) acc[i][jj][0] += part[partial_index<TM, TN>(wave, i, jj, v, lane)];
     }
-    read_frags(cur, 1, 1);
+    // move the sums to register position v, where store_tile expects them
+    f32x16 out[TM][TN];
 #pragma unroll
-    for (int e = 0; e < 4; ++e) mfma_e(0, e);
+    for (int i = 0; i < TM; ++i)
 #pragma unroll
-    for (int e = 0; e < 4; ++e) mfma_e(1, e);
-
-    store_tile<TM, TN>(p, acc, m0 + wm * WTM, n0 + wn * WTN, lane);
+        for (int jj = 0; jj < TN; ++jj)
+#pragma unroll
+            for (int u = 0; u < 16; ++u) out[i][jj][u] = acc[i][jj][0];
+    const int tile = p.dp_tiles + blockIdx.x;
+    const int m0 = (tile / nbn) * BM, n0 = (tile % nbn) * BN;
+    store_tile<TM, TN>(p, out, m0 + wm * (BM / 2), n0 + wn * (BN / 2), lane, v);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -809,47 +701,102 @@ lc_status launch_wgrad(const GemmWgrad& p, hipStream_t stream) {
     return lc_end_call();
 }
 
-template <int BM, int BN, bool SMALLC, bool DIST2>
-lc_status launch_conv_pipe(const GemmConv& p, hipStream_t stream) {
-    const long long tiles = (long long)((p.M + BM - 1) / BM) * ((p.N + BN - 1) / BN);
-    if (tiles <= 0 || tiles > 0x7fffffffLL) return LC_ERR_UNSUPPORTED;
-    hipLaunchKernelGGL((conv_gemm_f32_pipe_kernel<BM, BN, SMALLC, DIST2>), dim3((unsigned)tiles), dim3(256), 0, stream, p);
-    return lc_end_call();
+// Split of the output tiles into whole-tile blocks and stream-K blocks for a BM x BN tiling.
+struct SkPlan {
+    int dp_tiles, sk_blocks;
+    long long sk_iters;
+};
+
+int device_cu_count() {
+    static const int n = [] {
+        int dev = 0, cus = 0;
+        if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess ||
+            cus <= 0)
+            cus = 256;
+        (void)hipGetLastError();
+        return cus;
+    }();
+    return n;
+}
+
+SkPlan sk_plan(long long tiles, int nkt, int resident_blocks) {
+    SkPlan pl;
+    const long long rounds = tiles / resident_blocks;
+    long long dp = rounds * resident_blocks;
+    long long rest = tiles - dp;
+    pl.dp_tiles = (int)dp;
+    pl.sk_blocks = 0;
+    pl.sk_iters = 0;
+    if (rest == 0 || getenv("LARSCONV_NO_STREAMK")) {      // every round is full (or stream-K switched off for comparison runs)
+        pl.dp_tiles = (int)tiles;
+        return pl;
+    }
+    pl.sk_iters = rest * nkt;
+    long long blocks = pl.sk_iters / 8;                      // at least 8 k-steps per stream-K block
+    if (blocks > resident_blocks) blocks = resident_blocks;
+    if (blocks < 1) blocks = 1;
+    pl.sk_blocks = (int)blocks;
+    return pl;
+}
+
+// Blocks of the main kernel that fit on the chip at once: 3 per compute unit (32 KB LDS, ~140 registers).
+inline int resident_blocks() { return 3 * device_cu_count(); }
+
+template <int BM, int BN>
+bool sk_geometry(const GemmConv& p, long long* tiles, int* nkt) {
+    *tiles = (long long)((p.M + BM - 1) / BM) * ((p.N + BN - 1) / BN);
+    *nkt = (p.Kg + 15) / 16;
+    return *tiles > 0 && *tiles * *nkt < 0x7fffffffLL;
 }
 
 template <int BM, int BN, bool SMALLC>
-lc_status launch_conv_stage(const GemmConv& p, hipStream_t stream) {
-    const long long tiles = (long long)((p.M + BM - 1) / BM) * ((p.N + BN - 1) / BN);
-    if (tiles <= 0 || tiles > 0x7fffffffLL) return LC_ERR_UNSUPPORTED;
-    hipLaunchKernelGGL((conv_gemm_f32_stage_kernel<BM, BN, SMALLC>), dim3((unsigned)tiles), dim3(256), 0, stream, p);
+lc_status launch_conv_sk(GemmConv p, hipStream_t stream) {
+    long long tiles;
+    int nkt;
+    if (!sk_geometry<BM, BN>(p, &tiles, &nkt)) return LC_ERR_UNSUPPORTED;
+    SkPlan pl = sk_plan(tiles, nkt, resident_blocks());
+    if (pl.sk_blocks > 0 && !p.partial) {                    // no workspace for the parts: whole tiles only
+        pl.dp_tiles = (int)tiles;
+        pl.sk_blocks = 0;
+        pl.sk_iters = 0;
+    }
+    p.dp_tiles = pl.dp_tiles;
+    p.sk_blocks = pl.sk_blocks;
+    p.sk_iters = pl.sk_iters;
+    hipLaunchKernelGGL((conv_gemm_f32_sk_kernel<BM, BN, SMALLC>), dim3((unsigned)(pl.dp_tiles + pl.sk_blocks)), dim3(256), 0,
+                       stream, p);
+    if (pl.sk_blocks > 0)
+        hipLaunchKernelGGL((conv_gemm_f32_fixup_kernel<BM, BN>), dim3((unsigned)(tiles - pl.dp_tiles), 16), dim3(256), 0, stream, p);
     return lc_end_call();
 }
 
-// LARSCONV_KERNEL=classic selects the register-staged kernels everywhere (for comparison runs).
-static bool use_pipe_kernels() {
-    static const bool on = [] {
-        const char* e = getenv("LARSCONV_KERNEL");
-        return !(e && strcmp(e, "classic") == 0);
+inline bool use_main_kernel(const GemmConv& p) {
+    static const bool classic = [] {
+        const char* e = getenv("LARSCONV_KERNEL");          // LARSCONV_KERNEL=classic: comparison runs
+        return e && strcmp(e, "classic") == 0;
     }();
-    return on;
+    const bool vec = (p.Ci % 4 == 0) && aligned16(p.a) && aligned16(p.b);
+    return vec && !(p.dh > 1 || p.dw > 1) && !classic;
 }
 
 }  // namespace
 
+size_t lc_conv_gemm_workspace(const GemmConv& p) {
+    if (!use_main_kernel(p)) return 0;
+    long long tiles;
+    int nkt;
+    const bool wide = p.N > 64;
+    if (!(wide ? sk_geometry<128, 128>(p, &tiles, &nkt) : sk_geometry<128, 64>(p, &tiles, &nkt))) return 0;
+    const SkPlan pl = sk_plan(tiles, nkt, resident_blocks());
+    return (size_t)2 * pl.sk_blocks * 128 * (wide ? 128 : 64) * sizeof(float);
+}
+
 lc_status lc_launch_conv_gemm_f32(const GemmConv& p, hipStream_t stream) {
     const bool vec = (p.Ci % 4 == 0) && aligned16(p.a) && aligned16(p.b);
     if (!vec) return launch_conv<64, 64, 16, 1>(p, stream);
-    const bool dilated = p.dh > 1 || p.dw > 1;
-    if (!dilated && use_pipe_kernels()) {
-        static const bool stage = [] { const char* e = getenv("LARSCONV_KERNEL"); return e && strcmp(e, "stage") == 0; }();
-        if (stage) {
-            if (p.Ci < 16) return p.N > 64 ? launch_conv_stage<128, 128, true>(p, stream) : launch_conv_stage<128, 64, true>(p, stream);
-            return p.N > 64 ? launch_conv_stage<128, 128, false>(p, stream) : launch_conv_stage<128, 64, false>(p, stream);
-        }
-        static const bool d2 = [] { const char* e = getenv("LARSCONV_DIST"); return !(e && atoi(e) == 1); }();
-        if (p.Ci < 16) return p.N > 64 ? launch_conv_pipe<128, 128, true, true>(p, stream) : launch_conv_pipe<128, 64, true, true>(p, stream);
-        if (d2) return p.N > 64 ? launch_conv_pipe<128, 128, false, true>(p, stream) : launch_conv_pipe<128, 64, false, true>(p, stream);
-        return p.N > 64 ? launch_conv_pipe<128, 128, false, false>(p, stream) : launch_conv_pipe<128, 64, false, false>(p, stream);
+    if (use_main_kernel(p)) {
+        if (p.Ci < 16) return p.N > 64 ? launch_conv_sk<128, 128, true>(p, stream) : launch_conv_sk<128, 64, true>(p, stream);
+        return p.N > 64 ? launch_conv_sk<128, 128, false>(p, stream) : launch_conv_sk<128, 64, false>(p, stream);
     }
     if (p.N > 64) return launch_conv<128, 128, 16, 4>(p, stream);
     return launch_conv<128, 64, 16, 4>(p, stream);

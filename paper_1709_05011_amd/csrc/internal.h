@@ -47,8 +47,14 @@ struct GemmConv {
     // scatter epilogue (0 = off): row (img,po,qo) owns the cell [po*esh, po*esh+esh) x [qo*esw, ...) of
     // an [imgs][Ho][Wo][ldd] tensor; the value goes to the cell's corner, zeros to the rest of it.
     int scatter, Ho, Wo, esh, esw;
+    // stream-K split, filled in by the launcher: whole-tile blocks, blocks sharing the k-steps of the
+    // remaining tiles, their total k-steps, and the workspace for partial tiles (2 slots per such block)
+    int dp_tiles, sk_blocks;
+    long long sk_iters;
+    float* partial;
 };
 lc_status lc_launch_conv_gemm_f32(const GemmConv& p, hipStream_t stream);
+size_t lc_conv_gemm_workspace(const GemmConv& p);   // bytes `partial` must hold for this problem (0 = none)
 
 // Filter gradient: D[k][j] = sum_m dY[m][k] * Xg(m, j), m = (img, p, q), j = (r, s, c); the reduction
 // over m is cut into `splits` ranges, split z writing to d + z * K * J.

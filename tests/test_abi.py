@@ -52,7 +52,7 @@ def test_out_shape_and_descriptor_validation():
 
 def test_workspace_queries():
     nhwc = lc.ConvDesc(8, 64, 14, 14, 64, 3, 3, 1, 1, 1, 1)
-    assert lc.conv2d_workspace_bytes(nhwc, lc.LC_PASS_FWD) == 0
+    assert lc.conv2d_workspace_bytes(nhwc, lc.LC_PASS_FWD) % 256 == 0          # partial tiles of the stream-K blocks
     assert lc.conv2d_workspace_bytes(nhwc, lc.LC_PASS_BWD_DATA) >= 64 * 64 * 9 * 4
     assert lc.conv2d_workspace_bytes(nhwc, lc.LC_PASS_BWD_WEIGHT) % 256 == 0
     nchw = lc.ConvDesc(8, 64, 14, 14, 64, 3, 3, 1, 1, 1, 1, layout=lc.LC_NCHW)

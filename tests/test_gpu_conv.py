@@ -87,7 +87,7 @@ def test_misaligned_operands_take_the_scalar_path():
     xb[1:].copy_(torch.from_numpy(xl.ravel()))
     wb[1:].copy_(torch.from_numpy(wl.ravel()))
     y = torch.full((n, h, w, k), float("nan"), dtype=torch.float32, device=gu.DEV)
-    lc.conv2d_fwd(d, xb[1:], wb[1:], y, None)
+    lc.conv2d_fwd(d, xb[1:], wb[1:], y, gu.workspace(lc.conv2d_workspace_bytes(d, lc.LC_PASS_FWD)))
     torch.cuda.synchronize()
     assert gu.scaled_err(gu.from_layout(y.cpu().numpy(), lc.LC_NHWC), oracle.conv2d_fwd(x, wt, stride, pad)) <= TOL
 
