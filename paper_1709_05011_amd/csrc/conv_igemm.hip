@@ -812,11 +812,15 @@ int lc_wgrad_splits(int M, int K, int J) {
     int bm, bn;
     wgrad_tile(K, J, &bm, &bn);
     const long long tiles = (long long)((K + bm - 1) / bm) * ((J + bn - 1) / bn);
-    long long want = (1024 + tiles - 1) / tiles;          // about four blocks per compute unit in total
+    // blocks of this tiling that fit on the chip at once (registers and LDS of the kernel instances below):
+    // the split count fills exactly one such round, never spills a few blocks into a second one
+    const int per_cu = (bm == 128 && bn == 128) ? 4 : (bm == 64 && bn == 64) ? 8 : 6;
+    const long long round = (long long)per_cu * device_cu_count();
+    long long want = round / tiles;
     const long long most = (M + 255) / 256;               // at least 256 reduction rows per split
     if (want > most) want = most;
     if (want < 1) want = 1;
-    if (want > 4096) want = 4096;
+    if (want > 8192) want = 8192;
     return (int)want;
 }
 
