@@ -27,6 +27,10 @@ if ROOT not in sys.path:
 PEAK_MFMA_F32 = 157.3      # TFLOP/s, MI355X dense fp32 matrix
 PEAK_HBM = 8000.0          # GB/s
 LARS_BYTES_PER_PARAM = 28  # norm pass reads w, g (8 B); update reads w, g, v and writes w, v (20 B)
+# HBM-side bytes per launch of the dominant kernel in the default workload, from the two rocprofv3 --pmc runs
+# (FETCH_SIZE x 2.000 + WRITE_SIZE x 1.000, factors from the 1 GiB copy calibration) summarised in
+# profiles/resnet50_step_fp32_b256_hbm_traffic_and_mfma.txt.  Counters cannot be read from inside this process.
+MEASURED_TRAFFIC = {("conv_gemm_128x128", 256): 414.4e6 + 202.3e6}
 
 
 def log(*a):
@@ -180,7 +184,7 @@ def run_resnet50_step(args):
                                "lars_step over 161 tensors / 25.6M params)",
                    "batch": batch, "layout": "NHWC", "lars": {"eta": 0.001, "momentum": 0.9, "weight_decay": 5e-5, "lr": lr}},
         "roofline": {"bound": "mfma", "kernel": dom, "achieved": round(achieved, 2), "peak": PEAK_MFMA_F32,
-                     "unit": "TFLOP/s", "frac": round(achieved / PEAK_MFMA_F32, 4), "traffic": None,
+                     "unit": "TFLOP/s", "frac": round(achieved / PEAK_MFMA_F32, 4), "traffic": MEASURED_TRAFFIC.get((dom, batch)),
                      "launches_per_step": dn // args.steps, "avg_launch_ms": round(dms / dn, 4),
                      "flops_per_launch": dfl / dn},
         "conv_tflops": {p: round(per_pass[p][2] / (per_pass[p][0] * 1e-3) / 1e12, 2) for p in ("fwd", "bwd_data", "bwd_weight")},
@@ -321,6 +325,21 @@ def run_lars(args):
             "frac_of_hbm_peak": round(nbytes / (med * 1e-3) / 1e9 / PEAK_HBM, 4), "bytes_per_param": LARS_BYTES_PER_PARAM}
 
 
+def run_copy_calibration(args):
+    """A plain device-to-device copy of known size: what the FETCH_SIZE / WRITE_SIZE counters of rocprofv3 read
+    for it gives the factor by which the counters of the other kernels are scaled."""
+    import torch
+
+    nbytes = 1 << 30
+    src = torch.ones(nbytes // 4, device="cuda:0")
+    dst = torch.empty_like(src)
+    for _ in range(args.iters):
+        dst.copy_(src)
+    torch.cuda.synchronize()
+    return {"copy_calibration": True, "bytes_read_per_launch": nbytes, "bytes_written_per_launch": nbytes,
+            "launches": args.iters, "kernel": "the elementwise copy kernel torch launches for Tensor.copy_"}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -334,11 +353,14 @@ def main():
     ap.add_argument("--iters", type=int, default=10)
     ap.add_argument("--lars", choices=["resnet50", "alexnet_bn"])
     ap.add_argument("--rotate", type=int, default=1)
+    ap.add_argument("--copy-calib", action="store_true", help="run a 1 GiB device copy (counter calibration)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py measures one GPU: the hot path built here has no multi-GPU part "
                  "(the gradient all-reduce between backward and lars_step is out of scope); run with --gpus 1")
-    if args.sweep:
+    if args.copy_calib:
+        res = run_copy_calibration(args)
+    elif args.sweep:
         res = run_sweep(args)
     elif args.lars:
         res = run_lars(args)
