@@ -21,8 +21,8 @@ struct Regions {
 
 struct Plan {
     int P = 0, Q = 0, esize = 4;
-    bool nchw = false;
-    int cpad = 0;                    // channel count the kernels see for x / w (c rounded up to 4)
+    bool nchw = false, bf16 = false;
+    int cpad = 0;                    // channel count the kernels see for x / w (c rounded up to 4, to 8 for bf16)
     size_t a_nhwc = 0, b_nhwc = 0, out_nhwc = 0;   // NCHW staging: first operand, second operand, result
     size_t xpad = 0, wpad = 0;       // channel-padded copies
     size_t wt = 0;                   // re-ordered filter for backward-data
@@ -30,6 +30,11 @@ struct Plan {
     size_t sk = 0, sk_bytes = 0;     // partial tiles of the stream-K blocks (forward, backward-data)
     int splits = 1, m_per_split = 0;
     bool wgrad_direct = true;
+    // bf16 problems the bf16 MFMA kernel does not take (backward-data with k not a multiple of 8, or a strided
+    // window other than 1x1): operands are widened to fp32 copies, the fp32 pass runs on them, the result is
+    // rounded back to bf16.  Same arithmetic class: exact products of bf16 values, fp32 sums.
+    bool via_f32 = false;
+    size_t f_a = 0, f_b = 0, f_out = 0, f_ws = 0, f_ws_bytes = 0;
     size_t total = 0;
 };
 
@@ -45,7 +50,7 @@ lc_status check_desc(const lc_conv_desc* d, int* P, int* Q) {
     *Q = (d->w + 2 * d->pad_w - d->s) / d->stride_w + 1;
     // index ranges the kernels hold in 32-bit integers
     const long long lim = INT_MAX;
-    const long long cp = (d->c + 3) & ~3, kp = (d->k + 3) & ~3;
+    const long long cp = (d->c + 7) & ~7, kp = (d->k + 7) & ~7;
     if ((long long)d->n * *P * *Q > lim || (long long)d->n * d->h * d->w > lim) return LC_ERR_UNSUPPORTED;
     if ((long long)d->r * d->s * cp > lim || (long long)d->r * d->s * kp > lim) return LC_ERR_UNSUPPORTED;
     if ((long long)d->h * d->w * cp > lim || (long long)*P * *Q * kp > lim) return LC_ERR_UNSUPPORTED;
@@ -72,6 +77,7 @@ GemmConv gemm_fwd(const lc_conv_desc* d, int P, int Q, int cpad) {
     g.pw = d->pad_w;
     g.dh = g.dw = 1;
     g.ldd = d->k;
+    g.bf16 = d->dtype == LC_BF16;
     return g;
 }
 
@@ -88,6 +94,7 @@ GemmConv gemm_bwd_data(const lc_conv_desc* d, int P, int Q) {
     g.ldd = d->c;
     g.dh = g.dw = 1;
     g.sh = g.sw = 1;
+    g.bf16 = d->dtype == LC_BF16;
     if (d->r == 1 && d->s == 1 && d->pad_h == 0 && d->pad_w == 0) {
         // 1x1 window: one GEMM row per dy pixel; with a stride the result lands on the stride grid
         // of dx and the rest of each stride cell is zero.
@@ -115,19 +122,39 @@ GemmConv gemm_bwd_data(const lc_conv_desc* d, int P, int Q) {
     return g;
 }
 
+lc_conv_desc as_f32(const lc_conv_desc* d) {
+    lc_conv_desc f = *d;
+    f.dtype = LC_F32;
+    return f;
+}
+
 lc_status make_plan(const lc_conv_desc* d, lc_pass pass, Plan* pl) {
     const lc_status st = check_desc(d, &pl->P, &pl->Q);
     if (st != LC_OK) return st;
     if (pass != LC_PASS_FWD && pass != LC_PASS_BWD_DATA && pass != LC_PASS_BWD_WEIGHT) return LC_ERR_UNSUPPORTED;
-    if (d->dtype != LC_F32) return LC_ERR_UNSUPPORTED;   // bf16 kernels are not built yet
-    pl->esize = 4;
+    pl->bf16 = d->dtype == LC_BF16;
+    pl->esize = pl->bf16 ? 2 : 4;
     pl->nchw = d->layout == LC_NCHW;
     const size_t es = (size_t)pl->esize;
     const size_t nx = (size_t)d->n * d->h * d->w * d->c, ny = (size_t)d->n * pl->P * pl->Q * d->k;
     const size_t nw = (size_t)d->k * d->r * d->s * d->c;
-    pl->cpad = (d->c + 3) & ~3;
+    pl->cpad = pl->bf16 ? (d->c + 7) & ~7 : (d->c + 3) & ~3;
     const bool pad = pl->cpad != d->c;
     Regions rg;
+    if (pass == LC_PASS_BWD_DATA && pl->bf16) {
+        const GemmConv g = gemm_bwd_data(d, pl->P, pl->Q);
+        if (!lc_conv_gemm_bf16_native(g)) {        // pointers are empty here: a question of shape only
+            pl->via_f32 = true;
+            const lc_conv_desc f = as_f32(d);
+            pl->f_a = rg.take(ny * 4);
+            pl->f_b = rg.take(nw * 4);
+            pl->f_out = rg.take(nx * 4);
+            pl->f_ws_bytes = conv2d_workspace_bytes(&f, pass);
+            pl->f_ws = rg.take(pl->f_ws_bytes);
+            pl->total = rg.off;
+            return LC_OK;
+        }
+    }
     if (pass == LC_PASS_FWD) {
         if (pl->nchw) {
             pl->a_nhwc = rg.take(nx * es);
@@ -166,12 +193,14 @@ lc_status make_plan(const lc_conv_desc* d, lc_pass pass, Plan* pl) {
     return LC_OK;
 }
 
-lc_status check_buffers(const lc_conv_desc* d, const Plan& pl, const void* a, const void* b, const void* c,
+// a, b: the two operand tensors (of the descriptor's dtype); c: the result
+lc_status check_buffers(const Plan& pl, const void* a, const void* b, const void* c, size_t c_align,
                         const void* ws, size_t ws_bytes) {
     if (!a || !b || !c) return LC_ERR_NULL;
-    const uintptr_t mask = (uintptr_t)(pl.esize - 1);
+    // fp32 tensors need their natural alignment (16 bytes take the vector path); bf16 tensors 16 bytes
+    const uintptr_t mask = pl.bf16 ? 15 : 3;
     if (((uintptr_t)a | (uintptr_t)b) & mask) return LC_ERR_ALIGN;
-    (void)d;
+    if ((uintptr_t)c & (c_align - 1)) return LC_ERR_ALIGN;
     if (pl.total) {
         if (!ws || ((uintptr_t)ws & 255) || ws_bytes < pl.total) return LC_ERR_WORKSPACE;
     }
@@ -216,9 +245,8 @@ extern "C" lc_status conv2d_fwd(const lc_conv_desc* d, const void* x, const void
     Plan pl;
     lc_status st = make_plan(d, LC_PASS_FWD, &pl);
     if (st != LC_OK) return st;
-    st = check_buffers(d, pl, x, w, y, workspace, workspace_bytes);
+    st = check_buffers(pl, x, w, y, pl.bf16 ? 16 : 4, workspace, workspace_bytes);
     if (st != LC_OK) return st;
-    if (((uintptr_t)y) & (uintptr_t)(pl.esize - 1)) return LC_ERR_ALIGN;
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     lc_begin_call();
 
@@ -243,7 +271,7 @@ extern "C" lc_status conv2d_fwd(const lc_conv_desc* d, const void* x, const void
     g.b = wsrc;
     g.d = ydst;
     g.partial = pl.sk_bytes ? reinterpret_cast<float*>(at(workspace, pl.sk)) : nullptr;
-    st = lc_launch_conv_gemm_f32(g, stream);
+    st = lc_launch_conv_gemm(g, stream);
     if (st != LC_OK) return st;
     if (pl.nchw) lc_nhwc_to_nchw(ydst, y, d->n, d->k, pl.P * pl.Q, pl.esize, stream);
     return lc_end_call();
@@ -254,11 +282,25 @@ extern "C" lc_status conv2d_bwd_data(const lc_conv_desc* d, const void* dy, cons
     Plan pl;
     lc_status st = make_plan(d, LC_PASS_BWD_DATA, &pl);
     if (st != LC_OK) return st;
-    st = check_buffers(d, pl, dy, w, dx, workspace, workspace_bytes);
+    st = check_buffers(pl, dy, w, dx, pl.bf16 ? 16 : 4, workspace, workspace_bytes);
     if (st != LC_OK) return st;
-    if (((uintptr_t)dx) & (uintptr_t)(pl.esize - 1)) return LC_ERR_ALIGN;
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     lc_begin_call();
+
+    if (pl.via_f32) {
+        const size_t nx = (size_t)d->n * d->h * d->w * d->c, ny = (size_t)d->n * pl.P * pl.Q * d->k;
+        const size_t nw = (size_t)d->k * d->r * d->s * d->c;
+        float* fdy = reinterpret_cast<float*>(at(workspace, pl.f_a));
+        float* fw = reinterpret_cast<float*>(at(workspace, pl.f_b));
+        float* fdx = reinterpret_cast<float*>(at(workspace, pl.f_out));
+        lc_bf16_to_f32(dy, fdy, ny, stream);
+        lc_bf16_to_f32(w, fw, nw, stream);
+        const lc_conv_desc f = as_f32(d);
+        st = conv2d_bwd_data(&f, fdy, fw, fdx, pl.f_ws_bytes ? at(workspace, pl.f_ws) : nullptr, pl.f_ws_bytes, hip_stream);
+        if (st != LC_OK) return st;
+        lc_f32_to_bf16(fdx, dx, nx, stream);
+        return lc_end_call();
+    }
 
     const void* dys = dy;
     const void* wsrc = w;
@@ -279,7 +321,7 @@ extern "C" lc_status conv2d_bwd_data(const lc_conv_desc* d, const void* dy, cons
     g.b = wt;
     g.d = dxdst;
     g.partial = pl.sk_bytes ? reinterpret_cast<float*>(at(workspace, pl.sk)) : nullptr;
-    st = lc_launch_conv_gemm_f32(g, stream);
+    st = lc_launch_conv_gemm(g, stream);
     if (st != LC_OK) return st;
     if (pl.nchw) lc_nhwc_to_nchw(dxdst, dx, d->n, d->c, d->h * d->w, pl.esize, stream);
     return lc_end_call();
@@ -290,9 +332,8 @@ extern "C" lc_status conv2d_bwd_weight(const lc_conv_desc* d, const void* x, con
     Plan pl;
     lc_status st = make_plan(d, LC_PASS_BWD_WEIGHT, &pl);
     if (st != LC_OK) return st;
-    st = check_buffers(d, pl, x, dy, dw, workspace, workspace_bytes);
+    st = check_buffers(pl, x, dy, dw, 4, workspace, workspace_bytes);
     if (st != LC_OK) return st;
-    if (((uintptr_t)dw) & 3) return LC_ERR_ALIGN;
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     lc_begin_call();
 
@@ -329,6 +370,7 @@ extern "C" lc_status conv2d_bwd_weight(const lc_conv_desc* d, const void* x, con
     g.pw = d->pad_w;
     g.splits = pl.splits;
     g.m_per_split = pl.m_per_split;
+    g.bf16 = pl.bf16;
     g.d = pl.wgrad_direct ? dwdst : reinterpret_cast<float*>(at(workspace, pl.part));
     st = lc_launch_wgrad_f32(g, stream);
     if (st != LC_OK) return st;

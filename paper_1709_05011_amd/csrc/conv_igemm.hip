@@ -48,10 +48,18 @@ __device__ __forceinline__ int xcd_tile(int bid, int total) {
 
 // Write one wave's accumulators (TM x TN tiles of 32x32) to D: plain rows, or the scatter form used by
 // the strided 1x1 backward-data pass.
-template <int TM, int TN>
+// D holds fp32, or bf16 (rounded to nearest even) when BF16OUT.
+template <bool BF16OUT> struct OutT { using type = float; static __device__ __forceinline__ float cvt(float x) { return x; } };
+template <> struct OutT<true> {
+    using type = uint16_t;
+    static __device__ __forceinline__ uint16_t cvt(float x) { return lc_bf16_rne(x); }
+};
+
+template <int TM, int TN, bool BF16OUT = false>
 __device__ __forceinline__ void store_tile(const GemmConv& p, const f32x16 (&acc)[TM][TN], int row0, int col0, int lane,
                                            int vsel = -1 /* >= 0: only accumulator register vsel of each tile */) {
-    float* __restrict__ D = static_cast<float*>(p.d);
+    using O = typename OutT<BF16OUT>::type;
+    O* __restrict__ D = static_cast<O*>(p.d);
 #pragma unroll
     for (int i = 0; i < TM; ++i)
 #pragma unroll
@@ -60,11 +68,11 @@ __device__ __forceinline__ void store_tile(const GemmConv& p, const f32x16 (&acc
             const int row = row0 + i * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
             if (row >= p.M) continue;
             if (!p.scatter) {
-                float* drow = D + (long long)row * p.ldd;
+                O* drow = D + (long long)row * p.ldd;
 #pragma unroll
                 for (int j = 0; j < TN; ++j) {
                     const int col = col0 + j * 32 + (lane & 31);
-                    if (col < p.N) drow[col] = acc[i][j][v];
+                    if (col < p.N) drow[col] = OutT<BF16OUT>::cvt(acc[i][j][v]);
                 }
             } else {
                 const int qo = row % p.Qo, t = row / p.Qo;
@@ -75,12 +83,12 @@ __device__ __forceinline__ void store_tile(const GemmConv& p, const f32x16 (&acc
                     for (int dx = 0; dx < p.esw; ++dx) {
                         const int w = qo * p.esw + dx;
                         if (w >= p.Wo) break;
-                        float* drow = D + (((long long)img * p.Ho + h) * p.Wo + w) * p.ldd;
+                        O* drow = D + (((long long)img * p.Ho + h) * p.Wo + w) * p.ldd;
                         const bool corner = (dy | dx) == 0;
 #pragma unroll
                         for (int j = 0; j < TN; ++j) {
                             const int col = col0 + j * 32 + (lane & 31);
-                            if (col < p.N) drow[col] = corner ? acc[i][j][v] : 0.f;
+                            if (col < p.N) drow[col] = OutT<BF16OUT>::cvt(corner ? acc[i][j][v] : 0.f);
                         }
                     }
                 }
@@ -264,12 +272,12 @@ __device__ __attribute__((aligned(16))) const float g_zero_chunk[4] = {0.f, 0.f,
 __device__ __forceinline__ int swz(int row) { return ((row >> 1) ^ (row >> 2)) & 3; }
 
 // ok ? a : b on pointers by bit masking: never a branch, whatever the cost of computing a
-__device__ __forceinline__ const float* pick(bool ok, const float* a, const float* b) {
+__device__ __forceinline__ const void* pick(bool ok, const void* a, const void* b) {
     const uintptr_t m = (uintptr_t)0 - (uintptr_t)ok;
-    return reinterpret_cast<const float*>((reinterpret_cast<uintptr_t>(a) & m) | (reinterpret_cast<uintptr_t>(b) & ~m));
+    return reinterpret_cast<const void*>((reinterpret_cast<uintptr_t>(a) & m) | (reinterpret_cast<uintptr_t>(b) & ~m));
 }
 // 16-byte load through the global (not flat) path: a flat load would also count as an LDS operation
-__device__ __forceinline__ float4 load_global16(const float* ptr) {
+__device__ __forceinline__ float4 load_global16(const void* ptr) {
     typedef float gf4 __attribute__((ext_vector_type(4)));
     const gf4 v = *(const __attribute__((address_space(1))) gf4*)(uintptr_t)ptr;
     return make_float4(v.x, v.y, v.z, v.w);
@@ -285,12 +293,18 @@ __device__ __forceinline__ size_t partial_index(int wave, int i, int j, int v, i
     return ((((size_t)wave * TM + i) * TN + j) * 16 + v) * 64 + lane;
 }
 
-template <int BM, int BN, bool SMALLC>
-__global__ void __launch_bounds__(256) conv_gemm_f32_sk_kernel(const GemmConv p) {
-    constexpr int BK = 16;
+// BF16: operands are bf16 (8 per 16-byte chunk, k-step 32), multiplied with v_mfma_f32_32x32x16_bf16 (lane l
+// feeds A[row l%32][k 8*(l/32) .. +7], i.e. exactly one LDS chunk per MFMA); the result is stored as bf16.
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+
+template <int BM, int BN, bool SMALLC, bool BF16>
+__global__ void __launch_bounds__(256) conv_gemm_sk_kernel(const GemmConv p) {
+    using E = typename OutT<BF16>::type;                        // operand element type
+    constexpr int EPC = BF16 ? 8 : 4;                           // elements per 16-byte chunk
+    constexpr int BK = 4 * EPC;                                 // elements per k-step: one 64-byte LDS row
     constexpr int LA = BM / 64, LB = BN / 64, LPT = LA + LB;   // 16-row blocks (= 16-byte loads) per thread and tile
     constexpr int WTM = BM / 2, WTN = BN / 2, TM = WTM / 32, TN = WTN / 32;
-    constexpr int STAGE = (BM + BN) * BK;                       // floats per LDS buffer: A rows then B rows
+    constexpr int STAGE = (BM + BN) * 16;                       // floats per LDS buffer: A rows then B rows, 64 B each
     static_assert(BM % 64 == 0 && BN % 64 == 0, "tile shape");
 
     __shared__ __attribute__((aligned(1024))) float lds[2 * STAGE];
@@ -314,8 +328,8 @@ __global__ void __launch_bounds__(256) conv_gemm_f32_sk_kernel(const GemmConv p)
     }
     const int it_begin = it;
 
-    const float* __restrict__ A = static_cast<const float*>(p.a);
-    const float* __restrict__ B = static_cast<const float*>(p.b);
+    const E* __restrict__ A = static_cast<const E*>(p.a);
+    const E* __restrict__ B = static_cast<const E*>(p.b);
     // this lane's place in a 16-row block: row lane/4, LDS slot lane%4, global chunk slot ^ swz(row)
     const int lrow = lane >> 2;
     const int kq = (lane & 3) ^ swz(lrow);
@@ -325,7 +339,7 @@ __global__ void __launch_bounds__(256) conv_gemm_f32_sk_kernel(const GemmConv p)
     // fragment addressing: lane reads row (lane & 31) of a 32-row MFMA tile, chunk 2*k8 + (lane >> 5)
     const int frow = lane & 31, fhalf = lane >> 5;
     const int fsw = swz(frow);
-    const int a_frag = (wm * WTM + frow) * BK, b_frag = BM * BK + (wn * WTN + frow) * BK;
+    const int a_frag = (wm * WTM + frow) * 16, b_frag = BM * 16 + (wn * WTN + frow) * 16;
 
     while (it < it_end) {
         const int tile = it / nkt;
@@ -357,7 +371,7 @@ __global__ void __launch_bounds__(256) conv_gemm_f32_sk_kernel(const GemmConv p)
             b_off[i] = n < p.N ? (long long)n * p.Kg : -1;
         }
         // position of this lane's 16-byte chunk inside the filter window at k-step k0
-        int kg = k0 * BK + kq * 4;
+        int kg = k0 * BK + kq * EPC;
         int c = kg % p.Ci, r, s;
         {
             const int rs = kg / p.Ci;
@@ -379,7 +393,7 @@ __global__ void __launch_bounds__(256) conv_gemm_f32_sk_kernel(const GemmConv p)
         auto advance = [&]() {
             kg += BK;
             c += BK;
-            if (SMALLC) {                         // fewer than 16 channels: a k-step spans several taps
+            if (SMALLC) {                         // fewer channels than a k-step: it spans several taps
                 while (c >= Ci_) {
                     c -= Ci_;
                     if (++s == S_) {
@@ -406,7 +420,7 @@ __global__ void __launch_bounds__(256) conv_gemm_f32_sk_kernel(const GemmConv p)
             float* base = lds + buf * STAGE + wave * 256 + lane * 4;
 #pragma unroll
             for (int l = 0; l < LPT; ++l)
-                *reinterpret_cast<float4*>(base + (l < LA ? l * 1024 : BM * BK + (l - LA) * 1024)) = g[l];
+                *reinterpret_cast<float4*>(base + (l < LA ? l * 1024 : BM * 16 + (l - LA) * 1024)) = g[l];
         };
 
         f32x16 acc[TM][TN];
@@ -422,16 +436,23 @@ __global__ void __launch_bounds__(256) conv_gemm_f32_sk_kernel(const GemmConv p)
             const float* base = lds + buf * STAGE;
             const int ch = ((2 * k8 + fhalf) ^ fsw) * 4;
 #pragma unroll
-            for (int i = 0; i < TM; ++i) fa[slot][i] = *reinterpret_cast<const float4*>(base + a_frag + i * 32 * BK + ch);
+            for (int i = 0; i < TM; ++i) fa[slot][i] = *reinterpret_cast<const float4*>(base + a_frag + i * 32 * 16 + ch);
 #pragma unroll
-            for (int j = 0; j < TN; ++j) fb[slot][j] = *reinterpret_cast<const float4*>(base + b_frag + j * 32 * BK + ch);
+            for (int j = 0; j < TN; ++j) fb[slot][j] = *reinterpret_cast<const float4*>(base + b_frag + j * 32 * 16 + ch);
         };
+        // fp32: a chunk holds k = 4 values, MFMA e of 4 consumes value e; bf16: one MFMA (e == 0) consumes the chunk
         auto mfma_e = [&](int slot, int e) {
+            if (BF16 && e != 0) return;
 #pragma unroll
             for (int i = 0; i < TM; ++i)
 #pragma unroll
-                for (int j = 0; j < TN; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(elem(fa[slot][i], e), elem(fb[slot][j], e), acc[i][j], 0, 0, 0);
+                for (int j = 0; j < TN; ++j) {
+                    if constexpr (BF16)
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, fa[slot][i]),
+                                                                            __builtin_bit_cast(bf16x8, fb[slot][j]), acc[i][j], 0, 0, 0);
+                    else
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(elem(fa[slot][i], e), elem(fb[slot][j], e), acc[i][j], 0, 0, 0);
+                }
         };
 
         gload_tile();                             // k-step k0
@@ -466,7 +487,7 @@ __global__ void __launch_bounds__(256) conv_gemm_f32_sk_kernel(const GemmConv p)
         for (int e = 0; e < 4; ++e) mfma_e(1, e);
 
         if (k0 == 0 && k1 == nkt) {
-            store_tile<TM, TN>(p, acc, m0 + wm * WTM, n0 + wn * WTN, lane);
+            store_tile<TM, TN, BF16>(p, acc, m0 + wm * WTM, n0 + wn * WTN, lane);
         } else {
             // part of a tile: first segment of this block's range -> slot 2*sk_id, last -> slot 2*sk_id + 1
             float* part = p.partial + ((size_t)2 * sk_id + (it == it_begin ? 0 : 1)) * (BM * BN);
@@ -485,9 +506,9 @@ __global__ void __launch_bounds__(256) conv_gemm_f32_sk_kernel(const GemmConv p)
 // Adds the parts of every tile that stream-K blocks split between them, in k order, and stores the tile.
 // Block (t, v) handles accumulator register v of every 32x32 MFMA tile of stream-K tile t, with the thread
 // geometry of the main kernel: 16 blocks per tile keep the whole chip busy on what is a small reduction.
-template <int BM, int BN>
-__global__ void __launch_bounds__(256) conv_gemm_f32_fixup_kernel(const GemmConv p) {
-    constexpr int BK = 16, TM = BM / 64, TN = BN / 64;
+template <int BM, int BN, bool BF16>
+__global__ void __launch_bounds__(256) conv_gemm_fixup_kernel(const GemmConv p) {
+    constexpr int BK = BF16 ? 32 : 16, TM = BM / 64, TN = BN / 64;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int wm = wave >> 1, wn = wave & 1;
     const int v = blockIdx.y;
@@ -523,7 +544,7 @@ __global__ void __launch_bounds__(256) conv_gemm_f32_fixup_kernel(const GemmConv
             for (int u = 0; u < 16; ++u) out[i][jj][u] = acc[i][jj][0];
     const int tile = p.dp_tiles + blockIdx.x;
     const int m0 = (tile / nbn) * BM, n0 = (tile % nbn) * BN;
-    store_tile<TM, TN>(p, out, m0 + wm * (BM / 2), n0 + wn * (BN / 2), lane, v);
+    store_tile<TM, TN, BF16>(p, out, m0 + wm * (BM / 2), n0 + wn * (BN / 2), lane, v);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -531,8 +552,23 @@ __global__ void __launch_bounds__(256) conv_gemm_f32_fixup_kernel(const GemmConv
 // reduction index m strides over rows.  LDS holds [reduction][row] so that the row-contiguous
 // global vectors are stored as they arrive and MFMA fragments are read with unit lane stride.
 // ------------------------------------------------------------------------------------------------
-template <int BM, int BN, int BK, int WGM, int WGN, int VEC>
+// VEC operand elements from global memory as fp32 (bf16 is widened exactly)
+template <int VEC, bool BF16>
+__device__ __forceinline__ typename VecT<VEC>::type load_widen(const void* ptr) {
+    if constexpr (!BF16) {
+        return *static_cast<const typename VecT<VEC>::type*>(ptr);
+    } else if constexpr (VEC == 4) {
+        const uint2 u = *static_cast<const uint2*>(ptr);
+        return make_float4(__uint_as_float(u.x << 16), __uint_as_float(u.x & 0xffff0000u), __uint_as_float(u.y << 16),
+                           __uint_as_float(u.y & 0xffff0000u));
+    } else {
+        return __uint_as_float((uint32_t)*static_cast<const uint16_t*>(ptr) << 16);
+    }
+}
+
+template <int BM, int BN, int BK, int WGM, int WGN, int VEC, bool BF16>
 __global__ void __launch_bounds__(WGM* WGN * 64) wgrad_f32_kernel(const GemmWgrad p) {
+    using E = typename OutT<BF16>::type;              // operand element type
     constexpr int T = WGM * WGN * 64;
     constexpr int AQ = BM / VEC, BQ = BN / VEC;       // vectors per reduction row
     constexpr int ARPP = T / AQ, BRPP = T / BQ;       // reduction rows per pass
@@ -555,8 +591,8 @@ __global__ void __launch_bounds__(WGM* WGN * 64) wgrad_f32_kernel(const GemmWgra
     const int m_begin = z * p.m_per_split;
     const int m_end = min(p.M, m_begin + p.m_per_split);
 
-    const float* __restrict__ DY = static_cast<const float*>(p.dy);
-    const float* __restrict__ X = static_cast<const float*>(p.x);
+    const E* __restrict__ DY = static_cast<const E*>(p.dy);
+    const E* __restrict__ X = static_cast<const E*>(p.x);
 
     // dY tile: column (output channel) fixed per thread
     const int a_cq = tid % AQ, a_kr = tid / AQ;
@@ -590,15 +626,14 @@ __global__ void __launch_bounds__(WGM* WGN * 64) wgrad_f32_kernel(const GemmWgra
 #pragma unroll
         for (int i = 0; i < LA; ++i) {
             const int m = mt + a_kr + i * ARPP;
-            ra[i] = (a_ok && m < m_end) ? *reinterpret_cast<const V*>(DY + (long long)m * p.K + a_col) : VecT<VEC>::zero();
+            ra[i] = (a_ok && m < m_end) ? load_widen<VEC, BF16>(DY + (long long)m * p.K + a_col) : VecT<VEC>::zero();
         }
 #pragma unroll
         for (int i = 0; i < LB; ++i) {
             const int m = mt + b_kr + i * BRPP;
             const int h = b_p[i] * p.sh - p.ph + fr, w = b_q[i] * p.sw - p.pw + fs;
             const bool ok = b_ok && m < m_end && h >= 0 && h < p.H && w >= 0 && w < p.W;
-            rb[i] = ok ? *reinterpret_cast<const V*>(X + (((long long)b_img[i] * p.H + h) * p.W + w) * p.C + fc)
-                       : VecT<VEC>::zero();
+            rb[i] = ok ? load_widen<VEC, BF16>(X + (((long long)b_img[i] * p.H + h) * p.W + w) * p.C + fc) : VecT<VEC>::zero();
         }
     };
     auto advance = [&]() {
@@ -692,11 +727,11 @@ lc_status launch_conv(const GemmConv& p, hipStream_t stream) {
     return lc_end_call();
 }
 
-template <int BM, int BN, int BK, int VEC>
+template <int BM, int BN, int BK, int VEC, bool BF16>
 lc_status launch_wgrad(const GemmWgrad& p, hipStream_t stream) {
     const long long tiles = (long long)((p.K + BM - 1) / BM) * ((p.J + BN - 1) / BN);
     if (tiles <= 0 || tiles > 0x7fffffffLL || p.splits > 65535) return LC_ERR_UNSUPPORTED;
-    hipLaunchKernelGGL((wgrad_f32_kernel<BM, BN, BK, 2, 2, VEC>), dim3((unsigned)tiles, (unsigned)p.splits), dim3(256), 0,
+    hipLaunchKernelGGL((wgrad_f32_kernel<BM, BN, BK, 2, 2, VEC, BF16>), dim3((unsigned)tiles, (unsigned)p.splits), dim3(256), 0,
                        stream, p);
     return lc_end_call();
 }
@@ -744,12 +779,13 @@ inline int resident_blocks() { return 3 * device_cu_count(); }
 
 template <int BM, int BN>
 bool sk_geometry(const GemmConv& p, long long* tiles, int* nkt) {
+    const int bk = p.bf16 ? 32 : 16;
     *tiles = (long long)((p.M + BM - 1) / BM) * ((p.N + BN - 1) / BN);
-    *nkt = (p.Kg + 15) / 16;
+    *nkt = (p.Kg + bk - 1) / bk;
     return *tiles > 0 && *tiles * *nkt < 0x7fffffffLL;
 }
 
-template <int BM, int BN, bool SMALLC>
+template <int BM, int BN, bool SMALLC, bool BF16>
 lc_status launch_conv_sk(GemmConv p, hipStream_t stream) {
     long long tiles;
     int nkt;
@@ -763,10 +799,10 @@ lc_status launch_conv_sk(GemmConv p, hipStream_t stream) {
     p.dp_tiles = pl.dp_tiles;
     p.sk_blocks = pl.sk_blocks;
     p.sk_iters = pl.sk_iters;
-    hipLaunchKernelGGL((conv_gemm_f32_sk_kernel<BM, BN, SMALLC>), dim3((unsigned)(pl.dp_tiles + pl.sk_blocks)), dim3(256), 0,
+    hipLaunchKernelGGL((conv_gemm_sk_kernel<BM, BN, SMALLC, BF16>), dim3((unsigned)(pl.dp_tiles + pl.sk_blocks)), dim3(256), 0,
                        stream, p);
     if (pl.sk_blocks > 0)
-        hipLaunchKernelGGL((conv_gemm_f32_fixup_kernel<BM, BN>), dim3((unsigned)(tiles - pl.dp_tiles), 16), dim3(256), 0, stream, p);
+        hipLaunchKernelGGL((conv_gemm_fixup_kernel<BM, BN, BF16>), dim3((unsigned)(tiles - pl.dp_tiles), 16), dim3(256), 0, stream, p);
     return lc_end_call();
 }
 
@@ -775,8 +811,8 @@ inline bool use_main_kernel(const GemmConv& p) {
         const char* e = getenv("LARSCONV_KERNEL");          // LARSCONV_KERNEL=classic: comparison runs
         return e && strcmp(e, "classic") == 0;
     }();
-    const bool vec = (p.Ci % 4 == 0) && aligned16(p.a) && aligned16(p.b);
-    return vec && !(p.dh > 1 || p.dw > 1) && !classic;
+    const bool vec = (p.Ci % (p.bf16 ? 8 : 4) == 0) && aligned16(p.a) && aligned16(p.b);
+    return vec && !(p.dh > 1 || p.dw > 1) && !(classic && !p.bf16);
 }
 
 }  // namespace
@@ -791,12 +827,19 @@ size_t lc_conv_gemm_workspace(const GemmConv& p) {
     return (size_t)2 * pl.sk_blocks * 128 * (wide ? 128 : 64) * sizeof(float);
 }
 
-lc_status lc_launch_conv_gemm_f32(const GemmConv& p, hipStream_t stream) {
+bool lc_conv_gemm_bf16_native(const GemmConv& p) { return p.bf16 && use_main_kernel(p); }
+
+lc_status lc_launch_conv_gemm(const GemmConv& p, hipStream_t stream) {
+    if (p.bf16) {
+        if (!use_main_kernel(p)) return LC_ERR_UNSUPPORTED;       // the caller converts to fp32 instead
+        if (p.Ci < 32) return p.N > 64 ? launch_conv_sk<128, 128, true, true>(p, stream) : launch_conv_sk<128, 64, true, true>(p, stream);
+        return p.N > 64 ? launch_conv_sk<128, 128, false, true>(p, stream) : launch_conv_sk<128, 64, false, true>(p, stream);
+    }
     const bool vec = (p.Ci % 4 == 0) && aligned16(p.a) && aligned16(p.b);
     if (!vec) return launch_conv<64, 64, 16, 1>(p, stream);
     if (use_main_kernel(p)) {
-        if (p.Ci < 16) return p.N > 64 ? launch_conv_sk<128, 128, true>(p, stream) : launch_conv_sk<128, 64, true>(p, stream);
-        return p.N > 64 ? launch_conv_sk<128, 128, false>(p, stream) : launch_conv_sk<128, 64, false>(p, stream);
+        if (p.Ci < 16) return p.N > 64 ? launch_conv_sk<128, 128, true, false>(p, stream) : launch_conv_sk<128, 64, true, false>(p, stream);
+        return p.N > 64 ? launch_conv_sk<128, 128, false, false>(p, stream) : launch_conv_sk<128, 64, false, false>(p, stream);
     }
     if (p.N > 64) return launch_conv<128, 128, 16, 4>(p, stream);
     return launch_conv<128, 64, 16, 4>(p, stream);
@@ -824,13 +867,20 @@ int lc_wgrad_splits(int M, int K, int J) {
     return (int)want;
 }
 
-lc_status lc_launch_wgrad_f32(const GemmWgrad& p, hipStream_t stream) {
-    const bool vec = (p.C % 4 == 0) && (p.K % 4 == 0) && aligned16(p.dy) && aligned16(p.x);
+template <bool BF16>
+static lc_status dispatch_wgrad(const GemmWgrad& p, hipStream_t stream) {
+    // vector path: 4 elements per load (16 bytes fp32, 8 bytes bf16)
+    const uintptr_t amask = BF16 ? 7 : 15;
+    const bool vec = (p.C % 4 == 0) && (p.K % 4 == 0) && !(((uintptr_t)p.dy | (uintptr_t)p.x) & amask);
     int bm, bn;
     wgrad_tile(p.K, p.J, &bm, &bn);
-    if (!vec) return launch_wgrad<64, 64, 16, 1>(p, stream);
-    if (bm == 128 && bn == 128) return launch_wgrad<128, 128, 16, 4>(p, stream);
-    if (bm == 128) return launch_wgrad<128, 64, 16, 4>(p, stream);
-    if (bn == 128) return launch_wgrad<64, 128, 16, 4>(p, stream);
-    return launch_wgrad<64, 64, 16, 4>(p, stream);
+    if (!vec) return launch_wgrad<64, 64, 16, 1, BF16>(p, stream);
+    if (bm == 128 && bn == 128) return launch_wgrad<128, 128, 16, 4, BF16>(p, stream);
+    if (bm == 128) return launch_wgrad<128, 64, 16, 4, BF16>(p, stream);
+    if (bn == 128) return launch_wgrad<64, 128, 16, 4, BF16>(p, stream);
+    return launch_wgrad<64, 64, 16, 4, BF16>(p, stream);
+}
+
+lc_status lc_launch_wgrad_f32(const GemmWgrad& p, hipStream_t stream) {
+    return p.bf16 ? dispatch_wgrad<true>(p, stream) : dispatch_wgrad<false>(p, stream);
 }

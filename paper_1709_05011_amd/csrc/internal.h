@@ -12,7 +12,16 @@
 void lc_begin_call();
 lc_status lc_end_call();     // LC_OK, or LC_ERR_LAUNCH with the detail text recorded
 
+// fp32 -> bf16, round to nearest even (NaN stays NaN)
+__device__ __forceinline__ uint16_t lc_bf16_rne(float x) {
+    const uint32_t u = __float_as_uint(x);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40u);
+    return (uint16_t)((u + 0x7fffu + ((u >> 16) & 1u)) >> 16);
+}
+
 // ---- small device-side utilities (layout.hip) ----
+void lc_bf16_to_f32(const void* src, float* dst, size_t count, hipStream_t stream);
+void lc_f32_to_bf16(const float* src, void* dst, size_t count, hipStream_t stream);
 void lc_fill_f32(float* dst, float value, size_t count, hipStream_t stream);
 void lc_fill_u32x4(void* dst, size_t bytes16, hipStream_t stream);   // zero `bytes16` * 16 bytes
 
@@ -52,8 +61,10 @@ struct GemmConv {
     int dp_tiles, sk_blocks;
     long long sk_iters;
     float* partial;
+    int bf16;           // operands a, b and result d are bf16 (sums stay fp32)
 };
-lc_status lc_launch_conv_gemm_f32(const GemmConv& p, hipStream_t stream);
+lc_status lc_launch_conv_gemm(const GemmConv& p, hipStream_t stream);
+bool lc_conv_gemm_bf16_native(const GemmConv& p);   // can the bf16 MFMA kernel take this problem (shape and alignment)?
 size_t lc_conv_gemm_workspace(const GemmConv& p);   // bytes `partial` must hold for this problem (0 = none)
 
 // Filter gradient: D[k][j] = sum_m dY[m][k] * Xg(m, j), m = (img, p, q), j = (r, s, c); the reduction
@@ -66,6 +77,7 @@ struct GemmWgrad {
     int H, W, C, P, Q, R, S;
     int sh, sw, ph, pw;
     int splits, m_per_split;
+    int bf16;           // dy and x are bf16 (widened on the fly; the sums and d stay fp32)
 };
 lc_status lc_launch_wgrad_f32(const GemmWgrad& p, hipStream_t stream);
 int lc_wgrad_splits(int M, int K, int J);   // fixed function of the shape (determinism)

@@ -141,12 +141,6 @@ lars_finalize_kernel(LarsWorkspace ws, float eta, float weight_decay, float lr, 
     }
 }
 
-__device__ __forceinline__ uint16_t bf16_rne(float x) {
-    const uint32_t u = __float_as_uint(x);
-    if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40u);   // NaN stays NaN
-    return (uint16_t)((u + 0x7fffu + ((u >> 16) & 1u)) >> 16);
-}
-
 __global__ void __launch_bounds__(kThreads)
 lars_update_kernel(LarsWorkspace ws, int n_chunks, float momentum, float weight_decay) {
     const int chunk = n_chunks - 1 - (int)blockIdx.x;
@@ -185,10 +179,10 @@ lars_update_kernel(LarsWorkspace ws, int n_chunks, float momentum, float weight_
             reinterpret_cast<float4*>(w)[threadIdx.x + i * kThreads] = nw;
             if (lp) {
                 ushort4 h;
-                h.x = bf16_rne(nw.x);
-                h.y = bf16_rne(nw.y);
-                h.z = bf16_rne(nw.z);
-                h.w = bf16_rne(nw.w);
+                h.x = lc_bf16_rne(nw.x);
+                h.y = lc_bf16_rne(nw.y);
+                h.z = lc_bf16_rne(nw.z);
+                h.w = lc_bf16_rne(nw.w);
                 reinterpret_cast<ushort4*>(lp)[threadIdx.x + i * kThreads] = h;
             }
         }
@@ -199,7 +193,7 @@ lars_update_kernel(LarsWorkspace ws, int n_chunks, float momentum, float weight_
             const float nw = x - nv;
             v[i] = nv;
             w[i] = nw;
-            if (lp) lp[i] = bf16_rne(nw);
+            if (lp) lp[i] = lc_bf16_rne(nw);
         }
     }
 }

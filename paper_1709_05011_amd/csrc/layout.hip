@@ -122,7 +122,28 @@ __global__ void __launch_bounds__(256) reduce_splits_kernel(const float* __restr
     }
 }
 
+__global__ void bf16_to_f32_kernel(const uint16_t* __restrict__ src, float* __restrict__ dst, size_t count) {
+    for (size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x; i < count; i += (size_t)gridDim.x * blockDim.x)
+        dst[i] = __uint_as_float((uint32_t)src[i] << 16);
+}
+
+__global__ void f32_to_bf16_kernel(const float* __restrict__ src, uint16_t* __restrict__ dst, size_t count) {
+    for (size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x; i < count; i += (size_t)gridDim.x * blockDim.x)
+        dst[i] = lc_bf16_rne(src[i]);
+}
+
 }  // namespace
+
+void lc_bf16_to_f32(const void* src, float* dst, size_t count, hipStream_t stream) {
+    if (!count) return;
+    hipLaunchKernelGGL(bf16_to_f32_kernel, dim3(grid_for(count, 256)), dim3(256), 0, stream, static_cast<const uint16_t*>(src), dst,
+                       count);
+}
+
+void lc_f32_to_bf16(const float* src, void* dst, size_t count, hipStream_t stream) {
+    if (!count) return;
+    hipLaunchKernelGGL(f32_to_bf16_kernel, dim3(grid_for(count, 256)), dim3(256), 0, stream, src, static_cast<uint16_t*>(dst), count);
+}
 
 void lc_fill_f32(float* dst, float value, size_t count, hipStream_t stream) {
     if (!count) return;

@@ -1,0 +1,96 @@
+"""GPU parity for bf16 operands (fp32 accumulation): inputs are drawn in fp32, rounded once to bf16 on the
+host, and those exact values feed both sides.  The oracle sums in double; its result is rounded to bf16 for
+the comparison with y / dx (bf16 outputs) and left unrounded for dw (fp32 output).
+Tolerances: y, dx  max |gpu - oracle| / max |oracle| <= 2e-2 (one bf16 ulp is 2^-8 = 3.9e-3 relative);
+dw <= 1e-4 as for fp32 operands (the products of bf16 values are exact in fp32, only the sums round)."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_1709_05011_amd import larsconv as lc
+from paper_1709_05011_amd import synth
+
+import gpu_util as gu
+
+pytestmark = pytest.mark.gpu
+TOL_BF16, TOL_DW = 2e-2, 1e-4
+
+SHAPES = {
+    "3x3_multi_tile": (2, 64, 14, 14, 96, 3, 3, 1, 1),
+    "3x3_wide": (3, 32, 10, 12, 160, 3, 3, 1, 1),
+    "1x1_plain": (3, 256, 7, 7, 512, 1, 1, 1, 0),
+    "1x1_stride2_odd": (2, 64, 15, 15, 128, 1, 1, 2, 0),
+    "stem_7x7_s2": (2, 3, 30, 30, 64, 7, 7, 2, 3),            # c padded to 8; backward-data through fp32
+    "5x5_p2": (2, 16, 13, 13, 32, 5, 5, 1, 2),
+    "3x3_stride2": (2, 32, 17, 17, 48, 3, 3, 2, 1),           # strided window: backward-data through fp32
+    "odd_channels": (2, 6, 9, 9, 10, 3, 3, 1, 1),             # k = 10: backward-data through fp32, scalar filter gradient
+    "k8_c24": (2, 24, 9, 9, 8, 3, 3, 1, 1),
+    "full_window_fc": (4, 16, 6, 6, 40, 6, 6, 1, 0),
+    "single_everything": (1, 1, 5, 5, 1, 1, 1, 1, 0),
+    "fc_1x1_on_1x1": (16, 512, 1, 1, 104, 1, 1, 1, 0),
+    "resnet_28_stage": (8, 128, 28, 28, 128, 3, 3, 1, 1),
+}
+
+
+def _bf16_inputs(shape, seed):
+    n, c, h, w, k, r, s, stride, pad = shape
+    p, q = oracle.out_shape(h, w, r, s, stride, pad)
+    raw = (synth.normal((n, c, h, w), seed), synth.normal((k, c, r, s), seed + 1, std=float(np.sqrt(2.0 / (c * r * s)))),
+           synth.normal((n, k, p, q), seed + 2))
+    bits = [synth.to_bf16_bits(a) for a in raw]
+    vals = [synth.bf16_bits_to_f32(b) for b in bits]         # what both sides compute with
+    return bits, vals
+
+
+def _dev_bf16(bits_l):
+    return torch.from_numpy(np.ascontiguousarray(bits_l).view(np.int16)).to(gu.DEV)
+
+
+def _back(t):
+    return synth.bf16_bits_to_f32(t.cpu().numpy().view(np.uint16))
+
+
+@pytest.mark.parametrize("layout", [lc.LC_NHWC, lc.LC_NCHW], ids=["nhwc", "nchw"])
+@pytest.mark.parametrize("name", list(SHAPES))
+def test_three_passes_match_oracle_bf16(name, layout):
+    shape = SHAPES[name]
+    n, c, h, w, k, r, s, stride, pad = shape
+    (xb, wb, dyb), (x, wt, dy) = _bf16_inputs(shape, 5000 + 10 * list(SHAPES).index(name))
+    d = gu.desc_for(x.shape, wt.shape, stride, pad, layout, lc.LC_BF16)
+    print(f"bf16 case {name} layout {layout} desc {d}", flush=True)
+    p, q = lc.conv2d_out_shape(d)
+    xd, wd, dyd = (_dev_bf16(gu.to_layout(a, layout)) for a in (xb, wb, dyb))
+
+    yshape = (n, k, p, q) if layout == lc.LC_NCHW else (n, p, q, k)
+    y = torch.full(yshape, -1, dtype=torch.int16, device=gu.DEV)
+    lc.conv2d_fwd(d, xd, wd, y, gu.workspace(lc.conv2d_workspace_bytes(d, lc.LC_PASS_FWD)))
+    xshape = (n, c, h, w) if layout == lc.LC_NCHW else (n, h, w, c)
+    dx = torch.full(xshape, -1, dtype=torch.int16, device=gu.DEV)
+    lc.conv2d_bwd_data(d, dyd, wd, dx, gu.workspace(lc.conv2d_workspace_bytes(d, lc.LC_PASS_BWD_DATA)))
+    wshape = (k, c, r, s) if layout == lc.LC_NCHW else (k, r, s, c)
+    dw = torch.full(wshape, float("nan"), dtype=torch.float32, device=gu.DEV)
+    lc.conv2d_bwd_weight(d, xd, dyd, dw, gu.workspace(lc.conv2d_workspace_bytes(d, lc.LC_PASS_BWD_WEIGHT)))
+    torch.cuda.synchronize()
+
+    ref_y = oracle.conv2d_fwd(x, wt, stride, pad)
+    ref_dx = oracle.conv2d_bwd_data(dy, wt, (h, w), stride, pad)
+    ref_dw = oracle.conv2d_bwd_weight(x, dy, (r, s), stride, pad)
+    got_y = gu.from_layout(_back(y), layout)
+    got_dx = gu.from_layout(_back(dx), layout)
+    assert gu.scaled_err(got_y, oracle.round_to_bf16(ref_y)) <= TOL_BF16
+    assert gu.scaled_err(got_dx, oracle.round_to_bf16(ref_dx)) <= TOL_BF16
+    # tighter: at most one bf16 step away from the exact result, element by element
+    assert np.all(np.abs(got_y - ref_y) <= np.abs(ref_y) * 2.0 ** -7 + 1e-6 * np.max(np.abs(ref_y)))
+    assert np.all(np.abs(got_dx - ref_dx) <= np.abs(ref_dx) * 2.0 ** -7 + 1e-6 * max(np.max(np.abs(ref_dx)), 1e-30))
+    assert gu.scaled_err(gu.from_layout(dw.cpu().numpy(), layout), ref_dw) <= TOL_DW
+
+
+def test_bf16_tensors_need_16_byte_alignment():
+    d = lc.ConvDesc(2, 16, 9, 9, 24, 3, 3, 1, 1, 1, 1, lc.LC_BF16, lc.LC_NHWC)
+    buf = torch.zeros(1 << 16, dtype=torch.int16, device=gu.DEV)
+    y = torch.zeros(2 * 9 * 9 * 24, dtype=torch.int16, device=gu.DEV)
+    ws = gu.workspace(lc.conv2d_workspace_bytes(d, lc.LC_PASS_FWD))
+    with pytest.raises(lc.LarsConvError) as e:
+        lc.conv2d_fwd(d, buf[1:], buf[8192:], y, ws)
+    assert e.value.status == lc.LC_ERR_ALIGN
