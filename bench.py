@@ -25,6 +25,7 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 PEAK_MFMA_F32 = 157.3      # TFLOP/s, MI355X dense fp32 matrix
+PEAK_MFMA_BF16 = 2500.0    # TFLOP/s, MI355X dense bf16 matrix
 PEAK_HBM = 8000.0          # GB/s
 LARS_BYTES_PER_PARAM = 28  # norm pass reads w, g (8 B); update reads w, g, v and writes w, v (20 B)
 # HBM-side bytes per launch of the dominant kernel in the default workload, from the two rocprofv3 --pmc runs
@@ -40,18 +41,20 @@ def log(*a):
 class Layer:
     """Device buffers and descriptor of one convolution of the workload."""
 
-    def __init__(self, cs, gen, torch, lc, first: bool):
+    def __init__(self, cs, gen, torch, lc, first: bool, bf16: bool = False):
         dev = "cuda:0"
         self.cs = cs
         self.first = first
         self.desc = lc.ConvDesc(cs.n, cs.c, cs.h, cs.w, cs.k, cs.r, cs.s, cs.stride, cs.stride, cs.pad, cs.pad,
-                                lc.LC_F32, lc.LC_NHWC)
+                                lc.LC_BF16 if bf16 else lc.LC_F32, lc.LC_NHWC)
         std = (2.0 / (cs.c * cs.r * cs.s)) ** 0.5
-        self.x = torch.randn((cs.n, cs.h, cs.w, cs.c), generator=gen, device=dev)
-        self.w = torch.randn((cs.k, cs.r, cs.s, cs.c), generator=gen, device=dev) * std
-        self.dy = torch.randn((cs.n, cs.p, cs.q, cs.k), generator=gen, device=dev)
-        self.y = torch.empty((cs.n, cs.p, cs.q, cs.k), device=dev)
-        self.dx = None if first else torch.empty((cs.n, cs.h, cs.w, cs.c), device=dev)
+        act = torch.bfloat16 if bf16 else torch.float32
+        self.x = torch.randn((cs.n, cs.h, cs.w, cs.c), generator=gen, device=dev).to(act)
+        self.w_master = torch.randn((cs.k, cs.r, cs.s, cs.c), generator=gen, device=dev) * std   # fp32 weights
+        self.w = self.w_master.to(act) if bf16 else self.w_master                                # what the convolutions read
+        self.dy = torch.randn((cs.n, cs.p, cs.q, cs.k), generator=gen, device=dev).to(act)
+        self.y = torch.empty((cs.n, cs.p, cs.q, cs.k), device=dev, dtype=act)
+        self.dx = None if first else torch.empty((cs.n, cs.h, cs.w, cs.c), device=dev, dtype=act)
         self.dw = torch.empty((cs.k, cs.r, cs.s, cs.c), device=dev)
         self.ws_bytes = max(lc.conv2d_workspace_bytes(self.desc, p) for p in range(3))
 
@@ -97,24 +100,28 @@ def run_resnet50_step(args):
     from paper_1709_05011_amd import synth
 
     lc.lib()
-    batch = args.batch or 256
+    bf16 = args.dtype == "bf16"
+    batch = args.batch or (512 if bf16 else 256)
     gen = torch.Generator(device="cuda:0")
     gen.manual_seed(0x5EED0300)
     shapes = synth.resnet50_convs(batch) + [synth.resnet50_fc(batch)]
-    layers = [Layer(cs, gen, torch, lc, i == 0) for i, cs in enumerate(shapes)]
+    layers = [Layer(cs, gen, torch, lc, i == 0, bf16) for i, cs in enumerate(shapes)]
     ws = make_workspace(max(l.ws_bytes for l in layers), torch)
 
     # the 161 parameter tensors: filter, batch-norm scale, batch-norm shift per conv; classifier weight, bias
-    pw, pg, pv = [], [], []
+    pw, pg, pv, plow = [], [], [], []
     for l in layers[:-1]:
         k = l.cs.k
-        pw += [l.w, torch.ones(k, device="cuda:0"), torch.zeros(k, device="cuda:0")]
+        pw += [l.w_master, torch.ones(k, device="cuda:0"), torch.zeros(k, device="cuda:0")]
+        plow += [l.w, None, None]
         pg += [l.dw, torch.randn(k, generator=gen, device="cuda:0") * 1e-2,
                torch.randn(k, generator=gen, device="cuda:0") * 1e-2]
-    pw += [layers[-1].w, torch.zeros(1000, device="cuda:0")]
+    pw += [layers[-1].w_master, torch.zeros(1000, device="cuda:0")]
+    plow += [layers[-1].w, None]
     pg += [layers[-1].dw, torch.randn(1000, generator=gen, device="cuda:0") * 1e-2]
     pv = [torch.zeros_like(t) for t in pw]
-    largs = lc.LarsArgs(pw, pg, pv)
+    # bf16 run: fp32 master weights and momentum; lars_step also writes the bf16 weights the convolutions read
+    largs = lc.LarsArgs(pw, pg, pv, w_lowp=plow if bf16 else None)
     assert largs.n == 161 and sum(largs.numel) == 25_557_032
     lws = make_workspace(lc.lars_workspace_bytes(largs.numel), torch)
     trust = torch.empty(largs.n, device="cuda:0")
@@ -163,10 +170,13 @@ def run_resnet50_step(args):
     conv_ms = sum(per_pass[p][0] for p in ("fwd", "bwd_data", "bwd_weight"))
     conv_flops = sum(per_pass[p][2] for p in ("fwd", "bwd_data", "bwd_weight"))
     lars_ms = per_pass["lars"][0] / per_pass["lars"][1]
-    lars_gbps = LARS_BYTES_PER_PARAM * sum(largs.numel) / (lars_ms * 1e-3) / 1e9
+    lars_bpp = LARS_BYTES_PER_PARAM + (2 if bf16 else 0)       # + the bf16 copy of the filters (an upper bound: not the BN tensors)
+    lars_gbps = lars_bpp * sum(largs.numel) / (lars_ms * 1e-3) / 1e9
     dom = max((k for k in per_kernel if k != "lars"), key=lambda k: per_kernel[k][0])
     dms, dn, dfl = per_kernel[dom]
     achieved = dfl / (dms * 1e-3) / 1e12
+    # bf16: forward and backward-data run on the bf16 matrix pipe; the filter gradient still multiplies in fp32
+    peak = (PEAK_MFMA_F32 if dom == "wgrad" else PEAK_MFMA_BF16) if bf16 else PEAK_MFMA_F32
     result = {
         "metric": "ResNet-50 fwd+bwd+LARS images/sec/GPU",
         "value": round(batch / (ms_per_step * 1e-3), 2),
@@ -178,20 +188,21 @@ def run_resnet50_step(args):
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
-        "dtype": "f32",
+        "dtype": "bf16" if bf16 else "f32",
         "data": "synthetic",
-        "config": {"workload": f"resnet50_train_step_fp32_batch{batch}_nhwc (53 convs + fc: fwd, bwd_data, bwd_weight; "
+        "config": {"workload": f"resnet50_train_step_{'bf16' if bf16 else 'fp32'}_batch{batch}_nhwc (53 convs + fc: fwd, bwd_data, bwd_weight; "
                                "lars_step over 161 tensors / 25.6M params)",
                    "batch": batch, "layout": "NHWC", "lars": {"eta": 0.001, "momentum": 0.9, "weight_decay": 5e-5, "lr": lr}},
-        "roofline": {"bound": "mfma", "kernel": dom, "achieved": round(achieved, 2), "peak": PEAK_MFMA_F32,
-                     "unit": "TFLOP/s", "frac": round(achieved / PEAK_MFMA_F32, 4), "traffic": MEASURED_TRAFFIC.get((dom, batch)),
+        "roofline": {"bound": "mfma", "kernel": dom, "achieved": round(achieved, 2), "peak": peak,
+                     "unit": "TFLOP/s", "frac": round(achieved / peak, 4),
+                     "traffic": None if bf16 else MEASURED_TRAFFIC.get((dom, batch)),
                      "launches_per_step": dn // args.steps, "avg_launch_ms": round(dms / dn, 4),
                      "flops_per_launch": dfl / dn},
         "conv_tflops": {p: round(per_pass[p][2] / (per_pass[p][0] * 1e-3) / 1e12, 2) for p in ("fwd", "bwd_data", "bwd_weight")},
         "conv_tflops_all": round(conv_flops / (conv_ms * 1e-3) / 1e12, 2),
-        "conv_frac_of_mfma_peak": round(conv_flops / (conv_ms * 1e-3) / 1e12 / PEAK_MFMA_F32, 4),
+        "conv_frac_of_mfma_peak": round(conv_flops / (conv_ms * 1e-3) / 1e12 / peak, 4),
         "lars": {"ms": round(lars_ms, 4), "GBps": round(lars_gbps, 1), "frac_of_hbm_peak": round(lars_gbps / PEAK_HBM, 4),
-                 "bytes_per_param": LARS_BYTES_PER_PARAM},
+                 "bytes_per_param": lars_bpp},
         "kernel_ms_per_step": {k: round(v[0] / args.steps, 3) for k, v in per_kernel.items()},
     }
     if not args.no_cpu:
@@ -267,7 +278,7 @@ def run_sweep(args):
     for idx, (cs, count) in enumerate(synth.resnet50_distinct_shapes(batch), start=1):
         if args.only and idx not in args.only:
             continue
-        l = Layer(cs, gen, torch, lc, False)
+        l = Layer(cs, gen, torch, lc, False, args.dtype == "bf16")
         ws = make_workspace(l.ws_bytes, torch)
         calls = {
             "fwd": lambda: lc.conv2d_fwd(l.desc, l.x, l.w, l.y, ws),
@@ -289,7 +300,7 @@ def run_sweep(args):
     summary = {p: round(v[1] / (v[0] * 1e-3) / 1e12, 2) for p, v in tot.items() if v[0] > 0}
     all_ms = sum(v[0] for v in tot.values())
     all_fl = sum(v[1] for v in tot.values())
-    return {"sweep": "resnet50_distinct_conv_shapes", "batch": batch, "dtype": "f32", "layout": "NHWC",
+    return {"sweep": "resnet50_distinct_conv_shapes", "batch": batch, "dtype": args.dtype, "layout": "NHWC",
             "weighted_tflops": summary, "weighted_tflops_all": round(all_fl / (all_ms * 1e-3) / 1e12, 2),
             "frac_of_mfma_peak": round(all_fl / (all_ms * 1e-3) / 1e12 / PEAK_MFMA_F32, 4), "rows": rows}
 
@@ -346,6 +357,8 @@ def main():
     ap.add_argument("--steps", type=int, default=5)
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--batch", type=int, default=0)
+    ap.add_argument("--dtype", choices=["f32", "bf16"], default="f32",
+                    help="bf16: BASELINE configs[4] (bf16 activations/weights, fp32 sums, fp32 master weights; batch 512)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
     ap.add_argument("--cpu-batch", type=int, default=4)
     ap.add_argument("--sweep", action="store_true")
