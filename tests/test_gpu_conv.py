@@ -155,3 +155,68 @@ def test_full_size_sampled_outputs_and_adjoint(name):
     b = float(np.sum(wt.astype(np.float64) * dw))
     scale = float(np.sqrt(np.sum(y.astype(np.float64) ** 2) * np.sum(dy.astype(np.float64) ** 2)))
     assert abs(lhs - a) <= 1e-5 * scale and abs(lhs - b) <= 1e-5 * scale
+
+
+# ---- AlexNet-BN layer shapes at batch 256 (five convolutions, three FC layers as convolutions) ----
+ALEX = {c.name: c for c in synth.alexnet_bn_convs(256)}
+
+
+@pytest.mark.parametrize("name", list(ALEX))
+def test_alexnet_bn_layers_full_size_sampled(name):
+    cs = ALEX[name]
+    seed = 4000 + 10 * list(ALEX).index(name)
+    print(f"alexnet layer {name}: {cs}", flush=True)
+    x = synth.normal((cs.n, cs.h, cs.w, cs.c), seed)
+    wt = synth.normal((cs.k, cs.r, cs.s, cs.c), seed + 1, std=synth.he_std(cs))
+    dy = synth.normal((cs.n, cs.p, cs.q, cs.k), seed + 2)
+    d = lc.ConvDesc(cs.n, cs.c, cs.h, cs.w, cs.k, cs.r, cs.s, cs.stride, cs.stride, cs.pad, cs.pad, lc.LC_F32, lc.LC_NHWC)
+    xd, wd, dyd = gu.dev(x), gu.dev(wt), gu.dev(dy)
+    y = torch.empty((cs.n, cs.p, cs.q, cs.k), dtype=torch.float32, device=gu.DEV)
+    dx = torch.empty((cs.n, cs.h, cs.w, cs.c), dtype=torch.float32, device=gu.DEV)
+    dw = torch.empty((cs.k, cs.r, cs.s, cs.c), dtype=torch.float32, device=gu.DEV)
+    lc.conv2d_fwd(d, xd, wd, y, gu.workspace(lc.conv2d_workspace_bytes(d, lc.LC_PASS_FWD)))
+    lc.conv2d_bwd_data(d, dyd, wd, dx, gu.workspace(lc.conv2d_workspace_bytes(d, lc.LC_PASS_BWD_DATA)))
+    lc.conv2d_bwd_weight(d, xd, dyd, dw, gu.workspace(lc.conv2d_workspace_bytes(d, lc.LC_PASS_BWD_WEIGHT)))
+    torch.cuda.synchronize()
+    y, dx, dw = y.cpu().numpy(), dx.cpu().numpy(), dw.cpu().numpy()
+    cy = synth.sample_coords(1024, (cs.n, cs.k, cs.p, cs.q), seed + 3)
+    ref, _ = oracle.conv2d_fwd_at(x, wt, cy, cs.stride, cs.pad, oracle.NHWC)
+    assert np.max(np.abs(y[cy[:, 0], cy[:, 2], cy[:, 3], cy[:, 1]] - ref)) <= TOL * np.max(np.abs(ref))
+    cx = synth.sample_coords(1024, (cs.n, cs.c, cs.h, cs.w), seed + 4)
+    ref, _ = oracle.conv2d_bwd_data_at(dy, wt, (cs.h, cs.w), cx, cs.stride, cs.pad, oracle.NHWC)
+    assert np.max(np.abs(dx[cx[:, 0], cx[:, 2], cx[:, 3], cx[:, 1]] - ref)) <= TOL * max(np.max(np.abs(ref)), 1e-30)
+    cw = synth.sample_coords(256, (cs.k, cs.c, cs.r, cs.s), seed + 5)
+    ref, _ = oracle.conv2d_bwd_weight_at(x, dy, (cs.r, cs.s), cw, cs.stride, cs.pad, oracle.NHWC)
+    assert np.max(np.abs(dw[cw[:, 0], cw[:, 2], cw[:, 3], cw[:, 1]] - ref)) <= TOL * np.max(np.abs(ref))
+    assert np.all(np.isfinite(y)) and np.all(np.isfinite(dx)) and np.all(np.isfinite(dw))
+
+
+def test_resnet50_conv_sweep_batch128_sampled():
+    """Every distinct ResNet-50 convolution shape at batch 128, each pass checked on sampled outputs."""
+    for idx, (cs, count) in enumerate(synth.resnet50_distinct_shapes(128), start=1):
+        seed = 6000 + 10 * idx
+        print(f"sweep shape {idx}: {cs} (x{count})", flush=True)
+        x = synth.normal((cs.n, cs.h, cs.w, cs.c), seed)
+        wt = synth.normal((cs.k, cs.r, cs.s, cs.c), seed + 1, std=synth.he_std(cs))
+        dy = synth.normal((cs.n, cs.p, cs.q, cs.k), seed + 2)
+        d = lc.ConvDesc(cs.n, cs.c, cs.h, cs.w, cs.k, cs.r, cs.s, cs.stride, cs.stride, cs.pad, cs.pad, lc.LC_F32, lc.LC_NHWC)
+        xd, wd, dyd = gu.dev(x), gu.dev(wt), gu.dev(dy)
+        y = torch.empty((cs.n, cs.p, cs.q, cs.k), dtype=torch.float32, device=gu.DEV)
+        dx = torch.empty((cs.n, cs.h, cs.w, cs.c), dtype=torch.float32, device=gu.DEV)
+        dw = torch.empty((cs.k, cs.r, cs.s, cs.c), dtype=torch.float32, device=gu.DEV)
+        lc.conv2d_fwd(d, xd, wd, y, gu.workspace(lc.conv2d_workspace_bytes(d, lc.LC_PASS_FWD)))
+        lc.conv2d_bwd_data(d, dyd, wd, dx, gu.workspace(lc.conv2d_workspace_bytes(d, lc.LC_PASS_BWD_DATA)))
+        lc.conv2d_bwd_weight(d, xd, dyd, dw, gu.workspace(lc.conv2d_workspace_bytes(d, lc.LC_PASS_BWD_WEIGHT)))
+        torch.cuda.synchronize()
+        y, dx, dw = y.cpu().numpy(), dx.cpu().numpy(), dw.cpu().numpy()
+        cy = synth.sample_coords(512, (cs.n, cs.k, cs.p, cs.q), seed + 3)
+        ref, _ = oracle.conv2d_fwd_at(x, wt, cy, cs.stride, cs.pad, oracle.NHWC)
+        assert np.max(np.abs(y[cy[:, 0], cy[:, 2], cy[:, 3], cy[:, 1]] - ref)) <= TOL * np.max(np.abs(ref)), idx
+        cx = synth.sample_coords(512, (cs.n, cs.c, cs.h, cs.w), seed + 4)
+        ref, _ = oracle.conv2d_bwd_data_at(dy, wt, (cs.h, cs.w), cx, cs.stride, cs.pad, oracle.NHWC)
+        assert np.max(np.abs(dx[cx[:, 0], cx[:, 2], cx[:, 3], cx[:, 1]] - ref)) <= TOL * max(np.max(np.abs(ref)), 1e-30), idx
+        cw = synth.sample_coords(128, (cs.k, cs.c, cs.r, cs.s), seed + 5)
+        ref, _ = oracle.conv2d_bwd_weight_at(x, dy, (cs.r, cs.s), cw, cs.stride, cs.pad, oracle.NHWC)
+        assert np.max(np.abs(dw[cw[:, 0], cw[:, 2], cw[:, 3], cw[:, 1]] - ref)) <= TOL * np.max(np.abs(ref)), idx
+        del xd, wd, dyd
+        torch.cuda.empty_cache()

@@ -94,3 +94,34 @@ def test_bf16_tensors_need_16_byte_alignment():
     with pytest.raises(lc.LarsConvError) as e:
         lc.conv2d_fwd(d, buf[1:], buf[8192:], y, ws)
     assert e.value.status == lc.LC_ERR_ALIGN
+
+
+@pytest.mark.parametrize("name", ["res2a_3x3", "res3a_1x1a", "res4b_1x1a", "res5b_3x3"])
+def test_bf16_full_size_batch512_sampled(name):
+    """bf16 workload at its full size (batch 512, one worker's share of a 32K batch): sampled outputs."""
+    cs = {c.name: c for c in synth.resnet50_convs(512)}[name]
+    seed = 7000 + len(name)
+    print(f"bf16 full-size {name}: {cs}", flush=True)
+    xb = synth.to_bf16_bits(synth.normal((cs.n, cs.h, cs.w, cs.c), seed))
+    wb = synth.to_bf16_bits(synth.normal((cs.k, cs.r, cs.s, cs.c), seed + 1, std=synth.he_std(cs)))
+    dyb = synth.to_bf16_bits(synth.normal((cs.n, cs.p, cs.q, cs.k), seed + 2))
+    x, wt, dy = (synth.bf16_bits_to_f32(b) for b in (xb, wb, dyb))
+    d = lc.ConvDesc(cs.n, cs.c, cs.h, cs.w, cs.k, cs.r, cs.s, cs.stride, cs.stride, cs.pad, cs.pad, lc.LC_BF16, lc.LC_NHWC)
+    xd, wd, dyd = _dev_bf16(xb), _dev_bf16(wb), _dev_bf16(dyb)
+    y = torch.empty((cs.n, cs.p, cs.q, cs.k), dtype=torch.int16, device=gu.DEV)
+    dx = torch.empty((cs.n, cs.h, cs.w, cs.c), dtype=torch.int16, device=gu.DEV)
+    dw = torch.empty((cs.k, cs.r, cs.s, cs.c), dtype=torch.float32, device=gu.DEV)
+    lc.conv2d_fwd(d, xd, wd, y, gu.workspace(lc.conv2d_workspace_bytes(d, lc.LC_PASS_FWD)))
+    lc.conv2d_bwd_data(d, dyd, wd, dx, gu.workspace(lc.conv2d_workspace_bytes(d, lc.LC_PASS_BWD_DATA)))
+    lc.conv2d_bwd_weight(d, xd, dyd, dw, gu.workspace(lc.conv2d_workspace_bytes(d, lc.LC_PASS_BWD_WEIGHT)))
+    torch.cuda.synchronize()
+    y, dx, dw = _back(y), _back(dx), dw.cpu().numpy()
+    cy = synth.sample_coords(1024, (cs.n, cs.k, cs.p, cs.q), seed + 3)
+    ref, _ = oracle.conv2d_fwd_at(x, wt, cy, cs.stride, cs.pad, oracle.NHWC)
+    assert np.max(np.abs(y[cy[:, 0], cy[:, 2], cy[:, 3], cy[:, 1]] - oracle.round_to_bf16(ref))) <= TOL_BF16 * np.max(np.abs(ref))
+    cx = synth.sample_coords(1024, (cs.n, cs.c, cs.h, cs.w), seed + 4)
+    ref, _ = oracle.conv2d_bwd_data_at(dy, wt, (cs.h, cs.w), cx, cs.stride, cs.pad, oracle.NHWC)
+    assert np.max(np.abs(dx[cx[:, 0], cx[:, 2], cx[:, 3], cx[:, 1]] - oracle.round_to_bf16(ref))) <= TOL_BF16 * max(np.max(np.abs(ref)), 1e-30)
+    cw = synth.sample_coords(128, (cs.k, cs.c, cs.r, cs.s), seed + 5)
+    ref, _ = oracle.conv2d_bwd_weight_at(x, dy, (cs.r, cs.s), cw, cs.stride, cs.pad, oracle.NHWC)
+    assert np.max(np.abs(dw[cw[:, 0], cw[:, 2], cw[:, 3], cw[:, 1]] - ref)) <= TOL_DW * np.max(np.abs(ref))
