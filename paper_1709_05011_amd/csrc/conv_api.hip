@@ -184,7 +184,7 @@ lc_status make_plan(const lc_conv_desc* d, lc_pass pass, Plan* pl) {
         }
         if (pad) pl->xpad = rg.take((size_t)d->n * d->h * d->w * pl->cpad * es);
         const int M = d->n * pl->P * pl->Q, J = d->r * d->s * pl->cpad;
-        pl->splits = lc_wgrad_splits(M, d->k, J);
+        pl->splits = lc_wgrad_splits(M, d->k, J, pl->bf16);
         pl->m_per_split = (M + pl->splits - 1) / pl->splits;
         pl->wgrad_direct = pl->splits == 1 && !pad;
         if (!pl->wgrad_direct) pl->part = rg.take((size_t)pl->splits * d->k * J * sizeof(float));

@@ -717,6 +717,165 @@ __global__ void __launch_bounds__(WGM* WGN * 64) wgrad_f32_kernel(const GemmWgra
         }
 }
 
+// ------------------------------------------------------------------------------------------------
+// backward-weight kernel for bf16 operands on the bf16 matrix pipe (channel counts multiples of 8).
+// Same GEMM and split as wgrad_f32_kernel, reduction step 32.  LDS holds [reduction row][output index]
+// in bf16 as the 16-byte global vectors arrive; an MFMA operand (8 consecutive reduction rows of one
+// output index) is gathered with eight 16-bit LDS reads, consecutive lanes reading consecutive elements.
+// ------------------------------------------------------------------------------------------------
+template <int BM, int BN>
+__global__ void __launch_bounds__(256) wgrad_bf16_kernel(const GemmWgrad p) {
+    constexpr int BK = 32;                            // reduction rows per step: two k-16 MFMA steps
+    constexpr int AQ = BM / 8, BQ = BN / 8;           // 16-byte vectors per reduction row
+    constexpr int ARPP = 256 / AQ, BRPP = 256 / BQ;   // reduction rows per pass of the block
+    constexpr int LA = BK / ARPP, LB = BK / BRPP;
+    constexpr int PA = BM + 8, PB = BN + 8;           // elements; keeps rows 16-byte aligned
+    constexpr int WTM = BM / 2, WTN = BN / 2, TM = WTM / 32, TN = WTN / 32;
+    static_assert(256 % AQ == 0 && 256 % BQ == 0 && BK % ARPP == 0 && BK % BRPP == 0 && LA >= 1 && LB >= 1, "tile shape");
+
+    __shared__ __attribute__((aligned(16))) uint16_t As[2][BK * PA];
+    __shared__ __attribute__((aligned(16))) uint16_t Bs[2][BK * PB];
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave >> 1, wn = wave & 1;
+    const int nbn = (p.J + BN - 1) / BN;
+    const int tile = blockIdx.x;
+    const int k0 = (tile / nbn) * BM, j0 = (tile % nbn) * BN;
+    const int z = blockIdx.y;
+    const int m_begin = z * p.m_per_split;
+    const int m_end = min(p.M, m_begin + p.m_per_split);
+
+    const uint16_t* __restrict__ DY = static_cast<const uint16_t*>(p.dy);
+    const uint16_t* __restrict__ X = static_cast<const uint16_t*>(p.x);
+
+    const int a_cq = tid % AQ, a_kr = tid / AQ;
+    const int a_col = k0 + a_cq * 8;
+    const bool a_ok = a_col < p.K;
+    const int b_cq = tid % BQ, b_kr = tid / BQ;
+    const int b_col = j0 + b_cq * 8;
+    const bool b_ok = b_col < p.J;
+    int fr, fs, fc;
+    {
+        const int rs = b_col / p.C;
+        fc = b_col % p.C;
+        fs = rs % p.S;
+        fr = rs / p.S;
+    }
+    int b_img[LB], b_p[LB], b_q[LB];
+#pragma unroll
+    for (int i = 0; i < LB; ++i) {
+        const int m = m_begin + b_kr + i * BRPP;
+        b_q[i] = m % p.Q;
+        const int t = m / p.Q;
+        b_p[i] = t % p.P;
+        b_img[i] = t / p.P;
+    }
+    int mt = m_begin;
+
+    float4 ra[LA], rb[LB];                            // raw 16-byte vectors (8 bf16 each)
+    auto gload = [&]() {
+#pragma unroll
+        for (int i = 0; i < LA; ++i) {
+            const int m = mt + a_kr + i * ARPP;
+            ra[i] = load_global16(pick(a_ok & (m < m_end), DY + (long long)m * p.K + a_col, g_zero_chunk));
+        }
+#pragma unroll
+        for (int i = 0; i < LB; ++i) {
+            const int m = mt + b_kr + i * BRPP;
+            const int h = b_p[i] * p.sh - p.ph + fr, w = b_q[i] * p.sw - p.pw + fs;
+            const bool ok = b_ok & (m < m_end) & ((unsigned)h < (unsigned)p.H) & ((unsigned)w < (unsigned)p.W);
+            rb[i] = load_global16(pick(ok, X + (((long long)b_img[i] * p.H + h) * p.W + w) * p.C + fc, g_zero_chunk));
+        }
+    };
+    auto advance = [&]() {
+        mt += BK;
+#pragma unroll
+        for (int i = 0; i < LB; ++i) {
+            b_q[i] += BK;
+            while (b_q[i] >= p.Q) {
+                b_q[i] -= p.Q;
+                if (++b_p[i] == p.P) {
+                    b_p[i] = 0;
+                    ++b_img[i];
+                }
+            }
+        }
+    };
+    auto sstore = [&](int buf) {
+#pragma unroll
+        for (int i = 0; i < LA; ++i) *reinterpret_cast<float4*>(&As[buf][(a_kr + i * ARPP) * PA + a_cq * 8]) = ra[i];
+#pragma unroll
+        for (int i = 0; i < LB; ++i) *reinterpret_cast<float4*>(&Bs[buf][(b_kr + i * BRPP) * PB + b_cq * 8]) = rb[i];
+    };
+
+    f32x16 acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+    // operand of one MFMA: reduction rows 16*t + 8*(lane>>5) + 0..7 of output index (lane & 31)
+    auto frag = [&](const uint16_t* base, int pitch, int t) {
+        const uint16_t* q = base + (16 * t + 8 * (lane >> 5)) * pitch + (lane & 31);
+        uint4 u;
+        u.x = (uint32_t)q[0] | ((uint32_t)q[pitch] << 16);
+        u.y = (uint32_t)q[2 * pitch] | ((uint32_t)q[3 * pitch] << 16);
+        u.z = (uint32_t)q[4 * pitch] | ((uint32_t)q[5 * pitch] << 16);
+        u.w = (uint32_t)q[6 * pitch] | ((uint32_t)q[7 * pitch] << 16);
+        return __builtin_bit_cast(bf16x8, u);
+    };
+    auto compute = [&](int buf) {
+#pragma unroll
+        for (int t = 0; t < BK / 16; ++t) {
+            bf16x8 a[TM], b[TN];
+#pragma unroll
+            for (int i = 0; i < TM; ++i) a[i] = frag(&As[buf][wm * WTM + i * 32], PA, t);
+#pragma unroll
+            for (int j = 0; j < TN; ++j) b[j] = frag(&Bs[buf][wn * WTN + j * 32], PB, t);
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
+        }
+    };
+
+    const int nkt = (m_end - m_begin + BK - 1) / BK;
+    if (nkt > 0) {
+        gload();
+        sstore(0);
+        __syncthreads();
+        int cur = 0;
+        for (int kt = 0; kt < nkt; ++kt) {
+            const bool more = kt + 1 < nkt;
+            if (more) {
+                advance();
+                gload();
+            }
+            compute(cur);
+            if (more) sstore(cur ^ 1);
+            __syncthreads();
+            cur ^= 1;
+        }
+    }
+
+    float* __restrict__ D = p.d + (long long)z * p.K * p.J;
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int row = k0 + wm * WTM + i * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+            if (row >= p.K) continue;
+#pragma unroll
+            for (int j = 0; j < TN; ++j) {
+                const int col = j0 + wn * WTN + j * 32 + (lane & 31);
+                if (col < p.J) D[(long long)row * p.J + col] = acc[i][j][v];
+            }
+        }
+}
+
 inline bool aligned16(const void* ptr) { return (reinterpret_cast<uintptr_t>(ptr) & 15) == 0; }
 
 template <int BM, int BN, int BK, int VEC>
@@ -851,13 +1010,13 @@ static void wgrad_tile(int K, int J, int* bm, int* bn) {
     *bn = J > 64 ? 128 : 64;
 }
 
-int lc_wgrad_splits(int M, int K, int J) {
+int lc_wgrad_splits(int M, int K, int J, bool bf16) {
     int bm, bn;
     wgrad_tile(K, J, &bm, &bn);
     const long long tiles = (long long)((K + bm - 1) / bm) * ((J + bn - 1) / bn);
     // blocks of this tiling that fit on the chip at once (registers and LDS of the kernel instances below):
     // the split count fills exactly one such round, never spills a few blocks into a second one
-    const int per_cu = (bm == 128 && bn == 128) ? 4 : (bm == 64 && bn == 64) ? 8 : 6;
+    const int per_cu = (bm == 128 && bn == 128) ? (bf16 ? 3 : 4) : (bm == 64 && bn == 64) ? 8 : (bf16 ? 5 : 6);
     const long long round = (long long)per_cu * device_cu_count();
     long long want = round / tiles;
     const long long most = (M + 255) / 256;               // at least 256 reduction rows per split
@@ -867,8 +1026,24 @@ int lc_wgrad_splits(int M, int K, int J) {
     return (int)want;
 }
 
+template <int BM, int BN>
+static lc_status launch_wgrad_bf16(const GemmWgrad& p, hipStream_t stream) {
+    const long long tiles = (long long)((p.K + BM - 1) / BM) * ((p.J + BN - 1) / BN);
+    if (tiles <= 0 || tiles > 0x7fffffffLL || p.splits > 65535) return LC_ERR_UNSUPPORTED;
+    hipLaunchKernelGGL((wgrad_bf16_kernel<BM, BN>), dim3((unsigned)tiles, (unsigned)p.splits), dim3(256), 0, stream, p);
+    return lc_end_call();
+}
+
 template <bool BF16>
 static lc_status dispatch_wgrad(const GemmWgrad& p, hipStream_t stream) {
+    if (BF16 && p.C % 8 == 0 && p.K % 8 == 0 && aligned16(p.dy) && aligned16(p.x) && !getenv("LARSCONV_WGRAD_WIDEN")) {
+        int bm, bn;                                   // the bf16 matrix pipe; LARSCONV_WGRAD_WIDEN=1: comparison runs
+        wgrad_tile(p.K, p.J, &bm, &bn);
+        if (bm == 128 && bn == 128) return launch_wgrad_bf16<128, 128>(p, stream);
+        if (bm == 128) return launch_wgrad_bf16<128, 64>(p, stream);
+        if (bn == 128) return launch_wgrad_bf16<64, 128>(p, stream);
+        return launch_wgrad_bf16<64, 64>(p, stream);
+    }
     // vector path: 4 elements per load (16 bytes fp32, 8 bytes bf16)
     const uintptr_t amask = BF16 ? 7 : 15;
     const bool vec = (p.C % 4 == 0) && (p.K % 4 == 0) && !(((uintptr_t)p.dy | (uintptr_t)p.x) & amask);

@@ -80,4 +80,4 @@ struct GemmWgrad {
     int bf16;           // dy and x are bf16 (widened on the fly; the sums and d stay fp32)
 };
 lc_status lc_launch_wgrad_f32(const GemmWgrad& p, hipStream_t stream);
-int lc_wgrad_splits(int M, int K, int J);   // fixed function of the shape (determinism)
+int lc_wgrad_splits(int M, int K, int J, bool bf16);   // fixed function of the shape (determinism)

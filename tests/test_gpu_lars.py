@@ -60,7 +60,7 @@ def _check(sizes, seed, wd, lr, **kw):
 
 
 def test_ragged_sizes_around_the_chunk_size():
-    _check([1, 63, 64, 4095, 4096, 4097, 10000, 3 * 4096 + 5, 0, 2, 8192], 100, 5e-4, 1.0)
+    _check([1, 63, 64, 4095, 4096, 4097, 10000, 3 * 4096 + 5, 0, 2, 8192, 16385], 100, 5e-4, 1.0)
 
 
 def test_hand_values():
@@ -127,3 +127,10 @@ def test_step_length_invariant_on_gpu():
     _, gw, _, _ = _run_gpu(w, g, [np.zeros_like(w[0])], ETA, 0.0, 0.0, 0.5)
     ratio = np.linalg.norm(gw[0].astype(np.float64) - w[0]) / np.linalg.norm(w[0].astype(np.float64))
     assert abs(ratio - 0.5 * ETA) < 1e-4 * 0.5 * ETA
+
+
+def test_long_lists_take_several_launches_per_pass():
+    # more tensors than one launch can describe, with empty tensors among them, with and without the bf16 copy
+    sizes = [((7 * i) % 23) * 257 + (i % 3) for i in range(400)]
+    _check(sizes, 700, 5e-4, 0.9)
+    _check(sizes[:150], 800, 5e-5, 0.4, lowp=True)
