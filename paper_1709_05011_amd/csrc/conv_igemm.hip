@@ -552,17 +552,22 @@ __global__ void __launch_bounds__(256) conv_gemm_fixup_kernel(const GemmConv p) 
 // reduction index m strides over rows.  LDS holds [reduction][row] so that the row-contiguous
 // global vectors are stored as they arrive and MFMA fragments are read with unit lane stride.
 // ------------------------------------------------------------------------------------------------
-// VEC operand elements from global memory as fp32 (bf16 is widened exactly)
+// VEC operand elements from global memory as fp32 (bf16 is widened exactly); loads through the global path
+#define LC_GLOBAL __attribute__((address_space(1)))
 template <int VEC, bool BF16>
 __device__ __forceinline__ typename VecT<VEC>::type load_widen(const void* ptr) {
-    if constexpr (!BF16) {
-        return *static_cast<const typename VecT<VEC>::type*>(ptr);
+    const uintptr_t addr = reinterpret_cast<uintptr_t>(ptr);
+    if constexpr (!BF16 && VEC == 4) {
+        return load_global16(ptr);
+    } else if constexpr (!BF16) {
+        return *(const LC_GLOBAL float*)addr;
     } else if constexpr (VEC == 4) {
-        const uint2 u = *static_cast<const uint2*>(ptr);
+        typedef unsigned int gu2 __attribute__((ext_vector_type(2)));
+        const gu2 u = *(const LC_GLOBAL gu2*)addr;
         return make_float4(__uint_as_float(u.x << 16), __uint_as_float(u.x & 0xffff0000u), __uint_as_float(u.y << 16),
                            __uint_as_float(u.y & 0xffff0000u));
     } else {
-        return __uint_as_float((uint32_t)*static_cast<const uint16_t*>(ptr) << 16);
+        return __uint_as_float((uint32_t)(*(const LC_GLOBAL unsigned short*)addr) << 16);
     }
 }
 
@@ -626,14 +631,14 @@ __global__ void __launch_bounds__(WGM* WGN * 64) wgrad_f32_kernel(const GemmWgra
 #pragma unroll
         for (int i = 0; i < LA; ++i) {
             const int m = mt + a_kr + i * ARPP;
-            ra[i] = (a_ok && m < m_end) ? load_widen<VEC, BF16>(DY + (long long)m * p.K + a_col) : VecT<VEC>::zero();
+            ra[i] = load_widen<VEC, BF16>(pick(a_ok & (m < m_end), DY + (long long)m * p.K + a_col, g_zero_chunk));
         }
 #pragma unroll
         for (int i = 0; i < LB; ++i) {
             const int m = mt + b_kr + i * BRPP;
             const int h = b_p[i] * p.sh - p.ph + fr, w = b_q[i] * p.sw - p.pw + fs;
-            const bool ok = b_ok && m < m_end && h >= 0 && h < p.H && w >= 0 && w < p.W;
-            rb[i] = ok ? load_widen<VEC, BF16>(X + (((long long)b_img[i] * p.H + h) * p.W + w) * p.C + fc) : VecT<VEC>::zero();
+            const bool ok = b_ok & (m < m_end) & ((unsigned)h < (unsigned)p.H) & ((unsigned)w < (unsigned)p.W);
+            rb[i] = load_widen<VEC, BF16>(pick(ok, X + (((long long)b_img[i] * p.H + h) * p.W + w) * p.C + fc, g_zero_chunk));
         }
     };
     auto advance = [&]() {
@@ -665,21 +670,30 @@ __global__ void __launch_bounds__(WGM* WGN * 64) wgrad_f32_kernel(const GemmWgra
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
+    // fragments of the next pair of reduction rows are read while the current pair is multiplied
     auto compute = [&](int buf) {
         const float* as = &As[buf][(lane >> 5) * PA + wm * WTM + (lane & 31)];
         const float* bs = &Bs[buf][(lane >> 5) * PB + wn * WTN + (lane & 31)];
+        float a[2][TM], b[2][TN];
+#pragma unroll
+        for (int i = 0; i < TM; ++i) a[0][i] = as[i * 32];
+#pragma unroll
+        for (int j = 0; j < TN; ++j) b[0][j] = bs[j * 32];
 #pragma unroll
         for (int k2 = 0; k2 < BK / 2; ++k2) {
-            float a[TM], b[TN];
+            const int cs = k2 & 1, ns = cs ^ 1;
+            if (k2 + 1 < BK / 2) {
 #pragma unroll
-            for (int i = 0; i < TM; ++i) a[i] = as[2 * k2 * PA + i * 32];
+                for (int i = 0; i < TM; ++i) a[ns][i] = as[2 * (k2 + 1) * PA + i * 32];
 #pragma unroll
-            for (int j = 0; j < TN; ++j) b[j] = bs[2 * k2 * PB + j * 32];
+                for (int j = 0; j < TN; ++j) b[ns][j] = bs[2 * (k2 + 1) * PB + j * 32];
+                __builtin_amdgcn_sched_barrier(0);      // keep these reads in front of the MFMAs below
+            }
 #pragma unroll
             for (int i = 0; i < TM; ++i)
 #pragma unroll
                 for (int j = 0; j < TN; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i], b[j], acc[i][j], 0, 0, 0);
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[cs][i], b[cs][j], acc[i][j], 0, 0, 0);
         }
     };
 
