@@ -37,7 +37,8 @@ typedef enum {
     LC_ERR_UNSUPPORTED = 3, /* unknown enum value or a combination that is not built        */
     LC_ERR_WORKSPACE = 4,   /* workspace NULL, misaligned or smaller than the query         */
     LC_ERR_LAUNCH = 5,      /* the HIP runtime reported an error while enqueueing           */
-    LC_ERR_ALIGN = 6        /* a tensor pointer is not aligned to its element size          */
+    LC_ERR_ALIGN = 6        /* a tensor pointer is not aligned: 4 bytes for fp32 tensors,
+                               16 bytes for bf16 tensors (they are read in 16-byte vectors) */
 } lc_status;
 
 typedef enum { LC_F32 = 0, LC_BF16 = 1 } lc_dtype;   /* operand type; sums are always fp32 */
