@@ -297,7 +297,17 @@ __device__ __forceinline__ size_t partial_index(int wave, int i, int j, int v, i
 // feeds A[row l%32][k 8*(l/32) .. +7], i.e. exactly one LDS chunk per MFMA); the result is stored as bf16.
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 
-template <int BM, int BN, bool SMALLC, bool BF16>
+// UT ("uniform tap"): the channel count is a multiple of the k-step, so a k-step lies inside one filter tap
+// and its (r, s, first channel) are the same for every lane.  They are then tracked in scalar registers, the
+// operands are fetched with buffer loads (tile-relative 32-bit byte offset per lane + scalar offset of the
+// k-step), and a tap outside the image is a bit in a per-row mask that moves the lane's offset past the end
+// of the buffer, where the hardware returns zeros.  That leaves two vector ALU instructions per activation
+// load in the main loop; on this chip every vector ALU instruction displaces MFMA issue time.
+typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+constexpr unsigned kBufferWords3 = 0x00020000u;       // raw buffer, 32-bit data format
+constexpr unsigned kBufferBytes = 0x80000000u;        // buffer size given to the hardware; offsets with bit 31 set read zeros
+
+template <int BM, int BN, bool SMALLC, bool BF16, bool UT = false>
 __global__ void __launch_bounds__(256) conv_gemm_sk_kernel(const GemmConv p) {
     using E = typename OutT<BF16>::type;                        // operand element type
     constexpr int EPC = BF16 ? 8 : 4;                           // elements per 16-byte chunk
@@ -379,6 +389,50 @@ __global__ void __launch_bounds__(256) conv_gemm_sk_kernel(const GemmConv p) {
             r = rs / p.S;
         }
 
+        // UT: per-lane byte offsets relative to the tile's first image (A) and first filter row (B), the mask
+        // of taps that fall outside the image for each of this lane's rows, and the scalar position
+        unsigned a_voff[LA], a_inv[LA], b_voff[LB];
+        __amdgpu_buffer_rsrc_t a_rsrc, b_rsrc;
+        int u_kt = 0, u_c = 0, u_s = 0, u_r = 0;
+        if constexpr (UT) {
+            constexpr int ES = (int)sizeof(E);
+            const int pq = p.Po * p.Qo;
+            const int img0 = m0 / pq;
+            const int phb = max(p.ph, 0), pwb = max(p.pw, 0);
+#pragma unroll
+            for (int i = 0; i < LA; ++i) {
+                const int m = m0 + (i * 4 + wave) * 16 + lrow;
+                a_voff[i] = 0;
+                a_inv[i] = ~0u;
+                if (m < p.M) {
+                    const int qo = m % p.Qo, t = m / p.Qo;
+                    const int po = t % p.Po, img = t / p.Po;
+                    const int h0 = po * p.sh - p.ph, w0 = qo * p.sw - p.pw;
+                    a_voff[i] = (unsigned)(((((img - img0) * Hi_ + h0 + phb) * Wi_) + w0 + pwb) * Ci_ * ES + kq * 16);
+                    unsigned inv = 0;
+                    for (int rr = 0; rr < R_; ++rr)
+                        for (int ss = 0; ss < S_; ++ss) {
+                            const bool bad = ((unsigned)(h0 + rr) >= (unsigned)Hi_) | ((unsigned)(w0 + ss) >= (unsigned)Wi_);
+                            inv |= (bad ? 1u : 0u) << (rr * S_ + ss);
+                        }
+                    a_inv[i] = inv;
+                }
+            }
+#pragma unroll
+            for (int i = 0; i < LB; ++i) {
+                const int nl = (i * 4 + wave) * 16 + lrow;
+                b_voff[i] = (n0 + nl < p.N) ? (unsigned)(nl * p.Kg * ES + kq * 16) : kBufferBytes;
+            }
+            const long long a_first = ((long long)img0 * Hi_ * Wi_ - ((long long)phb * Wi_ + pwb)) * Ci_;
+            a_rsrc = __builtin_amdgcn_make_buffer_rsrc((void*)(A + a_first), 0, (int)kBufferBytes, (int)kBufferWords3);
+            b_rsrc = __builtin_amdgcn_make_buffer_rsrc((void*)(B + (long long)n0 * p.Kg), 0, (int)kBufferBytes, (int)kBufferWords3);
+            u_kt = k0;
+            const int kg0 = k0 * BK, rs0 = kg0 / Ci_;
+            u_c = kg0 - rs0 * Ci_;
+            u_s = rs0 % S_;
+            u_r = rs0 / S_;
+        }
+
         float4 g[LPT];                            // the tile in flight between global memory and LDS
         auto gload_one = [&](int l) {
             const bool kok = r < R_;              // same as kg < Kg
@@ -411,6 +465,33 @@ __global__ void __launch_bounds__(256) conv_gemm_sk_kernel(const GemmConv p) {
             }
         };
         auto gload_tile = [&]() {
+            if constexpr (UT) {
+                constexpr int ES = (int)sizeof(E);
+                const int tap = u_r * S_ + u_s;
+                const unsigned up = 31u - (unsigned)tap;                 // brings this tap's mask bit to bit 31
+                const int a_soff = ((u_r * Wi_ + u_s) * Ci_ + u_c) * ES;
+                const int b_soff = u_kt * BK * ES;
+#pragma unroll
+                for (int l = 0; l < LA; ++l) {
+                    const unsigned vo = ((a_inv[l] << up) & kBufferBytes) | a_voff[l];
+                    g[l] = __builtin_bit_cast(float4, __builtin_amdgcn_raw_buffer_load_b128(a_rsrc, (int)vo, a_soff, 0));
+                }
+#pragma unroll
+                for (int l = 0; l < LB; ++l)
+                    g[LA + l] = __builtin_bit_cast(float4, __builtin_amdgcn_raw_buffer_load_b128(b_rsrc, (int)b_voff[l], b_soff, 0));
+                // the step past the last one is fetched again instead (its data is never used)
+                // (scalar selects, no branches: the loop body stays one basic block)
+                const bool more = u_kt + 1 < nkt;
+                u_kt += more ? 1 : 0;
+                u_c += more ? BK : 0;
+                const bool wrap = u_c == Ci_;
+                u_c = wrap ? 0 : u_c;
+                u_s += wrap ? 1 : 0;
+                const bool wrap2 = u_s == S_;
+                u_s = wrap2 ? 0 : u_s;
+                u_r += wrap2 ? 1 : 0;
+                return;
+            }
 #pragma unroll
             for (int l = 0; l < LPT; ++l) gload_one(l);
             advance();
@@ -460,10 +541,9 @@ __global__ void __launch_bounds__(256) conv_gemm_sk_kernel(const GemmConv p) {
         gload_tile();                             // k-step k0+1 (zeros past the end of the filter window)
         lds_barrier();
         read_frags(0, 0, 0);
-        int cur = 0;
-        // The last k-step is peeled off so that the loop body is one basic block (a join between the fragment
-        // reads and the MFMAs that follow would make the compiler wait for the reads just issued).
-        for (int kt = k0; kt + 1 < k1; ++kt) {
+        // One k-step out of LDS buffer `cur` (a literal at every call, so that all LDS addresses are a register
+        // fixed for the whole tile plus an immediate).
+        auto step = [&](int cur) __attribute__((always_inline)) {
             read_frags(cur, 1, 1);                // k = 8..15 of this step
             mfma_e(0, 0);
             mfma_e(0, 1);
@@ -478,7 +558,17 @@ __global__ void __launch_bounds__(256) conv_gemm_sk_kernel(const GemmConv p) {
             read_frags(cur ^ 1, 0, 0);            // k = 0..7 of the next step
 #pragma unroll
             for (int e = 0; e < 4; ++e) mfma_e(1, e);
-            cur ^= 1;
+        };
+        // The last k-step is peeled off so that the loop body is one basic block (a join between the fragment
+        // reads and the MFMAs that follow would make the compiler wait for the reads just issued).
+        int kt = k0, cur = 0;
+        for (; kt + 2 < k1; kt += 2) {
+            step(0);
+            step(1);
+        }
+        if (kt + 1 < k1) {
+            step(0);
+            cur = 1;
         }
         read_frags(cur, 1, 1);
 #pragma unroll
@@ -958,6 +1048,21 @@ bool sk_geometry(const GemmConv& p, long long* tiles, int* nkt) {
     return *tiles > 0 && *tiles * *nkt < 0x7fffffffLL;
 }
 
+// Whether the uniform-tap variant of the main kernel takes this problem: k-steps that do not straddle taps,
+// a tap mask that fits 32 bits, and tile-relative byte offsets (the images a tile can touch plus one filter
+// window, and BN filter rows) that stay below 2^31.
+template <int BM, int BN>
+bool uniform_tap_ok(const GemmConv& p) {
+    static const bool off = getenv("LARSCONV_NO_UNIFORM_TAP") != nullptr;     // comparison runs
+    const int bk = p.bf16 ? 32 : 16, es = p.bf16 ? 2 : 4;
+    if (off || p.Ci % bk != 0 || (long long)p.R * p.S > 32) return false;
+    const long long pq = (long long)p.Po * p.Qo;
+    const long long images = BM / pq + 2;
+    const long long a_span = ((images * p.Hi + (p.ph > 0 ? p.ph : 0) + p.R + 1) * p.Wi + p.S + 1) * p.Ci * es;
+    const long long b_span = (long long)(BN + 1) * p.Kg * es;
+    return a_span < 0x7fff0000LL && b_span < 0x7fff0000LL;
+}
+
 template <int BM, int BN, bool SMALLC, bool BF16>
 lc_status launch_conv_sk(GemmConv p, hipStream_t stream) {
     long long tiles;
@@ -972,8 +1077,12 @@ lc_status launch_conv_sk(GemmConv p, hipStream_t stream) {
     p.dp_tiles = pl.dp_tiles;
     p.sk_blocks = pl.sk_blocks;
     p.sk_iters = pl.sk_iters;
-    hipLaunchKernelGGL((conv_gemm_sk_kernel<BM, BN, SMALLC, BF16>), dim3((unsigned)(pl.dp_tiles + pl.sk_blocks)), dim3(256), 0,
-                       stream, p);
+    if (!SMALLC && uniform_tap_ok<BM, BN>(p))
+        hipLaunchKernelGGL((conv_gemm_sk_kernel<BM, BN, false, BF16, true>), dim3((unsigned)(pl.dp_tiles + pl.sk_blocks)), dim3(256),
+                           0, stream, p);
+    else
+        hipLaunchKernelGGL((conv_gemm_sk_kernel<BM, BN, SMALLC, BF16>), dim3((unsigned)(pl.dp_tiles + pl.sk_blocks)), dim3(256), 0,
+                           stream, p);
     if (pl.sk_blocks > 0)
         hipLaunchKernelGGL((conv_gemm_fixup_kernel<BM, BN, BF16>), dim3((unsigned)(tiles - pl.dp_tiles), 16), dim3(256), 0, stream, p);
     return lc_end_call();
