@@ -13,6 +13,7 @@
 // global -> registers -> LDS with the next tile's global loads in flight while the current tile is
 // multiplied (two LDS buffers, one barrier per k-step).
 #include <hip/hip_runtime.h>
+#include <type_traits>
 #include <stdint.h>
 #include <stdlib.h>
 #include <string.h>
@@ -308,7 +309,7 @@ constexpr unsigned kBufferWords3 = 0x00020000u;       // raw buffer, 32-bit data
 constexpr unsigned kBufferBytes = 0x80000000u;        // buffer size given to the hardware; offsets with bit 31 set read zeros
 
 template <int BM, int BN, bool SMALLC, bool BF16, bool UT = false>
-__global__ void __launch_bounds__(256) conv_gemm_sk_kernel(const GemmConv p) {
+__global__ void __launch_bounds__(256, 3) conv_gemm_sk_kernel(const GemmConv p) {   // 3 blocks per compute unit: resident_blocks()
     using E = typename OutT<BF16>::type;                        // operand element type
     constexpr int EPC = BF16 ? 8 : 4;                           // elements per 16-byte chunk
     constexpr int BK = 4 * EPC;                                 // elements per k-step: one 64-byte LDS row
@@ -822,6 +823,209 @@ __global__ void __launch_bounds__(WGM* WGN * 64) wgrad_f32_kernel(const GemmWgra
 }
 
 // ------------------------------------------------------------------------------------------------
+// backward-weight kernel with scalar addressing (fp32 operands, channel counts multiples of 4, filter
+// windows of at most 32 taps).  Same GEMM, LDS layout, split and fragment reads as wgrad_f32_kernel; the
+// difference is where the address arithmetic runs.  A wave fetches whole reduction rows: one load
+// instruction covers the BN columns of ONE output pixel m, so the pixel's (image, p, q), its byte offset and
+// the set of filter taps that fall inside the image are wave-uniform and are kept in scalar registers
+// (advanced by 16 rows per step with precomputed digits of 16 in the (Q, P) number system).  A lane only
+// holds what depends on its column: the tap's byte offset and the tap's bit position.  A lane whose tap is
+// outside the image for this pixel gets bit 31 of its buffer offset set and the hardware returns zeros.
+// dY rows past the end of the split are cut off by the size of the dY buffer descriptor.
+// ------------------------------------------------------------------------------------------------
+template <int BM, int BN>
+__global__ void __launch_bounds__(256, 4) wgrad_ut_kernel(const GemmWgrad p) {   // 4 blocks per compute unit: lc_wgrad_splits()
+    constexpr int BK = 16;
+    constexpr int AQ = BM / 4, ARPP = 256 / AQ, LA = BK / ARPP;   // dY: 16-byte vectors, ARPP rows per pass
+    constexpr int BV = BN / 64;                                   // X: floats per lane and row (one row per wave and load)
+    constexpr int RW = BK / 4;                                    // X rows per wave and step
+    constexpr int PA = BM + 4, PB = BN + 4;
+    constexpr int WTM = BM / 2, WTN = BN / 2, TM = WTM / 32, TN = WTN / 32;
+    static_assert(BV == 1 || BV == 2, "tile shape");
+    using BVt = typename std::conditional<BV == 2, float2, float>::type;
+
+    __shared__ __attribute__((aligned(16))) float As[2][BK * PA];
+    __shared__ __attribute__((aligned(16))) float Bs[2][BK * PB];
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave >> 1, wn = wave & 1;
+    const int nbn = (p.J + BN - 1) / BN;
+    const int tile = blockIdx.x;
+    const int k0 = (tile / nbn) * BM, j0 = (tile % nbn) * BN;
+    const int z = blockIdx.y;
+    const int m_begin = z * p.m_per_split;
+    const int m_end = min(p.M, m_begin + p.m_per_split);
+    const int H_ = p.H, W_ = p.W, C_ = p.C, P_ = p.P, Q_ = p.Q, R_ = p.R, S_ = p.S, K_ = p.K;
+    const int sh_ = p.sh, sw_ = p.sw, ph_ = p.ph, pw_ = p.pw;
+
+    // dY: lane-constant offset inside a 16-row step; the step's first row is the scalar offset
+    const int a_cq = tid % AQ, a_kr = tid / AQ;
+    const int a_col = k0 + a_cq * 4;
+    unsigned a_voff[LA];
+#pragma unroll
+    for (int i = 0; i < LA; ++i) a_voff[i] = a_col < K_ ? (unsigned)(((a_kr + i * ARPP) * K_ + a_col) * 4) : kBufferBytes;
+    const __amdgpu_buffer_rsrc_t a_rsrc = __builtin_amdgcn_make_buffer_rsrc(
+        (void*)(static_cast<const float*>(p.dy) + (long long)m_begin * K_), 0, (int)((unsigned)(m_end - m_begin) * K_ * 4u),
+        (int)kBufferWords3);
+
+    // X: the lane's column j = (r, s, c): byte offset of the tap relative to the pixel's window origin, bit position
+    const int b_col = j0 + lane * BV;
+    unsigned b_voff = kBufferBytes, b_up = 0;
+    if (b_col < p.J) {
+        const int rs = b_col / C_, fc = b_col - rs * C_;
+        const int fr = rs / S_, fs = rs - fr * S_;
+        b_voff = (unsigned)(((fr * W_ + fs) * C_ + fc) * 4);
+        b_up = 31u - (unsigned)rs;
+    }
+    const int pq = P_ * Q_;
+    const int img_first = m_begin / pq;
+    const int phb = max(ph_, 0), pwb = max(pw_, 0);
+    const __amdgpu_buffer_rsrc_t b_rsrc = __builtin_amdgcn_make_buffer_rsrc(
+        (void*)(static_cast<const float*>(p.x) + ((long long)img_first * H_ * W_ - ((long long)phb * W_ + pwb)) * C_), 0,
+        (int)kBufferBytes, (int)kBufferWords3);
+    // scalar state of this wave's RW rows: (image - img_first, p, q) of row m_begin + step * 16 + wave * RW + i
+    int s_img[RW], s_p[RW], s_q[RW];
+#pragma unroll
+    for (int i = 0; i < RW; ++i) {
+        const int m = m_begin + wave * RW + i;
+        const int t = m / Q_;
+        s_q[i] = m - t * Q_;
+        const int im = t / P_;
+        s_p[i] = t - im * P_;
+        s_img[i] = im - img_first;
+    }
+    // 16 rows further: 16 = (d_img * P + d_p) * Q + d_q
+    const int d_q = BK % Q_, d_t = BK / Q_, d_p = d_t % P_, d_img = d_t / P_;
+    const int taps = R_ * S_;
+    const unsigned full = taps >= 32 ? ~0u : (1u << taps) - 1u;
+    unsigned rep = 0;                                             // bit r*S for every r: spreads a mask over s to all rows of the window
+    for (int r = 0; r < R_; ++r) rep |= 1u << (r * S_);
+    int mt = m_begin;                                             // first reduction row of the step being loaded
+
+    float4 ra[LA];
+    BVt rb[RW];
+    auto gload = [&]() {
+        const int a_soff = (mt - m_begin) * K_ * 4;
+#pragma unroll
+        for (int i = 0; i < LA; ++i)
+            ra[i] = __builtin_bit_cast(float4, __builtin_amdgcn_raw_buffer_load_b128(a_rsrc, (int)a_voff[i], a_soff, 0));
+#pragma unroll
+        for (int i = 0; i < RW; ++i) {
+            const int h0 = s_p[i] * sh_ - ph_, w0 = s_q[i] * sw_ - pw_;
+            int rlo = max(0, -h0), rhi = min(R_ - 1, H_ - 1 - h0);
+            int slo = max(0, -w0), shi = min(S_ - 1, W_ - 1 - w0);
+            const bool ok = (rlo <= rhi) & (slo <= shi) & (mt + wave * RW + i < m_end);
+            rlo = min(rlo, R_ - 1);                              // keep the shifts below in range when the row is dead
+            rhi = max(rhi, 0);
+            slo = min(slo, S_ - 1);
+            const int sspan = max(shi - slo, 0);
+            const unsigned hm = (full << (rlo * S_)) & (full >> ((R_ - 1 - rhi) * S_));
+            const unsigned wmask = rep * (((2u << sspan) - 1u) << slo);
+            const unsigned inv = ok ? ~(hm & wmask) : ~0u;        // taps outside the image for this pixel
+            const int soff = ok ? (((s_img[i] * H_ + s_p[i] * sh_ + phb - ph_) * W_ + s_q[i] * sw_ + pwb - pw_) * C_) * 4 : 0;
+            const unsigned vo = ((inv << b_up) & kBufferBytes) | b_voff;
+            if constexpr (BV == 2)
+                rb[i] = __builtin_bit_cast(float2, __builtin_amdgcn_raw_buffer_load_b64(b_rsrc, (int)vo, soff, 0));
+            else
+                rb[i] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(b_rsrc, (int)vo, soff, 0));
+        }
+    };
+    auto advance = [&]() {
+        mt += BK;
+#pragma unroll
+        for (int i = 0; i < RW; ++i) {
+            int q = s_q[i] + d_q;
+            const bool cq = q >= Q_;
+            q -= cq ? Q_ : 0;
+            int pp = s_p[i] + d_p + (cq ? 1 : 0);
+            const bool cp = pp >= P_;
+            pp -= cp ? P_ : 0;
+            s_q[i] = q;
+            s_p[i] = pp;
+            s_img[i] += d_img + (cp ? 1 : 0);
+        }
+    };
+    auto sstore = [&](int buf) {
+#pragma unroll
+        for (int i = 0; i < LA; ++i) *reinterpret_cast<float4*>(&As[buf][(a_kr + i * ARPP) * PA + a_cq * 4]) = ra[i];
+#pragma unroll
+        for (int i = 0; i < RW; ++i) *reinterpret_cast<BVt*>(&Bs[buf][(wave * RW + i) * PB + lane * BV]) = rb[i];
+    };
+
+    f32x16 acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+    // fragments of the next pair of reduction rows are read while the current pair is multiplied
+    auto compute = [&](int buf) {
+        const float* as = &As[buf][(lane >> 5) * PA + wm * WTM + (lane & 31)];
+        const float* bs = &Bs[buf][(lane >> 5) * PB + wn * WTN + (lane & 31)];
+        float a[2][TM], b[2][TN];
+#pragma unroll
+        for (int i = 0; i < TM; ++i) a[0][i] = as[i * 32];
+#pragma unroll
+        for (int j = 0; j < TN; ++j) b[0][j] = bs[j * 32];
+#pragma unroll
+        for (int k2 = 0; k2 < BK / 2; ++k2) {
+            const int cs = k2 & 1, ns = cs ^ 1;
+            if (k2 + 1 < BK / 2) {
+#pragma unroll
+                for (int i = 0; i < TM; ++i) a[ns][i] = as[2 * (k2 + 1) * PA + i * 32];
+#pragma unroll
+                for (int j = 0; j < TN; ++j) b[ns][j] = bs[2 * (k2 + 1) * PB + j * 32];
+                __builtin_amdgcn_sched_barrier(0);      // keep these reads in front of the MFMAs below
+            }
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[cs][i], b[cs][j], acc[i][j], 0, 0, 0);
+        }
+    };
+
+    // One step out of LDS buffer `cur` (a literal at each call).  The step after the last one is fetched and
+    // stored as well: all of its rows are past m_end, so nothing is read from memory and zeros are stored.
+    auto step = [&](int cur) __attribute__((always_inline)) {
+        advance();
+        gload();
+        compute(cur);
+        sstore(cur ^ 1);
+        __syncthreads();
+    };
+    const int nkt = (m_end - m_begin + BK - 1) / BK;
+    if (nkt > 0) {
+        gload();
+        sstore(0);
+        __syncthreads();
+        int kt = 0;
+        for (; kt + 2 <= nkt; kt += 2) {
+            step(0);
+            step(1);
+        }
+        if (kt < nkt) step(0);
+    }
+
+    float* __restrict__ D = p.d + (long long)z * p.K * p.J;
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int row = k0 + wm * WTM + i * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+            if (row >= p.K) continue;
+#pragma unroll
+            for (int j = 0; j < TN; ++j) {
+                const int col = j0 + wn * WTN + j * 32 + (lane & 31);
+                if (col < p.J) D[(long long)row * p.J + col] = acc[i][j][v];
+            }
+        }
+}
+
+// ------------------------------------------------------------------------------------------------
 // backward-weight kernel for bf16 operands on the bf16 matrix pipe (channel counts multiples of 8).
 // Same GEMM and split as wgrad_f32_kernel, reduction step 32.  LDS holds [reduction row][output index]
 // in bf16 as the 16-byte global vectors arrive; an MFMA operand (8 consecutive reduction rows of one
@@ -1157,8 +1361,36 @@ static lc_status launch_wgrad_bf16(const GemmWgrad& p, hipStream_t stream) {
     return lc_end_call();
 }
 
+// Whether wgrad_ut_kernel takes this problem: fp32, 16-byte vectors, a window of at most 32 taps, and buffer
+// offsets (a split's rows of dY; the images a split touches plus one window of X) below 2^31 bytes.
+static bool wgrad_ut_ok(const GemmWgrad& p) {
+    static const bool off = getenv("LARSCONV_NO_UNIFORM_TAP") != nullptr;     // comparison runs
+    if (off || p.bf16 || p.C % 4 != 0 || p.K % 4 != 0 || (long long)p.R * p.S > 32) return false;
+    if ((((uintptr_t)p.dy | (uintptr_t)p.x) & 15) != 0) return false;
+    const long long rows = (long long)p.m_per_split + 32;
+    const long long a_span = rows * p.K * 4;
+    const long long images = rows / ((long long)p.P * p.Q) + 2;
+    const long long b_span = ((images * p.H + (p.ph > 0 ? p.ph : 0) + p.R + 1) * p.W + p.S + 1) * p.C * 4;
+    return a_span < 0x7fff0000LL && b_span < 0x7fff0000LL;
+}
+
+template <int BM, int BN>
+static lc_status launch_wgrad_ut(const GemmWgrad& p, hipStream_t stream) {
+    const long long tiles = (long long)((p.K + BM - 1) / BM) * ((p.J + BN - 1) / BN);
+    if (tiles <= 0 || tiles > 0x7fffffffLL || p.splits > 65535) return LC_ERR_UNSUPPORTED;
+    hipLaunchKernelGGL((wgrad_ut_kernel<BM, BN>), dim3((unsigned)tiles, (unsigned)p.splits), dim3(256), 0, stream, p);
+    return lc_end_call();
+}
+
 template <bool BF16>
 static lc_status dispatch_wgrad(const GemmWgrad& p, hipStream_t stream) {
+    if (!BF16 && wgrad_ut_ok(p)) {
+        // only the 128 x 128 tiling: with narrower tiles a step has too few MFMAs to hide the scalar work and the
+        // narrower loads, and wgrad_f32_kernel measures faster
+        int bm, bn;
+        wgrad_tile(p.K, p.J, &bm, &bn);
+        if (bm == 128 && bn == 128) return launch_wgrad_ut<128, 128>(p, stream);
+    }
     if (BF16 && p.C % 8 == 0 && p.K % 8 == 0 && aligned16(p.dy) && aligned16(p.x) && !getenv("LARSCONV_WGRAD_WIDEN")) {
         int bm, bn;                                   // the bf16 matrix pipe; LARSCONV_WGRAD_WIDEN=1: comparison runs
         wgrad_tile(p.K, p.J, &bm, &bn);
