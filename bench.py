@@ -9,6 +9,8 @@ images/s, plus "roofline" for the dominant kernel and "cpu_baseline" (the CPU or
 host cores on a bounded sample).
 
     python bench.py [--steps K] [--warmup W]          # the headline line
+    python bench.py --dtype bf16                      # the same step at batch 512 with bf16 operands
+    python bench.py --model alexnet_bn                # AlexNet-BN shaped step (5 convs + 3 FC layers as convs, 21 tensors)
     python bench.py --sweep [--batch 128]             # every distinct ResNet-50 conv shape x 3 passes
     python bench.py --lars resnet50|alexnet_bn        # lars_step alone, GB/s against HBM peak
 """
@@ -94,7 +96,14 @@ def timed(timer, key, fn):
     b.record()
 
 
-def run_resnet50_step(args):
+def model_shapes(synth, model: str, batch: int):
+    """(layer shapes in network order, number of leading layers followed by batch norm, weight decay)."""
+    if model == "alexnet_bn":
+        return synth.alexnet_bn_convs(batch), 5, 5e-4
+    return synth.resnet50_convs(batch) + [synth.resnet50_fc(batch)], 53, 5e-5
+
+
+def run_train_step(args):
     import torch
     from paper_1709_05011_amd import larsconv as lc
     from paper_1709_05011_amd import synth
@@ -104,25 +113,24 @@ def run_resnet50_step(args):
     batch = args.batch or (512 if bf16 else 256)
     gen = torch.Generator(device="cuda:0")
     gen.manual_seed(0x5EED0300)
-    shapes = synth.resnet50_convs(batch) + [synth.resnet50_fc(batch)]
+    shapes, n_bn, weight_decay = model_shapes(synth, args.model, batch)
     layers = [Layer(cs, gen, torch, lc, i == 0, bf16) for i, cs in enumerate(shapes)]
     ws = make_workspace(max(l.ws_bytes for l in layers), torch)
 
-    # the 161 parameter tensors: filter, batch-norm scale, batch-norm shift per conv; classifier weight, bias
+    # parameter tensors: filter, batch-norm scale, batch-norm shift per convolution; weight and bias per FC layer
+    # (ResNet-50: 161 tensors, AlexNet-BN: 21)
     pw, pg, pv, plow = [], [], [], []
-    for l in layers[:-1]:
+    for i, l in enumerate(layers):
         k = l.cs.k
-        pw += [l.w_master, torch.ones(k, device="cuda:0"), torch.zeros(k, device="cuda:0")]
-        plow += [l.w, None, None]
-        pg += [l.dw, torch.randn(k, generator=gen, device="cuda:0") * 1e-2,
-               torch.randn(k, generator=gen, device="cuda:0") * 1e-2]
-    pw += [layers[-1].w_master, torch.zeros(1000, device="cuda:0")]
-    plow += [layers[-1].w, None]
-    pg += [layers[-1].dw, torch.randn(1000, generator=gen, device="cuda:0") * 1e-2]
+        extra = [torch.ones(k, device="cuda:0"), torch.zeros(k, device="cuda:0")] if i < n_bn else [torch.zeros(k, device="cuda:0")]
+        pw += [l.w_master] + extra
+        plow += [l.w] + [None] * len(extra)
+        pg += [l.dw] + [torch.randn(k, generator=gen, device="cuda:0") * 1e-2 for _ in extra]
     pv = [torch.zeros_like(t) for t in pw]
     # bf16 run: fp32 master weights and momentum; lars_step also writes the bf16 weights the convolutions read
     largs = lc.LarsArgs(pw, pg, pv, w_lowp=plow if bf16 else None)
-    assert largs.n == 161 and sum(largs.numel) == 25_557_032
+    expect = synth.alexnet_bn_param_numels() if args.model == "alexnet_bn" else synth.resnet50_param_numels()
+    assert list(largs.numel) == list(expect), "parameter list does not match the model's"
     lws = make_workspace(lc.lars_workspace_bytes(largs.numel), torch)
     trust = torch.empty(largs.n, device="cuda:0")
     T = synth.poly_total_iters()
@@ -146,7 +154,7 @@ def run_resnet50_step(args):
                       lambda l=l: lc.conv2d_bwd_data(l.desc, l.dy, l.w, l.dx, ws))
             timed(timer, ("bwd_weight", "wgrad", l.cs.flops),
                   lambda l=l: lc.conv2d_bwd_weight(l.desc, l.x, l.dy, l.dw, ws))
-        timed(timer, ("lars", "lars", 0), lambda: lc.lars_step(largs, 0.001, 0.9, 5e-5, lr, trust, lws))
+        timed(timer, ("lars", "lars", 0), lambda: lc.lars_step(largs, 0.001, 0.9, weight_decay, lr, trust, lws))
 
     for _ in range(args.warmup):
         step()
@@ -177,8 +185,10 @@ def run_resnet50_step(args):
     achieved = dfl / (dms * 1e-3) / 1e12
     # bf16: forward and backward-data run on the bf16 matrix pipe; the filter gradient still multiplies in fp32
     peak = (PEAK_MFMA_F32 if dom == "wgrad" else PEAK_MFMA_BF16) if bf16 else PEAK_MFMA_F32
+    name = "AlexNet-BN" if args.model == "alexnet_bn" else "ResNet-50"
+    n_fc = len(layers) - n_bn
     result = {
-        "metric": "ResNet-50 fwd+bwd+LARS images/sec/GPU",
+        "metric": f"{name} fwd+bwd+LARS images/sec/GPU",
         "value": round(batch / (ms_per_step * 1e-3), 2),
         "unit": "images/s",
         "n_gpus": 1,
@@ -190,12 +200,13 @@ def run_resnet50_step(args):
         "vs_baseline": None,
         "dtype": "bf16" if bf16 else "f32",
         "data": "synthetic",
-        "config": {"workload": f"resnet50_train_step_{'bf16' if bf16 else 'fp32'}_batch{batch}_nhwc (53 convs + fc: fwd, bwd_data, bwd_weight; "
-                               "lars_step over 161 tensors / 25.6M params)",
-                   "batch": batch, "layout": "NHWC", "lars": {"eta": 0.001, "momentum": 0.9, "weight_decay": 5e-5, "lr": lr}},
+        "config": {"workload": f"{args.model}_train_step_{'bf16' if bf16 else 'fp32'}_batch{batch}_nhwc ({n_bn} convs + {n_fc} fc: fwd, "
+                               f"bwd_data, bwd_weight; lars_step over {largs.n} tensors / {sum(largs.numel) / 1e6:.1f}M params)",
+                   "batch": batch, "layout": "NHWC",
+                   "lars": {"eta": 0.001, "momentum": 0.9, "weight_decay": weight_decay, "lr": lr}},
         "roofline": {"bound": "mfma", "kernel": dom, "achieved": round(achieved, 2), "peak": peak,
                      "unit": "TFLOP/s", "frac": round(achieved / peak, 4),
-                     "traffic": None if bf16 else MEASURED_TRAFFIC.get((dom, batch)),
+                     "traffic": None if bf16 or args.model != "resnet50" else MEASURED_TRAFFIC.get((dom, batch)),
                      "launches_per_step": dn // args.steps, "avg_launch_ms": round(dms / dn, 4),
                      "flops_per_launch": dfl / dn},
         "conv_tflops": {p: round(per_pass[p][2] / (per_pass[p][0] * 1e-3) / 1e12, 2) for p in ("fwd", "bwd_data", "bwd_weight")},
@@ -206,18 +217,18 @@ def run_resnet50_step(args):
         "kernel_ms_per_step": {k: round(v[0] / args.steps, 3) for k, v in per_kernel.items()},
     }
     if not args.no_cpu:
-        result["cpu_baseline"] = cpu_baseline(args.cpu_batch)
+        result["cpu_baseline"] = cpu_baseline(args.model, args.cpu_batch)
     return result
 
 
-def cpu_baseline(batch: int):
+def cpu_baseline(model: str, batch: int):
     """The oracle as it stands, timed on the host cores on a bounded sample: the same network (all
-    54 layers x 3 passes + the 161-tensor LARS step) at a small batch."""
+    layers x 3 passes + the LARS step over the model's parameter list) at a small batch."""
     import numpy as np
     import oracle
     from paper_1709_05011_amd import synth
 
-    shapes = synth.resnet50_convs(batch) + [synth.resnet50_fc(batch)]
+    shapes, _, weight_decay = model_shapes(synth, model, batch)
     cache = {}
 
     def data(cs):
@@ -229,7 +240,7 @@ def cpu_baseline(batch: int):
 
     for cs in shapes:
         data(cs)
-    sizes = synth.resnet50_param_numels()
+    sizes = synth.alexnet_bn_param_numels() if model == "alexnet_bn" else synth.resnet50_param_numels()
     w = [synth.normal((n,), 10) for n in sizes]
     g = [synth.normal((n,), 11, std=0.01) for n in sizes]
     v = [np.zeros(n, np.float32) for n in sizes]
@@ -241,10 +252,10 @@ def cpu_baseline(batch: int):
             oracle.conv2d_bwd_data(dy, wt, (cs.h, cs.w), cs.stride, cs.pad, oracle.NHWC)
         oracle.conv2d_bwd_weight(x, dy, (cs.r, cs.s), cs.stride, cs.pad, oracle.NHWC)
     t1 = time.perf_counter()
-    oracle.lars_step(w, g, v, 0.001, 0.9, 5e-5, 0.5)
+    oracle.lars_step(w, g, v, 0.001, 0.9, weight_decay, 0.5)
     t2 = time.perf_counter()
     return {"value": round(batch / (t2 - t0), 3), "unit": "images/s", "cores": oracle.threads(), "kind": "oracle",
-            "sample": f"whole ResNet-50 step (54 layers x fwd/bwd_data/bwd_weight + 161-tensor LARS) at batch {batch}: "
+            "sample": f"whole {model} step ({len(shapes)} layers x fwd/bwd_data/bwd_weight + {len(sizes)}-tensor LARS) at batch {batch}: "
                       f"conv {t1 - t0:.1f} s, LARS {t2 - t1:.2f} s",
             "lars_GBps": round(LARS_BYTES_PER_PARAM * sum(sizes) / (t2 - t1) / 1e9, 2)}
 
@@ -361,6 +372,8 @@ def main():
                     help="bf16: BASELINE configs[4] (bf16 activations/weights, fp32 sums, fp32 master weights; batch 512)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
     ap.add_argument("--cpu-batch", type=int, default=4)
+    ap.add_argument("--model", choices=["resnet50", "alexnet_bn"], default="resnet50",
+                    help="network whose layer shapes and parameter list make the step (default: the metric's ResNet-50)")
     ap.add_argument("--sweep", action="store_true")
     ap.add_argument("--only", type=int, nargs="*", help="sweep: shape numbers to run")
     ap.add_argument("--iters", type=int, default=10)
@@ -378,7 +391,7 @@ def main():
     elif args.lars:
         res = run_lars(args)
     else:
-        res = run_resnet50_step(args)
+        res = run_train_step(args)
     print(json.dumps(res), flush=True)
 
 

@@ -128,6 +128,25 @@ lc_conv_desc as_f32(const lc_conv_desc* d) {
     return f;
 }
 
+// A window that covers the whole (unpadded) input -- a fully connected layer written as a convolution -- is
+// the same sums as a 1x1 convolution over one pixel with c*h*w channels: the (c, window) index of the filter
+// and the (c, pixel) index of the input run in the same order in either layout.  Rewriting it so matters for
+// backward-data, where the general formulation would visit every (pixel, tap) pair and find all but one
+// empty.  Returns d itself when the rewrite does not apply (or d is not a valid descriptor to begin with).
+const lc_conv_desc* whole_window_as_1x1(const lc_conv_desc* d, lc_conv_desc* store) {
+    if (!d || d->n <= 0 || d->c <= 0 || d->h <= 0 || d->w <= 0 || d->k <= 0 || d->stride_h <= 0 || d->stride_w <= 0) return d;
+    if (d->pad_h != 0 || d->pad_w != 0 || d->r != d->h || d->s != d->w || (d->h == 1 && d->w == 1)) return d;
+    if (d->layout != LC_NCHW && d->layout != LC_NHWC) return d;
+    const long long cc = (long long)d->c * d->h * d->w;
+    if (cc > 0x7fffffffLL) return d;
+    *store = *d;
+    store->c = (int)cc;
+    store->h = store->w = store->r = store->s = 1;
+    store->stride_h = store->stride_w = 1;
+    store->layout = LC_NHWC;              // with one pixel the two layouts coincide
+    return store;
+}
+
 lc_status make_plan(const lc_conv_desc* d, lc_pass pass, Plan* pl) {
     const lc_status st = check_desc(d, &pl->P, &pl->Q);
     if (st != LC_OK) return st;
@@ -235,6 +254,8 @@ extern "C" lc_status conv2d_out_shape(const lc_conv_desc* desc, int* p, int* q) 
 }
 
 extern "C" size_t conv2d_workspace_bytes(const lc_conv_desc* desc, lc_pass pass) {
+    lc_conv_desc canon;
+    desc = whole_window_as_1x1(desc, &canon);
     Plan pl;
     if (make_plan(desc, pass, &pl) != LC_OK) return 0;
     return pl.total;
@@ -242,6 +263,8 @@ extern "C" size_t conv2d_workspace_bytes(const lc_conv_desc* desc, lc_pass pass)
 
 extern "C" lc_status conv2d_fwd(const lc_conv_desc* d, const void* x, const void* w, void* y,
                                 void* workspace, size_t workspace_bytes, void* hip_stream) {
+    lc_conv_desc canon;
+    d = whole_window_as_1x1(d, &canon);
     Plan pl;
     lc_status st = make_plan(d, LC_PASS_FWD, &pl);
     if (st != LC_OK) return st;
@@ -279,6 +302,8 @@ extern "C" lc_status conv2d_fwd(const lc_conv_desc* d, const void* x, const void
 
 extern "C" lc_status conv2d_bwd_data(const lc_conv_desc* d, const void* dy, const void* w, void* dx,
                                      void* workspace, size_t workspace_bytes, void* hip_stream) {
+    lc_conv_desc canon;
+    d = whole_window_as_1x1(d, &canon);
     Plan pl;
     lc_status st = make_plan(d, LC_PASS_BWD_DATA, &pl);
     if (st != LC_OK) return st;
@@ -329,6 +354,8 @@ extern "C" lc_status conv2d_bwd_data(const lc_conv_desc* d, const void* dy, cons
 
 extern "C" lc_status conv2d_bwd_weight(const lc_conv_desc* d, const void* x, const void* dy, float* dw,
                                        void* workspace, size_t workspace_bytes, void* hip_stream) {
+    lc_conv_desc canon;
+    d = whole_window_as_1x1(d, &canon);
     Plan pl;
     lc_status st = make_plan(d, LC_PASS_BWD_WEIGHT, &pl);
     if (st != LC_OK) return st;

@@ -29,6 +29,7 @@ SHAPES = {
     "odd_channels": (2, 6, 9, 9, 10, 3, 3, 1, 1),
     "asymmetric": (2, 8, 11, 9, 12, 3, 2, (2, 1), (1, 0)),
     "full_window_fc": (4, 16, 6, 6, 40, 6, 6, 1, 0),
+    "full_window_rect_stride3_odd": (3, 5, 3, 5, 7, 3, 5, 3, 0),
     "single_everything": (1, 1, 5, 5, 1, 1, 1, 1, 0),
     "fc_1x1_on_1x1": (16, 512, 1, 1, 100, 1, 1, 1, 0),
     "tiny_cnn_conv1": (16, 3, 32, 32, 16, 3, 3, 1, 1),
