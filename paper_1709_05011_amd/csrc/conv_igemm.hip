@@ -594,6 +594,405 @@ __global__ void __launch_bounds__(256, 3) conv_gemm_sk_kernel(const GemmConv p) 
     }
 }
 
+// ------------------------------------------------------------------------------------------------
+// Persistent form of the main kernel.  The grid is one round of resident blocks; each block walks its own
+// sequence of segments -- whole tiles (one per round of the launch), then its share of the stream-K
+// k-steps -- as ONE software pipeline: the loads run two k-steps ahead of the MFMAs straight across tile
+// boundaries, so the memory latency at the start of a tile and the stores at its end are covered by MFMAs
+// of neighbouring tiles instead of standing alone.  What is paid once per tile is kept off the vector ALU
+// (every vector ALU instruction displaces MFMA issue time on this chip, and layers with few k-steps pay it
+// often): index arithmetic uses multiply-high division with constants from the host, and the tile is stored with buffer stores
+// whose row part of the address is a scalar offset and whose bounds are the buffer's size (rows) and bit 31
+// of the lane offset (columns).
+// ------------------------------------------------------------------------------------------------
+__device__ __forceinline__ int div_by(int n, unsigned mul, unsigned shift) {       // n / d for 0 <= n < 2^31, see magic_for()
+    return mul ? (int)(__umulhi((unsigned)n, mul) >> shift) : n;
+}
+
+template <int BM, int BN, bool SMALLC, bool BF16, bool UT, bool SCATTER>
+__global__ void __launch_bounds__(256, 3) conv_gemm_pk_kernel(const GemmConv p) {   // 3 blocks per compute unit: resident_blocks()
+    using E = typename OutT<BF16>::type;
+    constexpr int ES = (int)sizeof(E);
+    constexpr int EPC = BF16 ? 8 : 4;
+    constexpr int BK = 4 * EPC;
+    constexpr int LA = BM / 64, LB = BN / 64, LPT = LA + LB;
+    constexpr int WTM = BM / 2, WTN = BN / 2, TM = WTM / 32, TN = WTN / 32;
+    constexpr int STAGE = (BM + BN) * 16;
+    static_assert(BM % 64 == 0 && BN % 64 == 0, "tile shape");
+
+    __shared__ __attribute__((aligned(1024))) float lds[2 * STAGE];
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave >> 1, wn = wave & 1;
+    const int nbn = (p.N + BN - 1) / BN;
+    const int nkt = (p.Kg + BK - 1) / BK;
+    const E* __restrict__ A = static_cast<const E*>(p.a);
+    const E* __restrict__ B = static_cast<const E*>(p.b);
+    const int lrow = lane >> 2;
+    const int kq = (lane & 3) ^ swz(lrow);
+    const int Hi_ = p.Hi, Wi_ = p.Wi, Ci_ = p.Ci, R_ = p.R, S_ = p.S, M_ = p.M, N_ = p.N, Kg_ = p.Kg, ldd_ = p.ldd;
+    const int sh_ = p.sh, sw_ = p.sw, ph_ = p.ph, pw_ = p.pw, Po_ = p.Po;
+    const unsigned qmul = p.qo_mul, qsh = p.qo_shift, pmul = p.po_mul, psh = p.po_shift;
+    const int Qo_ = p.Qo;
+    const int frow = lane & 31, fhalf = lane >> 5;
+    const int fsw = swz(frow);
+    const int a_frag = (wm * WTM + frow) * 16, b_frag = BM * 16 + (wn * WTN + frow) * 16;
+
+    // ---- this block's segments: `rounds` whole tiles, then its stream-K range cut at the tile boundaries ----
+    const int G = gridDim.x, bid = blockIdx.x;
+    const int rounds = p.dp_tiles / G;                     // the launcher makes dp_tiles a multiple of the grid
+    int sk_it = 0, sk_len = 0;
+    if (bid < p.sk_blocks) {
+        sk_it = (int)((long long)bid * p.sk_iters / p.sk_blocks);
+        sk_len = (int)((long long)(bid + 1) * p.sk_iters / p.sk_blocks) - sk_it;
+    }
+    const int sk_tile = sk_it / nkt, sk_k0 = sk_it - sk_tile * nkt;
+    const int F = rounds * nkt + sk_len;                   // k-steps this block runs
+    if (F == 0) return;
+    auto segment = [&](int s, int& tile, int& k0, int& k1) __attribute__((always_inline)) {
+        if (s < rounds) {
+            tile = xcd_tile(s * G + bid, p.dp_tiles);
+            k0 = 0;
+            k1 = nkt;
+        } else {                                           // piece s - rounds of the stream-K range
+            const int t = sk_tile + (s - rounds);
+            tile = p.dp_tiles + t;
+            k0 = s == rounds ? sk_k0 : 0;
+            k1 = min(nkt, sk_it + sk_len - t * nkt);
+        }
+    };
+
+    // ---------------- load side ----------------
+    int l_seg = -1, l_k = 0, l_k1 = 0;                     // segment being loaded, next k-step, end
+    // generic addressing (pointer per row, position in the window per lane)
+    long long a_base[LA];
+    int a_h[LA], a_w[LA];
+    long long b_off[LB];
+    int kg = 0, c = 0, r = 0, s = 0;
+    // uniform-tap addressing
+    unsigned a_voff[LA], a_inv[LA], b_voff[LB];
+    __amdgpu_buffer_rsrc_t a_rsrc = __builtin_amdgcn_make_buffer_rsrc((void*)A, 0, 0, (int)kBufferWords3);
+    __amdgpu_buffer_rsrc_t b_rsrc = a_rsrc;
+    int u_kt = 0, u_c = 0, u_s = 0, u_r = 0;
+
+    auto loader_setup = [&](int tile, int k0) __attribute__((always_inline)) {
+        const int tm = tile / nbn;
+        const int m0 = tm * BM, n0 = (tile - tm * nbn) * BN;
+        if constexpr (UT) {
+            const int pq = Po_ * Qo_;
+            const int img0 = m0 / pq;
+            const int phb = max(ph_, 0), pwb = max(pw_, 0);
+            const int taps = R_ * S_;
+            const unsigned full = taps >= 32 ? ~0u : (1u << taps) - 1u;
+            unsigned rep = 0;
+            for (int rr = 0; rr < R_; ++rr) rep |= 1u << (rr * S_);
+#pragma unroll
+            for (int i = 0; i < LA; ++i) {
+                const int m = m0 + (i * 4 + wave) * 16 + lrow;
+                const int t = div_by(m, qmul, qsh), qo = m - t * Qo_;
+                const int img = div_by(t, pmul, psh), po = t - img * Po_;
+                const int h0 = po * sh_ - ph_, w0 = qo * sw_ - pw_;
+                // taps of this pixel's window inside the image: rows rlo..rhi, columns slo..shi
+                int rlo = max(0, -h0), rhi = min(R_ - 1, Hi_ - 1 - h0);
+                int slo = max(0, -w0), shi = min(S_ - 1, Wi_ - 1 - w0);
+                const bool ok = (m < M_) & (rlo <= rhi) & (slo <= shi);
+                rlo = min(rlo, R_ - 1);
+                rhi = max(rhi, 0);
+                slo = min(slo, S_ - 1);
+                const int sspan = max(shi - slo, 0);
+                const unsigned hm = (full << (rlo * S_)) & (full >> ((R_ - 1 - rhi) * S_));
+                const unsigned wmk = rep * (((2u << sspan) - 1u) << slo);
+                a_inv[i] = ok ? ~(hm & wmk) : ~0u;
+                a_voff[i] = ok ? (unsigned)(((((img - img0) * Hi_ + h0 + phb) * Wi_) + w0 + pwb) * Ci_ * ES + kq * 16) : 0u;
+            }
+#pragma unroll
+            for (int i = 0; i < LB; ++i) {
+                const int nl = (i * 4 + wave) * 16 + lrow;
+                b_voff[i] = (n0 + nl < N_) ? (unsigned)(nl * Kg_ * ES + kq * 16) : kBufferBytes;
+            }
+            const long long a_first = ((long long)img0 * Hi_ * Wi_ - ((long long)phb * Wi_ + pwb)) * Ci_;
+            a_rsrc = __builtin_amdgcn_make_buffer_rsrc((void*)(A + a_first), 0, (int)kBufferBytes, (int)kBufferWords3);
+            b_rsrc = __builtin_amdgcn_make_buffer_rsrc((void*)(B + (long long)n0 * Kg_), 0, (int)kBufferBytes, (int)kBufferWords3);
+            u_kt = k0;
+            const int kg0 = k0 * BK, rs0 = kg0 / Ci_;
+            u_c = kg0 - rs0 * Ci_;
+            u_r = rs0 / S_;
+            u_s = rs0 - u_r * S_;
+        } else {
+#pragma unroll
+            for (int i = 0; i < LA; ++i) {
+                const int m = m0 + (i * 4 + wave) * 16 + lrow;
+                if (m < M_) {
+                    const int t = div_by(m, qmul, qsh), qo = m - t * Qo_;
+                    const int img = div_by(t, pmul, psh), po = t - img * Po_;
+                    a_h[i] = po * sh_ - ph_;
+                    a_w[i] = qo * sw_ - pw_;
+                    a_base[i] = (long long)img * Hi_ * Wi_ * Ci_;
+                } else {
+                    a_h[i] = -(1 << 28);              // every tap fails the bounds test
+                    a_w[i] = 0;
+                    a_base[i] = 0;
+                }
+            }
+#pragma unroll
+            for (int i = 0; i < LB; ++i) {
+                const int n = n0 + (i * 4 + wave) * 16 + lrow;
+                b_off[i] = n < N_ ? (long long)n * Kg_ : -1;
+            }
+            kg = k0 * BK + kq * EPC;
+            const int rs = kg / Ci_;
+            c = kg - rs * Ci_;
+            r = rs / S_;
+            s = rs - r * S_;
+        }
+    };
+
+    float4 g[LPT];                                // the k-step in flight between global memory and LDS
+    auto gload_tile = [&]() __attribute__((always_inline)) {
+        if constexpr (UT) {
+            const int tap = u_r * S_ + u_s;
+            const unsigned up = 31u - (unsigned)tap;
+            const int a_soff = ((u_r * Wi_ + u_s) * Ci_ + u_c) * ES;
+            const int b_soff = u_kt * BK * ES;
+#pragma unroll
+            for (int l = 0; l < LA; ++l) {
+                const unsigned vo = ((a_inv[l] << up) & kBufferBytes) | a_voff[l];
+                g[l] = __builtin_bit_cast(float4, __builtin_amdgcn_raw_buffer_load_b128(a_rsrc, (int)vo, a_soff, 0));
+            }
+#pragma unroll
+            for (int l = 0; l < LB; ++l)
+                g[LA + l] = __builtin_bit_cast(float4, __builtin_amdgcn_raw_buffer_load_b128(b_rsrc, (int)b_voff[l], b_soff, 0));
+            ++u_kt;
+            u_c += BK;
+            const bool wrap = u_c == Ci_;
+            u_c = wrap ? 0 : u_c;
+            u_s += wrap ? 1 : 0;
+            const bool wrap2 = u_s == S_;
+            u_s = wrap2 ? 0 : u_s;
+            u_r += wrap2 ? 1 : 0;
+        } else {
+            const bool kok = r < R_;              // same as kg < Kg
+#pragma unroll
+            for (int l = 0; l < LA; ++l) {
+                const int h = a_h[l] + r, w = a_w[l] + s;
+                const bool ok = kok & ((unsigned)h < (unsigned)Hi_) & ((unsigned)w < (unsigned)Wi_);
+                g[l] = load_global16(pick(ok, A + a_base[l] + ((long long)h * Wi_ + w) * Ci_ + c, g_zero_chunk));
+            }
+#pragma unroll
+            for (int l = 0; l < LB; ++l)
+                g[LA + l] = load_global16(pick(kok & (b_off[l] >= 0), B + b_off[l] + kg, g_zero_chunk));
+            kg += BK;
+            c += BK;
+            if (SMALLC) {
+                while (c >= Ci_) {
+                    c -= Ci_;
+                    if (++s == S_) {
+                        s = 0;
+                        ++r;
+                    }
+                }
+            } else {
+                const bool wrap = c >= Ci_;
+                c = wrap ? c - Ci_ : c;
+                s += wrap ? 1 : 0;
+                const bool wrap2 = s == S_;
+                s = wrap2 ? 0 : s;
+                r += wrap2 ? 1 : 0;
+            }
+        }
+    };
+    // fetch the next k-step of the block's sequence (the caller knows there is one)
+    auto load_step = [&]() __attribute__((always_inline)) {
+        if (l_k == l_k1) {
+            int tile;
+            ++l_seg;
+            segment(l_seg, tile, l_k, l_k1);
+            loader_setup(tile, l_k);
+        }
+        gload_tile();
+        ++l_k;
+    };
+    auto sstore = [&](int buf) __attribute__((always_inline)) {
+        float* base = lds + buf * STAGE + wave * 256 + lane * 4;
+#pragma unroll
+        for (int l = 0; l < LPT; ++l)
+            *reinterpret_cast<float4*>(base + (l < LA ? l * 1024 : BM * 16 + (l - LA) * 1024)) = g[l];
+    };
+
+    // ---------------- compute side ----------------
+    f32x16 acc[TM][TN];
+    float4 fa[2][TM], fb[2][TN];
+    auto read_frags = [&](int buf, int k8, int slot) __attribute__((always_inline)) {
+        const float* base = lds + buf * STAGE;
+        const int ch = ((2 * k8 + fhalf) ^ fsw) * 4;
+#pragma unroll
+        for (int i = 0; i < TM; ++i) fa[slot][i] = *reinterpret_cast<const float4*>(base + a_frag + i * 32 * 16 + ch);
+#pragma unroll
+        for (int j = 0; j < TN; ++j) fb[slot][j] = *reinterpret_cast<const float4*>(base + b_frag + j * 32 * 16 + ch);
+    };
+    // one group of MFMAs: every 32x32 tile of the wave advanced by one k-slice
+    auto mfma_group = [&](int slot, int e) __attribute__((always_inline)) {
+        if (BF16 && e != 0) return;
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j) {
+                if constexpr (BF16)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, fa[slot][i]),
+                                                                        __builtin_bit_cast(bf16x8, fb[slot][j]), acc[i][j], 0, 0, 0);
+                else
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(elem(fa[slot][i], e), elem(fb[slot][j], e), acc[i][j], 0, 0, 0);
+            }
+    };
+    auto clear_acc = [&]() __attribute__((always_inline)) {
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+    };
+
+    int c_seg = 0, c_tile, c_k0, c_k, c_k1;
+    segment(0, c_tile, c_k0, c_k1);
+    c_k = c_k0;
+    // store (or park) the finished segment
+    auto epilogue = [&]() __attribute__((always_inline)) {
+        const int tm = c_tile / nbn;
+        const int m0 = tm * BM, n0 = (c_tile - tm * nbn) * BN;
+        if (c_k0 == 0 && c_k1 == nkt) {
+            if constexpr (SCATTER) {
+                // Row (img, po, qo) owns the cell [po*esh, +esh) x [qo*esw, +esw) of the [imgs][Ho][Wo][ldd] result: its
+                // value goes to the cell's corner, zeros to the rest.  An accumulator register holds one row in lanes
+                // 0..31 and the row four further down in lanes 32..63; both rows are wave-uniform, so their pixel
+                // offsets are computed on the scalar unit (relative to the tile's first pixel) and each half is
+                // stored by its own instruction, the other half's lanes parked past the end of the buffer.
+                const int Ho_ = p.Ho, Wo_ = p.Wo, esh_ = p.esh, esw_ = p.esw;
+                int t0 = div_by(m0, qmul, qsh);
+                const int q0 = m0 - t0 * Qo_, i0 = div_by(t0, pmul, psh), p0 = t0 - i0 * Po_;
+                const long long first_px = ((long long)i0 * Ho_ + p0 * esh_) * Wo_ + q0 * esw_;
+                const __amdgpu_buffer_rsrc_t d_rsrc = __builtin_amdgcn_make_buffer_rsrc(
+                    (void*)(static_cast<E*>(p.d) + first_px * ldd_), 0, (int)kBufferBytes, (int)kBufferWords3);
+                unsigned d_voff[2][TN];
+#pragma unroll
+                for (int j = 0; j < TN; ++j) {
+                    const int col = n0 + wn * WTN + j * 32 + (lane & 31);
+                    d_voff[0][j] = (col < N_ && lane < 32) ? (unsigned)(col * ES) : kBufferBytes;
+                    d_voff[1][j] = (col < N_ && lane >= 32) ? (unsigned)(col * ES) : kBufferBytes;
+                }
+#pragma unroll
+                for (int i = 0; i < TM; ++i)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v)
+#pragma unroll
+                        for (int hs = 0; hs < 2; ++hs) {
+                            const int m = m0 + wm * WTM + i * 32 + 8 * (v >> 2) + 4 * hs + (v & 3);
+                            if (m >= M_) continue;
+                            const int t = div_by(m, qmul, qsh), qo = m - t * Qo_;
+                            const int img = div_by(t, pmul, psh), po = t - img * Po_;
+                            for (int dy = 0; dy < esh_ && po * esh_ + dy < Ho_; ++dy)
+                                for (int dx = 0; dx < esw_ && qo * esw_ + dx < Wo_; ++dx) {
+                                    const long long px = ((long long)img * Ho_ + po * esh_ + dy) * Wo_ + qo * esw_ + dx;
+                                    const int soff = (int)(px - first_px) * ldd_ * ES;
+                                    const bool corner = (dy | dx) == 0;
+#pragma unroll
+                                    for (int j = 0; j < TN; ++j) {
+                                        const float val = corner ? acc[i][j][v] : 0.f;
+                                        if constexpr (BF16)
+                                            __builtin_amdgcn_raw_buffer_store_b16((short)lc_bf16_rne(val), d_rsrc, (int)d_voff[hs][j], soff, 0);
+                                        else
+                                            __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(val), d_rsrc, (int)d_voff[hs][j], soff, 0);
+                                    }
+                                }
+                        }
+            } else {
+                // rows: scalar offset, cut off at M by the size of the buffer; columns: lane offset, bit 31 past N
+                const long long rows_left = (long long)(M_ - m0) * ldd_ * ES;
+                const __amdgpu_buffer_rsrc_t d_rsrc = __builtin_amdgcn_make_buffer_rsrc(
+                    (void*)(static_cast<E*>(p.d) + (long long)m0 * ldd_), 0, (int)(rows_left > 0x7fffffffLL ? 0x7fffffffLL : rows_left),
+                    (int)kBufferWords3);
+                unsigned d_voff[TN];
+#pragma unroll
+                for (int j = 0; j < TN; ++j) {
+                    const int col = n0 + wn * WTN + j * 32 + (lane & 31);
+                    d_voff[j] = col < N_ ? (unsigned)((4 * (lane >> 5) * ldd_ + col) * ES) : kBufferBytes;
+                }
+#pragma unroll
+                for (int i = 0; i < TM; ++i)
+#pragma unroll
+                    for (int v = 0; v < 16; v += 2) {
+                        // accumulator registers v and v + 1 are rows r0 and r0 + 1 of the same column
+                        const int r0 = wm * WTM + i * 32 + 8 * (v >> 2) + (v & 3);
+                        const int soff = r0 * ldd_ * ES;
+#pragma unroll
+                        for (int j = 0; j < TN; ++j) {
+                            if constexpr (BF16) {
+                                typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+                                typedef float f32x2 __attribute__((ext_vector_type(2)));
+                                const f32x2 pr = {acc[i][j][v], acc[i][j][v + 1]};
+                                const unsigned u = __builtin_bit_cast(unsigned, __builtin_convertvector(pr, bf16x2));
+                                __builtin_amdgcn_raw_buffer_store_b16((short)(u & 0xffffu), d_rsrc, (int)d_voff[j], soff, 0);
+                                __builtin_amdgcn_raw_buffer_store_b16((short)(u >> 16), d_rsrc, (int)d_voff[j], soff + ldd_ * ES, 0);
+                            } else {
+                                __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(acc[i][j][v]), d_rsrc, (int)d_voff[j], soff, 0);
+                                __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(acc[i][j][v + 1]), d_rsrc, (int)d_voff[j], soff + ldd_ * ES, 0);
+                            }
+                        }
+                    }
+            }
+        } else {
+            // part of a tile: it is the first piece of this block's stream-K range (slot 2*bid) or the last (2*bid + 1)
+            float* part = p.partial + ((size_t)2 * bid + (c_seg == rounds ? 0 : 1)) * (BM * BN);
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) part[partial_index<TM, TN>(wave, i, j, v, lane)] = acc[i][j][v];
+        }
+    };
+
+    // ---------------- the pipeline ----------------
+    load_step();                                  // k-step 0 of the sequence
+    sstore(0);
+    if (F > 1) load_step();                       // k-step 1
+    clear_acc();
+    lds_barrier();
+    read_frags(0, 0, 0);
+    // One k-step out of LDS buffer `cur` (a literal at both calls)
+    auto step = [&](int cur, int f) __attribute__((always_inline)) {
+        read_frags(cur, 1, 1);
+        mfma_group(0, 0);
+        mfma_group(0, 1);
+        __builtin_amdgcn_sched_barrier(0);
+        sstore(cur ^ 1);                          // k-step f + 1: its buffer was last read one step ago
+        mfma_group(0, 2);
+        __builtin_amdgcn_sched_barrier(0);
+        if (f + 2 < F) load_step();               // k-step f + 2 into the registers just stored
+        mfma_group(0, 3);
+        __builtin_amdgcn_sched_barrier(0);
+        lds_barrier();
+        read_frags(cur ^ 1, 0, 0);                // first half of k-step f + 1
+#pragma unroll
+        for (int e = 0; e < 4; ++e) mfma_group(1, e);
+        if (++c_k == c_k1) {                      // the segment is complete: store it, the next step starts a new one
+            __builtin_amdgcn_sched_barrier(0);
+            epilogue();
+            clear_acc();
+            ++c_seg;
+            segment(c_seg, c_tile, c_k0, c_k1);
+            c_k = c_k0;
+        }
+    };
+    // The last step runs through the same code: what it stores to LDS, reads back as "next" fragments and
+    // takes as the next segment is never used.
+    for (int f = 0; f < F; f += 2) {
+        step(0, f);
+        if (f + 1 < F) step(1, f + 1);
+    }
+}
+
 // Adds the parts of every tile that stream-K blocks split between them, in k order, and stores the tile.
 // Block (t, v) handles accumulator register v of every 32x32 MFMA tile of stream-K tile t, with the thread
 // geometry of the main kernel: 16 blocks per tile keep the whole chip busy on what is a small reduction.
@@ -1267,12 +1666,69 @@ bool uniform_tap_ok(const GemmConv& p) {
     return a_span < 0x7fff0000LL && b_span < 0x7fff0000LL;
 }
 
+// Constants for div_by(): n / d == umulhi(n, mul) >> shift for 0 <= n < 2^31 (mul == 0 stands for d == 1).
+// With L = ceil(log2 d) and mul = ceil(2^(31+L) / d) the error term n * (mul*d - 2^(31+L)) stays below 2^(31+L).
+void magic_for(int d, unsigned* mul, unsigned* shift) {
+    if (d <= 1) {
+        *mul = 0;
+        *shift = 0;
+        return;
+    }
+    int L = 0;
+    while ((1ll << L) < d) ++L;
+    *mul = (unsigned)((((unsigned long long)1 << (31 + L)) + (unsigned)d - 1) / (unsigned)d);
+    *shift = (unsigned)(L - 1);
+}
+
 template <int BM, int BN, bool SMALLC, bool BF16>
 lc_status launch_conv_sk(GemmConv p, hipStream_t stream) {
     long long tiles;
     int nkt;
     if (!sk_geometry<BM, BN>(p, &tiles, &nkt)) return LC_ERR_UNSUPPORTED;
     SkPlan pl = sk_plan(tiles, nkt, resident_blocks());
+    static const bool tile_kernel = [] {
+        const char* e = getenv("LARSCONV_KERNEL");          // LARSCONV_KERNEL=tile: one block per tile (comparison runs)
+        return e && strcmp(e, "tile") == 0;
+    }();
+    if (!tile_kernel) {
+        // persistent kernel: one round of resident blocks, each taking dp_tiles / grid whole tiles and then its
+        // stream-K range; without a workspace for partial tiles the ranges are whole tiles
+        const int resident = resident_blocks();
+        if (pl.sk_blocks > 0 && !p.partial) pl.sk_blocks = 0;
+        if (pl.sk_blocks == 0) {
+            const long long rest = tiles % resident;
+            pl.dp_tiles = (int)(tiles - rest);
+            pl.sk_blocks = (int)rest;
+            pl.sk_iters = rest * nkt;
+        }
+        p.dp_tiles = pl.dp_tiles;
+        p.sk_blocks = pl.sk_blocks;
+        p.sk_iters = pl.sk_iters;
+        magic_for(p.Qo, &p.qo_mul, &p.qo_shift);
+        magic_for(p.Po, &p.po_mul, &p.po_shift);
+        const unsigned grid = pl.dp_tiles > 0 ? (unsigned)resident : (unsigned)pl.sk_blocks;
+        const bool whole = pl.sk_blocks == 0 || pl.sk_iters == (long long)pl.sk_blocks * nkt;
+        const bool ut = !SMALLC && uniform_tap_ok<BM, BN>(p);
+        if (p.scatter) {                      // the scatter epilogue addresses the result relative to the tile's first pixel
+            const long long span = ((long long)BM / ((long long)p.Po * p.Qo) + 2) * p.Ho * p.Wo * p.ldd * (p.bf16 ? 2 : 4);
+            if (span >= 0x7fff0000LL) return LC_ERR_UNSUPPORTED;
+        }
+        if (p.scatter && !SMALLC) {
+            if (ut)
+                hipLaunchKernelGGL((conv_gemm_pk_kernel<BM, BN, false, BF16, true, true>), dim3(grid), dim3(256), 0, stream, p);
+            else
+                hipLaunchKernelGGL((conv_gemm_pk_kernel<BM, BN, false, BF16, false, true>), dim3(grid), dim3(256), 0, stream, p);
+        } else if (p.scatter) {
+            return LC_ERR_UNSUPPORTED;        // the scatter epilogue belongs to 1x1 windows, which never have fewer channels than a k-step
+        } else if (ut) {
+            hipLaunchKernelGGL((conv_gemm_pk_kernel<BM, BN, false, BF16, true, false>), dim3(grid), dim3(256), 0, stream, p);
+        } else {
+            hipLaunchKernelGGL((conv_gemm_pk_kernel<BM, BN, SMALLC, BF16, false, false>), dim3(grid), dim3(256), 0, stream, p);
+        }
+        if (!whole)
+            hipLaunchKernelGGL((conv_gemm_fixup_kernel<BM, BN, BF16>), dim3((unsigned)(tiles - pl.dp_tiles), 16), dim3(256), 0, stream, p);
+        return lc_end_call();
+    }
     if (pl.sk_blocks > 0 && !p.partial) {                    // no workspace for the parts: whole tiles only
         pl.dp_tiles = (int)tiles;
         pl.sk_blocks = 0;
@@ -1316,6 +1772,9 @@ size_t lc_conv_gemm_workspace(const GemmConv& p) {
 bool lc_conv_gemm_bf16_native(const GemmConv& p) { return p.bf16 && use_main_kernel(p); }
 
 lc_status lc_launch_conv_gemm(const GemmConv& p, hipStream_t stream) {
+    static const int narrow_kg = getenv("LARSCONV_NARROW_KG") ? atoi(getenv("LARSCONV_NARROW_KG")) : 0;   // experiment
+    if (narrow_kg && p.Kg <= narrow_kg && use_main_kernel(p) && p.Ci >= 32)
+        return p.bf16 ? launch_conv_sk<128, 64, false, true>(p, stream) : launch_conv_sk<128, 64, false, false>(p, stream);
     if (p.bf16) {
         if (!use_main_kernel(p)) return LC_ERR_UNSUPPORTED;       // the caller converts to fp32 instead
         if (p.Ci < 32) return p.N > 64 ? launch_conv_sk<128, 128, true, true>(p, stream) : launch_conv_sk<128, 64, true, true>(p, stream);

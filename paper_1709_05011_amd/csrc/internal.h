@@ -61,6 +61,8 @@ struct GemmConv {
     int dp_tiles, sk_blocks;
     long long sk_iters;
     float* partial;
+    // multiply-high division constants for Qo and Po (filled in by the launcher)
+    unsigned qo_mul, qo_shift, po_mul, po_shift;
     int bf16;           // operands a, b and result d are bf16 (sums stay fp32)
 };
 lc_status lc_launch_conv_gemm(const GemmConv& p, hipStream_t stream);
