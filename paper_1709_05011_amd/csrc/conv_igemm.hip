@@ -308,292 +308,6 @@ typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
 constexpr unsigned kBufferWords3 = 0x00020000u;       // raw buffer, 32-bit data format
 constexpr unsigned kBufferBytes = 0x80000000u;        // buffer size given to the hardware; offsets with bit 31 set read zeros
 
-template <int BM, int BN, bool SMALLC, bool BF16, bool UT = false>
-__global__ void __launch_bounds__(256, 3) conv_gemm_sk_kernel(const GemmConv p) {   // 3 blocks per compute unit: resident_blocks()
-    using E = typename OutT<BF16>::type;                        // operand element type
-    constexpr int EPC = BF16 ? 8 : 4;                           // elements per 16-byte chunk
-    constexpr int BK = 4 * EPC;                                 // elements per k-step: one 64-byte LDS row
-    constexpr int LA = BM / 64, LB = BN / 64, LPT = LA + LB;   // 16-row blocks (= 16-byte loads) per thread and tile
-    constexpr int WTM = BM / 2, WTN = BN / 2, TM = WTM / 32, TN = WTN / 32;
-    constexpr int STAGE = (BM + BN) * 16;                       // floats per LDS buffer: A rows then B rows, 64 B each
-    static_assert(BM % 64 == 0 && BN % 64 == 0, "tile shape");
-
-    __shared__ __attribute__((aligned(1024))) float lds[2 * STAGE];
-
-    const int tid = threadIdx.x, lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform, lives in an SGPR
-    const int wm = wave >> 1, wn = wave & 1;
-    const int nbn = (p.N + BN - 1) / BN;
-    const int nkt = (p.Kg + BK - 1) / BK;
-
-    // this block's range of (tile, k-step) pairs, as positions in the end-to-end sequence of k-steps
-    int it, it_end, sk_id = -1;
-    if ((int)blockIdx.x < p.dp_tiles) {
-        it = xcd_tile(blockIdx.x, p.dp_tiles) * nkt;
-        it_end = it + nkt;
-    } else {
-        sk_id = blockIdx.x - p.dp_tiles;
-        const long long base = (long long)p.dp_tiles * nkt;
-        it = (int)(base + (long long)sk_id * p.sk_iters / p.sk_blocks);
-        it_end = (int)(base + (long long)(sk_id + 1) * p.sk_iters / p.sk_blocks);
-    }
-    const int it_begin = it;
-
-    const E* __restrict__ A = static_cast<const E*>(p.a);
-    const E* __restrict__ B = static_cast<const E*>(p.b);
-    // this lane's place in a 16-row block: row lane/4, LDS slot lane%4, global chunk slot ^ swz(row)
-    const int lrow = lane >> 2;
-    const int kq = (lane & 3) ^ swz(lrow);
-    // copies of the descriptor fields used in the main loop (the inline-assembly memory clobbers would
-    // otherwise make the compiler re-read them from the kernel arguments every iteration)
-    const int Hi_ = p.Hi, Wi_ = p.Wi, Ci_ = p.Ci, R_ = p.R, S_ = p.S;
-    // fragment addressing: lane reads row (lane & 31) of a 32-row MFMA tile, chunk 2*k8 + (lane >> 5)
-    const int frow = lane & 31, fhalf = lane >> 5;
-    const int fsw = swz(frow);
-    const int a_frag = (wm * WTM + frow) * 16, b_frag = BM * 16 + (wn * WTN + frow) * 16;
-
-    while (it < it_end) {
-        const int tile = it / nkt;
-        const int k0 = it - tile * nkt;
-        const int k1 = min(nkt, k0 + (it_end - it));
-        const int m0 = (tile / nbn) * BM, n0 = (tile % nbn) * BN;
-
-        long long a_base[LA];
-        int a_h[LA], a_w[LA];
-#pragma unroll
-        for (int i = 0; i < LA; ++i) {
-            const int m = m0 + (i * 4 + wave) * 16 + lrow;
-            if (m < p.M) {
-                const int qo = m % p.Qo, t = m / p.Qo;
-                const int po = t % p.Po, img = t / p.Po;
-                a_h[i] = po * p.sh - p.ph;
-                a_w[i] = qo * p.sw - p.pw;
-                a_base[i] = (long long)img * p.Hi * p.Wi * p.Ci;
-            } else {
-                a_h[i] = -(1 << 28);              // every tap fails the bounds test
-                a_w[i] = 0;
-                a_base[i] = 0;
-            }
-        }
-        long long b_off[LB];
-#pragma unroll
-        for (int i = 0; i < LB; ++i) {
-            const int n = n0 + (i * 4 + wave) * 16 + lrow;
-            b_off[i] = n < p.N ? (long long)n * p.Kg : -1;
-        }
-        // position of this lane's 16-byte chunk inside the filter window at k-step k0
-        int kg = k0 * BK + kq * EPC;
-        int c = kg % p.Ci, r, s;
-        {
-            const int rs = kg / p.Ci;
-            s = rs % p.S;
-            r = rs / p.S;
-        }
-
-        // UT: per-lane byte offsets relative to the tile's first image (A) and first filter row (B), the mask
-        // of taps that fall outside the image for each of this lane's rows, and the scalar position
-        unsigned a_voff[LA], a_inv[LA], b_voff[LB];
-        __amdgpu_buffer_rsrc_t a_rsrc, b_rsrc;
-        int u_kt = 0, u_c = 0, u_s = 0, u_r = 0;
-        if constexpr (UT) {
-            constexpr int ES = (int)sizeof(E);
-            const int pq = p.Po * p.Qo;
-            const int img0 = m0 / pq;
-            const int phb = max(p.ph, 0), pwb = max(p.pw, 0);
-#pragma unroll
-            for (int i = 0; i < LA; ++i) {
-                const int m = m0 + (i * 4 + wave) * 16 + lrow;
-                a_voff[i] = 0;
-                a_inv[i] = ~0u;
-                if (m < p.M) {
-                    const int qo = m % p.Qo, t = m / p.Qo;
-                    const int po = t % p.Po, img = t / p.Po;
-                    const int h0 = po * p.sh - p.ph, w0 = qo * p.sw - p.pw;
-                    a_voff[i] = (unsigned)(((((img - img0) * Hi_ + h0 + phb) * Wi_) + w0 + pwb) * Ci_ * ES + kq * 16);
-                    unsigned inv = 0;
-                    for (int rr = 0; rr < R_; ++rr)
-                        for (int ss = 0; ss < S_; ++ss) {
-                            const bool bad = ((unsigned)(h0 + rr) >= (unsigned)Hi_) | ((unsigned)(w0 + ss) >= (unsigned)Wi_);
-                            inv |= (bad ? 1u : 0u) << (rr * S_ + ss);
-                        }
-                    a_inv[i] = inv;
-                }
-            }
-#pragma unroll
-            for (int i = 0; i < LB; ++i) {
-                const int nl = (i * 4 + wave) * 16 + lrow;
-                b_voff[i] = (n0 + nl < p.N) ? (unsigned)(nl * p.Kg * ES + kq * 16) : kBufferBytes;
-            }
-            const long long a_first = ((long long)img0 * Hi_ * Wi_ - ((long long)phb * Wi_ + pwb)) * Ci_;
-            a_rsrc = __builtin_amdgcn_make_buffer_rsrc((void*)(A + a_first), 0, (int)kBufferBytes, (int)kBufferWords3);
-            b_rsrc = __builtin_amdgcn_make_buffer_rsrc((void*)(B + (long long)n0 * p.Kg), 0, (int)kBufferBytes, (int)kBufferWords3);
-            u_kt = k0;
-            const int kg0 = k0 * BK, rs0 = kg0 / Ci_;
-            u_c = kg0 - rs0 * Ci_;
-            u_s = rs0 % S_;
-            u_r = rs0 / S_;
-        }
-
-        float4 g[LPT];                            // the tile in flight between global memory and LDS
-        auto gload_one = [&](int l) {
-            const bool kok = r < R_;              // same as kg < Kg
-            if (l < LA) {
-                const int h = a_h[l] + r, w = a_w[l] + s;
-                const bool ok = kok & ((unsigned)h < (unsigned)Hi_) & ((unsigned)w < (unsigned)Wi_);
-                g[l] = load_global16(pick(ok, A + a_base[l] + ((long long)h * Wi_ + w) * Ci_ + c, g_zero_chunk));
-            } else {
-                g[l] = load_global16(pick(kok & (b_off[l - LA] >= 0), B + b_off[l - LA] + kg, g_zero_chunk));
-            }
-        };
-        auto advance = [&]() {
-            kg += BK;
-            c += BK;
-            if (SMALLC) {                         // fewer channels than a k-step: it spans several taps
-                while (c >= Ci_) {
-                    c -= Ci_;
-                    if (++s == S_) {
-                        s = 0;
-                        ++r;
-                    }
-                }
-            } else {                              // at most one wrap: written without branches
-                const bool wrap = c >= Ci_;
-                c = wrap ? c - Ci_ : c;
-                s += wrap ? 1 : 0;
-                const bool wrap2 = s == S_;
-                s = wrap2 ? 0 : s;
-                r += wrap2 ? 1 : 0;
-            }
-        };
-        auto gload_tile = [&]() {
-            if constexpr (UT) {
-                constexpr int ES = (int)sizeof(E);
-                const int tap = u_r * S_ + u_s;
-                const unsigned up = 31u - (unsigned)tap;                 // brings this tap's mask bit to bit 31
-                const int a_soff = ((u_r * Wi_ + u_s) * Ci_ + u_c) * ES;
-                const int b_soff = u_kt * BK * ES;
-#pragma unroll
-                for (int l = 0; l < LA; ++l) {
-                    const unsigned vo = ((a_inv[l] << up) & kBufferBytes) | a_voff[l];
-                    g[l] = __builtin_bit_cast(float4, __builtin_amdgcn_raw_buffer_load_b128(a_rsrc, (int)vo, a_soff, 0));
-                }
-#pragma unroll
-                for (int l = 0; l < LB; ++l)
-                    g[LA + l] = __builtin_bit_cast(float4, __builtin_amdgcn_raw_buffer_load_b128(b_rsrc, (int)b_voff[l], b_soff, 0));
-                // the step past the last one is fetched again instead (its data is never used)
-                // (scalar selects, no branches: the loop body stays one basic block)
-                const bool more = u_kt + 1 < nkt;
-                u_kt += more ? 1 : 0;
-                u_c += more ? BK : 0;
-                const bool wrap = u_c == Ci_;
-                u_c = wrap ? 0 : u_c;
-                u_s += wrap ? 1 : 0;
-                const bool wrap2 = u_s == S_;
-                u_s = wrap2 ? 0 : u_s;
-                u_r += wrap2 ? 1 : 0;
-                return;
-            }
-#pragma unroll
-            for (int l = 0; l < LPT; ++l) gload_one(l);
-            advance();
-        };
-        // registers -> LDS: lane (row lane/4, slot lane%4) of 16-row block (l*4 + wave): 16 B per lane in lane order
-        auto sstore = [&](int buf) {
-            float* base = lds + buf * STAGE + wave * 256 + lane * 4;
-#pragma unroll
-            for (int l = 0; l < LPT; ++l)
-                *reinterpret_cast<float4*>(base + (l < LA ? l * 1024 : BM * 16 + (l - LA) * 1024)) = g[l];
-        };
-
-        f32x16 acc[TM][TN];
-#pragma unroll
-        for (int i = 0; i < TM; ++i)
-#pragma unroll
-            for (int j = 0; j < TN; ++j)
-#pragma unroll
-                for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
-
-        float4 fa[2][TM], fb[2][TN];
-        auto read_frags = [&](int buf, int k8, int slot) {
-            const float* base = lds + buf * STAGE;
-            const int ch = ((2 * k8 + fhalf) ^ fsw) * 4;
-#pragma unroll
-            for (int i = 0; i < TM; ++i) fa[slot][i] = *reinterpret_cast<const float4*>(base + a_frag + i * 32 * 16 + ch);
-#pragma unroll
-            for (int j = 0; j < TN; ++j) fb[slot][j] = *reinterpret_cast<const float4*>(base + b_frag + j * 32 * 16 + ch);
-        };
-        // fp32: a chunk holds k = 4 values, MFMA e of 4 consumes value e; bf16: one MFMA (e == 0) consumes the chunk
-        auto mfma_e = [&](int slot, int e) {
-            if (BF16 && e != 0) return;
-#pragma unroll
-            for (int i = 0; i < TM; ++i)
-#pragma unroll
-                for (int j = 0; j < TN; ++j) {
-                    if constexpr (BF16)
-                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, fa[slot][i]),
-                                                                            __builtin_bit_cast(bf16x8, fb[slot][j]), acc[i][j], 0, 0, 0);
-                    else
-                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(elem(fa[slot][i], e), elem(fb[slot][j], e), acc[i][j], 0, 0, 0);
-                }
-        };
-
-        gload_tile();                             // k-step k0
-        sstore(0);
-        gload_tile();                             // k-step k0+1 (zeros past the end of the filter window)
-        lds_barrier();
-        read_frags(0, 0, 0);
-        // One k-step out of LDS buffer `cur` (a literal at every call, so that all LDS addresses are a register
-        // fixed for the whole tile plus an immediate).
-        auto step = [&](int cur) __attribute__((always_inline)) {
-            read_frags(cur, 1, 1);                // k = 8..15 of this step
-            mfma_e(0, 0);
-            mfma_e(0, 1);
-            __builtin_amdgcn_sched_barrier(0);
-            sstore(cur ^ 1);                      // next step: its buffer was last read one iteration ago
-            mfma_e(0, 2);
-            __builtin_amdgcn_sched_barrier(0);
-            gload_tile();                         // the step after next, into the registers just stored
-            mfma_e(0, 3);
-            __builtin_amdgcn_sched_barrier(0);
-            lds_barrier();
-            read_frags(cur ^ 1, 0, 0);            // k = 0..7 of the next step
-#pragma unroll
-            for (int e = 0; e < 4; ++e) mfma_e(1, e);
-        };
-        // The last k-step is peeled off so that the loop body is one basic block (a join between the fragment
-        // reads and the MFMAs that follow would make the compiler wait for the reads just issued).
-        int kt = k0, cur = 0;
-        for (; kt + 2 < k1; kt += 2) {
-            step(0);
-            step(1);
-        }
-        if (kt + 1 < k1) {
-            step(0);
-            cur = 1;
-        }
-        read_frags(cur, 1, 1);
-#pragma unroll
-        for (int e = 0; e < 4; ++e) mfma_e(0, e);
-#pragma unroll
-        for (int e = 0; e < 4; ++e) mfma_e(1, e);
-
-        if (k0 == 0 && k1 == nkt) {
-            store_tile<TM, TN, BF16>(p, acc, m0 + wm * WTM, n0 + wn * WTN, lane);
-        } else {
-            // part of a tile: first segment of this block's range -> slot 2*sk_id, last -> slot 2*sk_id + 1
-            float* part = p.partial + ((size_t)2 * sk_id + (it == it_begin ? 0 : 1)) * (BM * BN);
-#pragma unroll
-            for (int i = 0; i < TM; ++i)
-#pragma unroll
-                for (int j = 0; j < TN; ++j)
-#pragma unroll
-                    for (int v = 0; v < 16; ++v) part[partial_index<TM, TN>(wave, i, j, v, lane)] = acc[i][j][v];
-        }
-        it += k1 - k0;
-        lds_barrier();                            // everybody is done with the LDS buffers before the next segment
-    }
-}
-
 // ------------------------------------------------------------------------------------------------
 // Persistent form of the main kernel.  The grid is one round of resident blocks; each block walks its own
 // sequence of segments -- whole tiles (one per round of the launch), then its share of the stream-K
@@ -1686,64 +1400,37 @@ lc_status launch_conv_sk(GemmConv p, hipStream_t stream) {
     int nkt;
     if (!sk_geometry<BM, BN>(p, &tiles, &nkt)) return LC_ERR_UNSUPPORTED;
     SkPlan pl = sk_plan(tiles, nkt, resident_blocks());
-    static const bool tile_kernel = [] {
-        const char* e = getenv("LARSCONV_KERNEL");          // LARSCONV_KERNEL=tile: one block per tile (comparison runs)
-        return e && strcmp(e, "tile") == 0;
-    }();
-    if (!tile_kernel) {
-        // persistent kernel: one round of resident blocks, each taking dp_tiles / grid whole tiles and then its
-        // stream-K range; without a workspace for partial tiles the ranges are whole tiles
-        const int resident = resident_blocks();
-        if (pl.sk_blocks > 0 && !p.partial) pl.sk_blocks = 0;
-        if (pl.sk_blocks == 0) {
-            const long long rest = tiles % resident;
-            pl.dp_tiles = (int)(tiles - rest);
-            pl.sk_blocks = (int)rest;
-            pl.sk_iters = rest * nkt;
-        }
-        p.dp_tiles = pl.dp_tiles;
-        p.sk_blocks = pl.sk_blocks;
-        p.sk_iters = pl.sk_iters;
-        magic_for(p.Qo, &p.qo_mul, &p.qo_shift);
-        magic_for(p.Po, &p.po_mul, &p.po_shift);
-        const unsigned grid = pl.dp_tiles > 0 ? (unsigned)resident : (unsigned)pl.sk_blocks;
-        const bool whole = pl.sk_blocks == 0 || pl.sk_iters == (long long)pl.sk_blocks * nkt;
-        const bool ut = !SMALLC && uniform_tap_ok<BM, BN>(p);
-        if (p.scatter) {                      // the scatter epilogue addresses the result relative to the tile's first pixel
-            const long long span = ((long long)BM / ((long long)p.Po * p.Qo) + 2) * p.Ho * p.Wo * p.ldd * (p.bf16 ? 2 : 4);
-            if (span >= 0x7fff0000LL) return LC_ERR_UNSUPPORTED;
-        }
-        if (p.scatter && !SMALLC) {
-            if (ut)
-                hipLaunchKernelGGL((conv_gemm_pk_kernel<BM, BN, false, BF16, true, true>), dim3(grid), dim3(256), 0, stream, p);
-            else
-                hipLaunchKernelGGL((conv_gemm_pk_kernel<BM, BN, false, BF16, false, true>), dim3(grid), dim3(256), 0, stream, p);
-        } else if (p.scatter) {
-            return LC_ERR_UNSUPPORTED;        // the scatter epilogue belongs to 1x1 windows, which never have fewer channels than a k-step
-        } else if (ut) {
-            hipLaunchKernelGGL((conv_gemm_pk_kernel<BM, BN, false, BF16, true, false>), dim3(grid), dim3(256), 0, stream, p);
-        } else {
-            hipLaunchKernelGGL((conv_gemm_pk_kernel<BM, BN, SMALLC, BF16, false, false>), dim3(grid), dim3(256), 0, stream, p);
-        }
-        if (!whole)
-            hipLaunchKernelGGL((conv_gemm_fixup_kernel<BM, BN, BF16>), dim3((unsigned)(tiles - pl.dp_tiles), 16), dim3(256), 0, stream, p);
-        return lc_end_call();
-    }
-    if (pl.sk_blocks > 0 && !p.partial) {                    // no workspace for the parts: whole tiles only
-        pl.dp_tiles = (int)tiles;
-        pl.sk_blocks = 0;
-        pl.sk_iters = 0;
+    // persistent kernel: one round of resident blocks, each taking dp_tiles / grid whole tiles and then its
+    // stream-K range; without a workspace for partial tiles the ranges are whole tiles
+    const int resident = resident_blocks();
+    if (pl.sk_blocks > 0 && !p.partial) pl.sk_blocks = 0;
+    if (pl.sk_blocks == 0) {
+        const long long rest = tiles % resident;
+        pl.dp_tiles = (int)(tiles - rest);
+        pl.sk_blocks = (int)rest;
+        pl.sk_iters = rest * nkt;
     }
     p.dp_tiles = pl.dp_tiles;
     p.sk_blocks = pl.sk_blocks;
     p.sk_iters = pl.sk_iters;
-    if (!SMALLC && uniform_tap_ok<BM, BN>(p))
-        hipLaunchKernelGGL((conv_gemm_sk_kernel<BM, BN, false, BF16, true>), dim3((unsigned)(pl.dp_tiles + pl.sk_blocks)), dim3(256),
-                           0, stream, p);
-    else
-        hipLaunchKernelGGL((conv_gemm_sk_kernel<BM, BN, SMALLC, BF16>), dim3((unsigned)(pl.dp_tiles + pl.sk_blocks)), dim3(256), 0,
-                           stream, p);
-    if (pl.sk_blocks > 0)
+    magic_for(p.Qo, &p.qo_mul, &p.qo_shift);
+    magic_for(p.Po, &p.po_mul, &p.po_shift);
+    const unsigned grid = pl.dp_tiles > 0 ? (unsigned)resident : (unsigned)pl.sk_blocks;
+    const bool whole = pl.sk_blocks == 0 || pl.sk_iters == (long long)pl.sk_blocks * nkt;
+    const bool ut = !SMALLC && uniform_tap_ok<BM, BN>(p);
+    if (p.scatter) {                          // the scatter epilogue addresses the result relative to the tile's first pixel
+        const long long span = ((long long)BM / ((long long)p.Po * p.Qo) + 2) * p.Ho * p.Wo * p.ldd * (p.bf16 ? 2 : 4);
+        if (span >= 0x7fff0000LL || SMALLC) return LC_ERR_UNSUPPORTED;   // (1x1 windows never have fewer channels than a k-step)
+        if (ut)
+            hipLaunchKernelGGL((conv_gemm_pk_kernel<BM, BN, false, BF16, true, true>), dim3(grid), dim3(256), 0, stream, p);
+        else
+            hipLaunchKernelGGL((conv_gemm_pk_kernel<BM, BN, false, BF16, false, true>), dim3(grid), dim3(256), 0, stream, p);
+    } else if (ut) {
+        hipLaunchKernelGGL((conv_gemm_pk_kernel<BM, BN, false, BF16, true, false>), dim3(grid), dim3(256), 0, stream, p);
+    } else {
+        hipLaunchKernelGGL((conv_gemm_pk_kernel<BM, BN, SMALLC, BF16, false, false>), dim3(grid), dim3(256), 0, stream, p);
+    }
+    if (!whole)
         hipLaunchKernelGGL((conv_gemm_fixup_kernel<BM, BN, BF16>), dim3((unsigned)(tiles - pl.dp_tiles), 16), dim3(256), 0, stream, p);
     return lc_end_call();
 }
@@ -1754,7 +1441,9 @@ inline bool use_main_kernel(const GemmConv& p) {
         return e && strcmp(e, "classic") == 0;
     }();
     const bool vec = (p.Ci % (p.bf16 ? 8 : 4) == 0) && aligned16(p.a) && aligned16(p.b);
-    return vec && !(p.dh > 1 || p.dw > 1) && !(classic && !p.bf16);
+    // (the scatter epilogue of the main kernel is not built for its few-channels variant)
+    const bool few_scatter = p.scatter && p.Ci < (p.bf16 ? 32 : 16);
+    return vec && !(p.dh > 1 || p.dw > 1) && !(classic && !p.bf16) && !few_scatter;
 }
 
 }  // namespace
@@ -1772,9 +1461,6 @@ size_t lc_conv_gemm_workspace(const GemmConv& p) {
 bool lc_conv_gemm_bf16_native(const GemmConv& p) { return p.bf16 && use_main_kernel(p); }
 
 lc_status lc_launch_conv_gemm(const GemmConv& p, hipStream_t stream) {
-    static const int narrow_kg = getenv("LARSCONV_NARROW_KG") ? atoi(getenv("LARSCONV_NARROW_KG")) : 0;   // experiment
-    if (narrow_kg && p.Kg <= narrow_kg && use_main_kernel(p) && p.Ci >= 32)
-        return p.bf16 ? launch_conv_sk<128, 64, false, true>(p, stream) : launch_conv_sk<128, 64, false, false>(p, stream);
     if (p.bf16) {
         if (!use_main_kernel(p)) return LC_ERR_UNSUPPORTED;       // the caller converts to fp32 instead
         if (p.Ci < 32) return p.N > 64 ? launch_conv_sk<128, 128, true, true>(p, stream) : launch_conv_sk<128, 64, true, true>(p, stream);

@@ -22,6 +22,7 @@ SHAPES = {
     "1x1_plain": (3, 256, 7, 7, 512, 1, 1, 1, 0),
     "1x1_stride2_odd": (2, 64, 15, 15, 128, 1, 1, 2, 0),
     "1x1_stride2_even_k64": (2, 128, 16, 16, 64, 1, 1, 2, 0),
+    "1x1_stride2_few_filters": (2, 32, 9, 9, 8, 1, 1, 2, 0),
     "stem_7x7_s2": (2, 3, 30, 30, 64, 7, 7, 2, 3),
     "alexnet_11x11_s4": (1, 3, 35, 35, 32, 11, 11, 4, 0),
     "5x5_p2": (2, 16, 13, 13, 32, 5, 5, 1, 2),
