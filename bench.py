@@ -33,7 +33,7 @@ LARS_BYTES_PER_PARAM = 28  # norm pass reads w, g (8 B); update reads w, g, v an
 # HBM-side bytes per launch of the dominant kernel in the default workload, from the two rocprofv3 --pmc runs
 # (FETCH_SIZE x 2.000 + WRITE_SIZE x 1.000, factors from the 1 GiB copy calibration) summarised in
 # profiles/resnet50_step_fp32_b256_hbm_traffic_and_mfma.txt.  Counters cannot be read from inside this process.
-MEASURED_TRAFFIC = {("conv_gemm_128x128", 256): 414.4e6 + 202.3e6}
+MEASURED_TRAFFIC = {("conv_gemm_128x128", 256): 417.3e6 + 184.6e6}
 
 
 def log(*a):
