@@ -794,9 +794,13 @@ __global__ void __launch_bounds__(WGM* WGN * 64) wgrad_f32_kernel(const GemmWgra
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave / WGN, wn = wave % WGN;
     const int nbn = (p.J + BN - 1) / BN;
-    const int tile = blockIdx.x;
+    // Work items are numbered split-major (all tiles of a split next to each other) and dealt to the XCDs in
+    // contiguous runs: the tiles of a split, which read the same rows of dY and X, then share one L2.
+    const int tiles_ = ((p.K + BM - 1) / BM) * nbn;
+    const int work = xcd_tile(blockIdx.x, tiles_ * p.splits);
+    const int z = work / tiles_;
+    const int tile = work - z * tiles_;
     const int k0 = (tile / nbn) * BM, j0 = (tile % nbn) * BN;
-    const int z = blockIdx.y;
     const int m_begin = z * p.m_per_split;
     const int m_end = min(p.M, m_begin + p.m_per_split);
 
@@ -964,9 +968,13 @@ __global__ void __launch_bounds__(256, 4) wgrad_ut_kernel(const GemmWgrad p) {  
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave >> 1, wn = wave & 1;
     const int nbn = (p.J + BN - 1) / BN;
-    const int tile = blockIdx.x;
+    // Work items are numbered split-major (all tiles of a split next to each other) and dealt to the XCDs in
+    // contiguous runs: the tiles of a split, which read the same rows of dY and X, then share one L2.
+    const int tiles_ = ((p.K + BM - 1) / BM) * nbn;
+    const int work = xcd_tile(blockIdx.x, tiles_ * p.splits);
+    const int z = work / tiles_;
+    const int tile = work - z * tiles_;
     const int k0 = (tile / nbn) * BM, j0 = (tile % nbn) * BN;
-    const int z = blockIdx.y;
     const int m_begin = z * p.m_per_split;
     const int m_end = min(p.M, m_begin + p.m_per_split);
     const int H_ = p.H, W_ = p.W, C_ = p.C, P_ = p.P, Q_ = p.Q, R_ = p.R, S_ = p.S, K_ = p.K;
@@ -1074,47 +1082,57 @@ __global__ void __launch_bounds__(256, 4) wgrad_ut_kernel(const GemmWgrad p) {  
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
-    // fragments of the next pair of reduction rows are read while the current pair is multiplied
-    auto compute = [&](int buf) {
-        const float* as = &As[buf][(lane >> 5) * PA + wm * WTM + (lane & 31)];
-        const float* bs = &Bs[buf][(lane >> 5) * PB + wn * WTN + (lane & 31)];
-        float a[2][TM], b[2][TN];
+    // Fragments: slot k2 & 1 holds reduction rows 2*k2 and 2*k2 + 1 of the step (lane half picks the row)
+    float fa[2][TM], fb[2][TN];
+    auto read_frags = [&](int buf, int k2, int slot) __attribute__((always_inline)) {
+        const float* as = &As[buf][(2 * k2 + (lane >> 5)) * PA + wm * WTM + (lane & 31)];
+        const float* bs = &Bs[buf][(2 * k2 + (lane >> 5)) * PB + wn * WTN + (lane & 31)];
 #pragma unroll
-        for (int i = 0; i < TM; ++i) a[0][i] = as[i * 32];
+        for (int i = 0; i < TM; ++i) fa[slot][i] = as[i * 32];
 #pragma unroll
-        for (int j = 0; j < TN; ++j) b[0][j] = bs[j * 32];
+        for (int j = 0; j < TN; ++j) fb[slot][j] = bs[j * 32];
+    };
+    auto mfma_pair = [&](int slot) __attribute__((always_inline)) {
 #pragma unroll
-        for (int k2 = 0; k2 < BK / 2; ++k2) {
-            const int cs = k2 & 1, ns = cs ^ 1;
-            if (k2 + 1 < BK / 2) {
+        for (int i = 0; i < TM; ++i)
 #pragma unroll
-                for (int i = 0; i < TM; ++i) a[ns][i] = as[2 * (k2 + 1) * PA + i * 32];
-#pragma unroll
-                for (int j = 0; j < TN; ++j) b[ns][j] = bs[2 * (k2 + 1) * PB + j * 32];
-                __builtin_amdgcn_sched_barrier(0);      // keep these reads in front of the MFMAs below
-            }
-#pragma unroll
-            for (int i = 0; i < TM; ++i)
-#pragma unroll
-                for (int j = 0; j < TN; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[cs][i], b[cs][j], acc[i][j], 0, 0, 0);
-        }
+            for (int j = 0; j < TN; ++j)
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[slot][i], fb[slot][j], acc[i][j], 0, 0, 0);
     };
 
-    // One step out of LDS buffer `cur` (a literal at each call).  The step after the last one is fetched and
-    // stored as well: all of its rows are past m_end, so nothing is read from memory and zeros are stored.
+    // One step out of LDS buffer `cur` (a literal at each call).  On entry slot 0 holds the step's first pair of
+    // rows and the registers hold the next step's rows.  Those go to the other LDS buffer after the second
+    // group of MFMAs, the loads of the step after next follow into the same registers, and behind the barrier
+    // near the end the first fragments of the next step are read while the last MFMAs run.  Steps past the end
+    // of the split are fetched and stored like the others: all of their rows are past m_end, so nothing is read
+    // from memory and zeros are stored.
     auto step = [&](int cur) __attribute__((always_inline)) {
-        advance();
-        gload();
-        compute(cur);
-        sstore(cur ^ 1);
-        __syncthreads();
+#pragma unroll
+        for (int k2 = 0; k2 < BK / 2; ++k2) {
+            if (k2 + 1 < BK / 2) {
+                read_frags(cur, k2 + 1, (k2 + 1) & 1);
+            } else {
+                lds_barrier();
+                read_frags(cur ^ 1, 0, 0);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            mfma_pair(k2 & 1);
+            __builtin_amdgcn_sched_barrier(0);
+            if (k2 == 1) sstore(cur ^ 1);
+            if (k2 == 3) {
+                advance();
+                gload();
+            }
+        }
     };
     const int nkt = (m_end - m_begin + BK - 1) / BK;
     if (nkt > 0) {
         gload();
         sstore(0);
-        __syncthreads();
+        advance();
+        gload();
+        lds_barrier();
+        read_frags(0, 0, 0);
         int kt = 0;
         for (; kt + 2 <= nkt; kt += 2) {
             step(0);
@@ -1160,9 +1178,13 @@ __global__ void __launch_bounds__(256) wgrad_bf16_kernel(const GemmWgrad p) {
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave >> 1, wn = wave & 1;
     const int nbn = (p.J + BN - 1) / BN;
-    const int tile = blockIdx.x;
+    // Work items are numbered split-major (all tiles of a split next to each other) and dealt to the XCDs in
+    // contiguous runs: the tiles of a split, which read the same rows of dY and X, then share one L2.
+    const int tiles_ = ((p.K + BM - 1) / BM) * nbn;
+    const int work = xcd_tile(blockIdx.x, tiles_ * p.splits);
+    const int z = work / tiles_;
+    const int tile = work - z * tiles_;
     const int k0 = (tile / nbn) * BM, j0 = (tile % nbn) * BN;
-    const int z = blockIdx.y;
     const int m_begin = z * p.m_per_split;
     const int m_end = min(p.M, m_begin + p.m_per_split);
 
@@ -1310,8 +1332,8 @@ lc_status launch_conv(const GemmConv& p, hipStream_t stream) {
 template <int BM, int BN, int BK, int VEC, bool BF16>
 lc_status launch_wgrad(const GemmWgrad& p, hipStream_t stream) {
     const long long tiles = (long long)((p.K + BM - 1) / BM) * ((p.J + BN - 1) / BN);
-    if (tiles <= 0 || tiles > 0x7fffffffLL || p.splits > 65535) return LC_ERR_UNSUPPORTED;
-    hipLaunchKernelGGL((wgrad_f32_kernel<BM, BN, BK, 2, 2, VEC, BF16>), dim3((unsigned)tiles, (unsigned)p.splits), dim3(256), 0,
+    if (tiles <= 0 || tiles * p.splits > 0x7fffffffLL) return LC_ERR_UNSUPPORTED;
+    hipLaunchKernelGGL((wgrad_f32_kernel<BM, BN, BK, 2, 2, VEC, BF16>), dim3((unsigned)(tiles * p.splits)), dim3(256), 0,
                        stream, p);
     return lc_end_call();
 }
@@ -1501,8 +1523,8 @@ int lc_wgrad_splits(int M, int K, int J, bool bf16) {
 template <int BM, int BN>
 static lc_status launch_wgrad_bf16(const GemmWgrad& p, hipStream_t stream) {
     const long long tiles = (long long)((p.K + BM - 1) / BM) * ((p.J + BN - 1) / BN);
-    if (tiles <= 0 || tiles > 0x7fffffffLL || p.splits > 65535) return LC_ERR_UNSUPPORTED;
-    hipLaunchKernelGGL((wgrad_bf16_kernel<BM, BN>), dim3((unsigned)tiles, (unsigned)p.splits), dim3(256), 0, stream, p);
+    if (tiles <= 0 || tiles * p.splits > 0x7fffffffLL) return LC_ERR_UNSUPPORTED;
+    hipLaunchKernelGGL((wgrad_bf16_kernel<BM, BN>), dim3((unsigned)(tiles * p.splits)), dim3(256), 0, stream, p);
     return lc_end_call();
 }
 
@@ -1522,8 +1544,8 @@ static bool wgrad_ut_ok(const GemmWgrad& p) {
 template <int BM, int BN>
 static lc_status launch_wgrad_ut(const GemmWgrad& p, hipStream_t stream) {
     const long long tiles = (long long)((p.K + BM - 1) / BM) * ((p.J + BN - 1) / BN);
-    if (tiles <= 0 || tiles > 0x7fffffffLL || p.splits > 65535) return LC_ERR_UNSUPPORTED;
-    hipLaunchKernelGGL((wgrad_ut_kernel<BM, BN>), dim3((unsigned)tiles, (unsigned)p.splits), dim3(256), 0, stream, p);
+    if (tiles <= 0 || tiles * p.splits > 0x7fffffffLL) return LC_ERR_UNSUPPORTED;
+    hipLaunchKernelGGL((wgrad_ut_kernel<BM, BN>), dim3((unsigned)(tiles * p.splits)), dim3(256), 0, stream, p);
     return lc_end_call();
 }
 
