@@ -1168,7 +1168,7 @@ __global__ void __launch_bounds__(256) wgrad_bf16_kernel(const GemmWgrad p) {
     constexpr int AQ = BM / 8, BQ = BN / 8;           // 16-byte vectors per reduction row
     constexpr int ARPP = 256 / AQ, BRPP = 256 / BQ;   // reduction rows per pass of the block
     constexpr int LA = BK / ARPP, LB = BK / BRPP;
-    constexpr int PA = BM + 8, PB = BN + 8;           // elements; keeps rows 16-byte aligned
+    constexpr int PA = BM + 32, PB = BN + 32;         // elements: four consecutive rows start 64 bytes apart modulo 256
     constexpr int WTM = BM / 2, WTN = BN / 2, TM = WTM / 32, TN = WTN / 32;
     static_assert(256 % AQ == 0 && 256 % BQ == 0 && BK % ARPP == 0 && BK % BRPP == 0 && LA >= 1 && LB >= 1, "tile shape");
 
@@ -1259,15 +1259,20 @@ __global__ void __launch_bounds__(256) wgrad_bf16_kernel(const GemmWgrad p) {
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
-    // operand of one MFMA: reduction rows 16*t + 8*(lane>>5) + 0..7 of output index (lane & 31)
-    auto frag = [&](const uint16_t* base, int pitch, int t) {
-        const uint16_t* q = base + (16 * t + 8 * (lane >> 5)) * pitch + (lane & 31);
-        uint4 u;
-        u.x = (uint32_t)q[0] | ((uint32_t)q[pitch] << 16);
-        u.y = (uint32_t)q[2 * pitch] | ((uint32_t)q[3 * pitch] << 16);
-        u.z = (uint32_t)q[4 * pitch] | ((uint32_t)q[5 * pitch] << 16);
-        u.w = (uint32_t)q[6 * pitch] | ((uint32_t)q[7 * pitch] << 16);
-        return __builtin_bit_cast(bf16x8, u);
+    // Operand of one MFMA: reduction rows 16*t + 8*(lane>>5) + 0..7 of output index (lane & 31), fetched with
+    // the transposing LDS read.  Within 16 lanes, lane i points at 4 consecutive elements of row i/4 (columns
+    // 4*(i%4)..) and receives column i of those 4 rows: 4 consecutive reduction rows of one output index.  Lanes
+    // 16..31 take the next 16 columns, lanes 32..63 the rows 8 further down; a second read 4 rows down
+    // completes the 8 values.
+    typedef short s16x4 __attribute__((ext_vector_type(4)));
+    const int tr_row = 8 * (lane >> 5) + ((lane & 15) >> 2), tr_col = 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
+    auto frag = [&](const uint16_t* base, int pitch, int t) __attribute__((always_inline)) {
+        const uint16_t* q = base + (16 * t + tr_row) * pitch + tr_col;
+        const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(uintptr_t)q);
+        const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(uintptr_t)(q + 4 * pitch));
+        typedef short s16x8 __attribute__((ext_vector_type(8)));
+        const s16x8 v = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+        return __builtin_bit_cast(bf16x8, v);
     };
     auto compute = [&](int buf) {
 #pragma unroll
