@@ -1515,7 +1515,7 @@ int lc_wgrad_splits(int M, int K, int J, bool bf16) {
     const long long tiles = (long long)((K + bm - 1) / bm) * ((J + bn - 1) / bn);
     // blocks of this tiling that fit on the chip at once (registers and LDS of the kernel instances below):
     // the split count fills exactly one such round, never spills a few blocks into a second one
-    const int per_cu = (bm == 128 && bn == 128) ? (bf16 ? 3 : 4) : (bm == 64 && bn == 64) ? 8 : (bf16 ? 5 : 6);
+    const int per_cu = (bm == 128 && bn == 128) ? 4 : (bm == 64 && bn == 64) ? 8 : (bf16 ? 5 : 6);
     const long long round = (long long)per_cu * device_cu_count();
     long long want = round / tiles;
     const long long most = (M + 255) / 256;               // at least 256 reduction rows per split

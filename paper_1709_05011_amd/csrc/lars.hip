@@ -24,7 +24,7 @@ namespace {
 constexpr int kThreads = 256;
 constexpr int kVecPerThread = 4;                            // float4 loads per thread per array
 constexpr int kChunk = kThreads * kVecPerThread * 4;        // 4096 elements
-constexpr int kTablePerLaunch = 64;                         // descriptors per table launch (3 KB of kernel arguments)
+constexpr int kTablePerLaunch = 192;                        // descriptors per table launch (9 KB of kernel arguments)
 
 struct LarsTensor {
     float* w;
