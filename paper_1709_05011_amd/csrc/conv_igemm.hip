@@ -1421,6 +1421,31 @@ void magic_for(int d, unsigned* mul, unsigned* shift) {
     *shift = (unsigned)(L - 1);
 }
 
+}  // namespace
+
+// Host-side check of the division constants against plain division (the device evaluates the same two
+// operations with __umulhi): 0 if n / d is reproduced for every divisor up to max_d at the edges of each
+// quotient step and at the top of the 31-bit range, otherwise the first failing divisor.
+extern "C" int lc_selftest_division(int max_d) {
+    for (int d = 1; d <= max_d; ++d) {
+        unsigned mul, shift;
+        magic_for(d, &mul, &shift);
+        auto q = [&](unsigned n) { return mul ? (unsigned)(((unsigned long long)n * mul) >> 32) >> shift : n; };
+        const unsigned top = 0x7fffffffu;
+        const unsigned probes[] = {0u, 1u, (unsigned)d - 1, (unsigned)d, (unsigned)d + 1, 2u * d - 1, 2u * d, 1000003u, top - 1, top,
+                                   top / d * d, top / d * d - 1};
+        for (unsigned n : probes)
+            if (n <= top && q(n) != n / (unsigned)d) return d;
+        for (unsigned k = 1; k < 4096; ++k) {                   // quotient steps spread over the range
+            const unsigned long long n = (unsigned long long)k * 524287ull % (top / d + 1) * d;
+            if (n >= 1 && (q((unsigned)n) != n / d || q((unsigned)n - 1) != (n - 1) / d)) return d;
+        }
+    }
+    return 0;
+}
+
+namespace {
+
 template <int BM, int BN, bool SMALLC, bool BF16>
 lc_status launch_conv_sk(GemmConv p, hipStream_t stream) {
     long long tiles;
@@ -1470,7 +1495,9 @@ inline bool use_main_kernel(const GemmConv& p) {
     const bool vec = (p.Ci % (p.bf16 ? 8 : 4) == 0) && aligned16(p.a) && aligned16(p.b);
     // (the scatter epilogue of the main kernel is not built for its few-channels variant)
     const bool few_scatter = p.scatter && p.Ci < (p.bf16 ? 32 : 16);
-    return vec && !(p.dh > 1 || p.dw > 1) && !(classic && !p.bf16) && !few_scatter;
+    // (its tile store addresses a tile's rows with 32-bit byte offsets)
+    const bool wide_rows = (long long)160 * p.ldd * (p.bf16 ? 2 : 4) >= 0x7fff0000LL;
+    return vec && !(p.dh > 1 || p.dw > 1) && !(classic && !p.bf16) && !few_scatter && !wide_rows;
 }
 
 }  // namespace

@@ -66,6 +66,7 @@ struct GemmConv {
     int bf16;           // operands a, b and result d are bf16 (sums stay fp32)
 };
 lc_status lc_launch_conv_gemm(const GemmConv& p, hipStream_t stream);
+extern "C" int lc_selftest_division(int max_d);   // host check of the multiply-high division constants (0 = all good)
 bool lc_conv_gemm_bf16_native(const GemmConv& p);   // can the bf16 MFMA kernel take this problem (shape and alignment)?
 size_t lc_conv_gemm_workspace(const GemmConv& p);   // bytes `partial` must hold for this problem (0 = none)
 

@@ -105,6 +105,15 @@ def test_lars_step_rejects_bad_arguments_before_launch():
     assert call(arr, arr, arr, numel, FAKE + 8, 1 << 20) == lc.LC_ERR_WORKSPACE
 
 
+def test_index_division_constants_match_plain_division():
+    # the kernels divide pixel indices by the output width and height with a multiply-high and a shift;
+    # the library checks its constants against plain division for every divisor up to the argument
+    L = lc.lib()
+    L.lc_selftest_division.restype = ctypes.c_int
+    L.lc_selftest_division.argtypes = [ctypes.c_int]
+    assert L.lc_selftest_division(20000) == 0
+
+
 def test_poly_lr_host_arithmetic():
     assert lc.lars_poly_lr(1.0, 0, 3516) == 1.0
     assert lc.lars_poly_lr(1.0, 3516, 3516) == 0.0
