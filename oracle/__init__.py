@@ -210,8 +210,50 @@ def lars_step(w: Sequence[np.ndarray], g: Sequence[np.ndarray], v: Sequence[np.n
     return trust, norms
 
 
+def lars_step_ex(w: Sequence[np.ndarray], g: Sequence[np.ndarray], v: Sequence[np.ndarray],
+                 eta: float, momentum: float, weight_decay: float, lr: float,
+                 eta_per_tensor=None, wd_per_tensor=None, skip=None):
+    """lars_step with per-tensor trust coefficients / weight decays (None = the scalar) and a skip list
+    (tensors that take trust ratio 1).  Returns (trust ratios, norms) like lars_step."""
+    L = len(w)
+    for a in list(w) + list(v):
+        if a.dtype != np.float32 or not a.flags["C_CONTIGUOUS"] or not a.flags["WRITEABLE"]:
+            raise ValueError("w and v must be writable contiguous float32 arrays")
+    g = [_f32(a) for a in g]
+    numel = np.array([a.size for a in w], dtype=np.int64)
+    if any(a.size != b.size or a.size != c.size for a, b, c in zip(w, g, v)):
+        raise ValueError("size mismatch")
+    arr = ctypes.c_void_p * max(L, 1)
+    wp = arr(*[a.ctypes.data for a in w])
+    gp = arr(*[a.ctypes.data for a in g])
+    vp = arr(*[a.ctypes.data for a in v])
+    trust = np.empty(L, dtype=np.float64)
+    norms = np.empty((L, 2), dtype=np.float64)
+    e = None if eta_per_tensor is None else np.ascontiguousarray(eta_per_tensor, dtype=np.float64)
+    b = None if wd_per_tensor is None else np.ascontiguousarray(wd_per_tensor, dtype=np.float64)
+    s = None if skip is None else np.ascontiguousarray(skip, dtype=np.uint8)
+    for a in (e, b, s):
+        if a is not None and a.size != L:
+            raise ValueError("per-tensor array of the wrong length")
+    lib = _load()
+    lib.oracle_lars_step_ex.restype = None
+    lib.oracle_lars_step_ex(ctypes.c_int(L), wp, gp, vp, _fp(numel), ctypes.c_double(eta), ctypes.c_double(momentum),
+                            ctypes.c_double(weight_decay), ctypes.c_double(lr),
+                            None if e is None else _fp(e), None if b is None else _fp(b), None if s is None else _fp(s),
+                            _fp(trust), _fp(norms))
+    return trust, norms
+
+
 def poly_lr(base_lr: float, it: int, max_iter: int, power: float = 2.0) -> float:
     return float(_load().oracle_poly_lr(base_lr, it, max_iter, power))
+
+
+def warmup_poly_lr(base_lr: float, start_lr: float, it: int, warmup_iters: int, max_iter: int, power: float = 2.0) -> float:
+    lib = _load()
+    lib.oracle_warmup_poly_lr.restype = ctypes.c_double
+    lib.oracle_warmup_poly_lr.argtypes = [ctypes.c_double, ctypes.c_double, ctypes.c_int64, ctypes.c_int64, ctypes.c_int64,
+                                          ctypes.c_double]
+    return float(lib.oracle_warmup_poly_lr(base_lr, start_lr, it, warmup_iters, max_iter, power))
 
 
 def round_to_bf16(a: np.ndarray) -> np.ndarray:

@@ -260,6 +260,58 @@ void oracle_lars_step(int n_tensors, float* const* w, const float* const* g, flo
     }
 }
 
+/* The same rule with per-tensor coefficients.  The paper applies the rule layer by layer ("Layer-wise
+ * Adaptive Rate Scaling", "Scaling up Batch Size"); which tensors take part, and with which eta and
+ * beta, is left to the user of the rule -- biases and batch-norm parameters are commonly given no
+ * layer-wise scaling.  eta_l and beta_l override the scalars where the arrays are not NULL; a tensor
+ * with skip[l] != 0 takes lambda_l = 1 (plain momentum SGD with its weight decay). */
+void oracle_lars_step_ex(int n_tensors, float* const* w, const float* const* g, float* const* v,
+                         const int64_t* numel, double eta, double momentum, double weight_decay, double lr,
+                         const double* eta_l, const double* beta_l, const unsigned char* skip,
+                         double* trust_out, double* norms_out) {
+#pragma omp parallel for schedule(dynamic, 1) /* tensors are independent */
+    for (int l = 0; l < n_tensors; ++l) {
+        const double eta_here = eta_l ? eta_l[l] : eta;
+        const double beta = beta_l ? beta_l[l] : weight_decay;
+        double sw = 0.0, sg = 0.0;
+        for (int64_t i = 0; i < numel[l]; ++i) {
+            sw += (double)w[l][i] * (double)w[l][i];
+            sg += (double)g[l][i] * (double)g[l][i];
+        }
+        const double nw = sqrt(sw), ng = sqrt(sg);
+        const double den = ng + beta * nw;
+        double lambda = (nw > 0.0 && den > 0.0) ? eta_here * nw / den : 1.0;
+        if (skip && skip[l]) lambda = 1.0;
+        for (int64_t i = 0; i < numel[l]; ++i) {
+            const double vi = momentum * (double)v[l][i] + lr * lambda * ((double)g[l][i] + beta * (double)w[l][i]);
+            v[l][i] = (float)vi;
+            w[l][i] = (float)((double)w[l][i] - vi);
+        }
+        if (trust_out) trust_out[l] = lambda;
+        if (norms_out) {
+            norms_out[2 * l] = nw;
+            norms_out[2 * l + 1] = ng;
+        }
+    }
+}
+
+/* Warm-up followed by the poly policy.  The paper's warm-up scheme starts from a small rate and raises it to
+ * the large one over the first few epochs ("Difficulty of Large-Batch Training"; 5 epochs for ResNet-50);
+ * the shape of the ramp is not printed and is taken to be linear.  For t < W:
+ *     gamma_t = gamma_start + (gamma_0 - gamma_start) * t / W
+ * and from t = W on the poly policy runs over the remaining T - W iterations, starting at gamma_0:
+ *     gamma_t = gamma_0 * (1 - (t - W)/(T - W))^power. */
+double oracle_warmup_poly_lr(double base_lr, double start_lr, int64_t iter, int64_t warmup_iters, int64_t max_iter,
+                             double power) {
+    if (warmup_iters > 0 && iter < warmup_iters)
+        return start_lr + (base_lr - start_lr) * (double)iter / (double)warmup_iters;
+    const int64_t w = warmup_iters > 0 ? warmup_iters : 0;
+    if (max_iter <= w) return base_lr;
+    double frac = 1.0 - (double)(iter - w) / (double)(max_iter - w);
+    if (frac < 0.0) frac = 0.0;
+    return base_lr * pow(frac, power);
+}
+
 /* Poly learning-rate policy: gamma_t = gamma_0 * (1 - t/T)^power; the paper uses power 2. */
 double oracle_poly_lr(double base_lr, int64_t iter, int64_t max_iter, double power) {
     if (max_iter <= 0) return base_lr;

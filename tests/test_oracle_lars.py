@@ -152,3 +152,75 @@ def test_poly_schedule_closed_form():
     assert abs(oracle.poly_lr(1.0, 1000, T) - (1 - 1000 / 3516) ** 2) < 1e-15
     assert abs(oracle.poly_lr(0.2, 879, T) - 0.2 * 0.75 ** 2) < 1e-15  # a quarter of the way
     assert abs(oracle.poly_lr(3.0, 10, 40, 1.0) - 2.25) < 1e-15
+
+
+# ---- per-tensor coefficients, skip list, warm-up schedule ----
+
+def _rand_lists(sizes, seed):
+    w = [synth.normal((n,), seed + 3 * i) for i, n in enumerate(sizes)]
+    g = [synth.normal((n,), seed + 3 * i + 1, std=0.01) for i, n in enumerate(sizes)]
+    v = [synth.normal((n,), seed + 3 * i + 2, std=0.001) for i, n in enumerate(sizes)]
+    return w, g, v
+
+
+def test_per_tensor_form_with_scalar_arrays_equals_the_plain_rule():
+    sizes = [5, 1, 300, 64]
+    w1, g1, v1 = _rand_lists(sizes, 900)
+    w2, v2 = [a.copy() for a in w1], [a.copy() for a in v1]
+    t1, n1 = oracle.lars_step(w1, g1, v1, ETA, MOM, WD, 0.7)
+    t2, n2 = oracle.lars_step_ex(w2, g1, v2, 123.0, MOM, 456.0, 0.7, eta_per_tensor=[ETA] * 4, wd_per_tensor=[WD] * 4,
+                                 skip=[0] * 4)
+    np.testing.assert_array_equal(t1, t2)
+    for a, b in zip(w1 + v1, w2 + v2):
+        np.testing.assert_array_equal(a, b)
+
+
+def test_per_tensor_hand_values_and_skip():
+    # tensor 0: ||w|| = 5, ||g|| = 1, eta 0.002, beta 0.001 -> lambda = 0.01 / 1.005
+    # tensor 1: skipped -> lambda = 1: v = m v + gamma (g + beta w), the plain momentum step with weight decay
+    # tensor 2: no array entry differs from the scalars' role: eta 0.001, beta 0 -> lambda = 0.001 * 2 / 0.5
+    w = [_f(3, 4), _f(1, -2), _f(0, 2)]
+    g = [_f(0.6, 0.8), _f(0.5, 0.25), _f(0.3, 0.4)]
+    v = [_f(0, 0), _f(0.125, -0.5), _f(0, 0)]
+    w0, v0 = [a.astype(np.float64) for a in w], [a.astype(np.float64) for a in v]
+    trust, _ = oracle.lars_step_ex(w, g, v, 9.0, 0.5, 9.0, 0.25, eta_per_tensor=[0.002, 0.7, 0.001],
+                                   wd_per_tensor=[0.001, 0.01, 0.0], skip=[0, 1, 0])
+    assert abs(trust[0] - 0.01 / 1.005) < 1e-9
+    assert trust[1] == 1.0
+    assert abs(trust[2] - 0.004) < 1e-9
+    v1_ref = 0.5 * v0[1] + 0.25 * (np.array([0.5, 0.25]) + 0.01 * w0[1])
+    np.testing.assert_allclose(v[1], v1_ref, rtol=2e-7)
+    np.testing.assert_allclose(w[1], w0[1] - v1_ref, rtol=2e-7)
+    v2_ref = 0.25 * 0.004 * np.array([0.3, 0.4], dtype=np.float32).astype(np.float64)
+    np.testing.assert_allclose(v[2], v2_ref, rtol=3e-7)
+
+
+def test_skip_only_changes_the_skipped_tensors():
+    sizes = [33, 7, 129]
+    w1, g1, v1 = _rand_lists(sizes, 950)
+    w2, v2 = [a.copy() for a in w1], [a.copy() for a in v1]
+    oracle.lars_step_ex(w1, g1, v1, ETA, MOM, WD, 0.5)
+    t2, _ = oracle.lars_step_ex(w2, g1, v2, ETA, MOM, WD, 0.5, skip=[0, 1, 0])
+    np.testing.assert_array_equal(w1[0], w2[0])
+    np.testing.assert_array_equal(w1[2], w2[2])
+    assert t2[1] == 1.0 and not np.array_equal(w1[1], w2[1])
+
+
+def test_warmup_schedule_endpoints_ramp_and_decay():
+    base, start, W, T = 3.2, 0.1, 195, 3516           # 5 epochs of 39 iterations each at batch 32K; 90 epochs in all
+    assert oracle.warmup_poly_lr(base, start, 0, W, T) == start
+    assert abs(oracle.warmup_poly_lr(base, start, W, W, T) - base) < 1e-15          # the ramp reaches the base rate ...
+    assert abs(oracle.warmup_poly_lr(base, start, W - 1, W, T) - (start + (base - start) * (W - 1) / W)) < 1e-12
+    mid = oracle.warmup_poly_lr(base, start, 97, W, T)                                # ... linearly
+    assert abs(mid - (start + (base - start) * 97 / 195)) < 1e-12
+    for t in (W + 1, 1000, 3000, T - 1):
+        want = base * (1 - (t - W) / (T - W)) ** 2
+        assert abs(oracle.warmup_poly_lr(base, start, t, W, T) - want) < 1e-12
+    assert oracle.warmup_poly_lr(base, start, T, W, T) == 0.0
+    # without warm-up it is the plain poly policy
+    for t in (0, 17, 2000):
+        assert oracle.warmup_poly_lr(base, start, t, 0, T) == oracle.poly_lr(base, t, T)
+    # monotone: up during the ramp, down afterwards
+    vals = [oracle.warmup_poly_lr(base, start, t, W, T) for t in range(0, T + 1, 13)]
+    peak = int(np.argmax(vals))
+    assert all(a < b for a, b in zip(vals[:peak], vals[1:peak + 1])) and all(a > b for a, b in zip(vals[peak:], vals[peak + 1:]))
