@@ -103,6 +103,26 @@ lc_status lars_step(int n_tensors, float* const* w, const float* const* g, float
                     float* trust_out, void* const* w_lowp_out,
                     void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/* lars_step with per-tensor coefficients.  The paper applies the rule layer by layer ("Scaling up Batch
+ * Size") and leaves open which tensors take part and with which coefficients; biases and batch-norm
+ * parameters are commonly given no layer-wise scaling.  eta_per_tensor, weight_decay_per_tensor: HOST arrays
+ * of n_tensors floats replacing the scalars, or NULL (the scalar for every tensor).  skip: HOST array of
+ * n_tensors bytes or NULL; a tensor with a non-zero entry takes trust ratio 1, i.e. the plain momentum step
+ * v <- momentum*v + lr*(g + weight_decay*w) with its weight decay, and trust_out reports 1 for it.
+ * Everything else as lars_step, which is this call with the three arrays NULL. */
+lc_status lars_step_ex(int n_tensors, float* const* w, const float* const* g, float* const* v,
+                       const int64_t* numel, float eta, float momentum, float weight_decay, float lr,
+                       const float* eta_per_tensor, const float* weight_decay_per_tensor, const uint8_t* skip,
+                       float* trust_out, void* const* w_lowp_out,
+                       void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* Warm-up followed by the poly policy (HOST arithmetic).  The paper's warm-up scheme starts from a small rate
+ * and raises it to the large one over the first few epochs ("Difficulty of Large-Batch Training"; 5 epochs
+ * for ResNet-50); the ramp is taken to be linear: start_lr + (base_lr - start_lr) * iter / warmup_iters for
+ * iter < warmup_iters, then base_lr * (1 - (iter - warmup_iters)/(max_iter - warmup_iters))^power.
+ * warmup_iters <= 0 gives lars_poly_lr. */
+float lars_warmup_poly_lr(float base_lr, float start_lr, int64_t iter, int64_t warmup_iters, int64_t max_iter, float power);
+
 /* Poly learning-rate policy (HOST arithmetic): base_lr * (1 - iter/max_iter)^power, 0 past max_iter.
  * The paper trains with power 2; max_iter = epochs * images / batch ("Scaling Efficiency of Large
  * Batches").  The result is the `lr` argument of lars_step. */

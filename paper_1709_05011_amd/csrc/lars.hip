@@ -24,7 +24,7 @@ namespace {
 constexpr int kThreads = 256;
 constexpr int kVecPerThread = 4;                            // float4 loads per thread per array
 constexpr int kChunk = kThreads * kVecPerThread * 4;        // 4096 elements
-constexpr int kTablePerLaunch = 192;                        // descriptors per table launch (9 KB of kernel arguments)
+constexpr int kTablePerLaunch = 192;                        // descriptors per table launch (12 KB of kernel arguments)
 
 struct LarsTensor {
     float* w;
@@ -34,8 +34,12 @@ struct LarsTensor {
     long long numel;
     int chunk_start;       // first chunk of this tensor
     int n_chunks;
+    float eta;             // trust coefficient of this tensor
+    float weight_decay;
+    int skip;              // != 0: trust ratio 1 (no layer-wise scaling)
+    int pad_;
 };
-static_assert(sizeof(LarsTensor) == 48, "descriptor layout");
+static_assert(sizeof(LarsTensor) == 64, "descriptor layout");
 
 struct LarsGroupArgs {
     LarsTensor t[kTablePerLaunch];
@@ -122,10 +126,12 @@ __global__ void __launch_bounds__(kThreads) lars_norm_kernel(const LarsGroupArgs
 }
 
 __global__ void __launch_bounds__(kThreads)
-lars_finalize_kernel(LarsWorkspace ws, float eta, float weight_decay, float lr, float* __restrict__ trust_out) {
+lars_finalize_kernel(LarsWorkspace ws, float lr, float* __restrict__ trust_out) {
     __shared__ double red[8];
     const int l = blockIdx.x;
     const int chunk_start = ws.table[l].chunk_start, n_chunks = ws.table[l].n_chunks;
+    const float eta = ws.table[l].eta, weight_decay = ws.table[l].weight_decay;
+    const bool skip = ws.table[l].skip != 0;
     double pw = 0.0, pg = 0.0;
     for (int c = threadIdx.x; c < n_chunks; c += kThreads) {
         pw += ws.partial[2 * (chunk_start + c)];
@@ -135,17 +141,18 @@ lars_finalize_kernel(LarsWorkspace ws, float eta, float weight_decay, float lr, 
     if (threadIdx.x == 0) {
         const double nw = sqrt(tot.x), ng = sqrt(tot.y);
         const double den = ng + (double)weight_decay * nw;
-        const double trust = (nw > 0.0 && den > 0.0) ? (double)eta * nw / den : 1.0;
+        const double trust = (!skip && nw > 0.0 && den > 0.0) ? (double)eta * nw / den : 1.0;
         ws.step_scale[l] = (float)((double)lr * trust);
         if (trust_out) trust_out[l] = (float)trust;
     }
 }
 
 __global__ void __launch_bounds__(kThreads)
-lars_update_kernel(LarsWorkspace ws, int n_chunks, float momentum, float weight_decay) {
+lars_update_kernel(LarsWorkspace ws, int n_chunks, float momentum) {
     const int chunk = n_chunks - 1 - (int)blockIdx.x;
     const int l = ws.chunk_tensor[chunk];
     const LarsTensor t = ws.table[l];
+    const float weight_decay = t.weight_decay;
     const float scale = ws.step_scale[l];
     const long long off = (long long)(chunk - t.chunk_start) * kChunk;
     const long long rem = t.numel - off;
@@ -234,10 +241,11 @@ extern "C" size_t lars_workspace_bytes(int n_tensors, const int64_t* numel) {
     return lay.total;
 }
 
-extern "C" lc_status lars_step(int n_tensors, float* const* w, const float* const* g, float* const* v,
-                               const int64_t* numel, float eta, float momentum, float weight_decay, float lr,
-                               float* trust_out, void* const* w_lowp_out,
-                               void* workspace, size_t workspace_bytes, void* hip_stream) {
+extern "C" lc_status lars_step_ex(int n_tensors, float* const* w, const float* const* g, float* const* v,
+                                  const int64_t* numel, float eta, float momentum, float weight_decay, float lr,
+                                  const float* eta_per_tensor, const float* weight_decay_per_tensor, const uint8_t* skip,
+                                  float* trust_out, void* const* w_lowp_out,
+                                  void* workspace, size_t workspace_bytes, void* hip_stream) {
     if (n_tensors < 0) return LC_ERR_SHAPE;
     if (n_tensors == 0) return LC_OK;
     if (!w || !g || !v || !numel) return LC_ERR_NULL;
@@ -273,6 +281,10 @@ extern "C" lc_status lars_step(int n_tensors, float* const* w, const float* cons
             t.v = v[l];
             t.w_lowp = w_lowp_out ? static_cast<uint16_t*>(w_lowp_out[l]) : nullptr;
             t.numel = numel[l];
+            t.eta = eta_per_tensor ? eta_per_tensor[l] : eta;
+            t.weight_decay = weight_decay_per_tensor ? weight_decay_per_tensor[l] : weight_decay;
+            t.skip = skip ? (int)skip[l] : 0;
+            t.pad_ = 0;
             t.chunk_start = chunk_cursor;
             t.n_chunks = (int)((numel[l] + kChunk - 1) / kChunk);
             chunk_cursor += t.n_chunks;
@@ -283,11 +295,30 @@ extern "C" lc_status lars_step(int n_tensors, float* const* w, const float* cons
         const int grid = args.chunk_count > 0 ? args.chunk_count : 1;
         hipLaunchKernelGGL(lars_norm_kernel, dim3(grid), dim3(kThreads), 0, stream, args, ws);
     }
-    hipLaunchKernelGGL(lars_finalize_kernel, dim3(n_tensors), dim3(kThreads), 0, stream, ws, eta, weight_decay, lr, trust_out);
+    hipLaunchKernelGGL(lars_finalize_kernel, dim3(n_tensors), dim3(kThreads), 0, stream, ws, lr, trust_out);
     if (lay.n_chunks > 0)
         hipLaunchKernelGGL(lars_update_kernel, dim3((unsigned)lay.n_chunks), dim3(kThreads), 0, stream, ws, (int)lay.n_chunks,
-                           momentum, weight_decay);
+                           momentum);
     return lc_end_call();
+}
+
+extern "C" lc_status lars_step(int n_tensors, float* const* w, const float* const* g, float* const* v,
+                               const int64_t* numel, float eta, float momentum, float weight_decay, float lr,
+                               float* trust_out, void* const* w_lowp_out,
+                               void* workspace, size_t workspace_bytes, void* hip_stream) {
+    return lars_step_ex(n_tensors, w, g, v, numel, eta, momentum, weight_decay, lr, nullptr, nullptr, nullptr, trust_out,
+                        w_lowp_out, workspace, workspace_bytes, hip_stream);
+}
+
+extern "C" float lars_warmup_poly_lr(float base_lr, float start_lr, int64_t iter, int64_t warmup_iters, int64_t max_iter,
+                                     float power) {
+    if (warmup_iters > 0 && iter < warmup_iters)
+        return (float)((double)start_lr + ((double)base_lr - (double)start_lr) * (double)iter / (double)warmup_iters);
+    const int64_t w = warmup_iters > 0 ? warmup_iters : 0;
+    if (max_iter <= w) return base_lr;
+    double frac = 1.0 - (double)(iter - w) / (double)(max_iter - w);
+    if (frac < 0.0) frac = 0.0;
+    return (float)((double)base_lr * pow(frac, (double)power));
 }
 
 extern "C" float lars_poly_lr(float base_lr, int64_t iter, int64_t max_iter, float power) {

@@ -20,7 +20,8 @@ LC_NCHW, LC_NHWC = 0, 1
 LC_PASS_FWD, LC_PASS_BWD_DATA, LC_PASS_BWD_WEIGHT = 0, 1, 2
 
 EXPORTS = ["conv2d_out_shape", "conv2d_workspace_bytes", "conv2d_fwd", "conv2d_bwd_data", "conv2d_bwd_weight",
-           "lars_workspace_bytes", "lars_step", "lars_poly_lr", "lc_status_string", "lc_last_error_detail"]
+           "lars_workspace_bytes", "lars_step", "lars_step_ex", "lars_poly_lr", "lars_warmup_poly_lr",
+           "lc_status_string", "lc_last_error_detail"]
 
 
 class LarsConvError(RuntimeError):
@@ -86,8 +87,14 @@ def lib() -> ctypes.CDLL:
         L.lars_step.restype = i32
         L.lars_step.argtypes = [i32, vp, vp, vp, vp, ctypes.c_float, ctypes.c_float, ctypes.c_float, ctypes.c_float,
                                 vp, vp, vp, sz, vp]
+        L.lars_step_ex.restype = i32
+        L.lars_step_ex.argtypes = [i32, vp, vp, vp, vp, ctypes.c_float, ctypes.c_float, ctypes.c_float, ctypes.c_float,
+                                   vp, vp, vp, vp, vp, vp, sz, vp]
         L.lars_poly_lr.restype = ctypes.c_float
         L.lars_poly_lr.argtypes = [ctypes.c_float, ctypes.c_int64, ctypes.c_int64, ctypes.c_float]
+        L.lars_warmup_poly_lr.restype = ctypes.c_float
+        L.lars_warmup_poly_lr.argtypes = [ctypes.c_float, ctypes.c_float, ctypes.c_int64, ctypes.c_int64, ctypes.c_int64,
+                                          ctypes.c_float]
         L.lc_status_string.restype = ctypes.c_char_p
         L.lc_status_string.argtypes = [i32]
         L.lc_last_error_detail.restype = ctypes.c_char_p
@@ -201,5 +208,28 @@ def lars_step(args: LarsArgs, eta: float, momentum: float, weight_decay: float, 
                            _ptr(trust_out), args.w_lowp, _ptr(workspace), nb, _stream(stream)), "lars_step")
 
 
+def lars_step_ex(args: LarsArgs, eta: float, momentum: float, weight_decay: float, lr: float, eta_per_tensor=None,
+                 weight_decay_per_tensor=None, skip=None, trust_out=None, workspace=None, stream=None,
+                 workspace_bytes: Optional[int] = None) -> None:
+    """lars_step with per-tensor coefficients (sequences of floats or None) and a skip list (sequence of 0/1 or None)."""
+    def farr(a):
+        if a is None:
+            return None
+        if len(a) != args.n:
+            raise ValueError("per-tensor array of the wrong length")
+        return (ctypes.c_float * max(args.n, 1))(*[float(x) for x in a])
+    e, b = farr(eta_per_tensor), farr(weight_decay_per_tensor)
+    if skip is not None and len(skip) != args.n:
+        raise ValueError("skip list of the wrong length")
+    sk = None if skip is None else (ctypes.c_uint8 * max(args.n, 1))(*[1 if x else 0 for x in skip])
+    nb = _nbytes(workspace) if workspace_bytes is None else workspace_bytes
+    _check(lib().lars_step_ex(args.n, args.w, args.g, args.v, args.numel_arr, eta, momentum, weight_decay, lr, e, b, sk,
+                              _ptr(trust_out), args.w_lowp, _ptr(workspace), nb, _stream(stream)), "lars_step_ex")
+
+
 def lars_poly_lr(base_lr: float, it: int, max_iter: int, power: float = 2.0) -> float:
     return float(lib().lars_poly_lr(base_lr, it, max_iter, power))
+
+
+def lars_warmup_poly_lr(base_lr: float, start_lr: float, it: int, warmup_iters: int, max_iter: int, power: float = 2.0) -> float:
+    return float(lib().lars_warmup_poly_lr(base_lr, start_lr, it, warmup_iters, max_iter, power))

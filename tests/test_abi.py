@@ -4,6 +4,8 @@ import ctypes
 import os
 import re
 
+import numpy as np
+
 import pytest
 
 from paper_1709_05011_amd import larsconv as lc
@@ -112,6 +114,28 @@ def test_index_division_constants_match_plain_division():
     L.lc_selftest_division.restype = ctypes.c_int
     L.lc_selftest_division.argtypes = [ctypes.c_int]
     assert L.lc_selftest_division(20000) == 0
+
+
+def test_warmup_poly_lr_host_arithmetic_matches_oracle():
+    import oracle
+    base, start, W, T = 3.2, 0.1, 195, 3516
+    for t in (0, 1, 97, 194, 195, 196, 1000, 3515, 3516, 4000):
+        want = oracle.warmup_poly_lr(float(np.float32(base)), float(np.float32(start)), t, W, T, 2.0)
+        assert abs(lc.lars_warmup_poly_lr(base, start, t, W, T, 2.0) - want) <= 1e-6 * max(want, 1e-3)
+    assert lc.lars_warmup_poly_lr(base, start, 50, 0, T, 2.0) == lc.lars_poly_lr(base, 50, T, 2.0)
+
+
+def test_lars_step_ex_rejects_bad_arguments_before_launch():
+    L = lc.lib()
+    arr = (ctypes.c_void_p * 2)(FAKE, FAKE)
+    numel = (ctypes.c_int64 * 2)(100, 5000)
+    eta = (ctypes.c_float * 2)(0.1, 0.2)
+    skip = (ctypes.c_uint8 * 2)(0, 1)
+    need = lc.lars_workspace_bytes([100, 5000])
+    call = lambda w, ws, nb: L.lars_step_ex(2, w, arr, arr, numel, 0.001, 0.9, 5e-5, 1.0, eta, None, skip, None, None, ws, nb, None)
+    assert call(None, ctypes.c_void_p(FAKE), need) == lc.LC_ERR_NULL
+    assert call(arr, None, need) == lc.LC_ERR_WORKSPACE
+    assert call(arr, ctypes.c_void_p(FAKE), need - 1) == lc.LC_ERR_WORKSPACE
 
 
 def test_poly_lr_host_arithmetic():
