@@ -128,6 +128,37 @@ float lars_warmup_poly_lr(float base_lr, float start_lr, int64_t iter, int64_t w
  * Batches").  The result is the `lr` argument of lars_step. */
 float lars_poly_lr(float base_lr, int64_t iter, int64_t max_iter, float power);
 
+/* ---- Glue layers of the small whole-path network (fp32) ----
+ * ReLU, 2x2 max pooling, global average pooling, bias and softmax cross-entropy: the paper does not discuss
+ * them (they are implied by the networks it trains, "Experimental Settings"); these are the textbook
+ * definitions, provided so that the tiny CNN runs end to end on the device.  They are simple memory-bound
+ * kernels, not part of the measured convolution + LARS path.  All pointers DEVICE, fp32, 4-byte aligned;
+ * reductions run in a fixed order. */
+
+/* y = max(x, 0);  dx = x > 0 ? dy : 0 (x is the forward INPUT).  count elements; the buffers must not overlap. */
+lc_status relu_fwd(const float* x, float* y, size_t count, void* hip_stream);
+lc_status relu_bwd(const float* x, const float* dy, float* dx, size_t count, void* hip_stream);
+
+/* 2x2 window, stride 2, h and w even.  x: [n,c,h,w] in `layout`, y: [n,c,h/2,w/2]; idx (one byte per
+ * output element, same order as y) receives the position 0..3, row-major in the window, of the first
+ * maximum; the backward pass sends dy there and zeros to the rest of the window (dx written in full). */
+lc_status maxpool2x2_fwd(const float* x, float* y, uint8_t* idx, int n, int c, int h, int w, lc_layout layout, void* hip_stream);
+lc_status maxpool2x2_bwd(const float* dy, const uint8_t* idx, float* dx, int n, int c, int h, int w, lc_layout layout,
+                         void* hip_stream);
+
+/* y[n,c] = mean over h, w of x[n,c,h,w];  dx[n,c,h,w] = dy[n,c] / (h*w). */
+lc_status global_avgpool_fwd(const float* x, float* y, int n, int c, int h, int w, lc_layout layout, void* hip_stream);
+lc_status global_avgpool_bwd(const float* dy, float* dx, int n, int c, int h, int w, lc_layout layout, void* hip_stream);
+
+/* y[r][j] += b[j] for rows x k values in place;  db[j] = sum over rows of dy[r][j]. */
+lc_status bias_add(float* y, const float* b, size_t rows, int k, void* hip_stream);
+lc_status bias_grad(const float* dy, float* db, size_t rows, int k, void* hip_stream);
+
+/* Mean softmax cross-entropy of logits [n][k] against labels (n int32 values in [0, k)) -> loss (one float),
+ * and its gradient (softmax - onehot) / n -> dlogits [n][k].  row_scratch: n floats of device scratch. */
+lc_status softmax_xent(const float* logits, const int32_t* labels, float* loss, float* dlogits, float* row_scratch, int n, int k,
+                       void* hip_stream);
+
 /* Static, human-readable name of a status code. */
 const char* lc_status_string(lc_status status);
 

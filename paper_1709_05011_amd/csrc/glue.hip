@@ -1,0 +1,274 @@
+// Glue layers of the small whole-path network: ReLU, 2x2 max pooling, global average pooling, bias, softmax
+// cross-entropy.  The paper does not discuss them (they are implied by the networks it trains, "Experimental
+// Settings"); these are the textbook definitions in fp32, memory-bound and simple on purpose: they exist so
+// that the tiny CNN runs end to end on the device through the C ABI, they are not part of the measured path.
+// Reductions run in a fixed order (bit-identical reruns).
+#include <hip/hip_runtime.h>
+
+#include <cstdint>
+
+#include "../../include/larsconv.h"
+#include "internal.h"
+
+namespace {
+
+constexpr int kThreads = 256;
+
+inline unsigned blocks_for(size_t count) {
+    size_t b = (count + kThreads - 1) / kThreads;
+    if (b > 65535u * 16u) b = 65535u * 16u;           // grid-stride loops take the rest
+    return (unsigned)(b ? b : 1);
+}
+
+__global__ void relu_fwd_kernel(const float* __restrict__ x, float* __restrict__ y, size_t count) {
+    for (size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x; i < count; i += (size_t)gridDim.x * blockDim.x)
+        y[i] = x[i] > 0.f ? x[i] : 0.f;
+}
+
+__global__ void relu_bwd_kernel(const float* __restrict__ x, const float* __restrict__ dy, float* __restrict__ dx, size_t count) {
+    for (size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x; i < count; i += (size_t)gridDim.x * blockDim.x)
+        dx[i] = x[i] > 0.f ? dy[i] : 0.f;
+}
+
+// element (n, c, h, w) of a tensor in either layout
+__device__ __forceinline__ size_t at(bool nhwc, int C, int H, int W, int n, int c, int h, int w) {
+    return nhwc ? (((size_t)n * H + h) * W + w) * C + c : (((size_t)n * C + c) * H + h) * W + w;
+}
+
+// One thread per output element; the index of the first maximum in row-major window order goes to idx.
+__global__ void maxpool2x2_fwd_kernel(const float* __restrict__ x, float* __restrict__ y, uint8_t* __restrict__ idx, int N, int C,
+                                      int H, int W, bool nhwc) {
+    const int Ho = H / 2, Wo = W / 2;
+    const size_t total = (size_t)N * C * Ho * Wo;
+    for (size_t o = blockIdx.x * (size_t)blockDim.x + threadIdx.x; o < total; o += (size_t)gridDim.x * blockDim.x) {
+        int n, c, p, q;
+        size_t t = o;
+        if (nhwc) {
+            c = (int)(t % C); t /= C;
+            q = (int)(t % Wo); t /= Wo;
+            p = (int)(t % Ho); n = (int)(t / Ho);
+        } else {
+            q = (int)(t % Wo); t /= Wo;
+            p = (int)(t % Ho); t /= Ho;
+            c = (int)(t % C); n = (int)(t / C);
+        }
+        float best = x[at(nhwc, C, H, W, n, c, 2 * p, 2 * q)];
+        int bi = 0;
+#pragma unroll
+        for (int k = 1; k < 4; ++k) {
+            const float v = x[at(nhwc, C, H, W, n, c, 2 * p + (k >> 1), 2 * q + (k & 1))];
+            if (v > best) {                             // strictly greater: the first maximum wins ties
+                best = v;
+                bi = k;
+            }
+        }
+        y[o] = best;
+        idx[o] = (uint8_t)bi;
+    }
+}
+
+__global__ void maxpool2x2_bwd_kernel(const float* __restrict__ dy, const uint8_t* __restrict__ idx, float* __restrict__ dx, int N,
+                                      int C, int H, int W, bool nhwc) {
+    const int Ho = H / 2, Wo = W / 2;
+    const size_t total = (size_t)N * C * Ho * Wo;
+    for (size_t o = blockIdx.x * (size_t)blockDim.x + threadIdx.x; o < total; o += (size_t)gridDim.x * blockDim.x) {
+        int n, c, p, q;
+        size_t t = o;
+        if (nhwc) {
+            c = (int)(t % C); t /= C;
+            q = (int)(t % Wo); t /= Wo;
+            p = (int)(t % Ho); n = (int)(t / Ho);
+        } else {
+            q = (int)(t % Wo); t /= Wo;
+            p = (int)(t % Ho); t /= Ho;
+            c = (int)(t % C); n = (int)(t / C);
+        }
+        const int bi = idx[o];
+        const float g = dy[o];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) dx[at(nhwc, C, H, W, n, c, 2 * p + (k >> 1), 2 * q + (k & 1))] = k == bi ? g : 0.f;
+    }
+}
+
+// One wave per (n, c): pixels summed in strides of 64, lanes combined by a fixed shuffle tree.
+__global__ void global_avgpool_fwd_kernel(const float* __restrict__ x, float* __restrict__ y, int N, int C, int H, int W, bool nhwc) {
+    const int lane = threadIdx.x & 63;
+    const size_t pair = (size_t)blockIdx.x * (kThreads / 64) + (threadIdx.x >> 6);
+    if (pair >= (size_t)N * C) return;
+    const int n = (int)(pair / C), c = (int)(pair % C);
+    const int hw = H * W;
+    float s = 0.f;
+    for (int i = lane; i < hw; i += 64) s += x[at(nhwc, C, H, W, n, c, i / W, i % W)];
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) s += __shfl_xor(s, off, 64);
+    if (lane == 0) y[pair] = s / (float)hw;
+}
+
+__global__ void global_avgpool_bwd_kernel(const float* __restrict__ dy, float* __restrict__ dx, int N, int C, int H, int W, bool nhwc) {
+    const size_t total = (size_t)N * C * H * W;
+    const float inv = 1.f / (float)(H * W);
+    for (size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x; i < total; i += (size_t)gridDim.x * blockDim.x) {
+        size_t nc;
+        if (nhwc) {
+            const int c = (int)(i % C);
+            nc = (i / ((size_t)C * H * W)) * C + c;
+        } else {
+            nc = i / ((size_t)H * W);
+        }
+        dx[i] = dy[nc] * inv;
+    }
+}
+
+__global__ void bias_add_kernel(float* __restrict__ y, const float* __restrict__ b, size_t rows, int K) {
+    const size_t total = rows * K;
+    for (size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x; i < total; i += (size_t)gridDim.x * blockDim.x) y[i] += b[i % K];
+}
+
+// One thread per column, rows added in order.
+__global__ void bias_grad_kernel(const float* __restrict__ dy, float* __restrict__ db, size_t rows, int K) {
+    const int k = blockIdx.x * blockDim.x + threadIdx.x;
+    if (k >= K) return;
+    float s = 0.f;
+    for (size_t r = 0; r < rows; ++r) s += dy[r * K + k];
+    db[k] = s;
+}
+
+// One wave per row: softmax, the row's -log p[label], and (softmax - onehot) / N.  row_loss[n] is reduced by
+// the second kernel in index order.
+__global__ void softmax_xent_rows_kernel(const float* __restrict__ logits, const int32_t* __restrict__ labels, float* __restrict__ row_loss,
+                                         float* __restrict__ dlogits, int N, int K) {
+    const int lane = threadIdx.x & 63;
+    const int n = blockIdx.x * (kThreads / 64) + (threadIdx.x >> 6);
+    if (n >= N) return;
+    const float* z = logits + (size_t)n * K;
+    float m = -3.402823466e38f;
+    for (int k = lane; k < K; k += 64) m = fmaxf(m, z[k]);
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) m = fmaxf(m, __shfl_xor(m, off, 64));
+    float s = 0.f;
+    for (int k = lane; k < K; k += 64) s += expf(z[k] - m);
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) s += __shfl_xor(s, off, 64);
+    const int lab = min(max(labels[n], 0), K - 1);   // (a label outside [0, K) is the caller's error; stay inside the row)
+    const float inv_n = 1.f / (float)N;
+    for (int k = lane; k < K; k += 64) {
+        const float p = expf(z[k] - m) / s;
+        dlogits[(size_t)n * K + k] = (p - (k == lab ? 1.f : 0.f)) * inv_n;
+    }
+    if (lane == 0) row_loss[n] = -(z[lab] - m - logf(s));
+}
+
+__global__ void mean_kernel(const float* __restrict__ v, float* __restrict__ out, int N) {
+    if (blockIdx.x != 0 || threadIdx.x != 0) return;
+    double s = 0.0;
+    for (int i = 0; i < N; ++i) s += (double)v[i];
+    out[0] = (float)(s / (double)N);
+}
+
+inline bool bad_layout(lc_layout l) { return l != LC_NCHW && l != LC_NHWC; }
+inline bool misaligned(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 3) != 0; }
+
+}  // namespace
+
+extern "C" lc_status relu_fwd(const float* x, float* y, size_t count, void* hip_stream) {
+    if (!x || !y) return LC_ERR_NULL;
+    if (misaligned(x) || misaligned(y)) return LC_ERR_ALIGN;
+    if (count == 0) return LC_OK;
+    lc_begin_call();
+    hipLaunchKernelGGL(relu_fwd_kernel, dim3(blocks_for(count)), dim3(kThreads), 0, static_cast<hipStream_t>(hip_stream), x, y, count);
+    return lc_end_call();
+}
+
+extern "C" lc_status relu_bwd(const float* x, const float* dy, float* dx, size_t count, void* hip_stream) {
+    if (!x || !dy || !dx) return LC_ERR_NULL;
+    if (misaligned(x) || misaligned(dy) || misaligned(dx)) return LC_ERR_ALIGN;
+    if (count == 0) return LC_OK;
+    lc_begin_call();
+    hipLaunchKernelGGL(relu_bwd_kernel, dim3(blocks_for(count)), dim3(kThreads), 0, static_cast<hipStream_t>(hip_stream), x, dy, dx,
+                       count);
+    return lc_end_call();
+}
+
+extern "C" lc_status maxpool2x2_fwd(const float* x, float* y, uint8_t* idx, int n, int c, int h, int w, lc_layout layout,
+                                    void* hip_stream) {
+    if (!x || !y || !idx) return LC_ERR_NULL;
+    if (n <= 0 || c <= 0 || h <= 0 || w <= 0 || (h & 1) || (w & 1)) return LC_ERR_SHAPE;
+    if (bad_layout(layout)) return LC_ERR_UNSUPPORTED;
+    if (misaligned(x) || misaligned(y)) return LC_ERR_ALIGN;
+    lc_begin_call();
+    const size_t total = (size_t)n * c * (h / 2) * (w / 2);
+    hipLaunchKernelGGL(maxpool2x2_fwd_kernel, dim3(blocks_for(total)), dim3(kThreads), 0, static_cast<hipStream_t>(hip_stream), x, y,
+                       idx, n, c, h, w, layout == LC_NHWC);
+    return lc_end_call();
+}
+
+extern "C" lc_status maxpool2x2_bwd(const float* dy, const uint8_t* idx, float* dx, int n, int c, int h, int w, lc_layout layout,
+                                    void* hip_stream) {
+    if (!dy || !idx || !dx) return LC_ERR_NULL;
+    if (n <= 0 || c <= 0 || h <= 0 || w <= 0 || (h & 1) || (w & 1)) return LC_ERR_SHAPE;
+    if (bad_layout(layout)) return LC_ERR_UNSUPPORTED;
+    if (misaligned(dy) || misaligned(dx)) return LC_ERR_ALIGN;
+    lc_begin_call();
+    const size_t total = (size_t)n * c * (h / 2) * (w / 2);
+    hipLaunchKernelGGL(maxpool2x2_bwd_kernel, dim3(blocks_for(total)), dim3(kThreads), 0, static_cast<hipStream_t>(hip_stream), dy,
+                       idx, dx, n, c, h, w, layout == LC_NHWC);
+    return lc_end_call();
+}
+
+extern "C" lc_status global_avgpool_fwd(const float* x, float* y, int n, int c, int h, int w, lc_layout layout, void* hip_stream) {
+    if (!x || !y) return LC_ERR_NULL;
+    if (n <= 0 || c <= 0 || h <= 0 || w <= 0) return LC_ERR_SHAPE;
+    if (bad_layout(layout)) return LC_ERR_UNSUPPORTED;
+    if (misaligned(x) || misaligned(y)) return LC_ERR_ALIGN;
+    lc_begin_call();
+    const size_t pairs = (size_t)n * c;
+    const size_t blocks = (pairs + kThreads / 64 - 1) / (kThreads / 64);
+    if (blocks > 0x7fffffffull) return LC_ERR_UNSUPPORTED;
+    hipLaunchKernelGGL(global_avgpool_fwd_kernel, dim3((unsigned)blocks), dim3(kThreads), 0, static_cast<hipStream_t>(hip_stream), x, y,
+                       n, c, h, w, layout == LC_NHWC);
+    return lc_end_call();
+}
+
+extern "C" lc_status global_avgpool_bwd(const float* dy, float* dx, int n, int c, int h, int w, lc_layout layout, void* hip_stream) {
+    if (!dy || !dx) return LC_ERR_NULL;
+    if (n <= 0 || c <= 0 || h <= 0 || w <= 0) return LC_ERR_SHAPE;
+    if (bad_layout(layout)) return LC_ERR_UNSUPPORTED;
+    if (misaligned(dy) || misaligned(dx)) return LC_ERR_ALIGN;
+    lc_begin_call();
+    hipLaunchKernelGGL(global_avgpool_bwd_kernel, dim3(blocks_for((size_t)n * c * h * w)), dim3(kThreads), 0,
+                       static_cast<hipStream_t>(hip_stream), dy, dx, n, c, h, w, layout == LC_NHWC);
+    return lc_end_call();
+}
+
+extern "C" lc_status bias_add(float* y, const float* b, size_t rows, int k, void* hip_stream) {
+    if (!y || !b) return LC_ERR_NULL;
+    if (k <= 0) return LC_ERR_SHAPE;
+    if (misaligned(y) || misaligned(b)) return LC_ERR_ALIGN;
+    if (rows == 0) return LC_OK;
+    lc_begin_call();
+    hipLaunchKernelGGL(bias_add_kernel, dim3(blocks_for(rows * k)), dim3(kThreads), 0, static_cast<hipStream_t>(hip_stream), y, b, rows, k);
+    return lc_end_call();
+}
+
+extern "C" lc_status bias_grad(const float* dy, float* db, size_t rows, int k, void* hip_stream) {
+    if (!dy || !db) return LC_ERR_NULL;
+    if (k <= 0) return LC_ERR_SHAPE;
+    if (misaligned(dy) || misaligned(db)) return LC_ERR_ALIGN;
+    lc_begin_call();
+    hipLaunchKernelGGL(bias_grad_kernel, dim3((unsigned)((k + kThreads - 1) / kThreads)), dim3(kThreads), 0,
+                       static_cast<hipStream_t>(hip_stream), dy, db, rows, k);
+    return lc_end_call();
+}
+
+extern "C" lc_status softmax_xent(const float* logits, const int32_t* labels, float* loss, float* dlogits, float* row_scratch, int n,
+                                  int k, void* hip_stream) {
+    if (!logits || !labels || !loss || !dlogits || !row_scratch) return LC_ERR_NULL;
+    if (n <= 0 || k <= 0) return LC_ERR_SHAPE;
+    if (misaligned(logits) || misaligned(labels) || misaligned(loss) || misaligned(dlogits) || misaligned(row_scratch)) return LC_ERR_ALIGN;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    lc_begin_call();
+    hipLaunchKernelGGL(softmax_xent_rows_kernel, dim3((unsigned)((n + kThreads / 64 - 1) / (kThreads / 64))), dim3(kThreads), 0, stream,
+                       logits, labels, row_scratch, dlogits, n, k);
+    hipLaunchKernelGGL(mean_kernel, dim3(1), dim3(64), 0, stream, row_scratch, loss, n);
+    return lc_end_call();
+}

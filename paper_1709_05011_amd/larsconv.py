@@ -21,7 +21,8 @@ LC_PASS_FWD, LC_PASS_BWD_DATA, LC_PASS_BWD_WEIGHT = 0, 1, 2
 
 EXPORTS = ["conv2d_out_shape", "conv2d_workspace_bytes", "conv2d_fwd", "conv2d_bwd_data", "conv2d_bwd_weight",
            "lars_workspace_bytes", "lars_step", "lars_step_ex", "lars_poly_lr", "lars_warmup_poly_lr",
-           "lc_status_string", "lc_last_error_detail"]
+           "relu_fwd", "relu_bwd", "maxpool2x2_fwd", "maxpool2x2_bwd", "global_avgpool_fwd", "global_avgpool_bwd",
+           "bias_add", "bias_grad", "softmax_xent", "lc_status_string", "lc_last_error_detail"]
 
 
 class LarsConvError(RuntimeError):
@@ -95,6 +96,18 @@ def lib() -> ctypes.CDLL:
         L.lars_warmup_poly_lr.restype = ctypes.c_float
         L.lars_warmup_poly_lr.argtypes = [ctypes.c_float, ctypes.c_float, ctypes.c_int64, ctypes.c_int64, ctypes.c_int64,
                                           ctypes.c_float]
+        L.relu_fwd.argtypes = [vp, vp, sz, vp]
+        L.relu_bwd.argtypes = [vp, vp, vp, sz, vp]
+        L.maxpool2x2_fwd.argtypes = [vp, vp, vp, i32, i32, i32, i32, i32, vp]
+        L.maxpool2x2_bwd.argtypes = [vp, vp, vp, i32, i32, i32, i32, i32, vp]
+        L.global_avgpool_fwd.argtypes = [vp, vp, i32, i32, i32, i32, i32, vp]
+        L.global_avgpool_bwd.argtypes = [vp, vp, i32, i32, i32, i32, i32, vp]
+        L.bias_add.argtypes = [vp, vp, sz, i32, vp]
+        L.bias_grad.argtypes = [vp, vp, sz, i32, vp]
+        L.softmax_xent.argtypes = [vp, vp, vp, vp, vp, i32, i32, vp]
+        for name in ("relu_fwd", "relu_bwd", "maxpool2x2_fwd", "maxpool2x2_bwd", "global_avgpool_fwd", "global_avgpool_bwd",
+                     "bias_add", "bias_grad", "softmax_xent"):
+            getattr(L, name).restype = i32
         L.lc_status_string.restype = ctypes.c_char_p
         L.lc_status_string.argtypes = [i32]
         L.lc_last_error_detail.restype = ctypes.c_char_p
@@ -233,3 +246,42 @@ def lars_poly_lr(base_lr: float, it: int, max_iter: int, power: float = 2.0) -> 
 
 def lars_warmup_poly_lr(base_lr: float, start_lr: float, it: int, warmup_iters: int, max_iter: int, power: float = 2.0) -> float:
     return float(lib().lars_warmup_poly_lr(base_lr, start_lr, it, warmup_iters, max_iter, power))
+
+
+# ---- glue layers of the small whole-path network (argument marshalling only) ----
+
+def relu_fwd(x, y, count: int, stream=None) -> None:
+    _check(lib().relu_fwd(_ptr(x), _ptr(y), count, _stream(stream)), "relu_fwd")
+
+
+def relu_bwd(x, dy, dx, count: int, stream=None) -> None:
+    _check(lib().relu_bwd(_ptr(x), _ptr(dy), _ptr(dx), count, _stream(stream)), "relu_bwd")
+
+
+def maxpool2x2_fwd(x, y, idx, n: int, c: int, h: int, w: int, layout: int, stream=None) -> None:
+    _check(lib().maxpool2x2_fwd(_ptr(x), _ptr(y), _ptr(idx), n, c, h, w, layout, _stream(stream)), "maxpool2x2_fwd")
+
+
+def maxpool2x2_bwd(dy, idx, dx, n: int, c: int, h: int, w: int, layout: int, stream=None) -> None:
+    _check(lib().maxpool2x2_bwd(_ptr(dy), _ptr(idx), _ptr(dx), n, c, h, w, layout, _stream(stream)), "maxpool2x2_bwd")
+
+
+def global_avgpool_fwd(x, y, n: int, c: int, h: int, w: int, layout: int, stream=None) -> None:
+    _check(lib().global_avgpool_fwd(_ptr(x), _ptr(y), n, c, h, w, layout, _stream(stream)), "global_avgpool_fwd")
+
+
+def global_avgpool_bwd(dy, dx, n: int, c: int, h: int, w: int, layout: int, stream=None) -> None:
+    _check(lib().global_avgpool_bwd(_ptr(dy), _ptr(dx), n, c, h, w, layout, _stream(stream)), "global_avgpool_bwd")
+
+
+def bias_add(y, b, rows: int, k: int, stream=None) -> None:
+    _check(lib().bias_add(_ptr(y), _ptr(b), rows, k, _stream(stream)), "bias_add")
+
+
+def bias_grad(dy, db, rows: int, k: int, stream=None) -> None:
+    _check(lib().bias_grad(_ptr(dy), _ptr(db), rows, k, _stream(stream)), "bias_grad")
+
+
+def softmax_xent(logits, labels, loss, dlogits, row_scratch, n: int, k: int, stream=None) -> None:
+    _check(lib().softmax_xent(_ptr(logits), _ptr(labels), _ptr(loss), _ptr(dlogits), _ptr(row_scratch), n, k, _stream(stream)),
+           "softmax_xent")

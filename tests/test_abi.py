@@ -138,6 +138,25 @@ def test_lars_step_ex_rejects_bad_arguments_before_launch():
     assert call(arr, ctypes.c_void_p(FAKE), need - 1) == lc.LC_ERR_WORKSPACE
 
 
+def test_glue_layers_reject_bad_arguments_before_launch():
+    L = lc.lib()
+    P = ctypes.c_void_p(FAKE)
+    odd = ctypes.c_void_p(FAKE + 2)
+    assert L.relu_fwd(None, P, 10, None) == lc.LC_ERR_NULL
+    assert L.relu_fwd(P, odd, 10, None) == lc.LC_ERR_ALIGN
+    assert L.relu_fwd(P, P, 0, None) == lc.LC_OK                       # nothing to do, nothing launched
+    assert L.relu_bwd(P, None, P, 10, None) == lc.LC_ERR_NULL
+    assert L.maxpool2x2_fwd(P, P, P, 2, 3, 5, 4, lc.LC_NCHW, None) == lc.LC_ERR_SHAPE      # odd height
+    assert L.maxpool2x2_fwd(P, P, None, 2, 3, 4, 4, lc.LC_NCHW, None) == lc.LC_ERR_NULL
+    assert L.maxpool2x2_bwd(P, P, P, 2, 3, 4, 4, 7, None) == lc.LC_ERR_UNSUPPORTED         # unknown layout
+    assert L.global_avgpool_fwd(P, P, 0, 3, 4, 4, lc.LC_NHWC, None) == lc.LC_ERR_SHAPE
+    assert L.global_avgpool_bwd(None, P, 1, 3, 4, 4, lc.LC_NHWC, None) == lc.LC_ERR_NULL
+    assert L.bias_add(P, P, 5, 0, None) == lc.LC_ERR_SHAPE
+    assert L.bias_grad(P, None, 5, 3, None) == lc.LC_ERR_NULL
+    assert L.softmax_xent(P, P, P, P, None, 4, 10, None) == lc.LC_ERR_NULL
+    assert L.softmax_xent(P, P, P, P, P, 4, 0, None) == lc.LC_ERR_SHAPE
+
+
 def test_poly_lr_host_arithmetic():
     assert lc.lars_poly_lr(1.0, 0, 3516) == 1.0
     assert lc.lars_poly_lr(1.0, 3516, 3516) == 0.0

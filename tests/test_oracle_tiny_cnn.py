@@ -64,3 +64,50 @@ def test_train_step_applies_lars_to_the_four_tensors():
         v_ref = lam * (t["d_" + k] + 5e-4 * before[k].astype(np.float64))
         np.testing.assert_allclose(vel[k], v_ref, rtol=1e-6, atol=1e-12)
         np.testing.assert_allclose(params[k], before[k] - v_ref, rtol=1e-6, atol=1e-12)
+
+
+# ---- the glue definitions one by one (textbook values) ----
+
+def test_relu_and_its_gradient_hand_values():
+    x = np.array([-2.0, -0.0, 0.0, 0.5, 3.0])
+    np.testing.assert_array_equal(tiny_cnn.relu(x), [0.0, 0.0, 0.0, 0.5, 3.0])
+    np.testing.assert_array_equal(tiny_cnn.relu_bwd(x, np.array([1.0, 2.0, 3.0, 4.0, 5.0])), [0.0, 0.0, 0.0, 4.0, 5.0])
+
+
+def test_maxpool_hand_example_first_maximum_wins():
+    x = np.array([[[[1.0, 5.0, 2.0, 2.0],
+                    [5.0, 0.0, 2.0, 2.0],
+                    [-1.0, -3.0, 0.0, 7.0],
+                    [-2.0, -0.5, 8.0, 7.5]]]])
+    y, idx = tiny_cnn.maxpool2(x)
+    np.testing.assert_array_equal(y[0, 0], [[5.0, 2.0], [-0.5, 8.0]])
+    np.testing.assert_array_equal(idx[0, 0], [[1, 0], [3, 2]])          # ties: position 1 before 2, 0 before the rest
+    dx = tiny_cnn.maxpool2_bwd(idx, np.array([[[[10.0, 20.0], [30.0, 40.0]]]]), 4, 4)
+    want = np.zeros((4, 4))
+    want[0, 1], want[0, 2], want[3, 1], want[3, 2] = 10.0, 20.0, 30.0, 40.0
+    np.testing.assert_array_equal(dx[0, 0], want)
+
+
+def test_global_average_pool_is_the_mean_and_spreads_its_gradient_evenly():
+    x = np.arange(2 * 3 * 2 * 5, dtype=np.float64).reshape(2, 3, 2, 5)
+    y = tiny_cnn.global_avgpool(x)
+    assert y[1, 2] == np.mean(np.arange(50, 60))
+    dx = tiny_cnn.global_avgpool_bwd(np.ones((2, 3)) * 10.0, 2, 5)
+    assert dx.shape == (2, 3, 2, 5) and np.all(dx == 1.0)
+
+
+def test_softmax_cross_entropy_closed_forms():
+    n, k = 4, 10
+    loss, d = tiny_cnn.softmax_xent(np.full((n, k), 3.7), np.array([0, 3, 9, 3]))   # equal logits: p = 1/k
+    assert abs(loss - np.log(k)) < 1e-12
+    onehot = np.eye(k)[[0, 3, 9, 3]]
+    np.testing.assert_allclose(d, (np.full((n, k), 1.0 / k) - onehot) / n, atol=1e-15)
+    # two classes: loss = log(1 + exp(-(z_label - z_other)))
+    z = np.array([[2.0, -1.0], [0.5, 0.25]])
+    loss, d = tiny_cnn.softmax_xent(z, np.array([0, 1]))
+    want = (np.log1p(np.exp(-3.0)) + np.log1p(np.exp(0.25))) / 2
+    assert abs(loss - want) < 1e-12
+    assert np.allclose(d.sum(axis=1), 0.0, atol=1e-15)
+    # shifting a row's logits changes nothing
+    loss2, d2 = tiny_cnn.softmax_xent(z + np.array([[100.0], [-50.0]]), np.array([0, 1]))
+    assert abs(loss2 - loss) < 1e-12 and np.allclose(d2, d, atol=1e-14)
