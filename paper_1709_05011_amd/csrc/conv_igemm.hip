@@ -950,19 +950,29 @@ __global__ void __launch_bounds__(WGM* WGN * 64) wgrad_f32_kernel(const GemmWgra
 // outside the image for this pixel gets bit 31 of its buffer offset set and the hardware returns zeros.
 // dY rows past the end of the split are cut off by the size of the dY buffer descriptor.
 // ------------------------------------------------------------------------------------------------
-template <int BM, int BN>
+// BF16: operands are bf16 (reduction step 32, LDS holds bf16, MFMA operands come from the transposing LDS read as
+// in wgrad_bf16_kernel); everything about the addressing is the same with 2-byte elements.
+// PLAIN: a 1x1 window with stride 1 and no padding.  Output pixel m then reads input pixel m, X is a plain
+// [M][C] matrix like dY, and both operands are fetched with 16-byte loads at a lane-constant offset plus the
+// step's scalar offset: no per-pixel work at all.
+template <int BM, int BN, bool BF16, bool PLAIN>
 __global__ void __launch_bounds__(256, 4) wgrad_ut_kernel(const GemmWgrad p) {   // 4 blocks per compute unit: lc_wgrad_splits()
-    constexpr int BK = 16;
-    constexpr int AQ = BM / 4, ARPP = 256 / AQ, LA = BK / ARPP;   // dY: 16-byte vectors, ARPP rows per pass
-    constexpr int BV = BN / 64;                                   // X: floats per lane and row (one row per wave and load)
+    using E = typename OutT<BF16>::type;                          // operand element type (float, or the bits of a bf16)
+    constexpr int ES = (int)sizeof(E);
+    constexpr int EPC = 16 / ES;                                  // elements per 16-byte vector
+    constexpr int BK = BF16 ? 32 : 16;
+    constexpr int AQ = BM / EPC, ARPP = 256 / AQ, LA = BK / ARPP; // dY: 16-byte vectors, ARPP rows per pass
+    constexpr int BV = BN / 64;                                   // X: elements per lane and row (one row per wave and load)
     constexpr int RW = BK / 4;                                    // X rows per wave and step
-    constexpr int PA = BM + 4, PB = BN + 4;
+    constexpr int BQ = BN / EPC, BRPP = 256 / BQ, LB = BK / BRPP; // PLAIN: X in 16-byte vectors like dY
+    constexpr int PA = BM + (BF16 ? 32 : 4), PB = BN + (BF16 ? 32 : 4);
     constexpr int WTM = BM / 2, WTN = BN / 2, TM = WTM / 32, TN = WTN / 32;
-    static_assert(BV == 1 || BV == 2, "tile shape");
-    using BVt = typename std::conditional<BV == 2, float2, float>::type;
+    static_assert(BV == 2 || (BV == 1 && !BF16), "tile shape");
+    static_assert(256 % AQ == 0 && BK % ARPP == 0 && LA >= 1, "tile shape");
+    using BVt = typename std::conditional<BF16, unsigned, typename std::conditional<BV == 2, float2, float>::type>::type;
 
-    __shared__ __attribute__((aligned(16))) float As[2][BK * PA];
-    __shared__ __attribute__((aligned(16))) float Bs[2][BK * PB];
+    __shared__ __attribute__((aligned(16))) E As[2][BK * PA];
+    __shared__ __attribute__((aligned(16))) E Bs[2][BK * PB];
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -982,28 +992,37 @@ __global__ void __launch_bounds__(256, 4) wgrad_ut_kernel(const GemmWgrad p) {  
 
     // dY: lane-constant offset inside a 16-row step; the step's first row is the scalar offset
     const int a_cq = tid % AQ, a_kr = tid / AQ;
-    const int a_col = k0 + a_cq * 4;
+    const int a_col = k0 + a_cq * EPC;
     unsigned a_voff[LA];
 #pragma unroll
-    for (int i = 0; i < LA; ++i) a_voff[i] = a_col < K_ ? (unsigned)(((a_kr + i * ARPP) * K_ + a_col) * 4) : kBufferBytes;
+    for (int i = 0; i < LA; ++i) a_voff[i] = a_col < K_ ? (unsigned)(((a_kr + i * ARPP) * K_ + a_col) * ES) : kBufferBytes;
     const __amdgpu_buffer_rsrc_t a_rsrc = __builtin_amdgcn_make_buffer_rsrc(
-        (void*)(static_cast<const float*>(p.dy) + (long long)m_begin * K_), 0, (int)((unsigned)(m_end - m_begin) * K_ * 4u),
+        (void*)(static_cast<const E*>(p.dy) + (long long)m_begin * K_), 0, (int)((unsigned)(m_end - m_begin) * K_ * (unsigned)ES),
         (int)kBufferWords3);
 
+    // PLAIN: X addressed like dY
+    const int pb_cq = tid % BQ, pb_kr = tid / BQ;
+    unsigned pb_voff[LB];
+#pragma unroll
+    for (int i = 0; i < LB; ++i)
+        pb_voff[i] = j0 + pb_cq * EPC < p.J ? (unsigned)(((pb_kr + i * BRPP) * C_ + j0 + pb_cq * EPC) * ES) : kBufferBytes;
+    const __amdgpu_buffer_rsrc_t pb_rsrc = __builtin_amdgcn_make_buffer_rsrc(
+        (void*)(static_cast<const E*>(p.x) + (long long)m_begin * C_), 0, (int)((unsigned)(m_end - m_begin) * C_ * (unsigned)ES),
+        (int)kBufferWords3);
     // X: the lane's column j = (r, s, c): byte offset of the tap relative to the pixel's window origin, bit position
     const int b_col = j0 + lane * BV;
     unsigned b_voff = kBufferBytes, b_up = 0;
     if (b_col < p.J) {
         const int rs = b_col / C_, fc = b_col - rs * C_;
         const int fr = rs / S_, fs = rs - fr * S_;
-        b_voff = (unsigned)(((fr * W_ + fs) * C_ + fc) * 4);
+        b_voff = (unsigned)(((fr * W_ + fs) * C_ + fc) * ES);
         b_up = 31u - (unsigned)rs;
     }
     const int pq = P_ * Q_;
     const int img_first = m_begin / pq;
     const int phb = max(ph_, 0), pwb = max(pw_, 0);
     const __amdgpu_buffer_rsrc_t b_rsrc = __builtin_amdgcn_make_buffer_rsrc(
-        (void*)(static_cast<const float*>(p.x) + ((long long)img_first * H_ * W_ - ((long long)phb * W_ + pwb)) * C_), 0,
+        (void*)(static_cast<const E*>(p.x) + ((long long)img_first * H_ * W_ - ((long long)phb * W_ + pwb)) * C_), 0,
         (int)kBufferBytes, (int)kBufferWords3);
     // scalar state of this wave's RW rows: (image - img_first, p, q) of row m_begin + step * 16 + wave * RW + i
     int s_img[RW], s_p[RW], s_q[RW];
@@ -1026,11 +1045,19 @@ __global__ void __launch_bounds__(256, 4) wgrad_ut_kernel(const GemmWgrad p) {  
 
     float4 ra[LA];
     BVt rb[RW];
-    auto gload = [&]() {
-        const int a_soff = (mt - m_begin) * K_ * 4;
+    float4 prb[LB];
+    auto gload = [&]() __attribute__((always_inline)) {
+        const int a_soff = (mt - m_begin) * K_ * ES;
 #pragma unroll
         for (int i = 0; i < LA; ++i)
             ra[i] = __builtin_bit_cast(float4, __builtin_amdgcn_raw_buffer_load_b128(a_rsrc, (int)a_voff[i], a_soff, 0));
+        if constexpr (PLAIN) {
+            const int b_soff = (mt - m_begin) * C_ * ES;
+#pragma unroll
+            for (int i = 0; i < LB; ++i)
+                prb[i] = __builtin_bit_cast(float4, __builtin_amdgcn_raw_buffer_load_b128(pb_rsrc, (int)pb_voff[i], b_soff, 0));
+            return;
+        }
 #pragma unroll
         for (int i = 0; i < RW; ++i) {
             const int h0 = s_p[i] * sh_ - ph_, w0 = s_q[i] * sw_ - pw_;
@@ -1044,16 +1071,19 @@ __global__ void __launch_bounds__(256, 4) wgrad_ut_kernel(const GemmWgrad p) {  
             const unsigned hm = (full << (rlo * S_)) & (full >> ((R_ - 1 - rhi) * S_));
             const unsigned wmask = rep * (((2u << sspan) - 1u) << slo);
             const unsigned inv = ok ? ~(hm & wmask) : ~0u;        // taps outside the image for this pixel
-            const int soff = ok ? (((s_img[i] * H_ + s_p[i] * sh_ + phb - ph_) * W_ + s_q[i] * sw_ + pwb - pw_) * C_) * 4 : 0;
+            const int soff = ok ? (((s_img[i] * H_ + s_p[i] * sh_ + phb - ph_) * W_ + s_q[i] * sw_ + pwb - pw_) * C_) * ES : 0;
             const unsigned vo = ((inv << b_up) & kBufferBytes) | b_voff;
-            if constexpr (BV == 2)
+            if constexpr (BF16)
+                rb[i] = __builtin_amdgcn_raw_buffer_load_b32(b_rsrc, (int)vo, soff, 0);
+            else if constexpr (BV == 2)
                 rb[i] = __builtin_bit_cast(float2, __builtin_amdgcn_raw_buffer_load_b64(b_rsrc, (int)vo, soff, 0));
             else
                 rb[i] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(b_rsrc, (int)vo, soff, 0));
         }
     };
-    auto advance = [&]() {
+    auto advance = [&]() __attribute__((always_inline)) {
         mt += BK;
+        if constexpr (PLAIN) return;
 #pragma unroll
         for (int i = 0; i < RW; ++i) {
             int q = s_q[i] + d_q;
@@ -1067,9 +1097,14 @@ __global__ void __launch_bounds__(256, 4) wgrad_ut_kernel(const GemmWgrad p) {  
             s_img[i] += d_img + (cp ? 1 : 0);
         }
     };
-    auto sstore = [&](int buf) {
+    auto sstore = [&](int buf) __attribute__((always_inline)) {
 #pragma unroll
-        for (int i = 0; i < LA; ++i) *reinterpret_cast<float4*>(&As[buf][(a_kr + i * ARPP) * PA + a_cq * 4]) = ra[i];
+        for (int i = 0; i < LA; ++i) *reinterpret_cast<float4*>(&As[buf][(a_kr + i * ARPP) * PA + a_cq * EPC]) = ra[i];
+        if constexpr (PLAIN) {
+#pragma unroll
+            for (int i = 0; i < LB; ++i) *reinterpret_cast<float4*>(&Bs[buf][(pb_kr + i * BRPP) * PB + pb_cq * EPC]) = prb[i];
+            return;
+        }
 #pragma unroll
         for (int i = 0; i < RW; ++i) *reinterpret_cast<BVt*>(&Bs[buf][(wave * RW + i) * PB + lane * BV]) = rb[i];
     };
@@ -1082,44 +1117,71 @@ __global__ void __launch_bounds__(256, 4) wgrad_ut_kernel(const GemmWgrad p) {  
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
-    // Fragments: slot k2 & 1 holds reduction rows 2*k2 and 2*k2 + 1 of the step (lane half picks the row)
-    float fa[2][TM], fb[2][TN];
-    auto read_frags = [&](int buf, int k2, int slot) __attribute__((always_inline)) {
-        const float* as = &As[buf][(2 * k2 + (lane >> 5)) * PA + wm * WTM + (lane & 31)];
-        const float* bs = &Bs[buf][(2 * k2 + (lane >> 5)) * PB + wn * WTN + (lane & 31)];
+    // Fragments of one group of reduction rows (fp32: 2 rows, one MFMA of k = 2 per tile; bf16: 16 rows, one MFMA of
+    // k = 16 per tile), double-buffered: slot g & 1 holds group g of the step.
+    constexpr int NG = BF16 ? BK / 16 : BK / 2;
+    using Frag = typename std::conditional<BF16, bf16x8, float>::type;
+    Frag fa[2][TM], fb[2][TN];
+    typedef short s16x4 __attribute__((ext_vector_type(4)));
+    typedef short s16x8 __attribute__((ext_vector_type(8)));
+    // bf16: the transposing LDS read (see wgrad_bf16_kernel): this lane's row and column inside a 16-row group
+    const int tr_row = 8 * (lane >> 5) + ((lane & 15) >> 2), tr_col = 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
+    auto read_frags = [&](int buf, int g, int slot) __attribute__((always_inline)) {
+        if constexpr (BF16) {
+            auto one = [&](const E* base, int pitch) __attribute__((always_inline)) {
+                const E* q = base + (16 * g + tr_row) * pitch + tr_col;
+                const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(uintptr_t)q);
+                const s16x4 hi =
+                    __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(uintptr_t)(q + 4 * pitch));
+                const s16x8 v = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+                return __builtin_bit_cast(bf16x8, v);
+            };
 #pragma unroll
-        for (int i = 0; i < TM; ++i) fa[slot][i] = as[i * 32];
+            for (int i = 0; i < TM; ++i) fa[slot][i] = one(&As[buf][wm * WTM + i * 32], PA);
 #pragma unroll
-        for (int j = 0; j < TN; ++j) fb[slot][j] = bs[j * 32];
+            for (int j = 0; j < TN; ++j) fb[slot][j] = one(&Bs[buf][wn * WTN + j * 32], PB);
+        } else {
+            const E* as = &As[buf][(2 * g + (lane >> 5)) * PA + wm * WTM + (lane & 31)];
+            const E* bs = &Bs[buf][(2 * g + (lane >> 5)) * PB + wn * WTN + (lane & 31)];
+#pragma unroll
+            for (int i = 0; i < TM; ++i) fa[slot][i] = as[i * 32];
+#pragma unroll
+            for (int j = 0; j < TN; ++j) fb[slot][j] = bs[j * 32];
+        }
     };
-    auto mfma_pair = [&](int slot) __attribute__((always_inline)) {
+    auto mfma_group = [&](int slot) __attribute__((always_inline)) {
 #pragma unroll
         for (int i = 0; i < TM; ++i)
 #pragma unroll
-            for (int j = 0; j < TN; ++j)
-                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[slot][i], fb[slot][j], acc[i][j], 0, 0, 0);
+            for (int j = 0; j < TN; ++j) {
+                if constexpr (BF16)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[slot][i], fb[slot][j], acc[i][j], 0, 0, 0);
+                else
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[slot][i], fb[slot][j], acc[i][j], 0, 0, 0);
+            }
     };
 
-    // One step out of LDS buffer `cur` (a literal at each call).  On entry slot 0 holds the step's first pair of
-    // rows and the registers hold the next step's rows.  Those go to the other LDS buffer after the second
-    // group of MFMAs, the loads of the step after next follow into the same registers, and behind the barrier
-    // near the end the first fragments of the next step are read while the last MFMAs run.  Steps past the end
-    // of the split are fetched and stored like the others: all of their rows are past m_end, so nothing is read
-    // from memory and zeros are stored.
+    // One step out of LDS buffer `cur` (a literal at each call).  On entry slot 0 holds the step's first group of
+    // rows and the registers hold the next step's rows.  Those go to the other LDS buffer early in the step, the
+    // loads of the step after next follow into the same registers, and behind the barrier before the last group
+    // the first fragments of the next step are read while the last MFMAs run.  Steps past the end of the split
+    // are fetched and stored like the others: all of their rows are past m_end, so nothing is read from memory
+    // and zeros are stored.
+    constexpr int G_STORE = NG > 2 ? 1 : 0, G_LOAD = NG > 2 ? 3 : 0;
     auto step = [&](int cur) __attribute__((always_inline)) {
 #pragma unroll
-        for (int k2 = 0; k2 < BK / 2; ++k2) {
-            if (k2 + 1 < BK / 2) {
-                read_frags(cur, k2 + 1, (k2 + 1) & 1);
+        for (int g = 0; g < NG; ++g) {
+            if (g + 1 < NG) {
+                read_frags(cur, g + 1, (g + 1) & 1);
             } else {
                 lds_barrier();
                 read_frags(cur ^ 1, 0, 0);
             }
             __builtin_amdgcn_sched_barrier(0);
-            mfma_pair(k2 & 1);
+            mfma_group(g & 1);
             __builtin_amdgcn_sched_barrier(0);
-            if (k2 == 1) sstore(cur ^ 1);
-            if (k2 == 3) {
+            if (g == G_STORE) sstore(cur ^ 1);
+            if (g == G_LOAD) {
                 advance();
                 gload();
             }
@@ -1560,35 +1622,41 @@ static lc_status launch_wgrad_bf16(const GemmWgrad& p, hipStream_t stream) {
     return lc_end_call();
 }
 
-// Whether wgrad_ut_kernel takes this problem: fp32, 16-byte vectors, a window of at most 32 taps, and buffer
-// offsets (a split's rows of dY; the images a split touches plus one window of X) below 2^31 bytes.
+// Whether wgrad_ut_kernel takes this problem: 16-byte vectors (channel counts multiples of 4, of 8 for bf16), a
+// window of at most 32 taps, and buffer offsets (a split's rows of dY; the images a split touches plus one
+// window of X) below 2^31 bytes.
 static bool wgrad_ut_ok(const GemmWgrad& p) {
     static const bool off = getenv("LARSCONV_NO_UNIFORM_TAP") != nullptr;     // comparison runs
-    if (off || p.bf16 || p.C % 4 != 0 || p.K % 4 != 0 || (long long)p.R * p.S > 32) return false;
+    const int epc = p.bf16 ? 8 : 4, es = p.bf16 ? 2 : 4;
+    if (off || p.C % epc != 0 || p.K % epc != 0 || (long long)p.R * p.S > 32) return false;
     if ((((uintptr_t)p.dy | (uintptr_t)p.x) & 15) != 0) return false;
-    const long long rows = (long long)p.m_per_split + 32;
-    const long long a_span = rows * p.K * 4;
+    const long long rows = (long long)p.m_per_split + 64;
+    const long long a_span = rows * p.K * es;
     const long long images = rows / ((long long)p.P * p.Q) + 2;
-    const long long b_span = ((images * p.H + (p.ph > 0 ? p.ph : 0) + p.R + 1) * p.W + p.S + 1) * p.C * 4;
+    const long long b_span = ((images * p.H + (p.ph > 0 ? p.ph : 0) + p.R + 1) * p.W + p.S + 1) * p.C * es;
     return a_span < 0x7fff0000LL && b_span < 0x7fff0000LL;
 }
 
-template <int BM, int BN>
+template <int BM, int BN, bool BF16, bool PLAIN>
 static lc_status launch_wgrad_ut(const GemmWgrad& p, hipStream_t stream) {
     const long long tiles = (long long)((p.K + BM - 1) / BM) * ((p.J + BN - 1) / BN);
     if (tiles <= 0 || tiles * p.splits > 0x7fffffffLL) return LC_ERR_UNSUPPORTED;
-    hipLaunchKernelGGL((wgrad_ut_kernel<BM, BN>), dim3((unsigned)(tiles * p.splits)), dim3(256), 0, stream, p);
+    hipLaunchKernelGGL((wgrad_ut_kernel<BM, BN, BF16, PLAIN>), dim3((unsigned)(tiles * p.splits)), dim3(256), 0, stream, p);
     return lc_end_call();
 }
 
 template <bool BF16>
 static lc_status dispatch_wgrad(const GemmWgrad& p, hipStream_t stream) {
-    if (!BF16 && wgrad_ut_ok(p)) {
+    if (wgrad_ut_ok(p) && !(BF16 && getenv("LARSCONV_WGRAD_WIDEN"))) {
         // only the 128 x 128 tiling: with narrower tiles a step has too few MFMAs to hide the scalar work and the
-        // narrower loads, and wgrad_f32_kernel measures faster
+        // narrower loads, and the kernels below measure faster
         int bm, bn;
         wgrad_tile(p.K, p.J, &bm, &bn);
-        if (bm == 128 && bn == 128) return launch_wgrad_ut<128, 128>(p, stream);
+        // (bf16: only the plain 1x1 case -- with eight pixels per wave and step and an eighth of the MFMA time the
+        // per-pixel scalar work of the general case does not hide)
+        const bool plain = p.R == 1 && p.S == 1 && p.sh == 1 && p.sw == 1 && p.ph == 0 && p.pw == 0 && p.H == p.P && p.W == p.Q;
+        if (bm == 128 && bn == 128 && plain) return launch_wgrad_ut<128, 128, BF16, true>(p, stream);
+        if (bm == 128 && bn == 128 && !BF16) return launch_wgrad_ut<128, 128, false, false>(p, stream);
     }
     if (BF16 && p.C % 8 == 0 && p.K % 8 == 0 && aligned16(p.dy) && aligned16(p.x) && !getenv("LARSCONV_WGRAD_WIDEN")) {
         int bm, bn;                                   // the bf16 matrix pipe; LARSCONV_WGRAD_WIDEN=1: comparison runs
