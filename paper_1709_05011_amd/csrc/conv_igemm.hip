@@ -626,12 +626,20 @@ __global__ void __launch_bounds__(256, 3) conv_gemm_pk_kernel(const GemmConv p) 
                 const __amdgpu_buffer_rsrc_t d_rsrc = __builtin_amdgcn_make_buffer_rsrc(
                     (void*)(static_cast<E*>(p.d) + (long long)m0 * ldd_), 0, (int)(rows_left > 0x7fffffffLL ? 0x7fffffffLL : rows_left),
                     (int)kBufferWords3);
+                // bf16 with an even row length: neighbouring lanes (neighbouring columns) trade values so that every
+                // lane stores a pair of columns as one dword -- even lanes for row r0, odd lanes for row r0 + 1.
+                const bool pairs = BF16 && ((N_ | ldd_) & 1) == 0;
+                const int odd = lane & 1;
                 unsigned d_voff[TN];
 #pragma unroll
                 for (int j = 0; j < TN; ++j) {
                     const int col = n0 + wn * WTN + j * 32 + (lane & 31);
                     d_voff[j] = col < N_ ? (unsigned)((4 * (lane >> 5) * ldd_ + col) * ES) : kBufferBytes;
+                    if (pairs && col < N_) d_voff[j] = (unsigned)(((4 * (lane >> 5) + odd) * ldd_ + (col & ~1)) * ES);
                 }
+                // byte selectors of v_perm_b32 over {received, own}: even lanes keep their low half and take the
+                // neighbour's low half above it; odd lanes take the neighbour's high half below their own high half
+                const unsigned perm_sel = odd ? 0x03020706u : 0x05040100u;
 #pragma unroll
                 for (int i = 0; i < TM; ++i)
 #pragma unroll
@@ -646,8 +654,14 @@ __global__ void __launch_bounds__(256, 3) conv_gemm_pk_kernel(const GemmConv p) 
                                 typedef float f32x2 __attribute__((ext_vector_type(2)));
                                 const f32x2 pr = {acc[i][j][v], acc[i][j][v + 1]};
                                 const unsigned u = __builtin_bit_cast(unsigned, __builtin_convertvector(pr, bf16x2));
-                                __builtin_amdgcn_raw_buffer_store_b16((short)(u & 0xffffu), d_rsrc, (int)d_voff[j], soff, 0);
-                                __builtin_amdgcn_raw_buffer_store_b16((short)(u >> 16), d_rsrc, (int)d_voff[j], soff + ldd_ * ES, 0);
+                                if (pairs) {
+                                    // u = {row r0 | row r0 + 1} of this lane's column; swap with the neighbouring lane
+                                    const unsigned got = (unsigned)__builtin_amdgcn_mov_dpp((int)u, 0xB1 /* quad_perm 1,0,3,2 */, 0xF, 0xF, true);
+                                    __builtin_amdgcn_raw_buffer_store_b32(__builtin_amdgcn_perm(got, u, perm_sel), d_rsrc, (int)d_voff[j], soff, 0);
+                                } else {
+                                    __builtin_amdgcn_raw_buffer_store_b16((short)(u & 0xffffu), d_rsrc, (int)d_voff[j], soff, 0);
+                                    __builtin_amdgcn_raw_buffer_store_b16((short)(u >> 16), d_rsrc, (int)d_voff[j], soff + ldd_ * ES, 0);
+                                }
                             } else {
                                 __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(acc[i][j][v]), d_rsrc, (int)d_voff[j], soff, 0);
                                 __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(acc[i][j][v + 1]), d_rsrc, (int)d_voff[j], soff + ldd_ * ES, 0);
