@@ -981,7 +981,7 @@ __global__ void __launch_bounds__(256, 4) wgrad_ut_kernel(const GemmWgrad p) {  
     constexpr int BQ = BN / EPC, BRPP = 256 / BQ, LB = BK / BRPP; // PLAIN: X in 16-byte vectors like dY
     constexpr int PA = BM + (BF16 ? 32 : 4), PB = BN + (BF16 ? 32 : 4);
     constexpr int WTM = BM / 2, WTN = BN / 2, TM = WTM / 32, TN = WTN / 32;
-    static_assert(BV == 2 || (BV == 1 && !BF16), "tile shape");
+    static_assert(PLAIN || BV == 2 || (BV == 1 && !BF16), "tile shape");
     static_assert(256 % AQ == 0 && BK % ARPP == 0 && LA >= 1, "tile shape");
     using BVt = typename std::conditional<BF16, unsigned, typename std::conditional<BV == 2, float2, float>::type>::type;
 
@@ -1670,6 +1670,11 @@ static lc_status dispatch_wgrad(const GemmWgrad& p, hipStream_t stream) {
         // per-pixel scalar work of the general case does not hide)
         const bool plain = p.R == 1 && p.S == 1 && p.sh == 1 && p.sw == 1 && p.ph == 0 && p.pw == 0 && p.H == p.P && p.W == p.Q;
         if (bm == 128 && bn == 128 && plain) return launch_wgrad_ut<128, 128, BF16, true>(p, stream);
+        if (plain) {                                  // (no per-pixel work: pays with every tile shape)
+            if (bm == 128) return launch_wgrad_ut<128, 64, BF16, true>(p, stream);
+            if (bn == 128) return launch_wgrad_ut<64, 128, BF16, true>(p, stream);
+            return launch_wgrad_ut<64, 64, BF16, true>(p, stream);
+        }
         if (bm == 128 && bn == 128 && !BF16) return launch_wgrad_ut<128, 128, false, false>(p, stream);
     }
     if (BF16 && p.C % 8 == 0 && p.K % 8 == 0 && aligned16(p.dy) && aligned16(p.x) && !getenv("LARSCONV_WGRAD_WIDEN")) {
