@@ -222,3 +222,48 @@ def test_resnet50_conv_sweep_batch128_sampled():
         assert np.max(np.abs(dw[cw[:, 0], cw[:, 2], cw[:, 3], cw[:, 1]] - ref)) <= TOL * np.max(np.abs(ref)), idx
         del xd, wd, dyd
         torch.cuda.empty_cache()
+
+
+def test_output_beyond_two_gibibytes_sampled():
+    """A 1x1 layer whose output (and output gradient) is larger than 2^31 bytes: the kernels address tiles with
+    32-bit offsets relative to per-tile bases, which must hold however large the tensor is."""
+    n, c, hw, k = 2200, 64, 14, 1280
+    p = q = hw
+    assert n * p * q * k * 4 > 2 ** 31
+    x = synth.normal((n, hw, hw, c), 9100)
+    wt = synth.normal((k, 1, 1, c), 9101, std=float(np.sqrt(2.0 / c)))
+    block = synth.normal((30_000_017,), 9102)                       # dY: a long non-periodic-looking block, repeated
+    total = n * p * q * k
+    dy = np.resize(block, total).reshape(n, p, q, k)
+    d = lc.ConvDesc(n, c, hw, hw, k, 1, 1, 1, 1, 0, 0, lc.LC_F32, lc.LC_NHWC)
+    xd, wd, dyd = gu.dev(x), gu.dev(wt), gu.dev(dy)
+    y = torch.empty((n, p, q, k), dtype=torch.float32, device=gu.DEV)
+    dx = torch.empty((n, hw, hw, c), dtype=torch.float32, device=gu.DEV)
+    dw = torch.empty((k, 1, 1, c), dtype=torch.float32, device=gu.DEV)
+    lc.conv2d_fwd(d, xd, wd, y, gu.workspace(lc.conv2d_workspace_bytes(d, lc.LC_PASS_FWD)))
+    lc.conv2d_bwd_data(d, dyd, wd, dx, gu.workspace(lc.conv2d_workspace_bytes(d, lc.LC_PASS_BWD_DATA)))
+    lc.conv2d_bwd_weight(d, xd, dyd, dw, gu.workspace(lc.conv2d_workspace_bytes(d, lc.LC_PASS_BWD_WEIGHT)))
+    torch.cuda.synchronize()
+    # the last rows of the output (beyond the 2 GiB mark) and a sample over everything
+    tail = y[-3:].cpu().numpy()
+    ref_tail = (x[-3:].reshape(-1, c).astype(np.float64) @ wt.reshape(k, c).astype(np.float64).T).reshape(3, p, q, k)
+    assert gu.scaled_err(tail, ref_tail) <= TOL
+    y = y.cpu().numpy()
+    cy = synth.sample_coords(2048, (n, k, p, q), 9103)
+    ref, mag = oracle.conv2d_fwd_at(x, wt, cy, 1, 0, oracle.NHWC)
+    got = y[cy[:, 0], cy[:, 2], cy[:, 3], cy[:, 1]]
+    assert np.max(np.abs(got - ref)) <= TOL * np.max(np.abs(ref))
+    del y
+    dx = dx.cpu().numpy()
+    cx = synth.sample_coords(1024, (n, c, hw, hw), 9104)
+    ref, _ = oracle.conv2d_bwd_data_at(dy, wt, (hw, hw), cx, 1, 0, oracle.NHWC)
+    got = dx[cx[:, 0], cx[:, 2], cx[:, 3], cx[:, 1]]
+    assert np.max(np.abs(got - ref)) <= TOL * np.max(np.abs(ref))
+    # last image of dX: its dY rows lie beyond the 2 GiB mark
+    ref_last = (dy[-1].reshape(-1, k).astype(np.float64) @ wt.reshape(k, c).astype(np.float64)).reshape(hw, hw, c)
+    assert gu.scaled_err(dx[-1], ref_last) <= TOL
+    dw = dw.cpu().numpy()
+    cw = synth.sample_coords(128, (k, c, 1, 1), 9105)
+    ref, mag = oracle.conv2d_bwd_weight_at(x, dy, (1, 1), cw, 1, 0, oracle.NHWC)
+    got = dw[cw[:, 0], cw[:, 2], cw[:, 3], cw[:, 1]]
+    assert np.max(np.abs(got - ref)) <= TOL * np.max(np.abs(ref))
