@@ -347,6 +347,50 @@ def run_lars(args):
             "frac_of_hbm_peak": round(nbytes / (med * 1e-3) / 1e9 / PEAK_HBM, 4), "bytes_per_param": LARS_BYTES_PER_PARAM}
 
 
+def run_batchnorm(args):
+    """Batch normalisation (training mode) over the outputs of the distinct ResNet-50 convolution shapes, forward and
+    backward timed separately; GB/s by the algorithmic bytes (forward 12, backward 20 bytes per element)."""
+    import torch
+    from paper_1709_05011_amd import larsconv as lc
+    from paper_1709_05011_amd import synth
+
+    batch = args.batch or 256
+    gen = torch.Generator(device="cuda:0")
+    gen.manual_seed(0x5EED0500)
+    rows, seen = [], set()
+    tot = {"fwd": [0.0, 0.0], "bwd": [0.0, 0.0]}
+    for cs, count in synth.resnet50_distinct_shapes(batch):
+        key = (cs.k, cs.p, cs.q)
+        if key in seen:
+            continue
+        seen.add(key)
+        n, c, h, w = cs.n, cs.k, cs.p, cs.q
+        x = torch.randn((n, h, w, c), generator=gen, device="cuda:0")
+        dy = torch.randn((n, h, w, c), generator=gen, device="cuda:0")
+        y, dx = torch.empty_like(x), torch.empty_like(x)
+        g, b = torch.ones(c, device="cuda:0"), torch.zeros(c, device="cuda:0")
+        m, s, dg, db = (torch.empty(c, device="cuda:0") for _ in range(4))
+        ws = make_workspace(lc.batchnorm_workspace_bytes(n, c, h, w, lc.LC_NHWC), torch)
+        f_med, _ = time_call(torch, lambda: lc.batchnorm_fwd(x, g, b, y, m, s, n, c, h, w, 1e-5, lc.LC_NHWC, ws), args.iters)
+        b_med, _ = time_call(torch, lambda: lc.batchnorm_bwd(x, dy, g, m, s, dx, dg, db, n, c, h, w, lc.LC_NHWC, ws), args.iters)
+        elems = x.numel()
+        row = {"c": c, "hw": h, "MB": round(elems * 4 / 1e6, 1), "fwd_ms": round(f_med, 4), "bwd_ms": round(b_med, 4),
+               "fwd_GBps": round(12 * elems / (f_med * 1e-3) / 1e9, 1), "bwd_GBps": round(20 * elems / (b_med * 1e-3) / 1e9, 1)}
+        rows.append(row)
+        log(json.dumps(row))
+        tot["fwd"][0] += f_med; tot["fwd"][1] += 12 * elems
+        tot["bwd"][0] += b_med; tot["bwd"][1] += 20 * elems
+        del x, dy, y, dx, ws
+        torch.cuda.empty_cache()
+    out = {"batchnorm": "outputs of the distinct ResNet-50 convolution shapes", "batch": batch, "layout": "NHWC", "dtype": "f32",
+           "bytes_per_element": {"fwd": 12, "bwd": 20}}
+    for p_, (ms, nbytes) in tot.items():
+        gbps = nbytes / (ms * 1e-3) / 1e9
+        out[p_] = {"GBps": round(gbps, 1), "frac_of_hbm_peak": round(gbps / PEAK_HBM, 4)}
+    out["rows"] = rows
+    return out
+
+
 def run_copy_calibration(args):
     """A plain device-to-device copy of known size: what the FETCH_SIZE / WRITE_SIZE counters of rocprofv3 read
     for it gives the factor by which the counters of the other kernels are scaled."""
@@ -379,6 +423,7 @@ def main():
     ap.add_argument("--iters", type=int, default=10)
     ap.add_argument("--lars", choices=["resnet50", "alexnet_bn"])
     ap.add_argument("--rotate", type=int, default=1)
+    ap.add_argument("--batchnorm", action="store_true", help="batch-normalisation layers alone, GB/s against HBM peak")
     ap.add_argument("--copy-calib", action="store_true", help="run a 1 GiB device copy (counter calibration)")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -390,6 +435,8 @@ def main():
         res = run_sweep(args)
     elif args.lars:
         res = run_lars(args)
+    elif args.batchnorm:
+        res = run_batchnorm(args)
     else:
         res = run_train_step(args)
     print(json.dumps(res), flush=True)

@@ -159,6 +159,23 @@ lc_status bias_grad(const float* dy, float* db, size_t rows, int k, void* hip_st
 lc_status softmax_xent(const float* logits, const int32_t* labels, float* loss, float* dlogits, float* row_scratch, int n, int k,
                        void* hip_stream);
 
+/* ---- Batch normalisation, training mode (fp32) ----
+ * The paper adds batch normalisation after each convolution of AlexNet ("Scaling up Batch Size") and trains
+ * ResNet-50, which has it throughout; this is the textbook layer with batch statistics: per channel c over the
+ * m = n*h*w values of the batch, mean and biased variance, xhat = (x - mean)/sqrt(var + eps),
+ * y = gamma[c]*xhat + beta[c].  save_mean, save_invstd (c floats each) receive mean and 1/sqrt(var + eps) for
+ * the backward pass.  Backward: dbeta[c] = sum dy, dgamma[c] = sum dy*xhat,
+ * dx = gamma[c]*invstd*(dy - dbeta[c]/m - xhat*dgamma[c]/m).  No running averages.
+ * x, y, dy, dx: [n,c,h,w] in `layout`, fp32, 4-byte aligned (16-byte alignment with c a multiple of 4 takes the
+ * vector path); per-channel arrays fp32 DEVICE.  Sums run in a fixed order (bit-identical reruns). */
+size_t batchnorm_workspace_bytes(int n, int c, int h, int w, lc_layout layout);
+lc_status batchnorm_fwd(const float* x, const float* gamma, const float* beta, float* y, float* save_mean, float* save_invstd,
+                        int n, int c, int h, int w, float eps, lc_layout layout, void* workspace, size_t workspace_bytes,
+                        void* hip_stream);
+lc_status batchnorm_bwd(const float* x, const float* dy, const float* gamma, const float* save_mean, const float* save_invstd,
+                        float* dx, float* dgamma, float* dbeta, int n, int c, int h, int w, lc_layout layout, void* workspace,
+                        size_t workspace_bytes, void* hip_stream);
+
 /* Static, human-readable name of a status code. */
 const char* lc_status_string(lc_status status);
 

@@ -22,7 +22,8 @@ LC_PASS_FWD, LC_PASS_BWD_DATA, LC_PASS_BWD_WEIGHT = 0, 1, 2
 EXPORTS = ["conv2d_out_shape", "conv2d_workspace_bytes", "conv2d_fwd", "conv2d_bwd_data", "conv2d_bwd_weight",
            "lars_workspace_bytes", "lars_step", "lars_step_ex", "lars_poly_lr", "lars_warmup_poly_lr",
            "relu_fwd", "relu_bwd", "maxpool2x2_fwd", "maxpool2x2_bwd", "global_avgpool_fwd", "global_avgpool_bwd",
-           "bias_add", "bias_grad", "softmax_xent", "lc_status_string", "lc_last_error_detail"]
+           "bias_add", "bias_grad", "softmax_xent", "batchnorm_workspace_bytes", "batchnorm_fwd", "batchnorm_bwd",
+           "lc_status_string", "lc_last_error_detail"]
 
 
 class LarsConvError(RuntimeError):
@@ -108,6 +109,12 @@ def lib() -> ctypes.CDLL:
         for name in ("relu_fwd", "relu_bwd", "maxpool2x2_fwd", "maxpool2x2_bwd", "global_avgpool_fwd", "global_avgpool_bwd",
                      "bias_add", "bias_grad", "softmax_xent"):
             getattr(L, name).restype = i32
+        L.batchnorm_workspace_bytes.restype = sz
+        L.batchnorm_workspace_bytes.argtypes = [i32, i32, i32, i32, i32]
+        L.batchnorm_fwd.restype = i32
+        L.batchnorm_fwd.argtypes = [vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, ctypes.c_float, i32, vp, sz, vp]
+        L.batchnorm_bwd.restype = i32
+        L.batchnorm_bwd.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, vp, sz, vp]
         L.lc_status_string.restype = ctypes.c_char_p
         L.lc_status_string.argtypes = [i32]
         L.lc_last_error_detail.restype = ctypes.c_char_p
@@ -285,3 +292,22 @@ def bias_grad(dy, db, rows: int, k: int, stream=None) -> None:
 def softmax_xent(logits, labels, loss, dlogits, row_scratch, n: int, k: int, stream=None) -> None:
     _check(lib().softmax_xent(_ptr(logits), _ptr(labels), _ptr(loss), _ptr(dlogits), _ptr(row_scratch), n, k, _stream(stream)),
            "softmax_xent")
+
+
+# ---- batch normalisation (training mode) ----
+
+def batchnorm_workspace_bytes(n: int, c: int, h: int, w: int, layout: int) -> int:
+    return int(lib().batchnorm_workspace_bytes(n, c, h, w, layout))
+
+
+def batchnorm_fwd(x, gamma, beta, y, save_mean, save_invstd, n: int, c: int, h: int, w: int, eps: float, layout: int,
+                  workspace=None, stream=None) -> None:
+    _check(lib().batchnorm_fwd(_ptr(x), _ptr(gamma), _ptr(beta), _ptr(y), _ptr(save_mean), _ptr(save_invstd), n, c, h, w, eps,
+                               layout, _ptr(workspace), _nbytes(workspace), _stream(stream)), "batchnorm_fwd")
+
+
+def batchnorm_bwd(x, dy, gamma, save_mean, save_invstd, dx, dgamma, dbeta, n: int, c: int, h: int, w: int, layout: int,
+                  workspace=None, stream=None) -> None:
+    _check(lib().batchnorm_bwd(_ptr(x), _ptr(dy), _ptr(gamma), _ptr(save_mean), _ptr(save_invstd), _ptr(dx), _ptr(dgamma),
+                               _ptr(dbeta), n, c, h, w, layout, _ptr(workspace), _nbytes(workspace), _stream(stream)),
+           "batchnorm_bwd")

@@ -157,6 +157,25 @@ def test_glue_layers_reject_bad_arguments_before_launch():
     assert L.softmax_xent(P, P, P, P, P, 4, 0, None) == lc.LC_ERR_SHAPE
 
 
+def test_batchnorm_rejects_bad_arguments_before_launch():
+    L = lc.lib()
+    P = ctypes.c_void_p(FAKE)
+    need = lc.batchnorm_workspace_bytes(4, 8, 5, 5, lc.LC_NHWC)
+    assert need > 0 and need % 256 == 0
+    assert lc.batchnorm_workspace_bytes(0, 8, 5, 5, lc.LC_NHWC) == 0
+    assert lc.batchnorm_workspace_bytes(4, 8, 5, 5, 9) == 0
+    fwd = lambda x, ws, nb, eps=1e-5, lay=lc.LC_NHWC, n=4: L.batchnorm_fwd(x, P, P, P, P, P, n, 8, 5, 5, eps, lay, ws, nb, None)
+    assert fwd(None, P, need) == lc.LC_ERR_NULL
+    assert fwd(P, None, need) == lc.LC_ERR_WORKSPACE
+    assert fwd(P, P, need - 1) == lc.LC_ERR_WORKSPACE
+    assert fwd(P, P, need, lay=5) == lc.LC_ERR_UNSUPPORTED
+    assert fwd(P, P, need, n=0) == lc.LC_ERR_SHAPE
+    assert fwd(P, P, need, eps=-1.0) == lc.LC_ERR_SHAPE
+    assert fwd(ctypes.c_void_p(FAKE + 2), P, need) == lc.LC_ERR_ALIGN
+    assert L.batchnorm_bwd(P, P, P, P, P, P, P, None, 4, 8, 5, 5, lc.LC_NHWC, P, need, None) == lc.LC_ERR_NULL
+    assert L.batchnorm_bwd(P, P, P, P, P, P, P, P, 4, 8, 5, 5, lc.LC_NHWC, P, 0, None) == lc.LC_ERR_WORKSPACE
+
+
 def test_poly_lr_host_arithmetic():
     assert lc.lars_poly_lr(1.0, 0, 3516) == 1.0
     assert lc.lars_poly_lr(1.0, 3516, 3516) == 0.0

@@ -1,0 +1,91 @@
+"""GPU parity: batchnorm_fwd / batchnorm_bwd through the C ABI against the numpy float64 oracle, both layouts,
+vector and scalar paths, shapes from ResNet-50 and AlexNet-BN down to single pixels.  Tolerance 1e-4 tensor-scaled
+(fp32 per-thread partial sums, fp64 combination; the variance comes from the sums of x and x^2)."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import batchnorm as obn
+from paper_1709_05011_amd import larsconv as lc
+from paper_1709_05011_amd import synth
+
+import gpu_util as gu
+
+pytestmark = pytest.mark.gpu
+TOL = 1e-4
+EPS = 1e-5
+
+SHAPES = {
+    "resnet_56x56_c64": (8, 64, 56, 56),
+    "resnet_7x7_c2048": (16, 2048, 7, 7),
+    "alexnet_13x13_c384": (8, 384, 13, 13),
+    "alexnet_c96": (3, 96, 27, 27),
+    "odd_channels_scalar_path": (5, 7, 9, 11),
+    "one_pixel_per_image": (64, 10, 1, 1),
+    "single_image": (1, 12, 6, 5),
+    "many_slabs": (32, 16, 64, 64),
+}
+
+
+def _lay(a, layout):
+    return np.ascontiguousarray(a.transpose(0, 2, 3, 1)) if layout == lc.LC_NHWC else np.ascontiguousarray(a)
+
+
+def _unlay(a, layout):
+    return a.transpose(0, 3, 1, 2) if layout == lc.LC_NHWC else a
+
+
+def _run(shape, layout, seed, offset=0):
+    n, c, h, w = shape
+    x = (synth.normal(shape, seed) * 2.0 + 0.7).astype(np.float32)          # non-zero mean: exercises E[x^2] - mean^2
+    dy = synth.normal(shape, seed + 1)
+    gamma = (1.0 + 0.5 * synth.normal((c,), seed + 2)).astype(np.float32)
+    beta = synth.normal((c,), seed + 3)
+
+    def put(a):                                                               # optional misalignment by `offset` floats
+        buf = torch.empty(a.size + offset, dtype=torch.float32, device=gu.DEV)
+        v = buf[offset:]
+        v.copy_(torch.from_numpy(np.ascontiguousarray(a).reshape(-1)))
+        return v
+    xd, dyd = put(_lay(x, layout)), put(_lay(dy, layout))
+    gd, bd = gu.dev(gamma), gu.dev(beta)
+    y, dx = torch.empty_like(xd), torch.empty_like(xd)
+    mean, invstd, dg, db = (torch.empty(c, device=gu.DEV) for _ in range(4))
+    ws = gu.workspace(lc.batchnorm_workspace_bytes(n, c, h, w, layout))
+    lc.batchnorm_fwd(xd, gd, bd, y, mean, invstd, n, c, h, w, EPS, layout, ws)
+    lc.batchnorm_bwd(xd, dyd, gd, mean, invstd, dx, dg, db, n, c, h, w, layout, ws)
+    torch.cuda.synchronize()
+    shp = (n, h, w, c) if layout == lc.LC_NHWC else shape
+    oy, omean, oinv = obn.forward(x, gamma, beta, EPS)
+    odx, odg, odb = obn.backward(x, dy, gamma, EPS)
+    assert gu.scaled_err(_unlay(y.cpu().numpy().reshape(shp), layout), oy) <= TOL
+    assert gu.scaled_err(mean.cpu().numpy(), omean) <= 1e-5
+    assert np.max(np.abs(invstd.cpu().numpy() - oinv) / oinv) <= 1e-4
+    assert gu.scaled_err(_unlay(dx.cpu().numpy().reshape(shp), layout), odx) <= TOL
+    assert gu.scaled_err(dg.cpu().numpy(), odg) <= TOL
+    assert gu.scaled_err(db.cpu().numpy(), odb) <= TOL
+
+
+@pytest.mark.parametrize("layout", [lc.LC_NHWC, lc.LC_NCHW], ids=["nhwc", "nchw"])
+@pytest.mark.parametrize("name", list(SHAPES))
+def test_forward_and_backward_match_oracle(name, layout):
+    _run(SHAPES[name], layout, 8300 + 10 * list(SHAPES).index(name))
+
+
+def test_misaligned_tensors_take_the_scalar_path():
+    _run((4, 16, 9, 9), lc.LC_NHWC, 8500, offset=1)
+
+
+def test_reruns_are_bit_identical():
+    n, c, h, w = 16, 128, 28, 28
+    x = gu.dev(synth.normal((n, h, w, c), 8600))
+    g, b = gu.dev(np.ones(c, np.float32)), gu.dev(np.zeros(c, np.float32))
+    ws = gu.workspace(lc.batchnorm_workspace_bytes(n, c, h, w, lc.LC_NHWC))
+    outs = []
+    for _ in range(2):
+        y, m, s = torch.empty_like(x), torch.empty(c, device=gu.DEV), torch.empty(c, device=gu.DEV)
+        lc.batchnorm_fwd(x, g, b, y, m, s, n, c, h, w, EPS, lc.LC_NHWC, ws)
+        torch.cuda.synchronize()
+        outs.append((y.cpu().numpy(), m.cpu().numpy(), s.cpu().numpy()))
+    for a, bb in zip(outs[0], outs[1]):
+        np.testing.assert_array_equal(a, bb)
