@@ -128,12 +128,11 @@ float lars_warmup_poly_lr(float base_lr, float start_lr, int64_t iter, int64_t w
  * Batches").  The result is the `lr` argument of lars_step. */
 float lars_poly_lr(float base_lr, int64_t iter, int64_t max_iter, float power);
 
-/* ---- Glue layers of the small whole-path network (fp32) ----
- * ReLU, 2x2 max pooling, global average pooling, bias and softmax cross-entropy: the paper does not discuss
- * them (they are implied by the networks it trains, "Experimental Settings"); these are the textbook
- * definitions, provided so that the tiny CNN runs end to end on the device.  They are simple memory-bound
- * kernels, not part of the measured convolution + LARS path.  All pointers DEVICE, fp32, 4-byte aligned;
- * reductions run in a fixed order. */
+/* ---- Glue layers of the networks the paper trains (fp32) ----
+ * ReLU, max pooling, global average pooling, bias, softmax cross-entropy and the gradient at a residual
+ * block's output: the paper does not discuss them (they are implied by the networks it trains, "Experimental
+ * Settings"; ResNet-50 in "ImageNet training with ResNet-50"); these are the textbook definitions, memory-bound
+ * streaming kernels.  All pointers DEVICE, fp32, 4-byte aligned; reductions run in a fixed order. */
 
 /* y = max(x, 0);  dx = x > 0 ? dy : 0 (x is the forward INPUT).  count elements; the buffers must not overlap. */
 lc_status relu_fwd(const float* x, float* y, size_t count, void* hip_stream);
@@ -145,6 +144,21 @@ lc_status relu_bwd(const float* x, const float* dy, float* dx, size_t count, voi
 lc_status maxpool2x2_fwd(const float* x, float* y, uint8_t* idx, int n, int c, int h, int w, lc_layout layout, void* hip_stream);
 lc_status maxpool2x2_bwd(const float* dy, const uint8_t* idx, float* dx, int n, int c, int h, int w, lc_layout layout,
                          void* hip_stream);
+
+/* Max pool with a window x window window (1..15), any stride >= 1 and 0 <= pad < window (the overlapping 3x3
+ * stride-2 pools of ResNet-50 and AlexNet); output size floor((h + 2*pad - window)/stride) + 1.  Padding taps
+ * never win.  idx (one byte per output element, same order as y) receives the tap, row * window + column, of
+ * the first maximum in row-major window order; the backward pass gives every input element the sum of dy over
+ * the outputs whose maximum it was (fixed order, no atomics; dx written in full, h and w are the INPUT's). */
+lc_status maxpool_fwd(const float* x, float* y, uint8_t* idx, int n, int c, int h, int w, int window, int stride, int pad,
+                      lc_layout layout, void* hip_stream);
+lc_status maxpool_bwd(const float* dy, const uint8_t* idx, float* dx, int n, int c, int h, int w, int window, int stride, int pad,
+                      lc_layout layout, void* hip_stream);
+
+/* dx = y > 0 ? da + db : 0 over count elements: the gradients that meet at a residual block's output y =
+ * max(branch + shortcut, 0) -- one from the next block's first convolution, one from its shortcut -- taken
+ * through the block's ReLU in one pass.  db may be NULL (dx = y > 0 ? da : 0).  Buffers must not overlap. */
+lc_status relu_add_bwd(const float* y, const float* da, const float* db, float* dx, size_t count, void* hip_stream);
 
 /* y[n,c] = mean over h, w of x[n,c,h,w];  dx[n,c,h,w] = dy[n,c] / (h*w). */
 lc_status global_avgpool_fwd(const float* x, float* y, int n, int c, int h, int w, lc_layout layout, void* hip_stream);
@@ -175,6 +189,19 @@ lc_status batchnorm_fwd(const float* x, const float* gamma, const float* beta, f
 lc_status batchnorm_bwd(const float* x, const float* dy, const float* gamma, const float* save_mean, const float* save_invstd,
                         float* dx, float* dgamma, float* dbeta, int n, int c, int h, int w, lc_layout layout, void* workspace,
                         size_t workspace_bytes, void* hip_stream);
+
+/* Fused forms for a network step (same statistics and sums as above).
+ * Forward: y = act(gamma*xhat + beta + residual); residual ([n,c,h,w] like x) may be NULL; relu != 0 clamps at
+ * zero.  Backward with relu != 0: dy is the gradient with respect to max(gamma*xhat + beta, 0) and is taken as
+ * zero where gamma*xhat + beta <= 0; the layer rebuilds that value from x (beta is then required, and the
+ * forward pass must have had no residual) with the arithmetic of the forward pass, so the mask is the one of
+ * the stored output.  relu == 0: beta may be NULL and the call is batchnorm_bwd.  Buffers must not overlap. */
+lc_status batchnorm_fwd_ex(const float* x, const float* gamma, const float* beta, const float* residual, float* y,
+                           float* save_mean, float* save_invstd, int n, int c, int h, int w, float eps, int relu, lc_layout layout,
+                           void* workspace, size_t workspace_bytes, void* hip_stream);
+lc_status batchnorm_bwd_ex(const float* x, const float* dy, const float* gamma, const float* beta, const float* save_mean,
+                           const float* save_invstd, float* dx, float* dgamma, float* dbeta, int n, int c, int h, int w, int relu,
+                           lc_layout layout, void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /* Static, human-readable name of a status code. */
 const char* lc_status_string(lc_status status);

@@ -10,6 +10,10 @@
 // Algorithmic bytes per element: forward 12 (x twice, y once), backward 20 (x and dy twice, dx once).
 // Threads accumulate in fp32 over a few hundred values each, in a fixed order; blocks and the partials of all
 // blocks are combined in fp64 in index order: results are bit-identical from run to run.
+// Fused variants (the *_ex entry points): the forward pass can add a second tensor (a residual shortcut) and
+// clamp at zero; the backward pass can take the gradient of the clamped output and rebuild the mask y > 0 from x
+// -- forward and backward derive y's scale and shift from the stored float statistics with the same code, so the
+// rebuilt y has the forward's bits.
 // NHWC: the tensor is a matrix [pixels][channels]; a block owns a slab of pixels, a thread a group of four
 // channels (16-byte accesses).  NCHW: a block owns one channel and a range of images and runs along the
 // contiguous pixels of each plane.
@@ -37,28 +41,41 @@ struct BnGeom {
 
 struct BnWorkspace {
     double* partial;      // [slabs][C][2]
-    float* coef;          // [3][C]
+    float* coef;          // [5][C]: p, q, r of out = p*A + q*B + r, then scale and shift of y = scale*x + shift
 };
 
+enum { kStats = 0, kSums = 1, kMaskedSums = 2 };
+
+// y = scale*x + shift from the stored statistics; both passes call this and get the same bits
+__device__ __forceinline__ void scale_shift(float gamma, float beta, float mean, float inv_std, float* scale, float* shift) {
+    const double sc = (double)gamma * (double)inv_std;
+    *scale = (float)sc;
+    *shift = (float)fma(-(double)mean, sc, (double)beta);
+}
+
 // ---------------- NHWC ----------------
-// A: first tensor (x), B: second tensor (dy) or null.  STATS: sums of x and x^2; otherwise sums of dy and
-// dy * (x - mean) * inv_std.
-template <int VEC, bool STATS>
+// MODE kStats: sums of x and x^2.  kSums: sums of dy and dy * (x - mean) * inv_std.  kMaskedSums: the same with
+// dy taken as zero where scale*x + shift <= 0.
+template <int VEC, int MODE>
 __global__ void __launch_bounds__(kThreads) bn_reduce_nhwc_kernel(const float* __restrict__ x, const float* __restrict__ dy,
                                                                   const float* __restrict__ mean, const float* __restrict__ inv_std,
+                                                                  const float* __restrict__ gamma, const float* __restrict__ beta,
                                                                   BnGeom g, BnWorkspace ws) {
+    constexpr bool STATS = MODE == kStats;
     __shared__ double red[kThreads][2 * VEC];
     const int tx = threadIdx.x % g.tx, ty = threadIdx.x / g.tx;
     const int c0 = (blockIdx.y * g.tx + tx) * VEC;
     const bool live = c0 < g.C;
     const long long r0 = (long long)blockIdx.x * g.rows_per_slab;
     const long long r1 = r0 + g.rows_per_slab < g.M ? r0 + g.rows_per_slab : g.M;
-    float s0[VEC], s1[VEC], mu[VEC], is[VEC];
+    float s0[VEC], s1[VEC], mu[VEC], is[VEC], sc[VEC], sh[VEC];
 #pragma unroll
     for (int e = 0; e < VEC; ++e) {
         s0[e] = s1[e] = 0.f;
         mu[e] = (!STATS && live) ? mean[c0 + e] : 0.f;
         is[e] = (!STATS && live) ? inv_std[c0 + e] : 0.f;
+        sc[e] = sh[e] = 0.f;
+        if (MODE == kMaskedSums && live) scale_shift(gamma[c0 + e], beta[c0 + e], mu[e], is[e], &sc[e], &sh[e]);
     }
     if (live) {
         for (long long r = r0 + ty; r < r1; r += g.ty) {
@@ -80,8 +97,9 @@ __global__ void __launch_bounds__(kThreads) bn_reduce_nhwc_kernel(const float* _
                     s0[e] += a[e];
                     s1[e] += a[e] * a[e];
                 } else {
-                    s0[e] += b[e];
-                    s1[e] += b[e] * ((a[e] - mu[e]) * is[e]);
+                    const float d = (MODE == kMaskedSums && !(fmaf(sc[e], a[e], sh[e]) > 0.f)) ? 0.f : b[e];
+                    s0[e] += d;
+                    s1[e] += d * ((a[e] - mu[e]) * is[e]);
                 }
             }
         }
@@ -107,8 +125,9 @@ __global__ void __launch_bounds__(kThreads) bn_reduce_nhwc_kernel(const float* _
     }
 }
 
-// out = p*A + q*B + r per channel (B may be null: out = p*A + r)
-template <int VEC, bool TWO>
+// out = p*A + q*B + r per channel (TWO false: out = p*A + r).  RELU: clamp the result at zero.  MASK: B counts as
+// zero where scale*A + shift <= 0.
+template <int VEC, bool TWO, bool RELU, bool MASK>
 __global__ void __launch_bounds__(kThreads) bn_apply_nhwc_kernel(const float* __restrict__ a, const float* __restrict__ b,
                                                                  float* __restrict__ out, const float* __restrict__ coef, BnGeom g) {
     const size_t total = (size_t)g.M * g.C / VEC;
@@ -120,29 +139,47 @@ __global__ void __launch_bounds__(kThreads) bn_apply_nhwc_kernel(const float* __
             const float4 r = *reinterpret_cast<const float4*>(coef + 2 * g.C + c0);
             float4 o = make_float4(fmaf(p.x, va.x, r.x), fmaf(p.y, va.y, r.y), fmaf(p.z, va.z, r.z), fmaf(p.w, va.w, r.w));
             if constexpr (TWO) {
-                const float4 vb = reinterpret_cast<const float4*>(b)[i];
+                float4 vb = reinterpret_cast<const float4*>(b)[i];
                 const float4 q = *reinterpret_cast<const float4*>(coef + g.C + c0);
+                if constexpr (MASK) {
+                    const float4 sc = *reinterpret_cast<const float4*>(coef + 3 * g.C + c0);
+                    const float4 sh = *reinterpret_cast<const float4*>(coef + 4 * g.C + c0);
+                    if (!(fmaf(sc.x, va.x, sh.x) > 0.f)) vb.x = 0.f;
+                    if (!(fmaf(sc.y, va.y, sh.y) > 0.f)) vb.y = 0.f;
+                    if (!(fmaf(sc.z, va.z, sh.z) > 0.f)) vb.z = 0.f;
+                    if (!(fmaf(sc.w, va.w, sh.w) > 0.f)) vb.w = 0.f;
+                }
                 o.x = fmaf(q.x, vb.x, o.x); o.y = fmaf(q.y, vb.y, o.y); o.z = fmaf(q.z, vb.z, o.z); o.w = fmaf(q.w, vb.w, o.w);
             }
+            if constexpr (RELU) { o.x = fmaxf(o.x, 0.f); o.y = fmaxf(o.y, 0.f); o.z = fmaxf(o.z, 0.f); o.w = fmaxf(o.w, 0.f); }
             reinterpret_cast<float4*>(out)[i] = o;
         } else {
             float o = fmaf(coef[c0], a[i], coef[2 * g.C + c0]);
-            if constexpr (TWO) o = fmaf(coef[g.C + c0], b[i], o);
+            if constexpr (TWO) {
+                float vb = b[i];
+                if constexpr (MASK) if (!(fmaf(coef[3 * g.C + c0], a[i], coef[4 * g.C + c0]) > 0.f)) vb = 0.f;
+                o = fmaf(coef[g.C + c0], vb, o);
+            }
+            if constexpr (RELU) o = fmaxf(o, 0.f);
             out[i] = o;
         }
     }
 }
 
 // ---------------- NCHW ----------------
-template <bool STATS>
+template <int MODE>
 __global__ void __launch_bounds__(kThreads) bn_reduce_nchw_kernel(const float* __restrict__ x, const float* __restrict__ dy,
                                                                   const float* __restrict__ mean, const float* __restrict__ inv_std,
+                                                                  const float* __restrict__ gamma, const float* __restrict__ beta,
                                                                   BnGeom g, BnWorkspace ws) {
+    constexpr bool STATS = MODE == kStats;
     __shared__ double red[kThreads][2];
     const int ch = blockIdx.y;
     const long long n0 = (long long)blockIdx.x * g.rows_per_slab;
     const long long n1 = n0 + g.rows_per_slab < g.N ? n0 + g.rows_per_slab : g.N;
     const float mu = STATS ? 0.f : mean[ch], is = STATS ? 0.f : inv_std[ch];
+    float sc = 0.f, sh = 0.f;
+    if (MODE == kMaskedSums) scale_shift(gamma[ch], beta[ch], mu, is, &sc, &sh);
     float s0 = 0.f, s1 = 0.f;
     for (long long n = n0; n < n1; ++n) {
         const size_t base = ((size_t)n * g.C + ch) * g.HW;
@@ -152,7 +189,7 @@ __global__ void __launch_bounds__(kThreads) bn_reduce_nchw_kernel(const float* _
                 s0 += a;
                 s1 += a * a;
             } else {
-                const float b = dy[base + i];
+                const float b = (MODE == kMaskedSums && !(fmaf(sc, a, sh) > 0.f)) ? 0.f : dy[base + i];
                 s0 += b;
                 s1 += b * ((a - mu) * is);
             }
@@ -173,14 +210,19 @@ __global__ void __launch_bounds__(kThreads) bn_reduce_nchw_kernel(const float* _
     }
 }
 
-template <bool TWO>
+template <bool TWO, bool RELU, bool MASK>
 __global__ void __launch_bounds__(kThreads) bn_apply_nchw_kernel(const float* __restrict__ a, const float* __restrict__ b,
                                                                  float* __restrict__ out, const float* __restrict__ coef, BnGeom g) {
     const size_t total = (size_t)g.M * g.C;
     for (size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x; i < total; i += (size_t)gridDim.x * blockDim.x) {
         const int ch = (int)((i / g.HW) % g.C);
         float o = fmaf(coef[ch], a[i], coef[2 * g.C + ch]);
-        if constexpr (TWO) o = fmaf(coef[g.C + ch], b[i], o);
+        if constexpr (TWO) {
+            float vb = b[i];
+            if constexpr (MASK) if (!(fmaf(coef[3 * g.C + ch], a[i], coef[4 * g.C + ch]) > 0.f)) vb = 0.f;
+            o = fmaf(coef[g.C + ch], vb, o);
+        }
+        if constexpr (RELU) o = fmaxf(o, 0.f);
         out[i] = o;
     }
 }
@@ -214,7 +256,7 @@ __device__ __forceinline__ bool channel_totals(const BnWorkspace& ws, const BnGe
     return true;
 }
 
-// forward: mean, 1/std, and y = scale*x + shift
+// forward: mean, 1/std, and y = scale*x + shift (+ residual)
 __global__ void __launch_bounds__(kFinChannels* kFinLanes)
 bn_finalize_fwd_kernel(BnWorkspace ws, const float* __restrict__ gamma, const float* __restrict__ beta,
                        float* __restrict__ save_mean, float* __restrict__ save_invstd, BnGeom g, float eps) {
@@ -226,17 +268,19 @@ bn_finalize_fwd_kernel(BnWorkspace ws, const float* __restrict__ gamma, const fl
     double var = s1 / m - mean * mean;
     if (var < 0.0) var = 0.0;
     const double inv_std = 1.0 / sqrt(var + (double)eps);
-    save_mean[ch] = (float)mean;
-    save_invstd[ch] = (float)inv_std;
-    const double scale = (double)gamma[ch] * inv_std;
-    ws.coef[ch] = (float)scale;
-    ws.coef[g.C + ch] = 0.f;
-    ws.coef[2 * g.C + ch] = (float)((double)beta[ch] - mean * scale);
+    const float mean_f = (float)mean, inv_std_f = (float)inv_std;
+    save_mean[ch] = mean_f;
+    save_invstd[ch] = inv_std_f;
+    float scale, shift;
+    scale_shift(gamma[ch], beta[ch], mean_f, inv_std_f, &scale, &shift);
+    ws.coef[ch] = scale;
+    ws.coef[g.C + ch] = 1.f;               // the residual, when there is one, is added as it is
+    ws.coef[2 * g.C + ch] = shift;
 }
 
 // backward: dgamma, dbeta, and dx = a*x + b*dy + c  (coefficient order matches the apply kernels: first tensor x)
 __global__ void __launch_bounds__(kFinChannels* kFinLanes)
-bn_finalize_bwd_kernel(BnWorkspace ws, const float* __restrict__ gamma, const float* __restrict__ mean,
+bn_finalize_bwd_kernel(BnWorkspace ws, const float* __restrict__ gamma, const float* __restrict__ beta, const float* __restrict__ mean,
                        const float* __restrict__ inv_std, float* __restrict__ dgamma, float* __restrict__ dbeta, BnGeom g) {
     int ch;
     double s0, s1;
@@ -249,6 +293,12 @@ bn_finalize_bwd_kernel(BnWorkspace ws, const float* __restrict__ gamma, const fl
     ws.coef[ch] = (float)bx;
     ws.coef[g.C + ch] = (float)a;
     ws.coef[2 * g.C + ch] = (float)(-a * s0 / m - bx * mu);
+    if (beta) {                            // the apply pass rebuilds the mask y > 0
+        float scale, shift;
+        scale_shift(gamma[ch], beta[ch], mean[ch], inv_std[ch], &scale, &shift);
+        ws.coef[3 * g.C + ch] = scale;
+        ws.coef[4 * g.C + ch] = shift;
+    }
 }
 
 bool geometry(int n, int c, int h, int w, lc_layout layout, bool aligned16, BnGeom* g) {
@@ -286,7 +336,7 @@ size_t ws_layout(const BnGeom& g, size_t* coef_off) {
     size_t off = (size_t)g.slabs * g.C * 2 * sizeof(double);
     off = (off + 255) & ~(size_t)255;
     *coef_off = off;
-    off += (size_t)3 * g.C * sizeof(float);
+    off += (size_t)5 * g.C * sizeof(float);
     return (off + 255) & ~(size_t)255;
 }
 
@@ -312,15 +362,15 @@ extern "C" size_t batchnorm_workspace_bytes(int n, int c, int h, int w, lc_layou
     return a > b ? a : b;
 }
 
-extern "C" lc_status batchnorm_fwd(const float* x, const float* gamma, const float* beta, float* y, float* save_mean,
-                                   float* save_invstd, int n, int c, int h, int w, float eps, lc_layout layout, void* workspace,
-                                   size_t workspace_bytes, void* hip_stream) {
+extern "C" lc_status batchnorm_fwd_ex(const float* x, const float* gamma, const float* beta, const float* residual, float* y,
+                                      float* save_mean, float* save_invstd, int n, int c, int h, int w, float eps, int relu,
+                                      lc_layout layout, void* workspace, size_t workspace_bytes, void* hip_stream) {
     if (!x || !gamma || !beta || !y || !save_mean || !save_invstd) return LC_ERR_NULL;
     if (layout != LC_NCHW && layout != LC_NHWC) return LC_ERR_UNSUPPORTED;
     if (!(eps >= 0.f)) return LC_ERR_SHAPE;
     BnGeom g;
-    if (!geometry(n, c, h, w, layout, al16(x) && al16(y), &g)) return LC_ERR_SHAPE;
-    if (!al4(x) || !al4(y) || !al4(gamma) || !al4(beta) || !al4(save_mean) || !al4(save_invstd)) return LC_ERR_ALIGN;
+    if (!geometry(n, c, h, w, layout, al16(x) && al16(y) && al16(residual), &g)) return LC_ERR_SHAPE;
+    if (!al4(x) || !al4(y) || !al4(residual) || !al4(gamma) || !al4(beta) || !al4(save_mean) || !al4(save_invstd)) return LC_ERR_ALIGN;
     size_t coef_off;
     const size_t need = ws_layout(g, &coef_off);
     if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255) || workspace_bytes < need) return LC_ERR_WORKSPACE;
@@ -330,35 +380,56 @@ extern "C" lc_status batchnorm_fwd(const float* x, const float* gamma, const flo
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     lc_begin_call();
     const size_t total = (size_t)g.M * g.C;
+    const dim3 fin_grid((c + kFinChannels - 1) / kFinChannels), fin_block(kFinChannels * kFinLanes);
+    const float* none = nullptr;
+    const bool two = residual != nullptr, clamp = relu != 0;
     if (layout == LC_NHWC) {
         const dim3 grid((unsigned)g.slabs, (unsigned)g.cblocks);
-        if (g.vec == 4) {
-            hipLaunchKernelGGL((bn_reduce_nhwc_kernel<4, true>), grid, dim3(kThreads), 0, stream, x, nullptr, nullptr, nullptr, g, ws);
-        } else {
-            hipLaunchKernelGGL((bn_reduce_nhwc_kernel<1, true>), grid, dim3(kThreads), 0, stream, x, nullptr, nullptr, nullptr, g, ws);
-        }
-        hipLaunchKernelGGL(bn_finalize_fwd_kernel, dim3((c + kFinChannels - 1) / kFinChannels), dim3(kFinChannels * kFinLanes), 0, stream, ws, gamma, beta, save_mean, save_invstd, g, eps);
         if (g.vec == 4)
-            hipLaunchKernelGGL((bn_apply_nhwc_kernel<4, false>), dim3(stream_blocks(total / 4)), dim3(kThreads), 0, stream, x, nullptr, y, ws.coef, g);
+            hipLaunchKernelGGL((bn_reduce_nhwc_kernel<4, kStats>), grid, dim3(kThreads), 0, stream, x, none, none, none, none, none, g, ws);
         else
-            hipLaunchKernelGGL((bn_apply_nhwc_kernel<1, false>), dim3(stream_blocks(total)), dim3(kThreads), 0, stream, x, nullptr, y, ws.coef, g);
+            hipLaunchKernelGGL((bn_reduce_nhwc_kernel<1, kStats>), grid, dim3(kThreads), 0, stream, x, none, none, none, none, none, g, ws);
+        hipLaunchKernelGGL(bn_finalize_fwd_kernel, fin_grid, fin_block, 0, stream, ws, gamma, beta, save_mean, save_invstd, g, eps);
+        const dim3 agrid(stream_blocks(total / g.vec));
+#define LC_BN_APPLY(VEC, TWO, RELU) \
+    hipLaunchKernelGGL((bn_apply_nhwc_kernel<VEC, TWO, RELU, false>), agrid, dim3(kThreads), 0, stream, x, residual, y, ws.coef, g)
+        if (g.vec == 4) {
+            if (two) { if (clamp) LC_BN_APPLY(4, true, true); else LC_BN_APPLY(4, true, false); }
+            else { if (clamp) LC_BN_APPLY(4, false, true); else LC_BN_APPLY(4, false, false); }
+        } else {
+            if (two) { if (clamp) LC_BN_APPLY(1, true, true); else LC_BN_APPLY(1, true, false); }
+            else { if (clamp) LC_BN_APPLY(1, false, true); else LC_BN_APPLY(1, false, false); }
+        }
+#undef LC_BN_APPLY
     } else {
-        hipLaunchKernelGGL((bn_reduce_nchw_kernel<true>), dim3((unsigned)g.slabs, (unsigned)c), dim3(kThreads), 0, stream, x, nullptr, nullptr,
-                           nullptr, g, ws);
-        hipLaunchKernelGGL(bn_finalize_fwd_kernel, dim3((c + kFinChannels - 1) / kFinChannels), dim3(kFinChannels * kFinLanes), 0, stream, ws, gamma, beta, save_mean, save_invstd, g, eps);
-        hipLaunchKernelGGL((bn_apply_nchw_kernel<false>), dim3(stream_blocks(total)), dim3(kThreads), 0, stream, x, nullptr, y, ws.coef, g);
+        hipLaunchKernelGGL((bn_reduce_nchw_kernel<kStats>), dim3((unsigned)g.slabs, (unsigned)c), dim3(kThreads), 0, stream, x, none, none, none,
+                           none, none, g, ws);
+        hipLaunchKernelGGL(bn_finalize_fwd_kernel, fin_grid, fin_block, 0, stream, ws, gamma, beta, save_mean, save_invstd, g, eps);
+        const dim3 agrid(stream_blocks(total));
+#define LC_BN_APPLY(TWO, RELU) \
+    hipLaunchKernelGGL((bn_apply_nchw_kernel<TWO, RELU, false>), agrid, dim3(kThreads), 0, stream, x, residual, y, ws.coef, g)
+        if (two) { if (clamp) LC_BN_APPLY(true, true); else LC_BN_APPLY(true, false); }
+        else { if (clamp) LC_BN_APPLY(false, true); else LC_BN_APPLY(false, false); }
+#undef LC_BN_APPLY
     }
     return lc_end_call();
 }
 
-extern "C" lc_status batchnorm_bwd(const float* x, const float* dy, const float* gamma, const float* save_mean,
-                                   const float* save_invstd, float* dx, float* dgamma, float* dbeta, int n, int c, int h, int w,
-                                   lc_layout layout, void* workspace, size_t workspace_bytes, void* hip_stream) {
-    if (!x || !dy || !gamma || !save_mean || !save_invstd || !dx || !dgamma || !dbeta) return LC_ERR_NULL;
+extern "C" lc_status batchnorm_fwd(const float* x, const float* gamma, const float* beta, float* y, float* save_mean,
+                                   float* save_invstd, int n, int c, int h, int w, float eps, lc_layout layout, void* workspace,
+                                   size_t workspace_bytes, void* hip_stream) {
+    return batchnorm_fwd_ex(x, gamma, beta, nullptr, y, save_mean, save_invstd, n, c, h, w, eps, 0, layout, workspace, workspace_bytes,
+                            hip_stream);
+}
+
+extern "C" lc_status batchnorm_bwd_ex(const float* x, const float* dy, const float* gamma, const float* beta, const float* save_mean,
+                                      const float* save_invstd, float* dx, float* dgamma, float* dbeta, int n, int c, int h, int w,
+                                      int relu, lc_layout layout, void* workspace, size_t workspace_bytes, void* hip_stream) {
+    if (!x || !dy || !gamma || !save_mean || !save_invstd || !dx || !dgamma || !dbeta || (relu && !beta)) return LC_ERR_NULL;
     if (layout != LC_NCHW && layout != LC_NHWC) return LC_ERR_UNSUPPORTED;
     BnGeom g;
     if (!geometry(n, c, h, w, layout, al16(x) && al16(dy) && al16(dx), &g)) return LC_ERR_SHAPE;
-    if (!al4(x) || !al4(dy) || !al4(dx) || !al4(gamma) || !al4(save_mean) || !al4(save_invstd) || !al4(dgamma) || !al4(dbeta))
+    if (!al4(x) || !al4(dy) || !al4(dx) || !al4(gamma) || !al4(beta) || !al4(save_mean) || !al4(save_invstd) || !al4(dgamma) || !al4(dbeta))
         return LC_ERR_ALIGN;
     size_t coef_off;
     const size_t need = ws_layout(g, &coef_off);
@@ -369,22 +440,42 @@ extern "C" lc_status batchnorm_bwd(const float* x, const float* dy, const float*
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     lc_begin_call();
     const size_t total = (size_t)g.M * g.C;
+    const dim3 fin_grid((c + kFinChannels - 1) / kFinChannels), fin_block(kFinChannels * kFinLanes);
+    const bool mask = relu != 0;
+    const float* mask_beta = mask ? beta : nullptr;
     if (layout == LC_NHWC) {
         const dim3 grid((unsigned)g.slabs, (unsigned)g.cblocks);
-        if (g.vec == 4)
-            hipLaunchKernelGGL((bn_reduce_nhwc_kernel<4, false>), grid, dim3(kThreads), 0, stream, x, dy, save_mean, save_invstd, g, ws);
-        else
-            hipLaunchKernelGGL((bn_reduce_nhwc_kernel<1, false>), grid, dim3(kThreads), 0, stream, x, dy, save_mean, save_invstd, g, ws);
-        hipLaunchKernelGGL(bn_finalize_bwd_kernel, dim3((c + kFinChannels - 1) / kFinChannels), dim3(kFinChannels * kFinLanes), 0, stream, ws, gamma, save_mean, save_invstd, dgamma, dbeta, g);
-        if (g.vec == 4)
-            hipLaunchKernelGGL((bn_apply_nhwc_kernel<4, true>), dim3(stream_blocks(total / 4)), dim3(kThreads), 0, stream, x, dy, dx, ws.coef, g);
-        else
-            hipLaunchKernelGGL((bn_apply_nhwc_kernel<1, true>), dim3(stream_blocks(total)), dim3(kThreads), 0, stream, x, dy, dx, ws.coef, g);
+#define LC_BN_REDUCE(VEC, MODE) \
+    hipLaunchKernelGGL((bn_reduce_nhwc_kernel<VEC, MODE>), grid, dim3(kThreads), 0, stream, x, dy, save_mean, save_invstd, gamma, mask_beta, g, ws)
+        if (g.vec == 4) { if (mask) LC_BN_REDUCE(4, kMaskedSums); else LC_BN_REDUCE(4, kSums); }
+        else { if (mask) LC_BN_REDUCE(1, kMaskedSums); else LC_BN_REDUCE(1, kSums); }
+#undef LC_BN_REDUCE
+        hipLaunchKernelGGL(bn_finalize_bwd_kernel, fin_grid, fin_block, 0, stream, ws, gamma, mask_beta, save_mean, save_invstd, dgamma, dbeta, g);
+        const dim3 agrid(stream_blocks(total / g.vec));
+#define LC_BN_APPLY(VEC, MASK) \
+    hipLaunchKernelGGL((bn_apply_nhwc_kernel<VEC, true, false, MASK>), agrid, dim3(kThreads), 0, stream, x, dy, dx, ws.coef, g)
+        if (g.vec == 4) { if (mask) LC_BN_APPLY(4, true); else LC_BN_APPLY(4, false); }
+        else { if (mask) LC_BN_APPLY(1, true); else LC_BN_APPLY(1, false); }
+#undef LC_BN_APPLY
     } else {
-        hipLaunchKernelGGL((bn_reduce_nchw_kernel<false>), dim3((unsigned)g.slabs, (unsigned)c), dim3(kThreads), 0, stream, x, dy, save_mean,
-                           save_invstd, g, ws);
-        hipLaunchKernelGGL(bn_finalize_bwd_kernel, dim3((c + kFinChannels - 1) / kFinChannels), dim3(kFinChannels * kFinLanes), 0, stream, ws, gamma, save_mean, save_invstd, dgamma, dbeta, g);
-        hipLaunchKernelGGL((bn_apply_nchw_kernel<true>), dim3(stream_blocks(total)), dim3(kThreads), 0, stream, x, dy, dx, ws.coef, g);
+        const dim3 grid((unsigned)g.slabs, (unsigned)c);
+        if (mask)
+            hipLaunchKernelGGL((bn_reduce_nchw_kernel<kMaskedSums>), grid, dim3(kThreads), 0, stream, x, dy, save_mean, save_invstd, gamma, mask_beta, g, ws);
+        else
+            hipLaunchKernelGGL((bn_reduce_nchw_kernel<kSums>), grid, dim3(kThreads), 0, stream, x, dy, save_mean, save_invstd, gamma, mask_beta, g, ws);
+        hipLaunchKernelGGL(bn_finalize_bwd_kernel, fin_grid, fin_block, 0, stream, ws, gamma, mask_beta, save_mean, save_invstd, dgamma, dbeta, g);
+        const dim3 agrid(stream_blocks(total));
+        if (mask)
+            hipLaunchKernelGGL((bn_apply_nchw_kernel<true, false, true>), agrid, dim3(kThreads), 0, stream, x, dy, dx, ws.coef, g);
+        else
+            hipLaunchKernelGGL((bn_apply_nchw_kernel<true, false, false>), agrid, dim3(kThreads), 0, stream, x, dy, dx, ws.coef, g);
     }
     return lc_end_call();
+}
+
+extern "C" lc_status batchnorm_bwd(const float* x, const float* dy, const float* gamma, const float* save_mean,
+                                   const float* save_invstd, float* dx, float* dgamma, float* dbeta, int n, int c, int h, int w,
+                                   lc_layout layout, void* workspace, size_t workspace_bytes, void* hip_stream) {
+    return batchnorm_bwd_ex(x, dy, gamma, nullptr, save_mean, save_invstd, dx, dgamma, dbeta, n, c, h, w, 0, layout, workspace,
+                            workspace_bytes, hip_stream);
 }

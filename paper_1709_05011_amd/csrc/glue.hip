@@ -1,7 +1,7 @@
-// Glue layers of the small whole-path network: ReLU, 2x2 max pooling, global average pooling, bias, softmax
-// cross-entropy.  The paper does not discuss them (they are implied by the networks it trains, "Experimental
-// Settings"); these are the textbook definitions in fp32, memory-bound and simple on purpose: they exist so
-// that the tiny CNN runs end to end on the device through the C ABI, they are not part of the measured path.
+// Glue layers of the networks the paper trains: ReLU, max pooling (2x2, and any window / stride / pad for the
+// overlapping pools of ResNet-50 and AlexNet), global average pooling, bias, softmax cross-entropy, and the
+// gradient that meets at a residual block's output.  The paper does not discuss them (they are implied by the
+// networks, "Experimental Settings"); these are the textbook definitions in fp32, memory-bound streaming kernels.
 // Reductions run in a fixed order (bit-identical reruns).
 #include <hip/hip_runtime.h>
 
@@ -28,6 +28,28 @@ __global__ void relu_fwd_kernel(const float* __restrict__ x, float* __restrict__
 __global__ void relu_bwd_kernel(const float* __restrict__ x, const float* __restrict__ dy, float* __restrict__ dx, size_t count) {
     for (size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x; i < count; i += (size_t)gridDim.x * blockDim.x)
         dx[i] = x[i] > 0.f ? dy[i] : 0.f;
+}
+
+// dx = (da + db) where y > 0, else 0: the two gradients that arrive at a residual block's output (from the next
+// block's first convolution and from its shortcut), taken through the block's last ReLU in one pass.
+template <int VEC, bool TWO>
+__global__ void __launch_bounds__(kThreads) relu_add_bwd_kernel(const float* __restrict__ y, const float* __restrict__ da,
+                                                                const float* __restrict__ db, float* __restrict__ dx, size_t count) {
+    for (size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x; i < count; i += (size_t)gridDim.x * blockDim.x) {
+        if constexpr (VEC == 4) {
+            const float4 m = reinterpret_cast<const float4*>(y)[i];
+            float4 g = reinterpret_cast<const float4*>(da)[i];
+            if constexpr (TWO) {
+                const float4 h = reinterpret_cast<const float4*>(db)[i];
+                g.x += h.x; g.y += h.y; g.z += h.z; g.w += h.w;
+            }
+            reinterpret_cast<float4*>(dx)[i] = make_float4(m.x > 0.f ? g.x : 0.f, m.y > 0.f ? g.y : 0.f, m.z > 0.f ? g.z : 0.f, m.w > 0.f ? g.w : 0.f);
+        } else {
+            float g = da[i];
+            if constexpr (TWO) g += db[i];
+            dx[i] = y[i] > 0.f ? g : 0.f;
+        }
+    }
 }
 
 // element (n, c, h, w) of a tensor in either layout
@@ -91,6 +113,78 @@ __global__ void maxpool2x2_bwd_kernel(const float* __restrict__ dy, const uint8_
 }
 
 // One wave per (n, c): pixels summed in strides of 64, lanes combined by a fixed shuffle tree.
+// Max pool, window K x K, any stride and pad (pad < K): one thread per output element; padding taps never win;
+// idx is the tap (row * K + column) of the first maximum in row-major window order.
+__global__ void __launch_bounds__(kThreads) maxpool_fwd_kernel(const float* __restrict__ x, float* __restrict__ y, uint8_t* __restrict__ idx,
+                                                               int N, int C, int H, int W, int K, int stride, int pad, int Ho, int Wo, bool nhwc) {
+    const size_t total = (size_t)N * C * Ho * Wo;
+    for (size_t o = blockIdx.x * (size_t)blockDim.x + threadIdx.x; o < total; o += (size_t)gridDim.x * blockDim.x) {
+        int n, c, p, q;
+        size_t t = o;
+        if (nhwc) {
+            c = (int)(t % C); t /= C;
+            q = (int)(t % Wo); t /= Wo;
+            p = (int)(t % Ho); n = (int)(t / Ho);
+        } else {
+            q = (int)(t % Wo); t /= Wo;
+            p = (int)(t % Ho); t /= Ho;
+            c = (int)(t % C); n = (int)(t / C);
+        }
+        float best = 0.f;
+        int bi = -1;
+        for (int r = 0; r < K; ++r) {
+            const int ih = p * stride - pad + r;
+            if (ih < 0 || ih >= H) continue;
+            for (int s2 = 0; s2 < K; ++s2) {
+                const int iw = q * stride - pad + s2;
+                if (iw < 0 || iw >= W) continue;
+                const float v = x[at(nhwc, C, H, W, n, c, ih, iw)];
+                if (bi < 0 || v > best) {               // strictly greater: the first maximum wins ties
+                    best = v;
+                    bi = r * K + s2;
+                }
+            }
+        }
+        y[o] = best;
+        idx[o] = (uint8_t)bi;
+    }
+}
+
+// One thread per input element gathers from the (at most ceil(K/stride)^2) windows that contain it, in output
+// order: no atomics, the sum order is fixed.
+__global__ void __launch_bounds__(kThreads) maxpool_bwd_kernel(const float* __restrict__ dy, const uint8_t* __restrict__ idx, float* __restrict__ dx,
+                                                               int N, int C, int H, int W, int K, int stride, int pad, int Ho, int Wo, bool nhwc) {
+    const size_t total = (size_t)N * C * H * W;
+    for (size_t o = blockIdx.x * (size_t)blockDim.x + threadIdx.x; o < total; o += (size_t)gridDim.x * blockDim.x) {
+        int n, c, h, w;
+        size_t t = o;
+        if (nhwc) {
+            c = (int)(t % C); t /= C;
+            w = (int)(t % W); t /= W;
+            h = (int)(t % H); n = (int)(t / H);
+        } else {
+            w = (int)(t % W); t /= W;
+            h = (int)(t % H); t /= H;
+            c = (int)(t % C); n = (int)(t / C);
+        }
+        // outputs p with p*stride - pad <= h <= p*stride - pad + K - 1
+        const int hp = h + pad, wp = w + pad;
+        int p0 = hp - K + 1 <= 0 ? 0 : (hp - K + stride) / stride;
+        int q0 = wp - K + 1 <= 0 ? 0 : (wp - K + stride) / stride;
+        int p1 = hp / stride, q1 = wp / stride;
+        if (p1 > Ho - 1) p1 = Ho - 1;
+        if (q1 > Wo - 1) q1 = Wo - 1;
+        float acc = 0.f;
+        for (int p = p0; p <= p1; ++p)
+            for (int q = q0; q <= q1; ++q) {
+                const int tap = (hp - p * stride) * K + (wp - q * stride);
+                const size_t oo = at(nhwc, C, Ho, Wo, n, c, p, q);
+                if (idx[oo] == (uint8_t)tap) acc += dy[oo];
+            }
+        dx[o] = acc;
+    }
+}
+
 __global__ void global_avgpool_fwd_kernel(const float* __restrict__ x, float* __restrict__ y, int N, int C, int H, int W, bool nhwc) {
     const int lane = threadIdx.x & 63;
     const size_t pair = (size_t)blockIdx.x * (kThreads / 64) + (threadIdx.x >> 6);
@@ -212,6 +306,65 @@ extern "C" lc_status maxpool2x2_bwd(const float* dy, const uint8_t* idx, float* 
     const size_t total = (size_t)n * c * (h / 2) * (w / 2);
     hipLaunchKernelGGL(maxpool2x2_bwd_kernel, dim3(blocks_for(total)), dim3(kThreads), 0, static_cast<hipStream_t>(hip_stream), dy,
                        idx, dx, n, c, h, w, layout == LC_NHWC);
+    return lc_end_call();
+}
+
+extern "C" lc_status relu_add_bwd(const float* y, const float* da, const float* db, float* dx, size_t count, void* hip_stream) {
+    if (!y || !da || !dx) return LC_ERR_NULL;
+    if (count == 0) return LC_OK;
+    if (misaligned(y) || misaligned(da) || misaligned(db) || misaligned(dx)) return LC_ERR_ALIGN;
+    lc_begin_call();
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    const auto al16 = [](const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; };
+    if (count % 4 == 0 && al16(y) && al16(da) && al16(db) && al16(dx)) {
+        const dim3 grid(blocks_for(count / 4));
+        if (db) hipLaunchKernelGGL((relu_add_bwd_kernel<4, true>), grid, dim3(kThreads), 0, stream, y, da, db, dx, count / 4);
+        else hipLaunchKernelGGL((relu_add_bwd_kernel<4, false>), grid, dim3(kThreads), 0, stream, y, da, db, dx, count / 4);
+    } else {
+        const dim3 grid(blocks_for(count));
+        if (db) hipLaunchKernelGGL((relu_add_bwd_kernel<1, true>), grid, dim3(kThreads), 0, stream, y, da, db, dx, count);
+        else hipLaunchKernelGGL((relu_add_bwd_kernel<1, false>), grid, dim3(kThreads), 0, stream, y, da, db, dx, count);
+    }
+    return lc_end_call();
+}
+
+namespace {
+// output size of a pool; false when the arguments make no sense
+bool pool_shape(int n, int c, int h, int w, int window, int stride, int pad, int* ho, int* wo) {
+    if (n <= 0 || c <= 0 || h <= 0 || w <= 0 || window < 1 || window > 15 || stride < 1 || pad < 0 || pad >= window) return false;
+    if (h + 2 * pad < window || w + 2 * pad < window) return false;
+    *ho = (h + 2 * pad - window) / stride + 1;
+    *wo = (w + 2 * pad - window) / stride + 1;
+    // the last window must start inside the image, or it would see padding only
+    return (*ho - 1) * stride - pad < h && (*wo - 1) * stride - pad < w;
+}
+}  // namespace
+
+extern "C" lc_status maxpool_fwd(const float* x, float* y, uint8_t* idx, int n, int c, int h, int w, int window, int stride, int pad,
+                                 lc_layout layout, void* hip_stream) {
+    if (!x || !y || !idx) return LC_ERR_NULL;
+    int ho, wo;
+    if (!pool_shape(n, c, h, w, window, stride, pad, &ho, &wo)) return LC_ERR_SHAPE;
+    if (bad_layout(layout)) return LC_ERR_UNSUPPORTED;
+    if (misaligned(x) || misaligned(y)) return LC_ERR_ALIGN;
+    lc_begin_call();
+    const size_t total = (size_t)n * c * ho * wo;
+    hipLaunchKernelGGL(maxpool_fwd_kernel, dim3(blocks_for(total)), dim3(kThreads), 0, static_cast<hipStream_t>(hip_stream), x, y, idx, n,
+                       c, h, w, window, stride, pad, ho, wo, layout == LC_NHWC);
+    return lc_end_call();
+}
+
+extern "C" lc_status maxpool_bwd(const float* dy, const uint8_t* idx, float* dx, int n, int c, int h, int w, int window, int stride,
+                                 int pad, lc_layout layout, void* hip_stream) {
+    if (!dy || !idx || !dx) return LC_ERR_NULL;
+    int ho, wo;
+    if (!pool_shape(n, c, h, w, window, stride, pad, &ho, &wo)) return LC_ERR_SHAPE;
+    if (bad_layout(layout)) return LC_ERR_UNSUPPORTED;
+    if (misaligned(dy) || misaligned(dx)) return LC_ERR_ALIGN;
+    lc_begin_call();
+    const size_t total = (size_t)n * c * h * w;
+    hipLaunchKernelGGL(maxpool_bwd_kernel, dim3(blocks_for(total)), dim3(kThreads), 0, static_cast<hipStream_t>(hip_stream), dy, idx, dx,
+                       n, c, h, w, window, stride, pad, ho, wo, layout == LC_NHWC);
     return lc_end_call();
 }
 

@@ -22,7 +22,8 @@ LC_PASS_FWD, LC_PASS_BWD_DATA, LC_PASS_BWD_WEIGHT = 0, 1, 2
 EXPORTS = ["conv2d_out_shape", "conv2d_workspace_bytes", "conv2d_fwd", "conv2d_bwd_data", "conv2d_bwd_weight",
            "lars_workspace_bytes", "lars_step", "lars_step_ex", "lars_poly_lr", "lars_warmup_poly_lr",
            "relu_fwd", "relu_bwd", "maxpool2x2_fwd", "maxpool2x2_bwd", "global_avgpool_fwd", "global_avgpool_bwd",
-           "bias_add", "bias_grad", "softmax_xent", "batchnorm_workspace_bytes", "batchnorm_fwd", "batchnorm_bwd",
+           "bias_add", "bias_grad", "softmax_xent", "maxpool_fwd", "maxpool_bwd", "relu_add_bwd",
+           "batchnorm_workspace_bytes", "batchnorm_fwd", "batchnorm_bwd", "batchnorm_fwd_ex", "batchnorm_bwd_ex",
            "lc_status_string", "lc_last_error_detail"]
 
 
@@ -106,8 +107,11 @@ def lib() -> ctypes.CDLL:
         L.bias_add.argtypes = [vp, vp, sz, i32, vp]
         L.bias_grad.argtypes = [vp, vp, sz, i32, vp]
         L.softmax_xent.argtypes = [vp, vp, vp, vp, vp, i32, i32, vp]
+        L.maxpool_fwd.argtypes = [vp, vp, vp, i32, i32, i32, i32, i32, i32, i32, i32, vp]
+        L.maxpool_bwd.argtypes = [vp, vp, vp, i32, i32, i32, i32, i32, i32, i32, i32, vp]
+        L.relu_add_bwd.argtypes = [vp, vp, vp, vp, sz, vp]
         for name in ("relu_fwd", "relu_bwd", "maxpool2x2_fwd", "maxpool2x2_bwd", "global_avgpool_fwd", "global_avgpool_bwd",
-                     "bias_add", "bias_grad", "softmax_xent"):
+                     "bias_add", "bias_grad", "softmax_xent", "maxpool_fwd", "maxpool_bwd", "relu_add_bwd"):
             getattr(L, name).restype = i32
         L.batchnorm_workspace_bytes.restype = sz
         L.batchnorm_workspace_bytes.argtypes = [i32, i32, i32, i32, i32]
@@ -115,6 +119,10 @@ def lib() -> ctypes.CDLL:
         L.batchnorm_fwd.argtypes = [vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, ctypes.c_float, i32, vp, sz, vp]
         L.batchnorm_bwd.restype = i32
         L.batchnorm_bwd.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, vp, sz, vp]
+        L.batchnorm_fwd_ex.restype = i32
+        L.batchnorm_fwd_ex.argtypes = [vp, vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, ctypes.c_float, i32, i32, vp, sz, vp]
+        L.batchnorm_bwd_ex.restype = i32
+        L.batchnorm_bwd_ex.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, vp, sz, vp]
         L.lc_status_string.restype = ctypes.c_char_p
         L.lc_status_string.argtypes = [i32]
         L.lc_last_error_detail.restype = ctypes.c_char_p
@@ -294,6 +302,18 @@ def softmax_xent(logits, labels, loss, dlogits, row_scratch, n: int, k: int, str
            "softmax_xent")
 
 
+def maxpool_fwd(x, y, idx, n: int, c: int, h: int, w: int, window: int, stride: int, pad: int, layout: int, stream=None) -> None:
+    _check(lib().maxpool_fwd(_ptr(x), _ptr(y), _ptr(idx), n, c, h, w, window, stride, pad, layout, _stream(stream)), "maxpool_fwd")
+
+
+def maxpool_bwd(dy, idx, dx, n: int, c: int, h: int, w: int, window: int, stride: int, pad: int, layout: int, stream=None) -> None:
+    _check(lib().maxpool_bwd(_ptr(dy), _ptr(idx), _ptr(dx), n, c, h, w, window, stride, pad, layout, _stream(stream)), "maxpool_bwd")
+
+
+def relu_add_bwd(y, da, db, dx, count: int, stream=None) -> None:
+    _check(lib().relu_add_bwd(_ptr(y), _ptr(da), _ptr(db), _ptr(dx), count, _stream(stream)), "relu_add_bwd")
+
+
 # ---- batch normalisation (training mode) ----
 
 def batchnorm_workspace_bytes(n: int, c: int, h: int, w: int, layout: int) -> int:
@@ -311,3 +331,17 @@ def batchnorm_bwd(x, dy, gamma, save_mean, save_invstd, dx, dgamma, dbeta, n: in
     _check(lib().batchnorm_bwd(_ptr(x), _ptr(dy), _ptr(gamma), _ptr(save_mean), _ptr(save_invstd), _ptr(dx), _ptr(dgamma),
                                _ptr(dbeta), n, c, h, w, layout, _ptr(workspace), _nbytes(workspace), _stream(stream)),
            "batchnorm_bwd")
+
+
+def batchnorm_fwd_ex(x, gamma, beta, residual, y, save_mean, save_invstd, n: int, c: int, h: int, w: int, eps: float, relu: bool,
+                     layout: int, workspace=None, stream=None) -> None:
+    _check(lib().batchnorm_fwd_ex(_ptr(x), _ptr(gamma), _ptr(beta), _ptr(residual), _ptr(y), _ptr(save_mean), _ptr(save_invstd),
+                                  n, c, h, w, eps, int(bool(relu)), layout, _ptr(workspace), _nbytes(workspace), _stream(stream)),
+           "batchnorm_fwd_ex")
+
+
+def batchnorm_bwd_ex(x, dy, gamma, beta, save_mean, save_invstd, dx, dgamma, dbeta, n: int, c: int, h: int, w: int, relu: bool,
+                     layout: int, workspace=None, stream=None) -> None:
+    _check(lib().batchnorm_bwd_ex(_ptr(x), _ptr(dy), _ptr(gamma), _ptr(beta), _ptr(save_mean), _ptr(save_invstd), _ptr(dx),
+                                  _ptr(dgamma), _ptr(dbeta), n, c, h, w, int(bool(relu)), layout, _ptr(workspace),
+                                  _nbytes(workspace), _stream(stream)), "batchnorm_bwd_ex")

@@ -89,3 +89,84 @@ def test_reruns_are_bit_identical():
         outs.append((y.cpu().numpy(), m.cpu().numpy(), s.cpu().numpy()))
     for a, bb in zip(outs[0], outs[1]):
         np.testing.assert_array_equal(a, bb)
+
+
+# ---------------------------------------------------------------- fused forms
+def _fused_case(shape, seed):
+    n, c, h, w = shape
+    x = (synth.normal(shape, seed) * 1.5 - 0.3).astype(np.float32)
+    dy = synth.normal(shape, seed + 1)
+    res = synth.normal(shape, seed + 4)
+    gamma = (1.0 + 0.5 * synth.normal((c,), seed + 2)).astype(np.float32)
+    beta = (0.5 * synth.normal((c,), seed + 3)).astype(np.float32)
+    return x, dy, res, gamma, beta
+
+
+@pytest.mark.parametrize("layout", [lc.LC_NHWC, lc.LC_NCHW], ids=["nhwc", "nchw"])
+@pytest.mark.parametrize("shape", [(6, 32, 14, 14), (3, 7, 5, 9)], ids=["vector", "scalar"])
+@pytest.mark.parametrize("relu,residual", [(True, False), (False, True), (True, True)], ids=["relu", "residual", "residual_relu"])
+def test_fused_forward_matches_oracle(shape, layout, relu, residual):
+    n, c, h, w = shape
+    x, _, res, gamma, beta = _fused_case(shape, 8700)
+    xd, gd, bd = gu.dev(_lay(x, layout)), gu.dev(gamma), gu.dev(beta)
+    rd = gu.dev(_lay(res, layout)) if residual else None
+    y = torch.empty_like(xd)
+    mean, invstd = torch.empty(c, device=gu.DEV), torch.empty(c, device=gu.DEV)
+    ws = gu.workspace(lc.batchnorm_workspace_bytes(n, c, h, w, layout))
+    lc.batchnorm_fwd_ex(xd, gd, bd, rd, y, mean, invstd, n, c, h, w, EPS, relu, layout, ws)
+    torch.cuda.synchronize()
+    want, _, _ = obn.forward(x, gamma, beta, EPS)
+    if residual:
+        want = want + res.astype(np.float64)
+    if relu:
+        want = np.maximum(want, 0.0)
+    assert gu.scaled_err(_unlay(y.cpu().numpy(), layout), want) <= TOL
+
+
+@pytest.mark.parametrize("layout", [lc.LC_NHWC, lc.LC_NCHW], ids=["nhwc", "nchw"])
+@pytest.mark.parametrize("shape", [(6, 32, 14, 14), (3, 7, 5, 9)], ids=["vector", "scalar"])
+def test_backward_through_relu_matches_oracle(shape, layout):
+    """The gradient is taken as zero where the batch-norm output is not positive.  Elements whose output the
+    oracle puts within 1e-4 of zero get dy = 0 on both sides: there fp32 and float64 may disagree on the sign."""
+    n, c, h, w = shape
+    x, dy, _, gamma, beta = _fused_case(shape, 8800)
+    oy, _, _ = obn.forward(x, gamma, beta, EPS)
+    dy = np.where(np.abs(oy) < 1e-4, 0.0, dy).astype(np.float32)
+    xd, dyd, gd, bd = gu.dev(_lay(x, layout)), gu.dev(_lay(dy, layout)), gu.dev(gamma), gu.dev(beta)
+    y, dx = torch.empty_like(xd), torch.empty_like(xd)
+    mean, invstd, dg, db = (torch.empty(c, device=gu.DEV) for _ in range(4))
+    ws = gu.workspace(lc.batchnorm_workspace_bytes(n, c, h, w, layout))
+    lc.batchnorm_fwd_ex(xd, gd, bd, None, y, mean, invstd, n, c, h, w, EPS, True, layout, ws)
+    lc.batchnorm_bwd_ex(xd, dyd, gd, bd, mean, invstd, dx, dg, db, n, c, h, w, True, layout, ws)
+    torch.cuda.synchronize()
+    odx, odg, odb = obn.backward(x, np.where(oy > 0.0, dy, 0.0), gamma, EPS)
+    assert gu.scaled_err(_unlay(dx.cpu().numpy(), layout), odx) <= TOL
+    assert gu.scaled_err(dg.cpu().numpy(), odg) <= TOL
+    assert gu.scaled_err(db.cpu().numpy(), odb) <= TOL
+
+
+@pytest.mark.parametrize("layout", [lc.LC_NHWC, lc.LC_NCHW], ids=["nhwc", "nchw"])
+def test_rebuilt_mask_is_the_mask_of_the_stored_output(layout):
+    """batchnorm_bwd_ex(relu) on dy must equal batchnorm_bwd on dy masked with the stored forward output > 0,
+    bit for bit: the backward pass rebuilds the forward's value exactly."""
+    n, c, h, w = 8, 64, 28, 28
+    x, dy, _, gamma, beta = _fused_case((n, c, h, w), 8900)
+    xd, dyd, gd, bd = gu.dev(_lay(x, layout)), gu.dev(_lay(dy, layout)), gu.dev(gamma), gu.dev(beta)
+    y = torch.empty_like(xd)
+    mean, invstd = torch.empty(c, device=gu.DEV), torch.empty(c, device=gu.DEV)
+    ws = gu.workspace(lc.batchnorm_workspace_bytes(n, c, h, w, layout))
+    lc.batchnorm_fwd_ex(xd, gd, bd, None, y, mean, invstd, n, c, h, w, EPS, True, layout, ws)
+    outs = []
+    for fused in (True, False):
+        dx, dg, db = torch.empty_like(xd), torch.empty(c, device=gu.DEV), torch.empty(c, device=gu.DEV)
+        if fused:
+            lc.batchnorm_bwd_ex(xd, dyd, gd, bd, mean, invstd, dx, dg, db, n, c, h, w, True, layout, ws)
+        else:
+            masked = torch.empty_like(xd)
+            lc.relu_add_bwd(y, dyd, None, masked, xd.numel())
+            lc.batchnorm_bwd(xd, masked, gd, mean, invstd, dx, dg, db, n, c, h, w, layout, ws)
+        torch.cuda.synchronize()
+        outs.append((dx.cpu().numpy(), dg.cpu().numpy(), db.cpu().numpy()))
+    assert float((y > 0).float().mean()) > 0.2             # the mask is not trivial
+    for a, b in zip(*outs):
+        np.testing.assert_array_equal(a, b)

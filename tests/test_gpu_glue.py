@@ -188,3 +188,65 @@ def test_tiny_cnn_end_to_end_on_the_device():
         assert gu.scaled_err(w[i].cpu().numpy().reshape(params[k].shape), params[k]) <= TOL, k
         if np.max(np.abs(vel[k])) > 0:
             assert gu.scaled_err(v[i].cpu().numpy().reshape(vel[k].shape), vel[k]) <= TOL, k
+
+
+# ---------------------------------------------------------------- overlapping max pool, residual gradient
+POOLS = {
+    "resnet_stem_3x3_s2_p1": (2, 64, 16, 16, 3, 2, 1),
+    "alexnet_3x3_s2_p0": (2, 6, 13, 13, 3, 2, 0),
+    "ragged_3x3_s2_p1": (2, 5, 11, 9, 3, 2, 1),
+    "stride1_3x3_p1": (1, 3, 7, 6, 3, 1, 1),
+    "window2_stride2": (2, 4, 8, 6, 2, 2, 0),
+    "window5_stride3_p2": (1, 2, 17, 14, 5, 3, 2),
+}
+
+
+@pytest.mark.parametrize("layout", [lc.LC_NCHW, lc.LC_NHWC], ids=["nchw", "nhwc"])
+@pytest.mark.parametrize("name", list(POOLS))
+def test_general_maxpool_forward_indices_and_backward(name, layout):
+    from oracle import resnet as ores
+    n, c, h, w, k, st, pd = POOLS[name]
+    x = synth.normal((n, c, h, w), 7700)
+    x[0, 0, 0:3, 0:3] = 2.5                             # ties inside and across windows: the first tap wins
+    want_y, want_idx = ores.maxpool(x.astype(np.float64), k, st, pd)
+    ph, pw = want_y.shape[2:]
+    dy = synth.normal((n, c, ph, pw), 7701)
+    xd = _dev(_lay(x, layout))
+    y, idx = _empty((n, c, ph, pw), layout), _empty((n, c, ph, pw), layout, torch.uint8)
+    dx = _empty((n, c, h, w), layout)
+    lc.maxpool_fwd(xd, y, idx, n, c, h, w, k, st, pd, layout)
+    lc.maxpool_bwd(_dev(_lay(dy, layout)), idx, dx, n, c, h, w, k, st, pd, layout)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(_unlay(y.cpu().numpy(), layout), want_y.astype(np.float32))
+    np.testing.assert_array_equal(_unlay(idx.cpu().numpy(), layout), want_idx.astype(np.uint8))
+    want_dx = ores.maxpool_bwd(want_idx, dy.astype(np.float64), (h, w), k, st, pd)
+    assert gu.scaled_err(_unlay(dx.cpu().numpy(), layout), want_dx) <= 1e-6       # at most four fp32 additions
+
+
+def test_general_maxpool_with_window2_equals_the_2x2_pool():
+    n, c, h, w = 2, 8, 12, 10
+    xd = _dev(synth.normal((n, h, w, c), 7710))
+    outs = []
+    for general in (False, True):
+        y = torch.empty((n, h // 2, w // 2, c), device=gu.DEV)
+        idx = torch.empty((n, h // 2, w // 2, c), dtype=torch.uint8, device=gu.DEV)
+        if general:
+            lc.maxpool_fwd(xd, y, idx, n, c, h, w, 2, 2, 0, lc.LC_NHWC)
+        else:
+            lc.maxpool2x2_fwd(xd, y, idx, n, c, h, w, lc.LC_NHWC)
+        torch.cuda.synchronize()
+        outs.append((y.cpu().numpy(), idx.cpu().numpy()))
+    np.testing.assert_array_equal(outs[0][0], outs[1][0])
+    np.testing.assert_array_equal(outs[0][1], outs[1][1])
+
+
+@pytest.mark.parametrize("count,two", [(4096 * 3, True), (4096 * 3, False), (1003, True), (7, False)])
+def test_relu_add_bwd(count, two):
+    y = synth.normal((count,), 7720)
+    y[::13] = 0.0
+    da, db = synth.normal((count,), 7721), synth.normal((count,), 7722)
+    dx = torch.empty(count, device=gu.DEV)
+    lc.relu_add_bwd(_dev(y), _dev(da), _dev(db) if two else None, dx, count)
+    torch.cuda.synchronize()
+    total = da.astype(np.float64) + (db.astype(np.float64) if two else 0.0)        # exact in float64
+    np.testing.assert_array_equal(dx.cpu().numpy(), np.where(y > 0.0, total, 0.0).astype(np.float32))
