@@ -157,7 +157,8 @@ lc_status maxpool_bwd(const float* dy, const uint8_t* idx, float* dx, int n, int
 
 /* dx = y > 0 ? da + db : 0 over count elements: the gradients that meet at a residual block's output y =
  * max(branch + shortcut, 0) -- one from the next block's first convolution, one from its shortcut -- taken
- * through the block's ReLU in one pass.  db may be NULL (dx = y > 0 ? da : 0).  Buffers must not overlap. */
+ * through the block's ReLU in one pass.  db may be NULL (dx = y > 0 ? da : 0); y may be NULL when db is not
+ * (dx = da + db, no ReLU at that point).  Buffers must not overlap. */
 lc_status relu_add_bwd(const float* y, const float* da, const float* db, float* dx, size_t count, void* hip_stream);
 
 /* y[n,c] = mean over h, w of x[n,c,h,w];  dx[n,c,h,w] = dy[n,c] / (h*w). */

@@ -137,6 +137,7 @@ class _Net:
             y = y + residual
         a = self.keep(np.maximum(y, 0.0) if relu else y)
         self.t[name + ".x"], self.t[name + ".z"], self.t[name + ".a"] = x, z, a
+        self.t[name + ".y"] = y                # before the ReLU, unrounded: tests look at its distance from zero
         return a
 
     def conv_bn_bwd(self, name, da, stride, pad, need_dx=True):
@@ -218,7 +219,8 @@ def _conv_f64(x, w, stride, pad):
 
 def forward_backward(x, labels, params, cfg: Config):
     """One forward and backward pass with float32 stores.  Returns (trace, grads): the trace holds
-    "<conv>.z" (convolution output), "<conv>.a" (after batch norm / residual / ReLU), "logits", "loss";
+    "<conv>.z" (convolution output), "<conv>.y" (after batch norm and residual, before the ReLU, float64),
+    "<conv>.a" (the stored activation), "logits", "loss";
     grads has one entry per parameter name."""
     net = _Net(cfg, params, store=True)
     _, dlogits = net.forward(np.asarray(x, dtype=np.float32), labels)

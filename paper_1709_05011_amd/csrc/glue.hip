@@ -32,12 +32,14 @@ __global__ void relu_bwd_kernel(const float* __restrict__ x, const float* __rest
 
 // dx = (da + db) where y > 0, else 0: the two gradients that arrive at a residual block's output (from the next
 // block's first convolution and from its shortcut), taken through the block's last ReLU in one pass.
-template <int VEC, bool TWO>
+// MASKED false: dx = da + db everywhere (y is not read).
+template <int VEC, bool TWO, bool MASKED>
 __global__ void __launch_bounds__(kThreads) relu_add_bwd_kernel(const float* __restrict__ y, const float* __restrict__ da,
                                                                 const float* __restrict__ db, float* __restrict__ dx, size_t count) {
     for (size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x; i < count; i += (size_t)gridDim.x * blockDim.x) {
         if constexpr (VEC == 4) {
-            const float4 m = reinterpret_cast<const float4*>(y)[i];
+            float4 m = make_float4(1.f, 1.f, 1.f, 1.f);
+            if constexpr (MASKED) m = reinterpret_cast<const float4*>(y)[i];
             float4 g = reinterpret_cast<const float4*>(da)[i];
             if constexpr (TWO) {
                 const float4 h = reinterpret_cast<const float4*>(db)[i];
@@ -47,7 +49,7 @@ __global__ void __launch_bounds__(kThreads) relu_add_bwd_kernel(const float* __r
         } else {
             float g = da[i];
             if constexpr (TWO) g += db[i];
-            dx[i] = y[i] > 0.f ? g : 0.f;
+            dx[i] = (!MASKED || y[i] > 0.f) ? g : 0.f;
         }
     }
 }
@@ -310,21 +312,27 @@ extern "C" lc_status maxpool2x2_bwd(const float* dy, const uint8_t* idx, float* 
 }
 
 extern "C" lc_status relu_add_bwd(const float* y, const float* da, const float* db, float* dx, size_t count, void* hip_stream) {
-    if (!y || !da || !dx) return LC_ERR_NULL;
+    if (!da || !dx || (!y && !db)) return LC_ERR_NULL;
     if (count == 0) return LC_OK;
     if (misaligned(y) || misaligned(da) || misaligned(db) || misaligned(dx)) return LC_ERR_ALIGN;
     lc_begin_call();
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     const auto al16 = [](const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; };
-    if (count % 4 == 0 && al16(y) && al16(da) && al16(db) && al16(dx)) {
-        const dim3 grid(blocks_for(count / 4));
-        if (db) hipLaunchKernelGGL((relu_add_bwd_kernel<4, true>), grid, dim3(kThreads), 0, stream, y, da, db, dx, count / 4);
-        else hipLaunchKernelGGL((relu_add_bwd_kernel<4, false>), grid, dim3(kThreads), 0, stream, y, da, db, dx, count / 4);
+    const bool vec = count % 4 == 0 && al16(y) && al16(da) && al16(db) && al16(dx);
+    const size_t items = vec ? count / 4 : count;
+    const dim3 grid(blocks_for(items));
+#define LC_RAB(VEC, TWO, MASKED) \
+    hipLaunchKernelGGL((relu_add_bwd_kernel<VEC, TWO, MASKED>), grid, dim3(kThreads), 0, stream, y, da, db, dx, items)
+    if (vec) {
+        if (!y) LC_RAB(4, true, false);
+        else if (db) LC_RAB(4, true, true);
+        else LC_RAB(4, false, true);
     } else {
-        const dim3 grid(blocks_for(count));
-        if (db) hipLaunchKernelGGL((relu_add_bwd_kernel<1, true>), grid, dim3(kThreads), 0, stream, y, da, db, dx, count);
-        else hipLaunchKernelGGL((relu_add_bwd_kernel<1, false>), grid, dim3(kThreads), 0, stream, y, da, db, dx, count);
+        if (!y) LC_RAB(1, true, false);
+        else if (db) LC_RAB(1, true, true);
+        else LC_RAB(1, false, true);
     }
+#undef LC_RAB
     return lc_end_call();
 }
 

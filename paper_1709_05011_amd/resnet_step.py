@@ -1,0 +1,198 @@
+"""One whole training step of a bottleneck residual network on the device: forward, backward and the LARS
+update, every layer a call into the C library (this module only owns buffers and the order of calls; torch is
+used for device memory).  The network is the one the paper trains in "ImageNet training with ResNet-50":
+stem convolution + batch norm + ReLU, 3x3 stride-2 max pool, stages of 1x1 -> 3x3 -> 1x1 blocks with batch norm
+after every convolution and the block input (through a strided 1x1 projection where the shape changes) added
+before the block's last ReLU, global average pool, classifier with bias, softmax cross-entropy, then LARS over
+all parameter tensors ("Scaling up Batch Size").  Layout NHWC, fp32.
+
+ResNet-50: ResNetStep(stem=(64, 7, 2, 3), widths=(64, 128, 256, 512), blocks=(3, 4, 6, 3), classes=1000, ...).
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass
+from typing import Dict, List, Optional, Sequence, Tuple
+
+import torch
+
+from . import larsconv as lc
+
+NHWC = lc.LC_NHWC
+
+
+@dataclass
+class _ConvBn:
+    name: str
+    desc: lc.ConvDesc
+    out_hw: Tuple[int, int]
+    relu: bool                       # ReLU fused into the batch norm (no residual at this layer)
+    x: Optional[torch.Tensor] = None  # input of the convolution
+    z: Optional[torch.Tensor] = None  # convolution output
+    a: Optional[torch.Tensor] = None  # after batch norm (+ residual, + ReLU)
+    mean: Optional[torch.Tensor] = None
+    invstd: Optional[torch.Tensor] = None
+
+
+class ResNetStep:
+    def __init__(self, stem: Tuple[int, int, int, int], widths: Sequence[int], blocks: Sequence[int], classes: int, batch: int,
+                 image_hw: Tuple[int, int], in_channels: int = 3, eps: float = 1e-5, device: str = "cuda:0"):
+        lc.lib()                     # fails here, loudly, when the library has not been built
+        self.dev, self.eps, self.batch, self.classes = device, eps, batch, classes
+        self.image_hw, self.in_channels = image_hw, in_channels
+        self.layers: Dict[str, _ConvBn] = {}
+        self.order: List[str] = []
+        h, w = image_hw
+        h, w = self._add("stem", in_channels, stem[0], stem[1], stem[2], stem[3], h, w, relu=True)
+        self.pool_in_hw = (h, w)
+        h, w = (h + 2 - 3) // 2 + 1, (w + 2 - 3) // 2 + 1
+        self.pool_out_hw = (h, w)
+        ch = stem[0]
+        self.blocks: List[Tuple[str, bool]] = []
+        for si, (wd, nb) in enumerate(zip(widths, blocks)):
+            for bi in range(nb):
+                stride = 2 if (bi == 0 and si > 0) else 1
+                name = f"s{si}b{bi}"
+                proj = ch != 4 * wd or stride != 1
+                h1, w1 = self._add(name + ".c1", ch, wd, 1, stride, 0, h, w, relu=True)
+                self._add(name + ".c2", wd, wd, 3, 1, 1, h1, w1, relu=True)
+                self._add(name + ".c3", wd, 4 * wd, 1, 1, 0, h1, w1, relu=False)
+                if proj:
+                    self._add(name + ".proj", ch, 4 * wd, 1, stride, 0, h, w, relu=False)
+                self.blocks.append((name, proj))
+                ch, h, w = 4 * wd, h1, w1
+        self.final_ch, self.final_hw = ch, (h, w)
+        self.fc_desc = lc.ConvDesc(batch, ch, 1, 1, classes, 1, 1, 1, 1, 0, 0, lc.LC_F32, NHWC)
+
+        # parameters, gradients, momentum: filter [k, r, s, c], scale [k], shift [k] per convolution; classifier
+        f32 = dict(dtype=torch.float32, device=device)
+        self.params: Dict[str, torch.Tensor] = {}
+        for name in self.order:
+            d = self.layers[name].desc
+            self.params[name + ".w"] = torch.zeros((d.k, d.r, d.s, d.c), **f32)
+            self.params[name + ".gamma"] = torch.ones(d.k, **f32)
+            self.params[name + ".beta"] = torch.zeros(d.k, **f32)
+        self.params["fc.w"] = torch.zeros((classes, 1, 1, ch), **f32)
+        self.params["fc.b"] = torch.zeros(classes, **f32)
+        self.grads = {k: torch.zeros_like(v) for k, v in self.params.items()}
+        self.velocity = {k: torch.zeros_like(v) for k, v in self.params.items()}
+        names = list(self.params)
+        self._lars = lc.LarsArgs([self.params[k] for k in names], [self.grads[k] for k in names], [self.velocity[k] for k in names])
+        self._lars_ws = self._bytes(lc.lars_workspace_bytes(self._lars.numel))
+        self.trust = torch.zeros(len(names), **f32)
+
+        # one workspace for every convolution pass and every batch norm
+        need = 0
+        for name in self.order:
+            L = self.layers[name]
+            for p in (lc.LC_PASS_FWD, lc.LC_PASS_BWD_DATA, lc.LC_PASS_BWD_WEIGHT):
+                need = max(need, lc.conv2d_workspace_bytes(L.desc, p))
+            need = max(need, lc.batchnorm_workspace_bytes(batch, L.desc.k, L.out_hw[0], L.out_hw[1], NHWC))
+        for p in (lc.LC_PASS_FWD, lc.LC_PASS_BWD_DATA, lc.LC_PASS_BWD_WEIGHT):
+            need = max(need, lc.conv2d_workspace_bytes(self.fc_desc, p))
+        self._ws = self._bytes(need)
+
+        # activations that the backward pass reads stay allocated; gradients of activations come and go
+        for name in self.order:
+            L = self.layers[name]
+            shape = (batch, L.out_hw[0], L.out_hw[1], L.desc.k)
+            L.z, L.a = torch.empty(shape, **f32), torch.empty(shape, **f32)
+            L.mean, L.invstd = torch.empty(L.desc.k, **f32), torch.empty(L.desc.k, **f32)
+        self.pool_out = torch.empty((batch, self.pool_out_hw[0], self.pool_out_hw[1], stem[0]), **f32)
+        self.pool_idx = torch.empty(self.pool_out.shape, dtype=torch.uint8, device=device)
+        self.gap = torch.empty((batch, ch), **f32)
+        self.logits = torch.empty((batch, classes), **f32)
+        self.dlogits = torch.empty((batch, classes), **f32)
+        self.loss = torch.zeros(1, **f32)
+        self._rows = torch.empty(batch, **f32)
+
+    # ------------------------------------------------------------------ construction helpers
+    def _bytes(self, n: int):
+        return torch.empty(max(n, 256), dtype=torch.uint8, device=self.dev)
+
+    def _add(self, name, cin, k, r, stride, pad, h, w, relu):
+        d = lc.ConvDesc(self.batch, cin, h, w, k, r, r, stride, stride, pad, pad, lc.LC_F32, NHWC)
+        p, q = lc.conv2d_out_shape(d)
+        self.layers[name] = _ConvBn(name, d, (p, q), relu)
+        self.order.append(name)
+        return p, q
+
+    def _new(self, like: torch.Tensor) -> torch.Tensor:
+        return torch.empty_like(like)
+
+    # ------------------------------------------------------------------ layers
+    def _conv_bn(self, name: str, x: torch.Tensor, residual: Optional[torch.Tensor] = None, relu_after_residual: bool = False):
+        L = self.layers[name]
+        L.x = x
+        k, (p, q) = L.desc.k, L.out_hw
+        lc.conv2d_fwd(L.desc, x, self.params[name + ".w"], L.z, self._ws)
+        lc.batchnorm_fwd_ex(L.z, self.params[name + ".gamma"], self.params[name + ".beta"], residual, L.a, L.mean, L.invstd,
+                            self.batch, k, p, q, self.eps, L.relu or relu_after_residual, NHWC, self._ws)
+        return L.a
+
+    def _conv_bn_bwd(self, name: str, da: torch.Tensor, need_dx: bool = True) -> Optional[torch.Tensor]:
+        """``da``: gradient with respect to the layer's output -- of the fused ReLU's output where the layer has
+        one, otherwise of the batch-norm output itself (the caller has applied the block's last ReLU)."""
+        L = self.layers[name]
+        k, (p, q) = L.desc.k, L.out_hw
+        dz = self._new(L.z)
+        lc.batchnorm_bwd_ex(L.z, da, self.params[name + ".gamma"], self.params[name + ".beta"], L.mean, L.invstd, dz,
+                            self.grads[name + ".gamma"], self.grads[name + ".beta"], self.batch, k, p, q, L.relu, NHWC, self._ws)
+        lc.conv2d_bwd_weight(L.desc, L.x, dz, self.grads[name + ".w"], self._ws)
+        if not need_dx:
+            return None
+        dx = self._new(L.x)
+        lc.conv2d_bwd_data(L.desc, dz, self.params[name + ".w"], dx, self._ws)
+        return dx
+
+    # ------------------------------------------------------------------ the step
+    def forward(self, x: torch.Tensor, labels: torch.Tensor) -> torch.Tensor:
+        """x: [batch, h, w, channels] fp32, labels: [batch] int32.  Returns the loss (a device tensor of one float)."""
+        n = self.batch
+        a = self._conv_bn("stem", x)
+        c0 = self.layers["stem"].desc.k
+        lc.maxpool_fwd(a, self.pool_out, self.pool_idx, n, c0, self.pool_in_hw[0], self.pool_in_hw[1], 3, 2, 1, NHWC)
+        a = self.pool_out
+        for name, proj in self.blocks:
+            sc = self._conv_bn(name + ".proj", a) if proj else a
+            b = self._conv_bn(name + ".c1", a)
+            b = self._conv_bn(name + ".c2", b)
+            a = self._conv_bn(name + ".c3", b, residual=sc, relu_after_residual=True)
+        lc.global_avgpool_fwd(a, self.gap, n, self.final_ch, self.final_hw[0], self.final_hw[1], NHWC)
+        lc.conv2d_fwd(self.fc_desc, self.gap, self.params["fc.w"], self.logits, self._ws)
+        lc.bias_add(self.logits, self.params["fc.b"], n, self.classes)
+        lc.softmax_xent(self.logits, labels, self.loss, self.dlogits, self._rows, n, self.classes)
+        return self.loss
+
+    def backward(self) -> None:
+        n = self.batch
+        lc.bias_grad(self.dlogits, self.grads["fc.b"], n, self.classes)
+        lc.conv2d_bwd_weight(self.fc_desc, self.gap, self.dlogits, self.grads["fc.w"], self._ws)
+        dgap = self._new(self.gap)
+        lc.conv2d_bwd_data(self.fc_desc, self.dlogits, self.params["fc.w"], dgap, self._ws)
+        last = self.layers[self.blocks[-1][0] + ".c3"].a
+        g1: torch.Tensor = self._new(last)
+        g2: Optional[torch.Tensor] = None
+        lc.global_avgpool_bwd(dgap, g1, n, self.final_ch, self.final_hw[0], self.final_hw[1], NHWC)
+        for name, proj in reversed(self.blocks):
+            out = self.layers[name + ".c3"].a
+            d_pre = self._new(out)
+            lc.relu_add_bwd(out, g1, g2, d_pre, out.numel())          # both arriving gradients through the block's last ReLU
+            d = self._conv_bn_bwd(name + ".c3", d_pre)
+            d = self._conv_bn_bwd(name + ".c2", d)
+            g1 = self._conv_bn_bwd(name + ".c1", d)
+            g2 = self._conv_bn_bwd(name + ".proj", d_pre) if proj else d_pre
+        d_pool = self._new(self.pool_out)
+        lc.relu_add_bwd(None, g1, g2, d_pool, d_pool.numel())         # the pool's output feeds the first block twice
+        stem = self.layers["stem"]
+        da = self._new(stem.a)
+        lc.maxpool_bwd(d_pool, self.pool_idx, da, n, stem.desc.k, self.pool_in_hw[0], self.pool_in_hw[1], 3, 2, 1, NHWC)
+        self._conv_bn_bwd("stem", da, need_dx=False)
+
+    def lars(self, eta: float, momentum: float, weight_decay: float, lr: float) -> None:
+        lc.lars_step(self._lars, eta, momentum, weight_decay, lr, self.trust, self._lars_ws)
+
+    def step(self, x: torch.Tensor, labels: torch.Tensor, eta: float, momentum: float, weight_decay: float, lr: float) -> torch.Tensor:
+        loss = self.forward(x, labels)
+        self.backward()
+        self.lars(eta, momentum, weight_decay, lr)
+        return loss

@@ -250,3 +250,12 @@ def test_relu_add_bwd(count, two):
     torch.cuda.synchronize()
     total = da.astype(np.float64) + (db.astype(np.float64) if two else 0.0)        # exact in float64
     np.testing.assert_array_equal(dx.cpu().numpy(), np.where(y > 0.0, total, 0.0).astype(np.float32))
+
+
+def test_relu_add_bwd_without_mask_is_a_plain_sum():
+    count = 4096 + 4
+    da, db = synth.normal((count,), 7731), synth.normal((count,), 7732)
+    dx = torch.empty(count, device=gu.DEV)
+    lc.relu_add_bwd(None, _dev(da), _dev(db), dx, count)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(dx.cpu().numpy(), (da.astype(np.float64) + db.astype(np.float64)).astype(np.float32))

@@ -1,0 +1,122 @@
+"""GPU parity of a WHOLE residual-network training step: the bottleneck network of oracle/resnet.py at a few
+channels (stem, overlapping max pool, a projection block, an identity block, a strided stage, classifier, loss),
+forward, backward and the LARS update on the device through the C ABI, against the float64 oracle.
+Tolerance 1e-4 tensor-scaled (the benchmark spec's fp32 bound) for every activation, gradient and updated weight.
+ReLU and the max pool take discrete decisions; the test first checks that the oracle's values leave a margin
+that fp32 rounding cannot cross, so both sides take the same decisions."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from oracle import resnet as ores
+from paper_1709_05011_amd import larsconv as lc
+from paper_1709_05011_amd import synth
+from paper_1709_05011_amd.resnet_step import ResNetStep
+
+import gpu_util as gu
+
+pytestmark = pytest.mark.gpu
+TOL = 1e-4
+CFG = ores.Config(stem=(8, 3, 1, 1), widths=(4, 8), blocks=(2, 1), classes=10)
+BATCH, HW = 8, 16
+
+
+def _problem(seed):
+    params = {}
+    for i, (name, shp) in enumerate(ores.param_shapes(CFG).items()):
+        if name.endswith(".gamma"):
+            params[name] = (1.0 + 0.2 * synth.normal(shp, seed + i)).astype(np.float32)
+        elif name.endswith(".beta") or name == "fc.b":
+            params[name] = (0.2 * synth.normal(shp, seed + i)).astype(np.float32)
+        else:
+            params[name] = synth.normal(shp, seed + i, std=(2.0 / int(np.prod(shp[1:]))) ** 0.5).astype(np.float32)
+    x = synth.normal((BATCH, 3, HW, HW), seed + 1000).astype(np.float32)
+    labels = synth.uniform_int(BATCH, seed + 2000, CFG.classes)
+    return x, labels, params
+
+
+def _to_device_layout(name, a):
+    if name.endswith(".w") and a.ndim == 4:
+        return np.ascontiguousarray(a.transpose(0, 2, 3, 1))          # [k, c, r, s] -> [k, r, s, c]
+    if name == "fc.w":
+        return np.ascontiguousarray(a.reshape(a.shape[0], 1, 1, a.shape[1]))
+    return a
+
+
+def _from_device_layout(name, a, ref_shape):
+    if name.endswith(".w") and len(ref_shape) == 4:
+        return a.transpose(0, 3, 1, 2)
+    return a.reshape(ref_shape)
+
+
+def test_whole_training_step_matches_oracle():
+    x, labels, params = _problem(4100)
+    trace, grads = ores.forward_backward(x, labels, params, CFG)
+
+    # premises: no ReLU input within 5e-6 of zero, no max-pool window whose two largest values are closer than 2e-5
+    for key, val in trace.items():
+        if key.endswith(".y") and not key.endswith(".proj.y"):           # every layer but the projections feeds a ReLU
+            assert np.min(np.abs(val)) > 5e-6, key
+    a = trace["stem.a"]
+    ap = np.pad(a, ((0, 0), (0, 0), (1, 1), (1, 1)), constant_values=-np.inf)
+    ph = (a.shape[2] + 2 - 3) // 2 + 1
+    wins = np.stack([ap[:, :, r:r + 2 * ph:2, s:s + 2 * ph:2] for r in range(3) for s in range(3)], axis=-1)
+    top2 = np.sort(wins, axis=-1)[..., -2:]
+    contested = top2[..., 1] > 0.0                                     # all-zero windows tie exactly on both sides
+    assert np.min((top2[..., 1] - top2[..., 0])[contested]) > 2e-5
+
+    net = ResNetStep(CFG.stem, CFG.widths, CFG.blocks, CFG.classes, BATCH, (HW, HW))
+    assert list(net.params) == list(params)
+    for k, v in params.items():
+        net.params[k].copy_(torch.from_numpy(_to_device_layout(k, v)))
+    xd = gu.dev(np.ascontiguousarray(x.transpose(0, 2, 3, 1)))
+    ld = gu.dev(labels.astype(np.int32))
+    loss = net.forward(xd, ld)
+    net.backward()
+    torch.cuda.synchronize()
+
+    assert abs(float(loss.item()) - float(trace["loss"])) <= 1e-5 * max(1.0, abs(float(trace["loss"])))
+    assert gu.scaled_err(net.logits.cpu().numpy(), trace["logits"]) <= TOL
+    for name in net.order:
+        L = net.layers[name]
+        assert gu.scaled_err(L.z.cpu().numpy().transpose(0, 3, 1, 2), trace[name + ".z"]) <= TOL, name
+        assert gu.scaled_err(L.a.cpu().numpy().transpose(0, 3, 1, 2), trace[name + ".a"]) <= TOL, name
+    worst = 0.0
+    for k in params:
+        got = _from_device_layout(k, net.grads[k].cpu().numpy(), grads[k].shape)
+        err = gu.scaled_err(got, grads[k])
+        worst = max(worst, err)
+        assert err <= TOL, (k, err)
+    print(f"worst gradient error {worst:.2e}")
+
+    # the update: LARS over all tensors with the gradients just produced
+    eta, momentum, wd, lr = 0.001, 0.9, 5e-4, 0.3
+    names = list(params)
+    ow = [params[k].copy() for k in names]
+    ov = [np.zeros_like(params[k]) for k in names]
+    og = [np.ascontiguousarray(grads[k], dtype=np.float32) for k in names]
+    trust, _ = oracle.lars_step(ow, og, ov, eta, momentum, wd, lr)
+    net.lars(eta, momentum, wd, lr)
+    torch.cuda.synchronize()
+    got_trust = net.trust.cpu().numpy().astype(np.float64)
+    assert np.max(np.abs(got_trust - trust) / np.abs(trust)) <= 1e-4     # the gradients themselves differ by <= 1e-4
+    for k, w_ref, v_ref in zip(names, ow, ov):
+        assert gu.scaled_err(_from_device_layout(k, net.params[k].cpu().numpy(), w_ref.shape), w_ref) <= TOL, k
+        assert gu.scaled_err(_from_device_layout(k, net.velocity[k].cpu().numpy(), v_ref.shape), v_ref) <= 2e-4, k
+
+
+def test_second_step_runs_on_updated_weights_and_lowers_the_loss():
+    """Two steps on the same batch with a small rate: buffers are reused, nothing is left over from step one,
+    and the loss goes down (a descent direction)."""
+    x, labels, params = _problem(4200)
+    net = ResNetStep(CFG.stem, CFG.widths, CFG.blocks, CFG.classes, BATCH, (HW, HW))
+    for k, v in params.items():
+        net.params[k].copy_(torch.from_numpy(_to_device_layout(k, v)))
+    xd = gu.dev(np.ascontiguousarray(x.transpose(0, 2, 3, 1)))
+    ld = gu.dev(labels.astype(np.int32))
+    losses = []
+    for _ in range(3):
+        losses.append(float(net.step(xd, ld, 0.02, 0.0, 0.0, 1.0).item()))
+    assert np.all(np.isfinite(losses))
+    assert losses[1] < losses[0] and losses[2] < losses[1], losses
