@@ -391,6 +391,52 @@ def run_batchnorm(args):
     return out
 
 
+def run_full_step(args):
+    """The WHOLE ResNet-50 training step at batch 256, fp32: every convolution, batch norm, ReLU, pool, the
+    classifier, the loss, all gradients and lars_step over the 161 tensors, each a call into the library
+    (paper_1709_05011_amd/resnet_step.py only orders the calls).  Weights are random (He), images and labels
+    synthetic.  This is a secondary mode: the headline metric times the convolution + LARS path."""
+    import torch
+    from paper_1709_05011_amd.resnet_step import ResNetStep
+
+    batch = args.batch or 256
+    gen = torch.Generator(device="cuda:0")
+    gen.manual_seed(0x5EED0600)
+    net = ResNetStep((64, 7, 2, 3), (64, 128, 256, 512), (3, 4, 6, 3), 1000, batch, (224, 224))
+    for name, t in net.params.items():
+        if name.endswith(".w"):
+            fan = t[0].numel()
+            t.copy_(torch.randn(t.shape, generator=gen, device="cuda:0") * (2.0 / fan) ** 0.5)
+    x = torch.randn((batch, 224, 224, 3), generator=gen, device="cuda:0")
+    labels = torch.randint(0, 1000, (batch,), generator=gen, device="cuda:0", dtype=torch.int32)
+    lr = 0.1
+    for _ in range(args.warmup):
+        net.step(x, labels, 0.001, 0.9, 1e-4, lr)
+    torch.cuda.synchronize()
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(4)]
+    phases = {"forward": 0.0, "backward": 0.0, "lars_step": 0.0}
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        ev[0].record()
+        loss = net.forward(x, labels)
+        ev[1].record()
+        net.backward()
+        ev[2].record()
+        net.lars(0.001, 0.9, 1e-4, lr)
+        ev[3].record()
+        torch.cuda.synchronize()
+        for k, (a, b) in zip(phases, ((0, 1), (1, 2), (2, 3))):
+            phases[k] += ev[a].elapsed_time(ev[b])
+    wall = time.perf_counter() - t0
+    ms = wall * 1e3 / args.steps
+    return {"metric": "resnet50_whole_step_images_per_second", "value": round(batch / (ms * 1e-3), 1), "unit": "images/s", "n_gpus": 1,
+            "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms, 3), "higher_is_better": True, "scaling": "weak",
+            "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+            "config": {"workload": f"ResNet-50 whole training step (all layers + LARS), batch {batch}, 224x224, NHWC"},
+            "phase_ms": {k: round(v / args.steps, 3) for k, v in phases.items()}, "loss": round(float(loss.item()), 4),
+            "peak_memory_GB": round(torch.cuda.max_memory_allocated() / 1e9, 2)}
+
+
 def run_copy_calibration(args):
     """A plain device-to-device copy of known size: what the FETCH_SIZE / WRITE_SIZE counters of rocprofv3 read
     for it gives the factor by which the counters of the other kernels are scaled."""
@@ -424,6 +470,7 @@ def main():
     ap.add_argument("--lars", choices=["resnet50", "alexnet_bn"])
     ap.add_argument("--rotate", type=int, default=1)
     ap.add_argument("--batchnorm", action="store_true", help="batch-normalisation layers alone, GB/s against HBM peak")
+    ap.add_argument("--full-step", action="store_true", help="the whole ResNet-50 step: all layers, loss, gradients, LARS")
     ap.add_argument("--copy-calib", action="store_true", help="run a 1 GiB device copy (counter calibration)")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -437,6 +484,8 @@ def main():
         res = run_lars(args)
     elif args.batchnorm:
         res = run_batchnorm(args)
+    elif args.full_step:
+        res = run_full_step(args)
     else:
         res = run_train_step(args)
     print(json.dumps(res), flush=True)

@@ -187,6 +187,71 @@ __global__ void __launch_bounds__(kThreads) maxpool_bwd_kernel(const float* __re
     }
 }
 
+// The same two kernels for NHWC with the channel count a multiple of four: a thread owns four neighbouring
+// channels of one pixel (16-byte accesses, four index bytes as one word).
+__global__ void __launch_bounds__(kThreads) maxpool_fwd_nhwc4_kernel(const float* __restrict__ x, float* __restrict__ y, uint8_t* __restrict__ idx,
+                                                                     int N, int C4, int H, int W, int K, int stride, int pad, int Ho, int Wo) {
+    const size_t total = (size_t)N * Ho * Wo * C4;
+    for (size_t o = blockIdx.x * (size_t)blockDim.x + threadIdx.x; o < total; o += (size_t)gridDim.x * blockDim.x) {
+        size_t t = o;
+        const int c4 = (int)(t % C4); t /= C4;
+        const int q = (int)(t % Wo); t /= Wo;
+        const int p = (int)(t % Ho);
+        const int n = (int)(t / Ho);
+        float best[4] = {0.f, 0.f, 0.f, 0.f};
+        int bi[4] = {-1, -1, -1, -1};
+        for (int r = 0; r < K; ++r) {
+            const int ih = p * stride - pad + r;
+            if (ih < 0 || ih >= H) continue;
+            for (int s2 = 0; s2 < K; ++s2) {
+                const int iw = q * stride - pad + s2;
+                if (iw < 0 || iw >= W) continue;
+                const float4 v4 = reinterpret_cast<const float4*>(x)[(((size_t)n * H + ih) * W + iw) * C4 + c4];
+                const float v[4] = {v4.x, v4.y, v4.z, v4.w};
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    if (bi[e] < 0 || v[e] > best[e]) {
+                        best[e] = v[e];
+                        bi[e] = r * K + s2;
+                    }
+            }
+        }
+        reinterpret_cast<float4*>(y)[o] = make_float4(best[0], best[1], best[2], best[3]);
+        reinterpret_cast<uchar4*>(idx)[o] = make_uchar4((uint8_t)bi[0], (uint8_t)bi[1], (uint8_t)bi[2], (uint8_t)bi[3]);
+    }
+}
+
+__global__ void __launch_bounds__(kThreads) maxpool_bwd_nhwc4_kernel(const float* __restrict__ dy, const uint8_t* __restrict__ idx, float* __restrict__ dx,
+                                                                     int N, int C4, int H, int W, int K, int stride, int pad, int Ho, int Wo) {
+    const size_t total = (size_t)N * H * W * C4;
+    for (size_t o = blockIdx.x * (size_t)blockDim.x + threadIdx.x; o < total; o += (size_t)gridDim.x * blockDim.x) {
+        size_t t = o;
+        const int c4 = (int)(t % C4); t /= C4;
+        const int w = (int)(t % W); t /= W;
+        const int h = (int)(t % H);
+        const int n = (int)(t / H);
+        const int hp = h + pad, wp = w + pad;
+        const int p0 = hp - K + 1 <= 0 ? 0 : (hp - K + stride) / stride;
+        const int q0 = wp - K + 1 <= 0 ? 0 : (wp - K + stride) / stride;
+        int p1 = hp / stride, q1 = wp / stride;
+        if (p1 > Ho - 1) p1 = Ho - 1;
+        if (q1 > Wo - 1) q1 = Wo - 1;
+        float acc[4] = {0.f, 0.f, 0.f, 0.f};
+        for (int p = p0; p <= p1; ++p)
+            for (int q = q0; q <= q1; ++q) {
+                const uint8_t tap = (uint8_t)((hp - p * stride) * K + (wp - q * stride));
+                const size_t oo = (((size_t)n * Ho + p) * Wo + q) * C4 + c4;
+                const uchar4 i4 = reinterpret_cast<const uchar4*>(idx)[oo];
+                const float4 g = reinterpret_cast<const float4*>(dy)[oo];
+                if (i4.x == tap) acc[0] += g.x;
+                if (i4.y == tap) acc[1] += g.y;
+                if (i4.z == tap) acc[2] += g.z;
+                if (i4.w == tap) acc[3] += g.w;
+            }
+        reinterpret_cast<float4*>(dx)[o] = make_float4(acc[0], acc[1], acc[2], acc[3]);
+    }
+}
+
 __global__ void global_avgpool_fwd_kernel(const float* __restrict__ x, float* __restrict__ y, int N, int C, int H, int W, bool nhwc) {
     const int lane = threadIdx.x & 63;
     const size_t pair = (size_t)blockIdx.x * (kThreads / 64) + (threadIdx.x >> 6);
@@ -263,6 +328,7 @@ __global__ void mean_kernel(const float* __restrict__ v, float* __restrict__ out
 
 inline bool bad_layout(lc_layout l) { return l != LC_NCHW && l != LC_NHWC; }
 inline bool misaligned(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 3) != 0; }
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
 
 }  // namespace
 
@@ -357,8 +423,12 @@ extern "C" lc_status maxpool_fwd(const float* x, float* y, uint8_t* idx, int n, 
     if (misaligned(x) || misaligned(y)) return LC_ERR_ALIGN;
     lc_begin_call();
     const size_t total = (size_t)n * c * ho * wo;
-    hipLaunchKernelGGL(maxpool_fwd_kernel, dim3(blocks_for(total)), dim3(kThreads), 0, static_cast<hipStream_t>(hip_stream), x, y, idx, n,
-                       c, h, w, window, stride, pad, ho, wo, layout == LC_NHWC);
+    if (layout == LC_NHWC && c % 4 == 0 && aligned16(x) && aligned16(y) && (reinterpret_cast<uintptr_t>(idx) & 3) == 0)
+        hipLaunchKernelGGL(maxpool_fwd_nhwc4_kernel, dim3(blocks_for(total / 4)), dim3(kThreads), 0, static_cast<hipStream_t>(hip_stream),
+                           x, y, idx, n, c / 4, h, w, window, stride, pad, ho, wo);
+    else
+        hipLaunchKernelGGL(maxpool_fwd_kernel, dim3(blocks_for(total)), dim3(kThreads), 0, static_cast<hipStream_t>(hip_stream), x, y, idx,
+                           n, c, h, w, window, stride, pad, ho, wo, layout == LC_NHWC);
     return lc_end_call();
 }
 
@@ -371,8 +441,12 @@ extern "C" lc_status maxpool_bwd(const float* dy, const uint8_t* idx, float* dx,
     if (misaligned(dy) || misaligned(dx)) return LC_ERR_ALIGN;
     lc_begin_call();
     const size_t total = (size_t)n * c * h * w;
-    hipLaunchKernelGGL(maxpool_bwd_kernel, dim3(blocks_for(total)), dim3(kThreads), 0, static_cast<hipStream_t>(hip_stream), dy, idx, dx,
-                       n, c, h, w, window, stride, pad, ho, wo, layout == LC_NHWC);
+    if (layout == LC_NHWC && c % 4 == 0 && aligned16(dy) && aligned16(dx) && (reinterpret_cast<uintptr_t>(idx) & 3) == 0)
+        hipLaunchKernelGGL(maxpool_bwd_nhwc4_kernel, dim3(blocks_for(total / 4)), dim3(kThreads), 0, static_cast<hipStream_t>(hip_stream),
+                           dy, idx, dx, n, c / 4, h, w, window, stride, pad, ho, wo);
+    else
+        hipLaunchKernelGGL(maxpool_bwd_kernel, dim3(blocks_for(total)), dim3(kThreads), 0, static_cast<hipStream_t>(hip_stream), dy, idx,
+                           dx, n, c, h, w, window, stride, pad, ho, wo, layout == LC_NHWC);
     return lc_end_call();
 }
 

@@ -176,6 +176,34 @@ def test_batchnorm_rejects_bad_arguments_before_launch():
     assert L.batchnorm_bwd(P, P, P, P, P, P, P, P, 4, 8, 5, 5, lc.LC_NHWC, P, 0, None) == lc.LC_ERR_WORKSPACE
 
 
+def test_fused_layers_reject_bad_arguments_before_launch():
+    L = lc.lib()
+    P = ctypes.c_void_p(FAKE)
+    need = lc.batchnorm_workspace_bytes(4, 8, 5, 5, lc.LC_NHWC)
+    # forward: the residual is optional, everything else is not
+    assert L.batchnorm_fwd_ex(P, P, None, None, P, P, P, 4, 8, 5, 5, 1e-5, 1, lc.LC_NHWC, P, need, None) == lc.LC_ERR_NULL
+    assert L.batchnorm_fwd_ex(P, P, P, ctypes.c_void_p(FAKE + 1), P, P, P, 4, 8, 5, 5, 1e-5, 1, lc.LC_NHWC, P, need, None) == lc.LC_ERR_ALIGN
+    assert L.batchnorm_fwd_ex(P, P, P, None, P, P, P, 4, 8, 5, 5, 1e-5, 1, lc.LC_NHWC, P, need - 1, None) == lc.LC_ERR_WORKSPACE
+    # backward through the ReLU needs beta; without the ReLU it may be missing (then the workspace check is reached)
+    assert L.batchnorm_bwd_ex(P, P, P, None, P, P, P, P, P, 4, 8, 5, 5, 1, lc.LC_NHWC, P, need, None) == lc.LC_ERR_NULL
+    assert L.batchnorm_bwd_ex(P, P, P, None, P, P, P, P, P, 4, 8, 5, 5, 0, lc.LC_NHWC, P, 0, None) == lc.LC_ERR_WORKSPACE
+    # pools: window 1..15, pad below the window, the window must fit
+    pool = lambda win, st, pd, h=9, lay=lc.LC_NHWC, x=P: L.maxpool_fwd(x, P, P, 2, 4, h, 9, win, st, pd, lay, None)
+    assert pool(3, 2, 1, x=None) == lc.LC_ERR_NULL
+    assert pool(0, 2, 0) == lc.LC_ERR_SHAPE
+    assert pool(16, 2, 0) == lc.LC_ERR_SHAPE
+    assert pool(3, 0, 1) == lc.LC_ERR_SHAPE
+    assert pool(3, 2, 3) == lc.LC_ERR_SHAPE
+    assert pool(5, 1, 0, h=3) == lc.LC_ERR_SHAPE
+    assert pool(3, 2, 1, lay=4) == lc.LC_ERR_UNSUPPORTED
+    assert L.maxpool_bwd(P, None, P, 2, 4, 9, 9, 3, 2, 1, lc.LC_NHWC, None) == lc.LC_ERR_NULL
+    # gradient at a block's output: y or db may be missing, not both
+    assert L.relu_add_bwd(None, P, None, P, 16, None) == lc.LC_ERR_NULL
+    assert L.relu_add_bwd(P, None, P, P, 16, None) == lc.LC_ERR_NULL
+    assert L.relu_add_bwd(P, P, P, ctypes.c_void_p(FAKE + 2), 16, None) == lc.LC_ERR_ALIGN
+    assert L.relu_add_bwd(P, P, P, P, 0, None) == lc.LC_OK
+
+
 def test_poly_lr_host_arithmetic():
     assert lc.lars_poly_lr(1.0, 0, 3516) == 1.0
     assert lc.lars_poly_lr(1.0, 3516, 3516) == 0.0
