@@ -282,10 +282,13 @@ def run_sweep(args):
     from paper_1709_05011_amd import synth
 
     batch = args.batch or 128
+    bf16 = args.dtype == "bf16"
+    peak = PEAK_MFMA_BF16 if bf16 else PEAK_MFMA_F32
     gen = torch.Generator(device="cuda:0")
     gen.manual_seed(0x5EED0200)
     rows = []
     tot = {"fwd": [0.0, 0.0], "bwd_data": [0.0, 0.0], "bwd_weight": [0.0, 0.0]}
+    roof_ms = 0.0
     for idx, (cs, count) in enumerate(synth.resnet50_distinct_shapes(batch), start=1):
         if args.only and idx not in args.only:
             continue
@@ -296,14 +299,27 @@ def run_sweep(args):
             "bwd_data": lambda: lc.conv2d_bwd_data(l.desc, l.dy, l.w, l.dx, ws),
             "bwd_weight": lambda: lc.conv2d_bwd_weight(l.desc, l.x, l.dy, l.dw, ws),
         }
+        # each pass against its own roof: min(MFMA peak, arithmetic intensity x HBM peak), the intensity from the
+        # bytes every pass must move at least once (both operands read, the result written; the filter gradient
+        # is fp32 in both modes)
+        es = 2 if bf16 else 4
+        xb, yb, wb = cs.n * cs.c * cs.h * cs.w * es, cs.n * cs.k * cs.p * cs.q * es, cs.weight_numel * es
+        min_bytes = {"fwd": xb + wb + yb, "bwd_data": yb + wb + xb, "bwd_weight": xb + yb + cs.weight_numel * 4}
         row = {"shape": idx, "name": cs.name, "c": cs.c, "k": cs.k, "rs": cs.r, "stride": cs.stride, "hw": cs.h,
                "count": count, "gflop": round(cs.flops / 1e9, 2)}
         for p, fn in calls.items():
+            if p == "bwd_data" and idx == 1:
+                continue                      # the first layer's input gradient is never needed in a training step
             med, mn = time_call(torch, fn, args.iters)
+            tf = cs.flops / (med * 1e-3) / 1e12
+            roof = min(peak, cs.flops / min_bytes[p] * PEAK_HBM / 1e3)
             row[p + "_ms"] = round(med, 4)
-            row[p + "_tflops"] = round(cs.flops / (med * 1e-3) / 1e12, 2)
+            row[p + "_tflops"] = round(tf, 2)
+            row[p + "_roof_tflops"] = round(roof, 1)
+            row[p + "_frac_of_roof"] = round(tf / roof, 3)
             tot[p][0] += med * count
             tot[p][1] += cs.flops * count
+            roof_ms += cs.flops / (roof * 1e12) * 1e3 * count
         rows.append(row)
         log(json.dumps(row))
         del l, ws
@@ -313,7 +329,9 @@ def run_sweep(args):
     all_fl = sum(v[1] for v in tot.values())
     return {"sweep": "resnet50_distinct_conv_shapes", "batch": batch, "dtype": args.dtype, "layout": "NHWC",
             "weighted_tflops": summary, "weighted_tflops_all": round(all_fl / (all_ms * 1e-3) / 1e12, 2),
-            "frac_of_mfma_peak": round(all_fl / (all_ms * 1e-3) / 1e12 / PEAK_MFMA_F32, 4), "rows": rows}
+            "frac_of_mfma_peak": round(all_fl / (all_ms * 1e-3) / 1e12 / peak, 4),
+            "roof": "per pass min(MFMA peak, flops / minimal bytes x 8 TB/s)", "ms_all": round(all_ms, 3),
+            "ms_at_roof": round(roof_ms, 3), "frac_of_roof": round(roof_ms / all_ms, 4), "rows": rows}
 
 
 def run_lars(args):

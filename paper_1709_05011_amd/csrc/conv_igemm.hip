@@ -323,8 +323,11 @@ __device__ __forceinline__ int div_by(int n, unsigned mul, unsigned shift) {    
     return mul ? (int)(__umulhi((unsigned)n, mul) >> shift) : n;
 }
 
+// Blocks per compute unit: 3 for tiles up to 128x128 (64 accumulator registers per lane), 2 for the 128x256 tile.
+constexpr int pk_blocks_per_cu(int bm, int bn) { return bm * bn > 128 * 128 ? 2 : 3; }
+
 template <int BM, int BN, bool SMALLC, bool BF16, bool UT, bool SCATTER>
-__global__ void __launch_bounds__(256, 3) conv_gemm_pk_kernel(const GemmConv p) {   // 3 blocks per compute unit: resident_blocks()
+__global__ void __launch_bounds__(256, pk_blocks_per_cu(BM, BN)) conv_gemm_pk_kernel(const GemmConv p) {
     using E = typename OutT<BF16>::type;
     constexpr int ES = (int)sizeof(E);
     constexpr int EPC = BF16 ? 8 : 4;
@@ -1457,8 +1460,21 @@ SkPlan sk_plan(long long tiles, int nkt, int resident_blocks) {
     return pl;
 }
 
-// Blocks of the main kernel that fit on the chip at once: 3 per compute unit (32 KB LDS, ~140 registers).
-inline int resident_blocks() { return 3 * device_cu_count(); }
+// Blocks of the main kernel that fit on the chip at once (the kernel's launch bounds hold it to this).
+inline int resident_blocks(int bm, int bn) { return pk_blocks_per_cu(bm, bn) * device_cu_count(); }
+
+// Tile of the main kernel for a problem: 64 columns for narrow results, otherwise 128 -- or 256 for bf16 results
+// at least that wide when there are at least three rounds of 128x256 tiles.  The wide tile issues a quarter
+// fewer LDS and load instructions per MFMA; that pays in the bf16 loop, which is bound by LDS bandwidth (measured:
+// 5 to 20 % on such layers), not in fp32 (slightly slower everywhere), and with fewer rounds the coarser tiles
+// leave compute units idle at the end.  The few-channels and scatter variants are built for 64 and 128 only.
+inline int main_tile_n(const GemmConv& p) {
+    static const bool no_wide = getenv("LARSCONV_NO_WIDE_TILE") != nullptr;    // comparison runs
+    if (p.N <= 64) return 64;
+    if (!p.bf16 || p.N < 256 || p.Ci < 32 || p.scatter || no_wide) return 128;
+    const long long tiles = (long long)((p.M + 127) / 128) * ((p.N + 255) / 256);
+    return tiles >= 3LL * resident_blocks(128, 256) ? 256 : 128;
+}
 
 template <int BM, int BN>
 bool sk_geometry(const GemmConv& p, long long* tiles, int* nkt) {
@@ -1527,10 +1543,10 @@ lc_status launch_conv_sk(GemmConv p, hipStream_t stream) {
     long long tiles;
     int nkt;
     if (!sk_geometry<BM, BN>(p, &tiles, &nkt)) return LC_ERR_UNSUPPORTED;
-    SkPlan pl = sk_plan(tiles, nkt, resident_blocks());
+    const int resident = resident_blocks(BM, BN);
+    SkPlan pl = sk_plan(tiles, nkt, resident);
     // persistent kernel: one round of resident blocks, each taking dp_tiles / grid whole tiles and then its
     // stream-K range; without a workspace for partial tiles the ranges are whole tiles
-    const int resident = resident_blocks();
     if (pl.sk_blocks > 0 && !p.partial) pl.sk_blocks = 0;
     if (pl.sk_blocks == 0) {
         const long long rest = tiles % resident;
@@ -1548,11 +1564,13 @@ lc_status launch_conv_sk(GemmConv p, hipStream_t stream) {
     const bool ut = !SMALLC && uniform_tap_ok<BM, BN>(p);
     if (p.scatter) {                          // the scatter epilogue addresses the result relative to the tile's first pixel
         const long long span = ((long long)BM / ((long long)p.Po * p.Qo) + 2) * p.Ho * p.Wo * p.ldd * (p.bf16 ? 2 : 4);
-        if (span >= 0x7fff0000LL || SMALLC) return LC_ERR_UNSUPPORTED;   // (1x1 windows never have fewer channels than a k-step)
-        if (ut)
-            hipLaunchKernelGGL((conv_gemm_pk_kernel<BM, BN, false, BF16, true, true>), dim3(grid), dim3(256), 0, stream, p);
-        else
-            hipLaunchKernelGGL((conv_gemm_pk_kernel<BM, BN, false, BF16, false, true>), dim3(grid), dim3(256), 0, stream, p);
+        if (span >= 0x7fff0000LL || SMALLC || BN > 128) return LC_ERR_UNSUPPORTED;   // (1x1 windows never have fewer channels than a k-step)
+        if constexpr (BN <= 128) {
+            if (ut)
+                hipLaunchKernelGGL((conv_gemm_pk_kernel<BM, BN, false, BF16, true, true>), dim3(grid), dim3(256), 0, stream, p);
+            else
+                hipLaunchKernelGGL((conv_gemm_pk_kernel<BM, BN, false, BF16, false, true>), dim3(grid), dim3(256), 0, stream, p);
+        }
     } else if (ut) {
         hipLaunchKernelGGL((conv_gemm_pk_kernel<BM, BN, false, BF16, true, false>), dim3(grid), dim3(256), 0, stream, p);
     } else {
@@ -1582,10 +1600,12 @@ size_t lc_conv_gemm_workspace(const GemmConv& p) {
     if (!use_main_kernel(p)) return 0;
     long long tiles;
     int nkt;
-    const bool wide = p.N > 64;
-    if (!(wide ? sk_geometry<128, 128>(p, &tiles, &nkt) : sk_geometry<128, 64>(p, &tiles, &nkt))) return 0;
-    const SkPlan pl = sk_plan(tiles, nkt, resident_blocks());
-    return (size_t)2 * pl.sk_blocks * 128 * (wide ? 128 : 64) * sizeof(float);
+    const int bn = main_tile_n(p);
+    if (!(bn == 256 ? sk_geometry<128, 256>(p, &tiles, &nkt) : bn == 128 ? sk_geometry<128, 128>(p, &tiles, &nkt)
+                                                                          : sk_geometry<128, 64>(p, &tiles, &nkt)))
+        return 0;
+    const SkPlan pl = sk_plan(tiles, nkt, resident_blocks(128, bn));
+    return (size_t)2 * pl.sk_blocks * 128 * bn * sizeof(float);
 }
 
 bool lc_conv_gemm_bf16_native(const GemmConv& p) { return p.bf16 && use_main_kernel(p); }
@@ -1594,7 +1614,9 @@ lc_status lc_launch_conv_gemm(const GemmConv& p, hipStream_t stream) {
     if (p.bf16) {
         if (!use_main_kernel(p)) return LC_ERR_UNSUPPORTED;       // the caller converts to fp32 instead
         if (p.Ci < 32) return p.N > 64 ? launch_conv_sk<128, 128, true, true>(p, stream) : launch_conv_sk<128, 64, true, true>(p, stream);
-        return p.N > 64 ? launch_conv_sk<128, 128, false, true>(p, stream) : launch_conv_sk<128, 64, false, true>(p, stream);
+        const int bn = main_tile_n(p);
+        if (bn == 256) return launch_conv_sk<128, 256, false, true>(p, stream);
+        return bn == 128 ? launch_conv_sk<128, 128, false, true>(p, stream) : launch_conv_sk<128, 64, false, true>(p, stream);
     }
     const bool vec = (p.Ci % 4 == 0) && aligned16(p.a) && aligned16(p.b);
     if (!vec) return launch_conv<64, 64, 16, 1>(p, stream);

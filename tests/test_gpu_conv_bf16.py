@@ -125,3 +125,36 @@ def test_bf16_full_size_batch512_sampled(name):
     cw = synth.sample_coords(128, (cs.k, cs.c, cs.r, cs.s), seed + 5)
     ref, _ = oracle.conv2d_bwd_weight_at(x, dy, (cs.r, cs.s), cw, cs.stride, cs.pad, oracle.NHWC)
     assert np.max(np.abs(dw[cw[:, 0], cw[:, 2], cw[:, 3], cw[:, 1]] - ref)) <= TOL_DW * np.max(np.abs(ref))
+
+
+def test_bf16_wide_tile_ragged_edges_sampled():
+    """A result wide and tall enough for the 128x256 tile of the main kernel (at least three rounds of tiles), with a
+    ragged last tile in both directions: 103,488 rows (808.5 tiles), 300 columns (256 + 44).  Sampled outputs plus the
+    last rows and columns; forward and backward-data (whose result is 320 wide: 256 + 64)."""
+    n, c, hw, k = 33, 320, 56, 300
+    seed = 7900
+    xb = synth.to_bf16_bits(synth.normal((n, hw, hw, c), seed))
+    wb = synth.to_bf16_bits(synth.normal((k, 1, 1, c), seed + 1, std=(2.0 / c) ** 0.5))
+    dyb = synth.to_bf16_bits(synth.normal((n, hw, hw, k), seed + 2))
+    x, wt, dy = (synth.bf16_bits_to_f32(b) for b in (xb, wb, dyb))
+    d = lc.ConvDesc(n, c, hw, hw, k, 1, 1, 1, 1, 0, 0, lc.LC_BF16, lc.LC_NHWC)
+    xd, wd, dyd = _dev_bf16(xb), _dev_bf16(wb), _dev_bf16(dyb)
+    y = torch.empty((n, hw, hw, k), dtype=torch.int16, device=gu.DEV)
+    dx = torch.empty((n, hw, hw, c), dtype=torch.int16, device=gu.DEV)
+    lc.conv2d_fwd(d, xd, wd, y, gu.workspace(lc.conv2d_workspace_bytes(d, lc.LC_PASS_FWD)))
+    lc.conv2d_bwd_data(d, dyd, wd, dx, gu.workspace(lc.conv2d_workspace_bytes(d, lc.LC_PASS_BWD_DATA)))
+    torch.cuda.synchronize()
+    y, dx = _back(y), _back(dx)
+    assert np.all(np.isfinite(y)) and np.all(np.isfinite(dx))
+
+    def coords(channels, sd):
+        rnd = synth.sample_coords(768, (n, channels, hw, hw), sd)
+        edge = np.array([[n - 1, ch, hw - 1, q] for ch in (0, 255, 256, channels - 1) for q in (0, hw - 2, hw - 1)] +
+                        [[0, ch, 0, 0] for ch in (0, 127, 128, 255, 256, channels - 1)], dtype=rnd.dtype)
+        return np.concatenate([rnd, edge])
+    cy = coords(k, seed + 3)
+    ref, _ = oracle.conv2d_fwd_at(x, wt, cy, 1, 0, oracle.NHWC)
+    assert np.max(np.abs(y[cy[:, 0], cy[:, 2], cy[:, 3], cy[:, 1]] - oracle.round_to_bf16(ref))) <= TOL_BF16 * np.max(np.abs(ref))
+    cx = coords(c, seed + 4)
+    ref, _ = oracle.conv2d_bwd_data_at(dy, wt, (hw, hw), cx, 1, 0, oracle.NHWC)
+    assert np.max(np.abs(dx[cx[:, 0], cx[:, 2], cx[:, 3], cx[:, 1]] - oracle.round_to_bf16(ref))) <= TOL_BF16 * np.max(np.abs(ref))
