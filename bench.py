@@ -142,7 +142,15 @@ def run_train_step(args):
         if pass_ == "bwd_weight":
             return "wgrad"
         n_gemm = cs.k if pass_ == "fwd" else cs.c
-        return "conv_gemm_128x128" if n_gemm > 64 else "conv_gemm_128x64"
+        if n_gemm <= 64:
+            return "conv_gemm_128x64"
+        # bf16: results at least 256 wide with three or more rounds of 128x256 tiles take the wide tile
+        # (not the strided 1x1 backward-data layers, whose scatter epilogue exists for 128 only)
+        rows = cs.n * cs.p * cs.q if pass_ == "fwd" or cs.stride > 1 else cs.n * cs.h * cs.w
+        scatter = pass_ == "bwd_data" and cs.stride > 1
+        if bf16 and n_gemm >= 256 and cs.c >= 32 and not scatter and -(-rows // 128) * -(-n_gemm // 256) >= 3 * 2 * 256:
+            return "conv_gemm_128x256"
+        return "conv_gemm_128x128"
 
     def step(timer=None):
         for l in layers:
@@ -183,8 +191,10 @@ def run_train_step(args):
     dom = max((k for k in per_kernel if k != "lars"), key=lambda k: per_kernel[k][0])
     dms, dn, dfl = per_kernel[dom]
     achieved = dfl / (dms * 1e-3) / 1e12
-    # bf16: forward and backward-data run on the bf16 matrix pipe; the filter gradient still multiplies in fp32
-    peak = (PEAK_MFMA_F32 if dom == "wgrad" else PEAK_MFMA_BF16) if bf16 else PEAK_MFMA_F32
+    # bf16: all three passes multiply on the bf16 matrix pipe (the filter gradient too, unless the comparison knob
+    # LARSCONV_WGRAD_WIDEN sends it through the widening fp32 kernel)
+    widened = dom == "wgrad" and os.environ.get("LARSCONV_WGRAD_WIDEN")
+    peak = PEAK_MFMA_BF16 if bf16 and not widened else PEAK_MFMA_F32
     name = "AlexNet-BN" if args.model == "alexnet_bn" else "ResNet-50"
     n_fc = len(layers) - n_bn
     result = {

@@ -8,6 +8,8 @@
 //              a, b, c with dx = a*dy + b*x + c)                                   -> dx
 //
 // Algorithmic bytes per element: forward 12 (x twice, y once), backward 20 (x and dy twice, dx once).
+// The forward sums are those of x - pivot and (x - pivot)^2 with the channel's first value as pivot, so that the
+// variance E[d^2] - E[d]^2 does not cancel when the mean is large against the spread (a constant channel gives 0).
 // Threads accumulate in fp32 over a few hundred values each, in a fixed order; blocks and the partials of all
 // blocks are combined in fp64 in index order: results are bit-identical from run to run.
 // Fused variants (the *_ex entry points): the forward pass can add a second tensor (a residual shortcut) and
@@ -76,6 +78,7 @@ __global__ void __launch_bounds__(kThreads) bn_reduce_nhwc_kernel(const float* _
         is[e] = (!STATS && live) ? inv_std[c0 + e] : 0.f;
         sc[e] = sh[e] = 0.f;
         if (MODE == kMaskedSums && live) scale_shift(gamma[c0 + e], beta[c0 + e], mu[e], is[e], &sc[e], &sh[e]);
+        if (STATS && live) mu[e] = x[c0 + e];          // the channel's pivot: its value at the first pixel
     }
     if (live) {
         for (long long r = r0 + ty; r < r1; r += g.ty) {
@@ -94,8 +97,9 @@ __global__ void __launch_bounds__(kThreads) bn_reduce_nhwc_kernel(const float* _
 #pragma unroll
             for (int e = 0; e < VEC; ++e) {
                 if constexpr (STATS) {
-                    s0[e] += a[e];
-                    s1[e] += a[e] * a[e];
+                    const float d = a[e] - mu[e];
+                    s0[e] += d;
+                    s1[e] += d * d;
                 } else {
                     const float d = (MODE == kMaskedSums && !(fmaf(sc[e], a[e], sh[e]) > 0.f)) ? 0.f : b[e];
                     s0[e] += d;
@@ -177,7 +181,7 @@ __global__ void __launch_bounds__(kThreads) bn_reduce_nchw_kernel(const float* _
     const int ch = blockIdx.y;
     const long long n0 = (long long)blockIdx.x * g.rows_per_slab;
     const long long n1 = n0 + g.rows_per_slab < g.N ? n0 + g.rows_per_slab : g.N;
-    const float mu = STATS ? 0.f : mean[ch], is = STATS ? 0.f : inv_std[ch];
+    const float mu = STATS ? x[(size_t)ch * g.HW] : mean[ch], is = STATS ? 0.f : inv_std[ch];   // STATS: the pivot
     float sc = 0.f, sh = 0.f;
     if (MODE == kMaskedSums) scale_shift(gamma[ch], beta[ch], mu, is, &sc, &sh);
     float s0 = 0.f, s1 = 0.f;
@@ -186,8 +190,9 @@ __global__ void __launch_bounds__(kThreads) bn_reduce_nchw_kernel(const float* _
         for (int i = threadIdx.x; i < g.HW; i += kThreads) {
             const float a = x[base + i];
             if constexpr (STATS) {
-                s0 += a;
-                s1 += a * a;
+                const float d = a - mu;
+                s0 += d;
+                s1 += d * d;
             } else {
                 const float b = (MODE == kMaskedSums && !(fmaf(sc, a, sh) > 0.f)) ? 0.f : dy[base + i];
                 s0 += b;
@@ -258,14 +263,15 @@ __device__ __forceinline__ bool channel_totals(const BnWorkspace& ws, const BnGe
 
 // forward: mean, 1/std, and y = scale*x + shift (+ residual)
 __global__ void __launch_bounds__(kFinChannels* kFinLanes)
-bn_finalize_fwd_kernel(BnWorkspace ws, const float* __restrict__ gamma, const float* __restrict__ beta,
-                       float* __restrict__ save_mean, float* __restrict__ save_invstd, BnGeom g, float eps) {
+bn_finalize_fwd_kernel(BnWorkspace ws, const float* __restrict__ x, size_t pivot_stride, const float* __restrict__ gamma,
+                       const float* __restrict__ beta, float* __restrict__ save_mean, float* __restrict__ save_invstd, BnGeom g, float eps) {
     int ch;
     double s0, s1;
     if (!channel_totals(ws, g, &ch, &s0, &s1)) return;
     const double m = (double)g.M;
-    const double mean = s0 / m;
-    double var = s1 / m - mean * mean;
+    const double off = s0 / m;                                  // mean of x - pivot
+    const double mean = (double)x[ch * pivot_stride] + off;
+    double var = s1 / m - off * off;
     if (var < 0.0) var = 0.0;
     const double inv_std = 1.0 / sqrt(var + (double)eps);
     const float mean_f = (float)mean, inv_std_f = (float)inv_std;
@@ -383,13 +389,14 @@ extern "C" lc_status batchnorm_fwd_ex(const float* x, const float* gamma, const 
     const dim3 fin_grid((c + kFinChannels - 1) / kFinChannels), fin_block(kFinChannels * kFinLanes);
     const float* none = nullptr;
     const bool two = residual != nullptr, clamp = relu != 0;
+    const size_t pivot_stride = layout == LC_NHWC ? 1 : (size_t)g.HW;       // the first pixel's value of channel ch sits at x[ch * stride]
     if (layout == LC_NHWC) {
         const dim3 grid((unsigned)g.slabs, (unsigned)g.cblocks);
         if (g.vec == 4)
             hipLaunchKernelGGL((bn_reduce_nhwc_kernel<4, kStats>), grid, dim3(kThreads), 0, stream, x, none, none, none, none, none, g, ws);
         else
             hipLaunchKernelGGL((bn_reduce_nhwc_kernel<1, kStats>), grid, dim3(kThreads), 0, stream, x, none, none, none, none, none, g, ws);
-        hipLaunchKernelGGL(bn_finalize_fwd_kernel, fin_grid, fin_block, 0, stream, ws, gamma, beta, save_mean, save_invstd, g, eps);
+        hipLaunchKernelGGL(bn_finalize_fwd_kernel, fin_grid, fin_block, 0, stream, ws, x, pivot_stride, gamma, beta, save_mean, save_invstd, g, eps);
         const dim3 agrid(stream_blocks(total / g.vec));
 #define LC_BN_APPLY(VEC, TWO, RELU) \
     hipLaunchKernelGGL((bn_apply_nhwc_kernel<VEC, TWO, RELU, false>), agrid, dim3(kThreads), 0, stream, x, residual, y, ws.coef, g)
@@ -404,7 +411,7 @@ extern "C" lc_status batchnorm_fwd_ex(const float* x, const float* gamma, const 
     } else {
         hipLaunchKernelGGL((bn_reduce_nchw_kernel<kStats>), dim3((unsigned)g.slabs, (unsigned)c), dim3(kThreads), 0, stream, x, none, none, none,
                            none, none, g, ws);
-        hipLaunchKernelGGL(bn_finalize_fwd_kernel, fin_grid, fin_block, 0, stream, ws, gamma, beta, save_mean, save_invstd, g, eps);
+        hipLaunchKernelGGL(bn_finalize_fwd_kernel, fin_grid, fin_block, 0, stream, ws, x, pivot_stride, gamma, beta, save_mean, save_invstd, g, eps);
         const dim3 agrid(stream_blocks(total));
 #define LC_BN_APPLY(TWO, RELU) \
     hipLaunchKernelGGL((bn_apply_nchw_kernel<TWO, RELU, false>), agrid, dim3(kThreads), 0, stream, x, residual, y, ws.coef, g)

@@ -1,6 +1,6 @@
 """GPU parity: batchnorm_fwd / batchnorm_bwd through the C ABI against the numpy float64 oracle, both layouts,
 vector and scalar paths, shapes from ResNet-50 and AlexNet-BN down to single pixels.  Tolerance 1e-4 tensor-scaled
-(fp32 per-thread partial sums, fp64 combination; the variance comes from the sums of x and x^2)."""
+(fp32 per-thread partial sums of x - pivot and its square, fp64 combination)."""
 import numpy as np
 import pytest
 import torch
@@ -37,7 +37,7 @@ def _unlay(a, layout):
 
 def _run(shape, layout, seed, offset=0):
     n, c, h, w = shape
-    x = (synth.normal(shape, seed) * 2.0 + 0.7).astype(np.float32)          # non-zero mean: exercises E[x^2] - mean^2
+    x = (synth.normal(shape, seed) * 2.0 + 0.7).astype(np.float32)          # non-zero mean
     dy = synth.normal(shape, seed + 1)
     gamma = (1.0 + 0.5 * synth.normal((c,), seed + 2)).astype(np.float32)
     beta = synth.normal((c,), seed + 3)
@@ -170,3 +170,50 @@ def test_rebuilt_mask_is_the_mask_of_the_stored_output(layout):
     assert float((y > 0).float().mean()) > 0.2             # the mask is not trivial
     for a, b in zip(*outs):
         np.testing.assert_array_equal(a, b)
+
+
+@pytest.mark.parametrize("layout", [lc.LC_NHWC, lc.LC_NCHW], ids=["nhwc", "nchw"])
+def test_degenerate_batches(layout):
+    """One value per channel (the batch variance is 0, y = beta, dx = 0 up to rounding) and a constant tensor."""
+    for shape, const in (((1, 8, 1, 1), None), ((4, 8, 3, 3), 2.5)):
+        n, c, h, w = shape
+        x = synth.normal(shape, 8950) if const is None else np.full(shape, const, np.float32)
+        dy = synth.normal(shape, 8951)
+        gamma = (1.0 + 0.5 * synth.normal((c,), 8952)).astype(np.float32)
+        beta = synth.normal((c,), 8953)
+        xd, dyd, gd, bd = gu.dev(_lay(x, layout)), gu.dev(_lay(dy, layout)), gu.dev(gamma), gu.dev(beta)
+        y, dx = torch.empty_like(xd), torch.empty_like(xd)
+        mean, invstd, dg, db = (torch.empty(c, device=gu.DEV) for _ in range(4))
+        ws = gu.workspace(lc.batchnorm_workspace_bytes(n, c, h, w, layout))
+        lc.batchnorm_fwd(xd, gd, bd, y, mean, invstd, n, c, h, w, EPS, layout, ws)
+        lc.batchnorm_bwd(xd, dyd, gd, mean, invstd, dx, dg, db, n, c, h, w, layout, ws)
+        torch.cuda.synchronize()
+        oy, omean, oinv = obn.forward(x, gamma, beta, EPS)
+        odx, odg, odb = obn.backward(x, dy, gamma, EPS)
+        assert np.allclose(invstd.cpu().numpy(), 1.0 / np.sqrt(EPS), rtol=1e-5)          # variance exactly 0 on both sides
+        assert np.allclose(oinv, 1.0 / np.sqrt(EPS), rtol=1e-12)
+        assert np.max(np.abs(_unlay(y.cpu().numpy(), layout) - oy)) <= 1e-3               # |x - mean| <= 1 ulp, times 1/sqrt(eps) = 316
+        assert gu.scaled_err(db.cpu().numpy(), odb) <= TOL
+        # xhat is exactly 0 on both sides (the mean of equal values is exact), so dgamma = 0 and
+        # dx = gamma / sqrt(eps) * (dy - mean(dy)): values of order 1e3, compared at fp32 rounding of that scale
+        assert np.max(np.abs(dg.cpu().numpy() - odg)) <= 1e-6
+        bound = 1e-5 * float(np.max(np.abs(gamma))) / np.sqrt(EPS) * float(np.max(np.abs(dy)))
+        assert np.max(np.abs(_unlay(dx.cpu().numpy(), layout) - odx)) <= bound
+
+
+@pytest.mark.parametrize("layout", [lc.LC_NHWC, lc.LC_NCHW], ids=["nhwc", "nchw"])
+def test_mean_far_from_zero_against_the_spread(layout):
+    """Mean 10, spread 0.05: sums of x and x^2 in fp32 would lose the variance to cancellation."""
+    n, c, h, w = 8, 16, 12, 12
+    x = (10.0 + 0.05 * synth.normal((n, c, h, w), 8960)).astype(np.float32)
+    gamma = np.ones(c, np.float32)
+    beta = np.zeros(c, np.float32)
+    xd, gd, bd = gu.dev(_lay(x, layout)), gu.dev(gamma), gu.dev(beta)
+    y = torch.empty_like(xd)
+    mean, invstd = torch.empty(c, device=gu.DEV), torch.empty(c, device=gu.DEV)
+    ws = gu.workspace(lc.batchnorm_workspace_bytes(n, c, h, w, layout))
+    lc.batchnorm_fwd(xd, gd, bd, y, mean, invstd, n, c, h, w, EPS, layout, ws)
+    torch.cuda.synchronize()
+    oy, omean, oinv = obn.forward(x, gamma, beta, EPS)
+    assert np.max(np.abs(invstd.cpu().numpy() - oinv) / oinv) <= 1e-5
+    assert gu.scaled_err(_unlay(y.cpu().numpy(), layout), oy) <= TOL
