@@ -33,6 +33,12 @@ void lc_nhwc_to_nchw(const void* src, void* dst, int n, int c, int hw, int esize
 //  KRSC -> [c][R-1-r][S-1-s][k]  (the filter of the backward-data convolution)
 void lc_filter_for_bwd_data(const void* w_krsc, void* out, int k, int c, int r, int s, int esize, hipStream_t stream);
 //  pad the channel dimension (innermost) of an [rows][c] array with zeros to [rows][cpad]
+// few-channel stride-2 convolution as a stride-1 convolution over 2x2 pixel blocks (see layout.hip)
+void lc_stem_unfold(const void* x, void* u, int n, int c, int h, int w, int q, int hb, int sb, int cu, int eph, int epw, int esize,
+                    hipStream_t stream);
+void lc_stem_filter(const void* w, void* wu, int k, int r, int s, int c, int rb, int sb, int cu, int eh, int ew, int esize,
+                    hipStream_t stream);
+void lc_stem_filter_grad(const float* dwu, float* dw, int k, int r, int s, int c, int rb, int cu, int eh, int ew, hipStream_t stream);
 void lc_pad_channels(const void* src, void* dst, size_t rows, int c, int cpad, int esize, hipStream_t stream);
 
 // dw[k][j] (j < cols, c index j % cpad < c kept) = sum over splits of part[z][k][cols] in index order.

@@ -3,6 +3,8 @@
 // All of them are plain bandwidth-bound kernels; none is on the NHWC fast path except the filter
 // re-ordering (a few MB) and the split reduction.
 #include <hip/hip_runtime.h>
+
+#include <type_traits>
 #include <stdint.h>
 
 #include "internal.h"
@@ -77,6 +79,111 @@ __global__ void pad_channels_kernel(const T* __restrict__ src, T* __restrict__ d
         const int ch = (int)(o % cpad);
         const size_t row = o / cpad;
         dst[o] = ch < c ? src[row * c + ch] : T(0);
+    }
+}
+
+// ---- few-channel stride-2 convolutions as a stride-1 convolution over 2x2 pixel blocks ----
+// With hb = (h + eph) / 2 and i = (h + eph) % 2 (eph = the padding rounded up to even), output row p reads the
+// block rows p .. p + RB - 1, and likewise along the width.  The unfolded tensor U[n][hb][q][cu] holds, for output
+// column q, the SB block columns q .. q + SB - 1 side by side: cu = ((bs*2 + i)*2 + j)*C + c is the input value at
+// h = 2*hb + i - eph, w = 2*(q + bs) + j - epw (zero outside the image and for cu >= SB*4*C).  The convolution is
+// then RB x 1, stride 1, no padding, over CU channels: every k-step of the matrix kernels lies in one tap.
+struct StemGeom {
+    int C, H, W, Q, HB, SB, CU, eph, epw;
+};
+
+template <typename T>
+__global__ void stem_unfold_kernel(const T* __restrict__ x, T* __restrict__ u, size_t total, StemGeom g) {
+    for (size_t o = blockIdx.x * (size_t)blockDim.x + threadIdx.x; o < total; o += (size_t)gridDim.x * blockDim.x) {
+        const int cu = (int)(o % g.CU);
+        size_t t = o / g.CU;
+        const int q = (int)(t % g.Q); t /= g.Q;
+        const int hb = (int)(t % g.HB);
+        const size_t n = t / g.HB;
+        T v = T(0);
+        if (cu < g.SB * 4 * g.C) {
+            const int c = cu % g.C, ij = (cu / g.C) & 3, bs = cu / (4 * g.C);
+            const int h = 2 * hb + (ij >> 1) - g.eph, w = 2 * (q + bs) + (ij & 1) - g.epw;
+            if (h >= 0 && h < g.H && w >= 0 && w < g.W) v = x[((n * g.H + h) * g.W + w) * g.C + c];
+        }
+        u[o] = v;
+    }
+}
+
+// The same through LDS: a block builds one row (n, hb) of U.  It first copies the two input rows the block row is
+// made of into LDS, shifted by the left padding and surrounded by zeros; there, for each row parity i, the values
+// of output column q and block column bs are the 2*C consecutive elements from (2*q + 2*bs)*C on.  Each thread
+// then assembles 16-byte chunks of U and stores them side by side.
+template <typename T, int C>
+__global__ void __launch_bounds__(256) stem_unfold_row_kernel(const T* __restrict__ x, T* __restrict__ u, StemGeom g, int wl) {
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
+    T* rows = reinterpret_cast<T*>(smem_raw);                 // [2][wl * C]
+    constexpr int EPC = 16 / (int)sizeof(T);
+    const int hb = blockIdx.x % g.HB;
+    const size_t n = blockIdx.x / g.HB;
+    const int row_len = wl * C;
+    for (int e = threadIdx.x; e < 2 * row_len; e += 256) {
+        const int i = e >= row_len, pos = e - i * row_len;
+        const int h = 2 * hb + i - g.eph;
+        const int w = pos / C - g.epw, c = pos % C;
+        T v = T(0);
+        if (h >= 0 && h < g.H && w >= 0 && w < g.W) v = x[((n * g.H + h) * g.W + w) * C + c];
+        rows[e] = v;
+    }
+    __syncthreads();
+    // Work in pairs of elements: the runs of 2*C elements start at even positions on both sides, so a pair never
+    // straddles two runs and sits at an even position in LDS (the row length is even as well).
+    using Pair = typename std::conditional<sizeof(T) == 4, uint2, unsigned>::type;
+    constexpr int PPC = EPC / 2;                              // pairs per 16-byte chunk
+    const Pair* prow = reinterpret_cast<const Pair*>(rows);
+    const int row_pairs = row_len / 2;
+    const int chunks_per_q = g.CU / EPC, chunks = g.Q * chunks_per_q;
+    T* out = u + ((n * g.HB + hb) * (size_t)g.Q) * g.CU;
+    for (int ch = threadIdx.x; ch < chunks; ch += 256) {
+        const int q = ch / chunks_per_q, pu0 = (ch % chunks_per_q) * PPC;
+        __attribute__((aligned(16))) Pair v[PPC];
+#pragma unroll
+        for (int e = 0; e < PPC; ++e) {
+            const int pu = pu0 + e;
+            const int bs = pu / (2 * C), rem = pu % (2 * C), i = rem / C, jp = rem % C;
+            v[e] = bs < g.SB ? prow[i * row_pairs + (q + bs) * C + jp] : Pair{};
+        }
+        *reinterpret_cast<uint4*>(out + (size_t)ch * EPC) = *reinterpret_cast<const uint4*>(v);
+    }
+}
+
+// filter [K][R][S][C] -> [K][RB][CU] in the order of U (taps that the blocks add beyond the window are zero),
+// and the gradient of that filter back to [K][R][S][C] (each window tap has exactly one place in the block form)
+template <typename T>
+__global__ void stem_filter_kernel(const T* __restrict__ w, T* __restrict__ wu, int K, int R, int S, int C, int RB, int SB, int CU,
+                                   int eh, int ew) {
+    const size_t total = (size_t)K * RB * CU;
+    for (size_t o = blockIdx.x * (size_t)blockDim.x + threadIdx.x; o < total; o += (size_t)gridDim.x * blockDim.x) {
+        const int cu = (int)(o % CU);
+        const int br = (int)((o / CU) % RB);
+        const size_t k = o / ((size_t)CU * RB);
+        T v = T(0);
+        if (cu < SB * 4 * C) {
+            const int c = cu % C, ij = (cu / C) & 3, bs = cu / (4 * C);
+            const int r = 2 * br + (ij >> 1) - eh, s2 = 2 * bs + (ij & 1) - ew;
+            if (r >= 0 && r < R && s2 >= 0 && s2 < S) v = w[((k * R + r) * S + s2) * C + c];
+        }
+        wu[o] = v;
+    }
+}
+
+__global__ void stem_filter_grad_kernel(const float* __restrict__ dwu, float* __restrict__ dw, int K, int R, int S, int C, int RB, int CU,
+                                        int eh, int ew) {
+    const size_t total = (size_t)K * R * S * C;
+    for (size_t o = blockIdx.x * (size_t)blockDim.x + threadIdx.x; o < total; o += (size_t)gridDim.x * blockDim.x) {
+        const int c = (int)(o % C);
+        size_t t = o / C;
+        const int s2 = (int)(t % S); t /= S;
+        const int r = (int)(t % R);
+        const size_t k = t / R;
+        const int rr = r + eh, ss = s2 + ew;
+        const int cu = (((ss >> 1) * 2 + (rr & 1)) * 2 + (ss & 1)) * C + c;
+        dw[o] = dwu[(k * RB + (rr >> 1)) * CU + cu];
     }
 }
 
@@ -184,6 +291,61 @@ void lc_pad_channels(const void* src, void* dst, size_t rows, int c, int cpad, i
     else
         hipLaunchKernelGGL(pad_channels_kernel<uint16_t>, dim3(grid_for(total, 256)), dim3(256), 0, stream,
                            static_cast<const uint16_t*>(src), static_cast<uint16_t*>(dst), rows, c, cpad);
+}
+
+void lc_stem_unfold(const void* x, void* u, int n, int c, int h, int w, int q, int hb, int sb, int cu, int eph, int epw, int esize,
+                    hipStream_t stream) {
+    const size_t total = (size_t)n * hb * q * cu;
+    if (!total) return;
+    const StemGeom g = {c, h, w, q, hb, sb, cu, eph, epw};
+    // the LDS row holds every pixel column a block row can touch: 2 * (q + sb - 1) of them, each c wide
+    const int wl = 2 * (q + sb - 1);
+    const size_t lds = (size_t)2 * wl * c * esize;
+    const bool by_rows = lds <= 48 * 1024 && (long long)n * hb <= 0x7fffffffLL && (reinterpret_cast<uintptr_t>(u) & 15) == 0 &&
+                         (cu * esize) % 16 == 0;
+    if (by_rows) {
+        const dim3 grid((unsigned)((size_t)n * hb));
+#define LC_UNFOLD(T, CC) \
+    hipLaunchKernelGGL((stem_unfold_row_kernel<T, CC>), grid, dim3(256), lds, stream, static_cast<const T*>(x), static_cast<T*>(u), g, wl)
+        if (esize == 4) {
+            switch (c) {
+                case 1: LC_UNFOLD(float, 1); return;
+                case 2: LC_UNFOLD(float, 2); return;
+                case 3: LC_UNFOLD(float, 3); return;
+                case 4: LC_UNFOLD(float, 4); return;
+            }
+        } else {
+            switch (c) {
+                case 1: LC_UNFOLD(uint16_t, 1); return;
+                case 2: LC_UNFOLD(uint16_t, 2); return;
+                case 3: LC_UNFOLD(uint16_t, 3); return;
+                case 4: LC_UNFOLD(uint16_t, 4); return;
+            }
+        }
+#undef LC_UNFOLD
+    }
+    if (esize == 4)
+        hipLaunchKernelGGL(stem_unfold_kernel<float>, dim3(grid_for(total, 256)), dim3(256), 0, stream, static_cast<const float*>(x),
+                           static_cast<float*>(u), total, g);
+    else
+        hipLaunchKernelGGL(stem_unfold_kernel<uint16_t>, dim3(grid_for(total, 256)), dim3(256), 0, stream,
+                           static_cast<const uint16_t*>(x), static_cast<uint16_t*>(u), total, g);
+}
+
+void lc_stem_filter(const void* w, void* wu, int k, int r, int s, int c, int rb, int sb, int cu, int eh, int ew, int esize,
+                    hipStream_t stream) {
+    const size_t total = (size_t)k * rb * cu;
+    if (esize == 4)
+        hipLaunchKernelGGL(stem_filter_kernel<float>, dim3(grid_for(total, 256)), dim3(256), 0, stream, static_cast<const float*>(w),
+                           static_cast<float*>(wu), k, r, s, c, rb, sb, cu, eh, ew);
+    else
+        hipLaunchKernelGGL(stem_filter_kernel<uint16_t>, dim3(grid_for(total, 256)), dim3(256), 0, stream,
+                           static_cast<const uint16_t*>(w), static_cast<uint16_t*>(wu), k, r, s, c, rb, sb, cu, eh, ew);
+}
+
+void lc_stem_filter_grad(const float* dwu, float* dw, int k, int r, int s, int c, int rb, int cu, int eh, int ew, hipStream_t stream) {
+    const size_t total = (size_t)k * r * s * c;
+    hipLaunchKernelGGL(stem_filter_grad_kernel, dim3(grid_for(total, 256)), dim3(256), 0, stream, dwu, dw, k, r, s, c, rb, cu, eh, ew);
 }
 
 void lc_reduce_splits(const float* part, float* dw, int splits, size_t count, int cpad, int c, hipStream_t stream) {

@@ -35,6 +35,12 @@ SHAPES = {
     "fc_1x1_on_1x1": (16, 512, 1, 1, 100, 1, 1, 1, 0),
     "tiny_cnn_conv1": (16, 3, 32, 32, 16, 3, 3, 1, 1),
     "pad_wider_than_window": (1, 4, 5, 5, 4, 2, 2, 1, 2),
+    # few channels, stride 2 (bf16 runs these over 2x2 pixel blocks; here they take the few-channels path)
+    "blocks_5x5_s2_p2_c3_ragged": (2, 3, 18, 15, 24, 5, 5, 2, 2),
+    "blocks_3x3_s2_p1_c4": (3, 4, 13, 16, 40, 3, 3, 2, 1),
+    "blocks_7x7_s2_p0_c1": (2, 1, 21, 20, 16, 7, 7, 2, 0),
+    "blocks_rect_7x3_s2_c2": (2, 2, 17, 14, 12, 7, 3, 2, (3, 1)),
+    "blocks_7x7_s2_p3_odd_image": (1, 3, 29, 31, 72, 7, 7, 2, 3),
 }
 
 

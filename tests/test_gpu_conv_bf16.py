@@ -21,7 +21,7 @@ SHAPES = {
     "3x3_wide": (3, 32, 10, 12, 160, 3, 3, 1, 1),
     "1x1_plain": (3, 256, 7, 7, 512, 1, 1, 1, 0),
     "1x1_stride2_odd": (2, 64, 15, 15, 128, 1, 1, 2, 0),
-    "stem_7x7_s2": (2, 3, 30, 30, 64, 7, 7, 2, 3),            # c padded to 8; backward-data through fp32
+    "stem_7x7_s2": (2, 3, 30, 30, 64, 7, 7, 2, 3),            # NHWC: 2x2 pixel blocks; NCHW: c padded to 8; backward-data through fp32
     "5x5_p2": (2, 16, 13, 13, 32, 5, 5, 1, 2),
     "3x3_stride2": (2, 32, 17, 17, 48, 3, 3, 2, 1),           # strided window: backward-data through fp32
     "odd_channels": (2, 6, 9, 9, 10, 3, 3, 1, 1),             # k = 10: backward-data through fp32, scalar filter gradient
@@ -30,6 +30,12 @@ SHAPES = {
     "single_everything": (1, 1, 5, 5, 1, 1, 1, 1, 0),
     "fc_1x1_on_1x1": (16, 512, 1, 1, 104, 1, 1, 1, 0),
     "resnet_28_stage": (8, 128, 28, 28, 128, 3, 3, 1, 1),
+    # few channels, stride 2: NHWC runs them over 2x2 pixel blocks where that saves multiplications
+    "blocks_5x5_s2_p2_c3_ragged": (2, 3, 18, 15, 24, 5, 5, 2, 2),
+    "blocks_3x3_s2_p1_c4": (3, 4, 13, 16, 40, 3, 3, 2, 1),
+    "blocks_7x7_s2_p0_c1": (2, 1, 21, 20, 16, 7, 7, 2, 0),
+    "blocks_rect_7x3_s2_c2": (2, 2, 17, 14, 12, 7, 3, 2, (3, 1)),
+    "blocks_7x7_s2_p3_odd_image": (1, 3, 29, 31, 72, 7, 7, 2, 3),
 }
 
 
