@@ -270,7 +270,7 @@ def cpu_baseline(model: str, batch: int):
             "lars_GBps": round(LARS_BYTES_PER_PARAM * sum(sizes) / (t2 - t1) / 1e9, 2)}
 
 
-def time_call(torch, fn, iters, warmup=2):
+def time_call(torch, fn, iters, warmup=5):
     for _ in range(warmup):
         fn()
     evs = []
@@ -494,7 +494,7 @@ def main():
                     help="network whose layer shapes and parameter list make the step (default: the metric's ResNet-50)")
     ap.add_argument("--sweep", action="store_true")
     ap.add_argument("--only", type=int, nargs="*", help="sweep: shape numbers to run")
-    ap.add_argument("--iters", type=int, default=10)
+    ap.add_argument("--iters", type=int, default=20, help="timed calls per measurement in the stand-alone modes (after 5 warm-up calls; median reported)")
     ap.add_argument("--lars", choices=["resnet50", "alexnet_bn"])
     ap.add_argument("--rotate", type=int, default=1)
     ap.add_argument("--batchnorm", action="store_true", help="batch-normalisation layers alone, GB/s against HBM peak")
