@@ -217,3 +217,49 @@ def test_mean_far_from_zero_against_the_spread(layout):
     oy, omean, oinv = obn.forward(x, gamma, beta, EPS)
     assert np.max(np.abs(invstd.cpu().numpy() - oinv) / oinv) <= 1e-5
     assert gu.scaled_err(_unlay(y.cpu().numpy(), layout), oy) <= TOL
+
+
+def test_full_size_stem_output_sampled():
+    """The largest tensor of the ResNet-50 step at its real size (batch 256, 112x112, 64 channels: 205 M values, the
+    launch geometry bench.py times): statistics and channel gradients against float64 sums over the whole tensor,
+    y and dx on sampled elements."""
+    n, c, h, w = 256, 64, 112, 112
+    gen = torch.Generator(device=gu.DEV)
+    gen.manual_seed(8970)
+    x = torch.randn((n, h, w, c), generator=gen, device=gu.DEV) * 1.7 + 0.4
+    dy = torch.randn((n, h, w, c), generator=gen, device=gu.DEV)
+    gamma = (1.0 + 0.3 * synth.normal((c,), 8971)).astype(np.float32)
+    beta = (0.2 * synth.normal((c,), 8972)).astype(np.float32)
+    gd, bd = gu.dev(gamma), gu.dev(beta)
+    y, dx = torch.empty_like(x), torch.empty_like(x)
+    mean, invstd, dg, db = (torch.empty(c, device=gu.DEV) for _ in range(4))
+    ws = gu.workspace(lc.batchnorm_workspace_bytes(n, c, h, w, lc.LC_NHWC))
+    lc.batchnorm_fwd(x, gd, bd, y, mean, invstd, n, c, h, w, EPS, lc.LC_NHWC, ws)
+    lc.batchnorm_bwd(x, dy, gd, mean, invstd, dx, dg, db, n, c, h, w, lc.LC_NHWC, ws)
+    torch.cuda.synchronize()
+    # the oracle's definitions on the whole tensor, in float64, one channel block at a time to bound host memory
+    xh = x.cpu().numpy().reshape(-1, c)
+    dyh = dy.cpu().numpy().reshape(-1, c)
+    m = xh.shape[0]
+    omean = xh.mean(axis=0, dtype=np.float64)
+    ovar = np.zeros(c)
+    odb = dyh.sum(axis=0, dtype=np.float64)
+    odg = np.zeros(c)
+    for c0 in range(0, c, 8):
+        blk = xh[:, c0:c0 + 8].astype(np.float64) - omean[c0:c0 + 8]
+        ovar[c0:c0 + 8] = (blk * blk).mean(axis=0)
+        odg[c0:c0 + 8] = (dyh[:, c0:c0 + 8] * blk).sum(axis=0) / np.sqrt(ovar[c0:c0 + 8] + EPS)
+    oinv = 1.0 / np.sqrt(ovar + EPS)
+    assert gu.scaled_err(mean.cpu().numpy(), omean) <= 1e-5
+    assert np.max(np.abs(invstd.cpu().numpy() - oinv) / oinv) <= 1e-5
+    assert gu.scaled_err(db.cpu().numpy(), odb) <= TOL
+    assert gu.scaled_err(dg.cpu().numpy(), odg) <= TOL
+    rows = synth.uniform_int(4096, 8973, m)
+    xs, dys = xh[rows].astype(np.float64), dyh[rows].astype(np.float64)
+    xhat = (xs - omean) * oinv
+    want_y = gamma * xhat + beta
+    want_dx = gamma * oinv * (dys - odb / m - xhat * odg / m)
+    got_y = y.reshape(-1, c)[torch.from_numpy(rows).to(gu.DEV)].cpu().numpy()
+    got_dx = dx.reshape(-1, c)[torch.from_numpy(rows).to(gu.DEV)].cpu().numpy()
+    assert np.max(np.abs(got_y - want_y)) <= TOL * np.max(np.abs(want_y))
+    assert np.max(np.abs(got_dx - want_dx)) <= TOL * np.max(np.abs(want_dx))
