@@ -314,7 +314,9 @@ def run_sweep(args):
         # is fp32 in both modes)
         es = 2 if bf16 else 4
         xb, yb, wb = cs.n * cs.c * cs.h * cs.w * es, cs.n * cs.k * cs.p * cs.q * es, cs.weight_numel * es
-        min_bytes = {"fwd": xb + wb + yb, "bwd_data": yb + wb + xb, "bwd_weight": xb + yb + cs.weight_numel * 4}
+        # a strided 1x1 window reads only the pixels on the stride grid (backward-data still writes all of dx)
+        xread = cs.n * cs.c * cs.p * cs.q * es if cs.r == 1 and cs.s == 1 and cs.stride > 1 else xb
+        min_bytes = {"fwd": xread + wb + yb, "bwd_data": yb + wb + xb, "bwd_weight": xread + yb + cs.weight_numel * 4}
         row = {"shape": idx, "name": cs.name, "c": cs.c, "k": cs.k, "rs": cs.r, "stride": cs.stride, "hw": cs.h,
                "count": count, "gflop": round(cs.flops / 1e9, 2)}
         for p, fn in calls.items():
