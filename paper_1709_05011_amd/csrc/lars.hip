@@ -4,7 +4,7 @@
 //
 // The parameter list is cut into fixed-size chunks of one tensor each, so that 161 tensors of
 // 64 .. 2.4 M elements (ResNet-50) load the chip evenly and no launch is made per tensor.
-//   1. lars_norm_kernel      one block per chunk: sum w^2 and sum g^2 (fp32 per thread over 16
+//   1. lars_norm_kernel      two chunks per block: sum w^2 and sum g^2 of each (fp32 per thread over 16
 //                            elements, then fp64 across lanes with wavefront shuffles and across waves
 //                            through LDS) -> one fp64 partial per chunk.  The per-tensor descriptors
 //                            travel as kernel arguments (64 per launch: no host staging buffer, no
@@ -40,6 +40,7 @@ struct LarsTensor {
     int pad_;
 };
 static_assert(sizeof(LarsTensor) == 64, "descriptor layout");
+static_assert(kTablePerLaunch <= kThreads, "the norm kernel probes the table with one thread per descriptor");
 
 struct LarsGroupArgs {
     LarsTensor t[kTablePerLaunch];
@@ -76,52 +77,79 @@ __device__ __forceinline__ double2 block_sum2(double a, double b, double* lds /*
     return make_double2((lds[0] + lds[1]) + (lds[2] + lds[3]), (lds[4] + lds[5]) + (lds[6] + lds[7]));
 }
 
+constexpr int kNormChunks = 2;                              // chunks per block of the norm pass
+
+// A block takes kNormChunks neighbouring chunks.  It finds the tensor of each with one parallel probe of the
+// descriptor table (a thread per tensor; the table sits in the kernel-argument segment), issues the loads of all its
+// chunks before it adds anything up, and writes one fp64 partial pair per chunk, as if each chunk had its own block.
 __global__ void __launch_bounds__(kThreads) lars_norm_kernel(const LarsGroupArgs args, LarsWorkspace ws) {
     __shared__ double red[8];
+    __shared__ int owner[kNormChunks];
     if (blockIdx.x == 0 && threadIdx.x < args.count) ws.table[args.first + threadIdx.x] = args.t[threadIdx.x];
-    if ((int)blockIdx.x >= args.chunk_count) return;      // a group of empty tensors still gets its table written
-    const int chunk = args.chunk_begin + blockIdx.x;
-    // last tensor of the group whose first chunk is <= chunk (tensors without elements own no chunk)
-    int lo = 0, hi = args.count - 1;
-    while (lo < hi) {
-        const int mid = (lo + hi + 1) >> 1;
-        if (args.t[mid].chunk_start <= chunk) lo = mid; else hi = mid - 1;
-    }
-    while (args.t[lo].n_chunks == 0) --lo;                // skip back over empty tensors sharing the start
-    const LarsTensor t = args.t[lo];
-    if (threadIdx.x == 0) ws.chunk_tensor[chunk] = args.first + lo;
-
-    const long long off = (long long)(chunk - t.chunk_start) * kChunk;
-    const long long rem = t.numel - off;
-    const int len = rem < kChunk ? (int)rem : kChunk;
-    const float* __restrict__ w = t.w + off;
-    const float* __restrict__ g = t.g + off;
-
-    float sw = 0.f, sg = 0.f;
-    const bool vec = ((((uintptr_t)w) | ((uintptr_t)g)) & 15) == 0;
-    if (vec && len == kChunk) {
-        float4 a[kVecPerThread], b[kVecPerThread];
+    const int c0 = (int)blockIdx.x * kNormChunks;          // first chunk of the block, relative to the group
+    if (c0 >= args.chunk_count) return;                    // a group of empty tensors still gets its table written
+    const int nc = args.chunk_count - c0 < kNormChunks ? args.chunk_count - c0 : kNormChunks;
+    if ((int)threadIdx.x < args.count) {                   // kTablePerLaunch <= kThreads: one probe covers the table
+        const int start = args.t[threadIdx.x].chunk_start, n = args.t[threadIdx.x].n_chunks;
 #pragma unroll
-        for (int i = 0; i < kVecPerThread; ++i) {
-            a[i] = reinterpret_cast<const float4*>(w)[threadIdx.x + i * kThreads];
-            b[i] = reinterpret_cast<const float4*>(g)[threadIdx.x + i * kThreads];
-        }
-#pragma unroll
-        for (int i = 0; i < kVecPerThread; ++i) {
-            sw += a[i].x * a[i].x + a[i].y * a[i].y + a[i].z * a[i].z + a[i].w * a[i].w;
-            sg += b[i].x * b[i].x + b[i].y * b[i].y + b[i].z * b[i].z + b[i].w * b[i].w;
-        }
-    } else {
-        for (int i = threadIdx.x; i < len; i += kThreads) {
-            const float x = w[i], y = g[i];
-            sw += x * x;
-            sg += y * y;
+        for (int k = 0; k < kNormChunks; ++k) {
+            const int chunk = args.chunk_begin + c0 + k;
+            if (k < nc && chunk >= start && chunk < start + n) owner[k] = (int)threadIdx.x;   // exactly one tensor owns a chunk
         }
     }
-    const double2 s = block_sum2((double)sw, (double)sg, red);
-    if (threadIdx.x == 0) {
-        ws.partial[2 * chunk] = s.x;
-        ws.partial[2 * chunk + 1] = s.y;
+    __syncthreads();
+
+    float4 a[kNormChunks][kVecPerThread], b[kNormChunks][kVecPerThread];
+    const float* wp[kNormChunks];
+    const float* gp[kNormChunks];
+    int len[kNormChunks];
+    bool full[kNormChunks];
+#pragma unroll
+    for (int k = 0; k < kNormChunks; ++k) {
+        full[k] = false;
+        len[k] = 0;
+        wp[k] = gp[k] = nullptr;
+        if (k >= nc) continue;
+        const int chunk = args.chunk_begin + c0 + k;
+        const int idx = owner[k];
+        if (threadIdx.x == 0) ws.chunk_tensor[chunk] = args.first + idx;
+        const long long off = (long long)(chunk - args.t[idx].chunk_start) * kChunk;
+        const long long rem = args.t[idx].numel - off;
+        len[k] = rem < kChunk ? (int)rem : kChunk;
+        wp[k] = args.t[idx].w + off;
+        gp[k] = args.t[idx].g + off;
+        full[k] = len[k] == kChunk && ((((uintptr_t)wp[k]) | ((uintptr_t)gp[k])) & 15) == 0;
+        if (full[k]) {
+#pragma unroll
+            for (int i = 0; i < kVecPerThread; ++i) {
+                a[k][i] = reinterpret_cast<const float4*>(wp[k])[threadIdx.x + i * kThreads];
+                b[k][i] = reinterpret_cast<const float4*>(gp[k])[threadIdx.x + i * kThreads];
+            }
+        }
+    }
+#pragma unroll
+    for (int k = 0; k < kNormChunks; ++k) {
+        if (k >= nc) continue;
+        float sw = 0.f, sg = 0.f;
+        if (full[k]) {
+#pragma unroll
+            for (int i = 0; i < kVecPerThread; ++i) {
+                sw += a[k][i].x * a[k][i].x + a[k][i].y * a[k][i].y + a[k][i].z * a[k][i].z + a[k][i].w * a[k][i].w;
+                sg += b[k][i].x * b[k][i].x + b[k][i].y * b[k][i].y + b[k][i].z * b[k][i].z + b[k][i].w * b[k][i].w;
+            }
+        } else {
+            for (int i = threadIdx.x; i < len[k]; i += kThreads) {
+                const float x = wp[k][i], y = gp[k][i];
+                sw += x * x;
+                sg += y * y;
+            }
+        }
+        const double2 s = block_sum2((double)sw, (double)sg, red);
+        if (threadIdx.x == 0) {
+            const int chunk = args.chunk_begin + c0 + k;
+            ws.partial[2 * chunk] = s.x;
+            ws.partial[2 * chunk + 1] = s.y;
+        }
     }
 }
 
@@ -292,7 +320,7 @@ extern "C" lc_status lars_step_ex(int n_tensors, float* const* w, const float* c
         args.first = first;
         args.count = count;
         args.chunk_count = chunk_cursor - args.chunk_begin;
-        const int grid = args.chunk_count > 0 ? args.chunk_count : 1;
+        const int grid = args.chunk_count > 0 ? (args.chunk_count + kNormChunks - 1) / kNormChunks : 1;
         hipLaunchKernelGGL(lars_norm_kernel, dim3(grid), dim3(kThreads), 0, stream, args, ws);
     }
     hipLaunchKernelGGL(lars_finalize_kernel, dim3(n_tensors), dim3(kThreads), 0, stream, ws, lr, trust_out);
