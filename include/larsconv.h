@@ -62,7 +62,11 @@ typedef struct {
 lc_status conv2d_out_shape(const lc_conv_desc* desc, int* p, int* q);
 
 /* Scratch bytes conv2d_{fwd,bwd_data,bwd_weight} needs for `desc` (0 is possible).  Returns 0 for an
- * invalid descriptor; the call itself then reports the error. */
+ * invalid descriptor; the call itself then reports the error.  Usually a few MB (partial tiles, split sums);
+ * it holds whole tensors where the library re-lays its operands: NCHW calls (NHWC copies of all three tensors),
+ * channel counts that are not a multiple of 4 (8 for bf16; a padded copy of x), and the bf16 forward and
+ * backward-weight passes of a stride-2 layer with at most 4 channels (x unfolded over 2x2 pixel blocks, about
+ * 5.5 times its size: 0.84 GB for 512 x 224 x 224 x 3). */
 size_t conv2d_workspace_bytes(const lc_conv_desc* desc, lc_pass pass);
 
 /* Forward pass: the per-image work the paper counts in flops ("Benefits of Large-Batch Training",
