@@ -142,13 +142,15 @@ def run_train_step(args):
         if pass_ == "bwd_weight":
             return "wgrad"
         n_gemm = cs.k if pass_ == "fwd" else cs.c
-        if n_gemm <= 64:
-            return "conv_gemm_128x64"
-        # bf16: results at least 256 wide with three or more rounds of 128x256 tiles take the wide tile
-        # (not the strided 1x1 backward-data layers, whose scatter epilogue exists for 128 only)
+        k_gemm = cs.c if pass_ == "fwd" else cs.k
         rows = cs.n * cs.p * cs.q if pass_ == "fwd" or cs.stride > 1 else cs.n * cs.h * cs.w
         scatter = pass_ == "bwd_data" and cs.stride > 1
-        if bf16 and n_gemm >= 256 and cs.c >= 32 and not scatter and -(-rows // 128) * -(-n_gemm // 256) >= 3 * 2 * 256:
+        # bf16 has two more tiles, each taken with three or more rounds of such tiles (and not by the strided 1x1
+        # backward-data layers, whose scatter epilogue exists for the 128-row tiles of 64 and 128 columns only)
+        special = bf16 and k_gemm >= 32 and not scatter
+        if n_gemm <= 64:
+            return "conv_gemm_256x64" if special and -(-rows // 256) >= 3 * 3 * 256 else "conv_gemm_128x64"
+        if special and n_gemm >= 256 and -(-rows // 128) * -(-n_gemm // 256) >= 3 * 2 * 256:
             return "conv_gemm_128x256"
         return "conv_gemm_128x128"
 

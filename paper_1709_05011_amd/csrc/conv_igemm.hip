@@ -1564,8 +1564,8 @@ lc_status launch_conv_sk(GemmConv p, hipStream_t stream) {
     const bool ut = !SMALLC && uniform_tap_ok<BM, BN>(p);
     if (p.scatter) {                          // the scatter epilogue addresses the result relative to the tile's first pixel
         const long long span = ((long long)BM / ((long long)p.Po * p.Qo) + 2) * p.Ho * p.Wo * p.ldd * (p.bf16 ? 2 : 4);
-        if (span >= 0x7fff0000LL || SMALLC || BN > 128) return LC_ERR_UNSUPPORTED;   // (1x1 windows never have fewer channels than a k-step)
-        if constexpr (BN <= 128) {
+        if (span >= 0x7fff0000LL || SMALLC || BN > 128 || BM > 128) return LC_ERR_UNSUPPORTED;   // (1x1 windows never have fewer channels than a k-step)
+        if constexpr (BN <= 128 && BM <= 128) {
             if (ut)
                 hipLaunchKernelGGL((conv_gemm_pk_kernel<BM, BN, false, BF16, true, true>), dim3(grid), dim3(256), 0, stream, p);
             else
@@ -1590,22 +1590,33 @@ inline bool use_main_kernel(const GemmConv& p) {
     // (the scatter epilogue of the main kernel is not built for its few-channels variant)
     const bool few_scatter = p.scatter && p.Ci < (p.bf16 ? 32 : 16);
     // (its tile store addresses a tile's rows with 32-bit byte offsets)
-    const bool wide_rows = (long long)160 * p.ldd * (p.bf16 ? 2 : 4) >= 0x7fff0000LL;
+    const bool wide_rows = (long long)288 * p.ldd * (p.bf16 ? 2 : 4) >= 0x7fff0000LL;
     return vec && !(p.dh > 1 || p.dw > 1) && !(classic && !p.bf16) && !few_scatter && !wide_rows;
 }
 
 }  // namespace
 
+// 256 rows for narrow bf16 results (at most 64 columns) with at least three rounds of such tiles: a wave then owns
+// 128 x 32 and issues as many MFMAs per load as in the 128 x 128 tile, instead of half as many (measured: 4 to 7 %
+// on the 56x56 layers with 64 filters or channels; no gain in fp32, where it is not used).
+inline int main_tile_m(const GemmConv& p) {
+    static const bool no_tall = getenv("LARSCONV_NO_TALL_TILE") != nullptr;    // comparison runs
+    if (!p.bf16 || p.N > 64 || p.scatter || p.Ci < 32 || no_tall) return 128;
+    return (p.M + 255) / 256 >= 3LL * resident_blocks(256, 64) ? 256 : 128;
+}
+
 size_t lc_conv_gemm_workspace(const GemmConv& p) {
     if (!use_main_kernel(p)) return 0;
     long long tiles;
     int nkt;
-    const int bn = main_tile_n(p);
-    if (!(bn == 256 ? sk_geometry<128, 256>(p, &tiles, &nkt) : bn == 128 ? sk_geometry<128, 128>(p, &tiles, &nkt)
-                                                                          : sk_geometry<128, 64>(p, &tiles, &nkt)))
+    const int bn = main_tile_n(p), bm = main_tile_m(p);
+    if (!(bm == 256  ? sk_geometry<256, 64>(p, &tiles, &nkt)
+          : bn == 256 ? sk_geometry<128, 256>(p, &tiles, &nkt)
+          : bn == 128 ? sk_geometry<128, 128>(p, &tiles, &nkt)
+                      : sk_geometry<128, 64>(p, &tiles, &nkt)))
         return 0;
-    const SkPlan pl = sk_plan(tiles, nkt, resident_blocks(128, bn));
-    return (size_t)2 * pl.sk_blocks * 128 * bn * sizeof(float);
+    const SkPlan pl = sk_plan(tiles, nkt, resident_blocks(bm, bn));
+    return (size_t)2 * pl.sk_blocks * bm * bn * sizeof(float);
 }
 
 bool lc_conv_gemm_bf16_native(const GemmConv& p) { return p.bf16 && use_main_kernel(p); }
@@ -1615,6 +1626,7 @@ lc_status lc_launch_conv_gemm(const GemmConv& p, hipStream_t stream) {
         if (!use_main_kernel(p)) return LC_ERR_UNSUPPORTED;       // the caller converts to fp32 instead
         if (p.Ci < 32) return p.N > 64 ? launch_conv_sk<128, 128, true, true>(p, stream) : launch_conv_sk<128, 64, true, true>(p, stream);
         const int bn = main_tile_n(p);
+        if (main_tile_m(p) == 256) return launch_conv_sk<256, 64, false, true>(p, stream);
         if (bn == 256) return launch_conv_sk<128, 256, false, true>(p, stream);
         return bn == 128 ? launch_conv_sk<128, 128, false, true>(p, stream) : launch_conv_sk<128, 64, false, true>(p, stream);
     }
