@@ -410,6 +410,8 @@ extern "C" lc_status conv2d_bwd_data(const lc_conv_desc* d, const void* dy, cons
     g.a = dys;
     g.b = wt;
     g.d = dxdst;
+    // a strided 1x1 window touches only the stride grid of dx: clear it first, the kernels write the grid
+    if (g.scatter) lc_zero_bytes(dxdst, (size_t)d->n * d->h * d->w * d->c * pl.esize, stream);
     g.partial = pl.sk_bytes ? reinterpret_cast<float*>(at(workspace, pl.sk)) : nullptr;
     st = lc_launch_conv_gemm(g, stream);
     if (st != LC_OK) return st;

@@ -580,49 +580,90 @@ __global__ void __launch_bounds__(256, pk_blocks_per_cu(BM, BN)) conv_gemm_pk_ke
         const int m0 = tm * BM, n0 = (c_tile - tm * nbn) * BN;
         if (c_k0 == 0 && c_k1 == nkt) {
             if constexpr (SCATTER) {
-                // Row (img, po, qo) owns the cell [po*esh, +esh) x [qo*esw, +esw) of the [imgs][Ho][Wo][ldd] result: its
-                // value goes to the cell's corner, zeros to the rest.  An accumulator register holds one row in lanes
-                // 0..31 and the row four further down in lanes 32..63; both rows are wave-uniform, so their pixel
-                // offsets are computed on the scalar unit (relative to the tile's first pixel) and each half is
-                // stored by its own instruction, the other half's lanes parked past the end of the buffer.
+                // Row (img, po, qo) of the GEMM is pixel (po*esh, qo*esw) of image img in the [imgs][Ho][Wo][ldd] result;
+                // the pixels between the stride grid are zero and were cleared by the caller before the launch.  An
+                // accumulator register holds one row in lanes 0..31 and the row four further down in lanes 32..63;
+                // rows are wave-uniform, so their pixel offsets (relative to the tile's first pixel) are computed
+                // on the scalar unit and each lane picks its own.
                 const int Ho_ = p.Ho, Wo_ = p.Wo, esh_ = p.esh, esw_ = p.esw;
                 int t0 = div_by(m0, qmul, qsh);
                 const int q0 = m0 - t0 * Qo_, i0 = div_by(t0, pmul, psh), p0 = t0 - i0 * Po_;
                 const long long first_px = ((long long)i0 * Ho_ + p0 * esh_) * Wo_ + q0 * esw_;
                 const __amdgpu_buffer_rsrc_t d_rsrc = __builtin_amdgcn_make_buffer_rsrc(
                     (void*)(static_cast<E*>(p.d) + first_px * ldd_), 0, (int)kBufferBytes, (int)kBufferWords3);
-                unsigned d_voff[2][TN];
+                auto px_off = [&](int m) __attribute__((always_inline)) {        // scalar: byte offset of row m's pixel
+                    const int t = div_by(m, qmul, qsh), qo = m - t * Qo_;
+                    const int img = div_by(t, pmul, psh), po = t - img * Po_;
+                    const long long px = ((long long)img * Ho_ + po * esh_) * Wo_ + qo * esw_;
+                    return (unsigned)((int)(px - first_px) * ldd_ * ES);
+                };
+                const bool hi = lane >= 32;
+                const int odd = lane & 1;
+                const bool pairs = BF16 && ((N_ | ldd_) & 1) == 0;
+                if (m0 + BM <= M_) {
+                    unsigned colpart[TN];                       // bit 31 past N: stays set after a pixel offset is added
 #pragma unroll
-                for (int j = 0; j < TN; ++j) {
-                    const int col = n0 + wn * WTN + j * 32 + (lane & 31);
-                    d_voff[0][j] = (col < N_ && lane < 32) ? (unsigned)(col * ES) : kBufferBytes;
-                    d_voff[1][j] = (col < N_ && lane >= 32) ? (unsigned)(col * ES) : kBufferBytes;
-                }
+                    for (int j = 0; j < TN; ++j) {
+                        const int col = n0 + wn * WTN + j * 32 + (lane & 31);
+                        colpart[j] = col < N_ ? (unsigned)((pairs ? (col & ~1) : col) * ES) : kBufferBytes;
+                    }
+                    const unsigned perm_sel = odd ? 0x03020706u : 0x05040100u;
 #pragma unroll
-                for (int i = 0; i < TM; ++i)
+                    for (int i = 0; i < TM; ++i)
 #pragma unroll
-                    for (int v = 0; v < 16; ++v)
+                        for (int v = 0; v < 16; v += 2) {
+                            const int m = m0 + wm * WTM + i * 32 + 8 * (v >> 2) + (v & 3);
+                            const unsigned o0 = px_off(m), o1 = px_off(m + 1), o4 = px_off(m + 4), o5 = px_off(m + 5);
+                            const unsigned row_a = hi ? o4 : o0, row_b = hi ? o5 : o1;     // rows of registers v and v + 1
 #pragma unroll
-                        for (int hs = 0; hs < 2; ++hs) {
-                            const int m = m0 + wm * WTM + i * 32 + 8 * (v >> 2) + 4 * hs + (v & 3);
-                            if (m >= M_) continue;
-                            const int t = div_by(m, qmul, qsh), qo = m - t * Qo_;
-                            const int img = div_by(t, pmul, psh), po = t - img * Po_;
-                            for (int dy = 0; dy < esh_ && po * esh_ + dy < Ho_; ++dy)
-                                for (int dx = 0; dx < esw_ && qo * esw_ + dx < Wo_; ++dx) {
-                                    const long long px = ((long long)img * Ho_ + po * esh_ + dy) * Wo_ + qo * esw_ + dx;
-                                    const int soff = (int)(px - first_px) * ldd_ * ES;
-                                    const bool corner = (dy | dx) == 0;
-#pragma unroll
-                                    for (int j = 0; j < TN; ++j) {
-                                        const float val = corner ? acc[i][j][v] : 0.f;
-                                        if constexpr (BF16)
-                                            __builtin_amdgcn_raw_buffer_store_b16((short)lc_bf16_rne(val), d_rsrc, (int)d_voff[hs][j], soff, 0);
-                                        else
-                                            __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(val), d_rsrc, (int)d_voff[hs][j], soff, 0);
+                            for (int j = 0; j < TN; ++j) {
+                                if constexpr (BF16) {
+                                    typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+                                    typedef float f32x2 __attribute__((ext_vector_type(2)));
+                                    const f32x2 pr = {acc[i][j][v], acc[i][j][v + 1]};
+                                    const unsigned u = __builtin_bit_cast(unsigned, __builtin_convertvector(pr, bf16x2));
+                                    if (pairs) {                // as in the plain tile store: a lane stores a column pair of one row
+                                        const unsigned got = (unsigned)__builtin_amdgcn_mov_dpp((int)u, 0xB1 /* quad_perm 1,0,3,2 */, 0xF, 0xF, true);
+                                        __builtin_amdgcn_raw_buffer_store_b32(__builtin_amdgcn_perm(got, u, perm_sel), d_rsrc,
+                                                                              (int)(colpart[j] + (odd ? row_b : row_a)), 0, 0);
+                                    } else {
+                                        __builtin_amdgcn_raw_buffer_store_b16((short)(u & 0xffffu), d_rsrc, (int)(colpart[j] + row_a), 0, 0);
+                                        __builtin_amdgcn_raw_buffer_store_b16((short)(u >> 16), d_rsrc, (int)(colpart[j] + row_b), 0, 0);
                                     }
+                                } else {
+                                    __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(acc[i][j][v]), d_rsrc, (int)(colpart[j] + row_a), 0, 0);
+                                    __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(acc[i][j][v + 1]), d_rsrc, (int)(colpart[j] + row_b), 0, 0);
                                 }
+                            }
                         }
+                } else {
+                    // the last tile along M: rows are checked one by one on the scalar unit, each half of the wave is
+                    // stored by its own instruction with the other half's lanes parked past the end of the buffer
+                    unsigned d_voff[2][TN];
+#pragma unroll
+                    for (int j = 0; j < TN; ++j) {
+                        const int col = n0 + wn * WTN + j * 32 + (lane & 31);
+                        d_voff[0][j] = (col < N_ && !hi) ? (unsigned)(col * ES) : kBufferBytes;
+                        d_voff[1][j] = (col < N_ && hi) ? (unsigned)(col * ES) : kBufferBytes;
+                    }
+#pragma unroll
+                    for (int i = 0; i < TM; ++i)
+#pragma unroll
+                        for (int v = 0; v < 16; ++v)
+#pragma unroll
+                            for (int hs = 0; hs < 2; ++hs) {
+                                const int m = m0 + wm * WTM + i * 32 + 8 * (v >> 2) + 4 * hs + (v & 3);
+                                if (m >= M_) continue;
+                                const int soff = (int)px_off(m);
+#pragma unroll
+                                for (int j = 0; j < TN; ++j) {
+                                    if constexpr (BF16)
+                                        __builtin_amdgcn_raw_buffer_store_b16((short)lc_bf16_rne(acc[i][j][v]), d_rsrc, (int)d_voff[hs][j], soff, 0);
+                                    else
+                                        __builtin_amdgcn_raw_buffer_store_b32(__float_as_uint(acc[i][j][v]), d_rsrc, (int)d_voff[hs][j], soff, 0);
+                                }
+                            }
+                }
             } else {
                 // rows: scalar offset, cut off at M by the size of the buffer; columns: lane offset, bit 31 past N
                 const long long rows_left = (long long)(M_ - m0) * ldd_ * ES;

@@ -24,6 +24,7 @@ void lc_bf16_to_f32(const void* src, float* dst, size_t count, hipStream_t strea
 void lc_f32_to_bf16(const float* src, void* dst, size_t count, hipStream_t stream);
 void lc_fill_f32(float* dst, float value, size_t count, hipStream_t stream);
 void lc_fill_u32x4(void* dst, size_t bytes16, hipStream_t stream);   // zero `bytes16` * 16 bytes
+void lc_zero_bytes(void* dst, size_t bytes, hipStream_t stream);      // zero an even number of bytes at a 2-byte aligned address
 
 // NCHW <-> NHWC for activations ([n][c][hw] <-> [n][hw][c]); esize 4 (fp32) or 2 (bf16).
 void lc_nchw_to_nhwc(const void* src, void* dst, int n, int c, int hw, int esize, hipStream_t stream);
@@ -59,8 +60,8 @@ struct GemmConv {
     int ph, pw;
     int dh, dw;         // > 1: "dilated" read, valid only where h % dh == 0, then h /= dh
     int ldd;
-    // scatter epilogue (0 = off): row (img,po,qo) owns the cell [po*esh, po*esh+esh) x [qo*esw, ...) of
-    // an [imgs][Ho][Wo][ldd] tensor; the value goes to the cell's corner, zeros to the rest of it.
+    // scatter epilogue (0 = off): row (img,po,qo) is pixel (po*esh, qo*esw) of an [imgs][Ho][Wo][ldd] tensor that
+    // the caller has cleared; the pixels between the stride grid stay zero.
     int scatter, Ho, Wo, esh, esw;
     // stream-K split, filled in by the launcher: whole-tile blocks, blocks sharing the k-steps of the
     // remaining tiles, their total k-steps, and the workspace for partial tiles (2 slots per such block)

@@ -16,6 +16,10 @@ __global__ void fill_f32_kernel(float* __restrict__ dst, float value, size_t cou
         dst[i] = value;
 }
 
+__global__ void zero2_kernel(uint16_t* __restrict__ dst, size_t count) {
+    for (size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x; i < count; i += (size_t)gridDim.x * blockDim.x) dst[i] = 0;
+}
+
 __global__ void zero16_kernel(uint4* __restrict__ dst, size_t count) {
     const uint4 z = make_uint4(0, 0, 0, 0);
     for (size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x; i < count; i += (size_t)gridDim.x * blockDim.x)
@@ -260,6 +264,24 @@ void lc_fill_f32(float* dst, float value, size_t count, hipStream_t stream) {
 void lc_fill_u32x4(void* dst, size_t count16, hipStream_t stream) {
     if (!count16) return;
     hipLaunchKernelGGL(zero16_kernel, dim3(grid_for(count16, 256)), dim3(256), 0, stream, static_cast<uint4*>(dst), count16);
+}
+
+// Zero `bytes` bytes (an even number) at a 2-byte aligned address: 16-byte stores where the alignment allows.
+void lc_zero_bytes(void* dst, size_t bytes, hipStream_t stream) {
+    if (!bytes) return;
+    char* p = static_cast<char*>(dst);
+    if ((reinterpret_cast<uintptr_t>(p) & 15) == 0) {
+        const size_t body = bytes / 16;
+        lc_fill_u32x4(p, body, stream);
+        p += body * 16;
+        bytes -= body * 16;
+    } else if ((reinterpret_cast<uintptr_t>(p) & 3) == 0) {
+        const size_t body = bytes / 4;
+        lc_fill_f32(reinterpret_cast<float*>(p), 0.f, body, stream);
+        p += body * 4;
+        bytes -= body * 4;
+    }
+    if (bytes) hipLaunchKernelGGL(zero2_kernel, dim3(grid_for(bytes / 2, 256)), dim3(256), 0, stream, reinterpret_cast<uint16_t*>(p), bytes / 2);
 }
 
 void lc_nchw_to_nhwc(const void* src, void* dst, int n, int c, int hw, int esize, hipStream_t stream) {
