@@ -429,17 +429,26 @@ def run_full_step(args):
     (paper_1709_05011_amd/resnet_step.py only orders the calls).  Weights are random (He), images and labels
     synthetic.  This is a secondary mode: the headline metric times the convolution + LARS path."""
     import torch
+    from paper_1709_05011_amd.alexnet_step import AlexNetStep
     from paper_1709_05011_amd.resnet_step import ResNetStep
 
     batch = args.batch or 256
     gen = torch.Generator(device="cuda:0")
     gen.manual_seed(0x5EED0600)
-    net = ResNetStep((64, 7, 2, 3), (64, 128, 256, 512), (3, 4, 6, 3), 1000, batch, (224, 224))
+    alex = args.model == "alexnet_bn"
+    if alex:       # --model alexnet_bn: the whole AlexNet-BN step (five convolutions with batch norm, three pools, three FC layers)
+        net = AlexNetStep(((96, 11, 4, 0, True), (256, 5, 1, 2, True), (384, 3, 1, 1, False), (384, 3, 1, 1, False),
+                           (256, 3, 1, 1, True)), (4096, 4096), 1000, batch, (227, 227))
+    else:
+        net = ResNetStep((64, 7, 2, 3), (64, 128, 256, 512), (3, 4, 6, 3), 1000, batch, (224, 224))
+    side = 227 if alex else 224
+    label = f"{'AlexNet-BN' if alex else 'ResNet-50'} whole training step (all layers + LARS), batch {batch}, {side}x{side}, NHWC"
+    metric = ("alexnet_bn" if alex else "resnet50") + "_whole_step_images_per_second"
     for name, t in net.params.items():
         if name.endswith(".w"):
             fan = t[0].numel()
             t.copy_(torch.randn(t.shape, generator=gen, device="cuda:0") * (2.0 / fan) ** 0.5)
-    x = torch.randn((batch, 224, 224, 3), generator=gen, device="cuda:0")
+    x = torch.randn((batch, side, side, 3), generator=gen, device="cuda:0")
     labels = torch.randint(0, 1000, (batch,), generator=gen, device="cuda:0", dtype=torch.int32)
     lr = 0.1
     for _ in range(args.warmup):
@@ -457,10 +466,10 @@ def run_full_step(args):
             graph.replay()
         torch.cuda.synchronize()
         ms = (time.perf_counter() - t0) * 1e3 / args.steps
-        return {"metric": "resnet50_whole_step_images_per_second", "value": round(batch / (ms * 1e-3), 1), "unit": "images/s",
+        return {"metric": metric, "value": round(batch / (ms * 1e-3), 1), "unit": "images/s",
                 "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms, 3), "higher_is_better": True,
                 "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
-                "config": {"workload": f"ResNet-50 whole training step (all layers + LARS), batch {batch}, 224x224, NHWC, one HIP graph"},
+                "config": {"workload": label + ", one HIP graph"},
                 "loss": round(float(net.loss.item()), 4)}
     ev = [torch.cuda.Event(enable_timing=True) for _ in range(4)]
     phases = {"forward": 0.0, "backward": 0.0, "lars_step": 0.0}
@@ -478,10 +487,10 @@ def run_full_step(args):
             phases[k] += ev[a].elapsed_time(ev[b])
     wall = time.perf_counter() - t0
     ms = wall * 1e3 / args.steps
-    return {"metric": "resnet50_whole_step_images_per_second", "value": round(batch / (ms * 1e-3), 1), "unit": "images/s", "n_gpus": 1,
+    return {"metric": metric, "value": round(batch / (ms * 1e-3), 1), "unit": "images/s", "n_gpus": 1,
             "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms, 3), "higher_is_better": True, "scaling": "weak",
             "vs_baseline": None, "dtype": "f32", "data": "synthetic",
-            "config": {"workload": f"ResNet-50 whole training step (all layers + LARS), batch {batch}, 224x224, NHWC"},
+            "config": {"workload": label},
             "phase_ms": {k: round(v / args.steps, 3) for k, v in phases.items()}, "loss": round(float(loss.item()), 4),
             "peak_memory_GB": round(torch.cuda.max_memory_allocated() / 1e9, 2)}
 

@@ -1,0 +1,115 @@
+"""GPU parity of a WHOLE AlexNet-BN training step: the network of oracle/alexnet.py at a few channels (four
+convolutions with batch norm and ReLU, three overlapping max pools, three fully connected layers, loss), forward,
+backward and the LARS update on the device through the C ABI, against the float64 oracle.  Tolerance 1e-4
+tensor-scaled for every activation, gradient and updated weight.  ReLU and the max pools take discrete decisions; the
+test first checks that the oracle's values leave a margin that fp32 rounding cannot cross."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from oracle import alexnet as oalex
+from paper_1709_05011_amd import synth
+from paper_1709_05011_amd.alexnet_step import AlexNetStep
+
+import gpu_util as gu
+
+pytestmark = pytest.mark.gpu
+TOL = 1e-4
+CFG = oalex.Config(convs=((6, 5, 2, 0, True), (8, 3, 1, 1, True), (10, 3, 1, 1, False), (8, 3, 1, 1, True)), fcs=(24, 16), classes=10)
+HW, BATCH = (49, 49), 6
+
+
+def _problem(seed):
+    params = {}
+    for i, (name, shp) in enumerate(oalex.param_shapes(CFG, HW).items()):
+        if name.endswith(".gamma"):
+            params[name] = (1.0 + 0.2 * synth.normal(shp, seed + i)).astype(np.float32)
+        elif name.endswith(".beta") or name.endswith(".b"):
+            params[name] = (0.2 * synth.normal(shp, seed + i)).astype(np.float32)
+        else:
+            params[name] = synth.normal(shp, seed + i, std=(2.0 / int(np.prod(shp[1:]))) ** 0.5).astype(np.float32)
+    x = synth.normal((BATCH, 3) + HW, seed + 1000).astype(np.float32)
+    labels = synth.uniform_int(BATCH, seed + 2000, CFG.classes)
+    return x, labels, params
+
+
+def _to_dev(name, a):        # [k, c, r, s] -> [k, r, s, c]; vectors and [out, in] matrices as they are
+    return np.ascontiguousarray(a.transpose(0, 2, 3, 1)) if a.ndim == 4 else a
+
+
+def _from_dev(name, a, ref_shape):
+    return a.transpose(0, 3, 1, 2) if len(ref_shape) == 4 else a.reshape(ref_shape)
+
+
+def _load(net, params):
+    for k, v in params.items():
+        net.params[k].copy_(torch.from_numpy(_to_dev(k, v)).reshape(net.params[k].shape))
+
+
+def test_whole_training_step_matches_oracle():
+    x, labels, params = _problem(5100)
+    trace, grads = oalex.forward_backward(x, labels, params, CFG)
+    for key, val in trace.items():                        # premises
+        if key.endswith(".y") or (key.startswith("fc") and key.endswith(".z") and key != "fc7.z"):
+            assert np.min(np.abs(val)) > 5e-6, key
+        if key.endswith(".pool_idx"):
+            a = trace[key[:-len(".pool_idx")] + ".a"]
+            ph = (a.shape[2] - 3) // 2 + 1
+            wins = np.stack([a[:, :, r:r + 2 * ph - 1:2, s:s + 2 * ph - 1:2] for r in range(3) for s in range(3)], axis=-1)
+            top2 = np.sort(wins, axis=-1)[..., -2:]
+            contested = top2[..., 1] > 0.0
+            assert np.min((top2[..., 1] - top2[..., 0])[contested]) > 2e-5, key
+
+    net = AlexNetStep(CFG.convs, CFG.fcs, CFG.classes, BATCH, HW)
+    assert list(net.params) == list(params)
+    _load(net, params)
+    xd = gu.dev(np.ascontiguousarray(x.transpose(0, 2, 3, 1)))
+    ld = gu.dev(labels.astype(np.int32))
+    loss = net.forward(xd, ld)
+    net.backward()
+    torch.cuda.synchronize()
+    assert abs(float(loss.item()) - float(trace["loss"])) <= 1e-5 * max(1.0, abs(float(trace["loss"])))
+    assert gu.scaled_err(net.logits.cpu().numpy(), trace["logits"]) <= TOL
+    for L in net.conv_layers:
+        assert gu.scaled_err(L["a"].cpu().numpy().transpose(0, 3, 1, 2), trace[L["name"] + ".a"]) <= TOL, L["name"]
+    worst = 0.0
+    for k in params:
+        got = _from_dev(k, net.grads[k].cpu().numpy(), grads[k].shape)
+        err = gu.scaled_err(got, grads[k])
+        worst = max(worst, err)
+        assert err <= TOL, (k, err)
+    print(f"worst gradient error {worst:.2e}")
+
+    eta, momentum, wd, lr = 0.001, 0.9, 5e-4, 0.3
+    names = list(params)
+    ow = [params[k].copy() for k in names]
+    ov = [np.zeros_like(params[k]) for k in names]
+    og = [np.ascontiguousarray(grads[k], dtype=np.float32) for k in names]
+    trust, _ = oracle.lars_step(ow, og, ov, eta, momentum, wd, lr)
+    net.lars(eta, momentum, wd, lr)
+    torch.cuda.synchronize()
+    assert np.max(np.abs(net.trust.cpu().numpy().astype(np.float64) - trust) / np.abs(trust)) <= 1e-4
+    for k, w_ref in zip(names, ow):
+        assert gu.scaled_err(_from_dev(k, net.params[k].cpu().numpy(), w_ref.shape), w_ref) <= TOL, k
+
+
+def test_full_size_alexnet_bn_graph_trains():
+    """The real AlexNet-BN graph (21 tensors, 62,379,720 parameters) on 227x227 images at batch 8: every layer shape
+    goes through the library, the loss stays finite and the first step lowers it."""
+    net = AlexNetStep(((96, 11, 4, 0, True), (256, 5, 1, 2, True), (384, 3, 1, 1, False), (384, 3, 1, 1, False), (256, 3, 1, 1, True)),
+                      (4096, 4096), 1000, 8, (227, 227))
+    assert len(net.params) == 21 and sum(t.numel() for t in net.params.values()) == 62_379_720
+    gen = torch.Generator(device=gu.DEV)
+    gen.manual_seed(5200)
+    for name, t in net.params.items():
+        if name.endswith(".w"):
+            t.copy_(torch.randn(t.shape, generator=gen, device=gu.DEV) * (2.0 / t[0].numel()) ** 0.5)
+    x = torch.randn((8, 227, 227, 3), generator=gen, device=gu.DEV)
+    labels = torch.randint(0, 1000, (8,), generator=gen, device=gu.DEV, dtype=torch.int32)
+    # LARS moves every tensor by eta * ||w|| per step whatever the size of the gradient: the first step must lower the
+    # loss on its own batch; once the eight images are fitted, later steps of the same length need not
+    losses = [float(net.step(x, labels, 0.004, 0.0, 0.0, 1.0).item()) for _ in range(3)]
+    assert np.all(np.isfinite(losses)) and losses[1] < losses[0], losses
+    for name, g in net.grads.items():
+        assert bool(torch.isfinite(g).all()), name
