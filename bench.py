@@ -33,7 +33,10 @@ LARS_BYTES_PER_PARAM = 28  # norm pass reads w, g (8 B); update reads w, g, v an
 # HBM-side bytes per launch of the dominant kernel in the default workload, from the two rocprofv3 --pmc runs
 # (FETCH_SIZE x 2.000 + WRITE_SIZE x 1.000, factors from the 1 GiB copy calibration) summarised in
 # profiles/resnet50_step_fp32_b256_hbm_traffic_and_mfma.txt.  Counters cannot be read from inside this process.
-MEASURED_TRAFFIC = {("conv_gemm_128x128", 256): 417.3e6 + 184.6e6}
+# The other two workloads: the same two runs on them, tables at the end of their kernel-trace files in profiles/.
+MEASURED_TRAFFIC = {("resnet50", "f32", "conv_gemm_128x128", 256): 417.0e6 + 184.6e6,
+                    ("alexnet_bn", "f32", "conv_gemm_128x128", 256): 1134.0e6 + 97.6e6,
+                    ("resnet50", "bf16", "conv_gemm_128x128", 512): 171.1e6 + 72.6e6}
 
 
 def log(*a):
@@ -218,7 +221,7 @@ def run_train_step(args):
                    "lars": {"eta": 0.001, "momentum": 0.9, "weight_decay": weight_decay, "lr": lr}},
         "roofline": {"bound": "mfma", "kernel": dom, "achieved": round(achieved, 2), "peak": peak,
                      "unit": "TFLOP/s", "frac": round(achieved / peak, 4),
-                     "traffic": None if bf16 or args.model != "resnet50" else MEASURED_TRAFFIC.get((dom, batch)),
+                     "traffic": MEASURED_TRAFFIC.get((args.model, "bf16" if bf16 else "f32", dom, batch)),
                      "launches_per_step": dn // args.steps, "avg_launch_ms": round(dms / dn, 4),
                      "flops_per_launch": dfl / dn},
         "conv_tflops": {p: round(per_pass[p][2] / (per_pass[p][0] * 1e-3) / 1e12, 2) for p in ("fwd", "bwd_data", "bwd_weight")},
