@@ -61,7 +61,27 @@ void transpose_batched(const void* src, void* dst, int batch, int rows, int cols
     }
 }
 
-// out[c][R-1-r][S-1-s][k] = in[k][r][s][c]
+// out[c][R-1-r][S-1-s][k] = in[k][r][s][c] as one 32x32 LDS-tiled transpose per window tap (blockIdx.z): rows of
+// 32 channels are read, rows of 32 filters written, both contiguous.
+template <typename T>
+__global__ void __launch_bounds__(256) filter_bwd_data_tiled_kernel(const T* __restrict__ in, T* __restrict__ out, int K, int C, int RS) {
+    __shared__ T tile[32][33];
+    const int tap = blockIdx.z, c0 = blockIdx.x * 32, k0 = blockIdx.y * 32;
+    const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
+    const T* src = in + (size_t)tap * C;                     // in[k][tap][c]:  k * RS*C + tap*C + c
+    T* dst = out + (size_t)(RS - 1 - tap) * K;               // out[c][RS-1-tap][k]: c * RS*K + (RS-1-tap)*K + k
+    for (int i = ty; i < 32; i += 8) {
+        const int k = k0 + i, c = c0 + tx;
+        if (k < K && c < C) tile[i][tx] = src[(size_t)k * RS * C + c];
+    }
+    __syncthreads();
+    for (int i = ty; i < 32; i += 8) {
+        const int c = c0 + i, k = k0 + tx;
+        if (k < K && c < C) dst[(size_t)c * RS * K + k] = tile[tx][i];
+    }
+}
+
+// the same, one thread per element (window counts beyond the grid's z range)
 template <typename T>
 __global__ void filter_bwd_data_kernel(const T* __restrict__ in, T* __restrict__ out, int K, int C, int R, int S) {
     const size_t total = (size_t)K * C * R * S;
@@ -296,6 +316,16 @@ void lc_nhwc_to_nchw(const void* src, void* dst, int n, int c, int hw, int esize
 
 void lc_filter_for_bwd_data(const void* w_krsc, void* out, int k, int c, int r, int s, int esize, hipStream_t stream) {
     const size_t total = (size_t)k * c * r * s;
+    if ((long long)r * s <= 65535 && (k + 31) / 32 <= 65535) {
+        const dim3 grid((c + 31) / 32, (k + 31) / 32, r * s);
+        if (esize == 4)
+            hipLaunchKernelGGL(filter_bwd_data_tiled_kernel<float>, grid, dim3(256), 0, stream, static_cast<const float*>(w_krsc),
+                               static_cast<float*>(out), k, c, r * s);
+        else
+            hipLaunchKernelGGL(filter_bwd_data_tiled_kernel<uint16_t>, grid, dim3(256), 0, stream, static_cast<const uint16_t*>(w_krsc),
+                               static_cast<uint16_t*>(out), k, c, r * s);
+        return;
+    }
     if (esize == 4)
         hipLaunchKernelGGL(filter_bwd_data_kernel<float>, dim3(grid_for(total, 256)), dim3(256), 0, stream,
                            static_cast<const float*>(w_krsc), static_cast<float*>(out), k, c, r, s);
