@@ -101,7 +101,9 @@ size_t lars_workspace_bytes(int n_tensors, const int64_t* numel);
  * place, g is read only; the three must not overlap.  trust_out: DEVICE, n_tensors floats, or NULL.
  * w_lowp_out: HOST array of DEVICE pointers receiving the new weights rounded to bf16 (nearest even),
  * or NULL; single entries may be NULL.  n_tensors = 0 is a no-op.  Norms are reduced in a fixed
- * order: results are bit-identical from run to run and independent of the other tensors in the list. */
+ * order: results are bit-identical from run to run and independent of the other tensors in the list.
+ * The pointer and size arrays are read during the call and travel to the kernels as launch arguments: a HIP graph
+ * that captured the call replays with the pointers of the capture, so a changed list means capturing again. */
 lc_status lars_step(int n_tensors, float* const* w, const float* const* g, float* const* v,
                     const int64_t* numel, float eta, float momentum, float weight_decay, float lr,
                     float* trust_out, void* const* w_lowp_out,

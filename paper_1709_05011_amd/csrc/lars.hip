@@ -7,7 +7,7 @@
 //   1. lars_norm_kernel      two chunks per block: sum w^2 and sum g^2 of each (fp32 per thread over 16
 //                            elements, then fp64 across lanes with wavefront shuffles and across waves
 //                            through LDS) -> one fp64 partial per chunk.  The per-tensor descriptors
-//                            travel as kernel arguments (64 per launch: no host staging buffer, no
+//                            travel as kernel arguments (192 per launch: no host staging buffer, no
 //                            copy engine, nothing to keep alive after the call returns); the blocks
 //                            copy them into the workspace and fill the chunk -> tensor map on the way.
 //   2. lars_finalize_kernel  one block per tensor adds its partials in index order and writes
@@ -161,10 +161,28 @@ lars_finalize_kernel(LarsWorkspace ws, float lr, float* __restrict__ trust_out) 
     const float eta = ws.table[l].eta, weight_decay = ws.table[l].weight_decay;
     const bool skip = ws.table[l].skip != 0;
     double pw = 0.0, pg = 0.0;
-    for (int c = threadIdx.x; c < n_chunks; c += kThreads) {
-        pw += ws.partial[2 * (chunk_start + c)];
-        pg += ws.partial[2 * (chunk_start + c) + 1];
+    // thread-strided, four independent running sums per thread so that the loads of a long tensor overlap; the
+    // order of every addition is fixed
+    const double2* __restrict__ part = reinterpret_cast<const double2*>(ws.partial) + chunk_start;
+    double qw[4] = {0.0, 0.0, 0.0, 0.0}, qg[4] = {0.0, 0.0, 0.0, 0.0};
+    int c = threadIdx.x;
+    for (; c + 3 * kThreads < n_chunks; c += 4 * kThreads) {
+        double2 p[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) p[j] = part[c + j * kThreads];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            qw[j] += p[j].x;
+            qg[j] += p[j].y;
+        }
     }
+    for (; c < n_chunks; c += kThreads) {
+        const double2 p = part[c];
+        qw[0] += p.x;
+        qg[0] += p.y;
+    }
+    pw = (qw[0] + qw[1]) + (qw[2] + qw[3]);
+    pg = (qg[0] + qg[1]) + (qg[2] + qg[3]);
     const double2 tot = block_sum2(pw, pg, red);
     if (threadIdx.x == 0) {
         const double nw = sqrt(tot.x), ng = sqrt(tot.y);
@@ -269,31 +287,33 @@ extern "C" size_t lars_workspace_bytes(int n_tensors, const int64_t* numel) {
     return lay.total;
 }
 
-extern "C" lc_status lars_step_ex(int n_tensors, float* const* w, const float* const* g, float* const* v,
-                                  const int64_t* numel, float eta, float momentum, float weight_decay, float lr,
-                                  const float* eta_per_tensor, const float* weight_decay_per_tensor, const uint8_t* skip,
-                                  float* trust_out, void* const* w_lowp_out,
-                                  void* workspace, size_t workspace_bytes, void* hip_stream) {
+namespace {
+
+// Argument checks shared by the entry points (everything but the workspace), then the layout of the scratch memory.
+lc_status lars_check(int n_tensors, float* const* w, const float* const* g, float* const* v, const int64_t* numel,
+                     void* const* w_lowp_out, LarsLayout* lay) {
     if (n_tensors < 0) return LC_ERR_SHAPE;
-    if (n_tensors == 0) return LC_OK;
     if (!w || !g || !v || !numel) return LC_ERR_NULL;
-    LarsLayout lay;
-    if (!lars_layout(n_tensors, numel, &lay)) return LC_ERR_SHAPE;
+    if (!lars_layout(n_tensors, numel, lay)) return LC_ERR_SHAPE;
     for (int l = 0; l < n_tensors; ++l) {
         if (numel[l] == 0) continue;
         if (!w[l] || !g[l] || !v[l]) return LC_ERR_NULL;
         if ((((uintptr_t)w[l]) | ((uintptr_t)g[l]) | ((uintptr_t)v[l])) & 3) return LC_ERR_ALIGN;
         if (w_lowp_out && (((uintptr_t)w_lowp_out[l]) & 1)) return LC_ERR_ALIGN;
     }
-    if (!workspace || (((uintptr_t)workspace) & 255) || workspace_bytes < lay.total) return LC_ERR_WORKSPACE;
+    return LC_OK;
+}
 
-    char* base = static_cast<char*>(workspace);
+// The launches of one step on scratch memory at `base` (device, 256-byte aligned, lay.total bytes).
+lc_status lars_run(int n_tensors, float* const* w, const float* const* g, float* const* v, const int64_t* numel, float eta,
+                   float momentum, float weight_decay, float lr, const float* eta_per_tensor,
+                   const float* weight_decay_per_tensor, const uint8_t* skip, float* trust_out, void* const* w_lowp_out,
+                   const LarsLayout& lay, char* base, hipStream_t stream) {
     LarsWorkspace ws;
     ws.table = reinterpret_cast<LarsTensor*>(base + lay.table);
     ws.chunk_tensor = reinterpret_cast<int*>(base + lay.chunk_tensor);
     ws.partial = reinterpret_cast<double*>(base + lay.partial);
     ws.step_scale = reinterpret_cast<float*>(base + lay.step_scale);
-    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     lc_begin_call();
 
     LarsGroupArgs args;
@@ -328,6 +348,22 @@ extern "C" lc_status lars_step_ex(int n_tensors, float* const* w, const float* c
         hipLaunchKernelGGL(lars_update_kernel, dim3((unsigned)lay.n_chunks), dim3(kThreads), 0, stream, ws, (int)lay.n_chunks,
                            momentum);
     return lc_end_call();
+}
+
+}  // namespace
+
+extern "C" lc_status lars_step_ex(int n_tensors, float* const* w, const float* const* g, float* const* v,
+                                  const int64_t* numel, float eta, float momentum, float weight_decay, float lr,
+                                  const float* eta_per_tensor, const float* weight_decay_per_tensor, const uint8_t* skip,
+                                  float* trust_out, void* const* w_lowp_out,
+                                  void* workspace, size_t workspace_bytes, void* hip_stream) {
+    if (n_tensors == 0) return LC_OK;
+    LarsLayout lay;
+    const lc_status st = lars_check(n_tensors, w, g, v, numel, w_lowp_out, &lay);
+    if (st != LC_OK) return st;
+    if (!workspace || (((uintptr_t)workspace) & 255) || workspace_bytes < lay.total) return LC_ERR_WORKSPACE;
+    return lars_run(n_tensors, w, g, v, numel, eta, momentum, weight_decay, lr, eta_per_tensor, weight_decay_per_tensor, skip,
+                    trust_out, w_lowp_out, lay, static_cast<char*>(workspace), static_cast<hipStream_t>(hip_stream));
 }
 
 extern "C" lc_status lars_step(int n_tensors, float* const* w, const float* const* g, float* const* v,

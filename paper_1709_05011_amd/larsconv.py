@@ -236,20 +236,24 @@ def lars_step(args: LarsArgs, eta: float, momentum: float, weight_decay: float, 
                            _ptr(trust_out), args.w_lowp, _ptr(workspace), nb, _stream(stream)), "lars_step")
 
 
-def lars_step_ex(args: LarsArgs, eta: float, momentum: float, weight_decay: float, lr: float, eta_per_tensor=None,
-                 weight_decay_per_tensor=None, skip=None, trust_out=None, workspace=None, stream=None,
-                 workspace_bytes: Optional[int] = None) -> None:
-    """lars_step with per-tensor coefficients (sequences of floats or None) and a skip list (sequence of 0/1 or None)."""
+def _per_tensor_arrays(args: "LarsArgs", eta_per_tensor, weight_decay_per_tensor, skip):
     def farr(a):
         if a is None:
             return None
         if len(a) != args.n:
             raise ValueError("per-tensor array of the wrong length")
         return (ctypes.c_float * max(args.n, 1))(*[float(x) for x in a])
-    e, b = farr(eta_per_tensor), farr(weight_decay_per_tensor)
     if skip is not None and len(skip) != args.n:
         raise ValueError("skip list of the wrong length")
     sk = None if skip is None else (ctypes.c_uint8 * max(args.n, 1))(*[1 if x else 0 for x in skip])
+    return farr(eta_per_tensor), farr(weight_decay_per_tensor), sk
+
+
+def lars_step_ex(args: LarsArgs, eta: float, momentum: float, weight_decay: float, lr: float, eta_per_tensor=None,
+                 weight_decay_per_tensor=None, skip=None, trust_out=None, workspace=None, stream=None,
+                 workspace_bytes: Optional[int] = None) -> None:
+    """lars_step with per-tensor coefficients (sequences of floats or None) and a skip list (sequence of 0/1 or None)."""
+    e, b, sk = _per_tensor_arrays(args, eta_per_tensor, weight_decay_per_tensor, skip)
     nb = _nbytes(workspace) if workspace_bytes is None else workspace_bytes
     _check(lib().lars_step_ex(args.n, args.w, args.g, args.v, args.numel_arr, eta, momentum, weight_decay, lr, e, b, sk,
                               _ptr(trust_out), args.w_lowp, _ptr(workspace), nb, _stream(stream)), "lars_step_ex")
