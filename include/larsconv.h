@@ -122,6 +122,22 @@ lc_status lars_step_ex(int n_tensors, float* const* w, const float* const* g, fl
                        float* trust_out, void* const* w_lowp_out,
                        void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/* lars_step_ex for callers that cannot allocate device memory or have none to pass: code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc.  Same arguments, results and errors as lars_step_ex without
+ * the workspace: the scratch memory is a fixed array of LARS_STATIC_SCRATCH_BYTES inside the library's device image
+ * (each GPU the library runs on holds one copy until the process ends), and the call allocates and frees nothing.
+ * A list whose lars_workspace_bytes() exceeds LARS_STATIC_SCRATCH_BYTES is refused with LC_ERR_WORKSPACE before
+ * anything is launched (2 MiB holds about 420 M parameters; ResNet-50's list needs 0.14 MB, AlexNet-BN's 0.31 MB).
+ * Every call on a GPU uses that GPU's one array: calls on the same GPU must be ordered (one stream, or events
+ * between streams); calls that overlap on one GPU race on the scratch memory and give undefined results.  The
+ * array keeps the last call's contents; nothing in it needs clearing, every value read is written first by the
+ * same call.  The device is the calling thread's current device. */
+#define LARS_STATIC_SCRATCH_BYTES ((size_t)2 << 20)
+lc_status lars_step_ex_static(int n_tensors, float* const* w, const float* const* g, float* const* v,
+                              const int64_t* numel, float eta, float momentum, float weight_decay, float lr,
+                              const float* eta_per_tensor, const float* weight_decay_per_tensor, const uint8_t* skip,
+                              float* trust_out, void* const* w_lowp_out, void* hip_stream);
+
 /* Warm-up followed by the poly policy (HOST arithmetic).  The paper's warm-up scheme starts from a small rate
  * and raises it to the large one over the first few epochs ("Difficulty of Large-Batch Training"; 5 epochs
  * for ResNet-50); the ramp is taken to be linear: start_lr + (base_lr - start_lr) * iter / warmup_iters for

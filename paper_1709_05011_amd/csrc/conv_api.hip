@@ -296,6 +296,12 @@ lc_status lc_end_call() {
     return LC_ERR_LAUNCH;
 }
 
+lc_status lc_fail_call(hipError_t e, const char* what) {
+    snprintf(g_detail, sizeof(g_detail), "%s: %s: %s", what, hipGetErrorName(e), hipGetErrorString(e));
+    (void)hipGetLastError();
+    return LC_ERR_LAUNCH;
+}
+
 extern "C" const char* lc_last_error_detail(void) { return g_detail; }
 
 extern "C" lc_status conv2d_out_shape(const lc_conv_desc* desc, int* p, int* q) {

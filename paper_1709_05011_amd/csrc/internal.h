@@ -11,6 +11,7 @@
 // runtime left on this thread, so that lc_end_call() reports only what this library's launches caused.
 void lc_begin_call();
 lc_status lc_end_call();     // LC_OK, or LC_ERR_LAUNCH with the detail text recorded
+lc_status lc_fail_call(hipError_t e, const char* what);   // records "what: error" as the detail text, returns LC_ERR_LAUNCH
 
 // fp32 -> bf16, round to nearest even (NaN stays NaN)
 __device__ __forceinline__ uint16_t lc_bf16_rne(float x) {

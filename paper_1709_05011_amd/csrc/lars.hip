@@ -17,6 +17,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <mutex>
+
 #include "internal.h"
 
 namespace {
@@ -364,6 +366,56 @@ extern "C" lc_status lars_step_ex(int n_tensors, float* const* w, const float* c
     if (!workspace || (((uintptr_t)workspace) & 255) || workspace_bytes < lay.total) return LC_ERR_WORKSPACE;
     return lars_run(n_tensors, w, g, v, numel, eta, momentum, weight_decay, lr, eta_per_tensor, weight_decay_per_tensor, skip,
                     trust_out, w_lowp_out, lay, static_cast<char*>(workspace), static_cast<hipStream_t>(hip_stream));
+}
+
+// ---- the same step on scratch memory that the library holds itself, for callers that cannot allocate ----
+// A fixed array in device memory; every GPU the library runs on holds its own copy at its own address until the
+// process ends.  Host code never uses the array's name as an address: the address on the current device is asked
+// for once per device and kept.
+constexpr size_t kStaticScratchBytes = LARS_STATIC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+namespace {
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+char* g_scratch_ptr[kMaxDevices];       // device address of `scratch` on each device, null until asked for
+
+lc_status scratch_of_current_device(char** out) {
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return lc_fail_call(e, "hipGetDevice");
+    if (dev < 0 || dev >= kMaxDevices) return LC_ERR_UNSUPPORTED;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void* p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return lc_fail_call(e, "hipGetSymbolAddress");
+        if (!p || (((uintptr_t)p) & 255)) return lc_fail_call(hipErrorInvalidSymbol, "hipGetSymbolAddress (null or misaligned)");
+        g_scratch_ptr[dev] = static_cast<char*>(p);
+    }
+    *out = g_scratch_ptr[dev];
+    return LC_OK;
+}
+
+}  // namespace
+
+extern "C" lc_status lars_step_ex_static(int n_tensors, float* const* w, const float* const* g, float* const* v,
+                                         const int64_t* numel, float eta, float momentum, float weight_decay, float lr,
+                                         const float* eta_per_tensor, const float* weight_decay_per_tensor,
+                                         const uint8_t* skip, float* trust_out, void* const* w_lowp_out, void* hip_stream) {
+    if (n_tensors == 0) return LC_OK;
+    LarsLayout lay;
+    const lc_status st = lars_check(n_tensors, w, g, v, numel, w_lowp_out, &lay);
+    if (st != LC_OK) return st;
+    if (lay.total > kStaticScratchBytes) return LC_ERR_WORKSPACE;     // the list needs more than the fixed array holds
+    char* base = nullptr;
+    const lc_status sp = scratch_of_current_device(&base);
+    if (sp != LC_OK) return sp;
+    // Nothing in the array has to start at zero: the norm pass writes the table, the chunk map and every partial
+    // sum of this list before the later kernels read them, and the finalize kernel writes every step scale.
+    return lars_run(n_tensors, w, g, v, numel, eta, momentum, weight_decay, lr, eta_per_tensor, weight_decay_per_tensor, skip,
+                    trust_out, w_lowp_out, lay, base, static_cast<hipStream_t>(hip_stream));
 }
 
 extern "C" lc_status lars_step(int n_tensors, float* const* w, const float* const* g, float* const* v,

@@ -20,7 +20,7 @@ LC_NCHW, LC_NHWC = 0, 1
 LC_PASS_FWD, LC_PASS_BWD_DATA, LC_PASS_BWD_WEIGHT = 0, 1, 2
 
 EXPORTS = ["conv2d_out_shape", "conv2d_workspace_bytes", "conv2d_fwd", "conv2d_bwd_data", "conv2d_bwd_weight",
-           "lars_workspace_bytes", "lars_step", "lars_step_ex", "lars_poly_lr", "lars_warmup_poly_lr",
+           "lars_workspace_bytes", "lars_step", "lars_step_ex", "lars_step_ex_static", "lars_poly_lr", "lars_warmup_poly_lr",
            "relu_fwd", "relu_bwd", "maxpool2x2_fwd", "maxpool2x2_bwd", "global_avgpool_fwd", "global_avgpool_bwd",
            "bias_add", "bias_grad", "softmax_xent", "maxpool_fwd", "maxpool_bwd", "relu_add_bwd",
            "batchnorm_workspace_bytes", "batchnorm_fwd", "batchnorm_bwd", "batchnorm_fwd_ex", "batchnorm_bwd_ex",
@@ -93,6 +93,9 @@ def lib() -> ctypes.CDLL:
         L.lars_step_ex.restype = i32
         L.lars_step_ex.argtypes = [i32, vp, vp, vp, vp, ctypes.c_float, ctypes.c_float, ctypes.c_float, ctypes.c_float,
                                    vp, vp, vp, vp, vp, vp, sz, vp]
+        L.lars_step_ex_static.restype = i32
+        L.lars_step_ex_static.argtypes = [i32, vp, vp, vp, vp, ctypes.c_float, ctypes.c_float, ctypes.c_float, ctypes.c_float,
+                                          vp, vp, vp, vp, vp, vp]
         L.lars_poly_lr.restype = ctypes.c_float
         L.lars_poly_lr.argtypes = [ctypes.c_float, ctypes.c_int64, ctypes.c_int64, ctypes.c_float]
         L.lars_warmup_poly_lr.restype = ctypes.c_float
@@ -257,6 +260,17 @@ def lars_step_ex(args: LarsArgs, eta: float, momentum: float, weight_decay: floa
     nb = _nbytes(workspace) if workspace_bytes is None else workspace_bytes
     _check(lib().lars_step_ex(args.n, args.w, args.g, args.v, args.numel_arr, eta, momentum, weight_decay, lr, e, b, sk,
                               _ptr(trust_out), args.w_lowp, _ptr(workspace), nb, _stream(stream)), "lars_step_ex")
+
+
+LARS_STATIC_SCRATCH_BYTES = 2 << 20
+
+
+def lars_step_ex_static(args: LarsArgs, eta: float, momentum: float, weight_decay: float, lr: float, eta_per_tensor=None,
+                        weight_decay_per_tensor=None, skip=None, trust_out=None, stream=None) -> None:
+    """lars_step_ex on the library's own fixed scratch array (no workspace argument, nothing allocated)."""
+    e, b, sk = _per_tensor_arrays(args, eta_per_tensor, weight_decay_per_tensor, skip)
+    _check(lib().lars_step_ex_static(args.n, args.w, args.g, args.v, args.numel_arr, eta, momentum, weight_decay, lr, e, b, sk,
+                                     _ptr(trust_out), args.w_lowp, _stream(stream)), "lars_step_ex_static")
 
 
 def lars_poly_lr(base_lr: float, it: int, max_iter: int, power: float = 2.0) -> float:

@@ -138,6 +138,25 @@ def test_lars_step_ex_rejects_bad_arguments_before_launch():
     assert call(arr, ctypes.c_void_p(FAKE), need - 1) == lc.LC_ERR_WORKSPACE
 
 
+def test_lars_step_ex_static_rejects_bad_arguments_before_launch():
+    # the entry point on the library's own fixed scratch array: same checks, and a list beyond the array is refused
+    L = lc.lib()
+    arr = (ctypes.c_void_p * 2)(FAKE, FAKE)
+    odd = (ctypes.c_void_p * 2)(FAKE + 2, FAKE)
+    numel = (ctypes.c_int64 * 2)(100, 5000)
+    call = lambda n, w, g, nm: L.lars_step_ex_static(n, w, g, arr, nm, 0.001, 0.9, 5e-5, 1.0, None, None, None, None, None, None)
+    assert call(2, None, arr, numel) == lc.LC_ERR_NULL
+    assert call(2, arr, arr, None) == lc.LC_ERR_NULL
+    assert call(-1, arr, arr, numel) == lc.LC_ERR_SHAPE
+    assert call(2, odd, arr, numel) == lc.LC_ERR_ALIGN
+    assert call(0, None, None, None) == lc.LC_OK
+    big = (ctypes.c_int64 * 2)(100, 600_000_000)
+    assert lc.lars_workspace_bytes([100, 600_000_000]) > lc.LARS_STATIC_SCRATCH_BYTES
+    assert call(2, arr, arr, big) == lc.LC_ERR_WORKSPACE
+    text = open(os.path.join(ROOT, "include", "larsconv.h")).read()
+    assert re.search(r"#define\s+LARS_STATIC_SCRATCH_BYTES\s+\(\(size_t\)2\s*<<\s*20\)", text) and lc.LARS_STATIC_SCRATCH_BYTES == 2 << 20
+
+
 def test_glue_layers_reject_bad_arguments_before_launch():
     L = lc.lib()
     P = ctypes.c_void_p(FAKE)
