@@ -6,7 +6,9 @@ classifier, backward-data and backward-weight of every layer (no backward-data f
 layer: there is no gradient with respect to the image), then one lars_step over the 161 parameter
 tensors, fp32, batch 256, NHWC, synthetic N(0,1) inputs resident in HBM.  Prints ONE JSON line:
 images/s, plus "roofline" for the dominant kernel and "cpu_baseline" (the CPU oracle timed on the
-host cores on a bounded sample).
+host cores on a bounded sample).  After the timed region the same line also gets lars_step on rotating
+parameter sets ("lars.cold"), the whole network step with its glue layers ("whole_step") and the bf16 form
+of the step at batch 512 ("bf16_step"), each a short run of its own (--no-extras skips them).
 
     python bench.py [--steps K] [--warmup W]          # the headline line
     python bench.py --dtype bf16                      # the same step at batch 512 with bf16 operands
@@ -30,13 +32,42 @@ PEAK_MFMA_F32 = 157.3      # TFLOP/s, MI355X dense fp32 matrix
 PEAK_MFMA_BF16 = 2500.0    # TFLOP/s, MI355X dense bf16 matrix
 PEAK_HBM = 8000.0          # GB/s
 LARS_BYTES_PER_PARAM = 28  # norm pass reads w, g (8 B); update reads w, g, v and writes w, v (20 B)
-# HBM-side bytes per launch of the dominant kernel in the default workload, from the two rocprofv3 --pmc runs
-# (FETCH_SIZE x 2.000 + WRITE_SIZE x 1.000, factors from the 1 GiB copy calibration) summarised in
-# profiles/resnet50_step_fp32_b256_hbm_traffic_and_mfma.txt.  Counters cannot be read from inside this process.
-# The other two workloads: the same two runs on them, tables at the end of their kernel-trace files in profiles/.
-MEASURED_TRAFFIC = {("resnet50", "f32", "conv_gemm_128x128", 256): 417.0e6 + 184.6e6,
-                    ("alexnet_bn", "f32", "conv_gemm_128x128", 256): 1134.0e6 + 97.6e6,
-                    ("resnet50", "bf16", "conv_gemm_128x128", 512): 171.1e6 + 72.6e6}
+# HBM-side bytes per launch of the dominant kernel: counters cannot be read from inside this process, so the figure is
+# parsed from the tracked rocprofv3 summaries (two --pmc runs, FETCH_SIZE then WRITE_SIZE, scaled by what the same
+# counters read for a 1 GiB copy; the commands are in the files).  None when the file or the kernel's row is missing.
+TRAFFIC_PROFILES = {("resnet50", "f32"): "resnet50_step_fp32_b256_hbm_traffic_and_mfma.txt",
+                    ("alexnet_bn", "f32"): "alexnet_bn_step_fp32_b256_kernel_trace.txt",
+                    ("resnet50", "bf16"): "resnet50_step_bf16_b512_kernel_trace.txt"}
+TRAFFIC_BATCH = {"f32": 256, "bf16": 512}
+
+
+def kernel_instance_name(label: str, bf16: bool) -> str:
+    """Name rocprofv3 prints for the main-kernel instance behind one of this file's labels (conv_gemm_128x128 ...)."""
+    bm, bn = label.rsplit("_", 1)[1].split("x")
+    return f"conv_gemm_pk_kernel<{bm}, {bn}, false, {'true' if bf16 else 'false'}, true, false>"
+
+
+def profile_traffic(model: str, dtype: str, label: str, batch: int):
+    """Read + written bytes per launch of kernel `label` from the FETCH_SIZE / WRITE_SIZE tables of the tracked summary."""
+    name = TRAFFIC_PROFILES.get((model, dtype))
+    if name is None or batch != TRAFFIC_BATCH[dtype] or not label.startswith("conv_gemm_"):
+        return None
+    path = os.path.join(ROOT, "profiles", name)
+    if not os.path.exists(path):
+        return None
+    want = kernel_instance_name(label, dtype == "bf16")
+    section, found = None, {}
+    for line in open(path):
+        head = line.strip()
+        if head.startswith("FETCH_SIZE"):
+            section = "FETCH_SIZE"
+        elif head.startswith("WRITE_SIZE"):
+            section = "WRITE_SIZE"
+        elif section and line.startswith(want) and section not in found:
+            found[section] = float(line.split()[-1]) * 1e6          # the scaled_MB/launch column
+    if len(found) != 2:
+        return None
+    return found["FETCH_SIZE"] + found["WRITE_SIZE"]
 
 
 def log(*a):
@@ -74,6 +105,7 @@ class Timer:
     def __init__(self, torch):
         self.torch = torch
         self.spans = []          # (key, start, stop)
+        self.step_starts = []    # index into spans of the first call of every timed step
 
     def span(self, key):
         t = self.torch
@@ -158,6 +190,8 @@ def run_train_step(args):
         return "conv_gemm_128x128"
 
     def step(timer=None):
+        if timer is not None:
+            timer.step_starts.append(len(timer.spans))
         for l in layers:
             timed(timer, ("fwd", gemm_kernel_of(l, "fwd"), l.cs.flops),
                   lambda l=l: lc.conv2d_fwd(l.desc, l.x, l.w, l.y, ws))
@@ -180,14 +214,28 @@ def run_train_step(args):
     wall = time.perf_counter() - t0
     ms_per_step = wall * 1e3 / args.steps
 
-    # aggregate the per-call spans
+    # aggregate the per-call spans: totals per pass and per kernel instance, and per-pass time of every step
     per_pass, per_kernel = {}, {}
-    for (pass_, kern, flops), a, b in timer.spans:
-        ms = a.elapsed_time(b)
-        p = per_pass.setdefault(pass_, [0.0, 0, 0])
-        p[0] += ms; p[1] += 1; p[2] += flops
-        q = per_kernel.setdefault(kern, [0.0, 0, 0])
-        q[0] += ms; q[1] += 1; q[2] += flops
+    bounds = timer.step_starts + [len(timer.spans)]
+    per_step = []                                       # one {pass: ms} per timed step
+    for si in range(len(bounds) - 1):
+        acc = {}
+        for (pass_, kern, flops), a, b in timer.spans[bounds[si]:bounds[si + 1]]:
+            ms = a.elapsed_time(b)
+            acc[pass_] = acc.get(pass_, 0.0) + ms
+            p = per_pass.setdefault(pass_, [0.0, 0, 0])
+            p[0] += ms; p[1] += 1; p[2] += flops
+            q = per_kernel.setdefault(kern, [0.0, 0, 0])
+            q[0] += ms; q[1] += 1; q[2] += flops
+        per_step.append(acc)
+
+    def med_min(vals):
+        v = sorted(vals)
+        return round(v[len(v) // 2], 4), round(v[0], 4)
+    pass_ms = {}
+    for pass_ in per_pass:
+        m, lo = med_min([st[pass_] for st in per_step])
+        pass_ms[pass_] = {"median": m, "min": lo}
     conv_ms = sum(per_pass[p][0] for p in ("fwd", "bwd_data", "bwd_weight"))
     conv_flops = sum(per_pass[p][2] for p in ("fwd", "bwd_data", "bwd_weight"))
     lars_ms = per_pass["lars"][0] / per_pass["lars"][1]
@@ -221,14 +269,19 @@ def run_train_step(args):
                    "lars": {"eta": 0.001, "momentum": 0.9, "weight_decay": weight_decay, "lr": lr}},
         "roofline": {"bound": "mfma", "kernel": dom, "achieved": round(achieved, 2), "peak": peak,
                      "unit": "TFLOP/s", "frac": round(achieved / peak, 4),
-                     "traffic": MEASURED_TRAFFIC.get((args.model, "bf16" if bf16 else "f32", dom, batch)),
+                     "traffic": profile_traffic(args.model, "bf16" if bf16 else "f32", dom, batch),
                      "launches_per_step": dn // args.steps, "avg_launch_ms": round(dms / dn, 4),
                      "flops_per_launch": dfl / dn},
         "conv_tflops": {p: round(per_pass[p][2] / (per_pass[p][0] * 1e-3) / 1e12, 2) for p in ("fwd", "bwd_data", "bwd_weight")},
         "conv_tflops_all": round(conv_flops / (conv_ms * 1e-3) / 1e12, 2),
         "conv_frac_of_mfma_peak": round(conv_flops / (conv_ms * 1e-3) / 1e12 / peak, 4),
-        "lars": {"ms": round(lars_ms, 4), "GBps": round(lars_gbps, 1), "frac_of_hbm_peak": round(lars_gbps / PEAK_HBM, 4),
+        # lars_step inside the step: its gradients were written a moment ago and part of the 307 MB working set is still
+        # in the 256 MB Infinity Cache, so this is an effective rate, not achieved HBM bandwidth ("cold" below is)
+        "lars": {"in_step": {"ms": round(lars_ms, 4), "GBps_effective": round(lars_gbps, 1),
+                             "frac_of_hbm_peak_effective": round(lars_gbps / PEAK_HBM, 4),
+                             "note": "cache-assisted: g was just written by backward-weight"},
                  "bytes_per_param": lars_bpp},
+        "pass_ms_per_step": pass_ms,
         "kernel_ms_per_step": {k: round(v[0] / args.steps, 3) for k, v in per_kernel.items()},
     }
     if not args.no_cpu:
@@ -351,15 +404,16 @@ def run_sweep(args):
             "ms_at_roof": round(roof_ms, 3), "frac_of_roof": round(roof_ms / all_ms, 4), "rows": rows}
 
 
-def run_lars(args):
+def measure_lars(which: str, n_sets: int, iters: int):
+    """lars_step alone over the model's parameter list; n_sets > 1 rotates over that many parameter sets so that no call
+    finds its data in the caches (each call then also pays the write-back of what the previous call left dirty)."""
     import torch
     from paper_1709_05011_amd import larsconv as lc
     from paper_1709_05011_amd import synth
 
-    sizes = synth.resnet50_param_numels() if args.lars == "resnet50" else synth.alexnet_bn_param_numels()
+    sizes = synth.resnet50_param_numels() if which == "resnet50" else synth.alexnet_bn_param_numels()
     gen = torch.Generator(device="cuda:0")
     gen.manual_seed(0x5EED0400)
-    n_sets = args.rotate          # rotate over several parameter sets so that no call finds its data in cache
     sets = []
     for _ in range(n_sets):
         w = [torch.randn(n, generator=gen, device="cuda:0") for n in sizes]
@@ -375,11 +429,15 @@ def run_lars(args):
         state["i"] += 1
         lc.lars_step(a, 0.001, 0.9, 5e-5, 0.5, trust, lws)
 
-    med, mn = time_call(torch, call, args.iters, warmup=max(2, n_sets))
+    med, mn = time_call(torch, call, iters, warmup=max(2, n_sets))
     nbytes = LARS_BYTES_PER_PARAM * sum(sizes)
-    return {"lars": args.lars, "tensors": len(sizes), "params": sum(sizes), "rotating_sets": n_sets,
+    return {"lars": which, "tensors": len(sizes), "params": sum(sizes), "rotating_sets": n_sets,
             "ms_median": round(med, 4), "ms_min": round(mn, 4), "GBps_median": round(nbytes / (med * 1e-3) / 1e9, 1),
             "frac_of_hbm_peak": round(nbytes / (med * 1e-3) / 1e9 / PEAK_HBM, 4), "bytes_per_param": LARS_BYTES_PER_PARAM}
+
+
+def run_lars(args):
+    return measure_lars(args.lars, args.rotate, args.iters)
 
 
 def run_batchnorm(args):
@@ -513,6 +571,48 @@ def run_copy_calibration(args):
             "launches": args.iters, "kernel": "the elementwise copy kernel torch launches for Tensor.copy_"}
 
 
+def add_secondary_measurements(res, args):
+    """Beside the headline (convolutions + LARS of the step's layers): lars_step on rotating parameter sets (cold), and --
+    for the default workload -- the whole network step with its glue layers and the bf16 form of the step, each a short
+    run of its own after the timed region, so that one recorded line carries them all."""
+    import copy
+    import gc
+
+    import torch
+
+    def release():
+        gc.collect()
+        torch.cuda.empty_cache()
+
+    release()
+    cold = measure_lars(args.model, 4, 20)
+    res["lars"]["cold"] = {"ms_median": cold["ms_median"], "ms_min": cold["ms_min"], "GBps": cold["GBps_median"],
+                           "frac_of_hbm_peak": cold["frac_of_hbm_peak"], "rotating_sets": 4,
+                           "note": "stand-alone on 4 rotating parameter sets: nothing in cache, and the previous call's "
+                                   "dirty lines are written back while this one reads"}
+    release()
+    if args.dtype != "f32" or args.batch:
+        return
+    a = copy.copy(args)
+    a.steps, a.warmup, a.graph, a.full_step = 5, 2, False, True
+    full = run_full_step(a)
+    res["whole_step"] = {"ms_per_step": full["ms_per_step"], "images_per_s": full["value"], "phase_ms": full["phase_ms"],
+                         "steps": a.steps, "workload": full["config"]["workload"],
+                         "note": "every layer of the network (batch norm, ReLU, pools, residual adds, classifier, loss) "
+                                 "besides the convolutions and lars_step of the headline"}
+    release()
+    if args.model != "resnet50":
+        return
+    b = copy.copy(args)
+    b.steps, b.warmup, b.dtype, b.no_cpu = 5, 2, "bf16", True
+    bf = run_train_step(b)
+    res["bf16_step"] = {"ms_per_step": bf["ms_per_step"], "images_per_s": bf["value"], "batch": 512, "steps": b.steps,
+                        "conv_tflops": bf["conv_tflops"], "conv_tflops_all": bf["conv_tflops_all"],
+                        "conv_frac_of_mfma_peak": bf["conv_frac_of_mfma_peak"], "roofline": bf["roofline"],
+                        "lars_in_step": bf["lars"]["in_step"], "workload": bf["config"]["workload"]}
+    release()
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -522,6 +622,8 @@ def main():
     ap.add_argument("--dtype", choices=["f32", "bf16"], default="f32",
                     help="bf16: BASELINE configs[4] (bf16 activations/weights, fp32 sums, fp32 master weights; batch 512)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
+    ap.add_argument("--no-extras", action="store_true",
+                    help="headline only: skip the cold lars_step, whole-step and bf16 legs that follow the timed region")
     ap.add_argument("--cpu-batch", type=int, default=4)
     ap.add_argument("--model", choices=["resnet50", "alexnet_bn"], default="resnet50",
                     help="network whose layer shapes and parameter list make the step (default: the metric's ResNet-50)")
@@ -550,6 +652,8 @@ def main():
         res = run_full_step(args)
     else:
         res = run_train_step(args)
+        if not args.no_extras:
+            add_secondary_measurements(res, args)
     print(json.dumps(res), flush=True)
 
 

@@ -1504,17 +1504,33 @@ SkPlan sk_plan(long long tiles, int nkt, int resident_blocks) {
 // Blocks of the main kernel that fit on the chip at once (the kernel's launch bounds hold it to this).
 inline int resident_blocks(int bm, int bn) { return pk_blocks_per_cu(bm, bn) * device_cu_count(); }
 
-// Tile of the main kernel for a problem: 64 columns for narrow results, otherwise 128 -- or 256 for bf16 results
-// at least that wide when there are at least three rounds of 128x256 tiles.  The wide tile issues a quarter
-// fewer LDS and load instructions per MFMA; that pays in the bf16 loop, which is bound by LDS bandwidth (measured:
-// 5 to 20 % on such layers), not in fp32 (slightly slower everywhere), and with fewer rounds the coarser tiles
-// leave compute units idle at the end.  The few-channels and scatter variants are built for 64 and 128 only.
-inline int main_tile_n(const GemmConv& p) {
+// Tile of the main kernel for a problem.  fp32: 128 rows, 64 columns for narrow results, otherwise 128.  bf16
+// adds larger tiles, because its loop is bound by what moves through LDS per MFMA, and both the staging writes and
+// the fragment reads per MFMA fall with the tile's sides:
+//   128x256 for results at least 256 wide with at least three rounds of such tiles (a quarter fewer LDS and load
+//           instructions per MFMA than 128x128: 5 to 20 % on such layers; with fewer rounds the coarser tiles
+//           leave compute units idle at the end);
+//   256x64  for results at most 64 wide with at least three rounds of such tiles: a wave then owns 128 x 32 and
+//           issues as many MFMAs per load as in the 128x128 tile (4 to 7 % on the 56x56 layers with 64 filters
+//           or channels).
+// The few-channels and scatter variants are built for 128 rows and 64 or 128 columns only.
+struct MainTile {
+    int bm, bn;
+};
+inline MainTile main_tile(const GemmConv& p) {
     static const bool no_wide = getenv("LARSCONV_NO_WIDE_TILE") != nullptr;    // comparison runs
-    if (p.N <= 64) return 64;
-    if (!p.bf16 || p.N < 256 || p.Ci < 32 || p.scatter || no_wide) return 128;
-    const long long tiles = (long long)((p.M + 127) / 128) * ((p.N + 255) / 256);
-    return tiles >= 3LL * resident_blocks(128, 256) ? 256 : 128;
+    static const bool no_tall = getenv("LARSCONV_NO_TALL_TILE") != nullptr;
+    MainTile t{128, p.N <= 64 ? 64 : 128};
+    if (!p.bf16 || p.Ci < 32 || p.scatter) return t;
+    if (p.N <= 64) {
+        if (!no_tall && (p.M + 255) / 256 >= 3LL * resident_blocks(256, 64)) t.bm = 256;
+        return t;
+    }
+    if (p.N >= 256 && !no_wide) {
+        const long long tiles = (long long)((p.M + 127) / 128) * ((p.N + 255) / 256);
+        if (tiles >= 3LL * resident_blocks(128, 256)) t.bn = 256;
+    }
+    return t;
 }
 
 template <int BM, int BN>
@@ -1637,27 +1653,25 @@ inline bool use_main_kernel(const GemmConv& p) {
 
 }  // namespace
 
-// 256 rows for narrow bf16 results (at most 64 columns) with at least three rounds of such tiles: a wave then owns
-// 128 x 32 and issues as many MFMAs per load as in the 128 x 128 tile, instead of half as many (measured: 4 to 7 %
-// on the 56x56 layers with 64 filters or channels; no gain in fp32, where it is not used).
-inline int main_tile_m(const GemmConv& p) {
-    static const bool no_tall = getenv("LARSCONV_NO_TALL_TILE") != nullptr;    // comparison runs
-    if (!p.bf16 || p.N > 64 || p.scatter || p.Ci < 32 || no_tall) return 128;
-    return (p.M + 255) / 256 >= 3LL * resident_blocks(256, 64) ? 256 : 128;
+// Calls f.template operator()<BM, BN>() for the tile main_tile() picks.
+template <typename F>
+auto with_main_tile(const GemmConv& p, F&& f) {
+    const MainTile t = main_tile(p);
+    if (t.bm == 256) return f.template operator()<256, 64>();
+    if (t.bn == 256) return f.template operator()<128, 256>();
+    if (t.bn == 128) return f.template operator()<128, 128>();
+    return f.template operator()<128, 64>();
 }
 
 size_t lc_conv_gemm_workspace(const GemmConv& p) {
     if (!use_main_kernel(p)) return 0;
-    long long tiles;
-    int nkt;
-    const int bn = main_tile_n(p), bm = main_tile_m(p);
-    if (!(bm == 256  ? sk_geometry<256, 64>(p, &tiles, &nkt)
-          : bn == 256 ? sk_geometry<128, 256>(p, &tiles, &nkt)
-          : bn == 128 ? sk_geometry<128, 128>(p, &tiles, &nkt)
-                      : sk_geometry<128, 64>(p, &tiles, &nkt)))
-        return 0;
-    const SkPlan pl = sk_plan(tiles, nkt, resident_blocks(bm, bn));
-    return (size_t)2 * pl.sk_blocks * bm * bn * sizeof(float);
+    return with_main_tile(p, [&]<int BM, int BN>() -> size_t {
+        long long tiles;
+        int nkt;
+        if (!sk_geometry<BM, BN>(p, &tiles, &nkt)) return 0;
+        const SkPlan pl = sk_plan(tiles, nkt, resident_blocks(BM, BN));
+        return (size_t)2 * pl.sk_blocks * BM * BN * sizeof(float);
+    });
 }
 
 bool lc_conv_gemm_bf16_native(const GemmConv& p) { return p.bf16 && use_main_kernel(p); }
@@ -1666,10 +1680,7 @@ lc_status lc_launch_conv_gemm(const GemmConv& p, hipStream_t stream) {
     if (p.bf16) {
         if (!use_main_kernel(p)) return LC_ERR_UNSUPPORTED;       // the caller converts to fp32 instead
         if (p.Ci < 32) return p.N > 64 ? launch_conv_sk<128, 128, true, true>(p, stream) : launch_conv_sk<128, 64, true, true>(p, stream);
-        const int bn = main_tile_n(p);
-        if (main_tile_m(p) == 256) return launch_conv_sk<256, 64, false, true>(p, stream);
-        if (bn == 256) return launch_conv_sk<128, 256, false, true>(p, stream);
-        return bn == 128 ? launch_conv_sk<128, 128, false, true>(p, stream) : launch_conv_sk<128, 64, false, true>(p, stream);
+        return with_main_tile(p, [&]<int BM, int BN>() { return launch_conv_sk<BM, BN, false, true>(p, stream); });
     }
     const bool vec = (p.Ci % 4 == 0) && aligned16(p.a) && aligned16(p.b);
     if (!vec) return launch_conv<64, 64, 16, 1>(p, stream);
