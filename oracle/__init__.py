@@ -186,6 +186,70 @@ def conv2d_bwd_weight_at(x, dy, rs, coords, stride=1, pad=0, layout=NCHW):
     return _at(_load().oracle_conv2d_bwd_weight_at, _desc(n, c, h, w, k, r, s, stride, pad, layout), x, dy, coords)
 
 
+def _grouped(fn: str, groups: int, d, a, b, out) -> None:
+    _load()
+    f = getattr(_lib, fn)
+    f.restype = None
+    f(ctypes.byref(d), ctypes.c_int(groups), _fp(a), _fp(b), _fp(out))
+
+
+def conv2d_fwd_grouped(x, wt, groups: int, stride=1, pad=0, layout=NCHW) -> np.ndarray:
+    """Grouped forward convolution: x has c channels, wt is [k][c/groups][r][s] (NHWC: [k][r][s][c/groups])."""
+    x, wt = _f32(x), _f32(wt)
+    if layout == NCHW:
+        n, c, h, w = x.shape
+        k, cg, r, s = wt.shape
+    else:
+        n, h, w, c = x.shape
+        k, r, s, cg = wt.shape
+    if groups < 1 or c % groups or k % groups or cg * groups != c:
+        raise ValueError("groups must divide both channel counts and match the filter")
+    d = _desc(n, c, h, w, k, r, s, stride, pad, layout)
+    p, q = out_shape(h, w, r, s, (d.stride_h, d.stride_w), (d.pad_h, d.pad_w))
+    y = np.empty(_act_shape(n, k, p, q, layout), dtype=np.float64)
+    _grouped("oracle_conv2d_fwd_grouped", groups, d, x, wt, y)
+    return y
+
+
+def conv2d_bwd_data_grouped(dy, wt, groups: int, x_hw: Tuple[int, int], stride=1, pad=0, layout=NCHW) -> np.ndarray:
+    dy, wt = _f32(dy), _f32(wt)
+    h, w = x_hw
+    if layout == NCHW:
+        n, k, p, q = dy.shape
+        k2, cg, r, s = wt.shape
+    else:
+        n, p, q, k = dy.shape
+        k2, r, s, cg = wt.shape
+    c = cg * groups
+    d = _desc(n, c, h, w, k, r, s, stride, pad, layout)
+    if groups < 1 or k != k2 or k % groups or (p, q) != out_shape(h, w, r, s, (d.stride_h, d.stride_w), (d.pad_h, d.pad_w)):
+        raise ValueError("dy shape does not match")
+    dx = np.empty(_act_shape(n, c, h, w, layout), dtype=np.float64)
+    _grouped("oracle_conv2d_bwd_data_grouped", groups, d, dy, wt, dx)
+    return dx
+
+
+def conv2d_bwd_weight_grouped(x, dy, groups: int, rs: Tuple[int, int], stride=1, pad=0, layout=NCHW) -> np.ndarray:
+    x, dy = _f32(x), _f32(dy)
+    r, s = rs
+    if layout == NCHW:
+        n, c, h, w = x.shape
+        n2, k, p, q = dy.shape
+    else:
+        n, h, w, c = x.shape
+        n2, p, q, k = dy.shape
+    if groups < 1 or c % groups or k % groups:
+        raise ValueError("groups must divide both channel counts")
+    cg = c // groups
+    wshape = (k, cg, r, s) if layout == NCHW else (k, r, s, cg)
+    d = _desc(n, c, h, w, k, r, s, stride, pad, layout)
+    if n != n2 or (p, q) != out_shape(h, w, r, s, (d.stride_h, d.stride_w), (d.pad_h, d.pad_w)):
+        raise ValueError("dy shape does not match")
+    dw = np.empty(wshape, dtype=np.float64)
+    _grouped("oracle_conv2d_bwd_weight_grouped", groups, d, x, dy, dw)
+    return dw
+
+
 def lars_step(w: Sequence[np.ndarray], g: Sequence[np.ndarray], v: Sequence[np.ndarray],
               eta: float, momentum: float, weight_decay: float, lr: float):
     """One LARS step over a list of tensors.  ``w`` and ``v`` (float32, contiguous) are updated

@@ -20,8 +20,10 @@
  * Parity pins (tests/test_oracle_*.py): hand-worked 3x3 example, 1x1 and
  * full-window cases against a matrix product, delta-filter shifts, central
  * finite differences, the adjoint identity, float64 library convolution, and
- * for LARS hand-computed trust ratios and the rule's invariants.  No function
- * here is "parity unpinned".
+ * for LARS hand-computed trust ratios and the rule's invariants; for the grouped
+ * convolution its reduction to independent convolutions on channel slices, the
+ * one-group case, the float64 library convolution and the paper's AlexNet
+ * counts.  No function here is "parity unpinned".
  */
 #include <math.h>
 #include <stddef.h>
@@ -146,6 +148,81 @@ void oracle_conv2d_bwd_weight(const oracle_conv* d, const float* x, const float*
                                 const int w = q * d->stride_w - d->pad_w + s;
                                 if (h >= 0 && h < d->h && w >= 0 && w < d->w)
                                     dw[wi(d, k, c, r, s)] += g * (double)x[xi(d, n, c, h, w)];
+                            }
+                }
+}
+
+/* ---- grouped convolution (the original AlexNet of the paper's scaling-ratio table: 61 million parameters and 1.5
+ * billion operations per image are the counts of the network whose second, fourth and fifth convolutions are split
+ * into two groups).  The c input channels and the k filters are cut into `groups` equal slices; filter k belongs to
+ * group k / (k/groups) and sees only that group's c/groups input channels, so the filter tensor is
+ * [K][C/groups][R][S] (NHWC: [K][R][S][C/groups]):
+ *     Y[n,k,p,q] = sum_{cl < C/groups, r, s} X[n, g(k)*C/groups + cl, p*sh-ph+r, q*sw-pw+s] * W[k,cl,r,s].
+ * The two gradients are again the transposed forward loop.  d->c and d->k are the TOTAL channel counts. ---- */
+static size_t wgi(const oracle_conv* d, int cg, int k, int cl, int r, int s) {
+    return d->layout == ORACLE_NHWC ? (((size_t)k * d->r + r) * d->s + s) * cg + cl
+                                    : (((size_t)k * cg + cl) * d->r + r) * d->s + s;
+}
+
+void oracle_conv2d_fwd_grouped(const oracle_conv* d, int groups, const float* x, const float* wt, double* y) {
+    const int P = out_p(d), Q = out_q(d), cg = d->c / groups, kg = d->k / groups;
+#pragma omp parallel for collapse(2) schedule(static)
+    for (int n = 0; n < d->n; ++n)
+        for (int k = 0; k < d->k; ++k)
+            for (int p = 0; p < P; ++p)
+                for (int q = 0; q < Q; ++q) {
+                    const int g = k / kg;
+                    double acc = 0.0;
+                    for (int cl = 0; cl < cg; ++cl)
+                        for (int r = 0; r < d->r; ++r)
+                            for (int s = 0; s < d->s; ++s) {
+                                const int h = p * d->stride_h - d->pad_h + r;
+                                const int w = q * d->stride_w - d->pad_w + s;
+                                if (h >= 0 && h < d->h && w >= 0 && w < d->w)
+                                    acc += (double)x[xi(d, n, g * cg + cl, h, w)] * (double)wt[wgi(d, cg, k, cl, r, s)];
+                            }
+                    y[yi(d, P, Q, n, k, p, q)] = acc;
+                }
+}
+
+void oracle_conv2d_bwd_data_grouped(const oracle_conv* d, int groups, const float* dy, const float* wt, double* dx) {
+    const int P = out_p(d), Q = out_q(d), cg = d->c / groups, kg = d->k / groups;
+    memset(dx, 0, sizeof(double) * (size_t)d->n * d->c * d->h * d->w);
+#pragma omp parallel for schedule(static) /* images are independent: each n owns dx[n] */
+    for (int n = 0; n < d->n; ++n)
+        for (int k = 0; k < d->k; ++k)
+            for (int p = 0; p < P; ++p)
+                for (int q = 0; q < Q; ++q) {
+                    const int g = k / kg;
+                    const double gr = (double)dy[yi(d, P, Q, n, k, p, q)];
+                    for (int cl = 0; cl < cg; ++cl)
+                        for (int r = 0; r < d->r; ++r)
+                            for (int s = 0; s < d->s; ++s) {
+                                const int h = p * d->stride_h - d->pad_h + r;
+                                const int w = q * d->stride_w - d->pad_w + s;
+                                if (h >= 0 && h < d->h && w >= 0 && w < d->w)
+                                    dx[xi(d, n, g * cg + cl, h, w)] += gr * (double)wt[wgi(d, cg, k, cl, r, s)];
+                            }
+                }
+}
+
+void oracle_conv2d_bwd_weight_grouped(const oracle_conv* d, int groups, const float* x, const float* dy, double* dw) {
+    const int P = out_p(d), Q = out_q(d), cg = d->c / groups, kg = d->k / groups;
+    memset(dw, 0, sizeof(double) * (size_t)d->k * cg * d->r * d->s);
+#pragma omp parallel for schedule(static) /* output channels are independent: each k owns dw[k] */
+    for (int k = 0; k < d->k; ++k)
+        for (int n = 0; n < d->n; ++n)
+            for (int p = 0; p < P; ++p)
+                for (int q = 0; q < Q; ++q) {
+                    const int g = k / kg;
+                    const double gr = (double)dy[yi(d, P, Q, n, k, p, q)];
+                    for (int cl = 0; cl < cg; ++cl)
+                        for (int r = 0; r < d->r; ++r)
+                            for (int s = 0; s < d->s; ++s) {
+                                const int h = p * d->stride_h - d->pad_h + r;
+                                const int w = q * d->stride_w - d->pad_w + s;
+                                if (h >= 0 && h < d->h && w >= 0 && w < d->w)
+                                    dw[wgi(d, cg, k, cl, r, s)] += gr * (double)x[xi(d, n, g * cg + cl, h, w)];
                             }
                 }
 }

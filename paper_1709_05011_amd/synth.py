@@ -106,6 +106,7 @@ class ConvShape:
     s: int
     stride: int = 1
     pad: int = 0
+    groups: int = 1          # filters see c / groups input channels each (c and k are the totals)
 
     @property
     def p(self) -> int:
@@ -117,7 +118,7 @@ class ConvShape:
 
     @property
     def macs(self) -> int:
-        return self.n * self.k * self.p * self.q * self.c * self.r * self.s
+        return self.n * self.k * self.p * self.q * (self.c // self.groups) * self.r * self.s
 
     @property
     def flops(self) -> int:
@@ -126,13 +127,13 @@ class ConvShape:
 
     @property
     def weight_numel(self) -> int:
-        return self.k * self.c * self.r * self.s
+        return self.k * (self.c // self.groups) * self.r * self.s
 
     def with_batch(self, n: int) -> "ConvShape":
         return replace(self, n=n)
 
     def key(self) -> Tuple[int, ...]:
-        return (self.c, self.k, self.r, self.s, self.stride, self.pad, self.h, self.w)
+        return (self.c, self.k, self.r, self.s, self.stride, self.pad, self.h, self.w) + ((self.groups,) if self.groups > 1 else ())
 
 
 def resnet50_convs(batch: int) -> List[ConvShape]:
@@ -208,6 +209,34 @@ def alexnet_bn_param_numels() -> List[int]:
         sizes.append(cs.weight_numel)
         sizes += [cs.k, cs.k] if i < 5 else [cs.k]
     return sizes
+
+
+def alexnet_grouped_convs(batch: int) -> List[ConvShape]:
+    """The original AlexNet of the paper's scaling-ratio table (61 million parameters, 1.5 billion operations per
+    image): the second, fourth and fifth convolutions split into two groups; fully connected layers as above."""
+    out = alexnet_bn_convs(batch)
+    for i in (1, 3, 4):
+        out[i] = replace(out[i], groups=2)
+    return out
+
+
+def alexnet_grouped_param_numels() -> List[int]:
+    """The original AlexNet's 16 tensors: a weight and a bias per layer."""
+    sizes: List[int] = []
+    for cs in alexnet_grouped_convs(1):
+        sizes += [cs.weight_numel, cs.k]
+    return sizes
+
+
+def resnet50_v15_extra_shapes(batch: int) -> List[ConvShape]:
+    """The shapes the "v1.5" form of ResNet-50 has and the original does not: the stride 2 of stages 3, 4, 5 sits on the
+    3x3 convolution instead of the first 1x1, which then runs at stride 1 on the larger map.  Not the network the paper
+    trains (its 7.72 G operations per image are the original's); listed as a second workload."""
+    out = []
+    for stage, (cin, mid, hw) in enumerate([(256, 128, 56), (512, 256, 28), (1024, 512, 14)], start=3):
+        out.append(ConvShape(f"v15_res{stage}a_1x1a", batch, cin, hw, hw, mid, 1, 1, 1, 0))
+        out.append(ConvShape(f"v15_res{stage}a_3x3s2", batch, mid, hw, hw, mid, 3, 3, 2, 1))
+    return out
 
 
 def tiny_cnn_convs(batch: int = 16) -> List[ConvShape]:
