@@ -47,15 +47,21 @@ typedef enum { LC_PASS_FWD = 0, LC_PASS_BWD_DATA = 1, LC_PASS_BWD_WEIGHT = 2 } l
 
 /* One convolution layer: input X[n,c,h,w], filter W[k,c,r,s], output Y[n,k,p,q] with
  * p = floor((h + 2*pad_h - r)/stride_h) + 1 (q likewise).  Cross-correlation (no filter flip),
- * zero padding, dilation 1, one group, no bias -- the convolution of the Caffe-style layers the
+ * zero padding, dilation 1, no bias -- the convolution of the Caffe-style layers the
  * paper's networks are made of ("Experimental Settings").  NHWC is the layout the matrix cores
- * are fed from; NCHW tensors are accepted and transposed through the workspace. */
+ * are fed from; NCHW tensors are accepted and transposed through the workspace.
+ * groups > 1: the c input channels and the k filters are cut into `groups` equal slices and filter j sees only the
+ * input channels of slice j / (k/groups), so the filter (and dw) is W[k, c/groups, r, s] -- the form of the original
+ * AlexNet whose 61 million parameters and 1.5 billion operations the paper's Table "Scaling Ratio for AlexNet and
+ * ResNet50" lists.  c and k stay the TOTAL channel counts and must be multiples of groups; 0 means 1.  Each group
+ * runs as a convolution of its own on channel slices copied through the workspace. */
 typedef struct {
     int n, c, h, w;
     int k, r, s;
     int stride_h, stride_w, pad_h, pad_w;
     lc_dtype dtype;   /* type of x, w, y, dy, dx.  dw is always fp32. */
     lc_layout layout;
+    int groups;       /* 0 or 1: every filter sees every input channel */
 } lc_conv_desc;
 
 /* Output height p and width q.  HOST pointers.  LC_ERR_SHAPE if the window does not fit. */
@@ -66,12 +72,12 @@ lc_status conv2d_out_shape(const lc_conv_desc* desc, int* p, int* q);
  * it holds whole tensors where the library re-lays its operands: NCHW calls (NHWC copies of all three tensors),
  * channel counts that are not a multiple of 4 (8 for bf16; a padded copy of x), and the bf16 forward and
  * backward-weight passes of a stride-2 layer with at most 4 channels (x unfolded over 2x2 pixel blocks, about
- * 5.5 times its size: 0.84 GB for 512 x 224 x 224 x 3). */
+ * 5.5 times its size: 0.84 GB for 512 x 224 x 224 x 3), and grouped layers (one group's slices of x and y). */
 size_t conv2d_workspace_bytes(const lc_conv_desc* desc, lc_pass pass);
 
 /* Forward pass: the per-image work the paper counts in flops ("Benefits of Large-Batch Training",
  * "Model Selection").   y[n,k,p,q] = sum_{c,r,s} x[n,c,p*stride_h-pad_h+r, q*stride_w-pad_w+s] * w[k,c,r,s],
- * reads outside the image being zero.  x: n*c*h*w, w: k*c*r*s, y: n*k*p*q elements of desc->dtype. */
+ * reads outside the image being zero.  x: n*c*h*w, w: k*(c/groups)*r*s, y: n*k*p*q elements of desc->dtype. */
 lc_status conv2d_fwd(const lc_conv_desc* desc, const void* x, const void* w, void* y,
                      void* workspace, size_t workspace_bytes, void* hip_stream);
 

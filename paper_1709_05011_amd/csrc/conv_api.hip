@@ -51,6 +51,7 @@ lc_status check_desc(const lc_conv_desc* d, int* P, int* Q) {
         d->stride_h <= 0 || d->stride_w <= 0 || d->pad_h < 0 || d->pad_w < 0)
         return LC_ERR_SHAPE;
     if ((long long)d->h + 2LL * d->pad_h < d->r || (long long)d->w + 2LL * d->pad_w < d->s) return LC_ERR_SHAPE;
+    if (d->groups < 0 || (d->groups > 1 && (d->c % d->groups != 0 || d->k % d->groups != 0))) return LC_ERR_SHAPE;
     if (d->dtype != LC_F32 && d->dtype != LC_BF16) return LC_ERR_UNSUPPORTED;
     if (d->layout != LC_NCHW && d->layout != LC_NHWC) return LC_ERR_UNSUPPORTED;
     *P = (d->h + 2 * d->pad_h - d->r) / d->stride_h + 1;
@@ -144,6 +145,7 @@ const lc_conv_desc* whole_window_as_1x1(const lc_conv_desc* d, lc_conv_desc* sto
     if (!d || d->n <= 0 || d->c <= 0 || d->h <= 0 || d->w <= 0 || d->k <= 0 || d->stride_h <= 0 || d->stride_w <= 0) return d;
     if (d->pad_h != 0 || d->pad_w != 0 || d->r != d->h || d->s != d->w || (d->h == 1 && d->w == 1)) return d;
     if (d->layout != LC_NCHW && d->layout != LC_NHWC) return d;
+    if (d->groups > 1) return d;
     const long long cc = (long long)d->c * d->h * d->w;
     if (cc > 0x7fffffffLL) return d;
     *store = *d;
@@ -314,7 +316,118 @@ extern "C" lc_status conv2d_out_shape(const lc_conv_desc* desc, int* p, int* q) 
     return LC_OK;
 }
 
+namespace {
+
+// A grouped layer runs group by group: the group's channel slice of each activation operand is copied to a dense
+// tensor in the workspace, the one-group convolution runs on it, and an activation result is copied back into its
+// slice.  The filter (and its gradient) of a group is a contiguous run of k/groups filters and is used in place,
+// unless a bf16 slice would start off a 16-byte boundary; then it goes through the workspace too.
+struct GroupPlan {
+    lc_conv_desc inner = {};
+    int G = 1, cg = 0, kg = 0, P = 0, Q = 0;
+    size_t es = 4;
+    size_t x_rows = 0, x_pitch = 0, x_width = 0;      // 2-D view of x (and dx): rows, pitch and slice width in bytes
+    size_t y_rows = 0, y_pitch = 0, y_width = 0;      // ... of y (and dy)
+    size_t w_bytes = 0;                               // one group's filter in the operand type
+    bool w_copy = false;
+    size_t xs = 0, ys = 0, wsl = 0, ws = 0, ws_bytes = 0, total = 0;
+};
+
+lc_status plan_groups(const lc_conv_desc* d, lc_pass pass, GroupPlan* gp) {
+    const lc_status st = check_desc(d, &gp->P, &gp->Q);
+    if (st != LC_OK) return st;
+    if (pass != LC_PASS_FWD && pass != LC_PASS_BWD_DATA && pass != LC_PASS_BWD_WEIGHT) return LC_ERR_UNSUPPORTED;
+    gp->G = d->groups;
+    gp->cg = d->c / gp->G;
+    gp->kg = d->k / gp->G;
+    gp->es = d->dtype == LC_BF16 ? 2 : 4;
+    gp->inner = *d;
+    gp->inner.c = gp->cg;
+    gp->inner.k = gp->kg;
+    gp->inner.groups = 1;
+    const size_t hw = (size_t)d->h * d->w, pq = (size_t)gp->P * gp->Q;
+    if (d->layout == LC_NHWC) {
+        gp->x_rows = (size_t)d->n * hw;
+        gp->x_pitch = (size_t)d->c * gp->es;
+        gp->x_width = (size_t)gp->cg * gp->es;
+        gp->y_rows = (size_t)d->n * pq;
+        gp->y_pitch = (size_t)d->k * gp->es;
+        gp->y_width = (size_t)gp->kg * gp->es;
+    } else {
+        gp->x_rows = gp->y_rows = (size_t)d->n;
+        gp->x_pitch = (size_t)d->c * hw * gp->es;
+        gp->x_width = (size_t)gp->cg * hw * gp->es;
+        gp->y_pitch = (size_t)d->k * pq * gp->es;
+        gp->y_width = (size_t)gp->kg * pq * gp->es;
+    }
+    gp->w_bytes = (size_t)gp->kg * gp->cg * d->r * d->s * gp->es;
+    gp->w_copy = pass != LC_PASS_BWD_WEIGHT && gp->es == 2 && (gp->w_bytes & 15) != 0;
+    Regions rg;
+    gp->xs = rg.take(gp->x_rows * gp->x_width);
+    gp->ys = rg.take(gp->y_rows * gp->y_width);
+    if (gp->w_copy) gp->wsl = rg.take(gp->w_bytes);
+    gp->ws_bytes = conv2d_workspace_bytes(&gp->inner, pass);
+    if (gp->ws_bytes) gp->ws = rg.take(gp->ws_bytes);
+    gp->total = rg.off;
+    return LC_OK;
+}
+
+// a, b: the pass's two operands, c: its result, as in the entry points.
+lc_status run_groups(const lc_conv_desc* d, lc_pass pass, const void* a, const void* b, void* c, void* workspace,
+                     size_t workspace_bytes, void* hip_stream) {
+    GroupPlan gp;
+    lc_status st = plan_groups(d, pass, &gp);
+    if (st != LC_OK) return st;
+    if (!a || !b || !c) return LC_ERR_NULL;
+    const uintptr_t mask = gp.es == 2 ? 15 : 3;
+    if ((((uintptr_t)a | (uintptr_t)b) & mask) || ((uintptr_t)c & (pass == LC_PASS_BWD_WEIGHT ? 3 : mask))) return LC_ERR_ALIGN;
+    if (!workspace || ((uintptr_t)workspace & 255) || workspace_bytes < gp.total) return LC_ERR_WORKSPACE;
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    char* xs = at(workspace, gp.xs);
+    char* ys = at(workspace, gp.ys);
+    void* iws = gp.ws_bytes ? at(workspace, gp.ws) : nullptr;
+    for (int g = 0; g < gp.G; ++g) {
+        const size_t xo = (size_t)g * gp.x_width, yo = (size_t)g * gp.y_width;
+        lc_begin_call();
+        if (pass == LC_PASS_FWD) {                      // a = x, b = w, c = y
+            const char* wg = static_cast<const char*>(b) + (size_t)g * gp.w_bytes;
+            lc_copy2d(static_cast<const char*>(a) + xo, gp.x_pitch, xs, gp.x_width, gp.x_width, gp.x_rows, stream);
+            if (gp.w_copy) lc_copy2d(wg, gp.w_bytes, at(workspace, gp.wsl), gp.w_bytes, gp.w_bytes, 1, stream);
+            if ((st = lc_end_call()) != LC_OK) return st;
+            st = conv2d_fwd(&gp.inner, xs, gp.w_copy ? at(workspace, gp.wsl) : wg, ys, iws, gp.ws_bytes, hip_stream);
+            if (st != LC_OK) return st;
+            lc_begin_call();
+            lc_copy2d(ys, gp.y_width, static_cast<char*>(c) + yo, gp.y_pitch, gp.y_width, gp.y_rows, stream);
+        } else if (pass == LC_PASS_BWD_DATA) {          // a = dy, b = w, c = dx
+            const char* wg = static_cast<const char*>(b) + (size_t)g * gp.w_bytes;
+            lc_copy2d(static_cast<const char*>(a) + yo, gp.y_pitch, ys, gp.y_width, gp.y_width, gp.y_rows, stream);
+            if (gp.w_copy) lc_copy2d(wg, gp.w_bytes, at(workspace, gp.wsl), gp.w_bytes, gp.w_bytes, 1, stream);
+            if ((st = lc_end_call()) != LC_OK) return st;
+            st = conv2d_bwd_data(&gp.inner, ys, gp.w_copy ? at(workspace, gp.wsl) : wg, xs, iws, gp.ws_bytes, hip_stream);
+            if (st != LC_OK) return st;
+            lc_begin_call();
+            lc_copy2d(xs, gp.x_width, static_cast<char*>(c) + xo, gp.x_pitch, gp.x_width, gp.x_rows, stream);
+        } else {                                        // a = x, b = dy, c = dw (fp32)
+            lc_copy2d(static_cast<const char*>(a) + xo, gp.x_pitch, xs, gp.x_width, gp.x_width, gp.x_rows, stream);
+            lc_copy2d(static_cast<const char*>(b) + yo, gp.y_pitch, ys, gp.y_width, gp.y_width, gp.y_rows, stream);
+            if ((st = lc_end_call()) != LC_OK) return st;
+            float* dwg = static_cast<float*>(c) + (size_t)g * gp.kg * gp.cg * d->r * d->s;
+            st = conv2d_bwd_weight(&gp.inner, xs, ys, dwg, iws, gp.ws_bytes, hip_stream);
+            if (st != LC_OK) return st;
+            lc_begin_call();
+        }
+        if ((st = lc_end_call()) != LC_OK) return st;
+    }
+    return LC_OK;
+}
+
+}  // namespace
+
 extern "C" size_t conv2d_workspace_bytes(const lc_conv_desc* desc, lc_pass pass) {
+    if (desc && desc->groups > 1) {
+        GroupPlan gp;
+        return plan_groups(desc, pass, &gp) == LC_OK ? gp.total : 0;
+    }
     lc_conv_desc canon;
     desc = whole_window_as_1x1(desc, &canon);
     Plan pl;
@@ -324,6 +437,7 @@ extern "C" size_t conv2d_workspace_bytes(const lc_conv_desc* desc, lc_pass pass)
 
 extern "C" lc_status conv2d_fwd(const lc_conv_desc* d, const void* x, const void* w, void* y,
                                 void* workspace, size_t workspace_bytes, void* hip_stream) {
+    if (d && d->groups > 1) return run_groups(d, LC_PASS_FWD, x, w, y, workspace, workspace_bytes, hip_stream);
     lc_conv_desc canon;
     d = whole_window_as_1x1(d, &canon);
     Plan pl;
@@ -373,6 +487,7 @@ extern "C" lc_status conv2d_fwd(const lc_conv_desc* d, const void* x, const void
 
 extern "C" lc_status conv2d_bwd_data(const lc_conv_desc* d, const void* dy, const void* w, void* dx,
                                      void* workspace, size_t workspace_bytes, void* hip_stream) {
+    if (d && d->groups > 1) return run_groups(d, LC_PASS_BWD_DATA, dy, w, dx, workspace, workspace_bytes, hip_stream);
     lc_conv_desc canon;
     d = whole_window_as_1x1(d, &canon);
     Plan pl;
@@ -427,6 +542,7 @@ extern "C" lc_status conv2d_bwd_data(const lc_conv_desc* d, const void* dy, cons
 
 extern "C" lc_status conv2d_bwd_weight(const lc_conv_desc* d, const void* x, const void* dy, float* dw,
                                        void* workspace, size_t workspace_bytes, void* hip_stream) {
+    if (d && d->groups > 1) return run_groups(d, LC_PASS_BWD_WEIGHT, x, dy, dw, workspace, workspace_bytes, hip_stream);
     lc_conv_desc canon;
     d = whole_window_as_1x1(d, &canon);
     Plan pl;

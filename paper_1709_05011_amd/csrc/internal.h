@@ -27,6 +27,9 @@ void lc_fill_f32(float* dst, float value, size_t count, hipStream_t stream);
 void lc_fill_u32x4(void* dst, size_t bytes16, hipStream_t stream);   // zero `bytes16` * 16 bytes
 void lc_zero_bytes(void* dst, size_t bytes, hipStream_t stream);      // zero an even number of bytes at a 2-byte aligned address
 
+// rows x width_bytes bytes from src (row pitch src_pitch bytes) to dst (row pitch dst_pitch); every size a multiple of 2
+void lc_copy2d(const void* src, size_t src_pitch, void* dst, size_t dst_pitch, size_t width_bytes, size_t rows, hipStream_t stream);
+
 // NCHW <-> NHWC for activations ([n][c][hw] <-> [n][hw][c]); esize 4 (fp32) or 2 (bf16).
 void lc_nchw_to_nhwc(const void* src, void* dst, int n, int c, int hw, int esize, hipStream_t stream);
 void lc_nhwc_to_nchw(const void* src, void* dst, int n, int c, int hw, int esize, hipStream_t stream);

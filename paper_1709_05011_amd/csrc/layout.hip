@@ -334,6 +334,33 @@ void lc_filter_for_bwd_data(const void* w_krsc, void* out, int k, int c, int r, 
                            static_cast<const uint16_t*>(w_krsc), static_cast<uint16_t*>(out), k, c, r, s);
 }
 
+// Strided 2-D copy (a channel slice of an activation tensor to or from a dense one): element (row, i) of width-V vectors.
+template <typename V>
+__global__ void __launch_bounds__(256) copy2d_kernel(const char* __restrict__ src, size_t src_pitch, char* __restrict__ dst,
+                                                     size_t dst_pitch, size_t wvec, size_t total) {
+    for (size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x; i < total; i += (size_t)gridDim.x * blockDim.x) {
+        const size_t row = i / wvec, col = i - row * wvec;
+        *reinterpret_cast<V*>(dst + row * dst_pitch + col * sizeof(V)) = *reinterpret_cast<const V*>(src + row * src_pitch + col * sizeof(V));
+    }
+}
+
+void lc_copy2d(const void* src, size_t src_pitch, void* dst, size_t dst_pitch, size_t width_bytes, size_t rows, hipStream_t stream) {
+    if (!width_bytes || !rows) return;
+    const uintptr_t all = (uintptr_t)src | (uintptr_t)dst | src_pitch | dst_pitch | width_bytes;
+    const char* s = static_cast<const char*>(src);
+    char* d = static_cast<char*>(dst);
+    if ((all & 15) == 0) {
+        const size_t wv = width_bytes / 16, total = wv * rows;
+        hipLaunchKernelGGL(copy2d_kernel<uint4>, dim3(grid_for(total, 256)), dim3(256), 0, stream, s, src_pitch, d, dst_pitch, wv, total);
+    } else if ((all & 3) == 0) {
+        const size_t wv = width_bytes / 4, total = wv * rows;
+        hipLaunchKernelGGL(copy2d_kernel<uint32_t>, dim3(grid_for(total, 256)), dim3(256), 0, stream, s, src_pitch, d, dst_pitch, wv, total);
+    } else {
+        const size_t wv = width_bytes / 2, total = wv * rows;
+        hipLaunchKernelGGL(copy2d_kernel<uint16_t>, dim3(grid_for(total, 256)), dim3(256), 0, stream, s, src_pitch, d, dst_pitch, wv, total);
+    }
+}
+
 void lc_pad_channels(const void* src, void* dst, size_t rows, int c, int cpad, int esize, hipStream_t stream) {
     const size_t total = rows * (size_t)cpad;
     if (!total) return;

@@ -36,7 +36,7 @@ class LarsConvError(RuntimeError):
 
 class lc_conv_desc(ctypes.Structure):
     _fields_ = [(f, ctypes.c_int) for f in
-                ("n", "c", "h", "w", "k", "r", "s", "stride_h", "stride_w", "pad_h", "pad_w", "dtype", "layout")]
+                ("n", "c", "h", "w", "k", "r", "s", "stride_h", "stride_w", "pad_h", "pad_w", "dtype", "layout", "groups")]
 
 
 @dataclass(frozen=True)
@@ -54,10 +54,11 @@ class ConvDesc:
     pad_w: int = 0
     dtype: int = LC_F32
     layout: int = LC_NHWC
+    groups: int = 1
 
     def c_struct(self) -> lc_conv_desc:
         return lc_conv_desc(self.n, self.c, self.h, self.w, self.k, self.r, self.s, self.stride_h, self.stride_w,
-                            self.pad_h, self.pad_w, self.dtype, self.layout)
+                            self.pad_h, self.pad_w, self.dtype, self.layout, self.groups)
 
 
 _lib = None

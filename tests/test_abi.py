@@ -52,6 +52,33 @@ def test_out_shape_and_descriptor_validation():
     assert lc.lib().conv2d_out_shape(None, None, None) == lc.LC_ERR_NULL
 
 
+def test_grouped_descriptor_validation():
+    ok = lc.ConvDesc(2, 96, 27, 27, 256, 5, 5, 1, 1, 2, 2, groups=2)
+    assert lc.conv2d_out_shape(ok) == (27, 27)
+    assert lc.conv2d_out_shape(lc.ConvDesc(2, 96, 27, 27, 256, 5, 5, 1, 1, 2, 2, groups=0)) == (27, 27)       # 0 means 1
+    for bad in [lc.ConvDesc(2, 96, 27, 27, 256, 5, 5, 1, 1, 2, 2, groups=5),      # does not divide c
+                lc.ConvDesc(2, 96, 27, 27, 250, 5, 5, 1, 1, 2, 2, groups=4),      # does not divide k
+                lc.ConvDesc(2, 96, 27, 27, 256, 5, 5, 1, 1, 2, 2, groups=-2)]:
+        with pytest.raises(lc.LarsConvError) as e:
+            lc.conv2d_out_shape(bad)
+        assert e.value.status == lc.LC_ERR_SHAPE
+        assert lc.conv2d_workspace_bytes(bad, lc.LC_PASS_FWD) == 0
+    # a grouped call needs the slices of x and y plus the one-group call's scratch
+    one = lc.ConvDesc(2, 48, 27, 27, 128, 5, 5, 1, 1, 2, 2)
+    for p in (lc.LC_PASS_FWD, lc.LC_PASS_BWD_DATA, lc.LC_PASS_BWD_WEIGHT):
+        need = lc.conv2d_workspace_bytes(ok, p)
+        assert need >= 2 * 27 * 27 * (48 + 128) * 4 + lc.conv2d_workspace_bytes(one, p)
+    L = lc.lib()
+    P = ctypes.c_void_p(FAKE)
+    d = ok.c_struct()
+    need = lc.conv2d_workspace_bytes(ok, lc.LC_PASS_FWD)
+    assert L.conv2d_fwd(ctypes.byref(d), None, P, P, P, need, None) == lc.LC_ERR_NULL
+    assert L.conv2d_fwd(ctypes.byref(d), P, P, P, None, need, None) == lc.LC_ERR_WORKSPACE
+    assert L.conv2d_fwd(ctypes.byref(d), P, P, P, P, need - 1, None) == lc.LC_ERR_WORKSPACE
+    assert L.conv2d_bwd_data(ctypes.byref(d), P, ctypes.c_void_p(FAKE + 2), P, P, 1 << 40, None) == lc.LC_ERR_ALIGN
+    assert L.conv2d_bwd_weight(ctypes.byref(d), P, P, None, P, 1 << 40, None) == lc.LC_ERR_NULL
+
+
 def test_workspace_queries():
     nhwc = lc.ConvDesc(8, 64, 14, 14, 64, 3, 3, 1, 1, 1, 1)
     assert lc.conv2d_workspace_bytes(nhwc, lc.LC_PASS_FWD) % 256 == 0          # partial tiles of the stream-K blocks
