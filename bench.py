@@ -14,7 +14,9 @@ of the step at batch 512 ("bf16_step"), each a short run of its own (--no-extras
     python bench.py --dtype bf16                      # the same step at batch 512 with bf16 operands
     python bench.py --model alexnet_bn                # AlexNet-BN shaped step (5 convs + 3 FC layers as convs, 21 tensors)
     python bench.py --sweep [--batch 128]             # every distinct ResNet-50 conv shape x 3 passes
+    python bench.py --model alexnet                   # the original grouped AlexNet (61 M parameters), bias per layer
     python bench.py --lars resnet50|alexnet_bn        # lars_step alone, GB/s against HBM peak
+    python bench.py --batch-curve                     # images/s against the per-GPU batch, 16 .. 512
 """
 from __future__ import annotations
 
@@ -82,16 +84,17 @@ class Layer:
         self.cs = cs
         self.first = first
         self.desc = lc.ConvDesc(cs.n, cs.c, cs.h, cs.w, cs.k, cs.r, cs.s, cs.stride, cs.stride, cs.pad, cs.pad,
-                                lc.LC_BF16 if bf16 else lc.LC_F32, lc.LC_NHWC)
-        std = (2.0 / (cs.c * cs.r * cs.s)) ** 0.5
+                                lc.LC_BF16 if bf16 else lc.LC_F32, lc.LC_NHWC, cs.groups)
+        cg = cs.c // cs.groups
+        std = (2.0 / (cg * cs.r * cs.s)) ** 0.5
         act = torch.bfloat16 if bf16 else torch.float32
         self.x = torch.randn((cs.n, cs.h, cs.w, cs.c), generator=gen, device=dev).to(act)
-        self.w_master = torch.randn((cs.k, cs.r, cs.s, cs.c), generator=gen, device=dev) * std   # fp32 weights
+        self.w_master = torch.randn((cs.k, cs.r, cs.s, cg), generator=gen, device=dev) * std     # fp32 weights
         self.w = self.w_master.to(act) if bf16 else self.w_master                                # what the convolutions read
         self.dy = torch.randn((cs.n, cs.p, cs.q, cs.k), generator=gen, device=dev).to(act)
         self.y = torch.empty((cs.n, cs.p, cs.q, cs.k), device=dev, dtype=act)
         self.dx = None if first else torch.empty((cs.n, cs.h, cs.w, cs.c), device=dev, dtype=act)
-        self.dw = torch.empty((cs.k, cs.r, cs.s, cs.c), device=dev)
+        self.dw = torch.empty((cs.k, cs.r, cs.s, cg), device=dev)
         self.ws_bytes = max(lc.conv2d_workspace_bytes(self.desc, p) for p in range(3))
 
 
@@ -135,6 +138,8 @@ def model_shapes(synth, model: str, batch: int):
     """(layer shapes in network order, number of leading layers followed by batch norm, weight decay)."""
     if model == "alexnet_bn":
         return synth.alexnet_bn_convs(batch), 5, 5e-4
+    if model == "alexnet":          # the original grouped network of the paper's scaling-ratio table: a bias per layer, no batch norm
+        return synth.alexnet_grouped_convs(batch), 0, 5e-4
     return synth.resnet50_convs(batch) + [synth.resnet50_fc(batch)], 53, 5e-5
 
 
@@ -164,7 +169,8 @@ def run_train_step(args):
     pv = [torch.zeros_like(t) for t in pw]
     # bf16 run: fp32 master weights and momentum; lars_step also writes the bf16 weights the convolutions read
     largs = lc.LarsArgs(pw, pg, pv, w_lowp=plow if bf16 else None)
-    expect = synth.alexnet_bn_param_numels() if args.model == "alexnet_bn" else synth.resnet50_param_numels()
+    expect = {"alexnet_bn": synth.alexnet_bn_param_numels, "alexnet": synth.alexnet_grouped_param_numels,
+              "resnet50": synth.resnet50_param_numels}[args.model]()
     assert list(largs.numel) == list(expect), "parameter list does not match the model's"
     lws = make_workspace(lc.lars_workspace_bytes(largs.numel), torch)
     trust = torch.empty(largs.n, device="cuda:0")
@@ -248,8 +254,9 @@ def run_train_step(args):
     # LARSCONV_WGRAD_WIDEN sends it through the widening fp32 kernel)
     widened = dom == "wgrad" and os.environ.get("LARSCONV_WGRAD_WIDEN")
     peak = PEAK_MFMA_BF16 if bf16 and not widened else PEAK_MFMA_F32
-    name = "AlexNet-BN" if args.model == "alexnet_bn" else "ResNet-50"
-    n_fc = len(layers) - n_bn
+    name = {"alexnet_bn": "AlexNet-BN", "alexnet": "AlexNet (grouped)", "resnet50": "ResNet-50"}[args.model]
+    n_conv = sum(1 for l in layers if l.cs.h * l.cs.w > 1 and not (l.cs.r == l.cs.h and l.cs.s == l.cs.w and l.cs.pad == 0))
+    n_fc = len(layers) - n_conv
     result = {
         "metric": f"{name} fwd+bwd+LARS images/sec/GPU",
         "value": round(batch / (ms_per_step * 1e-3), 2),
@@ -263,7 +270,7 @@ def run_train_step(args):
         "vs_baseline": None,
         "dtype": "bf16" if bf16 else "f32",
         "data": "synthetic",
-        "config": {"workload": f"{args.model}_train_step_{'bf16' if bf16 else 'fp32'}_batch{batch}_nhwc ({n_bn} convs + {n_fc} fc: fwd, "
+        "config": {"workload": f"{args.model}_train_step_{'bf16' if bf16 else 'fp32'}_batch{batch}_nhwc ({n_conv} convs + {n_fc} fc: fwd, "
                                f"bwd_data, bwd_weight; lars_step over {largs.n} tensors / {sum(largs.numel) / 1e6:.1f}M params)",
                    "batch": batch, "layout": "NHWC",
                    "lars": {"eta": 0.001, "momentum": 0.9, "weight_decay": weight_decay, "lr": lr}},
@@ -302,19 +309,25 @@ def cpu_baseline(model: str, batch: int):
     def data(cs):
         key = cs.key()
         if key not in cache:
-            cache[key] = (synth.normal((cs.n, cs.h, cs.w, cs.c), 1), synth.normal((cs.k, cs.r, cs.s, cs.c), 2),
+            cache[key] = (synth.normal((cs.n, cs.h, cs.w, cs.c), 1), synth.normal((cs.k, cs.r, cs.s, cs.c // cs.groups), 2),
                           synth.normal((cs.n, cs.p, cs.q, cs.k), 3))
         return cache[key]
 
     for cs in shapes:
         data(cs)
-    sizes = synth.alexnet_bn_param_numels() if model == "alexnet_bn" else synth.resnet50_param_numels()
+    sizes = {"alexnet_bn": synth.alexnet_bn_param_numels, "alexnet": synth.alexnet_grouped_param_numels,
+             "resnet50": synth.resnet50_param_numels}[model]()
     w = [synth.normal((n,), 10) for n in sizes]
     g = [synth.normal((n,), 11, std=0.01) for n in sizes]
     v = [np.zeros(n, np.float32) for n in sizes]
     t0 = time.perf_counter()
     for i, cs in enumerate(shapes):
         x, wt, dy = data(cs)
+        if cs.groups > 1:
+            oracle.conv2d_fwd_grouped(x, wt, cs.groups, cs.stride, cs.pad, oracle.NHWC)
+            oracle.conv2d_bwd_data_grouped(dy, wt, cs.groups, (cs.h, cs.w), cs.stride, cs.pad, oracle.NHWC)
+            oracle.conv2d_bwd_weight_grouped(x, dy, cs.groups, (cs.r, cs.s), cs.stride, cs.pad, oracle.NHWC)
+            continue
         oracle.conv2d_fwd(x, wt, cs.stride, cs.pad, oracle.NHWC)
         if i:
             oracle.conv2d_bwd_data(dy, wt, (cs.h, cs.w), cs.stride, cs.pad, oracle.NHWC)
@@ -357,7 +370,11 @@ def run_sweep(args):
     rows = []
     tot = {"fwd": [0.0, 0.0], "bwd_data": [0.0, 0.0], "bwd_weight": [0.0, 0.0]}
     roof_ms = 0.0
-    for idx, (cs, count) in enumerate(synth.resnet50_distinct_shapes(batch), start=1):
+    # after the 20 distinct shapes of the network the paper trains: the six layers only the "v1.5" form of ResNet-50 has
+    # (stride on the 3x3 convolution), labelled rows that do not enter the totals
+    shape_list = [(cs, count, False) for cs, count in synth.resnet50_distinct_shapes(batch)]
+    shape_list += [(cs, 1, True) for cs in synth.resnet50_v15_extra_shapes(batch)]
+    for idx, (cs, count, extra) in enumerate(shape_list, start=1):
         if args.only and idx not in args.only:
             continue
         l = Layer(cs, gen, torch, lc, False, args.dtype == "bf16")
@@ -377,6 +394,8 @@ def run_sweep(args):
         min_bytes = {"fwd": xread + wb + yb, "bwd_data": yb + wb + xb, "bwd_weight": xread + yb + cs.weight_numel * 4}
         row = {"shape": idx, "name": cs.name, "c": cs.c, "k": cs.k, "rs": cs.r, "stride": cs.stride, "hw": cs.h,
                "count": count, "gflop": round(cs.flops / 1e9, 2)}
+        if extra:
+            row["extra"] = "ResNet-50 v1.5 only; not in the totals"
         for p, fn in calls.items():
             if p == "bwd_data" and idx == 1:
                 continue                      # the first layer's input gradient is never needed in a training step
@@ -387,9 +406,10 @@ def run_sweep(args):
             row[p + "_tflops"] = round(tf, 2)
             row[p + "_roof_tflops"] = round(roof, 1)
             row[p + "_frac_of_roof"] = round(tf / roof, 3)
-            tot[p][0] += med * count
-            tot[p][1] += cs.flops * count
-            roof_ms += cs.flops / (roof * 1e12) * 1e3 * count
+            if not extra:
+                tot[p][0] += med * count
+                tot[p][1] += cs.flops * count
+                roof_ms += cs.flops / (roof * 1e12) * 1e3 * count
         rows.append(row)
         log(json.dumps(row))
         del l, ws
@@ -411,7 +431,8 @@ def measure_lars(which: str, n_sets: int, iters: int):
     from paper_1709_05011_amd import larsconv as lc
     from paper_1709_05011_amd import synth
 
-    sizes = synth.resnet50_param_numels() if which == "resnet50" else synth.alexnet_bn_param_numels()
+    sizes = {"alexnet_bn": synth.alexnet_bn_param_numels, "alexnet": synth.alexnet_grouped_param_numels,
+             "resnet50": synth.resnet50_param_numels}[which]()
     gen = torch.Generator(device="cuda:0")
     gen.manual_seed(0x5EED0400)
     sets = []
@@ -556,6 +577,37 @@ def run_full_step(args):
             "peak_memory_GB": round(torch.cuda.max_memory_allocated() / 1e9, 2)}
 
 
+def run_batch_curve(args):
+    """Images per second against the per-GPU batch (the paper's figure of per-GPU speed against batch size, "Benefits of
+    Large-Batch Training": larger local batches make the matrix kernels more efficient): the headline step
+    (convolutions + LARS) and the whole network step at every batch size of the list."""
+    import copy
+    import gc
+
+    import torch
+
+    points = []
+    for b in (args.batches or [16, 32, 64, 128, 256, 512]):
+        a = copy.copy(args)
+        a.batch, a.steps, a.warmup, a.no_cpu, a.graph = b, 5, 2, True, False
+        head = run_train_step(a)
+        gc.collect()
+        torch.cuda.empty_cache()
+        point = {"batch": b, "conv_lars_images_per_s": head["value"], "conv_lars_ms": head["ms_per_step"],
+                 "conv_tflops_all": head["conv_tflops_all"], "conv_frac_of_mfma_peak": head["conv_frac_of_mfma_peak"]}
+        if args.dtype == "f32" and args.model != "alexnet":
+            full = run_full_step(a)
+            point.update({"whole_step_images_per_s": full["value"], "whole_step_ms": full["ms_per_step"]})
+            gc.collect()
+            torch.cuda.empty_cache()
+        log(json.dumps(point))
+        points.append(point)
+    best = max(points, key=lambda p_: p_["conv_lars_images_per_s"])
+    return {"batch_curve": args.model, "dtype": args.dtype, "layout": "NHWC", "points": points,
+            "best_batch_conv_lars": best["batch"],
+            "note": "the paper's M40 peaks at 512 images per GPU and runs out of memory at 1024"}
+
+
 def run_copy_calibration(args):
     """A plain device-to-device copy of known size: what the FETCH_SIZE / WRITE_SIZE counters of rocprofv3 read
     for it gives the factor by which the counters of the other kernels are scaled."""
@@ -591,7 +643,7 @@ def add_secondary_measurements(res, args):
                            "note": "stand-alone on 4 rotating parameter sets: nothing in cache, and the previous call's "
                                    "dirty lines are written back while this one reads"}
     release()
-    if args.dtype != "f32" or args.batch:
+    if args.dtype != "f32" or args.batch or args.model == "alexnet":
         return
     a = copy.copy(args)
     a.steps, a.warmup, a.graph, a.full_step = 5, 2, False, True
@@ -625,23 +677,27 @@ def main():
     ap.add_argument("--no-extras", action="store_true",
                     help="headline only: skip the cold lars_step, whole-step and bf16 legs that follow the timed region")
     ap.add_argument("--cpu-batch", type=int, default=4)
-    ap.add_argument("--model", choices=["resnet50", "alexnet_bn"], default="resnet50",
+    ap.add_argument("--model", choices=["resnet50", "alexnet_bn", "alexnet"], default="resnet50",
                     help="network whose layer shapes and parameter list make the step (default: the metric's ResNet-50)")
     ap.add_argument("--sweep", action="store_true")
     ap.add_argument("--only", type=int, nargs="*", help="sweep: shape numbers to run")
     ap.add_argument("--iters", type=int, default=20, help="timed calls per measurement in the stand-alone modes (after 5 warm-up calls; median reported)")
-    ap.add_argument("--lars", choices=["resnet50", "alexnet_bn"])
+    ap.add_argument("--lars", choices=["resnet50", "alexnet_bn", "alexnet"])
     ap.add_argument("--rotate", type=int, default=1)
     ap.add_argument("--batchnorm", action="store_true", help="batch-normalisation layers alone, GB/s against HBM peak")
     ap.add_argument("--full-step", action="store_true", help="the whole ResNet-50 step: all layers, loss, gradients, LARS")
     ap.add_argument("--graph", action="store_true", help="--full-step: capture the step in a HIP graph and time replays")
     ap.add_argument("--copy-calib", action="store_true", help="run a 1 GiB device copy (counter calibration)")
+    ap.add_argument("--batch-curve", action="store_true", help="images/s against the per-GPU batch (headline step and whole step)")
+    ap.add_argument("--batches", type=int, nargs="*", help="--batch-curve: batch sizes (default 16 .. 512)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py measures one GPU: the hot path built here has no multi-GPU part "
                  "(the gradient all-reduce between backward and lars_step is out of scope); run with --gpus 1")
     if args.copy_calib:
         res = run_copy_calibration(args)
+    elif args.batch_curve:
+        res = run_batch_curve(args)
     elif args.sweep:
         res = run_sweep(args)
     elif args.lars:

@@ -35,6 +35,7 @@ struct Plan {
     // window other than 1x1): operands are widened to fp32 copies, the fp32 pass runs on them, the result is
     // rounded back to bf16.  Same arithmetic class: exact products of bf16 values, fp32 sums.
     bool via_f32 = false;
+    bool phases = false;             // strided window other than 1x1: backward-data as one GEMM per stride phase
     size_t f_a = 0, f_b = 0, f_out = 0, f_ws = 0, f_ws_bytes = 0;
     // few-channel stride-2 layer (a network's first convolution) run as a stride-1 convolution over 2x2 pixel
     // blocks: the unfolded input, the filter (or its gradient) in block form, the inner call's workspace
@@ -130,6 +131,86 @@ GemmConv gemm_bwd_data(const lc_conv_desc* d, int P, int Q) {
     return g;
 }
 
+// Backward-data through a strided window other than 1x1, phase by phase.  dx pixel (h, w) only receives the taps
+// with r = (h + pad_h) mod stride_h (mod stride_h) and s likewise, so the pixels of one phase (a, b) -- h = h0 + stride_h*po,
+// w = w0 + stride_w*qo -- are a stride-1 backward-data problem over dy with the Ra x Sb sub-filter r = a + stride_h*i,
+// s = b + stride_w*j:  dx[h0 + sh*po] = sum_i dy[po + base - i] * w[a + sh*i], base = (h0 + pad_h - a) / sh.  Its GEMM
+// has one row per dx pixel of the phase and scatters to the stride grid of dx, offset by (h0, w0).  No multiplication
+// is spent on the zeros a "dilated" read of dy would insert; the phases together do the forward pass's work.
+struct Phase {
+    GemmConv g;
+    int a, b, Ra, Sb;
+    size_t w_off;        // elements into the re-ordered filter region
+    long long d_off;     // elements into dx: (h0 * W + w0) * C
+};
+constexpr int kMaxPhases = 16;
+
+int plan_phases(const lc_conv_desc* d, int P, int Q, Phase* out, bool* all_covered) {
+    const int sh = d->stride_h, sw = d->stride_w;
+    int n = 0;
+    size_t w_off = 0;
+    *all_covered = true;
+    for (int a = 0; a < sh; ++a)
+        for (int b = 0; b < sw; ++b) {
+            const int Ra = a < d->r ? (d->r - 1 - a) / sh + 1 : 0, Sb = b < d->s ? (d->s - 1 - b) / sw + 1 : 0;
+            const int h0 = (((a - d->pad_h) % sh) + sh) % sh, w0 = (((b - d->pad_w) % sw) + sw) % sw;
+            const int Ha = h0 < d->h ? (d->h - h0 + sh - 1) / sh : 0, Wb = w0 < d->w ? (d->w - w0 + sw - 1) / sw : 0;
+            if (Ha == 0 || Wb == 0) continue;                 // no dx pixel has this phase
+            if (Ra == 0 || Sb == 0) {                         // pixels no tap reaches: they stay zero
+                *all_covered = false;
+                continue;
+            }
+            Phase& ph = out[n++];
+            ph.a = a;
+            ph.b = b;
+            ph.Ra = Ra;
+            ph.Sb = Sb;
+            ph.w_off = w_off;
+            w_off += (size_t)d->k * d->c * Ra * Sb;
+            ph.d_off = ((long long)h0 * d->w + w0) * d->c;
+            GemmConv g = {};
+            g.M = d->n * Ha * Wb;
+            g.N = d->c;
+            g.Kg = Ra * Sb * d->k;
+            g.Hi = P;
+            g.Wi = Q;
+            g.Ci = d->k;
+            g.Po = Ha;
+            g.Qo = Wb;
+            g.R = Ra;
+            g.S = Sb;
+            g.sh = g.sw = 1;
+            g.ph = Ra - 1 - (h0 + d->pad_h - a) / sh;
+            g.pw = Sb - 1 - (w0 + d->pad_w - b) / sw;
+            g.dh = g.dw = 1;
+            g.ldd = d->c;
+            g.scatter = 1;
+            g.Ho = d->h;
+            g.Wo = d->w;
+            g.esh = sh;
+            g.esw = sw;
+            g.bf16 = d->dtype == LC_BF16;
+            ph.g = g;
+        }
+    return n;
+}
+
+// Whether the phase form applies (shape only): a strided window that is not the 1x1 case, at most 4 x 4 phases, and
+// every phase a problem the main kernel's scatter epilogue takes.
+bool phases_ok(const lc_conv_desc* d, int P, int Q) {
+    static const bool off = getenv("LARSCONV_NO_STRIDE_PHASES") != nullptr;       // comparison runs
+    if (off || (d->stride_h == 1 && d->stride_w == 1) || d->stride_h > 4 || d->stride_w > 4) return false;
+    if (d->r == 1 && d->s == 1 && d->pad_h == 0 && d->pad_w == 0) return false;
+    if ((long long)d->n * d->h * d->w > INT_MAX) return false;
+    Phase ph[kMaxPhases];
+    bool covered;
+    const int n = plan_phases(d, P, Q, ph, &covered);
+    if (n == 0) return false;
+    for (int i = 0; i < n; ++i)
+        if (!lc_conv_gemm_scatter_ok(ph[i].g)) return false;
+    return true;
+}
+
 lc_conv_desc as_f32(const lc_conv_desc* d) {
     lc_conv_desc f = *d;
     f.dtype = LC_F32;
@@ -217,7 +298,8 @@ lc_status make_plan(const lc_conv_desc* d, lc_pass pass, Plan* pl) {
     pl->cpad = pl->bf16 ? (d->c + 7) & ~7 : (d->c + 3) & ~3;
     const bool pad = pl->cpad != d->c;
     Regions rg;
-    if (pass == LC_PASS_BWD_DATA && pl->bf16) {
+    pl->phases = pass == LC_PASS_BWD_DATA && phases_ok(d, pl->P, pl->Q);
+    if (pass == LC_PASS_BWD_DATA && pl->bf16 && !pl->phases) {
         const GemmConv g = gemm_bwd_data(d, pl->P, pl->Q);
         if (!lc_conv_gemm_bf16_native(g)) {        // pointers are empty here: a question of shape only
             pl->via_f32 = true;
@@ -250,7 +332,17 @@ lc_status make_plan(const lc_conv_desc* d, lc_pass pass, Plan* pl) {
             pl->out_nhwc = rg.take(nx * es);
         }
         pl->wt = rg.take(nw * es);
-        pl->sk_bytes = lc_conv_gemm_workspace(gemm_bwd_data(d, pl->P, pl->Q));
+        if (pl->phases) {                                // the phases run one after the other and share the region
+            Phase ph[kMaxPhases];
+            bool covered;
+            const int n = plan_phases(d, pl->P, pl->Q, ph, &covered);
+            for (int i = 0; i < n; ++i) {
+                const size_t b = lc_conv_gemm_workspace(ph[i].g);
+                if (b > pl->sk_bytes) pl->sk_bytes = b;
+            }
+        } else {
+            pl->sk_bytes = lc_conv_gemm_workspace(gemm_bwd_data(d, pl->P, pl->Q));
+        }
         if (pl->sk_bytes) pl->sk = rg.take(pl->sk_bytes);
     } else {
         if (pl->nchw) {
@@ -523,8 +615,28 @@ extern "C" lc_status conv2d_bwd_data(const lc_conv_desc* d, const void* dy, cons
         wsrc = at(workspace, pl.b_nhwc);
         dxdst = at(workspace, pl.out_nhwc);
     }
-    // filter of the backward convolution: [c][R-1-r][S-1-s][k]
     void* wt = at(workspace, pl.wt);
+    if (pl.phases) {
+        Phase ph[kMaxPhases];
+        bool covered;
+        const int n = plan_phases(d, pl.P, pl.Q, ph, &covered);
+        if (!covered) lc_zero_bytes(dxdst, (size_t)d->n * d->h * d->w * d->c * pl.esize, stream);
+        for (int i = 0; i < n; ++i) {
+            void* wp = static_cast<char*>(wt) + ph[i].w_off * pl.esize;
+            lc_filter_for_bwd_data_phase(wsrc, wp, d->k, d->c, d->r, d->s, ph[i].a, ph[i].b, d->stride_h, d->stride_w, ph[i].Ra,
+                                         ph[i].Sb, pl.esize, stream);
+            GemmConv g = ph[i].g;
+            g.a = dys;
+            g.b = wp;
+            g.d = static_cast<char*>(dxdst) + ph[i].d_off * pl.esize;
+            g.partial = pl.sk_bytes ? reinterpret_cast<float*>(at(workspace, pl.sk)) : nullptr;
+            st = lc_launch_conv_gemm(g, stream);
+            if (st != LC_OK) return st;
+        }
+        if (pl.nchw) lc_nhwc_to_nchw(dxdst, dx, d->n, d->c, d->h * d->w, pl.esize, stream);
+        return lc_end_call();
+    }
+    // filter of the backward convolution: [c][R-1-r][S-1-s][k]
     lc_filter_for_bwd_data(wsrc, wt, d->k, d->c, d->r, d->s, pl.esize, stream);
 
     GemmConv g = gemm_bwd_data(d, pl.P, pl.Q);

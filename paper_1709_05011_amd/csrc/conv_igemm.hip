@@ -76,22 +76,15 @@ __device__ __forceinline__ void store_tile(const GemmConv& p, const f32x16 (&acc
                     if (col < p.N) drow[col] = OutT<BF16OUT>::cvt(acc[i][j][v]);
                 }
             } else {
+                // the row's pixel on the stride grid; the pixels between the grid belong to the caller (cleared, or
+                // written by the other stride phases)
                 const int qo = row % p.Qo, t = row / p.Qo;
                 const int po = t % p.Po, img = t / p.Po;
-                for (int dy = 0; dy < p.esh; ++dy) {
-                    const int h = po * p.esh + dy;
-                    if (h >= p.Ho) break;
-                    for (int dx = 0; dx < p.esw; ++dx) {
-                        const int w = qo * p.esw + dx;
-                        if (w >= p.Wo) break;
-                        O* drow = D + (((long long)img * p.Ho + h) * p.Wo + w) * p.ldd;
-                        const bool corner = (dy | dx) == 0;
+                O* drow = D + (((long long)img * p.Ho + (long long)po * p.esh) * p.Wo + (long long)qo * p.esw) * p.ldd;
 #pragma unroll
-                        for (int j = 0; j < TN; ++j) {
-                            const int col = col0 + j * 32 + (lane & 31);
-                            if (col < p.N) drow[col] = OutT<BF16OUT>::cvt(corner ? acc[i][j][v] : 0.f);
-                        }
-                    }
+                for (int j = 0; j < TN; ++j) {
+                    const int col = col0 + j * 32 + (lane & 31);
+                    if (col < p.N) drow[col] = OutT<BF16OUT>::cvt(acc[i][j][v]);
                 }
             }
         }
@@ -1675,6 +1668,13 @@ size_t lc_conv_gemm_workspace(const GemmConv& p) {
 }
 
 bool lc_conv_gemm_bf16_native(const GemmConv& p) { return p.bf16 && use_main_kernel(p); }
+
+bool lc_conv_gemm_scatter_ok(const GemmConv& p) {
+    if (!p.scatter || !use_main_kernel(p) || p.Ci < (p.bf16 ? 32 : 16)) return false;
+    // (the scatter epilogue addresses the result relative to the tile's first pixel with 32-bit byte offsets)
+    const long long span = (128LL / ((long long)p.Po * p.Qo) + 2) * p.Ho * p.Wo * p.ldd * (p.bf16 ? 2 : 4);
+    return span < 0x7fff0000LL;
+}
 
 lc_status lc_launch_conv_gemm(const GemmConv& p, hipStream_t stream) {
     if (p.bf16) {

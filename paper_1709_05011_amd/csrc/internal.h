@@ -37,6 +37,9 @@ void lc_nhwc_to_nchw(const void* src, void* dst, int n, int c, int hw, int esize
 // Filter re-ordering.  All take and give fp32 or bf16 by esize.
 //  KRSC -> [c][R-1-r][S-1-s][k]  (the filter of the backward-data convolution)
 void lc_filter_for_bwd_data(const void* w_krsc, void* out, int k, int c, int r, int s, int esize, hipStream_t stream);
+//  the taps r = a, a + sh, ... / s = b, b + sw, ... of it (ra x sb of them) in the same order: one stride phase
+void lc_filter_for_bwd_data_phase(const void* w_krsc, void* out, int k, int c, int r, int s, int a, int b, int sh, int sw, int ra,
+                                  int sb, int esize, hipStream_t stream);
 //  pad the channel dimension (innermost) of an [rows][c] array with zeros to [rows][cpad]
 // few-channel stride-2 convolution as a stride-1 convolution over 2x2 pixel blocks (see layout.hip)
 void lc_stem_unfold(const void* x, void* u, int n, int c, int h, int w, int q, int hb, int sb, int cu, int eph, int epw, int esize,
@@ -79,6 +82,7 @@ struct GemmConv {
 lc_status lc_launch_conv_gemm(const GemmConv& p, hipStream_t stream);
 extern "C" int lc_selftest_division(int max_d);   // host check of the multiply-high division constants (0 = all good)
 bool lc_conv_gemm_bf16_native(const GemmConv& p);   // can the bf16 MFMA kernel take this problem (shape and alignment)?
+bool lc_conv_gemm_scatter_ok(const GemmConv& p);    // can the main kernel's scatter epilogue take this problem?
 size_t lc_conv_gemm_workspace(const GemmConv& p);   // bytes `partial` must hold for this problem (0 = none)
 
 // Filter gradient: D[k][j] = sum_m dY[m][k] * Xg(m, j), m = (img, p, q), j = (r, s, c); the reduction

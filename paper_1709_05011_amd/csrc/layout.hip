@@ -96,6 +96,24 @@ __global__ void filter_bwd_data_kernel(const T* __restrict__ in, T* __restrict__
     }
 }
 
+// Sub-filter of one stride phase of a strided backward-data pass, re-ordered like the whole filter above:
+// out[c][Ra-1-i][Sb-1-j][k] = in[k][a + sh*i][b + sw*j][c]  (the taps r = a, a + sh, ... and s = b, b + sw, ...).
+template <typename T>
+__global__ void filter_bwd_data_phase_kernel(const T* __restrict__ in, T* __restrict__ out, int K, int C, int R, int S, int a, int b,
+                                             int sh, int sw, int Ra, int Sb) {
+    const size_t total = (size_t)K * C * Ra * Sb;
+    for (size_t o = blockIdx.x * (size_t)blockDim.x + threadIdx.x; o < total; o += (size_t)gridDim.x * blockDim.x) {
+        const int k = (int)(o % K);
+        size_t t = o / K;
+        const int j2 = (int)(t % Sb);
+        t /= Sb;
+        const int i2 = (int)(t % Ra);
+        const int c = (int)(t / Ra);
+        const int r = a + sh * (Ra - 1 - i2), s2 = b + sw * (Sb - 1 - j2);
+        out[o] = in[(((size_t)k * R + r) * S + s2) * C + c];
+    }
+}
+
 template <typename T>
 __global__ void pad_channels_kernel(const T* __restrict__ src, T* __restrict__ dst, size_t rows, int c, int cpad) {
     const size_t total = rows * (size_t)cpad;
@@ -332,6 +350,18 @@ void lc_filter_for_bwd_data(const void* w_krsc, void* out, int k, int c, int r, 
     else
         hipLaunchKernelGGL(filter_bwd_data_kernel<uint16_t>, dim3(grid_for(total, 256)), dim3(256), 0, stream,
                            static_cast<const uint16_t*>(w_krsc), static_cast<uint16_t*>(out), k, c, r, s);
+}
+
+void lc_filter_for_bwd_data_phase(const void* w_krsc, void* out, int k, int c, int r, int s, int a, int b, int sh, int sw, int ra,
+                                  int sb, int esize, hipStream_t stream) {
+    const size_t total = (size_t)k * c * ra * sb;
+    if (!total) return;
+    if (esize == 4)
+        hipLaunchKernelGGL(filter_bwd_data_phase_kernel<float>, dim3(grid_for(total, 256)), dim3(256), 0, stream,
+                           static_cast<const float*>(w_krsc), static_cast<float*>(out), k, c, r, s, a, b, sh, sw, ra, sb);
+    else
+        hipLaunchKernelGGL(filter_bwd_data_phase_kernel<uint16_t>, dim3(grid_for(total, 256)), dim3(256), 0, stream,
+                           static_cast<const uint16_t*>(w_krsc), static_cast<uint16_t*>(out), k, c, r, s, a, b, sh, sw, ra, sb);
 }
 
 // Strided 2-D copy (a channel slice of an activation tensor to or from a dense one): element (row, i) of width-V vectors.

@@ -41,6 +41,18 @@ SHAPES = {
     "blocks_7x7_s2_p0_c1": (2, 1, 21, 20, 16, 7, 7, 2, 0),
     "blocks_rect_7x3_s2_c2": (2, 2, 17, 14, 12, 7, 3, 2, (3, 1)),
     "blocks_7x7_s2_p3_odd_image": (1, 3, 29, 31, 72, 7, 7, 2, 3),
+    # strided windows other than 1x1: backward-data runs one GEMM per stride phase (16 or more filters, a multiple of 4)
+    "phases_3x3_s2_p1_v15": (2, 128, 14, 14, 128, 3, 3, 2, 1),
+    "phases_3x3_s2_p1_odd_image": (3, 32, 15, 13, 64, 3, 3, 2, 1),
+    "phases_5x5_s2_p2": (2, 16, 13, 12, 32, 5, 5, 2, 2),
+    "phases_3x3_s3_p0": (2, 8, 14, 11, 16, 3, 3, 3, 0),
+    "phases_2x2_s2_p0": (2, 24, 12, 10, 40, 2, 2, 2, 0),
+    "phases_4x4_s2_p1": (2, 16, 12, 12, 32, 4, 4, 2, 1),
+    "phases_stride_1x2": (2, 16, 9, 12, 32, 3, 3, (1, 2), (1, 1)),
+    "phases_some_rows_without_taps": (2, 16, 9, 9, 32, 1, 3, 2, (0, 1)),      # window height 1 at stride 2: odd rows of dx stay zero
+    "phases_pad_beyond_window": (2, 8, 7, 7, 16, 2, 2, 2, 2),
+    "phases_4x4_s4_p0": (1, 8, 16, 16, 32, 4, 4, 4, 0),
+    "phases_7x7_s2_many_channels": (2, 20, 19, 18, 24, 7, 7, 2, 3),
 }
 
 
@@ -112,8 +124,8 @@ def test_filter_gradient_is_bit_reproducible():
 
 
 # ---- full benchmark sizes (batch 256, the launch configuration bench.py times): sampled outputs ----
-FULL = {c.name: c for c in synth.resnet50_convs(256)}
-FULL_CASES = ["conv1", "res2a_3x3", "res3a_1x1a", "res4a_proj", "res5b_3x3", "res5c_1x1a"]
+FULL = {c.name: c for c in synth.resnet50_convs(256) + synth.resnet50_v15_extra_shapes(256)}
+FULL_CASES = ["conv1", "res2a_3x3", "res3a_1x1a", "res4a_proj", "res5b_3x3", "res5c_1x1a", "v15_res3a_3x3s2", "v15_res5a_3x3s2"]
 
 
 @pytest.mark.parametrize("name", FULL_CASES)

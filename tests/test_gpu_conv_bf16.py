@@ -23,7 +23,12 @@ SHAPES = {
     "1x1_stride2_odd": (2, 64, 15, 15, 128, 1, 1, 2, 0),
     "stem_7x7_s2": (2, 3, 30, 30, 64, 7, 7, 2, 3),            # NHWC: 2x2 pixel blocks; NCHW: c padded to 8; backward-data through fp32
     "5x5_p2": (2, 16, 13, 13, 32, 5, 5, 1, 2),
-    "3x3_stride2": (2, 32, 17, 17, 48, 3, 3, 2, 1),           # strided window: backward-data through fp32
+    "3x3_stride2": (2, 32, 17, 17, 48, 3, 3, 2, 1),           # strided window: backward-data phase by phase
+    "3x3_stride2_k24": (2, 32, 17, 17, 24, 3, 3, 2, 1),       # fewer filters than a k-step: backward-data through fp32
+    "phases_3x3_s2_p1_v15": (2, 128, 14, 14, 128, 3, 3, 2, 1),
+    "phases_3x3_s2_odd_channels_out": (3, 33, 15, 13, 64, 3, 3, 2, 1),     # dx rows of 33 channels: 2-byte stores
+    "phases_5x5_s2_p2": (2, 16, 13, 12, 32, 5, 5, 2, 2),
+    "phases_some_rows_without_taps": (2, 16, 9, 9, 32, 1, 3, 2, (0, 1)),
     "odd_channels": (2, 6, 9, 9, 10, 3, 3, 1, 1),             # k = 10: backward-data through fp32, scalar filter gradient
     "k8_c24": (2, 24, 9, 9, 8, 3, 3, 1, 1),
     "full_window_fc": (4, 16, 6, 6, 40, 6, 6, 1, 0),
