@@ -95,6 +95,7 @@ class Layer:
         self.y = torch.empty((cs.n, cs.p, cs.q, cs.k), device=dev, dtype=act)
         self.dx = None if first else torch.empty((cs.n, cs.h, cs.w, cs.c), device=dev, dtype=act)
         self.dw = torch.empty((cs.k, cs.r, cs.s, cg), device=dev)
+        self.dw_sq = torch.empty(lc.conv2d_bwd_weight_sq_count(self.desc), dtype=torch.float64, device=dev)   # pieces of sum dw^2
         self.ws_bytes = max(lc.conv2d_workspace_bytes(self.desc, p) for p in range(3))
 
 
@@ -167,6 +168,14 @@ def run_train_step(args):
         plow += [l.w] + [None] * len(extra)
         pg += [l.dw] + [torch.randn(k, generator=gen, device="cuda:0") * 1e-2 for _ in extra]
     pv = [torch.zeros_like(t) for t in pw]
+    # the squared norm of every filter gradient comes out of its backward-weight pass (conv2d_bwd_weight_sq) and is handed
+    # to the update (lars_step_pre), which then reads those gradients once instead of twice; --plain-norms: the plain calls
+    fused_norms = not args.plain_norms
+    psq, psq_n = [], []
+    for i, l in enumerate(layers):
+        n_extra = 2 if i < n_bn else 1
+        psq += [l.dw_sq if fused_norms else None] + [None] * n_extra
+        psq_n += [l.dw_sq.numel() if fused_norms else 0] + [0] * n_extra
     # bf16 run: fp32 master weights and momentum; lars_step also writes the bf16 weights the convolutions read
     largs = lc.LarsArgs(pw, pg, pv, w_lowp=plow if bf16 else None)
     expect = {"alexnet_bn": synth.alexnet_bn_param_numels, "alexnet": synth.alexnet_grouped_param_numels,
@@ -205,9 +214,17 @@ def run_train_step(args):
             if not l.first:
                 timed(timer, ("bwd_data", gemm_kernel_of(l, "bwd_data"), l.cs.flops),
                       lambda l=l: lc.conv2d_bwd_data(l.desc, l.dy, l.w, l.dx, ws))
-            timed(timer, ("bwd_weight", "wgrad", l.cs.flops),
-                  lambda l=l: lc.conv2d_bwd_weight(l.desc, l.x, l.dy, l.dw, ws))
-        timed(timer, ("lars", "lars", 0), lambda: lc.lars_step(largs, 0.001, 0.9, weight_decay, lr, trust, lws))
+            if fused_norms:
+                timed(timer, ("bwd_weight", "wgrad", l.cs.flops),
+                      lambda l=l: lc.conv2d_bwd_weight_sq(l.desc, l.x, l.dy, l.dw, l.dw_sq, ws))
+            else:
+                timed(timer, ("bwd_weight", "wgrad", l.cs.flops),
+                      lambda l=l: lc.conv2d_bwd_weight(l.desc, l.x, l.dy, l.dw, ws))
+        if fused_norms:
+            timed(timer, ("lars", "lars", 0), lambda: lc.lars_step_pre(largs, 0.001, 0.9, weight_decay, lr, psq, psq_n, trust_out=trust,
+                                                                     workspace=lws))
+        else:
+            timed(timer, ("lars", "lars", 0), lambda: lc.lars_step(largs, 0.001, 0.9, weight_decay, lr, trust, lws))
 
     for _ in range(args.warmup):
         step()
@@ -286,6 +303,7 @@ def run_train_step(args):
         # in the 256 MB Infinity Cache, so this is an effective rate, not achieved HBM bandwidth ("cold" below is)
         "lars": {"in_step": {"ms": round(lars_ms, 4), "GBps_effective": round(lars_gbps, 1),
                              "frac_of_hbm_peak_effective": round(lars_gbps / PEAK_HBM, 4),
+                             "g_norms": "from backward-weight (24 bytes per parameter move)" if fused_norms else "computed by lars_step",
                              "note": "cache-assisted: g was just written by backward-weight"},
                  "bytes_per_param": lars_bpp},
         "pass_ms_per_step": pass_ms,
@@ -674,6 +692,8 @@ def main():
     ap.add_argument("--dtype", choices=["f32", "bf16"], default="f32",
                     help="bf16: BASELINE configs[4] (bf16 activations/weights, fp32 sums, fp32 master weights; batch 512)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
+    ap.add_argument("--plain-norms", action="store_true",
+                    help="conv2d_bwd_weight + lars_step instead of conv2d_bwd_weight_sq + lars_step_pre (the update reads every gradient twice)")
     ap.add_argument("--no-extras", action="store_true",
                     help="headline only: skip the cold lars_step, whole-step and bf16 legs that follow the timed region")
     ap.add_argument("--cpu-batch", type=int, default=4)

@@ -94,6 +94,16 @@ lc_status conv2d_bwd_data(const lc_conv_desc* desc, const void* dy, const void* 
 lc_status conv2d_bwd_weight(const lc_conv_desc* desc, const void* x, const void* dy, float* dw,
                             void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/* conv2d_bwd_weight that also hands over the squared Euclidean norm of the gradient it wrote, the quantity the
+ * layer-wise rule of "Scaling up Batch Size" needs of every gradient tensor: dw_sq_pieces (DEVICE, 8-byte aligned)
+ * receives conv2d_bwd_weight_sq_count(desc) doubles whose sum, taken in index order, is sum dw^2.  Where the pass ends
+ * in the fixed-order sum of its batch splits (every larger layer) the pieces come out of that kernel at no extra
+ * memory traffic; otherwise one more small kernel reads dw.  Everything else as conv2d_bwd_weight; the pieces are
+ * bit-identical from run to run.  conv2d_bwd_weight_sq_count returns 0 for an invalid descriptor. */
+size_t conv2d_bwd_weight_sq_count(const lc_conv_desc* desc);
+lc_status conv2d_bwd_weight_sq(const lc_conv_desc* desc, const void* x, const void* dy, float* dw, double* dw_sq_pieces,
+                               void* workspace, size_t workspace_bytes, void* hip_stream);
+
 /* Scratch bytes lars_step needs for this list of tensor sizes (HOST array).  0 on invalid input. */
 size_t lars_workspace_bytes(int n_tensors, const int64_t* numel);
 
@@ -127,6 +137,20 @@ lc_status lars_step_ex(int n_tensors, float* const* w, const float* const* g, fl
                        const float* eta_per_tensor, const float* weight_decay_per_tensor, const uint8_t* skip,
                        float* trust_out, void* const* w_lowp_out,
                        void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* lars_step_ex that takes sum g^2 of some tensors from where their gradients were written (conv2d_bwd_weight_sq), so
+ * that the norm pass does not read those gradients again: 24 instead of 28 bytes per parameter of such tensors.
+ * g_sq_pieces: HOST array of n_tensors DEVICE pointers (8-byte aligned), g_sq_counts: HOST array of n_tensors counts;
+ * for tensor l with a non-null pointer and a positive count, ||g_l||^2 is the sum of those doubles in index order and
+ * g_l is only read by the update pass; for the others (null / 0) the norm is computed here as in lars_step_ex.  Both
+ * arrays NULL: lars_step_ex.  The pieces must describe the g_l passed in the same call.  Trust ratios agree with
+ * lars_step_ex to rounding (the sums are taken in a different order, both in double). */
+lc_status lars_step_pre(int n_tensors, float* const* w, const float* const* g, float* const* v,
+                        const int64_t* numel, float eta, float momentum, float weight_decay, float lr,
+                        const float* eta_per_tensor, const float* weight_decay_per_tensor, const uint8_t* skip,
+                        const double* const* g_sq_pieces, const int64_t* g_sq_counts,
+                        float* trust_out, void* const* w_lowp_out,
+                        void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /* lars_step_ex for callers that cannot allocate device memory or have none to pass: code under HIP graph capture,
  * tight serving loops, harnesses that forbid hipMalloc.  Same arguments, results and errors as lars_step_ex without

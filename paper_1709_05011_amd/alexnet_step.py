@@ -72,6 +72,11 @@ class AlexNetStep:
         self._lars = lc.LarsArgs([self.params[k] for k in names], [self.grads[k] for k in names], [self.velocity[k] for k in names])
         self._lars_ws = torch.empty(max(lc.lars_workspace_bytes(self._lars.numel), 256), dtype=torch.uint8, device=device)
         self.trust = torch.zeros(len(names), **f32)
+        # the squared norm of every filter gradient comes out of its backward-weight pass and is handed to the update
+        self.gsq = {L["name"] + ".w": torch.zeros(lc.conv2d_bwd_weight_sq_count(L["desc"]), dtype=torch.float64, device=device)
+                    for L in self.conv_layers + self.fc_layers}
+        self._gsq_list = [self.gsq.get(k) for k in names]
+        self._gsq_counts = [0 if t is None else t.numel() for t in self._gsq_list]
         self.logits = self.fc_layers[-1]["z"]
         self.dlogits = torch.empty((batch, classes), **f32)
         self.loss = torch.zeros(1, **f32)
@@ -113,7 +118,7 @@ class AlexNetStep:
                 lc.relu_bwd(L["z"], d_out, dz, dz.numel())
                 d_out = dz
             lc.bias_grad(d_out, self.grads[name + ".b"], n, d.k)
-            lc.conv2d_bwd_weight(d, L["x"], d_out, self.grads[name + ".w"], self._ws)
+            lc.conv2d_bwd_weight_sq(d, L["x"], d_out, self.grads[name + ".w"], self.gsq[name + ".w"], self._ws)
             dx = torch.empty_like(L["x"])
             lc.conv2d_bwd_data(d, d_out, self.params[name + ".w"], dx, self._ws)
             d_out = dx
@@ -127,14 +132,15 @@ class AlexNetStep:
             dz = torch.empty_like(L["z"])
             lc.batchnorm_bwd_ex(L["z"], d_out, self.params[name + ".gamma"], self.params[name + ".beta"], L["mean"], L["invstd"], dz,
                                 self.grads[name + ".gamma"], self.grads[name + ".beta"], n, d.k, p, q, True, NHWC, self._ws)
-            lc.conv2d_bwd_weight(d, L["x"], dz, self.grads[name + ".w"], self._ws)
+            lc.conv2d_bwd_weight_sq(d, L["x"], dz, self.grads[name + ".w"], self.gsq[name + ".w"], self._ws)
             if i > 0:
                 dx = torch.empty_like(L["x"])
                 lc.conv2d_bwd_data(d, dz, self.params[name + ".w"], dx, self._ws)
                 d_out = dx
 
     def lars(self, eta: float, momentum: float, weight_decay: float, lr: float) -> None:
-        lc.lars_step(self._lars, eta, momentum, weight_decay, lr, self.trust, self._lars_ws)
+        lc.lars_step_pre(self._lars, eta, momentum, weight_decay, lr, self._gsq_list, self._gsq_counts, trust_out=self.trust,
+                         workspace=self._lars_ws)
 
     def step(self, x: torch.Tensor, labels: torch.Tensor, eta: float, momentum: float, weight_decay: float, lr: float) -> torch.Tensor:
         loss = self.forward(x, labels)

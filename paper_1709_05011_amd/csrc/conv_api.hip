@@ -652,9 +652,22 @@ extern "C" lc_status conv2d_bwd_data(const lc_conv_desc* d, const void* dy, cons
     return lc_end_call();
 }
 
-extern "C" lc_status conv2d_bwd_weight(const lc_conv_desc* d, const void* x, const void* dy, float* dw,
-                                       void* workspace, size_t workspace_bytes, void* hip_stream) {
-    if (d && d->groups > 1) return run_groups(d, LC_PASS_BWD_WEIGHT, x, dy, dw, workspace, workspace_bytes, hip_stream);
+namespace {
+
+// Whether the pass ends in the split reduction writing dw itself (the only place the squared norm comes for free).
+bool wgrad_sq_fused(const lc_conv_desc* d, const Plan& pl) { return d->groups <= 1 && !pl.blocks && !pl.nchw && !pl.wgrad_direct; }
+
+// conv2d_bwd_weight; sq (may be null) receives the pieces of dw's squared norm.
+lc_status bwd_weight_impl(const lc_conv_desc* d, const void* x, const void* dy, float* dw, double* sq, void* workspace,
+                          size_t workspace_bytes, void* hip_stream) {
+    if (d && d->groups > 1) {
+        const lc_status gs = run_groups(d, LC_PASS_BWD_WEIGHT, x, dy, dw, workspace, workspace_bytes, hip_stream);
+        if (gs != LC_OK || !sq) return gs;
+        lc_begin_call();
+        lc_sq_partials(dw, (size_t)d->k * (d->c / d->groups) * d->r * d->s, sq, static_cast<hipStream_t>(hip_stream));
+        return lc_end_call();
+    }
+    const size_t dw_numel = d ? (size_t)d->k * d->c * d->r * d->s : 0;      // (before the descriptor is canonicalised)
     lc_conv_desc canon;
     d = whole_window_as_1x1(d, &canon);
     Plan pl;
@@ -671,9 +684,10 @@ extern "C" lc_status conv2d_bwd_weight(const lc_conv_desc* d, const void* x, con
         lc_stem_unfold(x, u, d->n, d->c, d->h, d->w, pl.Q, pl.HB, pl.SB, pl.CU, pl.eph, pl.epw, pl.esize, stream);
         st = lc_end_call();
         if (st != LC_OK) return st;
-        st = conv2d_bwd_weight(&pl.inner, u, dy, dwu, pl.s_ws_bytes ? at(workspace, pl.s_ws) : nullptr, pl.s_ws_bytes, hip_stream);
+        st = bwd_weight_impl(&pl.inner, u, dy, dwu, nullptr, pl.s_ws_bytes ? at(workspace, pl.s_ws) : nullptr, pl.s_ws_bytes, hip_stream);
         if (st != LC_OK) return st;
         lc_stem_filter_grad(dwu, dw, d->k, d->r, d->s, d->c, pl.RB, pl.CU, pl.eh, pl.ew, stream);
+        if (sq) lc_sq_partials(dw, dw_numel, sq, stream);
         return lc_end_call();
     }
 
@@ -714,11 +728,42 @@ extern "C" lc_status conv2d_bwd_weight(const lc_conv_desc* d, const void* x, con
     g.d = pl.wgrad_direct ? dwdst : reinterpret_cast<float*>(at(workspace, pl.part));
     st = lc_launch_wgrad_f32(g, stream);
     if (st != LC_OK) return st;
+    const bool fused = sq && wgrad_sq_fused(d, pl);
     if (!pl.wgrad_direct)
-        lc_reduce_splits(g.d, dwdst, pl.splits, (size_t)d->k * g.J, pl.cpad, d->c, stream);
+        lc_reduce_splits(g.d, dwdst, pl.splits, (size_t)d->k * g.J, pl.cpad, d->c, fused ? sq : nullptr, stream);
     if (pl.nchw) lc_nhwc_to_nchw(dwdst, dw, d->k, d->c, d->r * d->s, 4, stream);
+    if (sq && !fused) lc_sq_partials(dw, dw_numel, sq, stream);
     return lc_end_call();
 }
+
+}  // namespace
+
+extern "C" lc_status conv2d_bwd_weight(const lc_conv_desc* d, const void* x, const void* dy, float* dw,
+                                       void* workspace, size_t workspace_bytes, void* hip_stream) {
+    return bwd_weight_impl(d, x, dy, dw, nullptr, workspace, workspace_bytes, hip_stream);
+}
+
+extern "C" size_t conv2d_bwd_weight_sq_count(const lc_conv_desc* d) {
+    if (!d) return 0;
+    int P, Q;
+    if (check_desc(d, &P, &Q) != LC_OK) return 0;
+    const size_t numel = (size_t)d->k * (d->groups > 1 ? d->c / d->groups : d->c) * d->r * d->s;
+    if (d->groups > 1) return lc_sq_partials_blocks(numel);
+    lc_conv_desc canon;
+    const lc_conv_desc* dc = whole_window_as_1x1(d, &canon);
+    Plan pl;
+    if (make_plan(dc, LC_PASS_BWD_WEIGHT, &pl) != LC_OK) return 0;
+    if (wgrad_sq_fused(dc, pl)) return lc_reduce_splits_blocks((size_t)dc->k * dc->r * dc->s * pl.cpad);
+    return lc_sq_partials_blocks(numel);
+}
+
+extern "C" lc_status conv2d_bwd_weight_sq(const lc_conv_desc* d, const void* x, const void* dy, float* dw, double* dw_sq_pieces,
+                                          void* workspace, size_t workspace_bytes, void* hip_stream) {
+    if (!dw_sq_pieces) return LC_ERR_NULL;
+    if ((uintptr_t)dw_sq_pieces & 7) return LC_ERR_ALIGN;
+    return bwd_weight_impl(d, x, dy, dw, dw_sq_pieces, workspace, workspace_bytes, hip_stream);
+}
+
 
 extern "C" const char* lc_status_string(lc_status status) {
     switch (status) {

@@ -50,7 +50,13 @@ void lc_stem_filter_grad(const float* dwu, float* dw, int k, int r, int s, int c
 void lc_pad_channels(const void* src, void* dst, size_t rows, int c, int cpad, int esize, hipStream_t stream);
 
 // dw[k][j] (j < cols, c index j % cpad < c kept) = sum over splits of part[z][k][cols] in index order.
-void lc_reduce_splits(const float* part, float* dw, int splits, size_t rows_times_cols, int cpad, int c, hipStream_t stream);
+// sq (may be null): one double per block of the reduction, lc_reduce_splits_blocks(rows_times_cols) of them, the sum of
+// the squares of the values that block wrote to dw.
+void lc_reduce_splits(const float* part, float* dw, int splits, size_t rows_times_cols, int cpad, int c, double* sq, hipStream_t stream);
+size_t lc_reduce_splits_blocks(size_t rows_times_cols);
+// sq[b] = sum of x[i]^2 over elements 4096*b .. 4096*b + 4095: lc_sq_partials_blocks(count) doubles
+void lc_sq_partials(const float* x, size_t count, double* sq, hipStream_t stream);
+size_t lc_sq_partials_blocks(size_t count);
 
 // ---- implicit-GEMM convolution kernels (conv_igemm.hip) ----
 // One problem D[m][n] = sum_kg A(m, kg) * B[n][kg] where A is gathered from an NHWC tensor:

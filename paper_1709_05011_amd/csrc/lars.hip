@@ -26,7 +26,7 @@ namespace {
 constexpr int kThreads = 256;
 constexpr int kVecPerThread = 4;                            // float4 loads per thread per array
 constexpr int kChunk = kThreads * kVecPerThread * 4;        // 4096 elements
-constexpr int kTablePerLaunch = 192;                        // descriptors per table launch (12 KB of kernel arguments)
+constexpr int kTablePerLaunch = 192;                        // descriptors per table launch (13.5 KB of kernel arguments)
 
 struct LarsTensor {
     float* w;
@@ -34,14 +34,15 @@ struct LarsTensor {
     float* v;
     uint16_t* w_lowp;      // bf16 copy of the new weights or null
     long long numel;
+    const double* g_sq;    // pieces of sum g^2 computed elsewhere (their sum in index order), or null: the norm pass reads g
     int chunk_start;       // first chunk of this tensor
     int n_chunks;
     float eta;             // trust coefficient of this tensor
     float weight_decay;
     int skip;              // != 0: trust ratio 1 (no layer-wise scaling)
-    int pad_;
+    int g_sq_count;
 };
-static_assert(sizeof(LarsTensor) == 64, "descriptor layout");
+static_assert(sizeof(LarsTensor) == 72, "descriptor layout");
 static_assert(kTablePerLaunch <= kThreads, "the norm kernel probes the table with one thread per descriptor");
 
 struct LarsGroupArgs {
@@ -105,10 +106,11 @@ __global__ void __launch_bounds__(kThreads) lars_norm_kernel(const LarsGroupArgs
     const float* wp[kNormChunks];
     const float* gp[kNormChunks];
     int len[kNormChunks];
-    bool full[kNormChunks];
+    bool full[kNormChunks], have_g[kNormChunks];
 #pragma unroll
     for (int k = 0; k < kNormChunks; ++k) {
         full[k] = false;
+        have_g[k] = false;
         len[k] = 0;
         wp[k] = gp[k] = nullptr;
         if (k >= nc) continue;
@@ -119,13 +121,15 @@ __global__ void __launch_bounds__(kThreads) lars_norm_kernel(const LarsGroupArgs
         const long long rem = args.t[idx].numel - off;
         len[k] = rem < kChunk ? (int)rem : kChunk;
         wp[k] = args.t[idx].w + off;
-        gp[k] = args.t[idx].g + off;
+        // a tensor whose sum g^2 arrives from elsewhere: g is not read (w stands in for the address, its squares are dropped)
+        have_g[k] = args.t[idx].g_sq != nullptr;
+        gp[k] = have_g[k] ? wp[k] : args.t[idx].g + off;
         full[k] = len[k] == kChunk && ((((uintptr_t)wp[k]) | ((uintptr_t)gp[k])) & 15) == 0;
         if (full[k]) {
 #pragma unroll
             for (int i = 0; i < kVecPerThread; ++i) {
                 a[k][i] = reinterpret_cast<const float4*>(wp[k])[threadIdx.x + i * kThreads];
-                b[k][i] = reinterpret_cast<const float4*>(gp[k])[threadIdx.x + i * kThreads];
+                if (!have_g[k]) b[k][i] = reinterpret_cast<const float4*>(gp[k])[threadIdx.x + i * kThreads];
             }
         }
     }
@@ -137,13 +141,17 @@ __global__ void __launch_bounds__(kThreads) lars_norm_kernel(const LarsGroupArgs
 #pragma unroll
             for (int i = 0; i < kVecPerThread; ++i) {
                 sw += a[k][i].x * a[k][i].x + a[k][i].y * a[k][i].y + a[k][i].z * a[k][i].z + a[k][i].w * a[k][i].w;
-                sg += b[k][i].x * b[k][i].x + b[k][i].y * b[k][i].y + b[k][i].z * b[k][i].z + b[k][i].w * b[k][i].w;
+                if (!have_g[k])
+                    sg += b[k][i].x * b[k][i].x + b[k][i].y * b[k][i].y + b[k][i].z * b[k][i].z + b[k][i].w * b[k][i].w;
             }
         } else {
             for (int i = threadIdx.x; i < len[k]; i += kThreads) {
-                const float x = wp[k][i], y = gp[k][i];
+                const float x = wp[k][i];
                 sw += x * x;
-                sg += y * y;
+                if (!have_g[k]) {
+                    const float y = gp[k][i];
+                    sg += y * y;
+                }
             }
         }
         const double2 s = block_sum2((double)sw, (double)sg, red);
@@ -185,6 +193,21 @@ lars_finalize_kernel(LarsWorkspace ws, float lr, float* __restrict__ trust_out) 
     }
     pw = (qw[0] + qw[1]) + (qw[2] + qw[3]);
     pg = (qg[0] + qg[1]) + (qg[2] + qg[3]);
+    const double* __restrict__ pieces = ws.table[l].g_sq;
+    if (pieces) {                          // sum g^2 was computed where g was written: add its pieces the same way
+        const int n_pieces = ws.table[l].g_sq_count;
+        double r[4] = {0.0, 0.0, 0.0, 0.0};
+        int j = threadIdx.x;
+        for (; j + 3 * kThreads < n_pieces; j += 4 * kThreads) {
+            double q[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) q[u] = pieces[j + u * kThreads];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) r[u] += q[u];
+        }
+        for (; j < n_pieces; j += kThreads) r[0] += pieces[j];
+        pg = (r[0] + r[1]) + (r[2] + r[3]);
+    }
     const double2 tot = block_sum2(pw, pg, red);
     if (threadIdx.x == 0) {
         const double nw = sqrt(tot.x), ng = sqrt(tot.y);
@@ -309,8 +332,9 @@ lc_status lars_check(int n_tensors, float* const* w, const float* const* g, floa
 // The launches of one step on scratch memory at `base` (device, 256-byte aligned, lay.total bytes).
 lc_status lars_run(int n_tensors, float* const* w, const float* const* g, float* const* v, const int64_t* numel, float eta,
                    float momentum, float weight_decay, float lr, const float* eta_per_tensor,
-                   const float* weight_decay_per_tensor, const uint8_t* skip, float* trust_out, void* const* w_lowp_out,
-                   const LarsLayout& lay, char* base, hipStream_t stream) {
+                   const float* weight_decay_per_tensor, const uint8_t* skip, const double* const* g_sq_pieces,
+                   const int64_t* g_sq_counts, float* trust_out, void* const* w_lowp_out, const LarsLayout& lay, char* base,
+                   hipStream_t stream) {
     LarsWorkspace ws;
     ws.table = reinterpret_cast<LarsTensor*>(base + lay.table);
     ws.chunk_tensor = reinterpret_cast<int*>(base + lay.chunk_tensor);
@@ -334,7 +358,9 @@ lc_status lars_run(int n_tensors, float* const* w, const float* const* g, float*
             t.eta = eta_per_tensor ? eta_per_tensor[l] : eta;
             t.weight_decay = weight_decay_per_tensor ? weight_decay_per_tensor[l] : weight_decay;
             t.skip = skip ? (int)skip[l] : 0;
-            t.pad_ = 0;
+            const bool pre = g_sq_pieces && g_sq_counts && g_sq_pieces[l] && g_sq_counts[l] > 0;
+            t.g_sq = pre ? g_sq_pieces[l] : nullptr;
+            t.g_sq_count = pre ? (int)g_sq_counts[l] : 0;
             t.chunk_start = chunk_cursor;
             t.n_chunks = (int)((numel[l] + kChunk - 1) / kChunk);
             chunk_cursor += t.n_chunks;
@@ -365,7 +391,29 @@ extern "C" lc_status lars_step_ex(int n_tensors, float* const* w, const float* c
     if (st != LC_OK) return st;
     if (!workspace || (((uintptr_t)workspace) & 255) || workspace_bytes < lay.total) return LC_ERR_WORKSPACE;
     return lars_run(n_tensors, w, g, v, numel, eta, momentum, weight_decay, lr, eta_per_tensor, weight_decay_per_tensor, skip,
-                    trust_out, w_lowp_out, lay, static_cast<char*>(workspace), static_cast<hipStream_t>(hip_stream));
+                    nullptr, nullptr, trust_out, w_lowp_out, lay, static_cast<char*>(workspace), static_cast<hipStream_t>(hip_stream));
+}
+
+extern "C" lc_status lars_step_pre(int n_tensors, float* const* w, const float* const* g, float* const* v,
+                                   const int64_t* numel, float eta, float momentum, float weight_decay, float lr,
+                                   const float* eta_per_tensor, const float* weight_decay_per_tensor, const uint8_t* skip,
+                                   const double* const* g_sq_pieces, const int64_t* g_sq_counts,
+                                   float* trust_out, void* const* w_lowp_out,
+                                   void* workspace, size_t workspace_bytes, void* hip_stream) {
+    if (n_tensors == 0) return LC_OK;
+    LarsLayout lay;
+    const lc_status st = lars_check(n_tensors, w, g, v, numel, w_lowp_out, &lay);
+    if (st != LC_OK) return st;
+    if ((g_sq_pieces == nullptr) != (g_sq_counts == nullptr)) return LC_ERR_NULL;
+    if (g_sq_pieces)
+        for (int l = 0; l < n_tensors; ++l) {
+            if (g_sq_counts[l] < 0 || g_sq_counts[l] > 0x7fffffffLL) return LC_ERR_SHAPE;
+            if (g_sq_pieces[l] && (((uintptr_t)g_sq_pieces[l]) & 7)) return LC_ERR_ALIGN;
+        }
+    if (!workspace || (((uintptr_t)workspace) & 255) || workspace_bytes < lay.total) return LC_ERR_WORKSPACE;
+    return lars_run(n_tensors, w, g, v, numel, eta, momentum, weight_decay, lr, eta_per_tensor, weight_decay_per_tensor, skip,
+                    g_sq_pieces, g_sq_counts, trust_out, w_lowp_out, lay, static_cast<char*>(workspace),
+                    static_cast<hipStream_t>(hip_stream));
 }
 
 // ---- the same step on scratch memory that the library holds itself, for callers that cannot allocate ----
@@ -415,7 +463,7 @@ extern "C" lc_status lars_step_ex_static(int n_tensors, float* const* w, const f
     // Nothing in the array has to start at zero: the norm pass writes the table, the chunk map and every partial
     // sum of this list before the later kernels read them, and the finalize kernel writes every step scale.
     return lars_run(n_tensors, w, g, v, numel, eta, momentum, weight_decay, lr, eta_per_tensor, weight_decay_per_tensor, skip,
-                    trust_out, w_lowp_out, lay, base, static_cast<hipStream_t>(hip_stream));
+                    nullptr, nullptr, trust_out, w_lowp_out, lay, base, static_cast<hipStream_t>(hip_stream));
 }
 
 extern "C" lc_status lars_step(int n_tensors, float* const* w, const float* const* g, float* const* v,

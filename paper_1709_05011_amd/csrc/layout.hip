@@ -229,14 +229,27 @@ __global__ void stem_filter_grad_kernel(const float* __restrict__ dwu, float* __
     }
 }
 
+// Sum over the block of one double per thread, in a fixed order (lanes by butterfly, then the four waves in order);
+// thread 0 holds the result.
+__device__ __forceinline__ double block_sum_double(double x, double* red /* 4 doubles of LDS */) {
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) x += __shfl_xor(x, off, 64);
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = x;
+    __syncthreads();
+    return (red[0] + red[1]) + (red[2] + red[3]);
+}
+
 // dw[i] = sum_z part[z][i].  SL lanes of the block share one output: lane j adds the j-th run of
 // consecutive splits (four interleaved partial sums, combined in a fixed tree), then the SL lane sums are
 // added in lane order.  The order depends on (splits, SL) only, never on timing: bit-identical reruns.
+// sq (may be null) receives, per block, the sum of the squares of the values the block wrote to dw (in double): the
+// filter gradient's squared norm in pieces, for the layer-wise update that follows.
 template <int SL>
 __global__ void __launch_bounds__(256) reduce_splits_kernel(const float* __restrict__ part, float* __restrict__ dw, int splits,
-                                                            size_t count, int cpad, int c) {
+                                                            size_t count, int cpad, int c, double* __restrict__ sq) {
     constexpr int OUT = 256 / SL;
     __shared__ float sm[SL][OUT];
+    __shared__ double red[4];
     const int o = threadIdx.x % OUT, lane = threadIdx.x / OUT;
     const size_t i = (size_t)blockIdx.x * OUT + o;
     float acc = 0.f;
@@ -257,18 +270,46 @@ __global__ void __launch_bounds__(256) reduce_splits_kernel(const float* __restr
     if (SL > 1) {
         sm[lane][o] = acc;
         __syncthreads();
-        if (lane != 0) return;
-        acc = sm[0][o];
+        if (lane == 0) {
+            acc = sm[0][o];
 #pragma unroll
-        for (int j = 1; j < SL; ++j) acc += sm[j][o];
+            for (int j = 1; j < SL; ++j) acc += sm[j][o];
+        }
     }
-    if (i >= count) return;
-    if (cpad == c) {
-        dw[i] = acc;
-    } else {
-        const int ch = (int)(i % cpad);
-        if (ch < c) dw[(i / cpad) * c + ch] = acc;
+    bool wrote = false;
+    if (lane == 0 && i < count) {
+        if (cpad == c) {
+            dw[i] = acc;
+            wrote = true;
+        } else {
+            const int ch = (int)(i % cpad);
+            if (ch < c) {
+                dw[(i / cpad) * c + ch] = acc;
+                wrote = true;
+            }
+        }
     }
+    if (sq) {
+        const double total = block_sum_double(wrote ? (double)acc * (double)acc : 0.0, red);
+        if (threadIdx.x == 0) sq[blockIdx.x] = total;
+    }
+}
+
+// sq[b] = sum of x[i]^2 over block b's 4096 elements (in double, fixed order): the squared norm of a tensor in pieces.
+__global__ void __launch_bounds__(256) sq_partials_kernel(const float* __restrict__ x, size_t count, double* __restrict__ sq) {
+    __shared__ double red[4];
+    const size_t base = (size_t)blockIdx.x * 4096;
+    double s = 0.0;
+#pragma unroll 4
+    for (int j = 0; j < 16; ++j) {
+        const size_t i = base + threadIdx.x + (size_t)j * 256;
+        if (i < count) {
+            const float v = x[i];
+            s += (double)v * (double)v;
+        }
+    }
+    const double total = block_sum_double(s, red);
+    if (threadIdx.x == 0) sq[blockIdx.x] = total;
 }
 
 __global__ void bf16_to_f32_kernel(const uint16_t* __restrict__ src, float* __restrict__ dst, size_t count) {
@@ -457,16 +498,28 @@ void lc_stem_filter_grad(const float* dwu, float* dw, int k, int r, int s, int c
     hipLaunchKernelGGL(stem_filter_grad_kernel, dim3(grid_for(total, 256)), dim3(256), 0, stream, dwu, dw, k, r, s, c, rb, cu, eh, ew);
 }
 
-void lc_reduce_splits(const float* part, float* dw, int splits, size_t count, int cpad, int c, hipStream_t stream) {
+// Grid of the split reduction for `count` outputs: few outputs spread each output's splits over more lanes so that the
+// chip still fills.  A fixed function of count (it is also the number of squared-norm pieces the reduction emits).
+static int reduce_splits_lanes(size_t count) { return count >= (size_t)1 << 18 ? 1 : count >= (size_t)1 << 15 ? 4 : 16; }
+
+size_t lc_reduce_splits_blocks(size_t count) {
+    const size_t out = 256 / reduce_splits_lanes(count);
+    return (count + out - 1) / out;
+}
+
+void lc_reduce_splits(const float* part, float* dw, int splits, size_t count, int cpad, int c, double* sq, hipStream_t stream) {
     if (!count) return;
-    // few outputs: spread each output's splits over more lanes so that the chip still fills
-    if (count >= (size_t)1 << 18)
-        hipLaunchKernelGGL(reduce_splits_kernel<1>, dim3((unsigned)((count + 255) / 256)), dim3(256), 0, stream, part, dw, splits,
-                           count, cpad, c);
-    else if (count >= (size_t)1 << 15)
-        hipLaunchKernelGGL(reduce_splits_kernel<4>, dim3((unsigned)((count + 63) / 64)), dim3(256), 0, stream, part, dw, splits,
-                           count, cpad, c);
-    else
-        hipLaunchKernelGGL(reduce_splits_kernel<16>, dim3((unsigned)((count + 15) / 16)), dim3(256), 0, stream, part, dw, splits,
-                           count, cpad, c);
+    const unsigned grid = (unsigned)lc_reduce_splits_blocks(count);
+    switch (reduce_splits_lanes(count)) {
+        case 1: hipLaunchKernelGGL(reduce_splits_kernel<1>, dim3(grid), dim3(256), 0, stream, part, dw, splits, count, cpad, c, sq); break;
+        case 4: hipLaunchKernelGGL(reduce_splits_kernel<4>, dim3(grid), dim3(256), 0, stream, part, dw, splits, count, cpad, c, sq); break;
+        default: hipLaunchKernelGGL(reduce_splits_kernel<16>, dim3(grid), dim3(256), 0, stream, part, dw, splits, count, cpad, c, sq);
+    }
+}
+
+size_t lc_sq_partials_blocks(size_t count) { return (count + 4095) / 4096; }
+
+void lc_sq_partials(const float* x, size_t count, double* sq, hipStream_t stream) {
+    if (!count) return;
+    hipLaunchKernelGGL(sq_partials_kernel, dim3((unsigned)lc_sq_partials_blocks(count)), dim3(256), 0, stream, x, count, sq);
 }

@@ -20,7 +20,8 @@ LC_NCHW, LC_NHWC = 0, 1
 LC_PASS_FWD, LC_PASS_BWD_DATA, LC_PASS_BWD_WEIGHT = 0, 1, 2
 
 EXPORTS = ["conv2d_out_shape", "conv2d_workspace_bytes", "conv2d_fwd", "conv2d_bwd_data", "conv2d_bwd_weight",
-           "lars_workspace_bytes", "lars_step", "lars_step_ex", "lars_step_ex_static", "lars_poly_lr", "lars_warmup_poly_lr",
+           "conv2d_bwd_weight_sq_count", "conv2d_bwd_weight_sq",
+           "lars_workspace_bytes", "lars_step", "lars_step_ex", "lars_step_pre", "lars_step_ex_static", "lars_poly_lr", "lars_warmup_poly_lr",
            "relu_fwd", "relu_bwd", "maxpool2x2_fwd", "maxpool2x2_bwd", "global_avgpool_fwd", "global_avgpool_bwd",
            "bias_add", "bias_grad", "softmax_xent", "maxpool_fwd", "maxpool_bwd", "relu_add_bwd",
            "batchnorm_workspace_bytes", "batchnorm_fwd", "batchnorm_bwd", "batchnorm_fwd_ex", "batchnorm_bwd_ex",
@@ -86,6 +87,13 @@ def lib() -> ctypes.CDLL:
             fn = getattr(L, name)
             fn.restype = i32
             fn.argtypes = [dp, vp, vp, vp, vp, sz, vp]
+        L.conv2d_bwd_weight_sq_count.restype = sz
+        L.conv2d_bwd_weight_sq_count.argtypes = [dp]
+        L.conv2d_bwd_weight_sq.restype = i32
+        L.conv2d_bwd_weight_sq.argtypes = [dp, vp, vp, vp, vp, vp, sz, vp]
+        L.lars_step_pre.restype = i32
+        L.lars_step_pre.argtypes = [i32, vp, vp, vp, vp, ctypes.c_float, ctypes.c_float, ctypes.c_float, ctypes.c_float,
+                                    vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.lars_workspace_bytes.restype = sz
         L.lars_workspace_bytes.argtypes = [i32, vp]
         L.lars_step.restype = i32
@@ -206,6 +214,16 @@ def conv2d_bwd_weight(desc, x, dy, dw, workspace=None, stream=None, workspace_by
                                    _stream(stream)), "conv2d_bwd_weight")
 
 
+def conv2d_bwd_weight_sq_count(desc) -> int:
+    return int(lib().conv2d_bwd_weight_sq_count(ctypes.byref(_desc(desc))))
+
+
+def conv2d_bwd_weight_sq(desc, x, dy, dw, dw_sq_pieces, workspace=None, stream=None, workspace_bytes: Optional[int] = None) -> None:
+    nb = _nbytes(workspace) if workspace_bytes is None else workspace_bytes
+    _check(lib().conv2d_bwd_weight_sq(ctypes.byref(_desc(desc)), _ptr(x), _ptr(dy), _ptr(dw), _ptr(dw_sq_pieces), _ptr(workspace),
+                                      nb, _stream(stream)), "conv2d_bwd_weight_sq")
+
+
 def _i64_array(vals: Sequence[int]):
     return (ctypes.c_int64 * max(len(vals), 1))(*vals)
 
@@ -261,6 +279,19 @@ def lars_step_ex(args: LarsArgs, eta: float, momentum: float, weight_decay: floa
     nb = _nbytes(workspace) if workspace_bytes is None else workspace_bytes
     _check(lib().lars_step_ex(args.n, args.w, args.g, args.v, args.numel_arr, eta, momentum, weight_decay, lr, e, b, sk,
                               _ptr(trust_out), args.w_lowp, _ptr(workspace), nb, _stream(stream)), "lars_step_ex")
+
+
+def lars_step_pre(args: LarsArgs, eta: float, momentum: float, weight_decay: float, lr: float, g_sq_pieces: Sequence,
+                  g_sq_counts: Sequence[int], eta_per_tensor=None, weight_decay_per_tensor=None, skip=None, trust_out=None,
+                  workspace=None, stream=None, workspace_bytes: Optional[int] = None) -> None:
+    """lars_step_ex with sum g^2 of some tensors handed over in pieces (None / 0 entries: computed from g)."""
+    if len(g_sq_pieces) != args.n or len(g_sq_counts) != args.n:
+        raise ValueError("per-tensor array of the wrong length")
+    e, b, sk = _per_tensor_arrays(args, eta_per_tensor, weight_decay_per_tensor, skip)
+    nb = _nbytes(workspace) if workspace_bytes is None else workspace_bytes
+    _check(lib().lars_step_pre(args.n, args.w, args.g, args.v, args.numel_arr, eta, momentum, weight_decay, lr, e, b, sk,
+                               _ptr_array(g_sq_pieces), _i64_array([int(c) for c in g_sq_counts]), _ptr(trust_out), args.w_lowp,
+                               _ptr(workspace), nb, _stream(stream)), "lars_step_pre")
 
 
 LARS_STATIC_SCRATCH_BYTES = 2 << 20

@@ -79,6 +79,14 @@ class ResNetStep:
         self._lars = lc.LarsArgs([self.params[k] for k in names], [self.grads[k] for k in names], [self.velocity[k] for k in names])
         self._lars_ws = self._bytes(lc.lars_workspace_bytes(self._lars.numel))
         self.trust = torch.zeros(len(names), **f32)
+        # the squared norm of every filter gradient comes out of its backward-weight pass in pieces and is handed to
+        # the update, which then reads those gradients once instead of twice
+        self.gsq: Dict[str, torch.Tensor] = {}
+        for name in self.order + ["fc"]:
+            d = self.fc_desc if name == "fc" else self.layers[name].desc
+            self.gsq[name + ".w"] = torch.zeros(lc.conv2d_bwd_weight_sq_count(d), dtype=torch.float64, device=device)
+        self._gsq_list = [self.gsq.get(k) for k in names]
+        self._gsq_counts = [0 if t is None else t.numel() for t in self._gsq_list]
 
         # one workspace for every convolution pass and every batch norm
         need = 0
@@ -137,7 +145,7 @@ class ResNetStep:
         dz = self._new(L.z)
         lc.batchnorm_bwd_ex(L.z, da, self.params[name + ".gamma"], self.params[name + ".beta"], L.mean, L.invstd, dz,
                             self.grads[name + ".gamma"], self.grads[name + ".beta"], self.batch, k, p, q, L.relu, NHWC, self._ws)
-        lc.conv2d_bwd_weight(L.desc, L.x, dz, self.grads[name + ".w"], self._ws)
+        lc.conv2d_bwd_weight_sq(L.desc, L.x, dz, self.grads[name + ".w"], self.gsq[name + ".w"], self._ws)
         if not need_dx:
             return None
         dx = self._new(L.x)
@@ -166,7 +174,7 @@ class ResNetStep:
     def backward(self) -> None:
         n = self.batch
         lc.bias_grad(self.dlogits, self.grads["fc.b"], n, self.classes)
-        lc.conv2d_bwd_weight(self.fc_desc, self.gap, self.dlogits, self.grads["fc.w"], self._ws)
+        lc.conv2d_bwd_weight_sq(self.fc_desc, self.gap, self.dlogits, self.grads["fc.w"], self.gsq["fc.w"], self._ws)
         dgap = self._new(self.gap)
         lc.conv2d_bwd_data(self.fc_desc, self.dlogits, self.params["fc.w"], dgap, self._ws)
         last = self.layers[self.blocks[-1][0] + ".c3"].a
@@ -189,7 +197,8 @@ class ResNetStep:
         self._conv_bn_bwd("stem", da, need_dx=False)
 
     def lars(self, eta: float, momentum: float, weight_decay: float, lr: float) -> None:
-        lc.lars_step(self._lars, eta, momentum, weight_decay, lr, self.trust, self._lars_ws)
+        lc.lars_step_pre(self._lars, eta, momentum, weight_decay, lr, self._gsq_list, self._gsq_counts, trust_out=self.trust,
+                         workspace=self._lars_ws)
 
     def step(self, x: torch.Tensor, labels: torch.Tensor, eta: float, momentum: float, weight_decay: float, lr: float) -> torch.Tensor:
         loss = self.forward(x, labels)

@@ -184,6 +184,30 @@ def test_lars_step_ex_static_rejects_bad_arguments_before_launch():
     assert re.search(r"#define\s+LARS_STATIC_SCRATCH_BYTES\s+\(\(size_t\)2\s*<<\s*20\)", text) and lc.LARS_STATIC_SCRATCH_BYTES == 2 << 20
 
 
+def test_norms_for_free_entry_points_reject_bad_arguments_before_launch():
+    L = lc.lib()
+    P = ctypes.c_void_p(FAKE)
+    d = lc.ConvDesc(8, 64, 14, 14, 64, 3, 3, 1, 1, 1, 1)
+    ds = d.c_struct()
+    assert lc.conv2d_bwd_weight_sq_count(d) > 0
+    assert lc.conv2d_bwd_weight_sq_count(lc.ConvDesc(0, 64, 14, 14, 64, 3, 3)) == 0
+    need = lc.conv2d_workspace_bytes(d, lc.LC_PASS_BWD_WEIGHT)
+    assert L.conv2d_bwd_weight_sq(ctypes.byref(ds), P, P, P, None, P, need, None) == lc.LC_ERR_NULL
+    assert L.conv2d_bwd_weight_sq(ctypes.byref(ds), P, P, P, ctypes.c_void_p(FAKE + 4), P, need, None) == lc.LC_ERR_ALIGN
+    assert L.conv2d_bwd_weight_sq(ctypes.byref(ds), P, P, P, P, P, need - 1, None) == lc.LC_ERR_WORKSPACE
+    arr = (ctypes.c_void_p * 2)(FAKE, FAKE)
+    numel = (ctypes.c_int64 * 2)(100, 5000)
+    need = lc.lars_workspace_bytes([100, 5000])
+    pieces = (ctypes.c_void_p * 2)(FAKE, None)
+    counts = (ctypes.c_int64 * 2)(10, 0)
+    call = lambda pc, ct, ws, nb: L.lars_step_pre(2, arr, arr, arr, numel, 0.001, 0.9, 5e-5, 1.0, None, None, None, pc, ct, None, None, ws, nb, None)
+    assert call(pieces, None, P, need) == lc.LC_ERR_NULL                 # the two arrays come together
+    assert call(pieces, (ctypes.c_int64 * 2)(-1, 0), P, need) == lc.LC_ERR_SHAPE
+    assert call((ctypes.c_void_p * 2)(FAKE + 4, None), counts, P, need) == lc.LC_ERR_ALIGN
+    assert call(pieces, counts, None, need) == lc.LC_ERR_WORKSPACE
+    assert call(pieces, counts, P, need - 1) == lc.LC_ERR_WORKSPACE
+
+
 def test_glue_layers_reject_bad_arguments_before_launch():
     L = lc.lib()
     P = ctypes.c_void_p(FAKE)
