@@ -200,8 +200,15 @@ def run_train_step(args):
         special = bf16 and k_gemm >= 32 and not scatter
         if n_gemm <= 64:
             return "conv_gemm_256x64" if special and -(-rows // 256) >= 3 * 3 * 256 else "conv_gemm_128x64"
-        if special and n_gemm >= 256 and -(-rows // 128) * -(-n_gemm // 256) >= 3 * 2 * 256:
-            return "conv_gemm_128x256"
+        if special and n_gemm >= 256:
+            tiles = -(-rows // 256) * -(-n_gemm // 256)            # 256x256 (eight waves): one block per compute unit
+            rounds = -(-tiles // 256)
+            nkt = -(-(k_gemm * cs.r * cs.s) // 32)
+            fill = 70 if n_gemm <= 512 else 85
+            if tiles >= 256 and tiles * 100 >= rounds * 256 * fill and (n_gemm <= 512 or nkt >= 16):
+                return "conv_gemm_256x256"
+            if -(-rows // 128) * -(-n_gemm // 256) >= 3 * 2 * 256:
+                return "conv_gemm_128x256"
         return "conv_gemm_128x128"
 
     def step(timer=None):

@@ -316,25 +316,30 @@ __device__ __forceinline__ int div_by(int n, unsigned mul, unsigned shift) {    
     return mul ? (int)(__umulhi((unsigned)n, mul) >> shift) : n;
 }
 
-// Blocks per compute unit: 3 for tiles up to 128x128 (64 accumulator registers per lane), 2 for the 128x256 tile.
-constexpr int pk_blocks_per_cu(int bm, int bn) { return bm * bn > 128 * 128 ? 2 : 3; }
+// Blocks per compute unit: 3 for tiles up to 128x128 (64 accumulator registers per lane), 2 for the 128x256 tile, 1 for
+// the 256x256 tile (run by eight waves, two per SIMD, each with 128 accumulator registers).
+constexpr int pk_blocks_per_cu(int bm, int bn) { return bm * bn >= 256 * 256 ? 1 : bm * bn > 128 * 128 ? 2 : 3; }
+// Waves along the columns of the tile: 2 (a 2 x 2 block of waves), or 4 for the 256x256 tile (2 x 4 waves of 128 x 64).
+constexpr int pk_waves_n(int bm, int bn) { return bm * bn >= 256 * 256 ? 4 : 2; }
 
 template <int BM, int BN, bool SMALLC, bool BF16, bool UT, bool SCATTER>
-__global__ void __launch_bounds__(256, pk_blocks_per_cu(BM, BN)) conv_gemm_pk_kernel(const GemmConv p) {
+__global__ void __launch_bounds__(2 * pk_waves_n(BM, BN) * 64, pk_blocks_per_cu(BM, BN) * pk_waves_n(BM, BN) / 2)
+conv_gemm_pk_kernel(const GemmConv p) {
     using E = typename OutT<BF16>::type;
     constexpr int ES = (int)sizeof(E);
     constexpr int EPC = BF16 ? 8 : 4;
     constexpr int BK = 4 * EPC;
-    constexpr int LA = BM / 64, LB = BN / 64, LPT = LA + LB;
-    constexpr int WTM = BM / 2, WTN = BN / 2, TM = WTM / 32, TN = WTN / 32;
+    constexpr int WN_ = pk_waves_n(BM, BN), NWV = 2 * WN_;              // waves: 2 along the rows x WN_ along the columns
+    constexpr int LA = BM / (16 * NWV), LB = BN / (16 * NWV), LPT = LA + LB;
+    constexpr int WTM = BM / 2, WTN = BN / WN_, TM = WTM / 32, TN = WTN / 32;
     constexpr int STAGE = (BM + BN) * 16;
-    static_assert(BM % 64 == 0 && BN % 64 == 0, "tile shape");
+    static_assert(BM % (16 * NWV) == 0 && BN % (16 * NWV) == 0 && WTM % 32 == 0 && WTN % 32 == 0, "tile shape");
 
     __shared__ __attribute__((aligned(1024))) float lds[2 * STAGE];
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int wm = wave >> 1, wn = wave & 1;
+    const int wm = wave / WN_, wn = wave % WN_;
     const int nbn = (p.N + BN - 1) / BN;
     const int nkt = (p.Kg + BK - 1) / BK;
     const E* __restrict__ A = static_cast<const E*>(p.a);
@@ -399,7 +404,7 @@ __global__ void __launch_bounds__(256, pk_blocks_per_cu(BM, BN)) conv_gemm_pk_ke
             for (int rr = 0; rr < R_; ++rr) rep |= 1u << (rr * S_);
 #pragma unroll
             for (int i = 0; i < LA; ++i) {
-                const int m = m0 + (i * 4 + wave) * 16 + lrow;
+                const int m = m0 + (i * NWV + wave) * 16 + lrow;
                 const int t = div_by(m, qmul, qsh), qo = m - t * Qo_;
                 const int img = div_by(t, pmul, psh), po = t - img * Po_;
                 const int h0 = po * sh_ - ph_, w0 = qo * sw_ - pw_;
@@ -418,7 +423,7 @@ __global__ void __launch_bounds__(256, pk_blocks_per_cu(BM, BN)) conv_gemm_pk_ke
             }
 #pragma unroll
             for (int i = 0; i < LB; ++i) {
-                const int nl = (i * 4 + wave) * 16 + lrow;
+                const int nl = (i * NWV + wave) * 16 + lrow;
                 b_voff[i] = (n0 + nl < N_) ? (unsigned)(nl * Kg_ * ES + kq * 16) : kBufferBytes;
             }
             const long long a_first = ((long long)img0 * Hi_ * Wi_ - ((long long)phb * Wi_ + pwb)) * Ci_;
@@ -432,7 +437,7 @@ __global__ void __launch_bounds__(256, pk_blocks_per_cu(BM, BN)) conv_gemm_pk_ke
         } else {
 #pragma unroll
             for (int i = 0; i < LA; ++i) {
-                const int m = m0 + (i * 4 + wave) * 16 + lrow;
+                const int m = m0 + (i * NWV + wave) * 16 + lrow;
                 if (m < M_) {
                     const int t = div_by(m, qmul, qsh), qo = m - t * Qo_;
                     const int img = div_by(t, pmul, psh), po = t - img * Po_;
@@ -447,7 +452,7 @@ __global__ void __launch_bounds__(256, pk_blocks_per_cu(BM, BN)) conv_gemm_pk_ke
             }
 #pragma unroll
             for (int i = 0; i < LB; ++i) {
-                const int n = n0 + (i * 4 + wave) * 16 + lrow;
+                const int n = n0 + (i * NWV + wave) * 16 + lrow;
                 b_off[i] = n < N_ ? (long long)n * Kg_ : -1;
             }
             kg = k0 * BK + kq * EPC;
@@ -527,7 +532,7 @@ __global__ void __launch_bounds__(256, pk_blocks_per_cu(BM, BN)) conv_gemm_pk_ke
         float* base = lds + buf * STAGE + wave * 256 + lane * 4;
 #pragma unroll
         for (int l = 0; l < LPT; ++l)
-            *reinterpret_cast<float4*>(base + (l < LA ? l * 1024 : BM * 16 + (l - LA) * 1024)) = g[l];
+            *reinterpret_cast<float4*>(base + (l < LA ? l * (NWV * 256) : BM * 16 + (l - LA) * (NWV * 256))) = g[l];
     };
 
     // ---------------- compute side ----------------
@@ -762,10 +767,11 @@ __global__ void __launch_bounds__(256, pk_blocks_per_cu(BM, BN)) conv_gemm_pk_ke
 // Block (t, v) handles accumulator register v of every 32x32 MFMA tile of stream-K tile t, with the thread
 // geometry of the main kernel: 16 blocks per tile keep the whole chip busy on what is a small reduction.
 template <int BM, int BN, bool BF16>
-__global__ void __launch_bounds__(256) conv_gemm_fixup_kernel(const GemmConv p) {
-    constexpr int BK = BF16 ? 32 : 16, TM = BM / 64, TN = BN / 64;
+__global__ void __launch_bounds__(2 * pk_waves_n(BM, BN) * 64) conv_gemm_fixup_kernel(const GemmConv p) {
+    constexpr int WN_ = pk_waves_n(BM, BN);
+    constexpr int BK = BF16 ? 32 : 16, TM = BM / 64, TN = BN / (32 * WN_);
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int wm = wave >> 1, wn = wave & 1;
+    const int wm = wave / WN_, wn = wave % WN_;
     const int v = blockIdx.y;
     const int nbn = (p.N + BN - 1) / BN;
     const int nkt = (p.Kg + BK - 1) / BK;
@@ -799,7 +805,7 @@ __global__ void __launch_bounds__(256) conv_gemm_fixup_kernel(const GemmConv p) 
             for (int u = 0; u < 16; ++u) out[i][jj][u] = acc[i][jj][0];
     const int tile = p.dp_tiles + blockIdx.x;
     const int m0 = (tile / nbn) * BM, n0 = (tile % nbn) * BN;
-    store_tile<TM, TN, BF16>(p, out, m0 + wm * (BM / 2), n0 + wn * (BN / 2), lane, v);
+    store_tile<TM, TN, BF16>(p, out, m0 + wm * (BM / 2), n0 + wn * (BN / WN_), lane, v);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -1474,7 +1480,7 @@ int device_cu_count() {
     return n;
 }
 
-SkPlan sk_plan(long long tiles, int nkt, int resident_blocks) {
+SkPlan sk_plan(long long tiles, int nkt, int resident_blocks, bool allow_split = true) {
     SkPlan pl;
     const long long rounds = tiles / resident_blocks;
     long long dp = rounds * resident_blocks;
@@ -1482,7 +1488,7 @@ SkPlan sk_plan(long long tiles, int nkt, int resident_blocks) {
     pl.dp_tiles = (int)dp;
     pl.sk_blocks = 0;
     pl.sk_iters = 0;
-    if (rest == 0 || getenv("LARSCONV_NO_STREAMK")) {      // every round is full (or stream-K switched off for comparison runs)
+    if (rest == 0 || !allow_split || getenv("LARSCONV_NO_STREAMK")) {   // every round is full, or splitting tiles is not wanted
         pl.dp_tiles = (int)tiles;
         return pl;
     }
@@ -1503,6 +1509,7 @@ inline int resident_blocks(int bm, int bn) { return pk_blocks_per_cu(bm, bn) * d
 //   128x256 for results at least 256 wide with at least three rounds of such tiles (a quarter fewer LDS and load
 //           instructions per MFMA than 128x128: 5 to 20 % on such layers; with fewer rounds the coarser tiles
 //           leave compute units idle at the end);
+//   256x256 (eight waves) for results at least 256 wide whose tiles fill whole rounds of the chip well enough;
 //   256x64  for results at most 64 wide with at least three rounds of such tiles: a wave then owns 128 x 32 and
 //           issues as many MFMAs per load as in the 128x128 tile (4 to 7 % on the 56x56 layers with 64 filters
 //           or channels).
@@ -1513,11 +1520,28 @@ struct MainTile {
 inline MainTile main_tile(const GemmConv& p) {
     static const bool no_wide = getenv("LARSCONV_NO_WIDE_TILE") != nullptr;    // comparison runs
     static const bool no_tall = getenv("LARSCONV_NO_TALL_TILE") != nullptr;
+    static const bool no_big = getenv("LARSCONV_NO_BIG_TILE") != nullptr;
     MainTile t{128, p.N <= 64 ? 64 : 128};
     if (!p.bf16 || p.Ci < 32 || p.scatter) return t;
     if (p.N <= 64) {
         if (!no_tall && (p.M + 255) / 256 >= 3LL * resident_blocks(256, 64)) t.bm = 256;
         return t;
+    }
+    if (p.N >= 256 && !no_big) {
+        // 256x256, eight waves: half the operand bytes per MFMA through the vector-memory path and LDS of the 128x128 tile.
+        // Taken when its tiles fill the chip at least once and the last, partly filled round wastes less than the tile
+        // gains (measured over ResNet-50's layers at batch 512: results up to 512 wide gain 5 to 20 % from 70 % fill on;
+        // wider results only with at least 16 k-steps per tile and 85 % fill, otherwise the 128x256 tile is faster).
+        const long long tiles = (long long)((p.M + 255) / 256) * ((p.N + 255) / 256);
+        const long long res = resident_blocks(256, 256);
+        const long long rounds = (tiles + res - 1) / res;
+        const int nkt = (p.Kg + 31) / 32;
+        static const int fill_env = [] {
+            const char* e = getenv("LARSCONV_BIG_TILE_FILL");                  // comparison runs: another threshold
+            return e ? atoi(e) : 0;
+        }();
+        const int fill = fill_env ? fill_env : (p.N <= 512 ? 70 : 85);
+        if (tiles >= res && tiles * 100 >= rounds * res * fill && (fill_env || p.N <= 512 || nkt >= 16)) return MainTile{256, 256};
     }
     if (p.N >= 256 && !no_wide) {
         const long long tiles = (long long)((p.M + 127) / 128) * ((p.N + 255) / 256);
@@ -1594,7 +1618,9 @@ lc_status launch_conv_sk(GemmConv p, hipStream_t stream) {
     int nkt;
     if (!sk_geometry<BM, BN>(p, &tiles, &nkt)) return LC_ERR_UNSUPPORTED;
     const int resident = resident_blocks(BM, BN);
-    SkPlan pl = sk_plan(tiles, nkt, resident);
+    // (a 256x256 tile's partial sums are 256 KB per block and piece: writing and re-reading them costs more than the idle
+    // end of the last round, which main_tile() has already bounded)
+    SkPlan pl = sk_plan(tiles, nkt, resident, BM * BN < 256 * 256);
     // persistent kernel: one round of resident blocks, each taking dp_tiles / grid whole tiles and then its
     // stream-K range; without a workspace for partial tiles the ranges are whole tiles
     if (pl.sk_blocks > 0 && !p.partial) pl.sk_blocks = 0;
@@ -1610,6 +1636,7 @@ lc_status launch_conv_sk(GemmConv p, hipStream_t stream) {
     magic_for(p.Qo, &p.qo_mul, &p.qo_shift);
     magic_for(p.Po, &p.po_mul, &p.po_shift);
     const unsigned grid = pl.dp_tiles > 0 ? (unsigned)resident : (unsigned)pl.sk_blocks;
+    const dim3 threads(2 * pk_waves_n(BM, BN) * 64);
     const bool whole = pl.sk_blocks == 0 || pl.sk_iters == (long long)pl.sk_blocks * nkt;
     const bool ut = !SMALLC && uniform_tap_ok<BM, BN>(p);
     if (p.scatter) {                          // the scatter epilogue addresses the result relative to the tile's first pixel
@@ -1617,17 +1644,17 @@ lc_status launch_conv_sk(GemmConv p, hipStream_t stream) {
         if (span >= 0x7fff0000LL || SMALLC || BN > 128 || BM > 128) return LC_ERR_UNSUPPORTED;   // (1x1 windows never have fewer channels than a k-step)
         if constexpr (BN <= 128 && BM <= 128) {
             if (ut)
-                hipLaunchKernelGGL((conv_gemm_pk_kernel<BM, BN, false, BF16, true, true>), dim3(grid), dim3(256), 0, stream, p);
+                hipLaunchKernelGGL((conv_gemm_pk_kernel<BM, BN, false, BF16, true, true>), dim3(grid), threads, 0, stream, p);
             else
-                hipLaunchKernelGGL((conv_gemm_pk_kernel<BM, BN, false, BF16, false, true>), dim3(grid), dim3(256), 0, stream, p);
+                hipLaunchKernelGGL((conv_gemm_pk_kernel<BM, BN, false, BF16, false, true>), dim3(grid), threads, 0, stream, p);
         }
     } else if (ut) {
-        hipLaunchKernelGGL((conv_gemm_pk_kernel<BM, BN, false, BF16, true, false>), dim3(grid), dim3(256), 0, stream, p);
+        hipLaunchKernelGGL((conv_gemm_pk_kernel<BM, BN, false, BF16, true, false>), dim3(grid), threads, 0, stream, p);
     } else {
-        hipLaunchKernelGGL((conv_gemm_pk_kernel<BM, BN, SMALLC, BF16, false, false>), dim3(grid), dim3(256), 0, stream, p);
+        hipLaunchKernelGGL((conv_gemm_pk_kernel<BM, BN, SMALLC, BF16, false, false>), dim3(grid), threads, 0, stream, p);
     }
     if (!whole)
-        hipLaunchKernelGGL((conv_gemm_fixup_kernel<BM, BN, BF16>), dim3((unsigned)(tiles - pl.dp_tiles), 16), dim3(256), 0, stream, p);
+        hipLaunchKernelGGL((conv_gemm_fixup_kernel<BM, BN, BF16>), dim3((unsigned)(tiles - pl.dp_tiles), 16), threads, 0, stream, p);
     return lc_end_call();
 }
 
@@ -1650,6 +1677,7 @@ inline bool use_main_kernel(const GemmConv& p) {
 template <typename F>
 auto with_main_tile(const GemmConv& p, F&& f) {
     const MainTile t = main_tile(p);
+    if (t.bm == 256 && t.bn == 256) return f.template operator()<256, 256>();
     if (t.bm == 256) return f.template operator()<256, 64>();
     if (t.bn == 256) return f.template operator()<128, 256>();
     if (t.bn == 128) return f.template operator()<128, 128>();
@@ -1662,7 +1690,7 @@ size_t lc_conv_gemm_workspace(const GemmConv& p) {
         long long tiles;
         int nkt;
         if (!sk_geometry<BM, BN>(p, &tiles, &nkt)) return 0;
-        const SkPlan pl = sk_plan(tiles, nkt, resident_blocks(BM, BN));
+        const SkPlan pl = sk_plan(tiles, nkt, resident_blocks(BM, BN), BM * BN < 256 * 256);
         return (size_t)2 * pl.sk_blocks * BM * BN * sizeof(float);
     });
 }

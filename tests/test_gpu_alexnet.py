@@ -87,9 +87,17 @@ def test_whole_training_step_matches_oracle():
     ov = [np.zeros_like(params[k]) for k in names]
     og = [np.ascontiguousarray(grads[k], dtype=np.float32) for k in names]
     trust, _ = oracle.lars_step(ow, og, ov, eta, momentum, wd, lr)
+    # the update's own error, apart from that of the gradients before it: the oracle on the very w and g the device holds
+    f = np.float32
+    dev_w = [net.params[k].cpu().numpy().ravel().copy() for k in names]
+    dev_g = [net.grads[k].cpu().numpy().ravel().copy() for k in names]
+    dev_v = [net.velocity[k].cpu().numpy().ravel().copy() for k in names]
+    trust_dev, _ = oracle.lars_step(dev_w, dev_g, dev_v, float(f(eta)), float(f(momentum)), float(f(wd)), float(f(lr)))
     net.lars(eta, momentum, wd, lr)
     torch.cuda.synchronize()
-    assert np.max(np.abs(net.trust.cpu().numpy().astype(np.float64) - trust) / np.abs(trust)) <= 1e-4
+    got_trust = net.trust.cpu().numpy().astype(np.float64)
+    assert np.max(np.abs(got_trust - trust_dev) / np.abs(trust_dev)) <= 1e-5      # the stated bar, on the step's real gradients
+    assert np.max(np.abs(got_trust - trust) / np.abs(trust)) <= 1e-4               # the oracle network's gradients differ by <= 1e-4
     for k, w_ref in zip(names, ow):
         assert gu.scaled_err(_from_dev(k, net.params[k].cpu().numpy(), w_ref.shape), w_ref) <= TOL, k
 

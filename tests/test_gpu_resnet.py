@@ -97,10 +97,20 @@ def test_whole_training_step_matches_oracle():
     ov = [np.zeros_like(params[k]) for k in names]
     og = [np.ascontiguousarray(grads[k], dtype=np.float32) for k in names]
     trust, _ = oracle.lars_step(ow, og, ov, eta, momentum, wd, lr)
+    # ... and, to separate the update's own error from that of the gradients before it: the oracle on the very w and g
+    # the device holds (the float hyper-parameters the C ABI takes)
+    f = np.float32
+    dev_w = [net.params[k].cpu().numpy().ravel().copy() for k in names]
+    dev_g = [net.grads[k].cpu().numpy().ravel().copy() for k in names]
+    dev_v = [net.velocity[k].cpu().numpy().ravel().copy() for k in names]
+    trust_dev, _ = oracle.lars_step(dev_w, dev_g, dev_v, float(f(eta)), float(f(momentum)), float(f(wd)), float(f(lr)))
     net.lars(eta, momentum, wd, lr)
     torch.cuda.synchronize()
     got_trust = net.trust.cpu().numpy().astype(np.float64)
-    assert np.max(np.abs(got_trust - trust) / np.abs(trust)) <= 1e-4     # the gradients themselves differ by <= 1e-4
+    assert np.max(np.abs(got_trust - trust_dev) / np.abs(trust_dev)) <= 1e-5      # the stated bar, on the step's real gradients
+    for k, w_ref in zip(names, dev_w):
+        assert gu.scaled_err(net.params[k].cpu().numpy().ravel(), w_ref) <= TOL, k
+    assert np.max(np.abs(got_trust - trust) / np.abs(trust)) <= 1e-4     # against the oracle network: its gradients differ by <= 1e-4
     for k, w_ref, v_ref in zip(names, ow, ov):
         assert gu.scaled_err(_from_device_layout(k, net.params[k].cpu().numpy(), w_ref.shape), w_ref) <= TOL, k
         assert gu.scaled_err(_from_device_layout(k, net.velocity[k].cpu().numpy(), v_ref.shape), v_ref) <= 2e-4, k
