@@ -614,7 +614,7 @@ def run_batch_curve(args):
     points = []
     for b in (args.batches or [16, 32, 64, 128, 256, 512]):
         a = copy.copy(args)
-        a.batch, a.steps, a.warmup, a.no_cpu, a.graph = b, 5, 2, True, False
+        a.batch, a.steps, a.warmup, a.no_cpu, a.graph = b, 10, 5, True, False
         head = run_train_step(a)
         gc.collect()
         torch.cuda.empty_cache()

@@ -27,10 +27,6 @@ def build(verbose: bool = False, extra_flags=()) -> str:
     """Compile every source and link the shared library; returns its path."""
     os.makedirs(OBJ, exist_ok=True)
     cc = _hipcc()
-    headers = [os.path.join(CSRC, f) for f in os.listdir(CSRC) if f.endswith(".h")]
-    headers.append(os.path.join(os.path.dirname(HERE), "include", "larsconv.h"))
-    newest_header = max(os.path.getmtime(h) for h in headers)
-
     def compile_one(src: str) -> str:
         obj = os.path.join(OBJ, src.replace(".hip", ".o"))
         path = os.path.join(CSRC, src)
@@ -51,7 +47,6 @@ def build(verbose: bool = False, extra_flags=()) -> str:
     tmp = LIB + f".tmp{os.getpid()}"
     subprocess.check_call([cc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", tmp, *objs])
     os.replace(tmp, LIB)
-    del newest_header
     return LIB
 
 

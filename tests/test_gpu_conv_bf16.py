@@ -138,6 +138,40 @@ def test_bf16_full_size_batch512_sampled(name):
     assert np.max(np.abs(dw[cw[:, 0], cw[:, 2], cw[:, 3], cw[:, 1]] - ref)) <= TOL_DW * np.max(np.abs(ref))
 
 
+def test_bf16_first_layer_full_size_batch512_sampled():
+    """The 7x7 stride-2 first layer at the bf16 workload's full size (512 x 224 x 224 x 3): forward and backward-weight run
+    over 2x2 pixel blocks through a 0.84 GB unfolded copy in the workspace.  Sampled outputs; backward-data is not part
+    of a training step for a first layer."""
+    cs = synth.resnet50_convs(512)[0]
+    seed = 7800
+    print(f"bf16 full-size first layer: {cs}", flush=True)
+    xb = synth.to_bf16_bits(synth.normal((cs.n, cs.h, cs.w, cs.c), seed))
+    wb = synth.to_bf16_bits(synth.normal((cs.k, cs.r, cs.s, cs.c), seed + 1, std=synth.he_std(cs)))
+    dyb = synth.to_bf16_bits(synth.normal((cs.n, cs.p, cs.q, cs.k), seed + 2))
+    x, wt, dy = (synth.bf16_bits_to_f32(b) for b in (xb, wb, dyb))
+    d = lc.ConvDesc(cs.n, cs.c, cs.h, cs.w, cs.k, cs.r, cs.s, cs.stride, cs.stride, cs.pad, cs.pad, lc.LC_BF16, lc.LC_NHWC)
+    assert lc.conv2d_workspace_bytes(d, lc.LC_PASS_FWD) > 800_000_000           # the unfolded input
+    xd, wd, dyd = _dev_bf16(xb), _dev_bf16(wb), _dev_bf16(dyb)
+    y = torch.empty((cs.n, cs.p, cs.q, cs.k), dtype=torch.int16, device=gu.DEV)
+    dw = torch.empty((cs.k, cs.r, cs.s, cs.c), dtype=torch.float32, device=gu.DEV)
+    lc.conv2d_fwd(d, xd, wd, y, gu.workspace(lc.conv2d_workspace_bytes(d, lc.LC_PASS_FWD)))
+    lc.conv2d_bwd_weight(d, xd, dyd, dw, gu.workspace(lc.conv2d_workspace_bytes(d, lc.LC_PASS_BWD_WEIGHT)))
+    torch.cuda.synchronize()
+    y, dw = _back(y), dw.cpu().numpy()
+    # samples spread over the image, plus the four corners of the first and the last image (padding on two sides each)
+    cy = synth.sample_coords(1024, (cs.n, cs.k, cs.p, cs.q), seed + 3)
+    corners = np.array([[n_, k_, p_, q_] for n_ in (0, cs.n - 1) for k_ in (0, cs.k - 1) for p_ in (0, cs.p - 1) for q_ in (0, cs.q - 1)],
+                       dtype=np.int32)
+    cy = np.concatenate([cy, corners])
+    ref, _ = oracle.conv2d_fwd_at(x, wt, cy, cs.stride, cs.pad, oracle.NHWC)
+    got = y[cy[:, 0], cy[:, 2], cy[:, 3], cy[:, 1]]
+    assert np.max(np.abs(got - oracle.round_to_bf16(ref))) <= TOL_BF16 * np.max(np.abs(ref))
+    assert np.all(np.abs(got - ref) <= np.abs(ref) * 2.0 ** -7 + 1e-6 * np.max(np.abs(ref)))
+    cw = synth.sample_coords(96, (cs.k, cs.c, cs.r, cs.s), seed + 5)
+    ref, _ = oracle.conv2d_bwd_weight_at(x, dy, (cs.r, cs.s), cw, cs.stride, cs.pad, oracle.NHWC)
+    assert np.max(np.abs(dw[cw[:, 0], cw[:, 2], cw[:, 3], cw[:, 1]] - ref)) <= TOL_DW * np.max(np.abs(ref))
+
+
 def test_bf16_wide_tile_ragged_edges_sampled():
     """A result wide and tall enough for the 128x256 tile of the main kernel (at least three rounds of tiles), with a
     ragged last tile in both directions: 103,488 rows (808.5 tiles), 300 columns (256 + 44).  Sampled outputs plus the
