@@ -539,7 +539,12 @@ def run_full_step(args):
     from paper_1709_05011_amd.alexnet_step import AlexNetStep
     from paper_1709_05011_amd.resnet_step import ResNetStep
 
-    batch = args.batch or 256
+    from paper_1709_05011_amd import larsconv as lc
+
+    bf16 = args.dtype == "bf16"
+    if bf16 and args.model != "resnet50":
+        raise SystemExit("--full-step --dtype bf16 is built for --model resnet50")
+    batch = args.batch or (512 if bf16 else 256)
     gen = torch.Generator(device="cuda:0")
     gen.manual_seed(0x5EED0600)
     alex = args.model == "alexnet_bn"
@@ -547,15 +552,23 @@ def run_full_step(args):
         net = AlexNetStep(((96, 11, 4, 0, True), (256, 5, 1, 2, True), (384, 3, 1, 1, False), (384, 3, 1, 1, False),
                            (256, 3, 1, 1, True)), (4096, 4096), 1000, batch, (227, 227))
     else:
-        net = ResNetStep((64, 7, 2, 3), (64, 128, 256, 512), (3, 4, 6, 3), 1000, batch, (224, 224))
+        net = ResNetStep((64, 7, 2, 3), (64, 128, 256, 512), (3, 4, 6, 3), 1000, batch, (224, 224),
+                         dtype=lc.LC_BF16 if bf16 else lc.LC_F32)
     side = 227 if alex else 224
     label = f"{'AlexNet-BN' if alex else 'ResNet-50'} whole training step (all layers + LARS), batch {batch}, {side}x{side}, NHWC"
+    if bf16:
+        label += ", bf16 activations and filters, fp32 master weights"
     metric = ("alexnet_bn" if alex else "resnet50") + "_whole_step_images_per_second"
+    dtype_name = "bf16" if bf16 else "f32"
     for name, t in net.params.items():
         if name.endswith(".w"):
             fan = t[0].numel()
             t.copy_(torch.randn(t.shape, generator=gen, device="cuda:0") * (2.0 / fan) ** 0.5)
+            if bf16 and name in net.lowp:
+                net.lowp[name].copy_(t)             # input preparation; from the first update on lars_step writes these copies
     x = torch.randn((batch, side, side, 3), generator=gen, device="cuda:0")
+    if bf16:
+        x = x.to(torch.bfloat16)
     labels = torch.randint(0, 1000, (batch,), generator=gen, device="cuda:0", dtype=torch.int32)
     lr = 0.1
     for _ in range(args.warmup):
@@ -575,7 +588,7 @@ def run_full_step(args):
         ms = (time.perf_counter() - t0) * 1e3 / args.steps
         return {"metric": metric, "value": round(batch / (ms * 1e-3), 1), "unit": "images/s",
                 "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms, 3), "higher_is_better": True,
-                "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+                "scaling": "weak", "vs_baseline": None, "dtype": dtype_name, "data": "synthetic",
                 "config": {"workload": label + ", one HIP graph"},
                 "loss": round(float(net.loss.item()), 4)}
     ev = [torch.cuda.Event(enable_timing=True) for _ in range(4)]
@@ -596,7 +609,7 @@ def run_full_step(args):
     ms = wall * 1e3 / args.steps
     return {"metric": metric, "value": round(batch / (ms * 1e-3), 1), "unit": "images/s", "n_gpus": 1,
             "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms, 3), "higher_is_better": True, "scaling": "weak",
-            "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+            "vs_baseline": None, "dtype": dtype_name, "data": "synthetic",
             "config": {"workload": label},
             "phase_ms": {k: round(v / args.steps, 3) for k, v in phases.items()}, "loss": round(float(loss.item()), 4),
             "peak_memory_GB": round(torch.cuda.max_memory_allocated() / 1e9, 2)}
@@ -687,6 +700,12 @@ def add_secondary_measurements(res, args):
                         "conv_tflops": bf["conv_tflops"], "conv_tflops_all": bf["conv_tflops_all"],
                         "conv_frac_of_mfma_peak": bf["conv_frac_of_mfma_peak"], "roofline": bf["roofline"],
                         "lars_in_step": bf["lars"]["in_step"], "workload": bf["config"]["workload"]}
+    release()
+    c = copy.copy(args)
+    c.steps, c.warmup, c.graph, c.full_step, c.dtype = 5, 2, False, True, "bf16"
+    bfull = run_full_step(c)
+    res["bf16_whole_step"] = {"ms_per_step": bfull["ms_per_step"], "images_per_s": bfull["value"], "batch": 512,
+                              "phase_ms": bfull["phase_ms"], "steps": c.steps, "workload": bfull["config"]["workload"]}
     release()
 
 

@@ -256,6 +256,30 @@ lc_status batchnorm_bwd_ex(const float* x, const float* dy, const float* gamma, 
                            const float* save_invstd, float* dx, float* dgamma, float* dbeta, int n, int c, int h, int w, int relu,
                            lc_layout layout, void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/* ---- The same layers on bf16 activations: the rest of a mixed-precision step ----
+ * The paper's fastest ResNet-50 runs train in reduced precision with fp32 master weights ("State-of-the-art
+ * results"); with LC_BF16 convolutions the activations between them are bf16, and these calls take them as they
+ * are.  `dtype` is the storage type of every `void*` tensor argument: LC_F32 is exactly the call of the same name
+ * without `_t`; LC_BF16 means bf16 bit patterns in NHWC with c (count for relu_add_bwd_t) a multiple of 8 and
+ * 16-byte aligned tensors (idx 8-byte aligned) -- anything else is LC_ERR_UNSUPPORTED / LC_ERR_ALIGN.
+ * All arithmetic is fp32 on the widened values, with the operation order of the fp32 kernels; a result stored as
+ * bf16 is rounded once, to nearest even.  gamma, beta, statistics, dgamma, dbeta stay fp32; the statistics are
+ * those of the bf16 values of x.  global_avgpool_fwd_t gives fp32 means and global_avgpool_bwd_t takes an fp32
+ * dy (the classifier behind it runs in fp32).  Workspace: batchnorm_workspace_bytes, for either type. */
+lc_status batchnorm_fwd_t(lc_dtype dtype, const void* x, const float* gamma, const float* beta, const void* residual, void* y,
+                          float* save_mean, float* save_invstd, int n, int c, int h, int w, float eps, int relu, lc_layout layout,
+                          void* workspace, size_t workspace_bytes, void* hip_stream);
+lc_status batchnorm_bwd_t(lc_dtype dtype, const void* x, const void* dy, const float* gamma, const float* beta, const float* save_mean,
+                          const float* save_invstd, void* dx, float* dgamma, float* dbeta, int n, int c, int h, int w, int relu,
+                          lc_layout layout, void* workspace, size_t workspace_bytes, void* hip_stream);
+lc_status maxpool_fwd_t(lc_dtype dtype, const void* x, void* y, uint8_t* idx, int n, int c, int h, int w, int window, int stride,
+                        int pad, lc_layout layout, void* hip_stream);
+lc_status maxpool_bwd_t(lc_dtype dtype, const void* dy, const uint8_t* idx, void* dx, int n, int c, int h, int w, int window,
+                        int stride, int pad, lc_layout layout, void* hip_stream);
+lc_status relu_add_bwd_t(lc_dtype dtype, const void* y, const void* da, const void* db, void* dx, size_t count, void* hip_stream);
+lc_status global_avgpool_fwd_t(lc_dtype dtype, const void* x, float* y, int n, int c, int h, int w, lc_layout layout, void* hip_stream);
+lc_status global_avgpool_bwd_t(lc_dtype dtype, const float* dy, void* dx, int n, int c, int h, int w, lc_layout layout, void* hip_stream);
+
 /* Static, human-readable name of a status code. */
 const char* lc_status_string(lc_status status);
 

@@ -10,6 +10,13 @@ global average pool, a fully connected classifier with bias, softmax cross-entro
 Every piece is the textbook definition in numpy float64; the convolutions go through ``oracle.c``; values are
 stored as float32 between layers, as a GPU worker stores them.  Layout NCHW.
 
+Mixed precision (``forward_backward_bf16``): the paper's fastest runs train in reduced precision with float32
+master weights ("State-of-the-art results") and say no more about it; the reading taken here is the usual one.
+Activations and their gradients are stored as bf16 (rounded to nearest even wherever the float32 trace rounds to
+float32), the convolutions see the filters rounded to bf16, and everything a parameter owns (scale, shift,
+statistics, every gradient of a parameter) as well as the pooled features, the classifier and the loss stay
+float32.
+
 ``Config`` fixes the sizes: ResNet-50 is Config(stem=(64, 7, 2, 3), widths=(64, 128, 256, 512),
 blocks=(3, 4, 6, 3), classes=1000); tests use a few-channel version of the same graph.
 """
@@ -20,7 +27,7 @@ from typing import Dict, List, Tuple
 
 import numpy as np
 
-from . import NCHW, batchnorm, conv2d_bwd_data, conv2d_bwd_weight, conv2d_fwd
+from . import NCHW, batchnorm, conv2d_bwd_data, conv2d_bwd_weight, conv2d_fwd, round_to_bf16
 from .tiny_cnn import fc, global_avgpool, global_avgpool_bwd, softmax_xent
 
 
@@ -114,28 +121,36 @@ def _f32(a):
 
 class _Net:
     """Runs the graph once, keeping what the backward pass needs.  ``store`` rounds to float32 between
-    layers (the trace a device is compared with) or keeps float64 (finite differences)."""
+    layers (the trace a device is compared with) or keeps float64 (finite differences); ``bf16`` stores
+    activations and their gradients as bf16 instead and hands the convolutions bf16 filters."""
 
-    def __init__(self, cfg: Config, params, store: bool):
-        self.cfg, self.p, self.store = cfg, params, store
+    def __init__(self, cfg: Config, params, store: bool, bf16: bool = False):
+        self.cfg, self.p, self.store, self.bf16 = cfg, params, store, bf16
         self.t: Dict[str, np.ndarray] = {}
         self.g: Dict[str, np.ndarray] = {}
 
     def keep(self, a):
         return _s(a) if self.store else np.asarray(a, dtype=np.float64)
 
+    def act(self, a):
+        """An activation or the gradient of one, as it is stored between layers."""
+        return round_to_bf16(np.asarray(a, dtype=np.float64)).astype(np.float64) if self.bf16 else self.keep(a)
+
+    def filt(self, name):
+        w = _f32(self.p[name + ".w"])
+        return round_to_bf16(w) if self.bf16 else w
+
     def conv(self, x, name, stride, pad):
-        w = self.p[name + ".w"]
         if self.store:
-            return self.keep(conv2d_fwd(_f32(x), _f32(w), stride, pad, NCHW))
-        return _conv_f64(x, np.asarray(w, dtype=np.float64), stride, pad)
+            return self.act(conv2d_fwd(_f32(x), self.filt(name), stride, pad, NCHW))
+        return _conv_f64(x, np.asarray(self.p[name + ".w"], dtype=np.float64), stride, pad)
 
     def conv_bn(self, x, name, stride, pad, relu, residual=None):
         z = self.conv(x, name, stride, pad)
         y, _, _ = batchnorm.forward(z, self.p[name + ".gamma"], self.p[name + ".beta"], self.cfg.eps)
         if residual is not None:
             y = y + residual
-        a = self.keep(np.maximum(y, 0.0) if relu else y)
+        a = self.act(np.maximum(y, 0.0) if relu else y)
         self.t[name + ".x"], self.t[name + ".z"], self.t[name + ".a"] = x, z, a
         self.t[name + ".y"] = y                # before the ReLU, unrounded: tests look at its distance from zero
         return a
@@ -145,20 +160,23 @@ class _Net:
         x, z = self.t[name + ".x"], self.t[name + ".z"]
         w = self.p[name + ".w"]
         dz, dgamma, dbeta = batchnorm.backward(z, da, self.p[name + ".gamma"], self.cfg.eps)
-        dz = self.keep(dz)
+        dz = self.act(dz)
         self.g[name + ".gamma"], self.g[name + ".beta"] = self.keep(dgamma), self.keep(dbeta)
         r = w.shape[2]
         self.g[name + ".w"] = self.keep(conv2d_bwd_weight(_f32(x), _f32(dz), (r, r), stride, pad, NCHW))
+        self.t[name + ".dz"] = dz
         if not need_dx:
             return None
-        return self.keep(conv2d_bwd_data(_f32(dz), _f32(w), x.shape[2:], stride, pad, NCHW))
+        dx = self.act(conv2d_bwd_data(_f32(dz), self.filt(name), x.shape[2:], stride, pad, NCHW))
+        self.t[name + ".dx"] = dx
+        return dx
 
     def forward(self, x, labels):
         cfg = self.cfg
-        a = self.conv_bn(self.keep(x), "stem", cfg.stem[2], cfg.stem[3], relu=True)
+        a = self.conv_bn(self.act(x), "stem", cfg.stem[2], cfg.stem[3], relu=True)
         self.t["pool.in_hw"] = a.shape[2:]
         pooled, self.t["pool.idx"] = maxpool(a, 3, 2, 1)
-        a = self.keep(pooled)
+        a = self.act(pooled)
         ch = cfg.stem[0]
         self.blocks: List[Tuple[str, int, bool]] = []
         for si, (wd, nb) in enumerate(zip(cfg.widths, cfg.blocks)):
@@ -187,19 +205,19 @@ class _Net:
         self.g["fc.b"] = self.keep(d.sum(axis=0))
         dpool = self.keep(d @ np.asarray(self.p["fc.w"], dtype=np.float64))
         last = self.t["gap.in"]
-        da = self.keep(global_avgpool_bwd(dpool, last.shape[2], last.shape[3]))        # gradient wrt the last block's output
+        da = self.act(global_avgpool_bwd(dpool, last.shape[2], last.shape[3]))         # gradient wrt the last block's output
         for name, stride, proj in reversed(self.blocks):
             out = self.t[name + ".c3.a"]
-            d_pre = self.keep(np.where(out > 0.0, da, 0.0))                           # through the block's last ReLU
+            d_pre = self.act(np.where(out > 0.0, da, 0.0))                            # through the block's last ReLU
             db = self.conv_bn_bwd(name + ".c3", d_pre, 1, 0)
-            db = self.keep(np.where(self.t[name + ".c2.a"] > 0.0, db, 0.0))
+            db = self.act(np.where(self.t[name + ".c2.a"] > 0.0, db, 0.0))
             db = self.conv_bn_bwd(name + ".c2", db, 1, 1)
-            db = self.keep(np.where(self.t[name + ".c1.a"] > 0.0, db, 0.0))
+            db = self.act(np.where(self.t[name + ".c1.a"] > 0.0, db, 0.0))
             d_in = self.conv_bn_bwd(name + ".c1", db, stride, 0)
             d_sc = self.conv_bn_bwd(name + ".proj", d_pre, stride, 0) if proj else d_pre
-            da = self.keep(d_in + d_sc)
-        da = self.keep(maxpool_bwd(self.t["pool.idx"], da, self.t["pool.in_hw"], 3, 2, 1))
-        da = self.keep(np.where(self.t["stem.a"] > 0.0, da, 0.0))
+            da = self.act(d_in + d_sc)
+        da = self.act(maxpool_bwd(self.t["pool.idx"], da, self.t["pool.in_hw"], 3, 2, 1))
+        da = self.act(np.where(self.t["stem.a"] > 0.0, da, 0.0))
         self.conv_bn_bwd("stem", da, self.cfg.stem[2], self.cfg.stem[3], need_dx=False)
 
 
@@ -220,9 +238,19 @@ def _conv_f64(x, w, stride, pad):
 def forward_backward(x, labels, params, cfg: Config):
     """One forward and backward pass with float32 stores.  Returns (trace, grads): the trace holds
     "<conv>.z" (convolution output), "<conv>.y" (after batch norm and residual, before the ReLU, float64),
-    "<conv>.a" (the stored activation), "logits", "loss";
+    "<conv>.a" (the stored activation), "<conv>.dz" / "<conv>.dx" (the stored gradients with respect to the
+    convolution's output and input), "logits", "loss";
     grads has one entry per parameter name."""
     net = _Net(cfg, params, store=True)
+    _, dlogits = net.forward(np.asarray(x, dtype=np.float32), labels)
+    net.backward(dlogits)
+    return net.t, net.g
+
+
+def forward_backward_bf16(x, labels, params, cfg: Config):
+    """The same pass with bf16 activations, activation gradients and convolution filters (see the module
+    header); parameters and their gradients float32.  ``x`` is rounded to bf16 first.  Returns (trace, grads)."""
+    net = _Net(cfg, params, store=True, bf16=True)
     _, dlogits = net.forward(np.asarray(x, dtype=np.float32), labels)
     net.backward(dlogits)
     return net.t, net.g

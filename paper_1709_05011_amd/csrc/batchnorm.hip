@@ -55,11 +55,55 @@ __device__ __forceinline__ void scale_shift(float gamma, float beta, float mean,
     *shift = (float)fma(-(double)mean, sc, (double)beta);
 }
 
+// VEC consecutive elements of a tensor of fp32 values (T = float) or bf16 bit patterns (T = uint16_t) as floats and back
+// (bf16 -> fp32 is exact; fp32 -> bf16 rounds to nearest even).  One 16-byte access where VEC elements fill it.
+template <typename T, int VEC>
+struct Pack;
+template <>
+struct Pack<float, 4> {
+    static __device__ __forceinline__ void load(const float* p, float (&v)[4]) {
+        const float4 u = *reinterpret_cast<const float4*>(p);
+        v[0] = u.x; v[1] = u.y; v[2] = u.z; v[3] = u.w;
+    }
+    static __device__ __forceinline__ void store(float* p, const float (&v)[4]) {
+        *reinterpret_cast<float4*>(p) = make_float4(v[0], v[1], v[2], v[3]);
+    }
+};
+template <>
+struct Pack<float, 1> {
+    static __device__ __forceinline__ void load(const float* p, float (&v)[1]) { v[0] = *p; }
+    static __device__ __forceinline__ void store(float* p, const float (&v)[1]) { *p = v[0]; }
+};
+template <>
+struct Pack<uint16_t, 8> {
+    static __device__ __forceinline__ void load(const uint16_t* p, float (&v)[8]) {
+        const uint4 u = *reinterpret_cast<const uint4*>(p);
+        const unsigned w[4] = {u.x, u.y, u.z, u.w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            v[2 * i] = __uint_as_float(w[i] << 16);
+            v[2 * i + 1] = __uint_as_float(w[i] & 0xffff0000u);
+        }
+    }
+    static __device__ __forceinline__ void store(uint16_t* p, const float (&v)[8]) {
+        unsigned w[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) w[i] = lc_bf16x2_rne(v[2 * i], v[2 * i + 1]);
+        *reinterpret_cast<uint4*>(p) = make_uint4(w[0], w[1], w[2], w[3]);
+    }
+};
+template <typename T>
+__device__ __forceinline__ float widen(T v);
+template <>
+__device__ __forceinline__ float widen<float>(float v) { return v; }
+template <>
+__device__ __forceinline__ float widen<uint16_t>(uint16_t v) { return __uint_as_float((unsigned)v << 16); }
+
 // ---------------- NHWC ----------------
 // MODE kStats: sums of x and x^2.  kSums: sums of dy and dy * (x - mean) * inv_std.  kMaskedSums: the same with
 // dy taken as zero where scale*x + shift <= 0.
-template <int VEC, int MODE>
-__global__ void __launch_bounds__(kThreads) bn_reduce_nhwc_kernel(const float* __restrict__ x, const float* __restrict__ dy,
+template <typename T, int VEC, int MODE>
+__global__ void __launch_bounds__(kThreads) bn_reduce_nhwc_kernel(const T* __restrict__ x, const T* __restrict__ dy,
                                                                   const float* __restrict__ mean, const float* __restrict__ inv_std,
                                                                   const float* __restrict__ gamma, const float* __restrict__ beta,
                                                                   BnGeom g, BnWorkspace ws) {
@@ -78,22 +122,13 @@ __global__ void __launch_bounds__(kThreads) bn_reduce_nhwc_kernel(const float* _
         is[e] = (!STATS && live) ? inv_std[c0 + e] : 0.f;
         sc[e] = sh[e] = 0.f;
         if (MODE == kMaskedSums && live) scale_shift(gamma[c0 + e], beta[c0 + e], mu[e], is[e], &sc[e], &sh[e]);
-        if (STATS && live) mu[e] = x[c0 + e];          // the channel's pivot: its value at the first pixel
+        if (STATS && live) mu[e] = widen<T>(x[c0 + e]);   // the channel's pivot: its value at the first pixel
     }
     if (live) {
         for (long long r = r0 + ty; r < r1; r += g.ty) {
             float a[VEC], b[VEC];
-            if constexpr (VEC == 4) {
-                const float4 va = *reinterpret_cast<const float4*>(x + r * g.C + c0);
-                a[0] = va.x; a[1] = va.y; a[2] = va.z; a[3] = va.w;
-                if constexpr (!STATS) {
-                    const float4 vb = *reinterpret_cast<const float4*>(dy + r * g.C + c0);
-                    b[0] = vb.x; b[1] = vb.y; b[2] = vb.z; b[3] = vb.w;
-                }
-            } else {
-                a[0] = x[r * g.C + c0];
-                if constexpr (!STATS) b[0] = dy[r * g.C + c0];
-            }
+            Pack<T, VEC>::load(x + r * g.C + c0, a);
+            if constexpr (!STATS) Pack<T, VEC>::load(dy + r * g.C + c0, b);
 #pragma unroll
             for (int e = 0; e < VEC; ++e) {
                 if constexpr (STATS) {
@@ -131,42 +166,57 @@ __global__ void __launch_bounds__(kThreads) bn_reduce_nhwc_kernel(const float* _
 
 // out = p*A + q*B + r per channel (TWO false: out = p*A + r).  RELU: clamp the result at zero.  MASK: B counts as
 // zero where scale*A + shift <= 0.
-template <int VEC, bool TWO, bool RELU, bool MASK>
-__global__ void __launch_bounds__(kThreads) bn_apply_nhwc_kernel(const float* __restrict__ a, const float* __restrict__ b,
-                                                                 float* __restrict__ out, const float* __restrict__ coef, BnGeom g) {
-    const size_t total = (size_t)g.M * g.C / VEC;
-    for (size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x; i < total; i += (size_t)gridDim.x * blockDim.x) {
-        const int c0 = (int)((i * VEC) % g.C);
-        if constexpr (VEC == 4) {
-            const float4 va = reinterpret_cast<const float4*>(a)[i];
-            const float4 p = *reinterpret_cast<const float4*>(coef + c0);
-            const float4 r = *reinterpret_cast<const float4*>(coef + 2 * g.C + c0);
-            float4 o = make_float4(fmaf(p.x, va.x, r.x), fmaf(p.y, va.y, r.y), fmaf(p.z, va.z, r.z), fmaf(p.w, va.w, r.w));
-            if constexpr (TWO) {
-                float4 vb = reinterpret_cast<const float4*>(b)[i];
-                const float4 q = *reinterpret_cast<const float4*>(coef + g.C + c0);
-                if constexpr (MASK) {
-                    const float4 sc = *reinterpret_cast<const float4*>(coef + 3 * g.C + c0);
-                    const float4 sh = *reinterpret_cast<const float4*>(coef + 4 * g.C + c0);
-                    if (!(fmaf(sc.x, va.x, sh.x) > 0.f)) vb.x = 0.f;
-                    if (!(fmaf(sc.y, va.y, sh.y) > 0.f)) vb.y = 0.f;
-                    if (!(fmaf(sc.z, va.z, sh.z) > 0.f)) vb.z = 0.f;
-                    if (!(fmaf(sc.w, va.w, sh.w) > 0.f)) vb.w = 0.f;
-                }
-                o.x = fmaf(q.x, vb.x, o.x); o.y = fmaf(q.y, vb.y, o.y); o.z = fmaf(q.z, vb.z, o.z); o.w = fmaf(q.w, vb.w, o.w);
-            }
-            if constexpr (RELU) { o.x = fmaxf(o.x, 0.f); o.y = fmaxf(o.y, 0.f); o.z = fmaxf(o.z, 0.f); o.w = fmaxf(o.w, 0.f); }
-            reinterpret_cast<float4*>(out)[i] = o;
-        } else {
-            float o = fmaf(coef[c0], a[i], coef[2 * g.C + c0]);
-            if constexpr (TWO) {
-                float vb = b[i];
-                if constexpr (MASK) if (!(fmaf(coef[3 * g.C + c0], a[i], coef[4 * g.C + c0]) > 0.f)) vb = 0.f;
-                o = fmaf(coef[g.C + c0], vb, o);
-            }
-            if constexpr (RELU) o = fmaxf(o, 0.f);
-            out[i] = o;
+// VEC consecutive per-channel coefficients (16-byte loads where VEC allows: the arrays start 16-byte aligned and the
+// vector paths have c a multiple of VEC)
+template <int VEC>
+__device__ __forceinline__ void load_coef(const float* __restrict__ p, float (&v)[VEC]) {
+    if constexpr (VEC % 4 == 0) {
+#pragma unroll
+        for (int q = 0; q < VEC / 4; ++q) {
+            const float4 u = reinterpret_cast<const float4*>(p)[q];
+            v[4 * q] = u.x; v[4 * q + 1] = u.y; v[4 * q + 2] = u.z; v[4 * q + 3] = u.w;
         }
+    } else {
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) v[e] = p[e];
+    }
+}
+
+// INV: the launch makes (threads in the grid) * VEC a multiple of c, so a thread meets the same channels on every
+// trip of its loop and keeps their coefficients in registers.
+template <typename T, int VEC, bool TWO, bool RELU, bool MASK, bool INV>
+__global__ void __launch_bounds__(kThreads) bn_apply_nhwc_kernel(const T* __restrict__ a, const T* __restrict__ b, T* __restrict__ out,
+                                                                 const float* __restrict__ coef, BnGeom g) {
+    const size_t total = (size_t)g.M * g.C / VEC;
+    const size_t first = blockIdx.x * (size_t)blockDim.x + threadIdx.x, stride = (size_t)gridDim.x * blockDim.x;
+    float p[VEC], r[VEC], q[TWO ? VEC : 1], ms[MASK ? VEC : 1], mh[MASK ? VEC : 1];
+    auto coefficients = [&](int c0) {
+        load_coef<VEC>(coef + c0, p);
+        load_coef<VEC>(coef + 2 * g.C + c0, r);
+        if constexpr (TWO) load_coef<VEC>(coef + g.C + c0, q);
+        if constexpr (MASK) {
+            load_coef<VEC>(coef + 3 * g.C + c0, ms);
+            load_coef<VEC>(coef + 4 * g.C + c0, mh);
+        }
+    };
+    if constexpr (INV) coefficients((int)((first * VEC) % g.C));
+    for (size_t i = first; i < total; i += stride) {
+        if constexpr (!INV) coefficients((int)((i * VEC) % g.C));
+        float va[VEC], vb[VEC], o[VEC];
+        Pack<T, VEC>::load(a + i * VEC, va);
+        if constexpr (TWO) Pack<T, VEC>::load(b + i * VEC, vb);
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) {
+            o[e] = fmaf(p[e], va[e], r[e]);
+            if constexpr (TWO) {
+                float t = vb[e];
+                if constexpr (MASK)
+                    if (!(fmaf(ms[e], va[e], mh[e]) > 0.f)) t = 0.f;
+                o[e] = fmaf(q[e], t, o[e]);
+            }
+            if constexpr (RELU) o[e] = fmaxf(o[e], 0.f);
+        }
+        Pack<T, VEC>::store(out + i * VEC, o);
     }
 }
 
@@ -233,21 +283,30 @@ __global__ void __launch_bounds__(kThreads) bn_apply_nchw_kernel(const float* __
 }
 
 // ---------------- per-channel finalize ----------------
-// A block of 256 threads finishes 16 channels: 16 lanes per channel add every 16th slab's partial, then the first
-// lane adds the 16 lane sums in lane order.  Returns true in the thread that holds the channel's totals.
-constexpr int kFinChannels = 16, kFinLanes = 16;
+// A block of 256 threads finishes 4 channels: 64 lanes per channel add every 64th slab's partial (two running sums
+// each, so that loads overlap), then the first lane adds the 64 lane sums in lane order.  Returns true in the thread
+// that holds the channel's totals.  Few channels per block: the layers with 64 channels still start 16 blocks.
+constexpr int kFinChannels = 4, kFinLanes = 64;
 __device__ __forceinline__ bool channel_totals(const BnWorkspace& ws, const BnGeom& g, int* ch_out, double* t0, double* t1) {
     __shared__ double red[kFinLanes][kFinChannels][2];
     const int cl = threadIdx.x % kFinChannels, sl = threadIdx.x / kFinChannels;
     const int ch = blockIdx.x * kFinChannels + cl;
-    double s0 = 0.0, s1 = 0.0;
-    if (ch < g.C)
-        for (int k = sl; k < g.slabs; k += kFinLanes) {
-            s0 += ws.partial[((size_t)k * g.C + ch) * 2];
-            s1 += ws.partial[((size_t)k * g.C + ch) * 2 + 1];
+    double s0 = 0.0, s1 = 0.0, u0 = 0.0, u1 = 0.0;
+    if (ch < g.C) {
+        const double2* part = reinterpret_cast<const double2*>(ws.partial);
+        int k = sl;
+        for (; k + kFinLanes < g.slabs; k += 2 * kFinLanes) {
+            const double2 a = part[(size_t)k * g.C + ch], b = part[(size_t)(k + kFinLanes) * g.C + ch];
+            s0 += a.x; s1 += a.y;
+            u0 += b.x; u1 += b.y;
         }
-    red[sl][cl][0] = s0;
-    red[sl][cl][1] = s1;
+        if (k < g.slabs) {
+            const double2 a = part[(size_t)k * g.C + ch];
+            s0 += a.x; s1 += a.y;
+        }
+    }
+    red[sl][cl][0] = s0 + u0;
+    red[sl][cl][1] = s1 + u1;
     __syncthreads();
     if (sl != 0 || ch >= g.C) return false;
     s0 = s1 = 0.0;
@@ -262,15 +321,16 @@ __device__ __forceinline__ bool channel_totals(const BnWorkspace& ws, const BnGe
 }
 
 // forward: mean, 1/std, and y = scale*x + shift (+ residual)
+template <typename T>
 __global__ void __launch_bounds__(kFinChannels* kFinLanes)
-bn_finalize_fwd_kernel(BnWorkspace ws, const float* __restrict__ x, size_t pivot_stride, const float* __restrict__ gamma,
+bn_finalize_fwd_kernel(BnWorkspace ws, const T* __restrict__ x, size_t pivot_stride, const float* __restrict__ gamma,
                        const float* __restrict__ beta, float* __restrict__ save_mean, float* __restrict__ save_invstd, BnGeom g, float eps) {
     int ch;
     double s0, s1;
     if (!channel_totals(ws, g, &ch, &s0, &s1)) return;
     const double m = (double)g.M;
     const double off = s0 / m;                                  // mean of x - pivot
-    const double mean = (double)x[ch * pivot_stride] + off;
+    const double mean = (double)widen<T>(x[ch * pivot_stride]) + off;
     double var = s1 / m - off * off;
     if (var < 0.0) var = 0.0;
     const double inv_std = 1.0 / sqrt(var + (double)eps);
@@ -307,7 +367,7 @@ bn_finalize_bwd_kernel(BnWorkspace ws, const float* __restrict__ gamma, const fl
     }
 }
 
-bool geometry(int n, int c, int h, int w, lc_layout layout, bool aligned16, BnGeom* g) {
+bool geometry(int n, int c, int h, int w, lc_layout layout, bool aligned16, BnGeom* g, int wide = 4) {
     if (n <= 0 || c <= 0 || h <= 0 || w <= 0) return false;
     const long long hw = (long long)h * w;
     if (hw > 0x7fffffffLL) return false;
@@ -316,7 +376,7 @@ bool geometry(int n, int c, int h, int w, lc_layout layout, bool aligned16, BnGe
     g->HW = (int)hw;
     g->M = (long long)n * hw;
     if (layout == LC_NHWC) {
-        g->vec = (c % 4 == 0 && aligned16) ? 4 : 1;
+        g->vec = (c % wide == 0 && aligned16) ? wide : 1;     // wide: elements in 16 bytes
         const int groups = c / g->vec;
         int tx = 1;
         while (tx < groups && tx < 64) tx <<= 1;
@@ -352,6 +412,18 @@ inline unsigned stream_blocks(size_t items) {
     return (unsigned)(b ? b : 1);
 }
 
+// grid of the NHWC apply pass over `items` threads' worth of work; *inv: the grid was sized so that every thread stays on
+// one group of channels (grid * kThreads * vec is a multiple of c)
+inline unsigned apply_blocks(size_t items, int c, int vec, bool* inv) {
+    unsigned b = stream_blocks(items);
+    long long x = (long long)kThreads * vec, y = c;
+    while (y) { const long long t = x % y; x = y; y = t; }            // x = gcd(kThreads * vec, c)
+    const long long m = c / x;
+    *inv = m <= 64;
+    if (*inv) b = (unsigned)((b + m - 1) / m * m);
+    return b;
+}
+
 inline bool al16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
 inline bool al4(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 3) == 0; }
 
@@ -368,15 +440,25 @@ extern "C" size_t batchnorm_workspace_bytes(int n, int c, int h, int w, lc_layou
     return a > b ? a : b;
 }
 
-extern "C" lc_status batchnorm_fwd_ex(const float* x, const float* gamma, const float* beta, const float* residual, float* y,
-                                      float* save_mean, float* save_invstd, int n, int c, int h, int w, float eps, int relu,
-                                      lc_layout layout, void* workspace, size_t workspace_bytes, void* hip_stream) {
+namespace {
+
+// bf16 tensors are taken in NHWC with whole 16-byte groups of channels only (what the bf16 convolutions produce)
+template <typename T>
+constexpr int kWide = 16 / (int)sizeof(T);
+
+template <typename T>
+lc_status bn_fwd_impl(const T* x, const float* gamma, const float* beta, const T* residual, T* y, float* save_mean, float* save_invstd,
+                      int n, int c, int h, int w, float eps, int relu, lc_layout layout, void* workspace, size_t workspace_bytes,
+                      void* hip_stream) {
+    constexpr bool kF32 = sizeof(T) == 4;
     if (!x || !gamma || !beta || !y || !save_mean || !save_invstd) return LC_ERR_NULL;
     if (layout != LC_NCHW && layout != LC_NHWC) return LC_ERR_UNSUPPORTED;
     if (!(eps >= 0.f)) return LC_ERR_SHAPE;
     BnGeom g;
-    if (!geometry(n, c, h, w, layout, al16(x) && al16(y) && al16(residual), &g)) return LC_ERR_SHAPE;
+    if (!geometry(n, c, h, w, layout, al16(x) && al16(y) && al16(residual), &g, kWide<T>)) return LC_ERR_SHAPE;
     if (!al4(x) || !al4(y) || !al4(residual) || !al4(gamma) || !al4(beta) || !al4(save_mean) || !al4(save_invstd)) return LC_ERR_ALIGN;
+    if (!kF32 && layout != LC_NHWC) return LC_ERR_UNSUPPORTED;
+    if (!kF32 && g.vec != kWide<T>) return c % kWide<T> ? LC_ERR_UNSUPPORTED : LC_ERR_ALIGN;
     size_t coef_off;
     const size_t need = ws_layout(g, &coef_off);
     if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255) || workspace_bytes < need) return LC_ERR_WORKSPACE;
@@ -387,57 +469,69 @@ extern "C" lc_status batchnorm_fwd_ex(const float* x, const float* gamma, const 
     lc_begin_call();
     const size_t total = (size_t)g.M * g.C;
     const dim3 fin_grid((c + kFinChannels - 1) / kFinChannels), fin_block(kFinChannels * kFinLanes);
-    const float* none = nullptr;
+    const T* none = nullptr;
+    const float* nonef = nullptr;
     const bool two = residual != nullptr, clamp = relu != 0;
     const size_t pivot_stride = layout == LC_NHWC ? 1 : (size_t)g.HW;       // the first pixel's value of channel ch sits at x[ch * stride]
     if (layout == LC_NHWC) {
         const dim3 grid((unsigned)g.slabs, (unsigned)g.cblocks);
-        if (g.vec == 4)
-            hipLaunchKernelGGL((bn_reduce_nhwc_kernel<4, kStats>), grid, dim3(kThreads), 0, stream, x, none, none, none, none, none, g, ws);
-        else
-            hipLaunchKernelGGL((bn_reduce_nhwc_kernel<1, kStats>), grid, dim3(kThreads), 0, stream, x, none, none, none, none, none, g, ws);
-        hipLaunchKernelGGL(bn_finalize_fwd_kernel, fin_grid, fin_block, 0, stream, ws, x, pivot_stride, gamma, beta, save_mean, save_invstd, g, eps);
-        const dim3 agrid(stream_blocks(total / g.vec));
-#define LC_BN_APPLY(VEC, TWO, RELU) \
-    hipLaunchKernelGGL((bn_apply_nhwc_kernel<VEC, TWO, RELU, false>), agrid, dim3(kThreads), 0, stream, x, residual, y, ws.coef, g)
-        if (g.vec == 4) {
-            if (two) { if (clamp) LC_BN_APPLY(4, true, true); else LC_BN_APPLY(4, true, false); }
-            else { if (clamp) LC_BN_APPLY(4, false, true); else LC_BN_APPLY(4, false, false); }
+        bool inv;
+        const dim3 agrid(apply_blocks(total / g.vec, c, g.vec, &inv));
+#define LC_BN_APPLY(VEC, TWO, RELU)                                                                                                   \
+    do {                                                                                                                              \
+        if (inv)                                                                                                                      \
+            hipLaunchKernelGGL((bn_apply_nhwc_kernel<T, VEC, TWO, RELU, false, true>), agrid, dim3(kThreads), 0, stream, x, residual, y, \
+                               ws.coef, g);                                                                                           \
+        else                                                                                                                          \
+            hipLaunchKernelGGL((bn_apply_nhwc_kernel<T, VEC, TWO, RELU, false, false>), agrid, dim3(kThreads), 0, stream, x, residual, y, \
+                               ws.coef, g);                                                                                           \
+    } while (0)
+#define LC_BN_FWD(VEC)                                                                                                                  \
+    do {                                                                                                                                \
+        hipLaunchKernelGGL((bn_reduce_nhwc_kernel<T, VEC, kStats>), grid, dim3(kThreads), 0, stream, x, none, nonef, nonef, nonef, nonef, g, \
+                           ws);                                                                                                         \
+        hipLaunchKernelGGL(bn_finalize_fwd_kernel<T>, fin_grid, fin_block, 0, stream, ws, x, pivot_stride, gamma, beta, save_mean,      \
+                           save_invstd, g, eps);                                                                                        \
+        if (two) { if (clamp) LC_BN_APPLY(VEC, true, true); else LC_BN_APPLY(VEC, true, false); }                                       \
+        else { if (clamp) LC_BN_APPLY(VEC, false, true); else LC_BN_APPLY(VEC, false, false); }                                         \
+    } while (0)
+        if constexpr (kF32) {
+            if (g.vec == 4) LC_BN_FWD(4); else LC_BN_FWD(1);
         } else {
-            if (two) { if (clamp) LC_BN_APPLY(1, true, true); else LC_BN_APPLY(1, true, false); }
-            else { if (clamp) LC_BN_APPLY(1, false, true); else LC_BN_APPLY(1, false, false); }
+            LC_BN_FWD(8);
         }
+#undef LC_BN_FWD
 #undef LC_BN_APPLY
     } else {
-        hipLaunchKernelGGL((bn_reduce_nchw_kernel<kStats>), dim3((unsigned)g.slabs, (unsigned)c), dim3(kThreads), 0, stream, x, none, none, none,
-                           none, none, g, ws);
-        hipLaunchKernelGGL(bn_finalize_fwd_kernel, fin_grid, fin_block, 0, stream, ws, x, pivot_stride, gamma, beta, save_mean, save_invstd, g, eps);
-        const dim3 agrid(stream_blocks(total));
+        if constexpr (kF32) {
+            hipLaunchKernelGGL((bn_reduce_nchw_kernel<kStats>), dim3((unsigned)g.slabs, (unsigned)c), dim3(kThreads), 0, stream, x, none, nonef,
+                               nonef, nonef, nonef, g, ws);
+            hipLaunchKernelGGL(bn_finalize_fwd_kernel<T>, fin_grid, fin_block, 0, stream, ws, x, pivot_stride, gamma, beta, save_mean,
+                               save_invstd, g, eps);
+            const dim3 agrid(stream_blocks(total));
 #define LC_BN_APPLY(TWO, RELU) \
     hipLaunchKernelGGL((bn_apply_nchw_kernel<TWO, RELU, false>), agrid, dim3(kThreads), 0, stream, x, residual, y, ws.coef, g)
-        if (two) { if (clamp) LC_BN_APPLY(true, true); else LC_BN_APPLY(true, false); }
-        else { if (clamp) LC_BN_APPLY(false, true); else LC_BN_APPLY(false, false); }
+            if (two) { if (clamp) LC_BN_APPLY(true, true); else LC_BN_APPLY(true, false); }
+            else { if (clamp) LC_BN_APPLY(false, true); else LC_BN_APPLY(false, false); }
 #undef LC_BN_APPLY
+        }
     }
     return lc_end_call();
 }
 
-extern "C" lc_status batchnorm_fwd(const float* x, const float* gamma, const float* beta, float* y, float* save_mean,
-                                   float* save_invstd, int n, int c, int h, int w, float eps, lc_layout layout, void* workspace,
-                                   size_t workspace_bytes, void* hip_stream) {
-    return batchnorm_fwd_ex(x, gamma, beta, nullptr, y, save_mean, save_invstd, n, c, h, w, eps, 0, layout, workspace, workspace_bytes,
-                            hip_stream);
-}
-
-extern "C" lc_status batchnorm_bwd_ex(const float* x, const float* dy, const float* gamma, const float* beta, const float* save_mean,
-                                      const float* save_invstd, float* dx, float* dgamma, float* dbeta, int n, int c, int h, int w,
-                                      int relu, lc_layout layout, void* workspace, size_t workspace_bytes, void* hip_stream) {
+template <typename T>
+lc_status bn_bwd_impl(const T* x, const T* dy, const float* gamma, const float* beta, const float* save_mean, const float* save_invstd,
+                      T* dx, float* dgamma, float* dbeta, int n, int c, int h, int w, int relu, lc_layout layout, void* workspace,
+                      size_t workspace_bytes, void* hip_stream) {
+    constexpr bool kF32 = sizeof(T) == 4;
     if (!x || !dy || !gamma || !save_mean || !save_invstd || !dx || !dgamma || !dbeta || (relu && !beta)) return LC_ERR_NULL;
     if (layout != LC_NCHW && layout != LC_NHWC) return LC_ERR_UNSUPPORTED;
     BnGeom g;
-    if (!geometry(n, c, h, w, layout, al16(x) && al16(dy) && al16(dx), &g)) return LC_ERR_SHAPE;
+    if (!geometry(n, c, h, w, layout, al16(x) && al16(dy) && al16(dx), &g, kWide<T>)) return LC_ERR_SHAPE;
     if (!al4(x) || !al4(dy) || !al4(dx) || !al4(gamma) || !al4(beta) || !al4(save_mean) || !al4(save_invstd) || !al4(dgamma) || !al4(dbeta))
         return LC_ERR_ALIGN;
+    if (!kF32 && layout != LC_NHWC) return LC_ERR_UNSUPPORTED;
+    if (!kF32 && g.vec != kWide<T>) return c % kWide<T> ? LC_ERR_UNSUPPORTED : LC_ERR_ALIGN;
     size_t coef_off;
     const size_t need = ws_layout(g, &coef_off);
     if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255) || workspace_bytes < need) return LC_ERR_WORKSPACE;
@@ -452,32 +546,93 @@ extern "C" lc_status batchnorm_bwd_ex(const float* x, const float* dy, const flo
     const float* mask_beta = mask ? beta : nullptr;
     if (layout == LC_NHWC) {
         const dim3 grid((unsigned)g.slabs, (unsigned)g.cblocks);
-#define LC_BN_REDUCE(VEC, MODE) \
-    hipLaunchKernelGGL((bn_reduce_nhwc_kernel<VEC, MODE>), grid, dim3(kThreads), 0, stream, x, dy, save_mean, save_invstd, gamma, mask_beta, g, ws)
-        if (g.vec == 4) { if (mask) LC_BN_REDUCE(4, kMaskedSums); else LC_BN_REDUCE(4, kSums); }
-        else { if (mask) LC_BN_REDUCE(1, kMaskedSums); else LC_BN_REDUCE(1, kSums); }
-#undef LC_BN_REDUCE
-        hipLaunchKernelGGL(bn_finalize_bwd_kernel, fin_grid, fin_block, 0, stream, ws, gamma, mask_beta, save_mean, save_invstd, dgamma, dbeta, g);
-        const dim3 agrid(stream_blocks(total / g.vec));
-#define LC_BN_APPLY(VEC, MASK) \
-    hipLaunchKernelGGL((bn_apply_nhwc_kernel<VEC, true, false, MASK>), agrid, dim3(kThreads), 0, stream, x, dy, dx, ws.coef, g)
-        if (g.vec == 4) { if (mask) LC_BN_APPLY(4, true); else LC_BN_APPLY(4, false); }
-        else { if (mask) LC_BN_APPLY(1, true); else LC_BN_APPLY(1, false); }
-#undef LC_BN_APPLY
+        bool inv;
+        const dim3 agrid(apply_blocks(total / g.vec, c, g.vec, &inv));
+#define LC_BN_BWD(VEC, MODE, MASK)                                                                                                       \
+    do {                                                                                                                                \
+        hipLaunchKernelGGL((bn_reduce_nhwc_kernel<T, VEC, MODE>), grid, dim3(kThreads), 0, stream, x, dy, save_mean, save_invstd, gamma, \
+                           mask_beta, g, ws);                                                                                           \
+        hipLaunchKernelGGL(bn_finalize_bwd_kernel, fin_grid, fin_block, 0, stream, ws, gamma, mask_beta, save_mean, save_invstd, dgamma, \
+                           dbeta, g);                                                                                                   \
+        if (inv)                                                                                                                        \
+            hipLaunchKernelGGL((bn_apply_nhwc_kernel<T, VEC, true, false, MASK, true>), agrid, dim3(kThreads), 0, stream, x, dy, dx,     \
+                               ws.coef, g);                                                                                             \
+        else                                                                                                                            \
+            hipLaunchKernelGGL((bn_apply_nhwc_kernel<T, VEC, true, false, MASK, false>), agrid, dim3(kThreads), 0, stream, x, dy, dx,    \
+                               ws.coef, g);                                                                                             \
+    } while (0)
+        if constexpr (kF32) {
+            if (g.vec == 4) { if (mask) LC_BN_BWD(4, kMaskedSums, true); else LC_BN_BWD(4, kSums, false); }
+            else { if (mask) LC_BN_BWD(1, kMaskedSums, true); else LC_BN_BWD(1, kSums, false); }
+        } else {
+            if (mask) LC_BN_BWD(8, kMaskedSums, true); else LC_BN_BWD(8, kSums, false);
+        }
+#undef LC_BN_BWD
     } else {
-        const dim3 grid((unsigned)g.slabs, (unsigned)c);
-        if (mask)
-            hipLaunchKernelGGL((bn_reduce_nchw_kernel<kMaskedSums>), grid, dim3(kThreads), 0, stream, x, dy, save_mean, save_invstd, gamma, mask_beta, g, ws);
-        else
-            hipLaunchKernelGGL((bn_reduce_nchw_kernel<kSums>), grid, dim3(kThreads), 0, stream, x, dy, save_mean, save_invstd, gamma, mask_beta, g, ws);
-        hipLaunchKernelGGL(bn_finalize_bwd_kernel, fin_grid, fin_block, 0, stream, ws, gamma, mask_beta, save_mean, save_invstd, dgamma, dbeta, g);
-        const dim3 agrid(stream_blocks(total));
-        if (mask)
-            hipLaunchKernelGGL((bn_apply_nchw_kernel<true, false, true>), agrid, dim3(kThreads), 0, stream, x, dy, dx, ws.coef, g);
-        else
-            hipLaunchKernelGGL((bn_apply_nchw_kernel<true, false, false>), agrid, dim3(kThreads), 0, stream, x, dy, dx, ws.coef, g);
+        if constexpr (kF32) {
+            const dim3 grid((unsigned)g.slabs, (unsigned)c);
+            if (mask)
+                hipLaunchKernelGGL((bn_reduce_nchw_kernel<kMaskedSums>), grid, dim3(kThreads), 0, stream, x, dy, save_mean, save_invstd, gamma, mask_beta, g, ws);
+            else
+                hipLaunchKernelGGL((bn_reduce_nchw_kernel<kSums>), grid, dim3(kThreads), 0, stream, x, dy, save_mean, save_invstd, gamma, mask_beta, g, ws);
+            hipLaunchKernelGGL(bn_finalize_bwd_kernel, fin_grid, fin_block, 0, stream, ws, gamma, mask_beta, save_mean, save_invstd, dgamma, dbeta, g);
+            const dim3 agrid(stream_blocks(total));
+            if (mask)
+                hipLaunchKernelGGL((bn_apply_nchw_kernel<true, false, true>), agrid, dim3(kThreads), 0, stream, x, dy, dx, ws.coef, g);
+            else
+                hipLaunchKernelGGL((bn_apply_nchw_kernel<true, false, false>), agrid, dim3(kThreads), 0, stream, x, dy, dx, ws.coef, g);
+        }
     }
     return lc_end_call();
+}
+
+}  // namespace
+
+extern "C" lc_status batchnorm_fwd_ex(const float* x, const float* gamma, const float* beta, const float* residual, float* y,
+                                      float* save_mean, float* save_invstd, int n, int c, int h, int w, float eps, int relu,
+                                      lc_layout layout, void* workspace, size_t workspace_bytes, void* hip_stream) {
+    return bn_fwd_impl<float>(x, gamma, beta, residual, y, save_mean, save_invstd, n, c, h, w, eps, relu, layout, workspace, workspace_bytes,
+                              hip_stream);
+}
+
+extern "C" lc_status batchnorm_fwd_t(lc_dtype dtype, const void* x, const float* gamma, const float* beta, const void* residual, void* y,
+                                     float* save_mean, float* save_invstd, int n, int c, int h, int w, float eps, int relu,
+                                     lc_layout layout, void* workspace, size_t workspace_bytes, void* hip_stream) {
+    if (dtype == LC_F32)
+        return bn_fwd_impl<float>(static_cast<const float*>(x), gamma, beta, static_cast<const float*>(residual), static_cast<float*>(y),
+                                  save_mean, save_invstd, n, c, h, w, eps, relu, layout, workspace, workspace_bytes, hip_stream);
+    if (dtype == LC_BF16)
+        return bn_fwd_impl<uint16_t>(static_cast<const uint16_t*>(x), gamma, beta, static_cast<const uint16_t*>(residual),
+                                     static_cast<uint16_t*>(y), save_mean, save_invstd, n, c, h, w, eps, relu, layout, workspace,
+                                     workspace_bytes, hip_stream);
+    return LC_ERR_UNSUPPORTED;
+}
+
+extern "C" lc_status batchnorm_fwd(const float* x, const float* gamma, const float* beta, float* y, float* save_mean,
+                                   float* save_invstd, int n, int c, int h, int w, float eps, lc_layout layout, void* workspace,
+                                   size_t workspace_bytes, void* hip_stream) {
+    return batchnorm_fwd_ex(x, gamma, beta, nullptr, y, save_mean, save_invstd, n, c, h, w, eps, 0, layout, workspace, workspace_bytes,
+                            hip_stream);
+}
+
+extern "C" lc_status batchnorm_bwd_ex(const float* x, const float* dy, const float* gamma, const float* beta, const float* save_mean,
+                                      const float* save_invstd, float* dx, float* dgamma, float* dbeta, int n, int c, int h, int w,
+                                      int relu, lc_layout layout, void* workspace, size_t workspace_bytes, void* hip_stream) {
+    return bn_bwd_impl<float>(x, dy, gamma, beta, save_mean, save_invstd, dx, dgamma, dbeta, n, c, h, w, relu, layout, workspace,
+                              workspace_bytes, hip_stream);
+}
+
+extern "C" lc_status batchnorm_bwd_t(lc_dtype dtype, const void* x, const void* dy, const float* gamma, const float* beta,
+                                     const float* save_mean, const float* save_invstd, void* dx, float* dgamma, float* dbeta, int n, int c,
+                                     int h, int w, int relu, lc_layout layout, void* workspace, size_t workspace_bytes, void* hip_stream) {
+    if (dtype == LC_F32)
+        return bn_bwd_impl<float>(static_cast<const float*>(x), static_cast<const float*>(dy), gamma, beta, save_mean, save_invstd,
+                                  static_cast<float*>(dx), dgamma, dbeta, n, c, h, w, relu, layout, workspace, workspace_bytes, hip_stream);
+    if (dtype == LC_BF16)
+        return bn_bwd_impl<uint16_t>(static_cast<const uint16_t*>(x), static_cast<const uint16_t*>(dy), gamma, beta, save_mean,
+                                     save_invstd, static_cast<uint16_t*>(dx), dgamma, dbeta, n, c, h, w, relu, layout, workspace,
+                                     workspace_bytes, hip_stream);
+    return LC_ERR_UNSUPPORTED;
 }
 
 extern "C" lc_status batchnorm_bwd(const float* x, const float* dy, const float* gamma, const float* save_mean,

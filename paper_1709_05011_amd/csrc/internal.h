@@ -13,11 +13,14 @@ void lc_begin_call();
 lc_status lc_end_call();     // LC_OK, or LC_ERR_LAUNCH with the detail text recorded
 lc_status lc_fail_call(hipError_t e, const char* what);   // records "what: error" as the detail text, returns LC_ERR_LAUNCH
 
-// fp32 -> bf16, round to nearest even (NaN stays NaN)
-__device__ __forceinline__ uint16_t lc_bf16_rne(float x) {
-    const uint32_t u = __float_as_uint(x);
-    if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40u);
-    return (uint16_t)((u + 0x7fffu + ((u >> 16) & 1u)) >> 16);
+// fp32 -> bf16, round to nearest even (NaN stays NaN): the conversion instruction of gfx950
+__device__ __forceinline__ uint16_t lc_bf16_rne(float x) { return __builtin_bit_cast(uint16_t, (__bf16)x); }
+// two at once: lo in bits 0..15, hi in bits 16..31
+__device__ __forceinline__ uint32_t lc_bf16x2_rne(float lo, float hi) {
+    typedef float lc_f32x2 __attribute__((ext_vector_type(2)));
+    typedef __bf16 lc_bf16x2 __attribute__((ext_vector_type(2)));
+    const lc_f32x2 v = {lo, hi};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, lc_bf16x2));
 }
 
 // ---- small device-side utilities (layout.hip) ----

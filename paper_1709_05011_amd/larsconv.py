@@ -25,6 +25,8 @@ EXPORTS = ["conv2d_out_shape", "conv2d_workspace_bytes", "conv2d_fwd", "conv2d_b
            "relu_fwd", "relu_bwd", "maxpool2x2_fwd", "maxpool2x2_bwd", "global_avgpool_fwd", "global_avgpool_bwd",
            "bias_add", "bias_grad", "softmax_xent", "maxpool_fwd", "maxpool_bwd", "relu_add_bwd",
            "batchnorm_workspace_bytes", "batchnorm_fwd", "batchnorm_bwd", "batchnorm_fwd_ex", "batchnorm_bwd_ex",
+           "batchnorm_fwd_t", "batchnorm_bwd_t", "maxpool_fwd_t", "maxpool_bwd_t", "relu_add_bwd_t", "global_avgpool_fwd_t",
+           "global_avgpool_bwd_t",
            "lc_status_string", "lc_last_error_detail"]
 
 
@@ -135,6 +137,14 @@ def lib() -> ctypes.CDLL:
         L.batchnorm_fwd_ex.argtypes = [vp, vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, ctypes.c_float, i32, i32, vp, sz, vp]
         L.batchnorm_bwd_ex.restype = i32
         L.batchnorm_bwd_ex.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, vp, sz, vp]
+        L.batchnorm_fwd_t.restype = i32
+        L.batchnorm_fwd_t.argtypes = [i32] + L.batchnorm_fwd_ex.argtypes
+        L.batchnorm_bwd_t.restype = i32
+        L.batchnorm_bwd_t.argtypes = [i32] + L.batchnorm_bwd_ex.argtypes
+        for name in ("maxpool_fwd", "maxpool_bwd", "relu_add_bwd", "global_avgpool_fwd", "global_avgpool_bwd"):
+            fn = getattr(L, name + "_t")
+            fn.restype = i32
+            fn.argtypes = [i32] + getattr(L, name).argtypes
         L.lc_status_string.restype = ctypes.c_char_p
         L.lc_status_string.argtypes = [i32]
         L.lc_last_error_detail.restype = ctypes.c_char_p
@@ -395,3 +405,43 @@ def batchnorm_bwd_ex(x, dy, gamma, beta, save_mean, save_invstd, dx, dgamma, dbe
     _check(lib().batchnorm_bwd_ex(_ptr(x), _ptr(dy), _ptr(gamma), _ptr(beta), _ptr(save_mean), _ptr(save_invstd), _ptr(dx),
                                   _ptr(dgamma), _ptr(dbeta), n, c, h, w, int(bool(relu)), layout, _ptr(workspace),
                                   _nbytes(workspace), _stream(stream)), "batchnorm_bwd_ex")
+
+
+# ---- the same layers with the storage type as an argument (LC_BF16: NHWC, channels a multiple of 8) ----
+
+def batchnorm_fwd_t(dtype: int, x, gamma, beta, residual, y, save_mean, save_invstd, n: int, c: int, h: int, w: int, eps: float,
+                    relu: bool, layout: int, workspace=None, stream=None) -> None:
+    _check(lib().batchnorm_fwd_t(dtype, _ptr(x), _ptr(gamma), _ptr(beta), _ptr(residual), _ptr(y), _ptr(save_mean),
+                                 _ptr(save_invstd), n, c, h, w, eps, int(bool(relu)), layout, _ptr(workspace), _nbytes(workspace),
+                                 _stream(stream)), "batchnorm_fwd_t")
+
+
+def batchnorm_bwd_t(dtype: int, x, dy, gamma, beta, save_mean, save_invstd, dx, dgamma, dbeta, n: int, c: int, h: int, w: int,
+                    relu: bool, layout: int, workspace=None, stream=None) -> None:
+    _check(lib().batchnorm_bwd_t(dtype, _ptr(x), _ptr(dy), _ptr(gamma), _ptr(beta), _ptr(save_mean), _ptr(save_invstd), _ptr(dx),
+                                 _ptr(dgamma), _ptr(dbeta), n, c, h, w, int(bool(relu)), layout, _ptr(workspace),
+                                 _nbytes(workspace), _stream(stream)), "batchnorm_bwd_t")
+
+
+def maxpool_fwd_t(dtype: int, x, y, idx, n: int, c: int, h: int, w: int, window: int, stride: int, pad: int, layout: int,
+                  stream=None) -> None:
+    _check(lib().maxpool_fwd_t(dtype, _ptr(x), _ptr(y), _ptr(idx), n, c, h, w, window, stride, pad, layout, _stream(stream)),
+           "maxpool_fwd_t")
+
+
+def maxpool_bwd_t(dtype: int, dy, idx, dx, n: int, c: int, h: int, w: int, window: int, stride: int, pad: int, layout: int,
+                  stream=None) -> None:
+    _check(lib().maxpool_bwd_t(dtype, _ptr(dy), _ptr(idx), _ptr(dx), n, c, h, w, window, stride, pad, layout, _stream(stream)),
+           "maxpool_bwd_t")
+
+
+def relu_add_bwd_t(dtype: int, y, da, db, dx, count: int, stream=None) -> None:
+    _check(lib().relu_add_bwd_t(dtype, _ptr(y), _ptr(da), _ptr(db), _ptr(dx), count, _stream(stream)), "relu_add_bwd_t")
+
+
+def global_avgpool_fwd_t(dtype: int, x, y, n: int, c: int, h: int, w: int, layout: int, stream=None) -> None:
+    _check(lib().global_avgpool_fwd_t(dtype, _ptr(x), _ptr(y), n, c, h, w, layout, _stream(stream)), "global_avgpool_fwd_t")
+
+
+def global_avgpool_bwd_t(dtype: int, dy, dx, n: int, c: int, h: int, w: int, layout: int, stream=None) -> None:
+    _check(lib().global_avgpool_bwd_t(dtype, _ptr(dy), _ptr(dx), n, c, h, w, layout, _stream(stream)), "global_avgpool_bwd_t")

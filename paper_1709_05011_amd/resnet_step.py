@@ -4,7 +4,12 @@ used for device memory).  The network is the one the paper trains in "ImageNet t
 stem convolution + batch norm + ReLU, 3x3 stride-2 max pool, stages of 1x1 -> 3x3 -> 1x1 blocks with batch norm
 after every convolution and the block input (through a strided 1x1 projection where the shape changes) added
 before the block's last ReLU, global average pool, classifier with bias, softmax cross-entropy, then LARS over
-all parameter tensors ("Scaling up Batch Size").  Layout NHWC, fp32.
+all parameter tensors ("Scaling up Batch Size").  Layout NHWC.
+
+dtype LC_F32: everything fp32.  dtype LC_BF16 (the mixed precision of the paper's fastest runs, "State-of-the-art
+results"): activations and their gradients are stored as bf16, the convolutions read a bf16 copy of each filter
+that the LARS update writes next to the fp32 master weights; scale, shift, statistics, all parameter gradients,
+momentum, the pooled features, the classifier and the loss stay fp32.  Channel counts must then be multiples of 8.
 
 ResNet-50: ResNetStep(stem=(64, 7, 2, 3), widths=(64, 128, 256, 512), blocks=(3, 4, 6, 3), classes=1000, ...).
 """
@@ -16,6 +21,7 @@ from typing import Dict, List, Optional, Sequence, Tuple
 import torch
 
 from . import larsconv as lc
+from . import synth
 
 NHWC = lc.LC_NHWC
 
@@ -35,9 +41,11 @@ class _ConvBn:
 
 class ResNetStep:
     def __init__(self, stem: Tuple[int, int, int, int], widths: Sequence[int], blocks: Sequence[int], classes: int, batch: int,
-                 image_hw: Tuple[int, int], in_channels: int = 3, eps: float = 1e-5, device: str = "cuda:0"):
+                 image_hw: Tuple[int, int], in_channels: int = 3, eps: float = 1e-5, device: str = "cuda:0", dtype: int = lc.LC_F32):
         lc.lib()                     # fails here, loudly, when the library has not been built
         self.dev, self.eps, self.batch, self.classes = device, eps, batch, classes
+        self.dtype = dtype
+        self._act = torch.bfloat16 if dtype == lc.LC_BF16 else torch.float32        # storage type of activations
         self.image_hw, self.in_channels = image_hw, in_channels
         self.layers: Dict[str, _ConvBn] = {}
         self.order: List[str] = []
@@ -75,8 +83,15 @@ class ResNetStep:
         self.params["fc.b"] = torch.zeros(classes, **f32)
         self.grads = {k: torch.zeros_like(v) for k, v in self.params.items()}
         self.velocity = {k: torch.zeros_like(v) for k, v in self.params.items()}
+        # bf16 copies of the filters for the convolutions (kept in step by the update)
+        self.lowp: Dict[str, torch.Tensor] = {}
+        if dtype == lc.LC_BF16:
+            for name in self.order:
+                self.lowp[name + ".w"] = torch.zeros_like(self.params[name + ".w"], dtype=torch.bfloat16)
         names = list(self.params)
-        self._lars = lc.LarsArgs([self.params[k] for k in names], [self.grads[k] for k in names], [self.velocity[k] for k in names])
+        self._lowp_list = [self.lowp.get(k) for k in names] if self.lowp else None
+        self._lars = lc.LarsArgs([self.params[k] for k in names], [self.grads[k] for k in names], [self.velocity[k] for k in names],
+                                 w_lowp=self._lowp_list)
         self._lars_ws = self._bytes(lc.lars_workspace_bytes(self._lars.numel))
         self.trust = torch.zeros(len(names), **f32)
         # the squared norm of every filter gradient comes out of its backward-weight pass in pieces and is handed to
@@ -103,9 +118,9 @@ class ResNetStep:
         for name in self.order:
             L = self.layers[name]
             shape = (batch, L.out_hw[0], L.out_hw[1], L.desc.k)
-            L.z, L.a = torch.empty(shape, **f32), torch.empty(shape, **f32)
+            L.z, L.a = torch.empty(shape, dtype=self._act, device=device), torch.empty(shape, dtype=self._act, device=device)
             L.mean, L.invstd = torch.empty(L.desc.k, **f32), torch.empty(L.desc.k, **f32)
-        self.pool_out = torch.empty((batch, self.pool_out_hw[0], self.pool_out_hw[1], stem[0]), **f32)
+        self.pool_out = torch.empty((batch, self.pool_out_hw[0], self.pool_out_hw[1], stem[0]), dtype=self._act, device=device)
         self.pool_idx = torch.empty(self.pool_out.shape, dtype=torch.uint8, device=device)
         self.gap = torch.empty((batch, ch), **f32)
         self.logits = torch.empty((batch, classes), **f32)
@@ -118,7 +133,7 @@ class ResNetStep:
         return torch.empty(max(n, 256), dtype=torch.uint8, device=self.dev)
 
     def _add(self, name, cin, k, r, stride, pad, h, w, relu):
-        d = lc.ConvDesc(self.batch, cin, h, w, k, r, r, stride, stride, pad, pad, lc.LC_F32, NHWC)
+        d = lc.ConvDesc(self.batch, cin, h, w, k, r, r, stride, stride, pad, pad, self.dtype, NHWC)
         p, q = lc.conv2d_out_shape(d)
         self.layers[name] = _ConvBn(name, d, (p, q), relu)
         self.order.append(name)
@@ -127,14 +142,27 @@ class ResNetStep:
     def _new(self, like: torch.Tensor) -> torch.Tensor:
         return torch.empty_like(like)
 
+    def _filter(self, name: str) -> torch.Tensor:
+        """the filter as the convolutions read it"""
+        return self.lowp[name + ".w"] if self.lowp else self.params[name + ".w"]
+
+    def load(self, host_params: Dict[str, "np.ndarray"]) -> None:
+        """Set the parameters from host arrays in the device layout (filters [k, r, s, c]); in bf16 mode the filters'
+        bf16 copies are rounded on the host (to nearest even) and uploaded beside them."""
+        for k, v in host_params.items():
+            self.params[k].copy_(torch.from_numpy(v).reshape(self.params[k].shape))
+            if k in self.lowp:
+                bits = synth.to_bf16_bits(v).reshape(self.params[k].shape)
+                self.lowp[k].copy_(torch.from_numpy(bits.view("int16")).view(torch.bfloat16))
+
     # ------------------------------------------------------------------ layers
     def _conv_bn(self, name: str, x: torch.Tensor, residual: Optional[torch.Tensor] = None, relu_after_residual: bool = False):
         L = self.layers[name]
         L.x = x
         k, (p, q) = L.desc.k, L.out_hw
-        lc.conv2d_fwd(L.desc, x, self.params[name + ".w"], L.z, self._ws)
-        lc.batchnorm_fwd_ex(L.z, self.params[name + ".gamma"], self.params[name + ".beta"], residual, L.a, L.mean, L.invstd,
-                            self.batch, k, p, q, self.eps, L.relu or relu_after_residual, NHWC, self._ws)
+        lc.conv2d_fwd(L.desc, x, self._filter(name), L.z, self._ws)
+        lc.batchnorm_fwd_t(self.dtype, L.z, self.params[name + ".gamma"], self.params[name + ".beta"], residual, L.a, L.mean, L.invstd,
+                           self.batch, k, p, q, self.eps, L.relu or relu_after_residual, NHWC, self._ws)
         return L.a
 
     def _conv_bn_bwd(self, name: str, da: torch.Tensor, need_dx: bool = True) -> Optional[torch.Tensor]:
@@ -143,29 +171,30 @@ class ResNetStep:
         L = self.layers[name]
         k, (p, q) = L.desc.k, L.out_hw
         dz = self._new(L.z)
-        lc.batchnorm_bwd_ex(L.z, da, self.params[name + ".gamma"], self.params[name + ".beta"], L.mean, L.invstd, dz,
-                            self.grads[name + ".gamma"], self.grads[name + ".beta"], self.batch, k, p, q, L.relu, NHWC, self._ws)
+        lc.batchnorm_bwd_t(self.dtype, L.z, da, self.params[name + ".gamma"], self.params[name + ".beta"], L.mean, L.invstd, dz,
+                           self.grads[name + ".gamma"], self.grads[name + ".beta"], self.batch, k, p, q, L.relu, NHWC, self._ws)
         lc.conv2d_bwd_weight_sq(L.desc, L.x, dz, self.grads[name + ".w"], self.gsq[name + ".w"], self._ws)
         if not need_dx:
             return None
         dx = self._new(L.x)
-        lc.conv2d_bwd_data(L.desc, dz, self.params[name + ".w"], dx, self._ws)
+        lc.conv2d_bwd_data(L.desc, dz, self._filter(name), dx, self._ws)
         return dx
 
     # ------------------------------------------------------------------ the step
     def forward(self, x: torch.Tensor, labels: torch.Tensor) -> torch.Tensor:
-        """x: [batch, h, w, channels] fp32, labels: [batch] int32.  Returns the loss (a device tensor of one float)."""
+        """x: [batch, h, w, channels] in the step's storage type, labels: [batch] int32.  Returns the loss (a device
+        tensor of one float)."""
         n = self.batch
         a = self._conv_bn("stem", x)
         c0 = self.layers["stem"].desc.k
-        lc.maxpool_fwd(a, self.pool_out, self.pool_idx, n, c0, self.pool_in_hw[0], self.pool_in_hw[1], 3, 2, 1, NHWC)
+        lc.maxpool_fwd_t(self.dtype, a, self.pool_out, self.pool_idx, n, c0, self.pool_in_hw[0], self.pool_in_hw[1], 3, 2, 1, NHWC)
         a = self.pool_out
         for name, proj in self.blocks:
             sc = self._conv_bn(name + ".proj", a) if proj else a
             b = self._conv_bn(name + ".c1", a)
             b = self._conv_bn(name + ".c2", b)
             a = self._conv_bn(name + ".c3", b, residual=sc, relu_after_residual=True)
-        lc.global_avgpool_fwd(a, self.gap, n, self.final_ch, self.final_hw[0], self.final_hw[1], NHWC)
+        lc.global_avgpool_fwd_t(self.dtype, a, self.gap, n, self.final_ch, self.final_hw[0], self.final_hw[1], NHWC)
         lc.conv2d_fwd(self.fc_desc, self.gap, self.params["fc.w"], self.logits, self._ws)
         lc.bias_add(self.logits, self.params["fc.b"], n, self.classes)
         lc.softmax_xent(self.logits, labels, self.loss, self.dlogits, self._rows, n, self.classes)
@@ -180,20 +209,20 @@ class ResNetStep:
         last = self.layers[self.blocks[-1][0] + ".c3"].a
         g1: torch.Tensor = self._new(last)
         g2: Optional[torch.Tensor] = None
-        lc.global_avgpool_bwd(dgap, g1, n, self.final_ch, self.final_hw[0], self.final_hw[1], NHWC)
+        lc.global_avgpool_bwd_t(self.dtype, dgap, g1, n, self.final_ch, self.final_hw[0], self.final_hw[1], NHWC)
         for name, proj in reversed(self.blocks):
             out = self.layers[name + ".c3"].a
             d_pre = self._new(out)
-            lc.relu_add_bwd(out, g1, g2, d_pre, out.numel())          # both arriving gradients through the block's last ReLU
+            lc.relu_add_bwd_t(self.dtype, out, g1, g2, d_pre, out.numel())   # both arriving gradients through the block's last ReLU
             d = self._conv_bn_bwd(name + ".c3", d_pre)
             d = self._conv_bn_bwd(name + ".c2", d)
             g1 = self._conv_bn_bwd(name + ".c1", d)
             g2 = self._conv_bn_bwd(name + ".proj", d_pre) if proj else d_pre
         d_pool = self._new(self.pool_out)
-        lc.relu_add_bwd(None, g1, g2, d_pool, d_pool.numel())         # the pool's output feeds the first block twice
+        lc.relu_add_bwd_t(self.dtype, None, g1, g2, d_pool, d_pool.numel())   # the pool's output feeds the first block twice
         stem = self.layers["stem"]
         da = self._new(stem.a)
-        lc.maxpool_bwd(d_pool, self.pool_idx, da, n, stem.desc.k, self.pool_in_hw[0], self.pool_in_hw[1], 3, 2, 1, NHWC)
+        lc.maxpool_bwd_t(self.dtype, d_pool, self.pool_idx, da, n, stem.desc.k, self.pool_in_hw[0], self.pool_in_hw[1], 3, 2, 1, NHWC)
         self._conv_bn_bwd("stem", da, need_dx=False)
 
     def lars(self, eta: float, momentum: float, weight_decay: float, lr: float) -> None:

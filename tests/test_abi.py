@@ -274,6 +274,46 @@ def test_fused_layers_reject_bad_arguments_before_launch():
     assert L.relu_add_bwd(P, P, P, P, 0, None) == lc.LC_OK
 
 
+def test_typed_layers_reject_bad_arguments_before_launch():
+    """The `_t` entry points: an unknown storage type, and for bf16 anything but NHWC with whole 16-byte channel groups."""
+    L = lc.lib()
+    P = ctypes.c_void_p(FAKE)
+    BF = lc.LC_BF16
+    need = lc.batchnorm_workspace_bytes(4, 16, 5, 5, lc.LC_NHWC)
+    fwd = lambda dt, c=16, lay=lc.LC_NHWC, x=P, nb=need: L.batchnorm_fwd_t(dt, x, P, P, None, P, P, P, 4, c, 5, 5, 1e-5, 1, lay, P, nb, None)
+    assert fwd(2) == lc.LC_ERR_UNSUPPORTED
+    assert fwd(BF, c=12) == lc.LC_ERR_UNSUPPORTED
+    assert fwd(BF, lay=lc.LC_NCHW) == lc.LC_ERR_UNSUPPORTED
+    assert fwd(BF, x=None) == lc.LC_ERR_NULL
+    assert fwd(BF, x=ctypes.c_void_p(FAKE + 8)) == lc.LC_ERR_ALIGN          # bf16 tensors: 16-byte aligned
+    assert fwd(BF, nb=need - 1) == lc.LC_ERR_WORKSPACE
+    assert fwd(lc.LC_F32, nb=need - 1) == lc.LC_ERR_WORKSPACE               # fp32: the checks of batchnorm_fwd_ex
+    bwd = lambda dt, beta=P, relu=1, c=16: L.batchnorm_bwd_t(dt, P, P, P, beta, P, P, P, P, P, 4, c, 5, 5, relu, lc.LC_NHWC, P, 0, None)
+    assert bwd(BF, beta=None) == lc.LC_ERR_NULL
+    assert bwd(BF, c=4) == lc.LC_ERR_UNSUPPORTED
+    assert bwd(BF) == lc.LC_ERR_WORKSPACE
+    assert bwd(3) == lc.LC_ERR_UNSUPPORTED
+    pool = lambda dt, c=8, lay=lc.LC_NHWC, idx=P, win=3: L.maxpool_fwd_t(dt, P, P, idx, 2, c, 9, 9, win, 2, 1, lay, None)
+    assert pool(BF, c=4) == lc.LC_ERR_UNSUPPORTED
+    assert pool(BF, lay=lc.LC_NCHW) == lc.LC_ERR_UNSUPPORTED
+    assert pool(BF, idx=None) == lc.LC_ERR_NULL
+    assert pool(BF, idx=ctypes.c_void_p(FAKE + 4)) == lc.LC_ERR_ALIGN
+    assert pool(BF, win=16) == lc.LC_ERR_SHAPE
+    assert pool(9) == lc.LC_ERR_UNSUPPORTED
+    assert L.maxpool_bwd_t(BF, P, P, None, 2, 8, 9, 9, 3, 2, 1, lc.LC_NHWC, None) == lc.LC_ERR_NULL
+    assert L.maxpool_bwd_t(BF, P, P, P, 2, 8, 9, 9, 3, 2, 3, lc.LC_NHWC, None) == lc.LC_ERR_SHAPE
+    assert L.relu_add_bwd_t(BF, None, P, None, P, 16, None) == lc.LC_ERR_NULL
+    assert L.relu_add_bwd_t(BF, P, P, P, P, 12, None) == lc.LC_ERR_UNSUPPORTED
+    assert L.relu_add_bwd_t(BF, P, P, P, ctypes.c_void_p(FAKE + 8), 16, None) == lc.LC_ERR_ALIGN
+    assert L.relu_add_bwd_t(BF, P, P, P, P, 0, None) == lc.LC_OK
+    assert L.relu_add_bwd_t(lc.LC_F32, None, P, None, P, 16, None) == lc.LC_ERR_NULL
+    assert L.global_avgpool_fwd_t(BF, P, P, 2, 12, 4, 4, lc.LC_NHWC, None) == lc.LC_ERR_UNSUPPORTED
+    assert L.global_avgpool_fwd_t(BF, P, None, 2, 16, 4, 4, lc.LC_NHWC, None) == lc.LC_ERR_NULL
+    assert L.global_avgpool_bwd_t(BF, P, P, 0, 16, 4, 4, lc.LC_NHWC, None) == lc.LC_ERR_SHAPE
+    assert L.global_avgpool_bwd_t(BF, P, P, 2, 16, 4, 4, lc.LC_NCHW, None) == lc.LC_ERR_UNSUPPORTED
+    assert L.global_avgpool_bwd_t(4, P, P, 2, 16, 4, 4, lc.LC_NHWC, None) == lc.LC_ERR_UNSUPPORTED
+
+
 def test_poly_lr_host_arithmetic():
     assert lc.lars_poly_lr(1.0, 0, 3516) == 1.0
     assert lc.lars_poly_lr(1.0, 3516, 3516) == 0.0
