@@ -61,23 +61,27 @@ template <typename T, int VEC>
 struct Pack;
 template <>
 struct Pack<float, 4> {
-    static __device__ __forceinline__ void load(const float* p, float (&v)[4]) {
-        const float4 u = *reinterpret_cast<const float4*>(p);
-        v[0] = u.x; v[1] = u.y; v[2] = u.z; v[3] = u.w;
-    }
+    typedef float4 raw;
+    static __device__ __forceinline__ raw fetch(const float* p) { return *reinterpret_cast<const float4*>(p); }
+    static __device__ __forceinline__ void unpack(const raw& u, float (&v)[4]) { v[0] = u.x; v[1] = u.y; v[2] = u.z; v[3] = u.w; }
+    static __device__ __forceinline__ void load(const float* p, float (&v)[4]) { unpack(fetch(p), v); }
     static __device__ __forceinline__ void store(float* p, const float (&v)[4]) {
         *reinterpret_cast<float4*>(p) = make_float4(v[0], v[1], v[2], v[3]);
     }
 };
 template <>
 struct Pack<float, 1> {
+    typedef float raw;
+    static __device__ __forceinline__ raw fetch(const float* p) { return *p; }
+    static __device__ __forceinline__ void unpack(const raw& u, float (&v)[1]) { v[0] = u; }
     static __device__ __forceinline__ void load(const float* p, float (&v)[1]) { v[0] = *p; }
     static __device__ __forceinline__ void store(float* p, const float (&v)[1]) { *p = v[0]; }
 };
 template <>
 struct Pack<uint16_t, 8> {
-    static __device__ __forceinline__ void load(const uint16_t* p, float (&v)[8]) {
-        const uint4 u = *reinterpret_cast<const uint4*>(p);
+    typedef uint4 raw;
+    static __device__ __forceinline__ raw fetch(const uint16_t* p) { return *reinterpret_cast<const uint4*>(p); }
+    static __device__ __forceinline__ void unpack(const raw& u, float (&v)[8]) {
         const unsigned w[4] = {u.x, u.y, u.z, u.w};
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
@@ -85,6 +89,7 @@ struct Pack<uint16_t, 8> {
             v[2 * i + 1] = __uint_as_float(w[i] & 0xffff0000u);
         }
     }
+    static __device__ __forceinline__ void load(const uint16_t* p, float (&v)[8]) { unpack(fetch(p), v); }
     static __device__ __forceinline__ void store(uint16_t* p, const float (&v)[8]) {
         unsigned w[4];
 #pragma unroll
@@ -108,12 +113,11 @@ __global__ void __launch_bounds__(kThreads) bn_reduce_nhwc_kernel(const T* __res
                                                                   const float* __restrict__ gamma, const float* __restrict__ beta,
                                                                   BnGeom g, BnWorkspace ws) {
     constexpr bool STATS = MODE == kStats;
-    __shared__ double red[kThreads][2 * VEC];
+    constexpr int U = 4;                                  // rows a thread has in flight
+    __shared__ float red[kThreads * 2 * VEC];
     const int tx = threadIdx.x % g.tx, ty = threadIdx.x / g.tx;
     const int c0 = (blockIdx.y * g.tx + tx) * VEC;
     const bool live = c0 < g.C;
-    const long long r0 = (long long)blockIdx.x * g.rows_per_slab;
-    const long long r1 = r0 + g.rows_per_slab < g.M ? r0 + g.rows_per_slab : g.M;
     float s0[VEC], s1[VEC], mu[VEC], is[VEC], sc[VEC], sh[VEC];
 #pragma unroll
     for (int e = 0; e < VEC; ++e) {
@@ -124,43 +128,66 @@ __global__ void __launch_bounds__(kThreads) bn_reduce_nhwc_kernel(const T* __res
         if (MODE == kMaskedSums && live) scale_shift(gamma[c0 + e], beta[c0 + e], mu[e], is[e], &sc[e], &sh[e]);
         if (STATS && live) mu[e] = widen<T>(x[c0 + e]);   // the channel's pivot: its value at the first pixel
     }
-    if (live) {
-        for (long long r = r0 + ty; r < r1; r += g.ty) {
-            float a[VEC], b[VEC];
-            Pack<T, VEC>::load(x + r * g.C + c0, a);
-            if constexpr (!STATS) Pack<T, VEC>::load(dy + r * g.C + c0, b);
+    auto add_row = [&](const float (&a)[VEC], const float (&b)[VEC]) {
 #pragma unroll
-            for (int e = 0; e < VEC; ++e) {
-                if constexpr (STATS) {
-                    const float d = a[e] - mu[e];
-                    s0[e] += d;
-                    s1[e] += d * d;
-                } else {
-                    const float d = (MODE == kMaskedSums && !(fmaf(sc[e], a[e], sh[e]) > 0.f)) ? 0.f : b[e];
-                    s0[e] += d;
-                    s1[e] += d * ((a[e] - mu[e]) * is[e]);
+        for (int e = 0; e < VEC; ++e) {
+            if constexpr (STATS) {
+                const float d = a[e] - mu[e];
+                s0[e] += d;
+                s1[e] += d * d;
+            } else {
+                const float d = (MODE == kMaskedSums && !(fmaf(sc[e], a[e], sh[e]) > 0.f)) ? 0.f : b[e];
+                s0[e] += d;
+                s1[e] += d * ((a[e] - mu[e]) * is[e]);
+            }
+        }
+    };
+    // Tiles of ty * U rows go round the blocks of the grid, so that at any moment the grid reads one contiguous
+    // stretch of the tensor (a block that kept to a region of its own would make as many scattered streams as blocks).
+    if (live) {
+        const long long tile = (long long)g.ty * U;
+        for (long long base = (long long)blockIdx.x * tile; base < g.M; base += (long long)gridDim.x * tile) {
+            const long long r = base + ty;
+            if (base + tile <= g.M) {                                             // U loads per tensor, then U rows in order
+                typename Pack<T, VEC>::raw ra[U], rb[U];
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    ra[u] = Pack<T, VEC>::fetch(x + (r + (long long)u * g.ty) * g.C + c0);
+                    if constexpr (!STATS) rb[u] = Pack<T, VEC>::fetch(dy + (r + (long long)u * g.ty) * g.C + c0);
+                }
+                __builtin_amdgcn_sched_barrier(0);        // all loads are issued before the first is waited for
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    float a[VEC], b[VEC];
+                    Pack<T, VEC>::unpack(ra[u], a);
+                    if constexpr (!STATS) Pack<T, VEC>::unpack(rb[u], b);
+                    add_row(a, b);
+                }
+            } else {                                                              // the tensor's last, partial tile
+                for (long long q = r; q < g.M; q += g.ty) {
+                    float a[VEC], b[VEC];
+                    Pack<T, VEC>::load(x + q * g.C + c0, a);
+                    if constexpr (!STATS) Pack<T, VEC>::load(dy + q * g.C + c0, b);
+                    add_row(a, b);
                 }
             }
         }
     }
+    // red[ty][tx][2 * VEC]: a row of the block's threads is one contiguous run of columns
 #pragma unroll
     for (int e = 0; e < VEC; ++e) {
-        red[threadIdx.x][2 * e] = (double)s0[e];
-        red[threadIdx.x][2 * e + 1] = (double)s1[e];
+        red[threadIdx.x * 2 * VEC + 2 * e] = s0[e];
+        red[threadIdx.x * 2 * VEC + 2 * e + 1] = s1[e];
     }
     __syncthreads();
-    if (ty == 0 && live) {
-#pragma unroll
-        for (int e = 0; e < VEC; ++e) {
-            double t0 = 0.0, t1 = 0.0;
-            for (int k = 0; k < g.ty; ++k) {              // rows of the block in order
-                t0 += red[k * g.tx + tx][2 * e];
-                t1 += red[k * g.tx + tx][2 * e + 1];
-            }
-            double* out = ws.partial + ((size_t)blockIdx.x * g.C + c0 + e) * 2;
-            out[0] = t0;
-            out[1] = t1;
-        }
+    // one thread per column adds the block's rows in order (double); columns of the channels beyond c are left out
+    const int ncols = g.tx * 2 * VEC;
+    for (int j = threadIdx.x; j < ncols; j += kThreads) {
+        const int ch2 = blockIdx.y * ncols + j;           // 2 * channel + which sum
+        if (ch2 >= 2 * g.C) continue;
+        double t = 0.0;
+        for (int k = 0; k < g.ty; ++k) t += (double)red[k * ncols + j];
+        ws.partial[(size_t)blockIdx.x * g.C * 2 + ch2] = t;
     }
 }
 
