@@ -198,14 +198,21 @@ def run_train_step(args):
         # bf16 has two more tiles, each taken with three or more rounds of such tiles (and not by the strided 1x1
         # backward-data layers, whose scatter epilogue exists for the 128-row tiles of 64 and 128 columns only)
         special = bf16 and k_gemm >= 32 and not scatter
-        if n_gemm <= 64:
-            return "conv_gemm_256x64" if special and -(-rows // 256) >= 3 * 3 * 256 else "conv_gemm_128x64"
+        big = False
         if special and n_gemm >= 256:
             tiles = -(-rows // 256) * -(-n_gemm // 256)            # 256x256 (eight waves): one block per compute unit
             rounds = -(-tiles // 256)
             nkt = -(-(k_gemm * cs.r * cs.s) // 32)
             fill = 70 if n_gemm <= 512 else 85
-            if tiles >= 256 and tiles * 100 >= rounds * 256 * fill and (n_gemm <= 512 or nkt >= 16):
+            big = tiles >= 256 and tiles * 100 >= rounds * 256 * fill and (n_gemm <= 512 or nkt >= 16)
+        # 3x3 stride-1 pad-1 layers in bf16: the kernel that stages the activation slab once for all nine taps
+        if (bf16 and cs.r == 3 and cs.s == 3 and cs.stride == 1 and cs.pad == 1 and k_gemm % 32 == 0 and not big
+                and -(-rows // 128) * -(-n_gemm // (128 if n_gemm > 64 else 64)) >= 256):
+            return "conv3x3_slab"
+        if n_gemm <= 64:
+            return "conv_gemm_256x64" if special and -(-rows // 256) >= 3 * 3 * 256 else "conv_gemm_128x64"
+        if special and n_gemm >= 256:
+            if big:
                 return "conv_gemm_256x256"
             if -(-rows // 128) * -(-n_gemm // 256) >= 3 * 2 * 256:
                 return "conv_gemm_128x256"

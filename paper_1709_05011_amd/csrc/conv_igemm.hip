@@ -809,6 +809,201 @@ __global__ void __launch_bounds__(2 * pk_waves_n(BM, BN) * 64) conv_gemm_fixup_k
 }
 
 // ------------------------------------------------------------------------------------------------
+// bf16 3x3 window, stride 1, padding 1 (forward, and backward-data, which is the same convolution of dy with the
+// re-ordered filter): the activation slab of a tile is staged ONCE per 32-channel chunk and all nine taps read it.
+// The main kernel fetches a tile's activation rows again for every tap; its bf16 loop is bound by exactly that operand
+// path (global -> LDS), and here the activation share of it falls to about a ninth (the slab with its halo is 1.6 to 3.2
+// times the tile's pixels).
+// Tile: 128 consecutive output pixels x BN filters, four waves (2 x 2).  Pixels are numbered over "virtual rows"
+// image * (H + 1) + row: the one empty row between two images is the lower halo of one and the upper halo of the next.
+// The slab holds the virtual rows of the tile's pixels plus one above and one below, each W + 2 pixels wide (the halo
+// columns), 80 bytes per pixel: 64 of data (32 channels) and 16 of padding, so that the 16-byte fragment reads of 16
+// consecutive pixels fall on distinct LDS banks without a per-tap swizzle.  Halo pixels are loaded as zeros (lane offset
+// past the end of the buffer).  A tap (r, s) then is a wave-uniform displacement ((r - 1) * (W + 2) + (s - 1)) * 80 bytes
+// of every lane's fragment address.  The filter tile of the next step is double-buffered as in the main kernel.
+// ------------------------------------------------------------------------------------------------
+constexpr int kSlabPitch = 80;         // bytes between slab pixels
+constexpr int kSlabMaxVec = 8;         // 16-byte slab vectors per thread: slabs of up to 512 pixels
+
+template <int BN>
+__global__ void __launch_bounds__(256, 2) conv3x3_slab_kernel(const GemmConv p) {
+    constexpr int BM = 128, WTM = 64, WTN = BN / 2, TM = 2, TN = WTN / 32, LB = BN * 4 / 256;
+    extern __shared__ __attribute__((aligned(1024))) unsigned char slab_smem[];
+    float* bl = reinterpret_cast<float*>(slab_smem);                 // filter tile, two stages of BN rows x 64 bytes
+    unsigned char* slab = slab_smem + 2 * BN * 64;
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave >> 1, wn = wave & 1;
+    const int nbn = (p.N + BN - 1) / BN;
+    const int tile = xcd_tile(blockIdx.x, gridDim.x);
+    const int m0 = (tile / nbn) * BM, n0 = (tile % nbn) * BN;
+    const int H = p.Hi, W = p.Wi, C = p.Ci, W2 = W + 2, HW = H * W, M_ = p.M, N_ = p.N, ldd_ = p.ldd;
+    const int imgs = M_ / HW;
+    const int ncc = C / 32, steps = ncc * 9;
+    const int lrow = lane >> 2, kq = (lane & 3) ^ swz(lrow);
+    const int frow = lane & 31, fhalf = lane >> 5, fsw = swz(frow);
+
+    const int img0 = m0 / HW, p0 = (m0 - img0 * HW) / W;
+    const int vr0 = img0 * (H + 1) + p0 - 1;                        // virtual row of slab row 0 (the upper halo)
+    const int m_last = min(m0 + BM, M_) - 1;
+    const int img1 = m_last / HW, p1 = (m_last - img1 * HW) / W;
+    const int slab_px = (img1 * (H + 1) + p1 + 2 - vr0) * W2;       // at most what the launcher sized the LDS for
+
+    // slab vector e = tid + i * 256 is chunk e % 4 of slab pixel e / 4
+    const __amdgpu_buffer_rsrc_t a_rsrc =
+        __builtin_amdgcn_make_buffer_rsrc((void*)p.a, 0, (int)((long long)M_ * C * 2), (int)kBufferWords3);
+    unsigned a_voff[kSlabMaxVec];
+#pragma unroll
+    for (int i = 0; i < kSlabMaxVec; ++i) {
+        const int e = tid + i * 256, sp = e >> 2, ch = e & 3;
+        const int srow = sp / W2, col = sp - srow * W2;
+        const int vr = vr0 + srow;
+        const int img = vr >= 0 ? vr / (H + 1) : 0, h = vr - img * (H + 1);
+        const bool ok = sp < slab_px && col >= 1 && col <= W && vr >= 0 && h < H && img < imgs;
+        a_voff[i] = ok ? (unsigned)((((long long)img * H + h) * W + (col - 1)) * C * 2 + ch * 16) : kBufferBytes;
+    }
+    const __amdgpu_buffer_rsrc_t b_rsrc =
+        __builtin_amdgcn_make_buffer_rsrc((void*)p.b, 0, (int)((long long)N_ * 9 * C * 2), (int)kBufferWords3);
+    unsigned b_voff[LB];
+#pragma unroll
+    for (int i = 0; i < LB; ++i) {
+        const int n = n0 + (i * 4 + wave) * 16 + lrow;
+        b_voff[i] = n < N_ ? (unsigned)((long long)n * 9 * C * 2 + kq * 16) : kBufferBytes;
+    }
+    unsigned a_frag[TM];
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+        int m = m0 + wm * WTM + i * 32 + frow;
+        if (m >= M_) m = m0;                                         // rows past the end read some valid pixel; never stored
+        const int img = m / HW, r = m - img * HW, pp = r / W, q = r - pp * W;
+        a_frag[i] = (unsigned)(((img * (H + 1) + pp - vr0) * W2 + q + 1) * kSlabPitch + fhalf * 16);
+    }
+    const int b_frag = (wn * WTN + frow) * 16;
+
+    u32x4 ga[kSlabMaxVec], gb[LB];
+    auto gload_slab = [&](int cc) __attribute__((always_inline)) {
+#pragma unroll
+        for (int i = 0; i < kSlabMaxVec; ++i)
+            if (i * 256 < slab_px * 4) ga[i] = __builtin_amdgcn_raw_buffer_load_b128(a_rsrc, a_voff[i], cc * 64, 0);
+    };
+    auto sstore_slab = [&]() __attribute__((always_inline)) {
+#pragma unroll
+        for (int i = 0; i < kSlabMaxVec; ++i) {
+            const int e = tid + i * 256;
+            if (e < slab_px * 4) *reinterpret_cast<u32x4*>(slab + (e >> 2) * kSlabPitch + (e & 3) * 16) = ga[i];
+        }
+    };
+    auto gload_b = [&](int t) __attribute__((always_inline)) {
+        const int cc = t / 9, tap = t - cc * 9;
+        const int soff = (tap * C + cc * 32) * 2;
+#pragma unroll
+        for (int i = 0; i < LB; ++i) gb[i] = __builtin_amdgcn_raw_buffer_load_b128(b_rsrc, b_voff[i], soff, 0);
+    };
+    auto sstore_b = [&](int buf) __attribute__((always_inline)) {
+        float* base = bl + buf * (BN * 16) + wave * 256 + lane * 4;
+#pragma unroll
+        for (int i = 0; i < LB; ++i) *reinterpret_cast<u32x4*>(base + i * 1024) = gb[i];
+    };
+
+    f32x16 acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+    float4 fa[2][TM], fb[2][TN];
+    auto read_frags = [&](int buf, int tap, int k8, int slot) __attribute__((always_inline)) {
+        const int r = tap / 3, s = tap - r * 3;
+        const int delta = ((r - 1) * W2 + (s - 1)) * kSlabPitch + k8 * 32;        // wave-uniform
+        const float* bb = bl + buf * (BN * 16);
+#pragma unroll
+        for (int i = 0; i < TM; ++i) fa[slot][i] = *reinterpret_cast<const float4*>(slab + (int)a_frag[i] + delta);
+        const int ch = ((2 * k8 + fhalf) ^ fsw) * 4;
+#pragma unroll
+        for (int j = 0; j < TN; ++j) fb[slot][j] = *reinterpret_cast<const float4*>(bb + b_frag + j * 32 * 16 + ch);
+    };
+    auto mfma = [&](int slot) __attribute__((always_inline)) {
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, fa[slot][i]),
+                                                                    __builtin_bit_cast(bf16x8, fb[slot][j]), acc[i][j], 0, 0, 0);
+    };
+
+    gload_slab(0);
+    gload_b(0);
+    sstore_slab();
+    sstore_b(0);
+    if (steps > 1) gload_b(1);
+    lds_barrier();
+    read_frags(0, 0, 0, 0);
+    int cur = 0;
+    for (int cc = 0; cc < ncc; ++cc) {
+        const bool more_cc = cc + 1 < ncc;
+        if (more_cc) gload_slab(cc + 1);                     // held in registers until this chunk's last tap is done
+#pragma unroll
+        for (int tap = 0; tap < 9; ++tap) {
+            const int t = cc * 9 + tap;
+            read_frags(cur, tap, 1, 1);
+            __builtin_amdgcn_sched_barrier(0);
+            if (t + 1 < steps) sstore_b(cur ^ 1);            // the filter tile of step t + 1, loaded a step ago
+            mfma(0);
+            __builtin_amdgcn_sched_barrier(0);
+            if (t + 2 < steps) gload_b(t + 2);
+            if (tap == 8 && more_cc) {
+                lds_barrier();                               // every wave has read its last fragments of this chunk's slab
+                sstore_slab();
+            }
+            lds_barrier();
+            if (t + 1 < steps) read_frags(cur ^ 1, tap == 8 ? 0 : tap + 1, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+            mfma(1);
+            cur ^= 1;
+        }
+    }
+
+    // tile store as in the main kernel: rows by scalar offset and cut off at M by the size of the buffer, columns by lane
+    // offset with bit 31 past N; with an even row length neighbouring lanes trade halves and store column pairs
+    {
+        const long long rows_left = (long long)(M_ - m0) * ldd_ * 2;
+        const __amdgpu_buffer_rsrc_t d_rsrc = __builtin_amdgcn_make_buffer_rsrc(
+            (void*)(static_cast<uint16_t*>(p.d) + (long long)m0 * ldd_), 0, (int)(rows_left > 0x7fffffffLL ? 0x7fffffffLL : rows_left),
+            (int)kBufferWords3);
+        const bool pairs = ((N_ | ldd_) & 1) == 0;
+        const int odd = lane & 1;
+        unsigned d_voff[TN];
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+            const int col = n0 + wn * WTN + j * 32 + frow;
+            d_voff[j] = col < N_ ? (unsigned)((4 * fhalf * ldd_ + col) * 2) : kBufferBytes;
+            if (pairs && col < N_) d_voff[j] = (unsigned)(((4 * fhalf + odd) * ldd_ + (col & ~1)) * 2);
+        }
+        const unsigned perm_sel = odd ? 0x03020706u : 0x05040100u;
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int v = 0; v < 16; v += 2) {
+                const int r0 = wm * WTM + i * 32 + 8 * (v >> 2) + (v & 3);       // registers v and v + 1: rows r0 and r0 + 1
+                const int soff = r0 * ldd_ * 2;
+#pragma unroll
+                for (int j = 0; j < TN; ++j) {
+                    const unsigned u = lc_bf16x2_rne(acc[i][j][v], acc[i][j][v + 1]);
+                    if (pairs) {
+                        const unsigned got = (unsigned)__builtin_amdgcn_mov_dpp((int)u, 0xB1 /* quad_perm 1,0,3,2 */, 0xF, 0xF, true);
+                        __builtin_amdgcn_raw_buffer_store_b32(__builtin_amdgcn_perm(got, u, perm_sel), d_rsrc, (int)d_voff[j], soff, 0);
+                    } else {
+                        __builtin_amdgcn_raw_buffer_store_b16((short)(u & 0xffffu), d_rsrc, (int)d_voff[j], soff, 0);
+                        __builtin_amdgcn_raw_buffer_store_b16((short)(u >> 16), d_rsrc, (int)d_voff[j], soff + ldd_ * 2, 0);
+                    }
+                }
+            }
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
 // backward-weight kernel: both operands contiguous along their *output* index (k resp. c), the
 // reduction index m strides over rows.  LDS holds [reduction][row] so that the row-contiguous
 // global vectors are stored as they arrive and MFMA fragments are read with unit lane stride.
@@ -1704,7 +1899,51 @@ bool lc_conv_gemm_scatter_ok(const GemmConv& p) {
     return span < 0x7fff0000LL;
 }
 
+// The slab kernel's conditions: bf16, 3x3 window with stride 1 and padding 1 (so the output has the input's size),
+// whole 32-channel chunks, byte offsets that fit 31 bits, a slab of at most 512 pixels, and enough tiles to fill the chip
+// (below that the main kernel's stream-K split is worth more).  Returns the LDS bytes of the launch in *lds.
+static bool slab_kernel_ok(const GemmConv& p, int bn, size_t* lds) {
+    static const bool off = getenv("LARSCONV_NO_SLAB") != nullptr;       // comparison runs
+    if (off || !p.bf16 || p.scatter || p.R != 3 || p.S != 3 || p.sh != 1 || p.sw != 1 || p.ph != 1 || p.pw != 1 || p.dh > 1 || p.dw > 1)
+        return false;
+    if (p.Po != p.Hi || p.Qo != p.Wi || p.Ci % 32 != 0 || p.Kg != 9 * p.Ci) return false;
+    if (!aligned16(p.a) || !aligned16(p.b) || (reinterpret_cast<uintptr_t>(p.d) & 3)) return false;
+    const long long hw = (long long)p.Hi * p.Wi;
+    if (p.M % hw != 0) return false;
+    if ((long long)p.M * p.Ci * 2 >= 0x7fff0000LL || (long long)p.N * 9 * p.Ci * 2 >= 0x7fff0000LL || (long long)288 * p.ldd * 2 >= 0x7fff0000LL)
+        return false;
+    // rows a tile's 128 consecutive pixels can span, the empty rows between the images it can touch, and the two halo rows
+    const long long rows = (128 + p.Wi - 2) / p.Wi + (128 + hw - 2) / hw + 3;
+    const long long px = rows * (p.Wi + 2);
+    if (px > (long long)kSlabMaxVec * 64) return false;
+    *lds = (size_t)2 * bn * 64 + (size_t)px * kSlabPitch;
+    const char* e = getenv("LARSCONV_SLAB_MIN_TILES");                      // tests lower it to send small shapes here
+    const long long min_tiles = e ? atoll(e) : device_cu_count();
+    const long long tiles = (long long)((p.M + 127) / 128) * ((p.N + bn - 1) / bn);
+    if (tiles < min_tiles) return false;
+    // where the main kernel runs its 256x256 tile (half the filter bytes per MFMA as well) it measures 4-6 % faster
+    const MainTile t = main_tile(p);
+    return e != nullptr || !(t.bm == 256 && t.bn == 256);
+}
+
+template <int BN>
+static lc_status launch_slab(const GemmConv& p, size_t lds, hipStream_t stream) {
+    static bool once = [] {
+        return hipFuncSetAttribute(reinterpret_cast<const void*>(conv3x3_slab_kernel<BN>), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                   2 * BN * 64 + kSlabMaxVec * 64 * kSlabPitch) == hipSuccess;
+    }();
+    if (!once) return LC_ERR_LAUNCH;
+    const long long tiles = (long long)((p.M + 127) / 128) * ((p.N + BN - 1) / BN);
+    hipLaunchKernelGGL((conv3x3_slab_kernel<BN>), dim3((unsigned)tiles), dim3(256), lds, stream, p);
+    return lc_end_call();
+}
+
 lc_status lc_launch_conv_gemm(const GemmConv& p, hipStream_t stream) {
+    if (p.bf16) {
+        size_t lds;
+        const int bn = p.N > 64 ? 128 : 64;
+        if (slab_kernel_ok(p, bn, &lds)) return bn == 128 ? launch_slab<128>(p, lds, stream) : launch_slab<64>(p, lds, stream);
+    }
     if (p.bf16) {
         if (!use_main_kernel(p)) return LC_ERR_UNSUPPORTED;       // the caller converts to fp32 instead
         if (p.Ci < 32) return p.N > 64 ? launch_conv_sk<128, 128, true, true>(p, stream) : launch_conv_sk<128, 64, true, true>(p, stream);
