@@ -297,3 +297,73 @@ def test_global_avgpool_bf16():
         torch.cuda.synchronize()
         assert gu.scaled_err(y.cpu().numpy(), otc.global_avgpool(x.astype(np.float64))) <= 1e-5
         _close_bf16(_back(dx), otc.global_avgpool_bwd(dy.astype(np.float64), h, w), extra=1e-6)
+
+
+def test_maxpool_bf16_ties_and_padding():
+    """Equal values: the first tap in row-major window order that lies inside the image wins (at the border that is not
+    tap 0); all-negative values: padding never wins."""
+    n, c, h, w = 2, 8, 6, 6
+    for value in (1.5, -2.0):
+        xb, x = _bf(np.full((n, c, h, w), value, np.float32))
+        oy, oidx = ores.maxpool(x, 3, 2, 1)
+        y = torch.full((n, 3, 3, c), -1, dtype=torch.int16, device=gu.DEV)
+        idx = torch.full((n, 3, 3, c), 255, dtype=torch.uint8, device=gu.DEV)
+        lc.maxpool_fwd_t(BF, _dev(xb), y, idx, n, c, h, w, 3, 2, 1, NHWC)
+        torch.cuda.synchronize()
+        np.testing.assert_array_equal(_back(y), np.full((n, c, 3, 3), value, np.float32))
+        got = idx.cpu().numpy().transpose(0, 3, 1, 2)
+        np.testing.assert_array_equal(got, oidx)
+        assert got[0, 0, 0, 0] == 4 and got[0, 0, 0, 1] == 3 and got[0, 0, 1, 0] == 1 and got[0, 0, 1, 1] == 0
+
+
+def test_typed_calls_with_fp32_are_the_fp32_calls():
+    n, c, h, w = 3, 16, 9, 9
+    x = gu.dev(synth.normal((n, h, w, c), 9870))
+    dy = gu.dev(synth.normal((n, 5, 5, c), 9871))
+    outs = []
+    for typed in (True, False):
+        y = torch.full((n, 5, 5, c), float("nan"), device=gu.DEV)
+        idx = torch.full((n, 5, 5, c), 255, dtype=torch.uint8, device=gu.DEV)
+        dx, s, g = torch.full_like(x, float("nan")), torch.full_like(x, float("nan")), torch.full((n, c), float("nan"), device=gu.DEV)
+        gx = torch.full_like(x, float("nan"))
+        if typed:
+            lc.maxpool_fwd_t(lc.LC_F32, x, y, idx, n, c, h, w, 3, 2, 1, NHWC)
+            lc.maxpool_bwd_t(lc.LC_F32, dy, idx, dx, n, c, h, w, 3, 2, 1, NHWC)
+            lc.relu_add_bwd_t(lc.LC_F32, x, x, dx, s, x.numel())
+            lc.global_avgpool_fwd_t(lc.LC_F32, x, g, n, c, h, w, NHWC)
+            lc.global_avgpool_bwd_t(lc.LC_F32, g, gx, n, c, h, w, NHWC)
+        else:
+            lc.maxpool_fwd(x, y, idx, n, c, h, w, 3, 2, 1, NHWC)
+            lc.maxpool_bwd(dy, idx, dx, n, c, h, w, 3, 2, 1, NHWC)
+            lc.relu_add_bwd(x, x, dx, s, x.numel())
+            lc.global_avgpool_fwd(x, g, n, c, h, w, NHWC)
+            lc.global_avgpool_bwd(g, gx, n, c, h, w, NHWC)
+        torch.cuda.synchronize()
+        outs.append([t.cpu().numpy() for t in (y, idx, dx, s, g, gx)])
+    for a, b in zip(*outs):
+        np.testing.assert_array_equal(a, b)
+
+
+def test_batchnorm_bf16_constant_tensor():
+    """A constant input: the batch variance is exactly zero on both sides (the pivot is the value itself), y = beta rounded
+    to bf16, and the backward pass stays finite with dx = gamma / sqrt(eps) * (dy - mean(dy)) rounded."""
+    n, c, h, w = 4, 16, 3, 3
+    xb, x = _bf(np.full((n, c, h, w), 2.5, np.float32))
+    dyb, dy = _bf(synth.normal((n, c, h, w), 9880))
+    gamma = (1.0 + 0.5 * synth.normal((c,), 9881)).astype(np.float32)
+    beta = synth.normal((c,), 9882)
+    xd, dyd, gd, bd = _dev(xb), _dev(dyb), gu.dev(gamma), gu.dev(beta)
+    y, dx = torch.full_like(xd, -1), torch.full_like(xd, -1)
+    mean, invstd, dg, db = (torch.empty(c, device=gu.DEV) for _ in range(4))
+    ws = gu.workspace(lc.batchnorm_workspace_bytes(n, c, h, w, NHWC))
+    lc.batchnorm_fwd_t(BF, xd, gd, bd, None, y, mean, invstd, n, c, h, w, EPS, False, NHWC, ws)
+    lc.batchnorm_bwd_t(BF, xd, dyd, gd, None, mean, invstd, dx, dg, db, n, c, h, w, False, NHWC, ws)
+    torch.cuda.synchronize()
+    assert np.allclose(invstd.cpu().numpy(), 1.0 / np.sqrt(EPS), rtol=1e-5)
+    np.testing.assert_array_equal(mean.cpu().numpy(), np.full(c, 2.5, np.float32))
+    oy, _, _ = obn.forward(x, gamma, beta, EPS)
+    _close_bf16(_back(y), oy, extra=1e-3)                 # |x - mean| is 0 or one fp32 step, times 1/sqrt(eps) = 316
+    odx, odg, odb = obn.backward(x, dy, gamma, EPS)
+    assert gu.scaled_err(db.cpu().numpy(), odb) <= 1e-4
+    assert np.max(np.abs(dg.cpu().numpy() - odg)) <= 1e-6
+    _close_bf16(_back(dx), odx, extra=1e-4)
