@@ -280,6 +280,23 @@ lc_status relu_add_bwd_t(lc_dtype dtype, const void* y, const void* da, const vo
 lc_status global_avgpool_fwd_t(lc_dtype dtype, const void* x, float* y, int n, int c, int h, int w, lc_layout layout, void* hip_stream);
 lc_status global_avgpool_bwd_t(lc_dtype dtype, const float* dy, void* dx, int n, int c, int h, int w, lc_layout layout, void* hip_stream);
 
+/* The gradient at a residual block's output and the sums of the batch-norm backward pass behind it, in one pass.
+ * In the residual networks the paper trains ("ImageNet training with ResNet-50") the gradient that relu_add_bwd makes is
+ * at once the dy of the block's last batch norm.  relu_add_bwd_bnsums_t is relu_add_bwd_t (y required, db may be NULL)
+ * on [n,c,h,w] tensors that, while it writes dx, also sums dx and dx * xhat per channel against x_bn, the INPUT of that
+ * batch norm (xhat from save_mean / save_invstd of its forward pass), and leaves the sums in `workspace`;
+ * batchnorm_bwd_presummed_t is batchnorm_bwd_t (no ReLU) that takes them from there instead of reading x and dy once
+ * more.  The pair gives bit for bit what relu_add_bwd_t followed by batchnorm_bwd_t gives, with one pass over x less.
+ * Between the two calls nothing else may use the workspace (the one exception to "contents undefined between calls");
+ * both need NHWC, 16-byte aligned tensors and c a multiple of 4 (fp32) or 8 (bf16): LC_ERR_UNSUPPORTED / LC_ERR_ALIGN
+ * otherwise, and callers then use the two plain calls.  Workspace: batchnorm_workspace_bytes. */
+lc_status relu_add_bwd_bnsums_t(lc_dtype dtype, const void* y, const void* da, const void* db, void* dx, const void* x_bn,
+                                const float* save_mean, const float* save_invstd, int n, int c, int h, int w, lc_layout layout,
+                                void* workspace, size_t workspace_bytes, void* hip_stream);
+lc_status batchnorm_bwd_presummed_t(lc_dtype dtype, const void* x, const void* dy, const float* gamma, const float* save_mean,
+                                    const float* save_invstd, void* dx, float* dgamma, float* dbeta, int n, int c, int h, int w,
+                                    lc_layout layout, void* workspace, size_t workspace_bytes, void* hip_stream);
+
 /* Static, human-readable name of a status code. */
 const char* lc_status_string(lc_status status);
 

@@ -65,6 +65,7 @@ struct Pack<float, 4> {
     static __device__ __forceinline__ raw fetch(const float* p) { return *reinterpret_cast<const float4*>(p); }
     static __device__ __forceinline__ void unpack(const raw& u, float (&v)[4]) { v[0] = u.x; v[1] = u.y; v[2] = u.z; v[3] = u.w; }
     static __device__ __forceinline__ void load(const float* p, float (&v)[4]) { unpack(fetch(p), v); }
+    static __device__ __forceinline__ raw pack(const float (&v)[4]) { return make_float4(v[0], v[1], v[2], v[3]); }
     static __device__ __forceinline__ void store(float* p, const float (&v)[4]) {
         *reinterpret_cast<float4*>(p) = make_float4(v[0], v[1], v[2], v[3]);
     }
@@ -75,6 +76,7 @@ struct Pack<float, 1> {
     static __device__ __forceinline__ raw fetch(const float* p) { return *p; }
     static __device__ __forceinline__ void unpack(const raw& u, float (&v)[1]) { v[0] = u; }
     static __device__ __forceinline__ void load(const float* p, float (&v)[1]) { v[0] = *p; }
+    static __device__ __forceinline__ raw pack(const float (&v)[1]) { return v[0]; }
     static __device__ __forceinline__ void store(float* p, const float (&v)[1]) { *p = v[0]; }
 };
 template <>
@@ -90,6 +92,12 @@ struct Pack<uint16_t, 8> {
         }
     }
     static __device__ __forceinline__ void load(const uint16_t* p, float (&v)[8]) { unpack(fetch(p), v); }
+    static __device__ __forceinline__ raw pack(const float (&v)[8]) {
+        unsigned w[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) w[i] = lc_bf16x2_rne(v[2 * i], v[2 * i + 1]);
+        return make_uint4(w[0], w[1], w[2], w[3]);
+    }
     static __device__ __forceinline__ void store(uint16_t* p, const float (&v)[8]) {
         unsigned w[4];
 #pragma unroll
@@ -107,13 +115,26 @@ __device__ __forceinline__ float widen<uint16_t>(uint16_t v) { return __uint_as_
 // ---------------- NHWC ----------------
 // MODE kStats: sums of x and x^2.  kSums: sums of dy and dy * (x - mean) * inv_std.  kMaskedSums: the same with
 // dy taken as zero where scale*x + shift <= 0.
-template <typename T, int VEC, int MODE>
+// JOIN 1 / 2 (with kSums): dy does not exist yet -- it is the gradient that meets at a residual block's output,
+// dy = (y > 0 ? da [+ db] : 0), and this pass makes it on the way: computed from y, da (and db), rounded to the storage
+// type, written to join.out and summed as stored.  One pass over x saved against making dy first and summing it after.
+template <typename T>
+struct BnJoin {
+    const T* y;
+    const T* da;
+    const T* db;
+    T* out;
+};
+
+template <typename T, int VEC, int MODE, int JOIN = 0>
 __global__ void __launch_bounds__(kThreads) bn_reduce_nhwc_kernel(const T* __restrict__ x, const T* __restrict__ dy,
                                                                   const float* __restrict__ mean, const float* __restrict__ inv_std,
                                                                   const float* __restrict__ gamma, const float* __restrict__ beta,
-                                                                  BnGeom g, BnWorkspace ws) {
+                                                                  BnGeom g, BnWorkspace ws, BnJoin<T> join = BnJoin<T>{}) {
     constexpr bool STATS = MODE == kStats;
-    constexpr int U = 4;                                  // rows a thread has in flight
+    constexpr int TU = 4;                                 // a tile is TU rows of the block's threads (the same for every form: equal sums)
+    constexpr int U = JOIN ? 2 : 4;                       // rows a thread has in flight
+    static_assert(JOIN == 0 || MODE == kSums, "the joined form makes an unmasked dy");
     __shared__ float red[kThreads * 2 * VEC];
     const int tx = threadIdx.x % g.tx, ty = threadIdx.x / g.tx;
     const int c0 = (blockIdx.y * g.tx + tx) * VEC;
@@ -145,29 +166,68 @@ __global__ void __launch_bounds__(kThreads) bn_reduce_nhwc_kernel(const T* __res
     // Tiles of ty * U rows go round the blocks of the grid, so that at any moment the grid reads one contiguous
     // stretch of the tensor (a block that kept to a region of its own would make as many scattered streams as blocks).
     if (live) {
-        const long long tile = (long long)g.ty * U;
+        const long long tile = (long long)g.ty * TU;
         for (long long base = (long long)blockIdx.x * tile; base < g.M; base += (long long)gridDim.x * tile) {
-            const long long r = base + ty;
             if (base + tile <= g.M) {                                             // U loads per tensor, then U rows in order
-                typename Pack<T, VEC>::raw ra[U], rb[U];
+              for (int part = 0; part < TU; part += U) {
+                const long long r = base + ty + (long long)part * g.ty;
+                typename Pack<T, VEC>::raw ra[U], rb[U], ry[JOIN ? U : 1], rc[JOIN == 2 ? U : 1];
 #pragma unroll
                 for (int u = 0; u < U; ++u) {
-                    ra[u] = Pack<T, VEC>::fetch(x + (r + (long long)u * g.ty) * g.C + c0);
-                    if constexpr (!STATS) rb[u] = Pack<T, VEC>::fetch(dy + (r + (long long)u * g.ty) * g.C + c0);
+                    const long long at = (r + (long long)u * g.ty) * g.C + c0;
+                    ra[u] = Pack<T, VEC>::fetch(x + at);
+                    if constexpr (JOIN) {
+                        ry[u] = Pack<T, VEC>::fetch(join.y + at);
+                        rb[u] = Pack<T, VEC>::fetch(join.da + at);
+                        if constexpr (JOIN == 2) rc[u] = Pack<T, VEC>::fetch(join.db + at);
+                    } else if constexpr (!STATS) {
+                        rb[u] = Pack<T, VEC>::fetch(dy + at);
+                    }
                 }
                 __builtin_amdgcn_sched_barrier(0);        // all loads are issued before the first is waited for
 #pragma unroll
                 for (int u = 0; u < U; ++u) {
                     float a[VEC], b[VEC];
                     Pack<T, VEC>::unpack(ra[u], a);
-                    if constexpr (!STATS) Pack<T, VEC>::unpack(rb[u], b);
+                    if constexpr (JOIN) {
+                        float yv[VEC], h2[VEC];
+                        Pack<T, VEC>::unpack(ry[u], yv);
+                        Pack<T, VEC>::unpack(rb[u], b);
+                        if constexpr (JOIN == 2) Pack<T, VEC>::unpack(rc[u], h2);
+#pragma unroll
+                        for (int e = 0; e < VEC; ++e) {
+                            if constexpr (JOIN == 2) b[e] += h2[e];
+                            if (!(yv[e] > 0.f)) b[e] = 0.f;
+                        }
+                        const typename Pack<T, VEC>::raw stored = Pack<T, VEC>::pack(b);
+                        *reinterpret_cast<typename Pack<T, VEC>::raw*>(join.out + (r + (long long)u * g.ty) * g.C + c0) = stored;
+                        Pack<T, VEC>::unpack(stored, b);                           // the sums are those of the stored values
+                    } else if constexpr (!STATS) {
+                        Pack<T, VEC>::unpack(rb[u], b);
+                    }
                     add_row(a, b);
                 }
+              }
             } else {                                                              // the tensor's last, partial tile
-                for (long long q = r; q < g.M; q += g.ty) {
+                for (long long q = base + ty; q < g.M; q += g.ty) {
                     float a[VEC], b[VEC];
                     Pack<T, VEC>::load(x + q * g.C + c0, a);
-                    if constexpr (!STATS) Pack<T, VEC>::load(dy + q * g.C + c0, b);
+                    if constexpr (JOIN) {
+                        float yv[VEC], h2[VEC];
+                        Pack<T, VEC>::load(join.y + q * g.C + c0, yv);
+                        Pack<T, VEC>::load(join.da + q * g.C + c0, b);
+                        if constexpr (JOIN == 2) Pack<T, VEC>::load(join.db + q * g.C + c0, h2);
+#pragma unroll
+                        for (int e = 0; e < VEC; ++e) {
+                            if constexpr (JOIN == 2) b[e] += h2[e];
+                            if (!(yv[e] > 0.f)) b[e] = 0.f;
+                        }
+                        const typename Pack<T, VEC>::raw stored = Pack<T, VEC>::pack(b);
+                        *reinterpret_cast<typename Pack<T, VEC>::raw*>(join.out + q * g.C + c0) = stored;
+                        Pack<T, VEC>::unpack(stored, b);
+                    } else if constexpr (!STATS) {
+                        Pack<T, VEC>::load(dy + q * g.C + c0, b);
+                    }
                     add_row(a, b);
                 }
             }
@@ -549,7 +609,7 @@ lc_status bn_fwd_impl(const T* x, const float* gamma, const float* beta, const T
 template <typename T>
 lc_status bn_bwd_impl(const T* x, const T* dy, const float* gamma, const float* beta, const float* save_mean, const float* save_invstd,
                       T* dx, float* dgamma, float* dbeta, int n, int c, int h, int w, int relu, lc_layout layout, void* workspace,
-                      size_t workspace_bytes, void* hip_stream) {
+                      size_t workspace_bytes, void* hip_stream, bool presummed = false) {
     constexpr bool kF32 = sizeof(T) == 4;
     if (!x || !dy || !gamma || !save_mean || !save_invstd || !dx || !dgamma || !dbeta || (relu && !beta)) return LC_ERR_NULL;
     if (layout != LC_NCHW && layout != LC_NHWC) return LC_ERR_UNSUPPORTED;
@@ -559,6 +619,8 @@ lc_status bn_bwd_impl(const T* x, const T* dy, const float* gamma, const float* 
         return LC_ERR_ALIGN;
     if (!kF32 && layout != LC_NHWC) return LC_ERR_UNSUPPORTED;
     if (!kF32 && g.vec != kWide<T>) return c % kWide<T> ? LC_ERR_UNSUPPORTED : LC_ERR_ALIGN;
+    // sums left in the workspace by relu_add_bwd_bnsums_t: only the geometry of the vector path is shared by the two calls
+    if (presummed && (layout != LC_NHWC || relu || g.vec != kWide<T>)) return LC_ERR_UNSUPPORTED;
     size_t coef_off;
     const size_t need = ws_layout(g, &coef_off);
     if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255) || workspace_bytes < need) return LC_ERR_WORKSPACE;
@@ -577,8 +639,9 @@ lc_status bn_bwd_impl(const T* x, const T* dy, const float* gamma, const float* 
         const dim3 agrid(apply_blocks(total / g.vec, c, g.vec, &inv));
 #define LC_BN_BWD(VEC, MODE, MASK)                                                                                                       \
     do {                                                                                                                                \
-        hipLaunchKernelGGL((bn_reduce_nhwc_kernel<T, VEC, MODE>), grid, dim3(kThreads), 0, stream, x, dy, save_mean, save_invstd, gamma, \
-                           mask_beta, g, ws);                                                                                           \
+        if (!presummed)                                                                                                                 \
+            hipLaunchKernelGGL((bn_reduce_nhwc_kernel<T, VEC, MODE>), grid, dim3(kThreads), 0, stream, x, dy, save_mean, save_invstd,    \
+                               gamma, mask_beta, g, ws, BnJoin<T>{});                                                                   \
         hipLaunchKernelGGL(bn_finalize_bwd_kernel, fin_grid, fin_block, 0, stream, ws, gamma, mask_beta, save_mean, save_invstd, dgamma, \
                            dbeta, g);                                                                                                   \
         if (inv)                                                                                                                        \
@@ -613,7 +676,65 @@ lc_status bn_bwd_impl(const T* x, const T* dy, const float* gamma, const float* 
     return lc_end_call();
 }
 
+// dx = (y > 0 ? da [+ db] : 0) and, in the workspace, the sums batch-norm backward needs of that dx against x_bn
+template <typename T>
+lc_status bn_join_impl(const T* y, const T* da, const T* db, T* dx, const T* x_bn, const float* save_mean, const float* save_invstd, int n,
+                       int c, int h, int w, lc_layout layout, void* workspace, size_t workspace_bytes, void* hip_stream) {
+    if (!y || !da || !dx || !x_bn || !save_mean || !save_invstd) return LC_ERR_NULL;
+    if (layout != LC_NHWC) return LC_ERR_UNSUPPORTED;
+    BnGeom g;
+    if (!geometry(n, c, h, w, layout, al16(y) && al16(da) && al16(db) && al16(dx) && al16(x_bn), &g, kWide<T>)) return LC_ERR_SHAPE;
+    if (!al4(y) || !al4(da) || !al4(db) || !al4(dx) || !al4(x_bn) || !al4(save_mean) || !al4(save_invstd)) return LC_ERR_ALIGN;
+    if (g.vec != kWide<T>) return c % kWide<T> ? LC_ERR_UNSUPPORTED : LC_ERR_ALIGN;
+    size_t coef_off;
+    const size_t need = ws_layout(g, &coef_off);
+    if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255) || workspace_bytes < need) return LC_ERR_WORKSPACE;
+    BnWorkspace ws;
+    ws.partial = static_cast<double*>(workspace);
+    ws.coef = reinterpret_cast<float*>(static_cast<char*>(workspace) + coef_off);
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    lc_begin_call();
+    const dim3 grid((unsigned)g.slabs, (unsigned)g.cblocks);
+    const float* nonef = nullptr;
+    const T* none = nullptr;
+    const BnJoin<T> join{y, da, db, dx};
+    if (db)
+        hipLaunchKernelGGL((bn_reduce_nhwc_kernel<T, kWide<T>, kSums, 2>), grid, dim3(kThreads), 0, stream, x_bn, none, save_mean, save_invstd,
+                           nonef, nonef, g, ws, join);
+    else
+        hipLaunchKernelGGL((bn_reduce_nhwc_kernel<T, kWide<T>, kSums, 1>), grid, dim3(kThreads), 0, stream, x_bn, none, save_mean, save_invstd,
+                           nonef, nonef, g, ws, join);
+    return lc_end_call();
+}
+
 }  // namespace
+
+extern "C" lc_status relu_add_bwd_bnsums_t(lc_dtype dtype, const void* y, const void* da, const void* db, void* dx, const void* x_bn,
+                                           const float* save_mean, const float* save_invstd, int n, int c, int h, int w, lc_layout layout,
+                                           void* workspace, size_t workspace_bytes, void* hip_stream) {
+    if (dtype == LC_F32)
+        return bn_join_impl<float>(static_cast<const float*>(y), static_cast<const float*>(da), static_cast<const float*>(db),
+                                   static_cast<float*>(dx), static_cast<const float*>(x_bn), save_mean, save_invstd, n, c, h, w, layout,
+                                   workspace, workspace_bytes, hip_stream);
+    if (dtype == LC_BF16)
+        return bn_join_impl<uint16_t>(static_cast<const uint16_t*>(y), static_cast<const uint16_t*>(da), static_cast<const uint16_t*>(db),
+                                      static_cast<uint16_t*>(dx), static_cast<const uint16_t*>(x_bn), save_mean, save_invstd, n, c, h, w,
+                                      layout, workspace, workspace_bytes, hip_stream);
+    return LC_ERR_UNSUPPORTED;
+}
+
+extern "C" lc_status batchnorm_bwd_presummed_t(lc_dtype dtype, const void* x, const void* dy, const float* gamma, const float* save_mean,
+                                               const float* save_invstd, void* dx, float* dgamma, float* dbeta, int n, int c, int h, int w,
+                                               lc_layout layout, void* workspace, size_t workspace_bytes, void* hip_stream) {
+    if (dtype == LC_F32)
+        return bn_bwd_impl<float>(static_cast<const float*>(x), static_cast<const float*>(dy), gamma, nullptr, save_mean, save_invstd,
+                                  static_cast<float*>(dx), dgamma, dbeta, n, c, h, w, 0, layout, workspace, workspace_bytes, hip_stream, true);
+    if (dtype == LC_BF16)
+        return bn_bwd_impl<uint16_t>(static_cast<const uint16_t*>(x), static_cast<const uint16_t*>(dy), gamma, nullptr, save_mean,
+                                     save_invstd, static_cast<uint16_t*>(dx), dgamma, dbeta, n, c, h, w, 0, layout, workspace,
+                                     workspace_bytes, hip_stream, true);
+    return LC_ERR_UNSUPPORTED;
+}
 
 extern "C" lc_status batchnorm_fwd_ex(const float* x, const float* gamma, const float* beta, const float* residual, float* y,
                                       float* save_mean, float* save_invstd, int n, int c, int h, int w, float eps, int relu,

@@ -41,8 +41,10 @@ class _ConvBn:
 
 class ResNetStep:
     def __init__(self, stem: Tuple[int, int, int, int], widths: Sequence[int], blocks: Sequence[int], classes: int, batch: int,
-                 image_hw: Tuple[int, int], in_channels: int = 3, eps: float = 1e-5, device: str = "cuda:0", dtype: int = lc.LC_F32):
+                 image_hw: Tuple[int, int], in_channels: int = 3, eps: float = 1e-5, device: str = "cuda:0", dtype: int = lc.LC_F32,
+                 join_sums: bool = True):
         lc.lib()                     # fails here, loudly, when the library has not been built
+        self.join_sums = join_sums   # False: the block-output gradient and the batch-norm sums behind it as two plain calls
         self.dev, self.eps, self.batch, self.classes = device, eps, batch, classes
         self.dtype = dtype
         self._act = torch.bfloat16 if dtype == lc.LC_BF16 else torch.float32        # storage type of activations
@@ -165,14 +167,19 @@ class ResNetStep:
                            self.batch, k, p, q, self.eps, L.relu or relu_after_residual, NHWC, self._ws)
         return L.a
 
-    def _conv_bn_bwd(self, name: str, da: torch.Tensor, need_dx: bool = True) -> Optional[torch.Tensor]:
+    def _conv_bn_bwd(self, name: str, da: torch.Tensor, need_dx: bool = True, presummed: bool = False) -> Optional[torch.Tensor]:
         """``da``: gradient with respect to the layer's output -- of the fused ReLU's output where the layer has
-        one, otherwise of the batch-norm output itself (the caller has applied the block's last ReLU)."""
+        one, otherwise of the batch-norm output itself (the caller has applied the block's last ReLU).  ``presummed``: the
+        call that made ``da`` has left the batch-norm backward sums in the workspace."""
         L = self.layers[name]
         k, (p, q) = L.desc.k, L.out_hw
         dz = self._new(L.z)
-        lc.batchnorm_bwd_t(self.dtype, L.z, da, self.params[name + ".gamma"], self.params[name + ".beta"], L.mean, L.invstd, dz,
-                           self.grads[name + ".gamma"], self.grads[name + ".beta"], self.batch, k, p, q, L.relu, NHWC, self._ws)
+        if presummed:
+            lc.batchnorm_bwd_presummed_t(self.dtype, L.z, da, self.params[name + ".gamma"], L.mean, L.invstd, dz,
+                                         self.grads[name + ".gamma"], self.grads[name + ".beta"], self.batch, k, p, q, NHWC, self._ws)
+        else:
+            lc.batchnorm_bwd_t(self.dtype, L.z, da, self.params[name + ".gamma"], self.params[name + ".beta"], L.mean, L.invstd, dz,
+                               self.grads[name + ".gamma"], self.grads[name + ".beta"], self.batch, k, p, q, L.relu, NHWC, self._ws)
         lc.conv2d_bwd_weight_sq(L.desc, L.x, dz, self.grads[name + ".w"], self.gsq[name + ".w"], self._ws)
         if not need_dx:
             return None
@@ -213,8 +220,16 @@ class ResNetStep:
         for name, proj in reversed(self.blocks):
             out = self.layers[name + ".c3"].a
             d_pre = self._new(out)
-            lc.relu_add_bwd_t(self.dtype, out, g1, g2, d_pre, out.numel())   # both arriving gradients through the block's last ReLU
-            d = self._conv_bn_bwd(name + ".c3", d_pre)
+            # both arriving gradients through the block's last ReLU -- and, where the layer's channel count allows the
+            # vector path, the sums of the batch-norm backward pass of the block's last convolution on the way
+            L3 = self.layers[name + ".c3"]
+            joined = self.join_sums and L3.desc.k % (8 if self.dtype == lc.LC_BF16 else 4) == 0
+            if joined:
+                lc.relu_add_bwd_bnsums_t(self.dtype, out, g1, g2, d_pre, L3.z, L3.mean, L3.invstd, n, L3.desc.k, L3.out_hw[0],
+                                         L3.out_hw[1], NHWC, self._ws)
+            else:
+                lc.relu_add_bwd_t(self.dtype, out, g1, g2, d_pre, out.numel())
+            d = self._conv_bn_bwd(name + ".c3", d_pre, presummed=joined)
             d = self._conv_bn_bwd(name + ".c2", d)
             g1 = self._conv_bn_bwd(name + ".c1", d)
             g2 = self._conv_bn_bwd(name + ".proj", d_pre) if proj else d_pre

@@ -314,6 +314,30 @@ def test_typed_layers_reject_bad_arguments_before_launch():
     assert L.global_avgpool_bwd_t(4, P, P, 2, 16, 4, 4, lc.LC_NHWC, None) == lc.LC_ERR_UNSUPPORTED
 
 
+def test_joined_block_gradient_rejects_bad_arguments_before_launch():
+    L = lc.lib()
+    P = ctypes.c_void_p(FAKE)
+    need = lc.batchnorm_workspace_bytes(4, 16, 5, 5, lc.LC_NHWC)
+    join = lambda dt=lc.LC_BF16, y=P, db=P, c=16, lay=lc.LC_NHWC, nb=need, xb=P: L.relu_add_bwd_bnsums_t(dt, y, P, db, P, xb, P, P, 4, c, 5, 5,
+                                                                                                       lay, P, nb, None)
+    assert join(y=None) == lc.LC_ERR_NULL                         # the mask is required here
+    assert join(xb=None) == lc.LC_ERR_NULL
+    assert join(db=None, nb=0) == lc.LC_ERR_WORKSPACE             # one gradient is fine: the workspace check is reached
+    assert join(nb=0) == lc.LC_ERR_WORKSPACE
+    assert join(c=12) == lc.LC_ERR_UNSUPPORTED                    # bf16: whole groups of eight channels
+    assert join(dt=lc.LC_F32, c=6) == lc.LC_ERR_UNSUPPORTED       # fp32: the vector path only
+    assert join(lay=lc.LC_NCHW) == lc.LC_ERR_UNSUPPORTED
+    assert join(dt=7) == lc.LC_ERR_UNSUPPORTED
+    assert join(xb=ctypes.c_void_p(FAKE + 8)) == lc.LC_ERR_ALIGN
+    pre = lambda dt=lc.LC_BF16, c=16, lay=lc.LC_NHWC, nb=need, dy=P: L.batchnorm_bwd_presummed_t(dt, P, dy, P, P, P, P, P, P, 4, c, 5, 5, lay,
+                                                                                                   P, nb, None)
+    assert pre(dy=None) == lc.LC_ERR_NULL
+    assert pre(c=12) == lc.LC_ERR_UNSUPPORTED
+    assert pre(dt=lc.LC_F32, lay=lc.LC_NCHW) == lc.LC_ERR_UNSUPPORTED
+    assert pre(nb=0) == lc.LC_ERR_WORKSPACE
+    assert pre(dt=9) == lc.LC_ERR_UNSUPPORTED
+
+
 def test_poly_lr_host_arithmetic():
     assert lc.lars_poly_lr(1.0, 0, 3516) == 1.0
     assert lc.lars_poly_lr(1.0, 3516, 3516) == 0.0

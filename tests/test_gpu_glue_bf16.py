@@ -367,3 +367,43 @@ def test_batchnorm_bf16_constant_tensor():
     assert gu.scaled_err(db.cpu().numpy(), odb) <= 1e-4
     assert np.max(np.abs(dg.cpu().numpy() - odg)) <= 1e-6
     _close_bf16(_back(dx), odx, extra=1e-4)
+
+
+@pytest.mark.parametrize("bf16", [False, True], ids=["fp32", "bf16"])
+@pytest.mark.parametrize("two", [True, False], ids=["two_gradients", "one_gradient"])
+@pytest.mark.parametrize("shape", [(6, 32, 14, 14), (3, 8, 5, 7), (16, 256, 7, 7), (2, 64, 56, 56)], ids=["14x14", "ragged", "wide", "many_rows"])
+def test_block_gradient_joined_with_batchnorm_sums_equals_the_two_plain_calls(shape, two, bf16):
+    """relu_add_bwd_bnsums_t + batchnorm_bwd_presummed_t against relu_add_bwd_t + batchnorm_bwd_t: bit for bit, and the
+    plain pair is itself checked against the oracle elsewhere in this file and in test_gpu_batchnorm.py."""
+    n, c, h, w = shape
+    dtype = BF if bf16 else lc.LC_F32
+
+    def put(a):
+        if bf16:
+            return _dev(_bf(a)[0])
+        return gu.dev(gu.to_layout(a, NHWC))
+    z = put((synth.normal(shape, 9900) * 1.5 + 0.4).astype(np.float32))
+    y = put(synth.normal(shape, 9901))                    # the block's output: its sign is the mask
+    g1, g2 = put(synth.normal(shape, 9902)), put(synth.normal(shape, 9903))
+    gamma = gu.dev((1.0 + 0.5 * synth.normal((c,), 9904)).astype(np.float32))
+    beta = gu.dev(synth.normal((c,), 9905))
+    ws = gu.workspace(lc.batchnorm_workspace_bytes(n, c, h, w, NHWC))
+    mean, invstd = torch.empty(c, device=gu.DEV), torch.empty(c, device=gu.DEV)
+    a = torch.empty_like(z)
+    lc.batchnorm_fwd_t(dtype, z, gamma, beta, None, a, mean, invstd, n, c, h, w, EPS, False, NHWC, ws)
+    outs = []
+    for joined in (False, True):
+        fill = -1 if bf16 else float("nan")
+        d_pre, dz = torch.full_like(z, fill), torch.full_like(z, fill)
+        dg, db = torch.empty(c, device=gu.DEV), torch.empty(c, device=gu.DEV)
+        if joined:
+            lc.relu_add_bwd_bnsums_t(dtype, y, g1, g2 if two else None, d_pre, z, mean, invstd, n, c, h, w, NHWC, ws)
+            lc.batchnorm_bwd_presummed_t(dtype, z, d_pre, gamma, mean, invstd, dz, dg, db, n, c, h, w, NHWC, ws)
+        else:
+            lc.relu_add_bwd_t(dtype, y, g1, g2 if two else None, d_pre, z.numel())
+            lc.batchnorm_bwd_t(dtype, z, d_pre, gamma, None, mean, invstd, dz, dg, db, n, c, h, w, False, NHWC, ws)
+        torch.cuda.synchronize()
+        outs.append([t.cpu().numpy() for t in (d_pre, dz, dg, db)])
+    for u, v in zip(*outs):
+        np.testing.assert_array_equal(u, v)
+    assert np.all(np.isfinite(outs[1][2])) and np.any(outs[1][1] != 0)
