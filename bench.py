@@ -632,7 +632,7 @@ def run_batch_curve(args):
     import torch
 
     points = []
-    for b in (args.batches or [16, 32, 64, 128, 256, 512]):
+    for b in (args.batches or [16, 32, 64, 128, 256, 512, 1024]):
         a = copy.copy(args)
         a.batch, a.steps, a.warmup, a.no_cpu, a.graph = b, 10, 5, True, False
         head = run_train_step(a)
@@ -744,7 +744,7 @@ def main():
     ap.add_argument("--graph", action="store_true", help="--full-step: capture the step in a HIP graph and time replays")
     ap.add_argument("--copy-calib", action="store_true", help="run a 1 GiB device copy (counter calibration)")
     ap.add_argument("--batch-curve", action="store_true", help="images/s against the per-GPU batch (headline step and whole step)")
-    ap.add_argument("--batches", type=int, nargs="*", help="--batch-curve: batch sizes (default 16 .. 512)")
+    ap.add_argument("--batches", type=int, nargs="*", help="--batch-curve: batch sizes (default 16 .. 1024)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py measures one GPU: the hot path built here has no multi-GPU part "
