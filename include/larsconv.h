@@ -296,6 +296,27 @@ lc_status relu_add_bwd_bnsums_t(lc_dtype dtype, const void* y, const void* da, c
 lc_status batchnorm_bwd_presummed_t(lc_dtype dtype, const void* x, const void* dy, const float* gamma, const float* save_mean,
                                     const float* save_invstd, void* dx, float* dgamma, float* dbeta, int n, int c, int h, int w,
                                     lc_layout layout, void* workspace, size_t workspace_bytes, void* hip_stream);
+/* ---- Batch-norm statistics out of the convolution ----
+ * Every convolution of the paper's networks is followed by batch normalisation ("Scaling up Batch Size",
+ * "ImageNet training with ResNet-50"), whose first step reads the convolution's whole output again to sum it.
+ * conv2d_fwd_stats is conv2d_fwd that also hands those sums over: stats receives
+ * conv2d_fwd_stats_count(desc) * k * 2 floats, [piece][channel][2] = the sum and the sum of squares, over one
+ * piece of 64 or 128 of the output's rows (n, p, q), of the values written to y (as written: after rounding where y is
+ * bf16).  They come out of the output tile's registers: 1/16 (fp32) or 1/8 (bf16) of y's bytes instead of a pass over y.
+ * The count is 0 -- and conv2d_fwd_stats returns LC_ERR_UNSUPPORTED -- for layers whose plan has no such epilogue: NCHW,
+ * groups > 1, and operands the MFMA kernels do not take (fp32 tensors off a 16-byte boundary, channel counts not a
+ * multiple of 4 resp. 8); callers then use conv2d_fwd and batchnorm_fwd_t.  stats: DEVICE, 8-byte aligned, written in full.
+ * batchnorm_fwd_pre is batchnorm_fwd_t (NHWC) on x = that y with the statistics taken from `stats`
+ * (stats_tiles = the count) instead of a pass over x: the pieces are added in a fixed order in double, then
+ * mean = sum / m, variance = sum of squares / m - mean^2.  Without a pivot this loses accuracy where a channel's mean is
+ * large against its deviation (relative error of the variance about 1e-7 * (1 + mean^2 / variance)): meant for
+ * convolution outputs, whose means are of the order of their deviations. */
+size_t conv2d_fwd_stats_count(const lc_conv_desc* desc);
+lc_status conv2d_fwd_stats(const lc_conv_desc* desc, const void* x, const void* w, void* y, float* stats, void* workspace,
+                           size_t workspace_bytes, void* hip_stream);
+lc_status batchnorm_fwd_pre(lc_dtype dtype, const void* x, const float* gamma, const float* beta, const void* residual, void* y,
+                            float* save_mean, float* save_invstd, int n, int c, int h, int w, float eps, int relu, lc_layout layout,
+                            const float* stats, size_t stats_tiles, void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /* Static, human-readable name of a status code. */
 const char* lc_status_string(lc_status status);

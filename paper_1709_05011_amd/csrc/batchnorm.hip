@@ -369,6 +369,22 @@ __global__ void __launch_bounds__(kThreads) bn_apply_nchw_kernel(const float* __
     }
 }
 
+// Statistics that arrive as fp32 pieces [pieces][cols] (cols = 2 * channels: sum and sum of squares side by side) are
+// folded into the slab partials the finalize kernel adds: slab s takes pieces s, s + slabs, ... in that order, in double.
+__global__ void __launch_bounds__(kThreads) bn_fold_pieces_kernel(const float* __restrict__ pieces, int n_pieces, double* __restrict__ partial,
+                                                                  int slabs, int cols) {
+    const int j = blockIdx.y * kThreads + threadIdx.x;
+    if (j >= cols) return;
+    double t0 = 0.0, t1 = 0.0;
+    int t = blockIdx.x;
+    for (; t + slabs < n_pieces; t += 2 * slabs) {
+        t0 += (double)pieces[(size_t)t * cols + j];
+        t1 += (double)pieces[(size_t)(t + slabs) * cols + j];
+    }
+    if (t < n_pieces) t0 += (double)pieces[(size_t)t * cols + j];
+    partial[(size_t)blockIdx.x * cols + j] = t0 + t1;
+}
+
 // ---------------- per-channel finalize ----------------
 // A block of 256 threads finishes 4 channels: 64 lanes per channel add every 64th slab's partial (two running sums
 // each, so that loads overlap), then the first lane adds the 64 lane sums in lane order.  Returns true in the thread
@@ -417,7 +433,7 @@ bn_finalize_fwd_kernel(BnWorkspace ws, const T* __restrict__ x, size_t pivot_str
     if (!channel_totals(ws, g, &ch, &s0, &s1)) return;
     const double m = (double)g.M;
     const double off = s0 / m;                                  // mean of x - pivot
-    const double mean = (double)widen<T>(x[ch * pivot_stride]) + off;
+    const double mean = (x ? (double)widen<T>(x[ch * pivot_stride]) : 0.0) + off;      // x null: plain sums, no pivot
     double var = s1 / m - off * off;
     if (var < 0.0) var = 0.0;
     const double inv_std = 1.0 / sqrt(var + (double)eps);
@@ -536,7 +552,7 @@ constexpr int kWide = 16 / (int)sizeof(T);
 template <typename T>
 lc_status bn_fwd_impl(const T* x, const float* gamma, const float* beta, const T* residual, T* y, float* save_mean, float* save_invstd,
                       int n, int c, int h, int w, float eps, int relu, lc_layout layout, void* workspace, size_t workspace_bytes,
-                      void* hip_stream) {
+                      void* hip_stream, const float* stats = nullptr, size_t stats_tiles = 0) {
     constexpr bool kF32 = sizeof(T) == 4;
     if (!x || !gamma || !beta || !y || !save_mean || !save_invstd) return LC_ERR_NULL;
     if (layout != LC_NCHW && layout != LC_NHWC) return LC_ERR_UNSUPPORTED;
@@ -546,6 +562,8 @@ lc_status bn_fwd_impl(const T* x, const float* gamma, const float* beta, const T
     if (!al4(x) || !al4(y) || !al4(residual) || !al4(gamma) || !al4(beta) || !al4(save_mean) || !al4(save_invstd)) return LC_ERR_ALIGN;
     if (!kF32 && layout != LC_NHWC) return LC_ERR_UNSUPPORTED;
     if (!kF32 && g.vec != kWide<T>) return c % kWide<T> ? LC_ERR_UNSUPPORTED : LC_ERR_ALIGN;
+    if (stats && (layout != LC_NHWC || stats_tiles == 0 || stats_tiles > 0x7fffffffull)) return LC_ERR_UNSUPPORTED;
+    if (stats && (reinterpret_cast<uintptr_t>(stats) & 7)) return LC_ERR_ALIGN;
     size_t coef_off;
     const size_t need = ws_layout(g, &coef_off);
     if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255) || workspace_bytes < need) return LC_ERR_WORKSPACE;
@@ -559,6 +577,8 @@ lc_status bn_fwd_impl(const T* x, const float* gamma, const float* beta, const T
     const T* none = nullptr;
     const float* nonef = nullptr;
     const bool two = residual != nullptr, clamp = relu != 0;
+    // sums handed over by the producer of x (plain sums of x and x^2, fp32 pieces in [stats_tiles][c][2]): no pass over x of
+    // our own; the pieces are first folded into this pass's slab partials, piece t into slab t mod slabs, in order
     const size_t pivot_stride = layout == LC_NHWC ? 1 : (size_t)g.HW;       // the first pixel's value of channel ch sits at x[ch * stride]
     if (layout == LC_NHWC) {
         const dim3 grid((unsigned)g.slabs, (unsigned)g.cblocks);
@@ -575,10 +595,17 @@ lc_status bn_fwd_impl(const T* x, const float* gamma, const float* beta, const T
     } while (0)
 #define LC_BN_FWD(VEC)                                                                                                                  \
     do {                                                                                                                                \
-        hipLaunchKernelGGL((bn_reduce_nhwc_kernel<T, VEC, kStats>), grid, dim3(kThreads), 0, stream, x, none, nonef, nonef, nonef, nonef, g, \
-                           ws);                                                                                                         \
-        hipLaunchKernelGGL(bn_finalize_fwd_kernel<T>, fin_grid, fin_block, 0, stream, ws, x, pivot_stride, gamma, beta, save_mean,      \
-                           save_invstd, g, eps);                                                                                        \
+        if (stats) {                                                                                                                    \
+            hipLaunchKernelGGL(bn_fold_pieces_kernel, dim3((unsigned)g.slabs, (unsigned)((2 * c + kThreads - 1) / kThreads)),           \
+                               dim3(kThreads), 0, stream, stats, (int)stats_tiles, ws.partial, g.slabs, 2 * c);                         \
+            hipLaunchKernelGGL(bn_finalize_fwd_kernel<T>, fin_grid, fin_block, 0, stream, ws, none, pivot_stride, gamma, beta,          \
+                               save_mean, save_invstd, g, eps);                                                                         \
+        } else {                                                                                                                        \
+            hipLaunchKernelGGL((bn_reduce_nhwc_kernel<T, VEC, kStats>), grid, dim3(kThreads), 0, stream, x, none, nonef, nonef, nonef,  \
+                               nonef, g, ws);                                                                                           \
+            hipLaunchKernelGGL(bn_finalize_fwd_kernel<T>, fin_grid, fin_block, 0, stream, ws, x, pivot_stride, gamma, beta, save_mean,  \
+                               save_invstd, g, eps);                                                                                    \
+        }                                                                                                                               \
         if (two) { if (clamp) LC_BN_APPLY(VEC, true, true); else LC_BN_APPLY(VEC, true, false); }                                       \
         else { if (clamp) LC_BN_APPLY(VEC, false, true); else LC_BN_APPLY(VEC, false, false); }                                         \
     } while (0)
@@ -753,6 +780,22 @@ extern "C" lc_status batchnorm_fwd_t(lc_dtype dtype, const void* x, const float*
         return bn_fwd_impl<uint16_t>(static_cast<const uint16_t*>(x), gamma, beta, static_cast<const uint16_t*>(residual),
                                      static_cast<uint16_t*>(y), save_mean, save_invstd, n, c, h, w, eps, relu, layout, workspace,
                                      workspace_bytes, hip_stream);
+    return LC_ERR_UNSUPPORTED;
+}
+
+extern "C" lc_status batchnorm_fwd_pre(lc_dtype dtype, const void* x, const float* gamma, const float* beta, const void* residual, void* y,
+                                       float* save_mean, float* save_invstd, int n, int c, int h, int w, float eps, int relu,
+                                       lc_layout layout, const float* stats, size_t stats_tiles, void* workspace,
+                                       size_t workspace_bytes, void* hip_stream) {
+    if (!stats) return LC_ERR_NULL;
+    if (dtype == LC_F32)
+        return bn_fwd_impl<float>(static_cast<const float*>(x), gamma, beta, static_cast<const float*>(residual), static_cast<float*>(y),
+                                  save_mean, save_invstd, n, c, h, w, eps, relu, layout, workspace, workspace_bytes, hip_stream, stats,
+                                  stats_tiles);
+    if (dtype == LC_BF16)
+        return bn_fwd_impl<uint16_t>(static_cast<const uint16_t*>(x), gamma, beta, static_cast<const uint16_t*>(residual),
+                                     static_cast<uint16_t*>(y), save_mean, save_invstd, n, c, h, w, eps, relu, layout, workspace,
+                                     workspace_bytes, hip_stream, stats, stats_tiles);
     return LC_ERR_UNSUPPORTED;
 }
 

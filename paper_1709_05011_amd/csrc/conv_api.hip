@@ -527,9 +527,12 @@ extern "C" size_t conv2d_workspace_bytes(const lc_conv_desc* desc, lc_pass pass)
     return pl.total;
 }
 
-extern "C" lc_status conv2d_fwd(const lc_conv_desc* d, const void* x, const void* w, void* y,
-                                void* workspace, size_t workspace_bytes, void* hip_stream) {
-    if (d && d->groups > 1) return run_groups(d, LC_PASS_FWD, x, w, y, workspace, workspace_bytes, hip_stream);
+namespace {
+
+// The forward pass; `stats` (may be null) receives the column sums of the result from the GEMM's epilogue (see
+// conv2d_fwd_stats) -- only for plans whose GEMM writes y itself, which fwd_stats_tiles() reports.
+lc_status fwd_impl(const lc_conv_desc* d, const void* x, const void* w, void* y, float* stats, void* workspace,
+                   size_t workspace_bytes, void* hip_stream) {
     lc_conv_desc canon;
     d = whole_window_as_1x1(d, &canon);
     Plan pl;
@@ -537,6 +540,7 @@ extern "C" lc_status conv2d_fwd(const lc_conv_desc* d, const void* x, const void
     if (st != LC_OK) return st;
     st = check_buffers(pl, x, w, y, pl.bf16 ? 16 : 4, workspace, workspace_bytes);
     if (st != LC_OK) return st;
+    if (stats && pl.nchw) return LC_ERR_UNSUPPORTED;
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     lc_begin_call();
 
@@ -547,7 +551,7 @@ extern "C" lc_status conv2d_fwd(const lc_conv_desc* d, const void* x, const void
         lc_stem_filter(w, wu, d->k, d->r, d->s, d->c, pl.RB, pl.SB, pl.CU, pl.eh, pl.ew, pl.esize, stream);
         st = lc_end_call();
         if (st != LC_OK) return st;
-        return conv2d_fwd(&pl.inner, u, wu, y, pl.s_ws_bytes ? at(workspace, pl.s_ws) : nullptr, pl.s_ws_bytes, hip_stream);
+        return fwd_impl(&pl.inner, u, wu, y, stats, pl.s_ws_bytes ? at(workspace, pl.s_ws) : nullptr, pl.s_ws_bytes, hip_stream);
     }
 
     const void* xs = x;
@@ -571,10 +575,48 @@ extern "C" lc_status conv2d_fwd(const lc_conv_desc* d, const void* x, const void
     g.b = wsrc;
     g.d = ydst;
     g.partial = pl.sk_bytes ? reinterpret_cast<float*>(at(workspace, pl.sk)) : nullptr;
+    g.stats = stats;
     st = lc_launch_conv_gemm(g, stream);
     if (st != LC_OK) return st;
     if (pl.nchw) lc_nhwc_to_nchw(ydst, y, d->n, d->k, pl.P * pl.Q, pl.esize, stream);
     return lc_end_call();
+}
+
+// Row pieces of the statistics conv2d_fwd_stats hands over for this layer; 0 when its plan has no such epilogue
+// (NCHW, groups, operands the main kernel does not take).  Needs the operand pointers' alignment only through
+// the plan, which assumes what check_buffers() enforces.
+size_t fwd_stats_tiles(const lc_conv_desc* d) {
+    lc_conv_desc canon;
+    int P, Q;
+    if (check_desc(d, &P, &Q) != LC_OK || d->groups > 1) return 0;
+    d = whole_window_as_1x1(d, &canon);
+    Plan pl;
+    if (make_plan(d, LC_PASS_FWD, &pl) != LC_OK || pl.nchw) return 0;
+    if (pl.blocks) return fwd_stats_tiles(&pl.inner);
+    GemmConv g = gemm_fwd(d, pl.P, pl.Q, pl.cpad);
+    return lc_conv_gemm_stats_tiles(g);
+}
+
+}  // namespace
+
+extern "C" lc_status conv2d_fwd(const lc_conv_desc* d, const void* x, const void* w, void* y,
+                                void* workspace, size_t workspace_bytes, void* hip_stream) {
+    if (d && d->groups > 1) return run_groups(d, LC_PASS_FWD, x, w, y, workspace, workspace_bytes, hip_stream);
+    return fwd_impl(d, x, w, y, nullptr, workspace, workspace_bytes, hip_stream);
+}
+
+extern "C" size_t conv2d_fwd_stats_count(const lc_conv_desc* d) { return d ? fwd_stats_tiles(d) : 0; }
+
+extern "C" lc_status conv2d_fwd_stats(const lc_conv_desc* d, const void* x, const void* w, void* y, float* stats, void* workspace,
+                                      size_t workspace_bytes, void* hip_stream) {
+    if (!d) return LC_ERR_NULL;
+    int P, Q;
+    const lc_status st = check_desc(d, &P, &Q);
+    if (st != LC_OK) return st;
+    if (fwd_stats_tiles(d) == 0) return LC_ERR_UNSUPPORTED;
+    if (!stats) return LC_ERR_NULL;
+    if (reinterpret_cast<uintptr_t>(stats) & 7) return LC_ERR_ALIGN;
+    return fwd_impl(d, x, w, y, stats, workspace, workspace_bytes, hip_stream);
 }
 
 extern "C" lc_status conv2d_bwd_data(const lc_conv_desc* d, const void* dy, const void* w, void* dx,

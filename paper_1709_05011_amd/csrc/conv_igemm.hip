@@ -711,6 +711,44 @@ conv_gemm_pk_kernel(const GemmConv p) {
                         }
                     }
             }
+            if constexpr (!SCATTER) {
+                if (p.stats) {
+                    // Per column, the sum and the sum of squares of what this wave has just stored (the values as stored:
+                    // rounded where the result is bf16) over its WTM rows; rows past M count as zero.  A lane holds 16 rows
+                    // of a column per 32x32 tile, the other half of the wave the other 16.
+                    typedef float flt2 __attribute__((ext_vector_type(2)));
+                    flt2* st = reinterpret_cast<flt2*>(p.stats) + (size_t)(tm * 2 + wm) * N_;
+                    const bool ragged = m0 + BM > M_;
+#pragma unroll
+                    for (int j = 0; j < TN; ++j) {
+                        float sum = 0.f, sq = 0.f;
+#pragma unroll
+                        for (int i = 0; i < TM; ++i)
+#pragma unroll
+                            for (int v = 0; v < 16; v += 2) {
+                                float x0 = acc[i][j][v], x1 = acc[i][j][v + 1];
+                                if constexpr (BF16) {
+                                    const unsigned u = lc_bf16x2_rne(x0, x1);
+                                    x0 = __uint_as_float(u << 16);
+                                    x1 = __uint_as_float(u & 0xffff0000u);
+                                }
+                                if (ragged) {
+                                    const int row = m0 + wm * WTM + i * 32 + 8 * (v >> 2) + 4 * fhalf + (v & 3);
+                                    if (row >= M_) x0 = 0.f;
+                                    if (row + 1 >= M_) x1 = 0.f;
+                                }
+                                sum += x0;
+                                sq = fmaf(x0, x0, sq);
+                                sum += x1;
+                                sq = fmaf(x1, x1, sq);
+                            }
+                        sum += __shfl_xor(sum, 32);
+                        sq += __shfl_xor(sq, 32);
+                        const int col = n0 + wn * WTN + j * 32 + frow;
+                        if (fhalf == 0 && col < N_) st[col] = flt2{sum, sq};
+                    }
+                }
+            }
         } else {
             // part of a tile: it is the first piece of this block's stream-K range (slot 2*bid) or the last (2*bid + 1)
             float* part = p.partial + ((size_t)2 * bid + (c_seg == rounds ? 0 : 1)) * (BM * BN);
@@ -806,6 +844,30 @@ __global__ void __launch_bounds__(2 * pk_waves_n(BM, BN) * 64) conv_gemm_fixup_k
     const int tile = p.dp_tiles + blockIdx.x;
     const int m0 = (tile / nbn) * BM, n0 = (tile % nbn) * BN;
     store_tile<TM, TN, BF16>(p, out, m0 + wm * (BM / 2), n0 + wn * (BN / WN_), lane, v);
+}
+
+// The column sums of the tiles that stream-K blocks shared (the main kernel sums the tiles it stores whole): block
+// (t, h) reads the rows of half h of tile first_tile + t back from d, one thread per column, rows in order.
+template <bool BF16>
+__global__ void __launch_bounds__(256) tile_stats_kernel(const GemmConv p, int bm, int bn, int first_tile) {
+    using E = typename OutT<BF16>::type;
+    const int nbn = (p.N + bn - 1) / bn;
+    const int tile = first_tile + blockIdx.x, tm = tile / nbn;
+    const int m0 = tm * bm + (int)blockIdx.y * (bm / 2), n0 = (tile - tm * nbn) * bn;
+    const int col = n0 + (int)threadIdx.x;
+    if ((int)threadIdx.x >= bn || col >= p.N) return;
+    const E* __restrict__ D = static_cast<const E*>(p.d);
+    const int m1 = min(m0 + bm / 2, p.M);
+    double sum = 0.0, sq = 0.0;
+    for (int r = m0; r < m1; ++r) {
+        float x;
+        if constexpr (BF16) x = __uint_as_float((unsigned)D[(long long)r * p.ldd + col] << 16);
+        else x = D[(long long)r * p.ldd + col];
+        sum += (double)x;
+        sq += (double)x * (double)x;
+    }
+    typedef float flt2 __attribute__((ext_vector_type(2)));
+    reinterpret_cast<flt2*>(p.stats)[(size_t)(tm * 2 + (int)blockIdx.y) * p.N + col] = flt2{(float)sum, (float)sq};
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -1000,6 +1062,36 @@ __global__ void __launch_bounds__(256, 2) conv3x3_slab_kernel(const GemmConv p) 
                     }
                 }
             }
+    }
+    if (p.stats) {
+        // per column, the sum and the sum of squares of the stored (rounded) values over this wave's 64 rows, as in the main kernel
+        typedef float flt2 __attribute__((ext_vector_type(2)));
+        flt2* st = reinterpret_cast<flt2*>(p.stats) + (size_t)((m0 / BM) * 2 + wm) * N_;
+        const bool ragged = m0 + BM > M_;
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+            float sum = 0.f, sq = 0.f;
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int v = 0; v < 16; v += 2) {
+                    const unsigned u = lc_bf16x2_rne(acc[i][j][v], acc[i][j][v + 1]);
+                    float x0 = __uint_as_float(u << 16), x1 = __uint_as_float(u & 0xffff0000u);
+                    if (ragged) {
+                        const int row = m0 + wm * WTM + i * 32 + 8 * (v >> 2) + 4 * fhalf + (v & 3);
+                        if (row >= M_) x0 = 0.f;
+                        if (row + 1 >= M_) x1 = 0.f;
+                    }
+                    sum += x0;
+                    sq = fmaf(x0, x0, sq);
+                    sum += x1;
+                    sq = fmaf(x1, x1, sq);
+                }
+            sum += __shfl_xor(sum, 32);
+            sq += __shfl_xor(sq, 32);
+            const int col = n0 + wn * WTN + j * 32 + frow;
+            if (fhalf == 0 && col < N_) st[col] = flt2{sum, sq};
+        }
     }
 }
 
@@ -1834,6 +1926,7 @@ lc_status launch_conv_sk(GemmConv p, hipStream_t stream) {
     const dim3 threads(2 * pk_waves_n(BM, BN) * 64);
     const bool whole = pl.sk_blocks == 0 || pl.sk_iters == (long long)pl.sk_blocks * nkt;
     const bool ut = !SMALLC && uniform_tap_ok<BM, BN>(p);
+    if (p.scatter && p.stats) return LC_ERR_UNSUPPORTED;
     if (p.scatter) {                          // the scatter epilogue addresses the result relative to the tile's first pixel
         const long long span = ((long long)BM / ((long long)p.Po * p.Qo) + 2) * p.Ho * p.Wo * p.ldd * (p.bf16 ? 2 : 4);
         if (span >= 0x7fff0000LL || SMALLC || BN > 128 || BM > 128) return LC_ERR_UNSUPPORTED;   // (1x1 windows never have fewer channels than a k-step)
@@ -1848,8 +1941,12 @@ lc_status launch_conv_sk(GemmConv p, hipStream_t stream) {
     } else {
         hipLaunchKernelGGL((conv_gemm_pk_kernel<BM, BN, SMALLC, BF16, false, false>), dim3(grid), threads, 0, stream, p);
     }
-    if (!whole)
+    if (!whole) {
         hipLaunchKernelGGL((conv_gemm_fixup_kernel<BM, BN, BF16>), dim3((unsigned)(tiles - pl.dp_tiles), 16), threads, 0, stream, p);
+        if (p.stats)
+            hipLaunchKernelGGL((tile_stats_kernel<BF16>), dim3((unsigned)(tiles - pl.dp_tiles), 2), dim3(256), 0, stream, p, BM, BN,
+                               pl.dp_tiles);
+    }
     return lc_end_call();
 }
 
@@ -1938,7 +2035,39 @@ static lc_status launch_slab(const GemmConv& p, size_t lds, hipStream_t stream) 
     return lc_end_call();
 }
 
+// The tile the main kernel runs a problem with (0 x 0: another kernel takes it); mirrors lc_launch_conv_gemm.
+static void main_kernel_tile(const GemmConv& p, int* bm, int* bn) {
+    *bm = *bn = 0;
+    size_t lds;
+    if (p.bf16 && slab_kernel_ok(p, p.N > 64 ? 128 : 64, &lds)) {       // the slab kernel: 128 rows
+        *bm = 128;
+        *bn = p.N > 64 ? 128 : 64;
+        return;
+    }
+    if (!use_main_kernel(p) || p.scatter) return;
+    if (p.bf16) {
+        if (p.Ci < 32) {
+            *bm = 128;
+            *bn = p.N > 64 ? 128 : 64;
+        } else {
+            const MainTile t = main_tile(p);
+            *bm = t.bm;
+            *bn = t.bn;
+        }
+        return;
+    }
+    *bm = 128;
+    *bn = p.N > 64 ? 128 : 64;
+}
+
+size_t lc_conv_gemm_stats_tiles(const GemmConv& p) {
+    int bm, bn;
+    main_kernel_tile(p, &bm, &bn);
+    return bm ? (size_t)2 * ((p.M + bm - 1) / bm) : 0;
+}
+
 lc_status lc_launch_conv_gemm(const GemmConv& p, hipStream_t stream) {
+    if (p.stats && lc_conv_gemm_stats_tiles(p) == 0) return LC_ERR_UNSUPPORTED;
     if (p.bf16) {
         size_t lds;
         const int bn = p.N > 64 ? 128 : 64;

@@ -87,8 +87,12 @@ struct GemmConv {
     // multiply-high division constants for Qo and Po (filled in by the launcher)
     unsigned qo_mul, qo_shift, po_mul, po_shift;
     int bf16;           // operands a, b and result d are bf16 (sums stay fp32)
+    // not null (main and slab kernels, no scatter): [lc_conv_gemm_stats_tiles()][N][2] floats -- per half tile of rows and
+    // per column, the sum and the sum of squares of the values stored to d (as stored: after rounding to bf16)
+    float* stats;
 };
 lc_status lc_launch_conv_gemm(const GemmConv& p, hipStream_t stream);
+size_t lc_conv_gemm_stats_tiles(const GemmConv& p);   // row pieces of `stats` for this problem; 0: the kernel that takes it has none
 extern "C" int lc_selftest_division(int max_d);   // host check of the multiply-high division constants (0 = all good)
 bool lc_conv_gemm_bf16_native(const GemmConv& p);   // can the bf16 MFMA kernel take this problem (shape and alignment)?
 bool lc_conv_gemm_scatter_ok(const GemmConv& p);    // can the main kernel's scatter epilogue take this problem?

@@ -27,6 +27,7 @@ EXPORTS = ["conv2d_out_shape", "conv2d_workspace_bytes", "conv2d_fwd", "conv2d_b
            "batchnorm_workspace_bytes", "batchnorm_fwd", "batchnorm_bwd", "batchnorm_fwd_ex", "batchnorm_bwd_ex",
            "batchnorm_fwd_t", "batchnorm_bwd_t", "maxpool_fwd_t", "maxpool_bwd_t", "relu_add_bwd_t", "global_avgpool_fwd_t",
            "global_avgpool_bwd_t", "relu_add_bwd_bnsums_t", "batchnorm_bwd_presummed_t",
+           "conv2d_fwd_stats_count", "conv2d_fwd_stats", "batchnorm_fwd_pre",
            "lc_status_string", "lc_last_error_detail"]
 
 
@@ -149,6 +150,12 @@ def lib() -> ctypes.CDLL:
         L.relu_add_bwd_bnsums_t.argtypes = [i32, vp, vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, vp, sz, vp]
         L.batchnorm_bwd_presummed_t.restype = i32
         L.batchnorm_bwd_presummed_t.argtypes = [i32, vp, vp, vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, vp, sz, vp]
+        L.conv2d_fwd_stats_count.restype = sz
+        L.conv2d_fwd_stats_count.argtypes = [dp]
+        L.conv2d_fwd_stats.restype = i32
+        L.conv2d_fwd_stats.argtypes = [dp, vp, vp, vp, vp, vp, sz, vp]
+        L.batchnorm_fwd_pre.restype = i32
+        L.batchnorm_fwd_pre.argtypes = [i32, vp, vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, ctypes.c_float, i32, i32, vp, sz, vp, sz, vp]
         L.lc_status_string.restype = ctypes.c_char_p
         L.lc_status_string.argtypes = [i32]
         L.lc_last_error_detail.restype = ctypes.c_char_p
@@ -465,3 +472,20 @@ def batchnorm_bwd_presummed_t(dtype: int, x, dy, gamma, save_mean, save_invstd, 
     _check(lib().batchnorm_bwd_presummed_t(dtype, _ptr(x), _ptr(dy), _ptr(gamma), _ptr(save_mean), _ptr(save_invstd), _ptr(dx),
                                            _ptr(dgamma), _ptr(dbeta), n, c, h, w, layout, _ptr(workspace), _nbytes(workspace),
                                            _stream(stream)), "batchnorm_bwd_presummed_t")
+# ---- batch-norm statistics out of the convolution's epilogue ----
+
+def conv2d_fwd_stats_count(desc) -> int:
+    return int(lib().conv2d_fwd_stats_count(ctypes.byref(_desc(desc))))
+
+
+def conv2d_fwd_stats(desc, x, w, y, stats, workspace=None, stream=None, workspace_bytes: Optional[int] = None) -> None:
+    nb = _nbytes(workspace) if workspace_bytes is None else workspace_bytes
+    _check(lib().conv2d_fwd_stats(ctypes.byref(_desc(desc)), _ptr(x), _ptr(w), _ptr(y), _ptr(stats), _ptr(workspace), nb,
+                                  _stream(stream)), "conv2d_fwd_stats")
+
+
+def batchnorm_fwd_pre(dtype: int, x, gamma, beta, residual, y, save_mean, save_invstd, n: int, c: int, h: int, w: int, eps: float,
+                      relu: bool, layout: int, stats, stats_tiles: int, workspace=None, stream=None) -> None:
+    _check(lib().batchnorm_fwd_pre(dtype, _ptr(x), _ptr(gamma), _ptr(beta), _ptr(residual), _ptr(y), _ptr(save_mean),
+                                   _ptr(save_invstd), n, c, h, w, eps, int(bool(relu)), layout, _ptr(stats), stats_tiles,
+                                   _ptr(workspace), _nbytes(workspace), _stream(stream)), "batchnorm_fwd_pre")

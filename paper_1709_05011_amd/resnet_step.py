@@ -42,7 +42,7 @@ class _ConvBn:
 class ResNetStep:
     def __init__(self, stem: Tuple[int, int, int, int], widths: Sequence[int], blocks: Sequence[int], classes: int, batch: int,
                  image_hw: Tuple[int, int], in_channels: int = 3, eps: float = 1e-5, device: str = "cuda:0", dtype: int = lc.LC_F32,
-                 join_sums: bool = True):
+                 join_sums: bool = True, fuse_stats: bool = True):
         lc.lib()                     # fails here, loudly, when the library has not been built
         self.join_sums = join_sums   # False: the block-output gradient and the batch-norm sums behind it as two plain calls
         self.dev, self.eps, self.batch, self.classes = device, eps, batch, classes
@@ -105,6 +105,13 @@ class ResNetStep:
         self._gsq_list = [self.gsq.get(k) for k in names]
         self._gsq_counts = [0 if t is None else t.numel() for t in self._gsq_list]
 
+        # batch-norm statistics out of the forward convolution's epilogue, where the layer's plan has one: one buffer,
+        # written by the convolution and read by the batch norm right behind it
+        self.stats_tiles: Dict[str, int] = {name: (lc.conv2d_fwd_stats_count(self.layers[name].desc) if fuse_stats else 0)
+                                            for name in self.order}
+        most = max([t * self.layers[name].desc.k * 2 for name, t in self.stats_tiles.items()] + [2])
+        self._stats = torch.empty(most, dtype=torch.float32, device=device)
+
         # one workspace for every convolution pass and every batch norm
         need = 0
         for name in self.order:
@@ -162,9 +169,16 @@ class ResNetStep:
         L = self.layers[name]
         L.x = x
         k, (p, q) = L.desc.k, L.out_hw
-        lc.conv2d_fwd(L.desc, x, self._filter(name), L.z, self._ws)
-        lc.batchnorm_fwd_t(self.dtype, L.z, self.params[name + ".gamma"], self.params[name + ".beta"], residual, L.a, L.mean, L.invstd,
-                           self.batch, k, p, q, self.eps, L.relu or relu_after_residual, NHWC, self._ws)
+        tiles = self.stats_tiles[name]
+        if tiles:
+            lc.conv2d_fwd_stats(L.desc, x, self._filter(name), L.z, self._stats, self._ws)
+            lc.batchnorm_fwd_pre(self.dtype, L.z, self.params[name + ".gamma"], self.params[name + ".beta"], residual, L.a, L.mean,
+                                 L.invstd, self.batch, k, p, q, self.eps, L.relu or relu_after_residual, NHWC, self._stats, tiles,
+                                 self._ws)
+        else:
+            lc.conv2d_fwd(L.desc, x, self._filter(name), L.z, self._ws)
+            lc.batchnorm_fwd_t(self.dtype, L.z, self.params[name + ".gamma"], self.params[name + ".beta"], residual, L.a, L.mean,
+                               L.invstd, self.batch, k, p, q, self.eps, L.relu or relu_after_residual, NHWC, self._ws)
         return L.a
 
     def _conv_bn_bwd(self, name: str, da: torch.Tensor, need_dx: bool = True, presummed: bool = False) -> Optional[torch.Tensor]:

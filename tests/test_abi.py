@@ -336,6 +336,35 @@ def test_joined_block_gradient_rejects_bad_arguments_before_launch():
     assert pre(dt=lc.LC_F32, lay=lc.LC_NCHW) == lc.LC_ERR_UNSUPPORTED
     assert pre(nb=0) == lc.LC_ERR_WORKSPACE
     assert pre(dt=9) == lc.LC_ERR_UNSUPPORTED
+def test_statistics_entry_points_reject_bad_arguments_before_launch():
+    L = lc.lib()
+    P = ctypes.c_void_p(FAKE)
+    d = lc.ConvDesc(4, 64, 14, 14, 128, 3, 3, 1, 1, 1, 1, lc.LC_F32, lc.LC_NHWC)
+    count = lc.conv2d_fwd_stats_count(d)
+    assert count == 2 * ((4 * 14 * 14 + 127) // 128)                       # two half tiles of 128 rows each
+    big = lc.ConvDesc(64, 128, 28, 28, 512, 1, 1, 1, 1, 0, 0, lc.LC_BF16, lc.LC_NHWC)
+    assert lc.conv2d_fwd_stats_count(big) in (2 * ((64 * 28 * 28 + 255) // 256), 2 * ((64 * 28 * 28 + 127) // 128))
+    assert lc.conv2d_fwd_stats_count(lc.ConvDesc(4, 64, 14, 14, 128, 3, 3, 1, 1, 1, 1, lc.LC_F32, lc.LC_NCHW)) == 0
+    assert lc.conv2d_fwd_stats_count(lc.ConvDesc(4, 64, 14, 14, 128, 3, 3, 1, 1, 1, 1, lc.LC_F32, lc.LC_NHWC, groups=2)) == 0
+    assert lc.conv2d_fwd_stats_count(lc.ConvDesc(0, 64, 14, 14, 128, 3, 3, 1, 1, 1, 1, lc.LC_F32, lc.LC_NHWC)) == 0
+    cs = d.c_struct()
+    need = lc.conv2d_workspace_bytes(d, lc.LC_PASS_FWD)
+    call = lambda desc, st, y=P: L.conv2d_fwd_stats(ctypes.byref(desc), P, P, y, st, P, need, None)
+    assert call(cs, None) == lc.LC_ERR_NULL
+    assert call(cs, ctypes.c_void_p(FAKE + 4)) == lc.LC_ERR_ALIGN
+    assert call(cs, P, y=None) == lc.LC_ERR_NULL
+    nchw = lc.ConvDesc(4, 64, 14, 14, 128, 3, 3, 1, 1, 1, 1, lc.LC_F32, lc.LC_NCHW).c_struct()
+    assert call(nchw, P) == lc.LC_ERR_UNSUPPORTED
+    assert L.conv2d_fwd_stats(None, P, P, P, P, P, need, None) == lc.LC_ERR_NULL
+    bneed = lc.batchnorm_workspace_bytes(4, 128, 14, 14, lc.LC_NHWC)
+    pre = lambda st, tiles, lay=lc.LC_NHWC, dt=lc.LC_F32, nb=bneed: L.batchnorm_fwd_pre(dt, P, P, P, None, P, P, P, 4, 128, 14, 14, 1e-5, 1,
+                                                                                     lay, st, tiles, P, nb, None)
+    assert pre(None, count) == lc.LC_ERR_NULL
+    assert pre(P, 0) == lc.LC_ERR_UNSUPPORTED
+    assert pre(P, count, lay=lc.LC_NCHW) == lc.LC_ERR_UNSUPPORTED
+    assert pre(ctypes.c_void_p(FAKE + 4), count) == lc.LC_ERR_ALIGN
+    assert pre(P, count, dt=5) == lc.LC_ERR_UNSUPPORTED
+    assert pre(P, count, nb=256) == lc.LC_ERR_WORKSPACE
 
 
 def test_poly_lr_host_arithmetic():
