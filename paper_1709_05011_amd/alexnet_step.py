@@ -43,12 +43,14 @@ class AlexNetStep:
             self.params[name + ".gamma"] = torch.ones(k, **f32)
             self.params[name + ".beta"] = torch.zeros(k, **f32)
             need = max(need, lc.batchnorm_workspace_bytes(batch, k, p, q, NHWC))
+            L["stats_tiles"] = lc.conv2d_fwd_stats_count(d)
             h, w, c = p, q, k
             if pool:
                 h, w = (h - 3) // 2 + 1, (w - 3) // 2 + 1
                 L["pooled"] = torch.empty((batch, h, w, k), **f32)
                 L["pool_idx"] = torch.empty((batch, h, w, k), dtype=torch.uint8, device=device)
             self.conv_layers.append(L)
+        self._stats = torch.empty(max([L["stats_tiles"] * L["desc"].k * 2 for L in self.conv_layers] + [2]), **f32)
         widths = list(fcs) + [classes]
         n_conv = len(convs)
         for j, out in enumerate(widths):
@@ -89,9 +91,15 @@ class AlexNetStep:
         for L in self.conv_layers:
             name, d, (p, q) = L["name"], L["desc"], L["out_hw"]
             L["x"] = a
-            lc.conv2d_fwd(d, a, self.params[name + ".w"], L["z"], self._ws)
-            lc.batchnorm_fwd_ex(L["z"], self.params[name + ".gamma"], self.params[name + ".beta"], None, L["a"], L["mean"], L["invstd"],
-                                n, d.k, p, q, self.eps, True, NHWC, self._ws)
+            tiles = L["stats_tiles"]
+            if tiles:           # the batch-norm statistics come out of the convolution's epilogue
+                lc.conv2d_fwd_stats(d, a, self.params[name + ".w"], L["z"], self._stats, self._ws)
+                lc.batchnorm_fwd_pre(lc.LC_F32, L["z"], self.params[name + ".gamma"], self.params[name + ".beta"], None, L["a"], L["mean"],
+                                     L["invstd"], n, d.k, p, q, self.eps, True, NHWC, self._stats, tiles, self._ws)
+            else:
+                lc.conv2d_fwd(d, a, self.params[name + ".w"], L["z"], self._ws)
+                lc.batchnorm_fwd_ex(L["z"], self.params[name + ".gamma"], self.params[name + ".beta"], None, L["a"], L["mean"],
+                                    L["invstd"], n, d.k, p, q, self.eps, True, NHWC, self._ws)
             a = L["a"]
             if L["pool"]:
                 lc.maxpool_fwd(a, L["pooled"], L["pool_idx"], n, d.k, p, q, 3, 2, 0, NHWC)
