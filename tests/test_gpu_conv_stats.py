@@ -178,3 +178,53 @@ def test_reruns_are_bit_identical():
         torch.cuda.synchronize()
         runs.append(st.cpu().numpy())
     np.testing.assert_array_equal(runs[0], runs[1])
+
+
+def test_statistics_at_full_size_bf16():
+    """res2a's 1x1 convolution of the bf16 workload at its full size (512 x 56 x 56 x 64 -> 256: 1.6 M rows, 411 M outputs), the
+    launch configuration bench.py times.  What holds at any size: y equals conv2d_fwd's bit for bit; the pieces, added up
+    on the host, are the column sums of y as the device stored it (summed in float64 here, channel by channel); the batch
+    norm that takes them returns that mean and 1/std and normalises sampled outputs accordingly."""
+    n, c, hw, k = 512, 64, 56, 256
+    gen = torch.Generator(device=gu.DEV)
+    gen.manual_seed(4242)
+    x = (torch.randn((n, hw, hw, c), generator=gen, device=gu.DEV) + 0.2).to(torch.bfloat16)
+    w = (torch.randn((k, 1, 1, c), generator=gen, device=gu.DEV) * (2.0 / c) ** 0.5).to(torch.bfloat16)
+    d = lc.ConvDesc(n, c, hw, hw, k, 1, 1, 1, 1, 0, 0, lc.LC_BF16, NHWC)
+    count = lc.conv2d_fwd_stats_count(d)
+    assert count > 0
+    ws = gu.workspace(lc.conv2d_workspace_bytes(d, lc.LC_PASS_FWD))
+    y0 = torch.empty((n, hw, hw, k), dtype=torch.bfloat16, device=gu.DEV)
+    y = torch.empty_like(y0)
+    stats = torch.full((count, k, 2), float("nan"), dtype=torch.float32, device=gu.DEV)
+    lc.conv2d_fwd(d, x, w, y0, ws)
+    lc.conv2d_fwd_stats(d, x, w, y, stats, ws)
+    torch.cuda.synchronize()
+    assert torch.equal(y.view(torch.int16), y0.view(torch.int16))
+    del y0
+    got = stats.cpu().numpy().astype(np.float64)
+    assert np.all(np.isfinite(got))
+    m = n * hw * hw
+    s1, s2 = np.zeros(k), np.zeros(k)
+    rows = y.view(m, k)
+    for lo in range(0, m, 1 << 18):                        # float64 sums on the host, a slice at a time
+        part = rows[lo:lo + (1 << 18)].to(torch.float32).cpu().numpy().astype(np.float64)
+        s1 += part.sum(axis=0)
+        s2 += (part * part).sum(axis=0)
+    assert np.all(np.abs(got[:, :, 0].sum(axis=0) - s1) <= 1e-6 * np.sqrt(m) * np.sqrt(s2 / m) + 1e-9 * np.abs(s1))
+    assert np.all(np.abs(got[:, :, 1].sum(axis=0) - s2) <= 1e-6 * s2)
+    mean_ref, var_ref = s1 / m, s2 / m - (s1 / m) ** 2
+    gamma = gu.dev((1.0 + 0.3 * synth.normal((k,), 4243)).astype(np.float32))
+    beta = gu.dev((0.3 * synth.normal((k,), 4244)).astype(np.float32))
+    out = torch.empty_like(y)
+    mean, invstd = torch.empty(k, device=gu.DEV), torch.empty(k, device=gu.DEV)
+    bws = gu.workspace(lc.batchnorm_workspace_bytes(n, k, hw, hw, NHWC))
+    lc.batchnorm_fwd_pre(lc.LC_BF16, y, gamma, beta, None, out, mean, invstd, n, k, hw, hw, EPS, True, NHWC, stats, count, bws)
+    torch.cuda.synchronize()
+    assert np.max(np.abs(mean.cpu().numpy() - mean_ref)) <= 1e-5 * float(np.max(np.abs(mean_ref)) + np.sqrt(np.max(var_ref)))
+    assert np.max(np.abs(invstd.cpu().numpy() * np.sqrt(var_ref + EPS) - 1.0)) <= 1e-4
+    idx = torch.from_numpy(synth.uniform_int(4096, 4245, m)).to(gu.DEV).long()
+    ys = rows[idx].to(torch.float32).cpu().numpy().astype(np.float64)
+    want = np.maximum((ys - mean_ref) / np.sqrt(var_ref + EPS) * gamma.cpu().numpy().astype(np.float64) + beta.cpu().numpy(), 0.0)
+    gots = out.view(m, k)[idx].to(torch.float32).cpu().numpy()
+    assert np.all(np.abs(gots - want) <= np.abs(want) * 2.0 ** -8 + 2e-4 * float(np.max(np.abs(want))))
