@@ -847,27 +847,72 @@ __global__ void __launch_bounds__(2 * pk_waves_n(BM, BN) * 64) conv_gemm_fixup_k
 }
 
 // The column sums of the tiles that stream-K blocks shared (the main kernel sums the tiles it stores whole): block
-// (t, h) reads the rows of half h of tile first_tile + t back from d, one thread per column, rows in order.
-template <bool BF16>
+// (t, h) reads the rows of half h of tile first_tile + t back from d.  VEC4: a thread owns four neighbouring columns and
+// every (256 / (bn / 4))-th row (one 16- or 8-byte load each, all independent), the rows of a column group are then
+// added in order through LDS; otherwise one thread per column walks the rows.
+template <bool BF16, bool VEC4>
 __global__ void __launch_bounds__(256) tile_stats_kernel(const GemmConv p, int bm, int bn, int first_tile) {
     using E = typename OutT<BF16>::type;
+    typedef float flt2 __attribute__((ext_vector_type(2)));
     const int nbn = (p.N + bn - 1) / bn;
     const int tile = first_tile + blockIdx.x, tm = tile / nbn;
     const int m0 = tm * bm + (int)blockIdx.y * (bm / 2), n0 = (tile - tm * nbn) * bn;
-    const int col = n0 + (int)threadIdx.x;
-    if ((int)threadIdx.x >= bn || col >= p.N) return;
     const E* __restrict__ D = static_cast<const E*>(p.d);
     const int m1 = min(m0 + bm / 2, p.M);
-    double sum = 0.0, sq = 0.0;
-    for (int r = m0; r < m1; ++r) {
-        float x;
-        if constexpr (BF16) x = __uint_as_float((unsigned)D[(long long)r * p.ldd + col] << 16);
-        else x = D[(long long)r * p.ldd + col];
-        sum += (double)x;
-        sq += (double)x * (double)x;
+    flt2* out = reinterpret_cast<flt2*>(p.stats) + (size_t)(tm * 2 + (int)blockIdx.y) * p.N;
+    if constexpr (VEC4) {
+        __shared__ double red[256][8];
+        const int groups = bn / 4, lanes = 256 / groups;          // bn 64, 128, 256: 16, 8, 4 row lanes per column group
+        const int cg = threadIdx.x % groups, rl = threadIdx.x / groups;
+        const int col = n0 + cg * 4;
+        double sum[4] = {0.0, 0.0, 0.0, 0.0}, sq[4] = {0.0, 0.0, 0.0, 0.0};
+        if (col < p.N)
+            for (int r = m0 + rl; r < m1; r += lanes) {
+                float x[4];
+                if constexpr (BF16) {
+                    const uint2 u = *reinterpret_cast<const uint2*>(D + (long long)r * p.ldd + col);
+                    x[0] = __uint_as_float(u.x << 16); x[1] = __uint_as_float(u.x & 0xffff0000u);
+                    x[2] = __uint_as_float(u.y << 16); x[3] = __uint_as_float(u.y & 0xffff0000u);
+                } else {
+                    const float4 u = *reinterpret_cast<const float4*>(D + (long long)r * p.ldd + col);
+                    x[0] = u.x; x[1] = u.y; x[2] = u.z; x[3] = u.w;
+                }
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    sum[e] += (double)x[e];
+                    sq[e] += (double)x[e] * (double)x[e];
+                }
+            }
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            red[threadIdx.x][e] = sum[e];
+            red[threadIdx.x][4 + e] = sq[e];
+        }
+        __syncthreads();
+        if (rl == 0 && col < p.N) {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                double s1 = 0.0, s2 = 0.0;
+                for (int k = 0; k < lanes; ++k) {
+                    s1 += red[k * groups + cg][e];
+                    s2 += red[k * groups + cg][4 + e];
+                }
+                out[col + e] = flt2{(float)s1, (float)s2};
+            }
+        }
+    } else {
+        const int col = n0 + (int)threadIdx.x;
+        if ((int)threadIdx.x >= bn || col >= p.N) return;
+        double sum = 0.0, sq = 0.0;
+        for (int r = m0; r < m1; ++r) {
+            float x;
+            if constexpr (BF16) x = __uint_as_float((unsigned)D[(long long)r * p.ldd + col] << 16);
+            else x = D[(long long)r * p.ldd + col];
+            sum += (double)x;
+            sq += (double)x * (double)x;
+        }
+        out[col] = flt2{(float)sum, (float)sq};
     }
-    typedef float flt2 __attribute__((ext_vector_type(2)));
-    reinterpret_cast<flt2*>(p.stats)[(size_t)(tm * 2 + (int)blockIdx.y) * p.N + col] = flt2{(float)sum, (float)sq};
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -1943,9 +1988,14 @@ lc_status launch_conv_sk(GemmConv p, hipStream_t stream) {
     }
     if (!whole) {
         hipLaunchKernelGGL((conv_gemm_fixup_kernel<BM, BN, BF16>), dim3((unsigned)(tiles - pl.dp_tiles), 16), threads, 0, stream, p);
-        if (p.stats)
-            hipLaunchKernelGGL((tile_stats_kernel<BF16>), dim3((unsigned)(tiles - pl.dp_tiles), 2), dim3(256), 0, stream, p, BM, BN,
-                               pl.dp_tiles);
+        if (p.stats) {
+            const dim3 sgrid((unsigned)(tiles - pl.dp_tiles), 2);
+            const bool vec4 = p.N % 4 == 0 && p.ldd % 4 == 0 && (reinterpret_cast<uintptr_t>(p.d) & 15) == 0;
+            if (vec4)
+                hipLaunchKernelGGL((tile_stats_kernel<BF16, true>), sgrid, dim3(256), 0, stream, p, BM, BN, pl.dp_tiles);
+            else
+                hipLaunchKernelGGL((tile_stats_kernel<BF16, false>), sgrid, dim3(256), 0, stream, p, BM, BN, pl.dp_tiles);
+        }
     }
     return lc_end_call();
 }
