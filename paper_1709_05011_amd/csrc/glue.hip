@@ -9,6 +9,7 @@
 
 #include "../../include/larsconv.h"
 #include "internal.h"
+#include "pool_patch.h"
 
 namespace {
 
@@ -265,6 +266,26 @@ __global__ void global_avgpool_fwd_kernel(const float* __restrict__ x, float* __
     if (lane == 0) y[pair] = s / (float)hw;
 }
 
+// NHWC with the channel count a multiple of four: a thread owns four neighbouring channels of one image and adds its pixels
+// in order (16-byte loads, neighbouring threads on neighbouring channels).
+__global__ void __launch_bounds__(kThreads) global_avgpool_fwd_nhwc4_kernel(const float4* __restrict__ x, float4* __restrict__ y, int N,
+                                                                            int C4, int HW) {
+    const size_t total = (size_t)N * C4;
+    const float inv = 1.f / (float)HW;
+    for (size_t o = blockIdx.x * (size_t)blockDim.x + threadIdx.x; o < total; o += (size_t)gridDim.x * blockDim.x) {
+        const size_t n = o / C4;
+        const int c4 = (int)(o % C4);
+        const float4* src = x + n * HW * C4 + c4;
+        float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll 7
+        for (int i = 0; i < HW; ++i) {
+            const float4 v = src[(size_t)i * C4];
+            s.x += v.x; s.y += v.y; s.z += v.z; s.w += v.w;
+        }
+        y[o] = make_float4(s.x * inv, s.y * inv, s.z * inv, s.w * inv);
+    }
+}
+
 __global__ void global_avgpool_bwd_kernel(const float* __restrict__ dy, float* __restrict__ dx, int N, int C, int H, int W, bool nhwc) {
     const size_t total = (size_t)N * C * H * W;
     const float inv = 1.f / (float)(H * W);
@@ -285,13 +306,25 @@ __global__ void bias_add_kernel(float* __restrict__ y, const float* __restrict__
     for (size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x; i < total; i += (size_t)gridDim.x * blockDim.x) y[i] += b[i % K];
 }
 
-// One thread per column, rows added in order.
-__global__ void bias_grad_kernel(const float* __restrict__ dy, float* __restrict__ db, size_t rows, int K) {
-    const int k = blockIdx.x * blockDim.x + threadIdx.x;
-    if (k >= K) return;
-    float s = 0.f;
-    for (size_t r = 0; r < rows; ++r) s += dy[r * K + k];
-    db[k] = s;
+// A block owns 64 columns; its four waves take every fourth row each, four rows in flight per wave, and the sixteen running
+// sums of a column are combined in a fixed order.
+__global__ void __launch_bounds__(kThreads) bias_grad_kernel(const float* __restrict__ dy, float* __restrict__ db, size_t rows, int K) {
+    constexpr int kWaves = kThreads / 64;
+    __shared__ float part[kWaves][64];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int k = blockIdx.x * 64 + lane;
+    float s[4] = {0.f, 0.f, 0.f, 0.f};
+    if (k < K) {
+        size_t r = wave;
+        for (; r + 3 * kWaves < rows; r += 4 * kWaves) {
+#pragma unroll
+            for (int u = 0; u < 4; ++u) s[u] += dy[(r + (size_t)u * kWaves) * K + k];
+        }
+        for (; r < rows; r += kWaves) s[0] += dy[r * K + k];
+    }
+    part[wave][lane] = (s[0] + s[1]) + (s[2] + s[3]);
+    __syncthreads();
+    if (wave == 0 && k < K) db[k] = (part[0][lane] + part[1][lane]) + (part[2][lane] + part[3][lane]);
 }
 
 // One wave per row: softmax, the row's -log p[label], and (softmax - onehot) / N.  row_loss[n] is reduced by
@@ -403,6 +436,16 @@ extern "C" lc_status relu_add_bwd(const float* y, const float* da, const float* 
 }
 
 namespace {
+struct PoolF32 {                                // four fp32 channels per thread
+    using T = float;
+    static constexpr int VEC = 4;
+    static __device__ void load(const float* p, float (&v)[4]) {
+        const float4 q = *reinterpret_cast<const float4*>(p);
+        v[0] = q.x; v[1] = q.y; v[2] = q.z; v[3] = q.w;
+    }
+    static __device__ void store(float* p, const float (&v)[4]) { *reinterpret_cast<float4*>(p) = make_float4(v[0], v[1], v[2], v[3]); }
+};
+
 // output size of a pool; false when the arguments make no sense
 bool pool_shape(int n, int c, int h, int w, int window, int stride, int pad, int* ho, int* wo) {
     if (n <= 0 || c <= 0 || h <= 0 || w <= 0 || window < 1 || window > 15 || stride < 1 || pad < 0 || pad >= window) return false;
@@ -441,7 +484,11 @@ extern "C" lc_status maxpool_bwd(const float* dy, const uint8_t* idx, float* dx,
     if (misaligned(dy) || misaligned(dx)) return LC_ERR_ALIGN;
     lc_begin_call();
     const size_t total = (size_t)n * c * h * w;
-    if (layout == LC_NHWC && c % 4 == 0 && aligned16(dy) && aligned16(dx) && (reinterpret_cast<uintptr_t>(idx) & 3) == 0)
+    const bool vec4 = layout == LC_NHWC && c % 4 == 0 && aligned16(dy) && aligned16(dx) && (reinterpret_cast<uintptr_t>(idx) & 3) == 0;
+    if (vec4 && window == 3 && stride == 2 && pad == 1)
+        hipLaunchKernelGGL(maxpool_bwd_3x3s2_kernel<PoolF32>, dim3(blocks_for((size_t)n * ((h + 1) / 2) * ((w + 1) / 2) * (c / 4))),
+                           dim3(kThreads), 0, static_cast<hipStream_t>(hip_stream), dy, idx, dx, n, c / 4, h, w, ho, wo);
+    else if (vec4)
         hipLaunchKernelGGL(maxpool_bwd_nhwc4_kernel, dim3(blocks_for(total / 4)), dim3(kThreads), 0, static_cast<hipStream_t>(hip_stream),
                            dy, idx, dx, n, c / 4, h, w, window, stride, pad, ho, wo);
     else
@@ -457,6 +504,12 @@ extern "C" lc_status global_avgpool_fwd(const float* x, float* y, int n, int c, 
     if (misaligned(x) || misaligned(y)) return LC_ERR_ALIGN;
     lc_begin_call();
     const size_t pairs = (size_t)n * c;
+    if (layout == LC_NHWC && c % 4 == 0 && aligned16(x) && aligned16(y) && (long long)h * w <= 0x7fffffffLL) {
+        hipLaunchKernelGGL(global_avgpool_fwd_nhwc4_kernel, dim3(blocks_for(pairs / 4)), dim3(kThreads), 0,
+                           static_cast<hipStream_t>(hip_stream), reinterpret_cast<const float4*>(x), reinterpret_cast<float4*>(y), n, c / 4,
+                           h * w);
+        return lc_end_call();
+    }
     const size_t blocks = (pairs + kThreads / 64 - 1) / (kThreads / 64);
     if (blocks > 0x7fffffffull) return LC_ERR_UNSUPPORTED;
     hipLaunchKernelGGL(global_avgpool_fwd_kernel, dim3((unsigned)blocks), dim3(kThreads), 0, static_cast<hipStream_t>(hip_stream), x, y,
@@ -490,7 +543,7 @@ extern "C" lc_status bias_grad(const float* dy, float* db, size_t rows, int k, v
     if (k <= 0) return LC_ERR_SHAPE;
     if (misaligned(dy) || misaligned(db)) return LC_ERR_ALIGN;
     lc_begin_call();
-    hipLaunchKernelGGL(bias_grad_kernel, dim3((unsigned)((k + kThreads - 1) / kThreads)), dim3(kThreads), 0,
+    hipLaunchKernelGGL(bias_grad_kernel, dim3((unsigned)((k + 63) / 64)), dim3(kThreads), 0,
                        static_cast<hipStream_t>(hip_stream), dy, db, rows, k);
     return lc_end_call();
 }

@@ -10,6 +10,7 @@
 
 #include "../../include/larsconv.h"
 #include "internal.h"
+#include "pool_patch.h"
 
 namespace {
 
@@ -37,6 +38,13 @@ __device__ __forceinline__ void store8(uint16_t* p, const float (&v)[8]) {
     for (int i = 0; i < 4; ++i) w[i] = lc_bf16x2_rne(v[2 * i], v[2 * i + 1]);
     *reinterpret_cast<uint4*>(p) = make_uint4(w[0], w[1], w[2], w[3]);
 }
+
+struct PoolBF16 {                               // eight bf16 channels per thread
+    using T = uint16_t;
+    static constexpr int VEC = 8;
+    static __device__ void load(const uint16_t* p, float (&v)[8]) { load8(p, v); }
+    static __device__ void store(uint16_t* p, const float (&v)[8]) { store8(p, v); }
+};
 
 // dx = round(da + db) where y > 0, else 0 (MASKED false: everywhere; TWO false: da alone)
 template <bool TWO, bool MASKED>
@@ -247,8 +255,13 @@ extern "C" lc_status maxpool_bwd_t(lc_dtype dtype, const void* dy, const uint8_t
     if (!al16(dy) || !al16(dx) || !al8(idx)) return LC_ERR_ALIGN;
     lc_begin_call();
     const size_t total = (size_t)n * h * w * (c / 8);
-    hipLaunchKernelGGL(maxpool_bwd_bf16_kernel, dim3(blocks_for(total)), dim3(kThreads), 0, static_cast<hipStream_t>(hip_stream),
-                       static_cast<const uint16_t*>(dy), idx, static_cast<uint16_t*>(dx), n, c / 8, h, w, window, stride, pad, ho, wo);
+    if (window == 3 && stride == 2 && pad == 1)
+        hipLaunchKernelGGL(maxpool_bwd_3x3s2_kernel<PoolBF16>, dim3(blocks_for((size_t)n * ((h + 1) / 2) * ((w + 1) / 2) * (c / 8))),
+                           dim3(kThreads), 0, static_cast<hipStream_t>(hip_stream), static_cast<const uint16_t*>(dy), idx,
+                           static_cast<uint16_t*>(dx), n, c / 8, h, w, ho, wo);
+    else
+        hipLaunchKernelGGL(maxpool_bwd_bf16_kernel, dim3(blocks_for(total)), dim3(kThreads), 0, static_cast<hipStream_t>(hip_stream),
+                           static_cast<const uint16_t*>(dy), idx, static_cast<uint16_t*>(dx), n, c / 8, h, w, window, stride, pad, ho, wo);
     return lc_end_call();
 }
 

@@ -71,8 +71,8 @@ def test_maxpool_forward_indices_and_backward(layout):
 
 @pytest.mark.parametrize("layout", [lc.LC_NCHW, lc.LC_NHWC], ids=["nchw", "nhwc"])
 def test_global_average_pool_forward_and_backward(layout):
-    n, c, h, w = 4, 33, 9, 7                           # 63 pixels: less than a wave; and a second case below with more
-    for (hh, ww, seed) in ((h, w, 7200), (16, 16, 7210)):
+    # 63 pixels: less than a wave; a case with more; channel counts that are multiples of four (NHWC: four channels per thread)
+    for (n, c, hh, ww, seed) in ((4, 33, 9, 7, 7200), (4, 33, 16, 16, 7210), (6, 2048, 7, 7, 7220), (3, 8, 5, 3, 7230), (2, 24, 1, 1, 7240)):
         x = synth.normal((n, c, hh, ww), seed)
         dy = synth.normal((n, c), seed + 1)
         y = torch.empty((n, c), device=gu.DEV)
@@ -84,8 +84,8 @@ def test_global_average_pool_forward_and_backward(layout):
         assert gu.scaled_err(_unlay(dx.cpu().numpy(), layout), tiny_cnn.global_avgpool_bwd(dy.astype(np.float64), hh, ww)) <= 1e-6
 
 
-def test_bias_add_and_bias_gradient():
-    rows, k = 37, 10
+@pytest.mark.parametrize("rows,k", [(37, 10), (512, 1000), (3, 70), (1, 5), (129, 64)])
+def test_bias_add_and_bias_gradient(rows, k):
     y = synth.normal((rows, k), 7300)
     b = synth.normal((k,), 7301)
     yd = _dev(y)
@@ -195,6 +195,10 @@ POOLS = {
     "resnet_stem_3x3_s2_p1": (2, 64, 16, 16, 3, 2, 1),
     "alexnet_3x3_s2_p0": (2, 6, 13, 13, 3, 2, 0),
     "ragged_3x3_s2_p1": (2, 5, 11, 9, 3, 2, 1),
+    "odd_image_3x3_s2_p1_c8": (2, 8, 11, 9, 3, 2, 1),
+    "odd_square_3x3_s2_p1_c12": (3, 12, 7, 7, 3, 2, 1),
+    "one_pixel_3x3_s2_p1": (2, 4, 1, 1, 3, 2, 1),
+    "one_row_3x3_s2_p1": (1, 4, 1, 6, 3, 2, 1),
     "stride1_3x3_p1": (1, 3, 7, 6, 3, 1, 1),
     "window2_stride2": (2, 4, 8, 6, 2, 2, 0),
     "window5_stride3_p2": (1, 2, 17, 14, 5, 3, 2),
@@ -214,6 +218,7 @@ def test_general_maxpool_forward_indices_and_backward(name, layout):
     xd = _dev(_lay(x, layout))
     y, idx = _empty((n, c, ph, pw), layout), _empty((n, c, ph, pw), layout, torch.uint8)
     dx = _empty((n, c, h, w), layout)
+    dx.fill_(float("nan"))                              # every element must be written
     lc.maxpool_fwd(xd, y, idx, n, c, h, w, k, st, pd, layout)
     lc.maxpool_bwd(_dev(_lay(dy, layout)), idx, dx, n, c, h, w, k, st, pd, layout)
     torch.cuda.synchronize()
@@ -221,6 +226,27 @@ def test_general_maxpool_forward_indices_and_backward(name, layout):
     np.testing.assert_array_equal(_unlay(idx.cpu().numpy(), layout), want_idx.astype(np.uint8))
     want_dx = ores.maxpool_bwd(want_idx, dy.astype(np.float64), (h, w), k, st, pd)
     assert gu.scaled_err(_unlay(dx.cpu().numpy(), layout), want_dx) <= 1e-6       # at most four fp32 additions
+
+
+def test_maxpool_3x3s2_gradient_is_the_same_in_both_layouts_bit_for_bit():
+    """NHWC with four channels per thread takes one thread per 2x2 input patch for the 3x3 / stride 2 / padding 1 pool, NCHW
+    one thread per input element; both add a pixel's windows in window order, so the sums are equal bit for bit."""
+    from oracle import resnet as ores
+    for (n, c, h, w, seed) in ((2, 64, 28, 28, 7750), (3, 8, 13, 10, 7751), (1, 4, 2, 3, 7752)):
+        x = synth.normal((n, c, h, w), seed)
+        _, idx_ref = ores.maxpool(x.astype(np.float64), 3, 2, 1)
+        ph, pw = idx_ref.shape[2:]
+        dy = synth.normal((n, c, ph, pw), seed + 10)
+        res = {}
+        for layout in (lc.LC_NCHW, lc.LC_NHWC):
+            idx = _dev(_lay(idx_ref.astype(np.uint8), layout), torch.uint8)
+            dx = _empty((n, c, h, w), layout)
+            dx.fill_(float("nan"))
+            lc.maxpool_bwd(_dev(_lay(dy, layout)), idx, dx, n, c, h, w, 3, 2, 1, layout)
+            torch.cuda.synchronize()
+            res[layout] = _unlay(dx.cpu().numpy(), layout)
+        np.testing.assert_array_equal(res[lc.LC_NCHW], res[lc.LC_NHWC])
+        assert np.all(np.isfinite(res[lc.LC_NHWC]))
 
 
 def test_general_maxpool_with_window2_equals_the_2x2_pool():

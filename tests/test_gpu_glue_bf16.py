@@ -194,6 +194,9 @@ def test_bf16_layers_refuse_what_they_do_not_take():
 POOLS = {
     "resnet_stem_3x3_s2_p1": ((4, 64, 28, 28), 3, 2, 1),
     "alexnet_3x3_s2": ((3, 96, 13, 13), 3, 2, 0),
+    "odd_image_3x3_s2_p1": ((3, 16, 11, 9), 3, 2, 1),
+    "one_pixel_3x3_s2_p1": ((2, 8, 1, 1), 3, 2, 1),
+    "one_column_3x3_s2_p1": ((1, 8, 5, 1), 3, 2, 1),
     "2x2_s2": ((2, 8, 6, 8), 2, 2, 0),
     "odd_image_5x5_s3_p2": ((2, 16, 11, 9), 5, 3, 2),
 }
