@@ -31,6 +31,7 @@ struct Plan {
     size_t sk = 0, sk_bytes = 0;     // partial tiles of the stream-K blocks (forward, backward-data)
     int splits = 1, m_per_split = 0;
     bool wgrad_direct = true;
+    bool wgrad_slab = false;         // bf16 3x3 stride-1 pad-1 layer: the kernel that stages the activations once for all taps
     // bf16 problems the bf16 MFMA kernel does not take (backward-data with k not a multiple of 8, or a strided
     // window other than 1x1): operands are widened to fp32 copies, the fp32 pass runs on them, the result is
     // rounded back to bf16.  Same arithmetic class: exact products of bf16 values, fp32 sums.
@@ -352,8 +353,14 @@ lc_status make_plan(const lc_conv_desc* d, lc_pass pass, Plan* pl) {
         }
         if (pad) pl->xpad = rg.take((size_t)d->n * d->h * d->w * pl->cpad * es);
         const int M = d->n * pl->P * pl->Q, J = d->r * d->s * pl->cpad;
-        pl->splits = lc_wgrad_splits(M, d->k, J, pl->bf16);
-        pl->m_per_split = (M + pl->splits - 1) / pl->splits;
+        pl->wgrad_slab = lc_wgrad_slab_ok(d->n, d->h, d->w, pl->cpad, d->k, d->r, d->s, d->stride_h, d->stride_w, d->pad_h, d->pad_w,
+                                          pl->P, pl->Q, pl->bf16);
+        if (pl->wgrad_slab) {
+            pl->splits = lc_wgrad_slab_splits(d->n, d->h, d->w, pl->cpad, d->k, &pl->m_per_split);
+        } else {
+            pl->splits = lc_wgrad_splits(M, d->k, J, pl->bf16);
+            pl->m_per_split = (M + pl->splits - 1) / pl->splits;
+        }
         pl->wgrad_direct = pl->splits == 1 && !pad;
         if (!pl->wgrad_direct) pl->part = rg.take((size_t)pl->splits * d->k * J * sizeof(float));
     }
@@ -767,6 +774,7 @@ lc_status bwd_weight_impl(const lc_conv_desc* d, const void* x, const void* dy, 
     g.splits = pl.splits;
     g.m_per_split = pl.m_per_split;
     g.bf16 = pl.bf16;
+    g.slab = pl.wgrad_slab;
     g.d = pl.wgrad_direct ? dwdst : reinterpret_cast<float*>(at(workspace, pl.part));
     st = lc_launch_wgrad_f32(g, stream);
     if (st != LC_OK) return st;

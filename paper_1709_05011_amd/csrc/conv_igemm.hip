@@ -1775,6 +1775,209 @@ __global__ void __launch_bounds__(256) wgrad_bf16_kernel(const GemmWgrad p) {
         }
 }
 
+// ------------------------------------------------------------------------------------------------
+// backward-weight of a 3x3 / stride 1 / padding 1 layer in bf16 with the activations staged once for all nine taps.
+// wgrad_bf16_kernel gathers the im2col matrix: every activation pixel is fetched nine times, once per tap, and the 64-wide
+// tiles of the layers with 64 filters feed few MFMAs per byte.  Here a block owns 64 filters x 64 channels x all nine taps.
+//
+// Pixels are numbered as positions of a padded image: virtual row v = image * (H + 1) + h (row H of every image is an empty
+// row: the lower halo of one image and the upper halo of the next), W + 2 columns (column 0 and W + 1 are halo), position
+// = v * (W + 2) + column.  With dY and X both zero on the halo,
+//     dW[k][r][s][c] = sum over positions of dY[position][k] * X[position + (r - 1) * (W + 2) + (s - 1)][c],
+// so a tap is a displacement of the X operand by a fixed number of positions.  The reduction runs over all positions (the
+// 2 / (W + 2) of them that are halo cost MFMAs on zeros), cut into `splits` ranges of m_per_split positions.
+//
+// LDS: dY of the current 32 positions (two buffers) and a ring of X positions reaching 32 * L >= W + 3 positions behind
+// and ahead of them, (2 L + 2) chunks of 32; both as [position][64 channels] with the pitch of wgrad_bf16_kernel, read with
+// the transposing LDS read.  A fragment's 16 positions start at any ring row, so rows 0..15 are mirrored behind the last
+// row and a read never wraps inside a fragment: its start row is scalar arithmetic.  Halo positions are loaded as zeros
+// (buffer loads, the offset of an invalid lane points past the buffer).  Positions are tracked on the scalar unit: a wave
+// loads eight consecutive positions, so column, image row and image of the first are wave-uniform and a lane that runs past
+// the end of the row (at most once: W + 2 >= 8) takes the next row's values.
+//
+// Pipeline: a step is 18 items (two halves of 16 positions x nine taps), one MFMA each; the X fragment of item g + 5 is
+// read before the MFMA of item g (six register sets; 18 % 6 == 0); the LDS stores of the next step and the barrier sit five
+// items before the end of the step, so the first reads of the next step run under the last MFMAs of this one; global loads
+// are two steps ahead and the barrier waits for LDS only.
+// ------------------------------------------------------------------------------------------------
+constexpr int kWsPitch = 96;          // elements between positions in LDS: 128 bytes of data, 64 of padding
+constexpr int kWsMaxL = 3;            // W + 3 <= 96
+
+__global__ void __launch_bounds__(256, 2) wgrad3x3_slab_kernel(const GemmWgrad p) {
+    extern __shared__ __attribute__((aligned(16))) uint16_t ws_smem[];
+    const int H = p.H, W = p.W, Wp = W + 2, H1 = H + 1;
+    const int L = (W + 3 + 31) / 32, RING = (2 * L + 2) * 32;
+    uint16_t* dys = ws_smem;                           // [2][32][kWsPitch]
+    uint16_t* xs = ws_smem + 2 * 32 * kWsPitch;        // [RING + 16][kWsPitch]: rows RING.. mirror rows 0..15
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int kh = wave >> 1, ch = wave & 1;
+    const int tiles_c = p.C / 64, tiles_ = (p.K / 64) * tiles_c;
+    const int work = xcd_tile(blockIdx.x, gridDim.x);  // split-major: the tiles of a split share its rows of dY and X in one L2
+    const int z = work / tiles_, tile = work - z * tiles_;
+    const int k0 = (tile / tiles_c) * 64, c0 = (tile % tiles_c) * 64;
+    const int imgs = p.M / (H * W);
+    const long long total = (long long)imgs * H1 * Wp;
+    const long long pos_begin = (long long)z * p.m_per_split;
+    int nsteps = 0;
+    if (pos_begin < total) {
+        const long long left = total - pos_begin;
+        nsteps = (int)((left < p.m_per_split ? left : (long long)p.m_per_split) + 31) / 32;
+    }
+
+    const int po = tid >> 3, cq = tid & 7, j8 = lane >> 3;
+    struct Track { int col, h, img, rowbase; };       // of a wave's first position; rowbase: first pixel of the (most recent) image row
+    const int per_img = H1 * Wp;
+    const int eimg = (32 * L + per_img - 1) / per_img;            // whole virtual images that make every position non-negative
+    auto init = [&](long long pos) {
+        const long long q = pos + (long long)eimg * per_img;
+        const long long v = q / Wp;
+        Track t;
+        t.col = (int)(q - v * Wp);
+        const long long im = v / H1;
+        t.h = (int)(v - im * H1);
+        t.img = (int)im - eimg;
+        t.rowbase = (t.img * H + (t.h < H ? t.h : H - 1)) * W;
+        return t;
+    };
+    auto advance = [&](Track& t) {
+        t.col += 32;
+        while (t.col >= Wp) {
+            t.col -= Wp;
+            if (++t.h == H1) {
+                t.h = 0;
+                ++t.img;
+            }
+            if (t.h != H) t.rowbase += W;
+        }
+    };
+    auto offset_of = [&](const Track& t, int pixel_bytes) {
+        int h2 = t.h + 1, img2 = t.img, rb2 = t.rowbase;          // the row after
+        if (h2 == H1) {
+            h2 = 0;
+            ++img2;
+        }
+        if (h2 != H) rb2 += W;
+        const bool v1 = ((unsigned)t.img < (unsigned)imgs) & (t.h < H), v2 = ((unsigned)img2 < (unsigned)imgs) & (h2 < H);
+        int c = t.col + j8;
+        const bool wr = c >= Wp;
+        c = wr ? c - Wp : c;
+        const bool ok = (wr ? v2 : v1) & (c >= 1) & (c <= W);
+        const int pix = (wr ? rb2 : t.rowbase) + c - 1;
+        return ok ? (unsigned)pix * (unsigned)pixel_bytes + (unsigned)cq * 16u : 0x80000000u;
+    };
+    Track ta = init(pos_begin + 8 * wave), tb = init(pos_begin - 32 * L + 8 * wave);
+    const uint16_t* DY = static_cast<const uint16_t*>(p.dy) + k0;
+    const uint16_t* X = static_cast<const uint16_t*>(p.x) + c0;
+    const __amdgpu_buffer_rsrc_t y_rsrc =
+        __builtin_amdgcn_make_buffer_rsrc((void*)DY, 0, (int)((long long)p.M * p.K * 2 - k0 * 2), 0x00020000);
+    const __amdgpu_buffer_rsrc_t x_rsrc =
+        __builtin_amdgcn_make_buffer_rsrc((void*)X, 0, (int)((long long)p.M * p.C * 2 - c0 * 2), 0x00020000);
+    auto load_y = [&]() {
+        const unsigned off = offset_of(ta, p.K * 2);
+        advance(ta);
+        return __builtin_amdgcn_raw_buffer_load_b128(y_rsrc, off, 0, 0);
+    };
+    auto load_x = [&]() {
+        const unsigned off = offset_of(tb, p.C * 2);
+        advance(tb);
+        return __builtin_amdgcn_raw_buffer_load_b128(x_rsrc, off, 0, 0);
+    };
+    int xslot = 0;                                                  // ring row of the next chunk of X (uniform)
+    auto store_x = [&](const u32x4& v) {
+        *reinterpret_cast<u32x4*>(&xs[(xslot + po) * kWsPitch + cq * 8]) = v;
+        if (xslot == 0 && po < 16) *reinterpret_cast<u32x4*>(&xs[(RING + po) * kWsPitch + cq * 8]) = v;
+        xslot += 32;
+        if (xslot == RING) xslot = 0;
+    };
+    auto store_y = [&](int buf, const u32x4& v) { *reinterpret_cast<u32x4*>(&dys[(buf * 32 + po) * kWsPitch + cq * 8]) = v; };
+
+    f32x16 acc[9];
+#pragma unroll
+    for (int t = 0; t < 9; ++t)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[t][v] = 0.f;
+
+    typedef short s16x4 __attribute__((ext_vector_type(4)));
+    typedef short s16x8 __attribute__((ext_vector_type(8)));
+    const int tr_row = 8 * (lane >> 5) + ((lane & 15) >> 2), tr_col = 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
+    const int lane_a = tr_row * kWsPitch + kh * 32 + tr_col, lane_b = tr_row * kWsPitch + ch * 32 + tr_col;
+    auto frag = [&](const uint16_t* q) __attribute__((always_inline)) {     // see wgrad_bf16_kernel
+        const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(uintptr_t)q);
+        const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(uintptr_t)(q + 4 * kWsPitch));
+        const s16x8 v = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+        return __builtin_bit_cast(bf16x8, v);
+    };
+
+    constexpr int PD = 5, NB = 6;
+    if (nsteps > 0) {
+        for (int j = 0; j < 2 * L + 1; ++j) store_x(load_x());
+        store_y(0, load_y());
+        u32x4 ra[2], rb[2];                                         // slot s % 2: operands of step s, loaded two steps before
+#pragma unroll
+        for (int d = 1; d <= 2; ++d)
+            if (d < nsteps) {
+                ra[d % 2] = load_y();
+                rb[d % 2] = load_x();
+            }
+        lds_barrier();
+        int base = 32 * L;                                          // ring row of the current step's first position
+        bf16x8 a0, a1, bq[NB];
+        auto read_item = [&](int i, int rbase, int buf) __attribute__((always_inline)) {   // item i: half i / 9, tap i % 9
+            const int t16 = i / 9, tap = i % 9;
+            if (tap == 0) {
+                const bf16x8 a = frag(dys + buf * 32 * kWsPitch + 16 * t16 * kWsPitch + lane_a);
+                if (t16 == 0) a0 = a; else a1 = a;
+            }
+            int u = rbase + 16 * t16 + (tap / 3 - 1) * Wp + (tap % 3 - 1);
+            u = u < 0 ? u + RING : (u >= RING ? u - RING : u);
+            bq[i % NB] = frag(xs + u * kWsPitch + lane_b);
+        };
+#pragma unroll
+        for (int i = 0; i < PD; ++i) read_item(i, base, 0);
+        auto step_fn = [&](int step, int par) __attribute__((always_inline)) {   // par = step & 1 (compile time)
+            int nbase = base + 32;
+            if (nbase == RING) nbase = 0;
+#pragma unroll
+            for (int i = 0; i < 18; ++i) {
+                if (i == 18 - PD) {
+                    if (step + 1 < nsteps) {
+                        store_y(par ^ 1, ra[par ^ 1]);
+                        store_x(rb[par ^ 1]);
+                        if (step + 3 < nsteps) {
+                            ra[par ^ 1] = load_y();
+                            rb[par ^ 1] = load_x();
+                        }
+                    }
+                    lds_barrier();
+                }
+                if (i + PD < 18) read_item(i + PD, base, par);
+                else read_item(i + PD - 18, nbase, par ^ 1);       // the next step's first items (in bounds; unused after the last step)
+                acc[i % 9] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(i < 9 ? a0 : a1, bq[i % NB], acc[i % 9], 0, 0, 0);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            base = nbase;
+        };
+        int step = 0;
+        for (; step + 2 <= nsteps; step += 2) {
+            step_fn(step, 0);
+            step_fn(step + 1, 1);
+        }
+        if (step < nsteps) step_fn(step, 0);
+    }
+
+    float* __restrict__ D = p.d + (long long)z * p.K * p.J;
+#pragma unroll
+    for (int tap = 0; tap < 9; ++tap)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int row = k0 + kh * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+            const int col = tap * p.C + c0 + ch * 32 + (lane & 31);
+            D[(long long)row * p.J + col] = acc[tap][v];
+        }
+}
+
 inline bool aligned16(const void* ptr) { return (reinterpret_cast<uintptr_t>(ptr) & 15) == 0; }
 
 template <int BM, int BN, int BK, int VEC>
@@ -2160,6 +2363,47 @@ int lc_wgrad_splits(int M, int K, int J, bool bf16) {
     return (int)want;
 }
 
+// Whether wgrad3x3_slab_kernel takes a layer (a fixed function of the shape: the plan's workspace depends on it).
+bool lc_wgrad_slab_ok(int imgs, int H, int W, int C, int K, int R, int S, int sh, int sw, int ph, int pw, int P, int Q, bool bf16) {
+    if (getenv("LARSCONV_NO_WGRAD_SLAB")) return false;                    // comparison runs
+    if (!bf16 || R != 3 || S != 3 || sh != 1 || sw != 1 || ph != 1 || pw != 1 || P != H || Q != W) return false;
+    if (C % 64 != 0 || K % 64 != 0 || W < 6 || (W + 3 + 31) / 32 > kWsMaxL) return false;
+    // narrow images spend too many MFMAs on halo positions (2 of every W + 2) and the 128-wide tiles of
+    // wgrad_bf16_kernel are as fast from 14 x 14 down; tests lower the threshold to send small shapes here
+    const char* e = getenv("LARSCONV_WGRAD_SLAB_MIN_W");
+    if (W < (e ? atoi(e) : 24)) return false;
+    const long long pixels = (long long)imgs * H * W, positions = (long long)imgs * (H + 1) * (W + 2);
+    return pixels * (C > K ? C : K) * 2 < 0x7fff0000LL && positions < 0x7ff00000LL;
+}
+
+// Splits of its reduction: two blocks per compute unit in one round, at least 256 positions each.
+int lc_wgrad_slab_splits(int imgs, int H, int W, int C, int K, int* pos_per_split) {
+    const long long tiles = (long long)(K / 64) * (C / 64), positions = (long long)imgs * (H + 1) * (W + 2);
+    long long want = 2LL * device_cu_count() / tiles;
+    const long long most = (positions + 255) / 256;
+    if (want > most) want = most;
+    if (want < 1) want = 1;
+    if (want > 8192) want = 8192;
+    *pos_per_split = (int)(((positions + want - 1) / want + 31) / 32 * 32);
+    return (int)want;
+}
+
+static lc_status launch_wgrad_slab(const GemmWgrad& p, hipStream_t stream) {
+    constexpr size_t most = (size_t)(2 * 32 + (2 * kWsMaxL + 2) * 32 + 16) * kWsPitch * 2;
+    static bool once = [] {
+        return hipFuncSetAttribute(reinterpret_cast<const void*>(wgrad3x3_slab_kernel), hipFuncAttributeMaxDynamicSharedMemorySize, (int)most) ==
+               hipSuccess;
+    }();
+    if (!once) return LC_ERR_LAUNCH;
+    if (!aligned16(p.dy) || !aligned16(p.x) || p.m_per_split % 32 != 0) return LC_ERR_ALIGN;
+    const int L = (p.W + 3 + 31) / 32;
+    const size_t lds = (size_t)(2 * 32 + (2 * L + 2) * 32 + 16) * kWsPitch * 2;
+    const long long tiles = (long long)(p.K / 64) * (p.C / 64);
+    if (L > kWsMaxL || tiles * p.splits > 0x7fffffffLL) return LC_ERR_UNSUPPORTED;
+    hipLaunchKernelGGL(wgrad3x3_slab_kernel, dim3((unsigned)(tiles * p.splits)), dim3(256), lds, stream, p);
+    return lc_end_call();
+}
+
 template <int BM, int BN>
 static lc_status launch_wgrad_bf16(const GemmWgrad& p, hipStream_t stream) {
     const long long tiles = (long long)((p.K + BM - 1) / BM) * ((p.J + BN - 1) / BN);
@@ -2193,6 +2437,7 @@ static lc_status launch_wgrad_ut(const GemmWgrad& p, hipStream_t stream) {
 
 template <bool BF16>
 static lc_status dispatch_wgrad(const GemmWgrad& p, hipStream_t stream) {
+    if (p.slab) return BF16 ? launch_wgrad_slab(p, stream) : LC_ERR_UNSUPPORTED;   // (m_per_split counts positions: no other kernel can take it)
     if (wgrad_ut_ok(p) && !(BF16 && getenv("LARSCONV_WGRAD_WIDEN"))) {
         // only the 128 x 128 tiling: with narrower tiles a step has too few MFMAs to hide the scalar work and the
         // narrower loads, and the kernels below measure faster

@@ -109,6 +109,9 @@ struct GemmWgrad {
     int sh, sw, ph, pw;
     int splits, m_per_split;
     int bf16;           // dy and x are bf16 (widened on the fly; the sums and d stay fp32)
+    int slab;           // 3x3 stride-1 pad-1 bf16 layer for wgrad3x3_slab_kernel: m_per_split counts padded positions
 };
 lc_status lc_launch_wgrad_f32(const GemmWgrad& p, hipStream_t stream);
 int lc_wgrad_splits(int M, int K, int J, bool bf16);   // fixed function of the shape (determinism)
+bool lc_wgrad_slab_ok(int imgs, int H, int W, int C, int K, int R, int S, int sh, int sw, int ph, int pw, int P, int Q, bool bf16);
+int lc_wgrad_slab_splits(int imgs, int H, int W, int C, int K, int* pos_per_split);
