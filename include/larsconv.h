@@ -301,8 +301,9 @@ lc_status batchnorm_bwd_presummed_t(lc_dtype dtype, const void* x, const void* d
  * "ImageNet training with ResNet-50"), whose first step reads the convolution's whole output again to sum it.
  * conv2d_fwd_stats is conv2d_fwd that also hands those sums over: stats receives
  * conv2d_fwd_stats_count(desc) * k * 2 floats, [piece][channel][2] = the sum and the sum of squares, over one
- * piece of 64 or 128 of the output's rows (n, p, q), of the values written to y (as written: after rounding where y is
- * bf16).  They come out of the output tile's registers: 1/16 (fp32) or 1/8 (bf16) of y's bytes instead of a pass over y.
+ * piece of the output's pixels, of the values written to y (as written: after rounding where y is bf16).  Every pixel
+ * (n, p, q) lies in exactly one piece: 64 or 128 consecutive pixels in (n, p, q) order, or -- ResNet's first layer in
+ * fp32, which has a kernel of its own -- a block of 4 x 16 pixels of one image.  They come out of the output tile's registers: 1/16 (fp32) or 1/8 (bf16) of y's bytes instead of a pass over y.
  * The count is 0 -- and conv2d_fwd_stats returns LC_ERR_UNSUPPORTED -- for layers whose plan has no such epilogue: NCHW,
  * groups > 1, and operands the MFMA kernels do not take (fp32 tensors off a 16-byte boundary, channel counts not a
  * multiple of 4 resp. 8); callers then use conv2d_fwd and batchnorm_fwd_t.  stats: DEVICE, 8-byte aligned, written in full.

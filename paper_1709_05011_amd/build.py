@@ -10,7 +10,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "liblarsconv.so")
 OBJ = os.path.join(HERE, "_build")
-SOURCES = ["conv_api.hip", "conv_igemm.hip", "layout.hip", "lars.hip", "glue.hip", "glue_bf16.hip", "batchnorm.hip"]
+SOURCES = ["conv_api.hip", "conv_igemm.hip", "conv_stem.hip", "layout.hip", "lars.hip", "glue.hip", "glue_bf16.hip", "batchnorm.hip"]
 # packed-fp32 instructions are switched off for device code (scalar fp32 ops are generated instead)
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++20", "-fPIC", "-Wall", "-Wno-unused-function",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]

@@ -536,6 +536,12 @@ extern "C" size_t conv2d_workspace_bytes(const lc_conv_desc* desc, lc_pass pass)
 
 namespace {
 
+// ResNet's first layer in fp32 and NHWC: the kernel of conv_stem.hip takes it.
+bool stem_direct(const lc_conv_desc* d, const Plan& pl) {
+    return !pl.bf16 && !pl.nchw && d->groups <= 1 &&
+           lc_conv_stem_f32_ok(d->n, d->c, d->h, d->w, d->k, d->r, d->s, d->stride_h, d->stride_w, d->pad_h, d->pad_w, pl.P, pl.Q);
+}
+
 // The forward pass; `stats` (may be null) receives the column sums of the result from the GEMM's epilogue (see
 // conv2d_fwd_stats) -- only for plans whose GEMM writes y itself, which fwd_stats_tiles() reports.
 lc_status fwd_impl(const lc_conv_desc* d, const void* x, const void* w, void* y, float* stats, void* workspace,
@@ -559,6 +565,12 @@ lc_status fwd_impl(const lc_conv_desc* d, const void* x, const void* w, void* y,
         st = lc_end_call();
         if (st != LC_OK) return st;
         return fwd_impl(&pl.inner, u, wu, y, stats, pl.s_ws_bytes ? at(workspace, pl.s_ws) : nullptr, pl.s_ws_bytes, hip_stream);
+    }
+
+    if (stem_direct(d, pl)) {
+        const StemConv sc = {static_cast<const float*>(x), static_cast<const float*>(w), static_cast<float*>(y), stats,
+                             d->n, d->h, d->w, pl.P, pl.Q};
+        return lc_launch_conv_stem_f32(sc, stream);
     }
 
     const void* xs = x;
@@ -600,6 +612,7 @@ size_t fwd_stats_tiles(const lc_conv_desc* d) {
     Plan pl;
     if (make_plan(d, LC_PASS_FWD, &pl) != LC_OK || pl.nchw) return 0;
     if (pl.blocks) return fwd_stats_tiles(&pl.inner);
+    if (stem_direct(d, pl)) return lc_conv_stem_f32_stats_pieces(d->n, pl.P, pl.Q);
     GemmConv g = gemm_fwd(d, pl.P, pl.Q, pl.cpad);
     return lc_conv_gemm_stats_tiles(g);
 }

@@ -1,0 +1,182 @@
+// Forward pass of ResNet's first layer in fp32 (7x7 window, stride 2, padding 3, 3 -> 64 channels, NHWC) from an input slab in
+// LDS (the paper's ResNet-50, "ImageNet training with ResNet-50"; the layer is 2 % of the network's multiplications and was
+// 4 % of the step's time on the general kernel).
+//
+// The general kernel pads the three channels to four (a pass over the input and 25 % more multiplications) and gathers every
+// window element with per-lane address arithmetic.  Here a block owns 16 x 16 output pixels: their 37 x 37 input pixels
+// (37 rows of 111 contiguous floats in NHWC) go to LDS once, the whole filter sits in LDS for the life of the block, and an
+// MFMA operand is read at `lane's pixel + (r, s, c)` where the second term is a compile-time constant: no address
+// arithmetic in the loop at all.  A filter row's 21 values are padded to 22 so that the two k of an MFMA (32x32x2) never
+// straddle rows: 154 k instead of 147 (the general kernel ran 196).  The slab pitch of 112 floats makes the A reads of a wave
+// (32 pixels: 2 rows x 16 columns, 6 floats apart, two k) fall on 64 distinct banks; the filter is stored [k][64] with the
+// two 32-column halves of odd rows swapped, for the same reason.  Blocks are persistent (filter loaded once), the next
+// tile's slab is fetched into registers under the MFMAs, operands are read one k pair ahead.  A wave owns 4 rows x 16 columns
+// of pixels x 64 filters; the batch-norm statistics of conv2d_fwd_stats come out of its accumulators, one piece per wave.
+#include <hip/hip_runtime.h>
+
+#include <cstdint>
+#include <cstdlib>
+
+#include "../../include/larsconv.h"
+#include "internal.h"
+
+namespace {
+
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+__device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" : : : "memory"); }
+
+namespace stem {
+constexpr int R = 7, S = 7, C = 3, N = 64, ST = 2, PAD = 3;
+constexpr int TH = 16, TW = 16;                    // output pixels per tile
+constexpr int SR = (TH - 1) * ST + R;              // 37 slab rows
+constexpr int SWF = ((TW - 1) * ST + S) * C;       // 111 floats of a slab row
+constexpr int SP = 112;                            // slab pitch in floats (element 111 stays zero: the 22nd tap of a window's last pixel)
+constexpr int T2 = (S * C + 1) / 2 * 2;            // 22: a filter row's 21 values and a zero, so that a k pair never straddles rows
+constexpr int KP = R * T2;                         // 154
+constexpr int SLAB = SR * SP;                      // 4144 floats
+constexpr int LD = (SLAB + 255) / 256;             // 17 loads per thread
+}  // namespace stem
+
+__global__ void __launch_bounds__(256, 2) conv_stem_f32_kernel(const StemConv p) {
+    using namespace stem;
+    extern __shared__ __attribute__((aligned(16))) float st_smem[];
+    float* Bs = st_smem;                 // [KP][64], the two 32-column halves of odd rows swapped
+    float* slab = st_smem + KP * N;      // [2][SLAB]
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int half = lane >> 5, m = lane & 31;
+    const int tiles_x = p.Q / TW, tiles_y = p.P / TH, tiles = p.imgs * tiles_y * tiles_x;
+
+    for (int idx = tid; idx < N * R * S * C; idx += 256) {          // coalesced reads of the filter, scattered into [k][n]
+        const int n = idx / (R * S * C), rem = idx - n * (R * S * C), r = rem / (S * C), t = rem - r * (S * C);
+        const int k = r * T2 + t;
+        Bs[k * N + (n ^ ((k & 1) << 5))] = p.w[idx];
+    }
+    if (T2 > S * C)
+        for (int idx = tid; idx < R * N; idx += 256) {              // the zero that completes each filter row's last k pair
+            const int r = idx / N, n = idx - r * N, k = r * T2 + T2 - 1;
+            Bs[k * N + (n ^ ((k & 1) << 5))] = 0.f;
+        }
+    const int a_lane = ((4 * wave + (m >> 4)) * ST) * SP + (m & 15) * ST * C + half;
+    int b_lane[2];
+#pragma unroll
+    for (int j = 0; j < 2; ++j) b_lane[j] = half * N + ((m + 32 * j) ^ (half << 5));
+
+    const __amdgpu_buffer_rsrc_t x_rsrc = __builtin_amdgcn_make_buffer_rsrc((void*)p.x, 0, (int)((long long)p.imgs * p.H * p.W * C * 4), 0x00020000);
+    float g[LD];
+    auto gload = [&](int tile) {
+        const int tx = tile % tiles_x, t2 = tile / tiles_x, ty = t2 % tiles_y, img = t2 / tiles_y;
+        const int h0 = ty * TH * ST - PAD, w0f = (tx * TW * ST - PAD) * C;
+        const int base = (img * p.H + h0) * p.W * C + w0f;              // floats; may be negative: only valid lanes use it
+#pragma unroll
+        for (int l = 0; l < LD; ++l) {
+            const int e = tid + 256 * l, i = e / SP, f = e - i * SP;
+            const bool ok = (e < SLAB) & (f < SWF) & ((unsigned)(h0 + i) < (unsigned)p.H) & ((unsigned)(w0f + f) < (unsigned)(p.W * C));
+            const unsigned off = ok ? (unsigned)(base + i * p.W * C + f) * 4u : 0x80000000u;
+            g[l] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(x_rsrc, off, 0, 0));
+        }
+    };
+    auto sstore = [&](int buf) {
+#pragma unroll
+        for (int l = 0; l < LD; ++l) {
+            const int e = tid + 256 * l;
+            if (e < SLAB) slab[buf * SLAB + e] = g[l];
+        }
+    };
+
+    int tile = blockIdx.x;
+    if (tile < tiles) gload(tile);
+    int buf = 0;
+    for (; tile < tiles; tile += gridDim.x) {
+        sstore(buf);
+        lds_barrier();
+        if (tile + (int)gridDim.x < tiles) gload(tile + gridDim.x);
+        f32x16 acc[2][2];
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int j = 0; j < 2; ++j)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+        const float* sa = slab + buf * SLAB + a_lane;
+        float a[2][2], b[2][2];                                        // [slot][tile]: operands of k pair kp in slot kp & 1
+        auto read_pair = [&](int kp, int slot) __attribute__((always_inline)) {
+            const int r = kp / (T2 / 2), t = 2 * (kp % (T2 / 2));
+#pragma unroll
+            for (int i = 0; i < 2; ++i) a[slot][i] = sa[(2 * i * ST + r) * SP + t];
+#pragma unroll
+            for (int j = 0; j < 2; ++j) b[slot][j] = Bs[kp * 2 * N + b_lane[j]];
+        };
+        read_pair(0, 0);
+#pragma unroll
+        for (int kp = 0; kp < KP / 2; ++kp) {
+            if (kp + 1 < KP / 2) read_pair(kp + 1, (kp + 1) & 1);     // one pair (four MFMAs) ahead
+#pragma unroll
+            for (int i = 0; i < 2; ++i)
+#pragma unroll
+                for (int j = 0; j < 2; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[kp & 1][i], b[kp & 1][j], acc[i][j], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        // the wave's 4 rows x 16 columns of output pixels, 64 channels
+        const int tx = tile % tiles_x, t2 = tile / tiles_x, ty = t2 % tiles_y, img = t2 / tiles_y;
+        float* yo = p.y + (((long long)img * p.P + ty * TH + 4 * wave) * p.Q + tx * TW) * N + 4 * half * N + m;
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int row = 2 * i + (v >> 3), col = 8 * ((v >> 2) & 1) + (v & 3);
+#pragma unroll
+                for (int j = 0; j < 2; ++j) yo[(row * p.Q + col) * N + 32 * j] = acc[i][j][v];
+            }
+        if (p.stats) {
+            typedef float flt2 __attribute__((ext_vector_type(2)));
+            flt2* st = reinterpret_cast<flt2*>(p.stats) + ((size_t)tile * 4 + wave) * N;
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+                float sum = 0.f, sq = 0.f;
+#pragma unroll
+                for (int i = 0; i < 2; ++i)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) {
+                        sum += acc[i][j][v];
+                        sq = fmaf(acc[i][j][v], acc[i][j][v], sq);
+                    }
+                sum += __shfl_xor(sum, 32);
+                sq += __shfl_xor(sq, 32);
+                if (half == 0) st[32 * j + m] = flt2{sum, sq};
+            }
+        }
+        buf ^= 1;
+    }
+}
+
+}  // namespace
+
+bool lc_conv_stem_f32_ok(int imgs, int c, int h, int w, int k, int r, int s, int sh, int sw, int ph, int pw, int P, int Q) {
+    using namespace stem;
+    if (getenv("LARSCONV_NO_STEM_DIRECT")) return false;                   // comparison runs
+    if (c != C || k != N || r != R || s != S || sh != ST || sw != ST || ph != PAD || pw != PAD) return false;
+    if (P % TH != 0 || Q % TW != 0) return false;
+    return (long long)imgs * h * w * C * 4 < 0x7fff0000LL && (long long)imgs * (P / TH) * (Q / TW) < 0x7fffffffLL / 4;
+}
+
+size_t lc_conv_stem_f32_stats_pieces(int imgs, int P, int Q) { return (size_t)imgs * (P / stem::TH) * (Q / stem::TW) * 4; }
+
+lc_status lc_launch_conv_stem_f32(const StemConv& p, hipStream_t stream) {
+    using namespace stem;
+    constexpr size_t lds = (size_t)(KP * N + 2 * SLAB) * 4;
+    static bool once = [] {
+        return hipFuncSetAttribute(reinterpret_cast<const void*>(conv_stem_f32_kernel), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) ==
+               hipSuccess;
+    }();
+    if (!once) return LC_ERR_LAUNCH;
+    if (p.P % TH != 0 || p.Q % TW != 0) return LC_ERR_UNSUPPORTED;
+    int dev = 0, cus = 0;
+    if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0) cus = 256;
+    const long long tiles = (long long)p.imgs * (p.P / TH) * (p.Q / TW);
+    const long long blocks = tiles < 2LL * cus ? tiles : 2LL * cus;        // two resident blocks per compute unit, each walks its tiles
+    hipLaunchKernelGGL(conv_stem_f32_kernel, dim3((unsigned)blocks), dim3(256), lds, stream, p);
+    return lc_end_call();
+}

@@ -98,6 +98,18 @@ bool lc_conv_gemm_bf16_native(const GemmConv& p);   // can the bf16 MFMA kernel 
 bool lc_conv_gemm_scatter_ok(const GemmConv& p);    // can the main kernel's scatter epilogue take this problem?
 size_t lc_conv_gemm_workspace(const GemmConv& p);   // bytes `partial` must hold for this problem (0 = none)
 
+// ResNet's first layer in fp32 (conv_stem.hip): 7x7, stride 2, padding 3, 3 -> 64 channels, NHWC, P and Q multiples of 16.
+struct StemConv {
+    const float* x;     // [imgs][H][W][3]
+    const float* w;     // [64][7][7][3]
+    float* y;           // [imgs][P][Q][64]
+    float* stats;       // [pieces][64][2] (sum, sum of squares per piece of 64 pixels) or null
+    int imgs, H, W, P, Q;
+};
+bool lc_conv_stem_f32_ok(int imgs, int c, int h, int w, int k, int r, int s, int sh, int sw, int ph, int pw, int P, int Q);
+size_t lc_conv_stem_f32_stats_pieces(int imgs, int P, int Q);
+lc_status lc_launch_conv_stem_f32(const StemConv& p, hipStream_t stream);
+
 // Filter gradient: D[k][j] = sum_m dY[m][k] * Xg(m, j), m = (img, p, q), j = (r, s, c); the reduction
 // over m is cut into `splits` ranges, split z writing to d + z * K * J.
 struct GemmWgrad {
