@@ -31,6 +31,7 @@ struct Plan {
     size_t sk = 0, sk_bytes = 0;     // partial tiles of the stream-K blocks (forward, backward-data)
     int splits = 1, m_per_split = 0;
     bool wgrad_direct = true;
+    bool stem_wgrad = false;         // ResNet's first layer in fp32: the filter-gradient kernel of conv_stem.hip
     bool wgrad_slab = false;         // bf16 3x3 stride-1 pad-1 layer: the kernel that stages the activations once for all taps
     // bf16 problems the bf16 MFMA kernel does not take (backward-data with k not a multiple of 8, or a strided
     // window other than 1x1): operands are widened to fp32 copies, the fp32 pass runs on them, the result is
@@ -274,6 +275,12 @@ bool plan_blocks(const lc_conv_desc* d, int P, int Q, Plan* pl) {
     return true;
 }
 
+// ResNet's first layer in fp32 and NHWC: the kernels of conv_stem.hip take it (forward and backward-weight).
+bool stem_direct(const lc_conv_desc* d, const Plan& pl) {
+    return !pl.bf16 && !pl.nchw && d->groups <= 1 &&
+           lc_conv_stem_f32_ok(d->n, d->c, d->h, d->w, d->k, d->r, d->s, d->stride_h, d->stride_w, d->pad_h, d->pad_w, pl.P, pl.Q);
+}
+
 lc_status make_plan(const lc_conv_desc* d, lc_pass pass, Plan* pl) {
     const lc_status st = check_desc(d, &pl->P, &pl->Q);
     if (st != LC_OK) return st;
@@ -297,6 +304,10 @@ lc_status make_plan(const lc_conv_desc* d, lc_pass pass, Plan* pl) {
     const size_t nx = (size_t)d->n * d->h * d->w * d->c, ny = (size_t)d->n * pl->P * pl->Q * d->k;
     const size_t nw = (size_t)d->k * d->r * d->s * d->c;
     pl->cpad = pl->bf16 ? (d->c + 7) & ~7 : (d->c + 3) & ~3;
+    if (pass == LC_PASS_BWD_WEIGHT && stem_direct(d, *pl)) {
+        pl->stem_wgrad = true;
+        pl->cpad = d->c;                         // its kernel reads the three channels as they are
+    }
     const bool pad = pl->cpad != d->c;
     Regions rg;
     pl->phases = pass == LC_PASS_BWD_DATA && phases_ok(d, pl->P, pl->Q);
@@ -355,13 +366,16 @@ lc_status make_plan(const lc_conv_desc* d, lc_pass pass, Plan* pl) {
         const int M = d->n * pl->P * pl->Q, J = d->r * d->s * pl->cpad;
         pl->wgrad_slab = lc_wgrad_slab_ok(d->n, d->h, d->w, pl->cpad, d->k, d->r, d->s, d->stride_h, d->stride_w, d->pad_h, d->pad_w,
                                           pl->P, pl->Q, pl->bf16);
-        if (pl->wgrad_slab) {
+        if (pl->stem_wgrad) {
+            pl->splits = lc_conv_stem_blocks(d->n, pl->P, pl->Q);      // one partial per resident block
+            pl->m_per_split = 0;
+        } else if (pl->wgrad_slab) {
             pl->splits = lc_wgrad_slab_splits(d->n, d->h, d->w, pl->cpad, d->k, &pl->m_per_split);
         } else {
             pl->splits = lc_wgrad_splits(M, d->k, J, pl->bf16);
             pl->m_per_split = (M + pl->splits - 1) / pl->splits;
         }
-        pl->wgrad_direct = pl->splits == 1 && !pad;
+        pl->wgrad_direct = pl->splits == 1 && !pad && !pl->stem_wgrad;
         if (!pl->wgrad_direct) pl->part = rg.take((size_t)pl->splits * d->k * J * sizeof(float));
     }
     pl->total = rg.off;
@@ -535,12 +549,6 @@ extern "C" size_t conv2d_workspace_bytes(const lc_conv_desc* desc, lc_pass pass)
 }
 
 namespace {
-
-// ResNet's first layer in fp32 and NHWC: the kernel of conv_stem.hip takes it.
-bool stem_direct(const lc_conv_desc* d, const Plan& pl) {
-    return !pl.bf16 && !pl.nchw && d->groups <= 1 &&
-           lc_conv_stem_f32_ok(d->n, d->c, d->h, d->w, d->k, d->r, d->s, d->stride_h, d->stride_w, d->pad_h, d->pad_w, pl.P, pl.Q);
-}
 
 // The forward pass; `stats` (may be null) receives the column sums of the result from the GEMM's epilogue (see
 // conv2d_fwd_stats) -- only for plans whose GEMM writes y itself, which fwd_stats_tiles() reports.
@@ -750,6 +758,17 @@ lc_status bwd_weight_impl(const lc_conv_desc* d, const void* x, const void* dy, 
         if (st != LC_OK) return st;
         lc_stem_filter_grad(dwu, dw, d->k, d->r, d->s, d->c, pl.RB, pl.CU, pl.eh, pl.ew, stream);
         if (sq) lc_sq_partials(dw, dw_numel, sq, stream);
+        return lc_end_call();
+    }
+
+    if (pl.stem_wgrad) {
+        float* part = reinterpret_cast<float*>(at(workspace, pl.part));
+        const StemWgrad sw = {static_cast<const float*>(x), static_cast<const float*>(dy), part, d->n, d->h, d->w, pl.P, pl.Q};
+        st = lc_launch_conv_stem_wgrad_f32(sw, pl.splits, stream);
+        if (st != LC_OK) return st;
+        const bool fused_sq = sq && wgrad_sq_fused(d, pl);
+        lc_reduce_splits(part, dw, pl.splits, (size_t)d->k * d->r * d->s * d->c, d->c, d->c, fused_sq ? sq : nullptr, stream);
+        if (sq && !fused_sq) lc_sq_partials(dw, dw_numel, sq, stream);
         return lc_end_call();
     }
 

@@ -152,6 +152,123 @@ __global__ void __launch_bounds__(256, 2) conv_stem_f32_kernel(const StemConv p)
     }
 }
 
+// The same layer's filter gradient, dW[k][r][s][c] = sum over output pixels of dY[pixel][k] * X[window of the pixel][r][s][c]
+// (the general kernel: channels padded to four, per-lane gathers, 1.09 ms + a padding pass at batch 256).  Same tiles, same
+// slab.  A wave owns 32 of the 64 filters and 8 of the tile's 16 pixel rows and keeps all 5 x 32 columns of its part of dW
+// (147 of them used) in registers for the whole life of the block; per pixel pair it reads dY straight from memory (one
+// value per lane, a row of pairs ahead) and the five X operands from the slab at `lane's (r, s, c) + pixel`, the pixel being
+// a compile-time constant.  When its tiles are done the block adds the two waves of each filter half through LDS and writes
+// one partial [64][147]; the fixed-order sum over the blocks is reduce_splits_kernel's, as for every filter gradient.
+__global__ void __launch_bounds__(256, 2) conv_stem_wgrad_f32_kernel(const StemWgrad p) {
+    using namespace stem;
+    constexpr int J = R * S * C, JT = (J + 31) / 32;          // 147 columns in 5 tiles of 32 (the last 13 columns are not stored)
+    extern __shared__ __attribute__((aligned(16))) float sw_smem[];
+    float* slab = sw_smem;               // [2][SLAB]; the block's final sum over its waves reuses it
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int half = lane >> 5, l = lane & 31;
+    const int kt = wave >> 1, rh = wave & 1;            // the wave's 32 filters and its 8 of the tile's 16 pixel rows
+    const int tiles_x = p.Q / TW, tiles_y = p.P / TH, tiles = p.imgs * tiles_y * tiles_x;
+
+    int b_lane[JT];                      // slab offset of this lane's (r, s, c) for each column tile, plus the wave's rows and the pixel of its half
+#pragma unroll
+    for (int jt = 0; jt < JT; ++jt) {
+        const int j = 32 * jt + l;
+        b_lane[jt] = (j < J ? (j / (S * C)) * SP + j % (S * C) : 0) + ST * C * half + ST * 8 * rh * SP;
+    }
+    const unsigned a_lane = (unsigned)(half * N + 32 * kt + l) * 4u;
+
+    const long long x_img = (long long)p.H * p.W * C, y_img = (long long)p.P * p.Q * N;
+    float g[LD];
+    auto gload = [&](int tile) {
+        const int tx = tile % tiles_x, t2 = tile / tiles_x, ty = t2 % tiles_y, img = t2 / tiles_y;
+        const int h0 = ty * TH * ST - PAD, w0f = (tx * TW * ST - PAD) * C;
+        const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc((void*)(p.x + img * x_img), 0, (int)(x_img * 4), 0x00020000);
+        const int base = h0 * p.W * C + w0f;                            // floats within the image; may be negative: only valid lanes use it
+#pragma unroll
+        for (int i2 = 0; i2 < LD; ++i2) {
+            const int e = tid + 256 * i2, i = e / SP, f = e - i * SP;
+            const bool ok = (e < SLAB) & (f < SWF) & ((unsigned)(h0 + i) < (unsigned)p.H) & ((unsigned)(w0f + f) < (unsigned)(p.W * C));
+            const unsigned off = ok ? (unsigned)(base + i * p.W * C + f) * 4u : 0x80000000u;
+            g[i2] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rsrc, off, 0, 0));
+        }
+    };
+    auto sstore = [&](int buf) {
+#pragma unroll
+        for (int i2 = 0; i2 < LD; ++i2) {
+            const int e = tid + 256 * i2;
+            if (e < SLAB) slab[buf * SLAB + e] = g[i2];
+        }
+    };
+    // dY of one row of the wave's pixels: 8 pixel pairs, one value per lane each
+    float a[2][8];
+    auto yload = [&](int tile, int row, int set) __attribute__((always_inline)) {
+        const int tx = tile % tiles_x, t2 = tile / tiles_x, ty = t2 % tiles_y, img = t2 / tiles_y;
+        const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc((void*)(p.dy + img * y_img), 0, (int)(y_img * 4), 0x00020000);
+        const int soff = (((ty * TH + 8 * rh + row) * p.Q + tx * TW) * N) * 4;
+#pragma unroll
+        for (int c2 = 0; c2 < 8; ++c2)
+            a[set][c2] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rsrc, a_lane, soff + 2 * c2 * N * 4, 0));
+    };
+
+    f32x16 acc[JT];
+#pragma unroll
+    for (int jt = 0; jt < JT; ++jt)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[jt][v] = 0.f;
+
+    int tile = blockIdx.x;
+    if (tile < tiles) {
+        gload(tile);
+        yload(tile, 0, 0);
+    }
+    int buf = 0;
+    for (; tile < tiles; tile += gridDim.x) {
+        sstore(buf);
+        lds_barrier();
+        const int next = tile + (int)gridDim.x;
+        if (next < tiles) gload(next);
+        const float* sb = slab + buf * SLAB;
+#pragma unroll
+        for (int row = 0; row < 8; ++row) {
+            if (row < 7) yload(tile, row + 1, (row + 1) & 1);
+            else if (next < tiles) yload(next, 0, 0);
+            float b[2][JT];
+#pragma unroll
+            for (int jt = 0; jt < JT; ++jt) b[0][jt] = sb[b_lane[jt] + ST * row * SP];
+#pragma unroll
+            for (int c2 = 0; c2 < 8; ++c2) {
+                if (c2 + 1 < 8) {
+#pragma unroll
+                    for (int jt = 0; jt < JT; ++jt) b[(c2 + 1) & 1][jt] = sb[b_lane[jt] + ST * row * SP + ST * C * 2 * (c2 + 1)];
+                }
+#pragma unroll
+                for (int jt = 0; jt < JT; ++jt)
+                    acc[jt] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[row & 1][c2], b[c2 & 1][jt], acc[jt], 0, 0, 0);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+        buf ^= 1;
+    }
+
+    // the block's sum over the two waves that share a filter half, one column tile of dw at a time, written as this block's partial
+    float* part = p.part + (size_t)blockIdx.x * N * J;
+#pragma unroll
+    for (int jt = 0; jt < JT; ++jt) {
+        lds_barrier();                                                    // the slab (or the last round) is no longer read
+#pragma unroll
+        for (int v = 0; v < 16; ++v) slab[(wave * 16 + v) * 64 + lane] = acc[jt][v];
+        lds_barrier();
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const int e = tid + 256 * i, k2 = e >> 10, v = (e >> 6) & 15, ln = e & 63;
+            const float s2 = slab[((2 * k2) * 16 + v) * 64 + ln] + slab[((2 * k2 + 1) * 16 + v) * 64 + ln];
+            const int rowk = k2 * 32 + 8 * (v >> 2) + 4 * (ln >> 5) + (v & 3), col = jt * 32 + (ln & 31);
+            if (col < J) part[rowk * J + col] = s2;
+        }
+    }
+}
+
 }  // namespace
 
 bool lc_conv_stem_f32_ok(int imgs, int c, int h, int w, int k, int r, int s, int sh, int sw, int ph, int pw, int P, int Q) {
@@ -159,10 +276,28 @@ bool lc_conv_stem_f32_ok(int imgs, int c, int h, int w, int k, int r, int s, int
     if (getenv("LARSCONV_NO_STEM_DIRECT")) return false;                   // comparison runs
     if (c != C || k != N || r != R || s != S || sh != ST || sw != ST || ph != PAD || pw != PAD) return false;
     if (P % TH != 0 || Q % TW != 0) return false;
-    return (long long)imgs * h * w * C * 4 < 0x7fff0000LL && (long long)imgs * (P / TH) * (Q / TW) < 0x7fffffffLL / 4;
+    // (buffer descriptors are per image for the filter gradient and over the whole input for the forward pass)
+    return (long long)imgs * h * w * C * 4 < 0x7fff0000LL && (long long)P * Q * N * 4 < 0x7fff0000LL &&
+           (long long)imgs * (P / TH) * (Q / TW) < 0x7fffffffLL / 4;
 }
 
 size_t lc_conv_stem_f32_stats_pieces(int imgs, int P, int Q) { return (size_t)imgs * (P / stem::TH) * (Q / stem::TW) * 4; }
+
+// Resident blocks of both kernels: two per compute unit, each walks its tiles (a fixed function of the shape and the device:
+// the plan sizes the partials of the filter gradient with it).
+int lc_conv_stem_blocks(int imgs, int P, int Q) {
+    int dev = 0, cus = 0;
+    if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0) cus = 256;
+    const long long tiles = (long long)imgs * (P / stem::TH) * (Q / stem::TW);
+    return (int)(tiles < 2LL * cus ? tiles : 2LL * cus);
+}
+
+lc_status lc_launch_conv_stem_wgrad_f32(const StemWgrad& p, int blocks, hipStream_t stream) {
+    using namespace stem;
+    if (p.P % TH != 0 || p.Q % TW != 0 || blocks != lc_conv_stem_blocks(p.imgs, p.P, p.Q)) return LC_ERR_UNSUPPORTED;
+    hipLaunchKernelGGL(conv_stem_wgrad_f32_kernel, dim3((unsigned)blocks), dim3(256), (size_t)(2 * SLAB) * 4, stream, p);
+    return lc_end_call();
+}
 
 lc_status lc_launch_conv_stem_f32(const StemConv& p, hipStream_t stream) {
     using namespace stem;
@@ -173,10 +308,7 @@ lc_status lc_launch_conv_stem_f32(const StemConv& p, hipStream_t stream) {
     }();
     if (!once) return LC_ERR_LAUNCH;
     if (p.P % TH != 0 || p.Q % TW != 0) return LC_ERR_UNSUPPORTED;
-    int dev = 0, cus = 0;
-    if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0) cus = 256;
-    const long long tiles = (long long)p.imgs * (p.P / TH) * (p.Q / TW);
-    const long long blocks = tiles < 2LL * cus ? tiles : 2LL * cus;        // two resident blocks per compute unit, each walks its tiles
+    const int blocks = lc_conv_stem_blocks(p.imgs, p.P, p.Q);
     hipLaunchKernelGGL(conv_stem_f32_kernel, dim3((unsigned)blocks), dim3(256), lds, stream, p);
     return lc_end_call();
 }

@@ -106,6 +106,14 @@ struct StemConv {
     float* stats;       // [pieces][64][2] (sum, sum of squares per piece of 64 pixels) or null
     int imgs, H, W, P, Q;
 };
+struct StemWgrad {
+    const float* x;     // [imgs][H][W][3]
+    const float* dy;    // [imgs][P][Q][64]
+    float* part;        // [blocks][64][147]: one partial filter gradient per block
+    int imgs, H, W, P, Q;
+};
+int lc_conv_stem_blocks(int imgs, int P, int Q);
+lc_status lc_launch_conv_stem_wgrad_f32(const StemWgrad& p, int blocks, hipStream_t stream);
 bool lc_conv_stem_f32_ok(int imgs, int c, int h, int w, int k, int r, int s, int sh, int sw, int ph, int pw, int P, int Q);
 size_t lc_conv_stem_f32_stats_pieces(int imgs, int P, int Q);
 lc_status lc_launch_conv_stem_f32(const StemConv& p, hipStream_t stream);

@@ -1,5 +1,6 @@
-"""GPU parity of the fp32 kernel for ResNet's first layer (7x7 window, stride 2, padding 3, 3 -> 64 channels, NHWC, output
-height and width multiples of 16), which runs a tile of 16 x 16 output pixels from an input slab in LDS: one tile and several
+"""GPU parity of the fp32 kernels for ResNet's first layer (7x7 window, stride 2, padding 3, 3 -> 64 channels, NHWC, output
+height and width multiples of 16), forward and backward-weight, which run a tile of 16 x 16 output pixels from an input slab
+in LDS: one tile and several
 per block, images of odd height and width (the last window rows and columns hang over the edge on both sides or on one),
 more than one tile per image in both directions, more blocks than tiles.  Each result is compared with the float64 oracle
 element by element (1e-4 tensor-scaled: both sides use the same fp32 operands, the GPU sums 147 products in fp32) and with
@@ -65,6 +66,36 @@ def test_first_layer_kernel_matches_oracle_and_general_kernel(name, restore_env)
     assert gu.scaled_err(y, other) <= 1e-5
 
 
+@pytest.mark.parametrize("name", list(SHAPES))
+def test_first_layer_filter_gradient_matches_oracle_and_general_kernel(name, restore_env):
+    n, h, w = SHAPES[name]
+    seed = 5500 + 10 * list(SHAPES).index(name)
+    x = synth.normal((n, 3, h, w), seed)
+    d = gu.desc_for(x.shape, (64, 3, 7, 7), 2, 3, NHWC)
+    p, q = lc.conv2d_out_shape(d)
+    dy = synth.normal((n, 64, p, q), seed + 2)
+    print(f"first-layer filter gradient case {name} desc {d}", flush=True)
+    xl, dyl = gu.to_layout(x, NHWC), gu.to_layout(dy, NHWC)
+    dw = gu.from_layout(gu.gpu_bwd_weight(d, xl, dyl), NHWC)
+    ref = oracle.conv2d_bwd_weight(x, dy, (7, 7), 2, 3)
+    assert np.all(np.isfinite(dw))
+    assert gu.scaled_err(dw, ref) <= TOL
+    np.testing.assert_array_equal(dw, gu.from_layout(gu.gpu_bwd_weight(d, xl, dyl), NHWC))   # fixed order: reruns are bit-identical
+    # the squared norm for LARS comes out of the sum over the blocks' partials
+    count = lc.conv2d_bwd_weight_sq_count(d)
+    pieces = torch.full((count,), float("nan"), dtype=torch.float64, device=gu.DEV)
+    dw2 = torch.full((64, 7, 7, 3), float("nan"), dtype=torch.float32, device=gu.DEV)
+    lc.conv2d_bwd_weight_sq(d, gu.dev(xl), gu.dev(dyl), dw2, pieces, gu.workspace(lc.conv2d_workspace_bytes(d, lc.LC_PASS_BWD_WEIGHT)))
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(gu.from_layout(dw2.cpu().numpy(), NHWC), dw)
+    want = float(np.sum(dw.astype(np.float64) ** 2))
+    assert abs(float(pieces.sum().item()) - want) <= 1e-6 * want
+    os.environ["LARSCONV_NO_STEM_DIRECT"] = "1"
+    other = gu.from_layout(gu.gpu_bwd_weight(d, xl, dyl), NHWC)
+    assert gu.scaled_err(other, ref) <= TOL
+    assert gu.scaled_err(dw, other) <= 2e-5
+
+
 def test_other_first_layers_keep_the_general_kernel(restore_env):
     """Shapes next to the one the kernel takes: an output that is not a multiple of 16, another filter count, stride or
     padding, NCHW.  All must still be right (the general kernel runs them)."""
@@ -77,3 +108,7 @@ def test_other_first_layers_keep_the_general_kernel(restore_env):
         d = gu.desc_for(xs, ws, stride, pad, layout)
         y = gu.from_layout(gu.gpu_fwd(d, gu.to_layout(x, layout), gu.to_layout(wt, layout)), layout)
         assert gu.scaled_err(y, oracle.conv2d_fwd(x, wt, stride, pad)) <= TOL
+        p, q = lc.conv2d_out_shape(d)
+        dy = synth.normal((xs[0], ws[0], p, q), 5480 + i)
+        dw = gu.from_layout(gu.gpu_bwd_weight(d, gu.to_layout(x, layout), gu.to_layout(dy, layout)), layout)
+        assert gu.scaled_err(dw, oracle.conv2d_bwd_weight(x, dy, (7, 7), stride, pad)) <= TOL
