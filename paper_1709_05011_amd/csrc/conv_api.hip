@@ -275,17 +275,21 @@ bool plan_blocks(const lc_conv_desc* d, int P, int Q, Plan* pl) {
     return true;
 }
 
-// ResNet's first layer in fp32 and NHWC: the kernels of conv_stem.hip take it (forward and backward-weight).
-bool stem_direct(const lc_conv_desc* d, const Plan& pl) {
-    return !pl.bf16 && !pl.nchw && d->groups <= 1 &&
-           lc_conv_stem_f32_ok(d->n, d->c, d->h, d->w, d->k, d->r, d->s, d->stride_h, d->stride_w, d->pad_h, d->pad_w, pl.P, pl.Q);
+// ResNet's first layer in NHWC: the kernels of conv_stem.hip take its forward pass (fp32 and bf16) and its fp32 filter gradient.
+bool stem_shape(const lc_conv_desc* d, int P, int Q) {
+    return d->layout == LC_NHWC && d->groups <= 1 &&
+           lc_conv_stem_f32_ok(d->n, d->c, d->h, d->w, d->k, d->r, d->s, d->stride_h, d->stride_w, d->pad_h, d->pad_w, P, Q);
+}
+bool stem_direct(const lc_conv_desc* d, const Plan& pl, lc_pass pass) {
+    if (pl.blocks || pl.nchw || !stem_shape(d, pl.P, pl.Q)) return false;
+    return pass == LC_PASS_FWD || (pass == LC_PASS_BWD_WEIGHT && !pl.bf16);
 }
 
 lc_status make_plan(const lc_conv_desc* d, lc_pass pass, Plan* pl) {
     const lc_status st = check_desc(d, &pl->P, &pl->Q);
     if (st != LC_OK) return st;
     if (pass != LC_PASS_FWD && pass != LC_PASS_BWD_DATA && pass != LC_PASS_BWD_WEIGHT) return LC_ERR_UNSUPPORTED;
-    if (pass != LC_PASS_BWD_DATA && plan_blocks(d, pl->P, pl->Q, pl)) {
+    if (pass != LC_PASS_BWD_DATA && !(pass == LC_PASS_FWD && stem_shape(d, pl->P, pl->Q)) && plan_blocks(d, pl->P, pl->Q, pl)) {
         pl->blocks = true;
         pl->bf16 = d->dtype == LC_BF16;
         pl->esize = pl->bf16 ? 2 : 4;
@@ -304,7 +308,11 @@ lc_status make_plan(const lc_conv_desc* d, lc_pass pass, Plan* pl) {
     const size_t nx = (size_t)d->n * d->h * d->w * d->c, ny = (size_t)d->n * pl->P * pl->Q * d->k;
     const size_t nw = (size_t)d->k * d->r * d->s * d->c;
     pl->cpad = pl->bf16 ? (d->c + 7) & ~7 : (d->c + 3) & ~3;
-    if (pass == LC_PASS_BWD_WEIGHT && stem_direct(d, *pl)) {
+    if (pass == LC_PASS_FWD && stem_direct(d, *pl, pass)) {
+        pl->total = 0;                           // the kernel reads x and w and writes y: no workspace
+        return LC_OK;
+    }
+    if (stem_direct(d, *pl, pass) && pass == LC_PASS_BWD_WEIGHT) {
         pl->stem_wgrad = true;
         pl->cpad = d->c;                         // its kernel reads the three channels as they are
     }
@@ -575,7 +583,12 @@ lc_status fwd_impl(const lc_conv_desc* d, const void* x, const void* w, void* y,
         return fwd_impl(&pl.inner, u, wu, y, stats, pl.s_ws_bytes ? at(workspace, pl.s_ws) : nullptr, pl.s_ws_bytes, hip_stream);
     }
 
-    if (stem_direct(d, pl)) {
+    if (stem_direct(d, pl, LC_PASS_FWD)) {
+        if (pl.bf16) {
+            const StemConvBf16 sb = {static_cast<const uint16_t*>(x), static_cast<const uint16_t*>(w), static_cast<uint16_t*>(y), stats,
+                                     d->n, d->h, d->w, pl.P, pl.Q};
+            return lc_launch_conv_stem_bf16(sb, stream);
+        }
         const StemConv sc = {static_cast<const float*>(x), static_cast<const float*>(w), static_cast<float*>(y), stats,
                              d->n, d->h, d->w, pl.P, pl.Q};
         return lc_launch_conv_stem_f32(sc, stream);
@@ -620,7 +633,7 @@ size_t fwd_stats_tiles(const lc_conv_desc* d) {
     Plan pl;
     if (make_plan(d, LC_PASS_FWD, &pl) != LC_OK || pl.nchw) return 0;
     if (pl.blocks) return fwd_stats_tiles(&pl.inner);
-    if (stem_direct(d, pl)) return lc_conv_stem_f32_stats_pieces(d->n, pl.P, pl.Q);
+    if (stem_direct(d, pl, LC_PASS_FWD)) return lc_conv_stem_f32_stats_pieces(d->n, pl.P, pl.Q);
     GemmConv g = gemm_fwd(d, pl.P, pl.Q, pl.cpad);
     return lc_conv_gemm_stats_tiles(g);
 }

@@ -1,4 +1,4 @@
-// Forward pass of ResNet's first layer in fp32 (7x7 window, stride 2, padding 3, 3 -> 64 channels, NHWC) from an input slab in
+// ResNet's first layer, forward in fp32 and bf16 and the filter gradient in fp32 (7x7 window, stride 2, padding 3, 3 -> 64 channels, NHWC) from an input slab in
 // LDS (the paper's ResNet-50, "ImageNet training with ResNet-50"; the layer is 2 % of the network's multiplications and was
 // 4 % of the step's time on the general kernel).
 //
@@ -23,6 +23,8 @@
 namespace {
 
 typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
 
 __device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" : : : "memory"); }
 
@@ -269,6 +271,143 @@ __global__ void __launch_bounds__(256, 2) conv_stem_wgrad_f32_kernel(const StemW
     }
 }
 
+// The forward pass in bf16 (bf16 x, w and y, fp32 sums, y rounded once).  Same tiles and slab (as bf16, fetched element by
+// element: a slab row starts on a 2-byte boundary).  An MFMA (32x32x16) takes 8 consecutive k from a lane, so a filter row's
+// 21 values are padded to 32: two MFMA steps per row, a lane's 8 values never straddle rows and start on a 4-byte boundary of
+// the slab (four 4-byte LDS reads); 224 k in 14 steps -- 56 MFMAs per wave and tile, a tenth of the fp32 kernel's matrix
+// time: the kernel is bound by its memory traffic (y is 5/6 of it).  The filter sits in LDS as [64][224 + 8].  Two
+// neighbouring pixels of a channel are rounded together and swapped with the neighbouring lane, so that every lane stores two
+// channels of one pixel as a dword; the statistics are those of the rounded values.
+namespace stemb {
+constexpr int R = 7, S = 7, C = 3, N = 64, ST = 2, PAD = 3;
+constexpr int TH = 16, TW = 16;
+constexpr int SR = (TH - 1) * ST + R;              // 37 slab rows
+constexpr int SWF = ((TW - 1) * ST + S) * C;       // 111 elements of a slab row
+constexpr int KR = 32;                             // k per filter row: its 21 values and 11 zeros (two MFMA steps of 16, a lane's 8 k never straddle rows)
+constexpr int KP = R * KR;                         // 224
+constexpr int SP = 124;                            // slab pitch in elements: a window's last pixel reads up to element 90 + 31
+constexpr int SLAB = SR * SP;                      // 4588
+constexpr int LD = (SLAB + 255) / 256;             // 18
+constexpr int BP = KP + 8;                         // filter pitch in elements (16-byte aligned rows, 8 banks apart)
+}  // namespace stemb
+
+__global__ void __launch_bounds__(256, 2) conv_stem_bf16_kernel(const StemConvBf16 p) {
+    using namespace stemb;
+    extern __shared__ __attribute__((aligned(16))) uint16_t sb_smem[];
+    uint16_t* Bs = sb_smem;                  // [64][BP]
+    uint16_t* slab = sb_smem + N * BP;       // [2][SLAB]
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int kb = lane >> 5, m = lane & 31;
+    const int tiles_x = p.Q / TW, tiles_y = p.P / TH, tiles = p.imgs * tiles_y * tiles_x;
+
+    for (int idx = tid; idx < N * BP / 2; idx += 256) reinterpret_cast<unsigned*>(Bs)[idx] = 0u;
+    __syncthreads();
+    for (int idx = tid; idx < N * R * S * C; idx += 256) {
+        const int n = idx / (R * S * C), rem = idx - n * (R * S * C), r = rem / (S * C), t = rem - r * (S * C);
+        Bs[n * BP + r * KR + t] = p.w[idx];
+    }
+    const int a_lane = ((4 * wave + (m >> 4)) * ST) * SP + (m & 15) * ST * C + 8 * kb;     // elements (even: 4-byte aligned)
+    int b_lane[2];
+#pragma unroll
+    for (int j = 0; j < 2; ++j) b_lane[j] = (m + 32 * j) * BP + 8 * kb;
+
+    const long long x_img = (long long)p.H * p.W * C;
+    unsigned g[LD];
+    auto gload = [&](int tile) {
+        const int tx = tile % tiles_x, t2 = tile / tiles_x, ty = t2 % tiles_y, img = t2 / tiles_y;
+        const int h0 = ty * TH * ST - PAD, w0f = (tx * TW * ST - PAD) * C;
+        const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc((void*)(p.x + img * x_img), 0, (int)(x_img * 2), 0x00020000);
+        const int base = h0 * p.W * C + w0f;
+#pragma unroll
+        for (int l = 0; l < LD; ++l) {
+            const int e = tid + 256 * l, i = e / SP, f = e - i * SP;
+            const bool ok = (e < SLAB) & (f < SWF) & ((unsigned)(h0 + i) < (unsigned)p.H) & ((unsigned)(w0f + f) < (unsigned)(p.W * C));
+            const unsigned off = ok ? (unsigned)(base + i * p.W * C + f) * 2u : 0x80000000u;
+            g[l] = __builtin_amdgcn_raw_buffer_load_b16(rsrc, off, 0, 0);
+        }
+    };
+    auto sstore = [&](int buf) {
+#pragma unroll
+        for (int l = 0; l < LD; ++l) {
+            const int e = tid + 256 * l;
+            if (e < SLAB) slab[buf * SLAB + e] = (uint16_t)g[l];
+        }
+    };
+
+    int tile = blockIdx.x;
+    if (tile < tiles) gload(tile);
+    int buf = 0;
+    for (; tile < tiles; tile += gridDim.x) {
+        sstore(buf);
+        lds_barrier();
+        if (tile + (int)gridDim.x < tiles) gload(tile + gridDim.x);
+        f32x16 acc[2][2];
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int j = 0; j < 2; ++j)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+        const uint16_t* sa = slab + buf * SLAB + a_lane;
+#pragma unroll
+        for (int s = 0; s < KP / 16; ++s) {
+            const int r = s / 2, t0 = 16 * (s % 2);
+            bf16x8 a[2], b[2];
+#pragma unroll
+            for (int i = 0; i < 2; ++i) {
+                const unsigned* q = reinterpret_cast<const unsigned*>(sa + (2 * i * ST + r) * SP + t0);
+                const u32x4 v = {q[0], q[1], q[2], q[3]};
+                a[i] = __builtin_bit_cast(bf16x8, v);
+            }
+#pragma unroll
+            for (int j = 0; j < 2; ++j) b[j] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(Bs + b_lane[j] + 16 * s));
+#pragma unroll
+            for (int i = 0; i < 2; ++i)
+#pragma unroll
+                for (int j = 0; j < 2; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
+        }
+        const int tx = tile % tiles_x, t2 = tile / tiles_x, ty = t2 % tiles_y, img = t2 / tiles_y;
+        // Registers v and v + 1 hold two neighbouring pixels of the lane's channel: the pair is rounded together, swapped with
+        // the neighbouring lane, and every lane stores two channels of one pixel as a dword (even lanes the first pixel, odd
+        // lanes the second).
+        const int odd = lane & 1;
+        uint16_t* yo = p.y + (((long long)img * p.P + ty * TH + 4 * wave) * p.Q + tx * TW) * N + (4 * kb + odd) * N + (m & ~1);
+        const unsigned perm_sel = odd ? 0x03020706u : 0x05040100u;
+        float sum[2] = {0.f, 0.f}, sq[2] = {0.f, 0.f};
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int v = 0; v < 16; v += 2) {
+                const int row = 2 * i + (v >> 3), col = 8 * ((v >> 2) & 1) + (v & 3);
+#pragma unroll
+                for (int j = 0; j < 2; ++j) {
+                    typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+                    typedef float f32x2 __attribute__((ext_vector_type(2)));
+                    const f32x2 pr = {acc[i][j][v], acc[i][j][v + 1]};
+                    const unsigned u = __builtin_bit_cast(unsigned, __builtin_convertvector(pr, bf16x2));
+                    const unsigned got = (unsigned)__builtin_amdgcn_mov_dpp((int)u, 0xB1 /* quad_perm 1,0,3,2 */, 0xF, 0xF, true);
+                    *reinterpret_cast<unsigned*>(yo + (row * p.Q + col) * N + 32 * j) = __builtin_amdgcn_perm(got, u, perm_sel);
+                    const float f0 = __uint_as_float(u << 16), f1 = __uint_as_float(u & 0xffff0000u);
+                    sum[j] += f0;
+                    sq[j] = fmaf(f0, f0, sq[j]);
+                    sum[j] += f1;
+                    sq[j] = fmaf(f1, f1, sq[j]);
+                }
+            }
+        if (p.stats) {
+            typedef float flt2 __attribute__((ext_vector_type(2)));
+            flt2* st = reinterpret_cast<flt2*>(p.stats) + ((size_t)tile * 4 + wave) * N;
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+                const float s1 = sum[j] + __shfl_xor(sum[j], 32), s2 = sq[j] + __shfl_xor(sq[j], 32);
+                if (kb == 0) st[32 * j + m] = flt2{s1, s2};
+            }
+        }
+        buf ^= 1;
+    }
+}
+
 }  // namespace
 
 bool lc_conv_stem_f32_ok(int imgs, int c, int h, int w, int k, int r, int s, int sh, int sw, int ph, int pw, int P, int Q) {
@@ -296,6 +435,16 @@ lc_status lc_launch_conv_stem_wgrad_f32(const StemWgrad& p, int blocks, hipStrea
     using namespace stem;
     if (p.P % TH != 0 || p.Q % TW != 0 || blocks != lc_conv_stem_blocks(p.imgs, p.P, p.Q)) return LC_ERR_UNSUPPORTED;
     hipLaunchKernelGGL(conv_stem_wgrad_f32_kernel, dim3((unsigned)blocks), dim3(256), (size_t)(2 * SLAB) * 4, stream, p);
+    return lc_end_call();
+}
+
+lc_status lc_launch_conv_stem_bf16(const StemConvBf16& p, hipStream_t stream) {
+    using namespace stemb;
+    constexpr size_t lds = (size_t)(N * BP + 2 * SLAB) * 2;
+    if (p.P % TH != 0 || p.Q % TW != 0) return LC_ERR_UNSUPPORTED;
+    if ((reinterpret_cast<uintptr_t>(p.x) | reinterpret_cast<uintptr_t>(p.w)) & 1 || reinterpret_cast<uintptr_t>(p.y) & 3) return LC_ERR_ALIGN;
+    const int blocks = lc_conv_stem_blocks(p.imgs, p.P, p.Q);
+    hipLaunchKernelGGL(conv_stem_bf16_kernel, dim3((unsigned)blocks), dim3(256), lds, stream, p);
     return lc_end_call();
 }
 

@@ -106,6 +106,14 @@ struct StemConv {
     float* stats;       // [pieces][64][2] (sum, sum of squares per piece of 64 pixels) or null
     int imgs, H, W, P, Q;
 };
+struct StemConvBf16 {
+    const uint16_t* x;  // [imgs][H][W][3]
+    const uint16_t* w;  // [64][7][7][3]
+    uint16_t* y;        // [imgs][P][Q][64]
+    float* stats;       // as StemConv
+    int imgs, H, W, P, Q;
+};
+lc_status lc_launch_conv_stem_bf16(const StemConvBf16& p, hipStream_t stream);
 struct StemWgrad {
     const float* x;     // [imgs][H][W][3]
     const float* dy;    // [imgs][P][Q][64]

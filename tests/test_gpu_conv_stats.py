@@ -87,7 +87,7 @@ def _case(name, shape, bf16):
     assert np.all(np.isfinite(got)), "a piece was not written"
     rows = _get(y, bf16).reshape(n * p * q, k).astype(np.float64)
     m = rows.shape[0]
-    if not bf16 and (c, k, r, s, stride, pad) == (3, 64, 7, 7, 2, 3) and p % 16 == 0 and q % 16 == 0:
+    if (c, k, r, s, stride, pad) == (3, 64, 7, 7, 2, 3) and p % 16 == 0 and q % 16 == 0:
         # the first-layer kernel: a piece is a 4 x 16 block of one image's output pixels, four to a 16 x 16 tile
         assert count == n * (p // 16) * (q // 16) * 4
         idx = np.arange(m).reshape(n, p, q)

@@ -96,6 +96,38 @@ def test_first_layer_filter_gradient_matches_oracle_and_general_kernel(name, res
     assert gu.scaled_err(dw, other) <= 2e-5
 
 
+@pytest.mark.parametrize("name", list(SHAPES))
+def test_first_layer_bf16_forward_matches_oracle_and_general_path(name, restore_env):
+    """bf16 operands and result, fp32 sums, one rounding: within one bf16 step of the float64 value element by element, and
+    equal to the result of the path over 2x2 pixel blocks in all but a few elements (same products, another order)."""
+    n, h, w = SHAPES[name]
+    seed = 5600 + 10 * list(SHAPES).index(name)
+    xb = synth.to_bf16_bits(synth.normal((n, 3, h, w), seed))
+    wb = synth.to_bf16_bits(synth.normal((64, 3, 7, 7), seed + 1, std=float(np.sqrt(2.0 / 147))))
+    x, wt = synth.bf16_bits_to_f32(xb), synth.bf16_bits_to_f32(wb)
+    d = gu.desc_for(x.shape, wt.shape, 2, 3, NHWC, lc.LC_BF16)
+    p, q = lc.conv2d_out_shape(d)
+    put = lambda bits: torch.from_numpy(np.ascontiguousarray(gu.to_layout(bits, NHWC)).view(np.int16)).to(gu.DEV)   # noqa: E731
+    xd, wd = put(xb), put(wb)
+
+    def run():
+        y = torch.full((n, p, q, 64), -1, dtype=torch.int16, device=gu.DEV)
+        lc.conv2d_fwd(d, xd, wd, y, gu.workspace(lc.conv2d_workspace_bytes(d, lc.LC_PASS_FWD)))
+        torch.cuda.synchronize()
+        return gu.from_layout(synth.bf16_bits_to_f32(y.cpu().numpy().view(np.uint16)), NHWC)
+
+    y = run()
+    ref = oracle.conv2d_fwd(x, wt, 2, 3)
+    assert np.all(np.isfinite(y))                                  # the fill pattern is a NaN
+    assert gu.scaled_err(y, oracle.round_to_bf16(ref)) <= 2e-2
+    assert np.all(np.abs(y - ref) <= np.abs(ref) * 2.0 ** -7 + 1e-6 * float(np.max(np.abs(ref))))
+    assert lc.conv2d_fwd_stats_count(d) == n * (p // 16) * (q // 16) * 4
+    os.environ["LARSCONV_NO_STEM_DIRECT"] = "1"
+    other = run()
+    assert np.mean(y == other) >= 0.99
+    assert np.all(np.abs(y - other) <= np.abs(other) * 2.0 ** -7 + 1e-6 * float(np.max(np.abs(other))))
+
+
 def test_other_first_layers_keep_the_general_kernel(restore_env):
     """Shapes next to the one the kernel takes: an output that is not a multiple of 16, another filter count, stride or
     padding, NCHW.  All must still be right (the general kernel runs them)."""
