@@ -104,18 +104,15 @@ def make_workspace(nbytes, torch):
 
 
 class Timer:
-    """HIP events on the stream the kernels are launched on (torch's current stream)."""
+    """HIP events on the stream the kernels are launched on (torch's current stream): one event after every library call,
+    a call's span running from the event behind the previous call to its own (one more event opens the chain).  Half the
+    events of a pair per call -- each costs the command processor a few microseconds between kernels."""
 
     def __init__(self, torch):
         self.torch = torch
         self.spans = []          # (key, start, stop)
         self.step_starts = []    # index into spans of the first call of every timed step
-
-    def span(self, key):
-        t = self.torch
-        a, b = t.cuda.Event(enable_timing=True), t.cuda.Event(enable_timing=True)
-        self.spans.append((key, a, b))
-        return a, b
+        self.last = None         # the event behind the latest call
 
     def totals(self):
         out = {}
@@ -129,10 +126,14 @@ def timed(timer, key, fn):
     if timer is None:
         fn()
         return
-    a, b = timer.span(key)
-    a.record()
+    if timer.last is None:
+        timer.last = timer.torch.cuda.Event(enable_timing=True)
+        timer.last.record()
     fn()
+    b = timer.torch.cuda.Event(enable_timing=True)
     b.record()
+    timer.spans.append((key, timer.last, b))
+    timer.last = b
 
 
 def model_shapes(synth, model: str, batch: int):
@@ -189,6 +190,11 @@ def run_train_step(args):
     def gemm_kernel_of(l, pass_):
         """Which conv kernel instance a call ends in (mirrors the library's dispatch; labels only)."""
         cs = l.cs
+        # ResNet's first layer has kernels of its own (forward in both types, the filter gradient in fp32)
+        stem = ((cs.c, cs.k, cs.r, cs.s, cs.stride, cs.pad) == (3, 64, 7, 7, 2, 3) and cs.p % 16 == 0 and cs.q % 16 == 0
+                and not os.environ.get("LARSCONV_NO_STEM_DIRECT"))
+        if stem and (pass_ == "fwd" or (pass_ == "bwd_weight" and not bf16)):
+            return "conv_stem"
         if pass_ == "bwd_weight":
             return "wgrad"
         n_gemm = cs.k if pass_ == "fwd" else cs.c
