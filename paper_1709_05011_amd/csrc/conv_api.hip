@@ -31,7 +31,7 @@ struct Plan {
     size_t sk = 0, sk_bytes = 0;     // partial tiles of the stream-K blocks (forward, backward-data)
     int splits = 1, m_per_split = 0;
     bool wgrad_direct = true;
-    bool stem_wgrad = false;         // ResNet's first layer in fp32: the filter-gradient kernel of conv_stem.hip
+    bool stem_wgrad = false;         // ResNet's first layer: the filter-gradient kernels of conv_stem.hip
     bool wgrad_slab = false;         // bf16 3x3 stride-1 pad-1 layer: the kernel that stages the activations once for all taps
     // bf16 problems the bf16 MFMA kernel does not take (backward-data with k not a multiple of 8, or a strided
     // window other than 1x1): operands are widened to fp32 copies, the fp32 pass runs on them, the result is
@@ -275,21 +275,21 @@ bool plan_blocks(const lc_conv_desc* d, int P, int Q, Plan* pl) {
     return true;
 }
 
-// ResNet's first layer in NHWC: the kernels of conv_stem.hip take its forward pass (fp32 and bf16) and its fp32 filter gradient.
+// ResNet's first layer in NHWC: the kernels of conv_stem.hip take its forward pass and its filter gradient, fp32 and bf16.
 bool stem_shape(const lc_conv_desc* d, int P, int Q) {
     return d->layout == LC_NHWC && d->groups <= 1 &&
            lc_conv_stem_f32_ok(d->n, d->c, d->h, d->w, d->k, d->r, d->s, d->stride_h, d->stride_w, d->pad_h, d->pad_w, P, Q);
 }
 bool stem_direct(const lc_conv_desc* d, const Plan& pl, lc_pass pass) {
     if (pl.blocks || pl.nchw || !stem_shape(d, pl.P, pl.Q)) return false;
-    return pass == LC_PASS_FWD || (pass == LC_PASS_BWD_WEIGHT && !pl.bf16);
+    return pass == LC_PASS_FWD || pass == LC_PASS_BWD_WEIGHT;
 }
 
 lc_status make_plan(const lc_conv_desc* d, lc_pass pass, Plan* pl) {
     const lc_status st = check_desc(d, &pl->P, &pl->Q);
     if (st != LC_OK) return st;
     if (pass != LC_PASS_FWD && pass != LC_PASS_BWD_DATA && pass != LC_PASS_BWD_WEIGHT) return LC_ERR_UNSUPPORTED;
-    if (pass != LC_PASS_BWD_DATA && !(pass == LC_PASS_FWD && stem_shape(d, pl->P, pl->Q)) && plan_blocks(d, pl->P, pl->Q, pl)) {
+    if (pass != LC_PASS_BWD_DATA && !stem_shape(d, pl->P, pl->Q) && plan_blocks(d, pl->P, pl->Q, pl)) {
         pl->blocks = true;
         pl->bf16 = d->dtype == LC_BF16;
         pl->esize = pl->bf16 ? 2 : 4;
@@ -776,8 +776,13 @@ lc_status bwd_weight_impl(const lc_conv_desc* d, const void* x, const void* dy, 
 
     if (pl.stem_wgrad) {
         float* part = reinterpret_cast<float*>(at(workspace, pl.part));
-        const StemWgrad sw = {static_cast<const float*>(x), static_cast<const float*>(dy), part, d->n, d->h, d->w, pl.P, pl.Q};
-        st = lc_launch_conv_stem_wgrad_f32(sw, pl.splits, stream);
+        if (pl.bf16) {
+            const StemWgradBf16 sb = {static_cast<const uint16_t*>(x), static_cast<const uint16_t*>(dy), part, d->n, d->h, d->w, pl.P, pl.Q};
+            st = lc_launch_conv_stem_wgrad_bf16(sb, pl.splits, stream);
+        } else {
+            const StemWgrad sw = {static_cast<const float*>(x), static_cast<const float*>(dy), part, d->n, d->h, d->w, pl.P, pl.Q};
+            st = lc_launch_conv_stem_wgrad_f32(sw, pl.splits, stream);
+        }
         if (st != LC_OK) return st;
         const bool fused_sq = sq && wgrad_sq_fused(d, pl);
         lc_reduce_splits(part, dw, pl.splits, (size_t)d->k * d->r * d->s * d->c, d->c, d->c, fused_sq ? sq : nullptr, stream);

@@ -1,4 +1,4 @@
-// ResNet's first layer, forward in fp32 and bf16 and the filter gradient in fp32 (7x7 window, stride 2, padding 3, 3 -> 64 channels, NHWC) from an input slab in
+// ResNet's first layer, forward and filter gradient, in fp32 and bf16 (7x7 window, stride 2, padding 3, 3 -> 64 channels, NHWC) from an input slab in
 // LDS (the paper's ResNet-50, "ImageNet training with ResNet-50"; the layer is 2 % of the network's multiplications and was
 // 4 % of the step's time on the general kernel).
 //
@@ -408,6 +408,134 @@ __global__ void __launch_bounds__(256, 2) conv_stem_bf16_kernel(const StemConvBf
     }
 }
 
+// The filter gradient in bf16 (bf16 x and dY, fp32 sums and dW).  The reduction runs over pixels, and a `32x32x16` MFMA takes
+// 8 consecutive reduction values from a lane: both operands come from LDS through the transposing read (see
+// wgrad_bf16_kernel), which lets every lane point anywhere.  dY of the tile sits in LDS as [pixel][64].  The slab keeps four
+// channels per pixel (the fourth zero), so that a pixel is 8 bytes and the 16 pixels of an output row, two input pixels
+// apart, are "rows" 16 bytes apart that overlap: row i of the operand matrix of filter row r is the 32 elements (s, c) from
+// pixel 2 i on -- 7 x 4 window elements and a zero tail.  One MFMA step is one output row of the tile (16 pixels); the columns
+// of dW come out as (r, s * 4 + c), 7 tiles of 32.  A wave owns 32 filters and the filter rows 0-3 or 4-6 for the life of the
+// block and writes its part of the block's partial itself (no sum across waves).  0.92 ms (unfolding pass + gathering
+// kernel) -> 0.33 ms at batch 512.
+namespace stemwb {
+constexpr int R = 7, S = 7, C = 3, N = 64, ST = 2, PAD = 3;
+constexpr int TH = 16, TW = 16;
+constexpr int SR = (TH - 1) * ST + R;              // 37 slab rows
+constexpr int SPX = (TW - 1) * ST + S;             // 37 slab pixels per row
+constexpr int CP = 4;                              // channels per slab pixel (the fourth stays zero): a pixel is 8 bytes
+constexpr int SPB = 152;                           // slab pitch in elements: the last pixel's 32 window elements end at 15 * 8 + 32
+constexpr int SLAB = SR * SPB;                     // 5624 elements
+constexpr int SLD = (SR * SPX * C + 255) / 256;    // 17 element loads per thread
+constexpr int PA = 96;                             // dY pitch in elements ([pixel][64] + 32: rows 64 bytes apart modulo 256)
+constexpr int J = R * S * C;                       // 147
+}  // namespace stemwb
+
+__global__ void __launch_bounds__(256, 2) conv_stem_wgrad_bf16_kernel(const StemWgradBf16 p) {
+    using namespace stemwb;
+    __shared__ __attribute__((aligned(16))) uint16_t slab[SLAB];
+    __shared__ __attribute__((aligned(16))) uint16_t dys[TH * TW * PA];
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int kt = wave >> 1, r0 = (wave & 1) * 4, nr = (wave & 1) ? 3 : 4;   // the wave's 32 filters and its filter rows r0 .. r0 + nr - 1
+    const int tiles_x = p.Q / TW, tiles_y = p.P / TH, tiles = p.imgs * tiles_y * tiles_x;
+
+    for (int i = tid; i < SLAB / 2; i += 256) reinterpret_cast<unsigned*>(slab)[i] = 0u;    // fourth channels and row tails stay zero
+
+    const long long x_img = (long long)p.H * p.W * C;
+    unsigned gx[SLD];
+    u32x4 gy[8];
+    auto gload = [&](int tile) {
+        int tid = threadIdx.x;
+        asm volatile("" : "+v"(tid));                                 // recompute the per-element indices every tile: hoisted, they cost 70 registers
+        const int tx = tile % tiles_x, t2 = tile / tiles_x, ty = t2 % tiles_y, img = t2 / tiles_y;
+        const int h0 = ty * TH * ST - PAD, w0 = tx * TW * ST - PAD;
+        const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc((void*)(p.x + img * x_img), 0, (int)(x_img * 2), 0x00020000);
+#pragma unroll
+        for (int l = 0; l < SLD; ++l) {
+            const int e = tid + 256 * l, i = e / (SPX * C), f = e - i * (SPX * C);
+            const bool ok = (e < SR * SPX * C) & ((unsigned)(h0 + i) < (unsigned)p.H) & ((unsigned)(w0 * C + f) < (unsigned)(p.W * C));
+            const unsigned off = ok ? (unsigned)(((h0 + i) * p.W + w0) * C + f) * 2u : 0x80000000u;
+            gx[l] = __builtin_amdgcn_raw_buffer_load_b16(rsrc, off, 0, 0);
+        }
+        const uint16_t* yb = p.dy + (((long long)img * p.P + ty * TH) * p.Q + tx * TW) * N;
+#pragma unroll
+        for (int l = 0; l < 8; ++l) {
+            const int id = tid + 256 * l, px = id >> 3, cq = id & 7;
+            gy[l] = *reinterpret_cast<const u32x4*>(yb + ((long long)(px >> 4) * p.Q + (px & 15)) * N + cq * 8);
+        }
+    };
+    auto sstore = [&]() {
+        int tid = threadIdx.x;
+        asm volatile("" : "+v"(tid));
+#pragma unroll
+        for (int l = 0; l < SLD; ++l) {
+            const int e = tid + 256 * l, i = e / (SPX * C), f = e - i * (SPX * C), px = f / C, c = f - px * C;
+            if (e < SR * SPX * C) slab[i * SPB + px * CP + c] = (uint16_t)gx[l];
+        }
+#pragma unroll
+        for (int l = 0; l < 8; ++l) {
+            const int id = tid + 256 * l, px = id >> 3, cq = id & 7;
+            *reinterpret_cast<u32x4*>(&dys[px * PA + cq * 8]) = gy[l];
+        }
+    };
+
+    typedef short s16x4 __attribute__((ext_vector_type(4)));
+    typedef short s16x8 __attribute__((ext_vector_type(8)));
+    // transposing read: within 16 lanes, lane i points at 4 consecutive elements of reduction row i / 4 (columns 4 * (i % 4) ..)
+    // and receives column i of those 4 rows; lanes 16..31 the next 16 columns, lanes 32..63 the rows 8 further down
+    const int tr_row = 8 * (lane >> 5) + ((lane & 15) >> 2), tr_col = 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
+    auto tr4 = [&](const uint16_t* q) __attribute__((always_inline)) {
+        return __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(uintptr_t)q);
+    };
+    const int a_lane = tr_row * PA + kt * 32 + tr_col;               // dY: reduction rows are the 16 pixels of an output row
+    const int b_lane = tr_row * (ST * CP) + tr_col;                  // X: pixel i of the row sits 8 elements after pixel i - 1
+
+    f32x16 acc[4];
+#pragma unroll
+    for (int t = 0; t < 4; ++t)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[t][v] = 0.f;
+
+    int tile = blockIdx.x;
+    if (tile < tiles) gload(tile);
+    for (; tile < tiles; tile += gridDim.x) {
+        lds_barrier();                                                // everyone is done with the previous tile (and the clearing)
+        sstore();
+        lds_barrier();
+        if (tile + (int)gridDim.x < tiles) gload(tile + gridDim.x);
+#pragma unroll
+        for (int py = 0; py < TH; ++py) {
+            const uint16_t* qa = dys + py * TW * PA + a_lane;
+            const s16x4 alo = tr4(qa), ahi = tr4(qa + 4 * PA);
+            const s16x8 av = {alo[0], alo[1], alo[2], alo[3], ahi[0], ahi[1], ahi[2], ahi[3]};
+            const bf16x8 a = __builtin_bit_cast(bf16x8, av);
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                if (t < nr) {
+                    const uint16_t* qb = slab + (ST * py + r0 + t) * SPB + b_lane;
+                    const s16x4 blo = tr4(qb), bhi = tr4(qb + 4 * ST * CP);
+                    const s16x8 bv = {blo[0], blo[1], blo[2], blo[3], bhi[0], bhi[1], bhi[2], bhi[3]};
+                    acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, __builtin_bit_cast(bf16x8, bv), acc[t], 0, 0, 0);
+                }
+            }
+            if (py & 1) __builtin_amdgcn_sched_barrier(0);           // keep the reads of at most two rows in flight (registers)
+        }
+    }
+
+    // each wave owns its (filters, filter rows) part of dW: column t' = s * 4 + c of filter row r -> element (r, s, c)
+    float* part = p.part + (size_t)blockIdx.x * N * J;
+    const int tq = lane & 31, s = tq >> 2, c = tq & 3;
+#pragma unroll
+    for (int t = 0; t < 4; ++t)
+        if (t < nr && s < S && c < C) {
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int k = kt * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+                part[k * J + ((r0 + t) * S + s) * C + c] = acc[t][v];
+            }
+        }
+}
+
 }  // namespace
 
 bool lc_conv_stem_f32_ok(int imgs, int c, int h, int w, int k, int r, int s, int sh, int sw, int ph, int pw, int P, int Q) {
@@ -435,6 +563,14 @@ lc_status lc_launch_conv_stem_wgrad_f32(const StemWgrad& p, int blocks, hipStrea
     using namespace stem;
     if (p.P % TH != 0 || p.Q % TW != 0 || blocks != lc_conv_stem_blocks(p.imgs, p.P, p.Q)) return LC_ERR_UNSUPPORTED;
     hipLaunchKernelGGL(conv_stem_wgrad_f32_kernel, dim3((unsigned)blocks), dim3(256), (size_t)(2 * SLAB) * 4, stream, p);
+    return lc_end_call();
+}
+
+lc_status lc_launch_conv_stem_wgrad_bf16(const StemWgradBf16& p, int blocks, hipStream_t stream) {
+    using namespace stemwb;
+    if (p.P % TH != 0 || p.Q % TW != 0 || blocks != lc_conv_stem_blocks(p.imgs, p.P, p.Q)) return LC_ERR_UNSUPPORTED;
+    if ((reinterpret_cast<uintptr_t>(p.dy) & 15) || (reinterpret_cast<uintptr_t>(p.x) & 1)) return LC_ERR_ALIGN;
+    hipLaunchKernelGGL(conv_stem_wgrad_bf16_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, p);
     return lc_end_call();
 }
 

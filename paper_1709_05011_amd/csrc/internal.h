@@ -120,6 +120,13 @@ struct StemWgrad {
     float* part;        // [blocks][64][147]: one partial filter gradient per block
     int imgs, H, W, P, Q;
 };
+struct StemWgradBf16 {
+    const uint16_t* x;  // [imgs][H][W][3]
+    const uint16_t* dy; // [imgs][P][Q][64]
+    float* part;        // as StemWgrad
+    int imgs, H, W, P, Q;
+};
+lc_status lc_launch_conv_stem_wgrad_bf16(const StemWgradBf16& p, int blocks, hipStream_t stream);
 int lc_conv_stem_blocks(int imgs, int P, int Q);
 lc_status lc_launch_conv_stem_wgrad_f32(const StemWgrad& p, int blocks, hipStream_t stream);
 bool lc_conv_stem_f32_ok(int imgs, int c, int h, int w, int k, int r, int s, int sh, int sw, int ph, int pw, int P, int Q);

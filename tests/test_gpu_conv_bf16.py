@@ -139,9 +139,10 @@ def test_bf16_full_size_batch512_sampled(name):
 
 
 def test_bf16_first_layer_full_size_batch512_sampled():
-    """The 7x7 stride-2 first layer at the bf16 workload's full size (512 x 224 x 224 x 3): forward runs in the kernel
-    that keeps a tile's input slab in LDS (no workspace), backward-weight over 2x2 pixel blocks through a 0.84 GB unfolded
-    copy in the workspace.  Sampled outputs; backward-data is not part of a training step for a first layer."""
+    """The 7x7 stride-2 first layer at the bf16 workload's full size (512 x 224 x 224 x 3): forward and backward-weight run
+    in the kernels that keep a tile's input slab in LDS (no workspace for the forward pass, one partial filter gradient
+    per resident block for backward-weight).  Sampled outputs; backward-data is not part of a training step for a first
+    layer."""
     cs = synth.resnet50_convs(512)[0]
     seed = 7800
     print(f"bf16 full-size first layer: {cs}", flush=True)
@@ -151,7 +152,7 @@ def test_bf16_first_layer_full_size_batch512_sampled():
     x, wt, dy = (synth.bf16_bits_to_f32(b) for b in (xb, wb, dyb))
     d = lc.ConvDesc(cs.n, cs.c, cs.h, cs.w, cs.k, cs.r, cs.s, cs.stride, cs.stride, cs.pad, cs.pad, lc.LC_BF16, lc.LC_NHWC)
     assert lc.conv2d_workspace_bytes(d, lc.LC_PASS_FWD) == 0
-    assert lc.conv2d_workspace_bytes(d, lc.LC_PASS_BWD_WEIGHT) > 800_000_000    # the unfolded input
+    assert 0 < lc.conv2d_workspace_bytes(d, lc.LC_PASS_BWD_WEIGHT) < 100_000_000   # the blocks' partials, no unfolded input
     xd, wd, dyd = _dev_bf16(xb), _dev_bf16(wb), _dev_bf16(dyb)
     y = torch.empty((cs.n, cs.p, cs.q, cs.k), dtype=torch.int16, device=gu.DEV)
     dw = torch.empty((cs.k, cs.r, cs.s, cs.c), dtype=torch.float32, device=gu.DEV)

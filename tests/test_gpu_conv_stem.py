@@ -128,6 +128,48 @@ def test_first_layer_bf16_forward_matches_oracle_and_general_path(name, restore_
     assert np.all(np.abs(y - other) <= np.abs(other) * 2.0 ** -7 + 1e-6 * float(np.max(np.abs(other))))
 
 
+@pytest.mark.parametrize("name", list(SHAPES))
+def test_first_layer_bf16_filter_gradient_matches_oracle_and_general_path(name, restore_env):
+    """bf16 x and dy, fp32 sums and dw: exact products of bf16 values, so the result agrees with the float64 oracle on the
+    same operands to fp32 summation error, and with the path over 2x2 pixel blocks likewise."""
+    n, h, w = SHAPES[name]
+    seed = 5700 + 10 * list(SHAPES).index(name)
+    xb = synth.to_bf16_bits(synth.normal((n, 3, h, w), seed))
+    x = synth.bf16_bits_to_f32(xb)
+    d = gu.desc_for(x.shape, (64, 3, 7, 7), 2, 3, NHWC, lc.LC_BF16)
+    p, q = lc.conv2d_out_shape(d)
+    dyb = synth.to_bf16_bits(synth.normal((n, 64, p, q), seed + 2))
+    dy = synth.bf16_bits_to_f32(dyb)
+    put = lambda bits: torch.from_numpy(np.ascontiguousarray(gu.to_layout(bits, NHWC)).view(np.int16)).to(gu.DEV)   # noqa: E731
+    xd, dyd = put(xb), put(dyb)
+
+    def run(sq=False):
+        dw = torch.full((64, 7, 7, 3), float("nan"), dtype=torch.float32, device=gu.DEV)
+        ws = gu.workspace(lc.conv2d_workspace_bytes(d, lc.LC_PASS_BWD_WEIGHT))
+        pieces = None
+        if sq:
+            pieces = torch.full((lc.conv2d_bwd_weight_sq_count(d),), float("nan"), dtype=torch.float64, device=gu.DEV)
+            lc.conv2d_bwd_weight_sq(d, xd, dyd, dw, pieces, ws)
+        else:
+            lc.conv2d_bwd_weight(d, xd, dyd, dw, ws)
+        torch.cuda.synchronize()
+        return gu.from_layout(dw.cpu().numpy(), NHWC), pieces
+
+    dw, _ = run()
+    ref = oracle.conv2d_bwd_weight(x, dy, (7, 7), 2, 3)
+    assert np.all(np.isfinite(dw))
+    assert gu.scaled_err(dw, ref) <= TOL
+    np.testing.assert_array_equal(dw, run()[0])
+    dw2, pieces = run(sq=True)
+    np.testing.assert_array_equal(dw2, dw)
+    want = float(np.sum(dw.astype(np.float64) ** 2))
+    assert abs(float(pieces.sum().item()) - want) <= 1e-6 * want
+    os.environ["LARSCONV_NO_STEM_DIRECT"] = "1"
+    other, _ = run()
+    assert gu.scaled_err(other, ref) <= TOL
+    assert gu.scaled_err(dw, other) <= 2e-5
+
+
 def test_other_first_layers_keep_the_general_kernel(restore_env):
     """Shapes next to the one the kernel takes: an output that is not a multiple of 16, another filter count, stride or
     padding, NCHW.  All must still be right (the general kernel runs them)."""
