@@ -247,7 +247,8 @@ const lc_conv_desc* whole_window_as_1x1(const lc_conv_desc* d, lc_conv_desc* sto
 // multiplications than the padded original (measured on the 7x7 first layer of ResNet-50 at batch 512: forward
 // 1.32 -> 0.95 ms, backward-weight 1.51 -> 0.92 ms including the unfolding; in fp32, where padding to four channels
 // wastes less, the two forms take the same time and the original is kept).  The layer's backward-data (never
-// needed for a first layer) keeps the general path.
+// needed for a first layer) keeps the general path.  ResNet's own first layer (stem_shape below) goes to the kernels of
+// conv_stem.hip instead, in both types.
 bool plan_blocks(const lc_conv_desc* d, int P, int Q, Plan* pl) {
     static const bool off = getenv("LARSCONV_NO_STEM_BLOCKS") != nullptr;       // comparison runs
     const bool bf16 = d->dtype == LC_BF16;
