@@ -190,13 +190,12 @@ def run_train_step(args):
     def gemm_kernel_of(l, pass_):
         """Which conv kernel instance a call ends in (mirrors the library's dispatch; labels only)."""
         cs = l.cs
-        # ResNet's first layer has kernels of its own (forward in both types, the filter gradient in fp32)
-        stem = ((cs.c, cs.k, cs.r, cs.s, cs.stride, cs.pad) == (3, 64, 7, 7, 2, 3) and cs.p % 16 == 0 and cs.q % 16 == 0
-                and not os.environ.get("LARSCONV_NO_STEM_DIRECT"))
-        if stem and (pass_ == "fwd" or (pass_ == "bwd_weight" and not bf16)):
-            return "conv_stem"
         if pass_ == "bwd_weight":
             return "wgrad"
+        # ResNet's first layer has a forward kernel of its own
+        if ((cs.c, cs.k, cs.r, cs.s, cs.stride, cs.pad) == (3, 64, 7, 7, 2, 3) and cs.p % 16 == 0 and cs.q % 16 == 0
+                and not os.environ.get("LARSCONV_NO_STEM_DIRECT")):
+            return "conv_stem"
         n_gemm = cs.k if pass_ == "fwd" else cs.c
         k_gemm = cs.c if pass_ == "fwd" else cs.k
         rows = cs.n * cs.p * cs.q if pass_ == "fwd" or cs.stride > 1 else cs.n * cs.h * cs.w
