@@ -319,6 +319,22 @@ lc_status batchnorm_fwd_pre(lc_dtype dtype, const void* x, const float* gamma, c
                             float* save_mean, float* save_invstd, int n, int c, int h, int w, float eps, int relu, lc_layout layout,
                             const float* stats, size_t stats_tiles, void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/* Two batch norms that meet in one sum: y = relu?(bn(x) + bn2(x2)), the output of a residual block whose shortcut has a
+ * projection (convolution + batch norm) in the residual networks the paper trains ("ImageNet training with ResNet-50").
+ * As batchnorm_fwd_t on (x2, gamma2, beta2) without ReLU followed by batchnorm_fwd_t on (x, gamma, beta) with that result
+ * as residual, except that the second batch norm's output is never stored: its statistics are made first (save_mean2,
+ * save_invstd2), its scale and shift go into the coefficients of the one stream pass that reads x and x2 and writes y.
+ * One tensor less written and read; in bf16 also one rounding less (the shortcut's value is not rounded to bf16 before
+ * the sum).  stats / stats2: the pieces conv2d_fwd_stats handed over for x / x2 (with their counts), or NULL: then a pass
+ * over that tensor makes its statistics (NULL is the only choice for NCHW).  Everything else -- layouts, types,
+ * alignment, workspace (batchnorm_workspace_bytes), errors -- as batchnorm_fwd_t; x2 and y must not be NULL.  The
+ * backward pass is two batchnorm_bwd_t calls on (x, dy) and (x2, dy) with the same dy, as without the fusion. */
+lc_status batchnorm_fwd_pair_t(lc_dtype dtype, const void* x, const float* gamma, const float* beta, const float* stats,
+                               size_t stats_tiles, const void* x2, const float* gamma2, const float* beta2, const float* stats2,
+                               size_t stats_tiles2, void* y, float* save_mean, float* save_invstd, float* save_mean2,
+                               float* save_invstd2, int n, int c, int h, int w, float eps, int relu, lc_layout layout, void* workspace,
+                               size_t workspace_bytes, void* hip_stream);
+
 /* Static, human-readable name of a status code. */
 const char* lc_status_string(lc_status status);
 

@@ -17,6 +17,11 @@ float32), the convolutions see the filters rounded to bf16, and everything a par
 statistics, every gradient of a parameter) as well as the pooled features, the classifier and the loss stay
 float32.
 
+``pair=True`` (both precisions): a value is rounded where it is stored, and a worker that computes the output of a
+block with a projection as relu(bn(c3) + bn(projection)) in one pass never stores the projection's batch-norm
+output; with ``pair`` that value enters the sum as computed.  Nothing else changes (the gradient that arrives at it is
+the block output's stored gradient either way).
+
 ``Config`` fixes the sizes: ResNet-50 is Config(stem=(64, 7, 2, 3), widths=(64, 128, 256, 512),
 blocks=(3, 4, 6, 3), classes=1000); tests use a few-channel version of the same graph.
 """
@@ -124,8 +129,8 @@ class _Net:
     layers (the trace a device is compared with) or keeps float64 (finite differences); ``bf16`` stores
     activations and their gradients as bf16 instead and hands the convolutions bf16 filters."""
 
-    def __init__(self, cfg: Config, params, store: bool, bf16: bool = False):
-        self.cfg, self.p, self.store, self.bf16 = cfg, params, store, bf16
+    def __init__(self, cfg: Config, params, store: bool, bf16: bool = False, pair: bool = False):
+        self.cfg, self.p, self.store, self.bf16, self.pair = cfg, params, store, bf16, pair
         self.t: Dict[str, np.ndarray] = {}
         self.g: Dict[str, np.ndarray] = {}
 
@@ -145,12 +150,13 @@ class _Net:
             return self.act(conv2d_fwd(_f32(x), self.filt(name), stride, pad, NCHW))
         return _conv_f64(x, np.asarray(self.p[name + ".w"], dtype=np.float64), stride, pad)
 
-    def conv_bn(self, x, name, stride, pad, relu, residual=None):
+    def conv_bn(self, x, name, stride, pad, relu, residual=None, stored=True):
         z = self.conv(x, name, stride, pad)
         y, _, _ = batchnorm.forward(z, self.p[name + ".gamma"], self.p[name + ".beta"], self.cfg.eps)
         if residual is not None:
             y = y + residual
-        a = self.act(np.maximum(y, 0.0) if relu else y)
+        a = np.maximum(y, 0.0) if relu else y
+        a = self.act(a) if stored else np.asarray(a, dtype=np.float64)     # not stored: handed on as computed, unrounded
         self.t[name + ".x"], self.t[name + ".z"], self.t[name + ".a"] = x, z, a
         self.t[name + ".y"] = y                # before the ReLU, unrounded: tests look at its distance from zero
         return a
@@ -184,7 +190,8 @@ class _Net:
                 stride = 2 if (bi == 0 and si > 0) else 1
                 name = f"s{si}b{bi}"
                 proj = ch != 4 * wd or stride != 1
-                sc = self.conv_bn(a, name + ".proj", stride, 0, relu=False) if proj else a
+                # (pair: the projection's batch-norm output goes straight into the block's sum and is never stored)
+                sc = self.conv_bn(a, name + ".proj", stride, 0, relu=False, stored=not self.pair) if proj else a
                 b = self.conv_bn(a, name + ".c1", stride, 0, relu=True)
                 b = self.conv_bn(b, name + ".c2", 1, 1, relu=True)
                 a = self.conv_bn(b, name + ".c3", 1, 0, relu=True, residual=sc)
@@ -235,22 +242,22 @@ def _conv_f64(x, w, stride, pad):
     return y
 
 
-def forward_backward(x, labels, params, cfg: Config):
+def forward_backward(x, labels, params, cfg: Config, pair: bool = False):
     """One forward and backward pass with float32 stores.  Returns (trace, grads): the trace holds
     "<conv>.z" (convolution output), "<conv>.y" (after batch norm and residual, before the ReLU, float64),
     "<conv>.a" (the stored activation), "<conv>.dz" / "<conv>.dx" (the stored gradients with respect to the
     convolution's output and input), "logits", "loss";
     grads has one entry per parameter name."""
-    net = _Net(cfg, params, store=True)
+    net = _Net(cfg, params, store=True, pair=pair)
     _, dlogits = net.forward(np.asarray(x, dtype=np.float32), labels)
     net.backward(dlogits)
     return net.t, net.g
 
 
-def forward_backward_bf16(x, labels, params, cfg: Config):
+def forward_backward_bf16(x, labels, params, cfg: Config, pair: bool = False):
     """The same pass with bf16 activations, activation gradients and convolution filters (see the module
     header); parameters and their gradients float32.  ``x`` is rounded to bf16 first.  Returns (trace, grads)."""
-    net = _Net(cfg, params, store=True, bf16=True)
+    net = _Net(cfg, params, store=True, bf16=True, pair=pair)
     _, dlogits = net.forward(np.asarray(x, dtype=np.float32), labels)
     net.backward(dlogits)
     return net.t, net.g

@@ -424,10 +424,19 @@ __device__ __forceinline__ bool channel_totals(const BnWorkspace& ws, const BnGe
 }
 
 // forward: mean, 1/std, and y = scale*x + shift (+ residual)
+// A second batch norm whose output is the residual of the first (its statistics already final): see batchnorm_fwd_pair_t.
+struct BnSecond {
+    const float* gamma = nullptr;
+    const float* beta = nullptr;
+    const float* mean = nullptr;
+    const float* inv_std = nullptr;
+};
+
 template <typename T>
 __global__ void __launch_bounds__(kFinChannels* kFinLanes)
 bn_finalize_fwd_kernel(BnWorkspace ws, const T* __restrict__ x, size_t pivot_stride, const float* __restrict__ gamma,
-                       const float* __restrict__ beta, float* __restrict__ save_mean, float* __restrict__ save_invstd, BnGeom g, float eps) {
+                       const float* __restrict__ beta, float* __restrict__ save_mean, float* __restrict__ save_invstd, BnGeom g, float eps,
+                       BnSecond second) {
     int ch;
     double s0, s1;
     if (!channel_totals(ws, g, &ch, &s0, &s1)) return;
@@ -442,8 +451,14 @@ bn_finalize_fwd_kernel(BnWorkspace ws, const T* __restrict__ x, size_t pivot_str
     save_invstd[ch] = inv_std_f;
     float scale, shift;
     scale_shift(gamma[ch], beta[ch], mean_f, inv_std_f, &scale, &shift);
+    float scale2 = 1.f;                    // the residual, when there is one, is added as it is ...
+    if (second.gamma) {                    // ... unless it is the input of a second batch norm, normalised on the way
+        float shift2;
+        scale_shift(second.gamma[ch], second.beta[ch], second.mean[ch], second.inv_std[ch], &scale2, &shift2);
+        shift += shift2;
+    }
     ws.coef[ch] = scale;
-    ws.coef[g.C + ch] = 1.f;               // the residual, when there is one, is added as it is
+    ws.coef[g.C + ch] = scale2;
     ws.coef[2 * g.C + ch] = shift;
 }
 
@@ -552,14 +567,17 @@ constexpr int kWide = 16 / (int)sizeof(T);
 template <typename T>
 lc_status bn_fwd_impl(const T* x, const float* gamma, const float* beta, const T* residual, T* y, float* save_mean, float* save_invstd,
                       int n, int c, int h, int w, float eps, int relu, lc_layout layout, void* workspace, size_t workspace_bytes,
-                      void* hip_stream, const float* stats = nullptr, size_t stats_tiles = 0) {
+                      void* hip_stream, const float* stats = nullptr, size_t stats_tiles = 0, bool stats_only = false,
+                      BnSecond second = BnSecond{}, bool check_only = false) {
     constexpr bool kF32 = sizeof(T) == 4;
-    if (!x || !gamma || !beta || !y || !save_mean || !save_invstd) return LC_ERR_NULL;
+    if (!x || !gamma || !beta || (!y && !stats_only) || !save_mean || !save_invstd) return LC_ERR_NULL;
+    if (second.gamma && !residual) return LC_ERR_NULL;
     if (layout != LC_NCHW && layout != LC_NHWC) return LC_ERR_UNSUPPORTED;
     if (!(eps >= 0.f)) return LC_ERR_SHAPE;
     BnGeom g;
     if (!geometry(n, c, h, w, layout, al16(x) && al16(y) && al16(residual), &g, kWide<T>)) return LC_ERR_SHAPE;
     if (!al4(x) || !al4(y) || !al4(residual) || !al4(gamma) || !al4(beta) || !al4(save_mean) || !al4(save_invstd)) return LC_ERR_ALIGN;
+    if (!al4(second.gamma) || !al4(second.beta) || !al4(second.mean) || !al4(second.inv_std)) return LC_ERR_ALIGN;
     if (!kF32 && layout != LC_NHWC) return LC_ERR_UNSUPPORTED;
     if (!kF32 && g.vec != kWide<T>) return c % kWide<T> ? LC_ERR_UNSUPPORTED : LC_ERR_ALIGN;
     if (stats && (layout != LC_NHWC || stats_tiles == 0 || stats_tiles > 0x7fffffffull)) return LC_ERR_UNSUPPORTED;
@@ -567,6 +585,7 @@ lc_status bn_fwd_impl(const T* x, const float* gamma, const float* beta, const T
     size_t coef_off;
     const size_t need = ws_layout(g, &coef_off);
     if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255) || workspace_bytes < need) return LC_ERR_WORKSPACE;
+    if (check_only) return LC_OK;          // (a caller that launches something else first wants every argument checked before)
     BnWorkspace ws;
     ws.partial = static_cast<double*>(workspace);
     ws.coef = reinterpret_cast<float*>(static_cast<char*>(workspace) + coef_off);
@@ -599,13 +618,14 @@ lc_status bn_fwd_impl(const T* x, const float* gamma, const float* beta, const T
             hipLaunchKernelGGL(bn_fold_pieces_kernel, dim3((unsigned)g.slabs, (unsigned)((2 * c + kThreads - 1) / kThreads)),           \
                                dim3(kThreads), 0, stream, stats, (int)stats_tiles, ws.partial, g.slabs, 2 * c);                         \
             hipLaunchKernelGGL(bn_finalize_fwd_kernel<T>, fin_grid, fin_block, 0, stream, ws, none, pivot_stride, gamma, beta,          \
-                               save_mean, save_invstd, g, eps);                                                                         \
+                               save_mean, save_invstd, g, eps, second);                                                                 \
         } else {                                                                                                                        \
             hipLaunchKernelGGL((bn_reduce_nhwc_kernel<T, VEC, kStats>), grid, dim3(kThreads), 0, stream, x, none, nonef, nonef, nonef,  \
                                nonef, g, ws);                                                                                           \
             hipLaunchKernelGGL(bn_finalize_fwd_kernel<T>, fin_grid, fin_block, 0, stream, ws, x, pivot_stride, gamma, beta, save_mean,  \
-                               save_invstd, g, eps);                                                                                    \
+                               save_invstd, g, eps, second);                                                                            \
         }                                                                                                                               \
+        if (stats_only) break;                                                                                                          \
         if (two) { if (clamp) LC_BN_APPLY(VEC, true, true); else LC_BN_APPLY(VEC, true, false); }                                       \
         else { if (clamp) LC_BN_APPLY(VEC, false, true); else LC_BN_APPLY(VEC, false, false); }                                         \
     } while (0)
@@ -621,16 +641,41 @@ lc_status bn_fwd_impl(const T* x, const float* gamma, const float* beta, const T
             hipLaunchKernelGGL((bn_reduce_nchw_kernel<kStats>), dim3((unsigned)g.slabs, (unsigned)c), dim3(kThreads), 0, stream, x, none, nonef,
                                nonef, nonef, nonef, g, ws);
             hipLaunchKernelGGL(bn_finalize_fwd_kernel<T>, fin_grid, fin_block, 0, stream, ws, x, pivot_stride, gamma, beta, save_mean,
-                               save_invstd, g, eps);
+                               save_invstd, g, eps, second);
             const dim3 agrid(stream_blocks(total));
 #define LC_BN_APPLY(TWO, RELU) \
     hipLaunchKernelGGL((bn_apply_nchw_kernel<TWO, RELU, false>), agrid, dim3(kThreads), 0, stream, x, residual, y, ws.coef, g)
+            if (stats_only) return lc_end_call();
             if (two) { if (clamp) LC_BN_APPLY(true, true); else LC_BN_APPLY(true, false); }
             else { if (clamp) LC_BN_APPLY(false, true); else LC_BN_APPLY(false, false); }
 #undef LC_BN_APPLY
         }
     }
     return lc_end_call();
+}
+
+// y = relu?(bn(x) + bn2(x2)): the statistics of the second batch norm first (no stream pass), then the first with the
+// second's scale and shift folded into its residual coefficients, one stream pass over x and x2.
+template <typename T>
+lc_status bn_fwd_pair_impl(const T* x, const float* gamma, const float* beta, const float* stats, size_t stats_tiles, const T* x2,
+                           const float* gamma2, const float* beta2, const float* stats2, size_t stats_tiles2, T* y, float* save_mean,
+                           float* save_invstd, float* save_mean2, float* save_invstd2, int n, int c, int h, int w, float eps, int relu,
+                           lc_layout layout, void* workspace, size_t workspace_bytes, void* hip_stream) {
+    if (!x2 || !y) return LC_ERR_NULL;
+    BnSecond second;
+    second.gamma = gamma2;
+    second.beta = beta2;
+    second.mean = save_mean2;
+    second.inv_std = save_invstd2;
+    // both calls' arguments are checked before the first launches anything
+    lc_status st = bn_fwd_impl<T>(x, gamma, beta, x2, y, save_mean, save_invstd, n, c, h, w, eps, relu, layout, workspace, workspace_bytes,
+                                  hip_stream, stats, stats_tiles, false, second, true);
+    if (st != LC_OK) return st;
+    st = bn_fwd_impl<T>(x2, gamma2, beta2, nullptr, nullptr, save_mean2, save_invstd2, n, c, h, w, eps, 0, layout, workspace,
+                        workspace_bytes, hip_stream, stats2, stats_tiles2, true);
+    if (st != LC_OK) return st;
+    return bn_fwd_impl<T>(x, gamma, beta, x2, y, save_mean, save_invstd, n, c, h, w, eps, relu, layout, workspace, workspace_bytes,
+                          hip_stream, stats, stats_tiles, false, second);
 }
 
 template <typename T>
@@ -796,6 +841,22 @@ extern "C" lc_status batchnorm_fwd_pre(lc_dtype dtype, const void* x, const floa
         return bn_fwd_impl<uint16_t>(static_cast<const uint16_t*>(x), gamma, beta, static_cast<const uint16_t*>(residual),
                                      static_cast<uint16_t*>(y), save_mean, save_invstd, n, c, h, w, eps, relu, layout, workspace,
                                      workspace_bytes, hip_stream, stats, stats_tiles);
+    return LC_ERR_UNSUPPORTED;
+}
+
+extern "C" lc_status batchnorm_fwd_pair_t(lc_dtype dtype, const void* x, const float* gamma, const float* beta, const float* stats,
+                                          size_t stats_tiles, const void* x2, const float* gamma2, const float* beta2, const float* stats2,
+                                          size_t stats_tiles2, void* y, float* save_mean, float* save_invstd, float* save_mean2,
+                                          float* save_invstd2, int n, int c, int h, int w, float eps, int relu, lc_layout layout,
+                                          void* workspace, size_t workspace_bytes, void* hip_stream) {
+    if (dtype == LC_F32)
+        return bn_fwd_pair_impl<float>(static_cast<const float*>(x), gamma, beta, stats, stats_tiles, static_cast<const float*>(x2), gamma2,
+                                       beta2, stats2, stats_tiles2, static_cast<float*>(y), save_mean, save_invstd, save_mean2, save_invstd2,
+                                       n, c, h, w, eps, relu, layout, workspace, workspace_bytes, hip_stream);
+    if (dtype == LC_BF16)
+        return bn_fwd_pair_impl<uint16_t>(static_cast<const uint16_t*>(x), gamma, beta, stats, stats_tiles, static_cast<const uint16_t*>(x2),
+                                          gamma2, beta2, stats2, stats_tiles2, static_cast<uint16_t*>(y), save_mean, save_invstd, save_mean2,
+                                          save_invstd2, n, c, h, w, eps, relu, layout, workspace, workspace_bytes, hip_stream);
     return LC_ERR_UNSUPPORTED;
 }
 

@@ -27,7 +27,7 @@ EXPORTS = ["conv2d_out_shape", "conv2d_workspace_bytes", "conv2d_fwd", "conv2d_b
            "batchnorm_workspace_bytes", "batchnorm_fwd", "batchnorm_bwd", "batchnorm_fwd_ex", "batchnorm_bwd_ex",
            "batchnorm_fwd_t", "batchnorm_bwd_t", "maxpool_fwd_t", "maxpool_bwd_t", "relu_add_bwd_t", "global_avgpool_fwd_t",
            "global_avgpool_bwd_t", "relu_add_bwd_bnsums_t", "batchnorm_bwd_presummed_t",
-           "conv2d_fwd_stats_count", "conv2d_fwd_stats", "batchnorm_fwd_pre",
+           "conv2d_fwd_stats_count", "conv2d_fwd_stats", "batchnorm_fwd_pre", "batchnorm_fwd_pair_t",
            "lc_status_string", "lc_last_error_detail"]
 
 
@@ -154,6 +154,9 @@ def lib() -> ctypes.CDLL:
         L.conv2d_fwd_stats_count.argtypes = [dp]
         L.conv2d_fwd_stats.restype = i32
         L.conv2d_fwd_stats.argtypes = [dp, vp, vp, vp, vp, vp, sz, vp]
+        L.batchnorm_fwd_pair_t.restype = i32
+        L.batchnorm_fwd_pair_t.argtypes = [i32, vp, vp, vp, vp, sz, vp, vp, vp, vp, sz, vp, vp, vp, vp, vp, i32, i32, i32, i32, ctypes.c_float,
+                                           i32, i32, vp, sz, vp]
         L.batchnorm_fwd_pre.restype = i32
         L.batchnorm_fwd_pre.argtypes = [i32, vp, vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, ctypes.c_float, i32, i32, vp, sz, vp, sz, vp]
         L.lc_status_string.restype = ctypes.c_char_p
@@ -482,6 +485,15 @@ def conv2d_fwd_stats(desc, x, w, y, stats, workspace=None, stream=None, workspac
     nb = _nbytes(workspace) if workspace_bytes is None else workspace_bytes
     _check(lib().conv2d_fwd_stats(ctypes.byref(_desc(desc)), _ptr(x), _ptr(w), _ptr(y), _ptr(stats), _ptr(workspace), nb,
                                   _stream(stream)), "conv2d_fwd_stats")
+
+
+def batchnorm_fwd_pair_t(dtype: int, x, gamma, beta, stats, stats_tiles: int, x2, gamma2, beta2, stats2, stats_tiles2: int, y, save_mean,
+                         save_invstd, save_mean2, save_invstd2, n: int, c: int, h: int, w: int, eps: float, relu: bool, layout: int,
+                         workspace, stream=None) -> None:
+    _check(lib().batchnorm_fwd_pair_t(dtype, _ptr(x), _ptr(gamma), _ptr(beta), _ptr(stats), stats_tiles, _ptr(x2), _ptr(gamma2), _ptr(beta2),
+                                      _ptr(stats2), stats_tiles2, _ptr(y), _ptr(save_mean), _ptr(save_invstd), _ptr(save_mean2),
+                                      _ptr(save_invstd2), n, c, h, w, eps, int(bool(relu)), layout, _ptr(workspace), _nbytes(workspace),
+                                      _stream(stream)), "batchnorm_fwd_pair_t")
 
 
 def batchnorm_fwd_pre(dtype: int, x, gamma, beta, residual, y, save_mean, save_invstd, n: int, c: int, h: int, w: int, eps: float,

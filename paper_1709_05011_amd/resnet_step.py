@@ -42,9 +42,10 @@ class _ConvBn:
 class ResNetStep:
     def __init__(self, stem: Tuple[int, int, int, int], widths: Sequence[int], blocks: Sequence[int], classes: int, batch: int,
                  image_hw: Tuple[int, int], in_channels: int = 3, eps: float = 1e-5, device: str = "cuda:0", dtype: int = lc.LC_F32,
-                 join_sums: bool = True, fuse_stats: bool = True):
+                 join_sums: bool = True, fuse_stats: bool = True, pair_bn: bool = True):
         lc.lib()                     # fails here, loudly, when the library has not been built
         self.join_sums = join_sums   # False: the block-output gradient and the batch-norm sums behind it as two plain calls
+        self.pair_bn = pair_bn       # False: a projection's batch norm writes its output, which the block's last batch norm then adds
         self.dev, self.eps, self.batch, self.classes = device, eps, batch, classes
         self.dtype = dtype
         self._act = torch.bfloat16 if dtype == lc.LC_BF16 else torch.float32        # storage type of activations
@@ -111,6 +112,9 @@ class ResNetStep:
                                             for name in self.order}
         most = max([t * self.layers[name].desc.k * 2 for name, t in self.stats_tiles.items()] + [2])
         self._stats = torch.empty(most, dtype=torch.float32, device=device)
+        # a projection's statistics wait for the block's last convolution (batchnorm_fwd_pair_t takes both): a buffer of their own
+        most_proj = max([t * self.layers[name].desc.k * 2 for name, t in self.stats_tiles.items() if name.endswith(".proj")] + [2])
+        self._stats_proj = torch.empty(most_proj, dtype=torch.float32, device=device)
 
         # one workspace for every convolution pass and every batch norm
         need = 0
@@ -127,7 +131,9 @@ class ResNetStep:
         for name in self.order:
             L = self.layers[name]
             shape = (batch, L.out_hw[0], L.out_hw[1], L.desc.k)
-            L.z, L.a = torch.empty(shape, dtype=self._act, device=device), torch.empty(shape, dtype=self._act, device=device)
+            L.z = torch.empty(shape, dtype=self._act, device=device)
+            # (with pair_bn a projection's batch-norm output is never stored)
+            L.a = None if pair_bn and name.endswith(".proj") else torch.empty(shape, dtype=self._act, device=device)
             L.mean, L.invstd = torch.empty(L.desc.k, **f32), torch.empty(L.desc.k, **f32)
         self.pool_out = torch.empty((batch, self.pool_out_hw[0], self.pool_out_hw[1], stem[0]), dtype=self._act, device=device)
         self.pool_idx = torch.empty(self.pool_out.shape, dtype=torch.uint8, device=device)
@@ -181,6 +187,25 @@ class ResNetStep:
                                L.invstd, self.batch, k, p, q, self.eps, L.relu or relu_after_residual, NHWC, self._ws)
         return L.a
 
+    def _conv_only(self, name: str, x: torch.Tensor, stats: torch.Tensor) -> None:
+        L = self.layers[name]
+        L.x = x
+        if self.stats_tiles[name]:
+            lc.conv2d_fwd_stats(L.desc, x, self._filter(name), L.z, stats, self._ws)
+        else:
+            lc.conv2d_fwd(L.desc, x, self._filter(name), L.z, self._ws)
+
+    def _conv_bn_pair(self, name: str, x: torch.Tensor, other: str) -> torch.Tensor:
+        """The block's last convolution, then relu(bn(its output) + bn_other(the projection's output)) in one pass."""
+        self._conv_only(name, x, self._stats)
+        L, O = self.layers[name], self.layers[other]
+        k, (p, q) = L.desc.k, L.out_hw
+        t1, t2 = self.stats_tiles[name], self.stats_tiles[other]
+        lc.batchnorm_fwd_pair_t(self.dtype, L.z, self.params[name + ".gamma"], self.params[name + ".beta"], self._stats if t1 else None, t1,
+                                O.z, self.params[other + ".gamma"], self.params[other + ".beta"], self._stats_proj if t2 else None, t2,
+                                L.a, L.mean, L.invstd, O.mean, O.invstd, self.batch, k, p, q, self.eps, True, NHWC, self._ws)
+        return L.a
+
     def _conv_bn_bwd(self, name: str, da: torch.Tensor, need_dx: bool = True, presummed: bool = False) -> Optional[torch.Tensor]:
         """``da``: gradient with respect to the layer's output -- of the fused ReLU's output where the layer has
         one, otherwise of the batch-norm output itself (the caller has applied the block's last ReLU).  ``presummed``: the
@@ -211,6 +236,13 @@ class ResNetStep:
         lc.maxpool_fwd_t(self.dtype, a, self.pool_out, self.pool_idx, n, c0, self.pool_in_hw[0], self.pool_in_hw[1], 3, 2, 1, NHWC)
         a = self.pool_out
         for name, proj in self.blocks:
+            if proj and self.pair_bn:
+                # the projection's convolution now, its batch norm together with the block's last one: relu(bn(c3) + bn(proj))
+                self._conv_only(name + ".proj", a, self._stats_proj)
+                b = self._conv_bn(name + ".c1", a)
+                b = self._conv_bn(name + ".c2", b)
+                a = self._conv_bn_pair(name + ".c3", b, name + ".proj")
+                continue
             sc = self._conv_bn(name + ".proj", a) if proj else a
             b = self._conv_bn(name + ".c1", a)
             b = self._conv_bn(name + ".c2", b)

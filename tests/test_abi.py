@@ -365,6 +365,20 @@ def test_statistics_entry_points_reject_bad_arguments_before_launch():
     assert pre(ctypes.c_void_p(FAKE + 4), count) == lc.LC_ERR_ALIGN
     assert pre(P, count, dt=5) == lc.LC_ERR_UNSUPPORTED
     assert pre(P, count, nb=256) == lc.LC_ERR_WORKSPACE
+    # the two batch norms of a projection block in one pass: every argument is checked before anything is launched
+    def pair(x=P, x2=P, y=P, g2=P, st=None, tiles=0, st2=None, tiles2=0, lay=lc.LC_NHWC, dt=lc.LC_F32, nb=bneed, m2=P):
+        return L.batchnorm_fwd_pair_t(dt, x, P, P, st, tiles, x2, g2, P, st2, tiles2, y, P, P, m2, P, 4, 128, 14, 14, 1e-5, 1, lay, P, nb, None)
+    assert pair(x2=None) == lc.LC_ERR_NULL
+    assert pair(y=None) == lc.LC_ERR_NULL
+    assert pair(x=None) == lc.LC_ERR_NULL
+    assert pair(g2=None) == lc.LC_ERR_NULL
+    assert pair(m2=None) == lc.LC_ERR_NULL
+    assert pair(dt=5) == lc.LC_ERR_UNSUPPORTED
+    assert pair(nb=256) == lc.LC_ERR_WORKSPACE
+    assert pair(st2=P, tiles2=0) == lc.LC_ERR_UNSUPPORTED                  # pieces without a count
+    assert pair(st2=ctypes.c_void_p(FAKE + 4), tiles2=count) == lc.LC_ERR_ALIGN
+    assert pair(st2=P, tiles2=count, lay=lc.LC_NCHW) == lc.LC_ERR_UNSUPPORTED
+    assert pair(x2=ctypes.c_void_p(FAKE + 2)) == lc.LC_ERR_ALIGN
 
 
 def test_poly_lr_host_arithmetic():

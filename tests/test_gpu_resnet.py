@@ -50,9 +50,12 @@ def _from_device_layout(name, a, ref_shape):
     return a.reshape(ref_shape)
 
 
-def test_whole_training_step_matches_oracle():
+@pytest.mark.parametrize("pair", [True, False], ids=["paired_batch_norms", "plain_batch_norms"])
+def test_whole_training_step_matches_oracle(pair):
+    """``pair``: the blocks with a projection compute relu(bn(c3) + bn(projection)) in one pass (batchnorm_fwd_pair_t) and
+    never store the projection's batch-norm output; the oracle then hands that value on unrounded as well."""
     x, labels, params = _problem(4100)
-    trace, grads = ores.forward_backward(x, labels, params, CFG)
+    trace, grads = ores.forward_backward(x, labels, params, CFG, pair=pair)
 
     # premises: no ReLU input within 5e-6 of zero, no max-pool window whose two largest values are closer than 2e-5
     for key, val in trace.items():
@@ -66,8 +69,9 @@ def test_whole_training_step_matches_oracle():
     contested = top2[..., 1] > 0.0                                     # all-zero windows tie exactly on both sides
     assert np.min((top2[..., 1] - top2[..., 0])[contested]) > 2e-5
 
-    net = ResNetStep(CFG.stem, CFG.widths, CFG.blocks, CFG.classes, BATCH, (HW, HW))
+    net = ResNetStep(CFG.stem, CFG.widths, CFG.blocks, CFG.classes, BATCH, (HW, HW), pair_bn=pair)
     assert list(net.params) == list(params)
+    assert any(L.a is None for L in net.layers.values()) == pair
     for k, v in params.items():
         net.params[k].copy_(torch.from_numpy(_to_device_layout(k, v)))
     xd = gu.dev(np.ascontiguousarray(x.transpose(0, 2, 3, 1)))
@@ -81,7 +85,8 @@ def test_whole_training_step_matches_oracle():
     for name in net.order:
         L = net.layers[name]
         assert gu.scaled_err(L.z.cpu().numpy().transpose(0, 3, 1, 2), trace[name + ".z"]) <= TOL, name
-        assert gu.scaled_err(L.a.cpu().numpy().transpose(0, 3, 1, 2), trace[name + ".a"]) <= TOL, name
+        if L.a is not None:                                          # (a projection's output is not stored when paired)
+            assert gu.scaled_err(L.a.cpu().numpy().transpose(0, 3, 1, 2), trace[name + ".a"]) <= TOL, name
     worst = 0.0
     for k in params:
         got = _from_device_layout(k, net.grads[k].cpu().numpy(), grads[k].shape)

@@ -5,6 +5,7 @@ import pytest
 import torch
 import torch.nn.functional as F
 
+import oracle
 from oracle import resnet, tiny_cnn
 from paper_1709_05011_amd import synth
 
@@ -181,6 +182,32 @@ def _is_bf16(a):
     return not np.any(np.ascontiguousarray(a, dtype=np.float32).view(np.uint32) & np.uint32(0xFFFF))
 
 
+def test_unstored_shortcut_changes_roundings_only():
+    """pair=True hands the projection's batch-norm output on unrounded: in the float32 trace that moves the block outputs by
+    float32 rounding at most, in the bf16 trace by a bf16 step at most and in a minority of elements; the projection's
+    own trace entry is then the unrounded value, whose rounding is the stored one."""
+    x, labels, params = _mini_problem(seed=23)
+    t0, g0 = resnet.forward_backward(x, labels, params, MINI)
+    t1, g1 = resnet.forward_backward(x, labels, params, MINI, pair=True)
+    projs = [k[:-2] for k in t0 if k.endswith(".proj.a")]
+    assert projs
+    first = projs[0][:-len(".proj")]                                                          # (later blocks see changed inputs)
+    assert np.array_equal(t0[first + ".proj.a"], t1[first + ".proj.a"].astype(np.float32))   # same value, stored or not
+    for name in projs:
+        blk = name[:-len(".proj")]
+        d = np.abs(t0[blk + ".c3.a"] - t1[blk + ".c3.a"])
+        assert d.max() <= 1e-5 * np.abs(t0[blk + ".c3.a"]).max()
+    assert abs(t0["loss"] - t1["loss"]) <= 1e-6 * t0["loss"]
+    b0, _ = resnet.forward_backward_bf16(x, labels, params, MINI)
+    b1, _ = resnet.forward_backward_bf16(x, labels, params, MINI, pair=True)
+    assert np.array_equal(b0[first + ".proj.z"], b1[first + ".proj.z"])
+    assert np.array_equal(b0[first + ".proj.a"], oracle.round_to_bf16(b1[first + ".proj.a"]))
+    a0, a1 = b0[first + ".c3.a"], b1[first + ".c3.a"]
+    assert _is_bf16(a1) and 0.5 < np.mean(a0 == a1) < 1.0
+    # the shortcut's value moves by half a bf16 step of its own size at most, the sum is then rounded once
+    assert np.all(np.abs(a0 - a1) <= 2.0 ** -8 * np.abs(b1[first + ".proj.a"]) + 2.0 ** -7 * np.maximum(np.abs(a0), np.abs(a1)) + 1e-30)
+
+
 def test_bf16_trace_stores_bf16_values_and_float32_parameter_gradients():
     x, labels, params = _mini_problem(seed=17)
     trace, grads = resnet.forward_backward_bf16(x, labels, params, MINI)
@@ -201,13 +228,15 @@ def test_bf16_trace_stores_bf16_values_and_float32_parameter_gradients():
     assert 0.0 < num < 0.5 ** 2 * den
 
 
-def test_bf16_trace_matches_torch_with_rounding_at_the_same_places():
+@pytest.mark.parametrize("pair", [False, True], ids=["shortcut_stored", "shortcut_not_stored"])
+def test_bf16_trace_matches_torch_with_rounding_at_the_same_places(pair):
     """An independent run of the same graph: torch float64 autograd, with torch's own bfloat16 cast applied (value
     replaced, gradient passed straight through) to every stored activation and to the filters, and a hook that
     rounds the gradient wherever the trace stores one.  The two differ only where float32 rounding of a stored
-    gradient of a parameter moves a later value across a bf16 rounding boundary: isolated elements, one bf16 step."""
+    gradient of a parameter moves a later value across a bf16 rounding boundary: isolated elements, one bf16 step.
+    ``pair``: the projection's batch-norm output is not stored, so torch does not round it either."""
     x, labels, params = _mini_problem(seed=19)
-    trace, grads = resnet.forward_backward_bf16(x, labels, params, MINI)
+    trace, grads = resnet.forward_backward_bf16(x, labels, params, MINI, pair=pair)
     tp = {k: torch.from_numpy(v.astype(np.float64)).requires_grad_(True) for k, v in params.items()}
 
     def rnd(t):
@@ -239,7 +268,11 @@ def test_bf16_trace_matches_torch_with_rounding_at_the_same_places():
         for bi in range(nb):
             stride = 2 if (bi == 0 and si > 0) else 1
             name = f"s{si}b{bi}"
-            sc = store(cbn(a, name + ".proj", stride, 0)) if (ch != 4 * wd or stride != 1) else a
+            if ch != 4 * wd or stride != 1:
+                sc = cbn(a, name + ".proj", stride, 0)
+                sc = sc if pair else store(sc)
+            else:
+                sc = a
             b = store(F.relu(cbn(a, name + ".c1", stride, 0)))
             b = store(F.relu(cbn(b, name + ".c2", 1, 1)))
             a = store(F.relu(cbn(b, name + ".c3", 1, 0) + sc))
