@@ -1,6 +1,8 @@
-// ResNet's first layer, forward and filter gradient, in fp32 and bf16 (7x7 window, stride 2, padding 3, 3 -> 64 channels, NHWC) from an input slab in
-// LDS (the paper's ResNet-50, "ImageNet training with ResNet-50"; the layer is 2 % of the network's multiplications and was
-// 4 % of the step's time on the general kernel).
+// ResNet's first layer (7x7 window, stride 2, padding 3, 3 -> 64 channels, NHWC, output height and width multiples of 16):
+// forward pass and filter gradient, each in fp32 and in bf16, from an input slab in LDS.  The layer is the first of the
+// paper's ResNet-50 ("ImageNet training with ResNet-50"): 2 % of the network's multiplications, 4 % of the step's time on
+// the general kernels.  Four kernels: conv_stem_f32_kernel (described first), conv_stem_wgrad_f32_kernel,
+// conv_stem_bf16_kernel, conv_stem_wgrad_bf16_kernel; lc_conv_stem_f32_ok() is the shape test for all of them.
 //
 // The general kernel pads the three channels to four (a pass over the input and 25 % more multiplications) and gathers every
 // window element with per-lane address arithmetic.  Here a block owns 16 x 16 output pixels: their 37 x 37 input pixels
