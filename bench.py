@@ -566,7 +566,8 @@ def run_full_step(args):
     else:
         net = ResNetStep((64, 7, 2, 3), (64, 128, 256, 512), (3, 4, 6, 3), 1000, batch, (224, 224),
                          dtype=lc.LC_BF16 if bf16 else lc.LC_F32, join_sums=not args.no_join, fuse_stats=not args.no_fused_stats,
-                         pair_bn=not args.no_pair)
+                         pair_bn=not args.no_pair,
+                         side_wgrad=not args.no_side_stream and not args.graph)     # (replays of a captured step gain nothing from the second stream)
     side = 227 if alex else 224
     label = f"{'AlexNet-BN' if alex else 'ResNet-50'} whole training step (all layers + LARS), batch {batch}, {side}x{side}, NHWC"
     if bf16:
@@ -751,6 +752,8 @@ def main():
                     help="--full-step: batch norm sums its input itself instead of taking the sums from the convolution's epilogue")
     ap.add_argument("--no-pair", action="store_true",
                     help="with --full-step: the two batch norms at the output of a projection block as two plain passes")
+    ap.add_argument("--no-side-stream", action="store_true",
+                    help="with --full-step: the filter gradients on the main stream instead of a second one")
     ap.add_argument("--graph", action="store_true", help="--full-step: capture the step in a HIP graph and time replays")
     ap.add_argument("--copy-calib", action="store_true", help="run a 1 GiB device copy (counter calibration)")
     ap.add_argument("--batch-curve", action="store_true", help="images/s against the per-GPU batch (headline step and whole step)")

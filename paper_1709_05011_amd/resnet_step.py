@@ -42,9 +42,14 @@ class _ConvBn:
 class ResNetStep:
     def __init__(self, stem: Tuple[int, int, int, int], widths: Sequence[int], blocks: Sequence[int], classes: int, batch: int,
                  image_hw: Tuple[int, int], in_channels: int = 3, eps: float = 1e-5, device: str = "cuda:0", dtype: int = lc.LC_F32,
-                 join_sums: bool = True, fuse_stats: bool = True, pair_bn: bool = True):
+                 join_sums: bool = True, fuse_stats: bool = True, pair_bn: bool = True, side_wgrad: bool = True):
         lc.lib()                     # fails here, loudly, when the library has not been built
         self.join_sums = join_sums   # False: the block-output gradient and the batch-norm sums behind it as two plain calls
+        # The filter gradient of a layer and the gradient of its input both need only dz, and nothing before lars_step reads a
+        # filter gradient: with side_wgrad the backward-weight calls go to a second stream (default priority, a workspace of
+        # its own), which joins the main one before lars_step.  Same kernels on the same operands: the results do not change.
+        self._side = torch.cuda.Stream(device=device) if side_wgrad else None
+        self._keep: List[torch.Tensor] = []     # the dz tensors the second stream still reads (held until the join)
         self.pair_bn = pair_bn       # False: a projection's batch norm writes its output, which the block's last batch norm then adds
         self.dev, self.eps, self.batch, self.classes = device, eps, batch, classes
         self.dtype = dtype
@@ -126,6 +131,7 @@ class ResNetStep:
         for p in (lc.LC_PASS_FWD, lc.LC_PASS_BWD_DATA, lc.LC_PASS_BWD_WEIGHT):
             need = max(need, lc.conv2d_workspace_bytes(self.fc_desc, p))
         self._ws = self._bytes(need)
+        self._ws_side = self._bytes(need) if self._side is not None else None
 
         # activations that the backward pass reads stay allocated; gradients of activations come and go
         for name in self.order:
@@ -219,7 +225,15 @@ class ResNetStep:
         else:
             lc.batchnorm_bwd_t(self.dtype, L.z, da, self.params[name + ".gamma"], self.params[name + ".beta"], L.mean, L.invstd, dz,
                                self.grads[name + ".gamma"], self.grads[name + ".beta"], self.batch, k, p, q, L.relu, NHWC, self._ws)
-        lc.conv2d_bwd_weight_sq(L.desc, L.x, dz, self.grads[name + ".w"], self.gsq[name + ".w"], self._ws)
+        if self._side is not None:
+            ev = torch.cuda.Event()
+            ev.record()
+            with torch.cuda.stream(self._side):
+                self._side.wait_event(ev)
+                lc.conv2d_bwd_weight_sq(L.desc, L.x, dz, self.grads[name + ".w"], self.gsq[name + ".w"], self._ws_side)
+            self._keep.append(dz)
+        else:
+            lc.conv2d_bwd_weight_sq(L.desc, L.x, dz, self.grads[name + ".w"], self.gsq[name + ".w"], self._ws)
         if not need_dx:
             return None
         dx = self._new(L.x)
@@ -285,6 +299,9 @@ class ResNetStep:
         da = self._new(stem.a)
         lc.maxpool_bwd_t(self.dtype, d_pool, self.pool_idx, da, n, stem.desc.k, self.pool_in_hw[0], self.pool_in_hw[1], 3, 2, 1, NHWC)
         self._conv_bn_bwd("stem", da, need_dx=False)
+        if self._side is not None:
+            torch.cuda.current_stream().wait_stream(self._side)
+            self._keep.clear()
 
     def lars(self, eta: float, momentum: float, weight_decay: float, lr: float) -> None:
         lc.lars_step_pre(self._lars, eta, momentum, weight_decay, lr, self._gsq_list, self._gsq_counts, trust_out=self.trust,

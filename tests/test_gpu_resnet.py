@@ -137,6 +137,29 @@ def test_second_step_runs_on_updated_weights_and_lowers_the_loss():
     assert losses[1] < losses[0] and losses[2] < losses[1], losses
 
 
+def test_second_stream_for_filter_gradients_changes_no_bit():
+    """The step walker sends its backward-weight calls to a second stream (the filter gradient and the input gradient of a
+    layer both wait only for dz) and joins it before lars_step.  Same kernels on the same operands: after three steps every
+    gradient, weight and velocity equals, bit for bit, what the single-stream walker leaves."""
+    x, labels, params = _problem(4300)
+    xd = gu.dev(np.ascontiguousarray(x.transpose(0, 2, 3, 1)))
+    ld = gu.dev(labels.astype(np.int32))
+    nets = []
+    for side in (True, False):
+        net = ResNetStep(CFG.stem, CFG.widths, CFG.blocks, CFG.classes, BATCH, (HW, HW), side_wgrad=side)
+        for k, v in params.items():
+            net.params[k].copy_(torch.from_numpy(_to_device_layout(k, v)))
+        losses = [float(net.step(xd, ld, 0.02, 0.9, 1e-4, 1.0).item()) for _ in range(3)]
+        torch.cuda.synchronize()
+        nets.append((net, losses))
+    (a, la), (b, lb) = nets
+    assert la == lb
+    for k in a.params:
+        assert torch.equal(a.grads[k], b.grads[k]), k
+        assert torch.equal(a.params[k], b.params[k]), k
+        assert torch.equal(a.velocity[k], b.velocity[k]), k
+
+
 def test_resnet50_graph_at_small_images_trains():
     """The real ResNet-50 graph (53 convolutions, 161 tensors, 25,557,032 parameters) on 64x64 images at batch 8:
     every layer shape of the network goes through the library, the loss stays finite and the first step lowers it.  (Parity of the arithmetic is checked on the few-channel graph above; at this size fp32 and float64 no
