@@ -567,7 +567,7 @@ def run_full_step(args):
         net = ResNetStep((64, 7, 2, 3), (64, 128, 256, 512), (3, 4, 6, 3), 1000, batch, (224, 224),
                          dtype=lc.LC_BF16 if bf16 else lc.LC_F32, join_sums=not args.no_join, fuse_stats=not args.no_fused_stats,
                          pair_bn=not args.no_pair,
-                         side_wgrad=not args.no_side_stream and not args.graph)     # (replays of a captured step gain nothing from the second stream)
+                         side_wgrad=not args.no_side_stream and not args.graph, grid_grads=not args.no_grid_grads)     # (replays of a captured step gain nothing from the second stream)
     side = 227 if alex else 224
     label = f"{'AlexNet-BN' if alex else 'ResNet-50'} whole training step (all layers + LARS), batch {batch}, {side}x{side}, NHWC"
     if bf16:
@@ -752,6 +752,8 @@ def main():
                     help="--full-step: batch norm sums its input itself instead of taking the sums from the convolution's epilogue")
     ap.add_argument("--no-pair", action="store_true",
                     help="with --full-step: the two batch norms at the output of a projection block as two plain passes")
+    ap.add_argument("--no-grid-grads", action="store_true",
+                    help="with --full-step: the input gradients of the strided 1x1 layers as full tensors (zeros between the grid pixels)")
     ap.add_argument("--no-side-stream", action="store_true",
                     help="with --full-step: the filter gradients on the main stream instead of a second one")
     ap.add_argument("--graph", action="store_true", help="--full-step: capture the step in a HIP graph and time replays")

@@ -296,6 +296,18 @@ lc_status relu_add_bwd_bnsums_t(lc_dtype dtype, const void* y, const void* da, c
 lc_status batchnorm_bwd_presummed_t(lc_dtype dtype, const void* x, const void* dy, const float* gamma, const float* save_mean,
                                     const float* save_invstd, void* dx, float* dgamma, float* dbeta, int n, int c, int h, int w,
                                     lc_layout layout, void* workspace, size_t workspace_bytes, void* hip_stream);
+/* The same pass where the arriving gradients come out of strided 1x1 convolutions.  The first block of a stage of the
+ * paper's ResNet-50 ("ImageNet training with ResNet-50") reads the previous block's output through two 1x1 convolutions of
+ * stride 2 (its first convolution and its projection); their input gradients are zero except at the pixels
+ * (i * grad_stride, j * grad_stride).  relu_add_bwd_bnsums_grid_t is relu_add_bwd_bnsums_t whose da and db (db may be
+ * NULL) are [n, c, ceil(h / grad_stride), ceil(w / grad_stride)] tensors holding only those pixels -- what conv2d_bwd_data
+ * of the same filters gives when the descriptor describes the output grid with stride 1 -- so neither the zeros nor the
+ * scatter are ever written or read.  Results are bit for bit those of relu_add_bwd_bnsums_t on the scattered tensors.
+ * grad_stride = 1 is relu_add_bwd_bnsums_t itself; grad_stride < 1, or more than 2^31 - 1 pixels with grad_stride > 1:
+ * LC_ERR_SHAPE.  Everything else (layout, alignment, channel multiples, workspace, errors) as relu_add_bwd_bnsums_t. */
+lc_status relu_add_bwd_bnsums_grid_t(lc_dtype dtype, const void* y, const void* da, const void* db, void* dx, const void* x_bn,
+                                     const float* save_mean, const float* save_invstd, int n, int c, int h, int w, int grad_stride,
+                                     lc_layout layout, void* workspace, size_t workspace_bytes, void* hip_stream);
 /* ---- Batch-norm statistics out of the convolution ----
  * Every convolution of the paper's networks is followed by batch normalisation ("Scaling up Batch Size",
  * "ImageNet training with ResNet-50"), whose first step reads the convolution's whole output again to sum it.

@@ -124,6 +124,17 @@ struct BnJoin {
     const T* da;
     const T* db;
     T* out;
+    // stride > 1: da and db hold the gradient only at the pixels (i * stride, j * stride) of every image, as
+    // [n][hq][wq][c] tensors; it is zero everywhere else (what backward-data of a strided 1x1 convolution produces)
+    int stride = 1, w = 0, hw = 0, wq = 0, hwq = 0;
+    // row of da / db for pixel row `row` of the full tensor, or -1 off the grid (rows < 2^31: checked on the host)
+    __device__ __forceinline__ long long grid_row(long long row) const {
+        const unsigned r = (unsigned)row, img = r / (unsigned)hw, rem = r - img * (unsigned)hw;
+        const unsigned hh = rem / (unsigned)w, ww = rem - hh * (unsigned)w;
+        const unsigned hs = hh / (unsigned)stride, wss = ww / (unsigned)stride;
+        if (hs * (unsigned)stride != hh || wss * (unsigned)stride != ww) return -1;
+        return (long long)img * hwq + (long long)hs * wq + wss;
+    }
 };
 
 template <typename T, int VEC, int MODE, int JOIN = 0>
@@ -178,8 +189,17 @@ __global__ void __launch_bounds__(kThreads) bn_reduce_nhwc_kernel(const T* __res
                     ra[u] = Pack<T, VEC>::fetch(x + at);
                     if constexpr (JOIN) {
                         ry[u] = Pack<T, VEC>::fetch(join.y + at);
-                        rb[u] = Pack<T, VEC>::fetch(join.da + at);
-                        if constexpr (JOIN == 2) rc[u] = Pack<T, VEC>::fetch(join.db + at);
+                        long long gat = at;
+                        if (join.stride > 1) {
+                            const long long gr = join.grid_row(r + (long long)u * g.ty);
+                            gat = gr < 0 ? -1 : gr * g.C + c0;
+                        }
+                        rb[u] = typename Pack<T, VEC>::raw{};
+                        if (gat >= 0) rb[u] = Pack<T, VEC>::fetch(join.da + gat);
+                        if constexpr (JOIN == 2) {
+                            rc[u] = typename Pack<T, VEC>::raw{};
+                            if (gat >= 0) rc[u] = Pack<T, VEC>::fetch(join.db + gat);
+                        }
                     } else if constexpr (!STATS) {
                         rb[u] = Pack<T, VEC>::fetch(dy + at);
                     }
@@ -215,8 +235,17 @@ __global__ void __launch_bounds__(kThreads) bn_reduce_nhwc_kernel(const T* __res
                     if constexpr (JOIN) {
                         float yv[VEC], h2[VEC];
                         Pack<T, VEC>::load(join.y + q * g.C + c0, yv);
-                        Pack<T, VEC>::load(join.da + q * g.C + c0, b);
-                        if constexpr (JOIN == 2) Pack<T, VEC>::load(join.db + q * g.C + c0, h2);
+                        long long gat = q * g.C + c0;
+                        if (join.stride > 1) {
+                            const long long gr = join.grid_row(q);
+                            gat = gr < 0 ? -1 : gr * g.C + c0;
+                        }
+#pragma unroll
+                        for (int e = 0; e < VEC; ++e) b[e] = h2[e] = 0.f;
+                        if (gat >= 0) {
+                            Pack<T, VEC>::load(join.da + gat, b);
+                            if constexpr (JOIN == 2) Pack<T, VEC>::load(join.db + gat, h2);
+                        }
 #pragma unroll
                         for (int e = 0; e < VEC; ++e) {
                             if constexpr (JOIN == 2) b[e] += h2[e];
@@ -751,13 +780,15 @@ lc_status bn_bwd_impl(const T* x, const T* dy, const float* gamma, const float* 
 // dx = (y > 0 ? da [+ db] : 0) and, in the workspace, the sums batch-norm backward needs of that dx against x_bn
 template <typename T>
 lc_status bn_join_impl(const T* y, const T* da, const T* db, T* dx, const T* x_bn, const float* save_mean, const float* save_invstd, int n,
-                       int c, int h, int w, lc_layout layout, void* workspace, size_t workspace_bytes, void* hip_stream) {
+                       int c, int h, int w, lc_layout layout, void* workspace, size_t workspace_bytes, void* hip_stream, int stride = 1) {
     if (!y || !da || !dx || !x_bn || !save_mean || !save_invstd) return LC_ERR_NULL;
     if (layout != LC_NHWC) return LC_ERR_UNSUPPORTED;
+    if (stride < 1) return LC_ERR_SHAPE;
     BnGeom g;
     if (!geometry(n, c, h, w, layout, al16(y) && al16(da) && al16(db) && al16(dx) && al16(x_bn), &g, kWide<T>)) return LC_ERR_SHAPE;
     if (!al4(y) || !al4(da) || !al4(db) || !al4(dx) || !al4(x_bn) || !al4(save_mean) || !al4(save_invstd)) return LC_ERR_ALIGN;
     if (g.vec != kWide<T>) return c % kWide<T> ? LC_ERR_UNSUPPORTED : LC_ERR_ALIGN;
+    if (stride > 1 && g.M > 0x7fffffffLL) return LC_ERR_SHAPE;          // the grid index arithmetic is 32-bit
     size_t coef_off;
     const size_t need = ws_layout(g, &coef_off);
     if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255) || workspace_bytes < need) return LC_ERR_WORKSPACE;
@@ -769,7 +800,14 @@ lc_status bn_join_impl(const T* y, const T* da, const T* db, T* dx, const T* x_b
     const dim3 grid((unsigned)g.slabs, (unsigned)g.cblocks);
     const float* nonef = nullptr;
     const T* none = nullptr;
-    const BnJoin<T> join{y, da, db, dx};
+    BnJoin<T> join{y, da, db, dx};
+    if (stride > 1) {
+        join.stride = stride;
+        join.w = w;
+        join.hw = g.HW;
+        join.wq = (w + stride - 1) / stride;
+        join.hwq = ((h + stride - 1) / stride) * join.wq;
+    }
     if (db)
         hipLaunchKernelGGL((bn_reduce_nhwc_kernel<T, kWide<T>, kSums, 2>), grid, dim3(kThreads), 0, stream, x_bn, none, save_mean, save_invstd,
                            nonef, nonef, g, ws, join);
@@ -792,6 +830,21 @@ extern "C" lc_status relu_add_bwd_bnsums_t(lc_dtype dtype, const void* y, const 
         return bn_join_impl<uint16_t>(static_cast<const uint16_t*>(y), static_cast<const uint16_t*>(da), static_cast<const uint16_t*>(db),
                                       static_cast<uint16_t*>(dx), static_cast<const uint16_t*>(x_bn), save_mean, save_invstd, n, c, h, w,
                                       layout, workspace, workspace_bytes, hip_stream);
+    return LC_ERR_UNSUPPORTED;
+}
+
+extern "C" lc_status relu_add_bwd_bnsums_grid_t(lc_dtype dtype, const void* y, const void* da, const void* db, void* dx, const void* x_bn,
+                                                const float* save_mean, const float* save_invstd, int n, int c, int h, int w,
+                                                int grad_stride, lc_layout layout, void* workspace, size_t workspace_bytes,
+                                                void* hip_stream) {
+    if (dtype == LC_F32)
+        return bn_join_impl<float>(static_cast<const float*>(y), static_cast<const float*>(da), static_cast<const float*>(db),
+                                   static_cast<float*>(dx), static_cast<const float*>(x_bn), save_mean, save_invstd, n, c, h, w, layout,
+                                   workspace, workspace_bytes, hip_stream, grad_stride);
+    if (dtype == LC_BF16)
+        return bn_join_impl<uint16_t>(static_cast<const uint16_t*>(y), static_cast<const uint16_t*>(da), static_cast<const uint16_t*>(db),
+                                      static_cast<uint16_t*>(dx), static_cast<const uint16_t*>(x_bn), save_mean, save_invstd, n, c, h, w,
+                                      layout, workspace, workspace_bytes, hip_stream, grad_stride);
     return LC_ERR_UNSUPPORTED;
 }
 

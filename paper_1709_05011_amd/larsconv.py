@@ -26,7 +26,7 @@ EXPORTS = ["conv2d_out_shape", "conv2d_workspace_bytes", "conv2d_fwd", "conv2d_b
            "bias_add", "bias_grad", "softmax_xent", "maxpool_fwd", "maxpool_bwd", "relu_add_bwd",
            "batchnorm_workspace_bytes", "batchnorm_fwd", "batchnorm_bwd", "batchnorm_fwd_ex", "batchnorm_bwd_ex",
            "batchnorm_fwd_t", "batchnorm_bwd_t", "maxpool_fwd_t", "maxpool_bwd_t", "relu_add_bwd_t", "global_avgpool_fwd_t",
-           "global_avgpool_bwd_t", "relu_add_bwd_bnsums_t", "batchnorm_bwd_presummed_t",
+           "global_avgpool_bwd_t", "relu_add_bwd_bnsums_t", "relu_add_bwd_bnsums_grid_t", "batchnorm_bwd_presummed_t",
            "conv2d_fwd_stats_count", "conv2d_fwd_stats", "batchnorm_fwd_pre", "batchnorm_fwd_pair_t",
            "lc_status_string", "lc_last_error_detail"]
 
@@ -148,6 +148,8 @@ def lib() -> ctypes.CDLL:
             fn.argtypes = [i32] + getattr(L, name).argtypes
         L.relu_add_bwd_bnsums_t.restype = i32
         L.relu_add_bwd_bnsums_t.argtypes = [i32, vp, vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, vp, sz, vp]
+        L.relu_add_bwd_bnsums_grid_t.restype = i32
+        L.relu_add_bwd_bnsums_grid_t.argtypes = [i32, vp, vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, vp, sz, vp]
         L.batchnorm_bwd_presummed_t.restype = i32
         L.batchnorm_bwd_presummed_t.argtypes = [i32, vp, vp, vp, vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, vp, sz, vp]
         L.conv2d_fwd_stats_count.restype = sz
@@ -468,6 +470,14 @@ def relu_add_bwd_bnsums_t(dtype: int, y, da, db, dx, x_bn, save_mean, save_invst
     _check(lib().relu_add_bwd_bnsums_t(dtype, _ptr(y), _ptr(da), _ptr(db), _ptr(dx), _ptr(x_bn), _ptr(save_mean), _ptr(save_invstd),
                                        n, c, h, w, layout, _ptr(workspace), _nbytes(workspace), _stream(stream)),
            "relu_add_bwd_bnsums_t")
+
+
+def relu_add_bwd_bnsums_grid_t(dtype: int, y, da, db, dx, x_bn, save_mean, save_invstd, n: int, c: int, h: int, w: int, grad_stride: int,
+                               layout: int, workspace=None, stream=None) -> None:
+    _check(lib().relu_add_bwd_bnsums_grid_t(dtype, _ptr(y), _ptr(da), _ptr(db), _ptr(dx), _ptr(x_bn), _ptr(save_mean),
+                                            _ptr(save_invstd), n, c, h, w, grad_stride, layout, _ptr(workspace), _nbytes(workspace),
+                                            _stream(stream)),
+           "relu_add_bwd_bnsums_grid_t")
 
 
 def batchnorm_bwd_presummed_t(dtype: int, x, dy, gamma, save_mean, save_invstd, dx, dgamma, dbeta, n: int, c: int, h: int, w: int,

@@ -42,7 +42,8 @@ class _ConvBn:
 class ResNetStep:
     def __init__(self, stem: Tuple[int, int, int, int], widths: Sequence[int], blocks: Sequence[int], classes: int, batch: int,
                  image_hw: Tuple[int, int], in_channels: int = 3, eps: float = 1e-5, device: str = "cuda:0", dtype: int = lc.LC_F32,
-                 join_sums: bool = True, fuse_stats: bool = True, pair_bn: bool = True, side_wgrad: bool = True):
+                 join_sums: bool = True, fuse_stats: bool = True, pair_bn: bool = True, side_wgrad: bool = True,
+                 grid_grads: bool = True):
         lc.lib()                     # fails here, loudly, when the library has not been built
         self.join_sums = join_sums   # False: the block-output gradient and the batch-norm sums behind it as two plain calls
         # The filter gradient of a layer and the gradient of its input both need only dz, and nothing before lars_step reads a
@@ -50,6 +51,10 @@ class ResNetStep:
         # its own), which joins the main one before lars_step.  Same kernels on the same operands: the results do not change.
         self._side = torch.cuda.Stream(device=device) if side_wgrad else None
         self._keep: List[torch.Tensor] = []     # the dz tensors the second stream still reads (held until the join)
+        # grid_grads: the input gradients of a stage's first block (two 1x1 convolutions of stride 2) stay on their output grid
+        # -- backward-data through a stride-1 descriptor of that grid -- and the pass that joins them at the previous block's
+        # output reads them there (relu_add_bwd_bnsums_grid_t): the zeros between the grid pixels are neither written nor read
+        self.grid_grads = grid_grads
         self.pair_bn = pair_bn       # False: a projection's batch norm writes its output, which the block's last batch norm then adds
         self.dev, self.eps, self.batch, self.classes = device, eps, batch, classes
         self.dtype = dtype
@@ -130,6 +135,15 @@ class ResNetStep:
             need = max(need, lc.batchnorm_workspace_bytes(batch, L.desc.k, L.out_hw[0], L.out_hw[1], NHWC))
         for p in (lc.LC_PASS_FWD, lc.LC_PASS_BWD_DATA, lc.LC_PASS_BWD_WEIGHT):
             need = max(need, lc.conv2d_workspace_bytes(self.fc_desc, p))
+        # a strided 1x1 layer seen from its output grid: the same filters, stride 1, input of the output's size
+        self._grid_desc: Dict[str, "lc.ConvDesc"] = {}
+        for name in self.order:
+            d = self.layers[name].desc
+            if d.r == 1 and d.s == 1 and d.pad_h == 0 and d.pad_w == 0 and d.stride_h == d.stride_w and d.stride_h > 1:
+                p_, q_ = self.layers[name].out_hw
+                gd = lc.ConvDesc(batch, d.c, p_, q_, d.k, 1, 1, 1, 1, 0, 0, self.dtype, NHWC)
+                self._grid_desc[name] = gd
+                need = max(need, lc.conv2d_workspace_bytes(gd, lc.LC_PASS_BWD_DATA))
         self._ws = self._bytes(need)
         self._ws_side = self._bytes(need) if self._side is not None else None
 
@@ -212,7 +226,8 @@ class ResNetStep:
                                 L.a, L.mean, L.invstd, O.mean, O.invstd, self.batch, k, p, q, self.eps, True, NHWC, self._ws)
         return L.a
 
-    def _conv_bn_bwd(self, name: str, da: torch.Tensor, need_dx: bool = True, presummed: bool = False) -> Optional[torch.Tensor]:
+    def _conv_bn_bwd(self, name: str, da: torch.Tensor, need_dx: bool = True, presummed: bool = False,
+                     on_grid: bool = False) -> Optional[torch.Tensor]:
         """``da``: gradient with respect to the layer's output -- of the fused ReLU's output where the layer has
         one, otherwise of the batch-norm output itself (the caller has applied the block's last ReLU).  ``presummed``: the
         call that made ``da`` has left the batch-norm backward sums in the workspace."""
@@ -236,6 +251,10 @@ class ResNetStep:
             lc.conv2d_bwd_weight_sq(L.desc, L.x, dz, self.grads[name + ".w"], self.gsq[name + ".w"], self._ws)
         if not need_dx:
             return None
+        if on_grid:                      # the gradient at the pixels the strided layer reads, [n, p, q, c]; zero elsewhere (not stored)
+            dx = torch.empty((self.batch, p, q, L.desc.c), dtype=self._act, device=self.dev)
+            lc.conv2d_bwd_data(self._grid_desc[name], dz, self._filter(name), dx, self._ws)
+            return dx
         dx = self._new(L.x)
         lc.conv2d_bwd_data(L.desc, dz, self._filter(name), dx, self._ws)
         return dx
@@ -277,22 +296,34 @@ class ResNetStep:
         g1: torch.Tensor = self._new(last)
         g2: Optional[torch.Tensor] = None
         lc.global_avgpool_bwd_t(self.dtype, dgap, g1, n, self.final_ch, self.final_hw[0], self.final_hw[1], NHWC)
-        for name, proj in reversed(self.blocks):
+        gstride = 1                      # > 1: g1 and g2 hold the gradient on the stride grid only
+        for bi in range(len(self.blocks) - 1, -1, -1):
+            name, proj = self.blocks[bi]
             out = self.layers[name + ".c3"].a
             d_pre = self._new(out)
             # both arriving gradients through the block's last ReLU -- and, where the layer's channel count allows the
             # vector path, the sums of the batch-norm backward pass of the block's last convolution on the way
             L3 = self.layers[name + ".c3"]
             joined = self.join_sums and L3.desc.k % (8 if self.dtype == lc.LC_BF16 else 4) == 0
-            if joined:
+            if joined and gstride > 1:
+                lc.relu_add_bwd_bnsums_grid_t(self.dtype, out, g1, g2, d_pre, L3.z, L3.mean, L3.invstd, n, L3.desc.k, L3.out_hw[0],
+                                              L3.out_hw[1], gstride, NHWC, self._ws)
+            elif joined:
                 lc.relu_add_bwd_bnsums_t(self.dtype, out, g1, g2, d_pre, L3.z, L3.mean, L3.invstd, n, L3.desc.k, L3.out_hw[0],
                                          L3.out_hw[1], NHWC, self._ws)
             else:
                 lc.relu_add_bwd_t(self.dtype, out, g1, g2, d_pre, out.numel())
             d = self._conv_bn_bwd(name + ".c3", d_pre, presummed=joined)
             d = self._conv_bn_bwd(name + ".c2", d)
-            g1 = self._conv_bn_bwd(name + ".c1", d)
-            g2 = self._conv_bn_bwd(name + ".proj", d_pre) if proj else d_pre
+            # this block's two input gradients stay on the stride grid when both come from strided 1x1 layers and the pass
+            # that takes them (the previous block's output) is the joined one
+            gstride = 1
+            if self.grid_grads and proj and bi > 0 and (name + ".c1") in self._grid_desc and (name + ".proj") in self._grid_desc:
+                Lp = self.layers[self.blocks[bi - 1][0] + ".c3"]
+                if self.join_sums and Lp.desc.k % (8 if self.dtype == lc.LC_BF16 else 4) == 0:
+                    gstride = self.layers[name + ".c1"].desc.stride_h
+            g1 = self._conv_bn_bwd(name + ".c1", d, on_grid=gstride > 1)
+            g2 = (self._conv_bn_bwd(name + ".proj", d_pre, on_grid=gstride > 1) if proj else d_pre)
         d_pool = self._new(self.pool_out)
         lc.relu_add_bwd_t(self.dtype, None, g1, g2, d_pool, d_pool.numel())   # the pool's output feeds the first block twice
         stem = self.layers["stem"]

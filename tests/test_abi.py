@@ -329,6 +329,16 @@ def test_joined_block_gradient_rejects_bad_arguments_before_launch():
     assert join(lay=lc.LC_NCHW) == lc.LC_ERR_UNSUPPORTED
     assert join(dt=7) == lc.LC_ERR_UNSUPPORTED
     assert join(xb=ctypes.c_void_p(FAKE + 8)) == lc.LC_ERR_ALIGN
+    grid = lambda dt=lc.LC_BF16, y=P, st=2, c=16, lay=lc.LC_NHWC, nb=need: L.relu_add_bwd_bnsums_grid_t(dt, y, P, P, P, P, P, P, 4, c, 5, 5, st,
+                                                                                                       lay, P, nb, None)
+    assert grid(y=None) == lc.LC_ERR_NULL
+    assert grid(st=0) == lc.LC_ERR_SHAPE                          # the gradients' stride is at least 1
+    assert grid(st=-2) == lc.LC_ERR_SHAPE
+    assert grid(nb=0) == lc.LC_ERR_WORKSPACE                      # a valid stride reaches the workspace check
+    assert grid(st=1, nb=0) == lc.LC_ERR_WORKSPACE
+    assert grid(c=12) == lc.LC_ERR_UNSUPPORTED
+    assert grid(lay=lc.LC_NCHW) == lc.LC_ERR_UNSUPPORTED
+    assert grid(dt=7) == lc.LC_ERR_UNSUPPORTED
     pre = lambda dt=lc.LC_BF16, c=16, lay=lc.LC_NHWC, nb=need, dy=P: L.batchnorm_bwd_presummed_t(dt, P, dy, P, P, P, P, P, P, 4, c, 5, 5, lay,
                                                                                                    P, nb, None)
     assert pre(dy=None) == lc.LC_ERR_NULL

@@ -410,3 +410,59 @@ def test_block_gradient_joined_with_batchnorm_sums_equals_the_two_plain_calls(sh
     for u, v in zip(*outs):
         np.testing.assert_array_equal(u, v)
     assert np.all(np.isfinite(outs[1][2])) and np.any(outs[1][1] != 0)
+
+
+@pytest.mark.parametrize("bf16", [False, True], ids=["fp32", "bf16"])
+@pytest.mark.parametrize("two", [True, False], ids=["two_gradients", "one_gradient"])
+@pytest.mark.parametrize("case", [(6, 32, 14, 14, 2), (3, 8, 5, 7, 2), (2, 64, 56, 56, 2), (5, 16, 9, 9, 3), (4, 8, 1, 6, 2)],
+                         ids=["14x14", "odd_sizes", "many_rows", "stride_3", "one_row"])
+def test_block_gradient_from_gradients_on_the_stride_grid(case, two, bf16):
+    """relu_add_bwd_bnsums_grid_t takes the arriving gradients as [n, ceil(h/s), ceil(w/s), c] tensors that hold the pixels
+    (i s, j s) only (what backward-data of a strided 1x1 convolution produces on its output grid).  Bit for bit the result of
+    relu_add_bwd_bnsums_t on the same gradients scattered into zero tensors, sums included (checked through
+    batchnorm_bwd_presummed_t); stride 1 is the plain call."""
+    n, c, h, w, s = case
+    hq, wq = (h + s - 1) // s, (w + s - 1) // s
+    dtype = BF if bf16 else lc.LC_F32
+    shape, qshape = (n, c, h, w), (n, c, hq, wq)
+
+    def put(a):
+        if bf16:
+            return _dev(_bf(a)[0])
+        return gu.dev(gu.to_layout(a, NHWC))
+    z = put((synth.normal(shape, 9950) * 1.5 + 0.4).astype(np.float32))
+    y = put(synth.normal(shape, 9951))
+    small = [synth.normal(qshape, 9952), synth.normal(qshape, 9953)]
+    full = []
+    for a in small:
+        f = np.zeros(shape, dtype=np.float32)
+        f[:, :, ::s, ::s] = a
+        full.append(f)
+    g_small, g_full = [put(a) for a in small], [put(a) for a in full]
+    gamma = gu.dev((1.0 + 0.5 * synth.normal((c,), 9954)).astype(np.float32))
+    beta = gu.dev(synth.normal((c,), 9955))
+    ws = gu.workspace(lc.batchnorm_workspace_bytes(n, c, h, w, NHWC))
+    mean, invstd = torch.empty(c, device=gu.DEV), torch.empty(c, device=gu.DEV)
+    a = torch.empty_like(z)
+    lc.batchnorm_fwd_t(dtype, z, gamma, beta, None, a, mean, invstd, n, c, h, w, EPS, False, NHWC, ws)
+    outs = []
+    for grid in (False, True):
+        fill = -1 if bf16 else float("nan")
+        d_pre, dz = torch.full_like(z, fill), torch.full_like(z, fill)
+        dg, db = torch.empty(c, device=gu.DEV), torch.empty(c, device=gu.DEV)
+        if grid:
+            lc.relu_add_bwd_bnsums_grid_t(dtype, y, g_small[0], g_small[1] if two else None, d_pre, z, mean, invstd, n, c, h, w, s, NHWC, ws)
+        else:
+            lc.relu_add_bwd_bnsums_t(dtype, y, g_full[0], g_full[1] if two else None, d_pre, z, mean, invstd, n, c, h, w, NHWC, ws)
+        lc.batchnorm_bwd_presummed_t(dtype, z, d_pre, gamma, mean, invstd, dz, dg, db, n, c, h, w, NHWC, ws)
+        torch.cuda.synchronize()
+        outs.append([t.cpu().numpy() for t in (d_pre, dz, dg, db)])
+    for u, v in zip(*outs):
+        np.testing.assert_array_equal(u, v)
+    assert np.all(np.isfinite(outs[1][2])) and np.any(outs[1][0] != 0)
+    # stride 1: the plain call
+    d1, d2 = torch.empty_like(z), torch.empty_like(z)
+    lc.relu_add_bwd_bnsums_grid_t(dtype, y, g_full[0], None, d1, z, mean, invstd, n, c, h, w, 1, NHWC, ws)
+    lc.relu_add_bwd_bnsums_t(dtype, y, g_full[0], None, d2, z, mean, invstd, n, c, h, w, NHWC, ws)
+    torch.cuda.synchronize()
+    assert torch.equal(d1.view(torch.int16) if bf16 else d1, d2.view(torch.int16) if bf16 else d2)
